@@ -1,0 +1,297 @@
+/*
+ * flexco — one co-serving iteration of a LoRA-augmented decoder layer over a mixed
+ * token batch, for AMD MI355X (gfx950).  C ABI.
+ *
+ * Method: FlexLLM, "Co-Serving Large Language Model Inference and Parameter-Efficient
+ * Finetuning" (arXiv 2402.18789).  Section / algorithm numbers below refer to it.
+ *
+ * Conventions (all entry points)
+ *   - Every function returns an int32 status: FLEXCO_OK or a negative FLEXCO_E* code.
+ *     flexco_last_error() gives a thread-local, human-readable message for the last
+ *     failure on the calling thread.  No exception crosses this boundary.
+ *   - The caller owns ALL memory.  The library never allocates or frees device memory
+ *     and never synchronises: work is enqueued on `stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream) and the call returns.
+ *   - "device" pointers are GPU global memory, 16-byte aligned, dense, row-major.
+ *     "host" pointers are ordinary process memory.  Which is which is stated per
+ *     argument; the library cannot check it.
+ *   - Validation is done on the host before anything is launched; a failing call
+ *     launches nothing.
+ *   - Storage type `dtype`: FLEXCO_F32 or FLEXCO_BF16 for activations, weights, LoRA
+ *     matrices and the caches.  Accumulators (LoRA gradients, KV-gradient accumulator,
+ *     log-sum-exp) are always float.
+ *   - Every weight matrix, LoRA matrices included, is stored [out_features, in_features]
+ *     (the layout of the HuggingFace checkpoints the paper's runtime loads, Sec. 7).
+ *     In the paper's notation Y = f_B(X) + f_A(X) (Sec. 4.1) with
+ *     f_A(X) = scale * (X A^T) B^T,  A [r, in],  B [out, r].
+ *   - Gradients are ACCUMULATED into (dA, dB, dk_accum, dv_accum): the caller zeroes
+ *     them when a new finetuning mini-batch starts.
+ */
+#ifndef FLEXCO_H
+#define FLEXCO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FLEXCO_OK            0
+#define FLEXCO_EINVAL       (-1)  /* null / misaligned pointer, negative or zero size            */
+#define FLEXCO_ESHAPE       (-2)  /* inconsistent dimensions                                     */
+#define FLEXCO_EWORKSPACE   (-3)  /* workspace or blob too small                                 */
+#define FLEXCO_EPAGE        (-4)  /* page id out of range, kv_len beyond pages, duplicate slot   */
+#define FLEXCO_EUNSUPPORTED (-5)  /* valid request this build cannot run                         */
+#define FLEXCO_EHIP         (-6)  /* a HIP runtime call failed                                   */
+
+#define FLEXCO_F32  0
+#define FLEXCO_BF16 1
+
+/* LoRA targets, bit order of lora_targets and index order of flexco_lora arrays. */
+#define FLEXCO_T_Q 0
+#define FLEXCO_T_K 1
+#define FLEXCO_T_V 2
+#define FLEXCO_T_O 3
+#define FLEXCO_T_GATE 4
+#define FLEXCO_T_UP 5
+#define FLEXCO_T_DOWN 6
+#define FLEXCO_N_TARGETS 7
+
+/* Request kinds of the mixed batch (Sec. 6.2: inference tokens scheduled first, then a
+ * window of finetuning tokens appended). */
+#define FLEXCO_DECODE   0
+#define FLEXCO_PREFILL  1
+#define FLEXCO_FINETUNE 2
+
+typedef struct flexco_layer_cfg {
+  int32_t hidden;        /* H                                             */
+  int32_t n_q_heads;     /* nq                                            */
+  int32_t n_kv_heads;    /* nkv, divides nq                               */
+  int32_t head_dim;      /* d, even                                       */
+  int32_t ffn;           /* F                                             */
+  int32_t dtype;         /* FLEXCO_F32 | FLEXCO_BF16                      */
+  int32_t page_size;     /* positions per KV page                         */
+  int32_t lora_rank;     /* r (<= 64)                                     */
+  int32_t lora_targets;  /* bitmask, bit FLEXCO_T_*                       */
+  float   rms_eps;
+  float   rope_theta;    /* rotary base; pairs (i, i + d/2), angle pos * theta^(-2i/d) */
+  float   lora_scale;    /* alpha / r                                     */
+} flexco_layer_cfg;
+
+/* Frozen backbone weights of one layer (device, dtype of cfg). */
+typedef struct flexco_base_weights {
+  const void* wqkv;  /* [(nq + 2 nkv) d, H]: q rows, then k rows, then v rows      */
+  const void* bqkv;  /* [(nq + 2 nkv) d] or NULL                                   */
+  const void* wo;    /* [H, nq d]                                                  */
+  const void* wgu;   /* [2F, H]: gate rows, then up rows                           */
+  const void* wd;    /* [H, F]                                                     */
+  const void* g1;    /* [H] RMSNorm gain before attention                          */
+  const void* g2;    /* [H] RMSNorm gain before the MLP                            */
+} flexco_base_weights;
+
+/* One LoRA adapter (device).  Entry t is used iff bit t of cfg.lora_targets is set. */
+typedef struct flexco_lora {
+  const void* A[FLEXCO_N_TARGETS];   /* [r, in]   dtype of cfg                     */
+  const void* B[FLEXCO_N_TARGETS];   /* [out, r]  dtype of cfg                     */
+  float*      dA[FLEXCO_N_TARGETS];  /* [r, in]   float, accumulated (backward)    */
+  float*      dB[FLEXCO_N_TARGETS];  /* [out, r]  float, accumulated (backward)    */
+} flexco_lora;
+
+/* The mixed batch as the scheduler hands it over (host arrays of n_req entries). */
+typedef struct flexco_batch_desc {
+  int32_t        n_req;
+  const int32_t* kind;          /* FLEXCO_DECODE | PREFILL | FINETUNE                      */
+  const int32_t* start_pos;     /* positions [0, start_pos) of the sequence are cached     */
+  const int32_t* n_new;         /* tokens of this request in the batch (> 0)               */
+  const int32_t* adapter;       /* -1: base model only; >= 0: LoRA adapter id              */
+  const int32_t* req_page_off;  /* [n_req + 1] offsets into req_pages                      */
+  const int32_t* req_pages;     /* physical page ids of each request's sequence, in order  */
+} flexco_batch_desc;
+
+/* Index maps of a mixed batch.  All arrays are int32 and live in ONE caller-owned blob,
+ * so a batch is uploaded with a single copy; the struct holds pointers into the blob
+ * (host pointers as filled by flexco_build_maps, device pointers after
+ * flexco_maps_rebase).  The scalar fields are always host values.
+ *
+ * Conventions (the paper fixes none of them): tokens are laid out request by request in
+ * the order given; token i of a request has position start_pos + i; kv_len = start_pos +
+ * n_new; slot = pages[pos / page_size] * page_size + pos % page_size; block_table row r
+ * = the first ceil(kv_len_r / page_size) pages of request r padded with -1 to max_pages
+ * (>= 1) columns; ft_tok = ascending indices of finetune tokens; LoRA segments = maximal
+ * runs of tokens with equal adapter id.
+ *
+ * The attention work list is a pure function of the batch: each request's tokens are cut
+ * into column tiles of tile_tokens = max(1, 16 / (nq / nkv)) tokens (a decode request is
+ * one tile); a tile's visible key range [0, last position of the tile] is cut into splits
+ * of kv_split_pages pages; one work item = (tile, split). */
+typedef struct flexco_maps {
+  int32_t T, n_req, n_ft, n_seg, max_pages, page_size;
+  int32_t n_tiles, n_items, n_parts;   /* n_parts = sum over tiles of their split count   */
+  int32_t tile_tokens, kv_split_pages;
+  int32_t ft_req;                      /* index of the finetune request, -1 if none       */
+  int32_t ft_tok0, ft_pos0;            /* its first token index and first position        */
+  int32_t n_lora;                      /* tokens whose segment has adapter >= 0           */
+  int32_t max_kv_len;
+  int32_t blob_ints;                   /* int32 words used in the blob                    */
+  const int32_t* tok_req;       /* [T]                                                    */
+  const int32_t* tok_pos;       /* [T]                                                    */
+  const int32_t* slot;          /* [T]                                                    */
+  const int32_t* req_tok_off;   /* [n_req + 1]                                            */
+  const int32_t* req_kv_len;    /* [n_req]                                                */
+  const int32_t* req_kind;      /* [n_req]                                                */
+  const int32_t* block_table;   /* [n_req, max_pages]                                     */
+  const int32_t* ft_tok;        /* [n_ft]                                                 */
+  const int32_t* seg_off;       /* [n_seg + 1]                                            */
+  const int32_t* seg_adapter;   /* [n_seg]                                                */
+  const int32_t* lora_tok;      /* [n_lora] ascending indices of tokens with adapter >= 0 */
+  const int32_t* tile_req;      /* [n_tiles]                                              */
+  const int32_t* tile_tok0;     /* [n_tiles] first token of the tile                      */
+  const int32_t* tile_ntok;     /* [n_tiles] tokens in the tile                           */
+  const int32_t* tile_nsplit;   /* [n_tiles]                                              */
+  const int32_t* tile_part0;    /* [n_tiles] first partial-result row of the tile         */
+  const int32_t* item_tile;     /* [n_items]                                              */
+  const int32_t* item_split;    /* [n_items]                                              */
+  const int32_t* tok_tile;      /* [T] tile of each token                                 */
+} flexco_maps;
+
+/* Paged KV cache of one layer (device, dtype of cfg).  Sec. 7, memory management.
+ *   k_pages [num_pages, nkv, page_size, d]   keys after RoPE
+ *   v_pages [num_pages, nkv, d, page_size]   values, position-minor inside a page     */
+typedef struct flexco_kv_pool {
+  void*   k_pages;
+  void*   v_pages;
+  int32_t num_pages;
+  int32_t page_size;
+} flexco_kv_pool;
+
+/* Per-layer state of ONE finetuning sequence of seq_len rows (device).  Alg. 2 keeps a
+ * Q/K/V cache per layer: K and V live in the paged pool like any sequence's, Q here.
+ * saved_* are the activations graph pruning (Alg. 1) leaves alive for this layer:
+ * x, x2 (input of the second norm), gate, up; the attention output and the softmax
+ * log-sum-exp are kept in addition (8 KB + 128 B per token at 8B shape) so that the
+ * backward pass needs no second forward pass over the keys.
+ * dk_accum / dv_accum: the statically allocated KV-gradient accumulator of Sec. 7. */
+typedef struct flexco_ft_state {
+  int32_t seq_len;
+  void*  q_cache;     /* [L, nq d]  after RoPE        */
+  void*  saved_x;     /* [L, H]                       */
+  void*  saved_x2;    /* [L, H]                       */
+  void*  saved_gate;  /* [L, F]                       */
+  void*  saved_up;    /* [L, F]                       */
+  void*  saved_attn;  /* [L, nq d]                    */
+  float* lse;         /* [L, nq]                      */
+  float* dk_accum;    /* [L, nkv d] float             */
+  float* dv_accum;    /* [L, nkv d] float             */
+} flexco_ft_state;
+
+/* Message for the last failing call on this thread ("" if none). */
+const char* flexco_last_error(void);
+
+/* Library ABI version (increases when a struct above changes). */
+int32_t flexco_abi_version(void);
+
+/* Upper bound of the int32 words flexco_build_maps needs for `desc` (host only). */
+int32_t flexco_maps_blob_ints(const flexco_batch_desc* desc, int32_t page_size,
+                              int32_t n_q_heads, int32_t n_kv_heads, int32_t kv_split_pages,
+                              size_t* out_ints);
+
+/* Builds the index maps of a mixed batch on the host (Sec. 6.2: the scheduler's output is
+ * this call's input).  desc, blob: host.  blob_ints: capacity of blob in int32 words.
+ * num_pages: size of the pool the page ids refer to.  kv_split_pages: 0 = default (32).
+ * Errors: EINVAL (null, non-positive sizes, unknown kind), EPAGE (page id outside
+ * [0, num_pages), kv_len beyond the request's pages, two tokens on one slot),
+ * EUNSUPPORTED (more than one finetune request), EWORKSPACE (blob too small). */
+int32_t flexco_build_maps(const flexco_batch_desc* desc, int32_t page_size, int32_t num_pages,
+                          int32_t n_q_heads, int32_t n_kv_heads, int32_t kv_split_pages,
+                          int32_t* blob, size_t blob_ints, flexco_maps* out);
+
+/* Rewrites the pointers of `host_maps` (pointing into host_blob) so that they point into
+ * a copy of the blob at `other_blob` (typically device memory).  Host only. */
+int32_t flexco_maps_rebase(const flexco_maps* host_maps, const int32_t* host_blob,
+                           const int32_t* other_blob, flexco_maps* out);
+
+/* Bytes of device workspace that flexco_layer_forward / flexco_attention_mixed /
+ * flexco_lora_bwd need for batches of at most T_max tokens with at most n_parts_max
+ * attention partial rows, and backward windows of at most win_max rows over at most
+ * kv_max cached positions. */
+int32_t flexco_workspace_bytes(const flexco_layer_cfg* cfg, int32_t T_max, int32_t n_parts_max,
+                               int32_t win_max, int32_t kv_max, size_t* out_bytes);
+
+/* One forward iteration of the layer over the mixed batch (Sec. 6.2 fused forward;
+ * Alg. 2 Forward + Append for the finetune window).
+ *   maps     : device-rebased maps of the batch
+ *   x_in     : device [T, H]; x_out: device [T, H] (may not alias x_in)
+ *   pool     : this layer's cache; K/V of the batch's tokens are appended at their slots
+ *   ft       : state of the finetune sequence, NULL iff the batch has no finetune request;
+ *              rows [start_pos, start_pos + n_new) of q_cache, saved_*, lse are written
+ *   lora     : adapter applied to tokens whose segment has adapter >= 0 (NULL: none)
+ * Base projections run over all T tokens at once; LoRA only on adapter rows. */
+int32_t flexco_layer_forward(const flexco_layer_cfg* cfg, const flexco_base_weights* w,
+                             const flexco_lora* lora, const flexco_maps* maps,
+                             const void* x_in, void* x_out, const flexco_kv_pool* pool,
+                             const flexco_ft_state* ft, void* ws, size_t ws_bytes, void* stream);
+
+/* Mixed attention (Sec. 6.2): every token attends to positions 0..own position of its
+ * own sequence through the block table; decode tokens, prefill chunks and finetune
+ * windows in one launch sequence.
+ *   q   : device [T, nq d], after RoPE; the batch's K/V must already be in the pool
+ *   out : device [T, nq d];  lse: device float [T, nq] or NULL */
+int32_t flexco_attention_mixed(const flexco_layer_cfg* cfg, const flexco_maps* maps,
+                               const void* q, const flexco_kv_pool* pool, void* out, float* lse,
+                               void* ws, size_t ws_bytes, void* stream);
+
+/* Segmented LoRA forward (Sec. 4.1 bypass network): for every segment s with adapter
+ * a = seg_adapter[s] >= 0 and rows [seg_off[s], seg_off[s+1]):
+ *     y[rows] += scale * (x[rows] A_a^T) B_a^T.
+ *   x: device [T, in]; y: device [T, out], updated in place; rows of other segments are
+ *   untouched.  A_list / B_list: HOST arrays of n_adapters device pointers ([r, in] and
+ *   [out, r]).  seg_off / seg_adapter: HOST arrays (n_seg + 1 and n_seg entries).
+ *   u_ws: device scratch of at least T * r floats. */
+int32_t flexco_lora_fwd(const void* x, void* y, int32_t T, int32_t in_features, int32_t out_features,
+                        int32_t rank, float scale, int32_t dtype,
+                        const void* const* A_list, const void* const* B_list, int32_t n_adapters,
+                        const int32_t* seg_off, const int32_t* seg_adapter, int32_t n_seg,
+                        float* u_ws, void* stream);
+
+/* Token-level LoRA backward of one window through one layer (Alg. 2, the Backward / Add /
+ * Slice / CalculateGrads steps; Sec. 6.1; Sec. 7 KV-gradient accumulator).
+ * Window = rows [win_start, win_start + win_len) of the finetune sequence; windows of a
+ * sequence must be visited from its end downwards.
+ *   seq_pages : device int32 page ids of the sequence, n_seq_pages >= ceil(l / page_size),
+ *               l = win_start + win_len
+ *   ft        : the state the forward windows filled
+ *   dY        : device [win_len, H] gradient of the layer output rows
+ *   dX        : device [win_len, H] gradient of the layer input rows, or NULL when no
+ *               trainable parameter sits below this layer (Alg. 1 dead-output pruning)
+ *   lora      : A, B read; dA, dB accumulated for every target of cfg.lora_targets
+ * Effects: ft->dk_accum / dv_accum rows [0, l) += this window's contributions; rows
+ * [win_start, l) are then complete and are consumed for the k/v-side gradients. */
+int32_t flexco_lora_bwd(const flexco_layer_cfg* cfg, const flexco_base_weights* w,
+                        const flexco_lora* lora, const flexco_kv_pool* pool,
+                        const int32_t* seq_pages, int32_t n_seq_pages,
+                        const flexco_ft_state* ft, int32_t win_start, int32_t win_len,
+                        const void* dY, void* dX, void* ws, size_t ws_bytes, void* stream);
+
+/* Attention backward of one window (the attention part of flexco_lora_bwd, exported for
+ * unit parity).  q, out, dout: device [win_len, nq d] rows of the window (q after RoPE);
+ * lse: device float [win_len, nq].  dq: device [win_len, nq d] (dtype of cfg), written.
+ * dk_accum / dv_accum: device float [>= l, nkv d], rows [0, l) accumulated into. */
+int32_t flexco_attention_window_bwd(const flexco_layer_cfg* cfg, const flexco_kv_pool* pool,
+                                    const int32_t* seq_pages, int32_t n_seq_pages,
+                                    int32_t win_start, int32_t win_len,
+                                    const void* q, const void* out, const float* lse,
+                                    const void* dout, void* dq, float* dk_accum, float* dv_accum,
+                                    void* ws, size_t ws_bytes, void* stream);
+
+/* Dense projection used by the layer (exported for unit parity and roofline timing):
+ *   trans_w = 0:  C[M, N] = A[M, K] W[N, K]^T (+ bias[N]) (+ residual[M, N])
+ *   trans_w = 1:  C[M, N] = A[M, K] W[K, N]                 (input-gradient form)
+ * A, W, C, bias, residual: device, dtype; bias / residual may be NULL. */
+int32_t flexco_gemm(const void* A, const void* W, void* C, const void* bias, const void* residual,
+                    int32_t M, int32_t N, int32_t K, int32_t trans_w, int32_t dtype, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLEXCO_H */

@@ -1,0 +1,240 @@
+"""ctypes binding of libflexco.so: the same names as include/flexco.h, argument marshalling only.
+
+Every step of the layer runs inside the library's HIP kernels; PyTorch tensors are used
+here only as owners of device memory (data_ptr) and for the current stream handle.
+There is no fallback: if the shared library is missing, importing fails loudly.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libflexco.so")
+
+FLEXCO_OK, FLEXCO_EINVAL, FLEXCO_ESHAPE, FLEXCO_EWORKSPACE, FLEXCO_EPAGE, FLEXCO_EUNSUPPORTED, FLEXCO_EHIP = \
+    0, -1, -2, -3, -4, -5, -6
+FLEXCO_F32, FLEXCO_BF16 = 0, 1
+TARGET_NAMES = ("q", "k", "v", "o", "gate", "up", "down")
+N_TARGETS = 7
+ABI_VERSION = 1
+
+
+class FlexcoError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("flexco error %d: %s" % (code, msg))
+        self.code = code
+
+
+class LayerCfg(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("hidden", "n_q_heads", "n_kv_heads", "head_dim", "ffn", "dtype",
+                                         "page_size", "lora_rank", "lora_targets")] + \
+               [(n, C.c_float) for n in ("rms_eps", "rope_theta", "lora_scale")]
+
+
+class BaseWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("wqkv", "bqkv", "wo", "wgu", "wd", "g1", "g2")]
+
+
+class Lora(C.Structure):
+    _fields_ = [("A", C.c_void_p * N_TARGETS), ("B", C.c_void_p * N_TARGETS),
+                ("dA", C.c_void_p * N_TARGETS), ("dB", C.c_void_p * N_TARGETS)]
+
+
+class BatchDesc(C.Structure):
+    _fields_ = [("n_req", C.c_int32)] + [(n, C.POINTER(C.c_int32)) for n in
+                                         ("kind", "start_pos", "n_new", "adapter", "req_page_off", "req_pages")]
+
+
+_MAP_SCALARS = ("T", "n_req", "n_ft", "n_seg", "max_pages", "page_size", "n_tiles", "n_items", "n_parts",
+                "tile_tokens", "kv_split_pages", "ft_req", "ft_tok0", "ft_pos0", "n_lora", "max_kv_len", "blob_ints")
+_MAP_ARRAYS = ("tok_req", "tok_pos", "slot", "req_tok_off", "req_kv_len", "req_kind", "block_table", "ft_tok",
+               "seg_off", "seg_adapter", "lora_tok", "tile_req", "tile_tok0", "tile_ntok", "tile_nsplit",
+               "tile_part0", "item_tile", "item_split", "tok_tile")
+
+
+class Maps(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in _MAP_SCALARS] + [(n, C.c_void_p) for n in _MAP_ARRAYS]
+
+
+class KVPool(C.Structure):
+    _fields_ = [("k_pages", C.c_void_p), ("v_pages", C.c_void_p), ("num_pages", C.c_int32), ("page_size", C.c_int32)]
+
+
+class FtState(C.Structure):
+    _fields_ = [("seq_len", C.c_int32)] + [(n, C.c_void_p) for n in
+                                           ("q_cache", "saved_x", "saved_x2", "saved_gate", "saved_up", "saved_attn",
+                                            "lse", "dk_accum", "dv_accum")]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("libflexco.so is not built: run `python -m paper_2402_18789_amd.build` "
+                          "(there is no CPU fallback)")
+    lib = C.CDLL(LIB_PATH)
+    lib.flexco_last_error.restype = C.c_char_p
+    lib.flexco_abi_version.restype = C.c_int32
+    if lib.flexco_abi_version() != ABI_VERSION:
+        raise ImportError("libflexco.so has ABI version %d, binding expects %d" % (lib.flexco_abi_version(), ABI_VERSION))
+    P = C.POINTER
+    i32, vp, sz, f32 = C.c_int32, C.c_void_p, C.c_size_t, C.c_float
+    sigs = {
+        "flexco_maps_blob_ints": [P(BatchDesc), i32, i32, i32, i32, P(sz)],
+        "flexco_build_maps": [P(BatchDesc), i32, i32, i32, i32, i32, vp, sz, P(Maps)],
+        "flexco_maps_rebase": [P(Maps), vp, vp, P(Maps)],
+        "flexco_workspace_bytes": [P(LayerCfg), i32, i32, i32, i32, P(sz)],
+        "flexco_layer_forward": [P(LayerCfg), P(BaseWeights), P(Lora), P(Maps), vp, vp, P(KVPool), P(FtState), vp, sz, vp],
+        "flexco_attention_mixed": [P(LayerCfg), P(Maps), vp, P(KVPool), vp, vp, vp, sz, vp],
+        "flexco_lora_fwd": [vp, vp, i32, i32, i32, i32, f32, i32, P(vp), P(vp), i32, P(i32), P(i32), i32, vp, vp],
+        "flexco_lora_bwd": [P(LayerCfg), P(BaseWeights), P(Lora), P(KVPool), vp, i32, P(FtState), i32, i32, vp, vp, vp, sz, vp],
+        "flexco_attention_window_bwd": [P(LayerCfg), P(KVPool), vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
+        "flexco_gemm": [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp],
+    }
+    for name, args in sigs.items():
+        fn = getattr(lib, name)
+        fn.argtypes = args
+        fn.restype = C.c_int32
+    return lib
+
+
+_lib = _load()
+EXPORTS = ("flexco_last_error", "flexco_abi_version", "flexco_maps_blob_ints", "flexco_build_maps",
+           "flexco_maps_rebase", "flexco_workspace_bytes", "flexco_layer_forward", "flexco_attention_mixed",
+           "flexco_lora_fwd", "flexco_lora_bwd", "flexco_attention_window_bwd", "flexco_gemm")
+
+
+def _check(rc):
+    if rc != FLEXCO_OK:
+        raise FlexcoError(rc, _lib.flexco_last_error().decode())
+
+
+def _ptr(t):
+    """device/host address of a torch tensor, numpy array, int or None"""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if isinstance(t, np.ndarray):
+        return t.ctypes.data
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return getattr(stream, "cuda_stream", stream)
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def flexco_last_error():
+    return _lib.flexco_last_error().decode()
+
+
+def flexco_abi_version():
+    return _lib.flexco_abi_version()
+
+
+def make_batch_desc(kind, start_pos, n_new, adapter, req_pages_lists):
+    """Returns (BatchDesc, keepalive arrays)."""
+    kind, start_pos, n_new, adapter = _i32(kind), _i32(start_pos), _i32(n_new), _i32(adapter)
+    off = _i32(np.concatenate([[0], np.cumsum([len(p) for p in req_pages_lists])]))
+    pages = _i32(np.concatenate([np.asarray(p, dtype=np.int32).reshape(-1) for p in req_pages_lists])
+                 if len(req_pages_lists) else np.zeros(0))
+    if pages.size == 0:
+        pages = np.zeros(1, dtype=np.int32)
+    ip = lambda a: a.ctypes.data_as(C.POINTER(C.c_int32))
+    d = BatchDesc(len(kind), ip(kind), ip(start_pos), ip(n_new), ip(adapter), ip(off), ip(pages))
+    return d, (kind, start_pos, n_new, adapter, off, pages)
+
+
+def flexco_maps_blob_ints(desc, page_size, n_q_heads, n_kv_heads, kv_split_pages=0):
+    out = C.c_size_t(0)
+    _check(_lib.flexco_maps_blob_ints(C.byref(desc), page_size, n_q_heads, n_kv_heads, kv_split_pages, C.byref(out)))
+    return out.value
+
+
+def flexco_build_maps(desc, page_size, num_pages, n_q_heads, n_kv_heads, kv_split_pages=0, blob=None):
+    """Returns (Maps with host pointers, blob: np.int32 array that owns the arrays)."""
+    if blob is None:
+        blob = np.zeros(flexco_maps_blob_ints(desc, page_size, n_q_heads, n_kv_heads, kv_split_pages), dtype=np.int32)
+    m = Maps()
+    _check(_lib.flexco_build_maps(C.byref(desc), page_size, num_pages, n_q_heads, n_kv_heads, kv_split_pages,
+                                  blob.ctypes.data, blob.size, C.byref(m)))
+    return m, blob
+
+
+def maps_to_numpy(m, blob):
+    """Host view of every array of host-side maps (for the bit-exact parity tests)."""
+    base = blob.ctypes.data
+    cpt = None
+    lens = {"tok_req": m.T, "tok_pos": m.T, "slot": m.T, "req_tok_off": m.n_req + 1, "req_kv_len": m.n_req,
+            "req_kind": m.n_req, "block_table": m.n_req * m.max_pages, "ft_tok": m.n_ft, "seg_off": m.n_seg + 1,
+            "seg_adapter": m.n_seg, "lora_tok": m.n_lora, "tile_req": m.n_tiles, "tile_tok0": m.n_tiles,
+            "tile_ntok": m.n_tiles, "tile_nsplit": m.n_tiles, "tile_part0": m.n_tiles, "item_tile": m.n_items,
+            "item_split": m.n_items, "tok_tile": m.T}
+    out = {n: getattr(m, n) for n in _MAP_SCALARS}
+    for n, ln in lens.items():
+        off = (getattr(m, n) - base) // 4
+        out[n] = blob[off:off + ln].copy()
+    out["block_table"] = out["block_table"].reshape(m.n_req, m.max_pages)
+    return out
+
+
+def flexco_maps_rebase(host_maps, host_blob, other_blob):
+    out = Maps()
+    _check(_lib.flexco_maps_rebase(C.byref(host_maps), _ptr(host_blob), _ptr(other_blob), C.byref(out)))
+    return out
+
+
+def flexco_workspace_bytes(cfg, T_max, n_parts_max, win_max, kv_max):
+    out = C.c_size_t(0)
+    _check(_lib.flexco_workspace_bytes(C.byref(cfg), T_max, n_parts_max, win_max, kv_max, C.byref(out)))
+    return out.value
+
+
+def _opt(struct):
+    return C.byref(struct) if struct is not None else None
+
+
+def flexco_layer_forward(cfg, w, lora, maps, x_in, x_out, pool, ft, ws, ws_bytes, stream=None):
+    _check(_lib.flexco_layer_forward(C.byref(cfg), C.byref(w), _opt(lora), C.byref(maps), _ptr(x_in), _ptr(x_out),
+                                     C.byref(pool), _opt(ft), _ptr(ws), ws_bytes, _stream(stream)))
+
+
+def flexco_attention_mixed(cfg, maps, q, pool, out, lse, ws, ws_bytes, stream=None):
+    _check(_lib.flexco_attention_mixed(C.byref(cfg), C.byref(maps), _ptr(q), C.byref(pool), _ptr(out), _ptr(lse),
+                                       _ptr(ws), ws_bytes, _stream(stream)))
+
+
+def flexco_lora_fwd(x, y, T, in_features, out_features, rank, scale, dtype, A_list, B_list, seg_off, seg_adapter,
+                    u_ws, stream=None):
+    n = len(A_list)
+    Aarr = (C.c_void_p * n)(*[_ptr(a) for a in A_list])
+    Barr = (C.c_void_p * n)(*[_ptr(b) for b in B_list])
+    so, sa = _i32(seg_off), _i32(seg_adapter)
+    ip = lambda a: a.ctypes.data_as(C.POINTER(C.c_int32))
+    _check(_lib.flexco_lora_fwd(_ptr(x), _ptr(y), T, in_features, out_features, rank, scale, dtype, Aarr, Barr, n,
+                                ip(so), ip(sa), len(sa), _ptr(u_ws), _stream(stream)))
+
+
+def flexco_lora_bwd(cfg, w, lora, pool, seq_pages, n_seq_pages, ft, win_start, win_len, dY, dX, ws, ws_bytes,
+                    stream=None):
+    _check(_lib.flexco_lora_bwd(C.byref(cfg), C.byref(w), _opt(lora), C.byref(pool), _ptr(seq_pages), n_seq_pages,
+                                C.byref(ft), win_start, win_len, _ptr(dY), _ptr(dX), _ptr(ws), ws_bytes,
+                                _stream(stream)))
+
+
+def flexco_attention_window_bwd(cfg, pool, seq_pages, n_seq_pages, win_start, win_len, q, out, lse, dout, dq,
+                                dk_accum, dv_accum, ws, ws_bytes, stream=None):
+    _check(_lib.flexco_attention_window_bwd(C.byref(cfg), C.byref(pool), _ptr(seq_pages), n_seq_pages, win_start,
+                                            win_len, _ptr(q), _ptr(out), _ptr(lse), _ptr(dout), _ptr(dq),
+                                            _ptr(dk_accum), _ptr(dv_accum), _ptr(ws), ws_bytes, _stream(stream)))
+
+
+def flexco_gemm(A, W, Cout, bias, residual, M, N, K, trans_w, dtype, stream=None):
+    _check(_lib.flexco_gemm(_ptr(A), _ptr(W), _ptr(Cout), _ptr(bias), _ptr(residual), M, N, K, int(trans_w), dtype,
+                            _stream(stream)))

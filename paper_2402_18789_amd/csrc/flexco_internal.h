@@ -1,0 +1,70 @@
+// Internal declarations shared by the host API and the kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "flexco.h"
+
+namespace flexco {
+
+int32_t fail(int32_t code, const char* fmt, ...);
+void clear_error();
+
+#define FLEXCO_CHECK(cond, code, ...) \
+  do { if (!(cond)) return ::flexco::fail((code), __VA_ARGS__); } while (0)
+#define FLEXCO_TRY(expr) \
+  do { int32_t rc_ = (expr); if (rc_ != FLEXCO_OK) return rc_; } while (0)
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t esize(int dtype) { return dtype == FLEXCO_BF16 ? 2 : 4; }
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---- launchers: no validation, the entry points have done it -------------------------
+// C[M,N] = A[M,K] W[N,K]^T (+bias) (+residual);  trans_w: W is [K,N].  Leading dimensions in elements.
+int32_t launch_gemm(const void* A, const void* W, void* C, const void* bias, const void* residual, int M, int N,
+                    int K, size_t lda, size_t ldw, size_t ldc, size_t ldr, bool trans_w, int dtype, hipStream_t s);
+int32_t launch_gemm_generic(const void* A, const void* W, void* C, const void* bias, const void* residual, int M,
+                            int N, int K, size_t lda, size_t ldw, size_t ldc, size_t ldr, bool trans_w, int dtype,
+                            hipStream_t s);
+// bf16 MFMA path; returns FLEXCO_EUNSUPPORTED (without launching) for shapes it does not cover
+int32_t launch_gemm_mfma(const void* A, const void* W, void* C, const void* bias, const void* residual, int M,
+                         int N, int K, size_t lda, size_t ldw, size_t ldc, size_t ldr, bool trans_w, hipStream_t s);
+
+int32_t launch_rmsnorm(const void* x, const void* g, void* h, int T, int H, float eps, int dtype, hipStream_t s);
+int32_t launch_rmsnorm_bwd(const void* x, const void* g, const void* dh, const void* add, void* dx, int T, int H,
+                           float eps, int dtype, hipStream_t s);
+int32_t launch_rope_append(const flexco_layer_cfg& c, void* qkv, const int32_t* tok_pos, const int32_t* slot,
+                           const flexco_kv_pool& pool, int T, int ft_tok0, int n_ft, int ft_pos0, void* q_cache,
+                           hipStream_t s);
+int32_t launch_rope_bwd_pack(const flexco_layer_cfg& c, const void* dq, const float* dk_rows, const float* dv_rows,
+                             void* dqkv, int win_start, int n, hipStream_t s);
+int32_t launch_swiglu(const void* gu, void* act, int T, int F, int dtype, hipStream_t s);
+int32_t launch_swiglu_bwd(const void* gate, const void* up, const void* dact, void* dgu, int n, int F, int dtype,
+                          hipStream_t s);
+int32_t launch_swiglu_remat(const void* gate, const void* up, void* act, int n, int F, int dtype, hipStream_t s);
+int32_t launch_copy_rows(const void* src, size_t ld_src_bytes, void* dst, size_t ld_dst_bytes, int n_rows,
+                         size_t width_bytes, hipStream_t s);
+
+int32_t launch_lora_shrink(const void* x, size_t ldx, const void* A, float* u, int n, int in, int r, int dtype,
+                           const int32_t* row_idx, hipStream_t s);
+int32_t launch_lora_expand(const float* u, const void* B, void* y, size_t ldy, int n, int out, int r, float scale,
+                           int dtype, const int32_t* row_idx, hipStream_t s);
+int32_t launch_lora_bwd(const void* x, size_t ldx, const void* dy, size_t lddy, const void* A, const void* B,
+                        float* dA, float* dB, void* dx, size_t lddx, float* u_ws, float* t_ws, int n, int in,
+                        int out, int r, float scale, int dtype, hipStream_t s);
+
+int32_t launch_attention_generic(const flexco_layer_cfg& c, const flexco_maps& m, const void* q, size_t ldq,
+                                 const flexco_kv_pool& pool, float* part_ml, float* part_acc, hipStream_t s);
+// bf16, head_dim 128, page_size 16, group <= 16; otherwise FLEXCO_EUNSUPPORTED without launching
+int32_t launch_attention_mfma(const flexco_layer_cfg& c, const flexco_maps& m, const void* q, size_t ldq,
+                              const flexco_kv_pool& pool, float* part_ml, float* part_acc, hipStream_t s);
+int32_t launch_attention_merge(const flexco_layer_cfg& c, const flexco_maps& m, const float* part_ml,
+                               const float* part_acc, void* out, size_t ldo, float* lse, hipStream_t s);
+int32_t launch_attention_delta(const flexco_layer_cfg& c, const void* out, const void* dout, float* delta, int n,
+                               hipStream_t s);
+int32_t launch_attention_bwd_generic(const flexco_layer_cfg& c, const flexco_kv_pool& pool, const int32_t* seq_pages,
+                                     int win_start, int win_len, const void* q, const float* lse, const float* delta,
+                                     const void* dout, void* dq, float* dk_accum, float* dv_accum, hipStream_t s);
+
+}  // namespace flexco

@@ -1,0 +1,245 @@
+// Host side of the boundary: error reporting and the index maps of a mixed batch.
+//
+// The hybrid token scheduler (Sec. 6.2 of the paper) decides which inference requests and
+// how many finetuning tokens share an iteration; this file turns that decision into the
+// integer arrays the kernels index with.  Pure host code, no device calls.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <algorithm>
+#include <unordered_set>
+#include <vector>
+
+#include "flexco_internal.h"
+
+namespace flexco {
+
+static thread_local char g_err[512] = "";
+
+int32_t fail(int32_t code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+void clear_error() { g_err[0] = 0; }
+
+namespace {
+
+struct Built {
+  std::vector<int32_t> tok_req, tok_pos, slot, req_tok_off, req_kv_len, req_kind, block_table, ft_tok,
+      seg_off, seg_adapter, lora_tok, tile_req, tile_tok0, tile_ntok, tile_nsplit, tile_part0, item_tile,
+      item_split, tok_tile;
+  int32_t T = 0, n_ft = 0, n_seg = 0, max_pages = 1, n_parts = 0, ft_req = -1, max_kv_len = 0;
+  int32_t tile_tokens = 1, split_pages = 32, ft_pos0 = 0;
+};
+
+int32_t validate_desc(const flexco_batch_desc* d, int32_t page_size, int32_t nq, int32_t nkv) {
+  FLEXCO_CHECK(d != nullptr, FLEXCO_EINVAL, "batch descriptor is NULL");
+  FLEXCO_CHECK(d->n_req > 0, FLEXCO_EINVAL, "n_req must be positive (got %d)", d->n_req);
+  FLEXCO_CHECK(d->kind && d->start_pos && d->n_new && d->adapter && d->req_page_off && d->req_pages,
+               FLEXCO_EINVAL, "batch descriptor has a NULL array");
+  FLEXCO_CHECK(page_size > 0, FLEXCO_EINVAL, "page_size must be positive (got %d)", page_size);
+  FLEXCO_CHECK(nq > 0 && nkv > 0 && nq % nkv == 0, FLEXCO_ESHAPE,
+               "n_kv_heads (%d) must divide n_q_heads (%d)", nkv, nq);
+  return FLEXCO_OK;
+}
+
+// Fills `b`.  With count_only the page checks are skipped (sizes only).
+int32_t build(const flexco_batch_desc* d, int32_t page_size, int32_t num_pages, int32_t nq, int32_t nkv,
+              int32_t kv_split_pages, Built& b, bool count_only) {
+  const int group = nq / nkv;
+  b.tile_tokens = std::max(1, 16 / group);
+  b.split_pages = kv_split_pages > 0 ? kv_split_pages : 32;
+  FLEXCO_CHECK(b.split_pages % 2 == 0, FLEXCO_EINVAL, "kv_split_pages must be even (got %d)", b.split_pages);
+  const int n_req = d->n_req;
+  std::vector<int32_t> need(n_req);
+  int64_t T64 = 0;
+  for (int r = 0; r < n_req; ++r) {
+    FLEXCO_CHECK(d->kind[r] >= 0 && d->kind[r] <= 2, FLEXCO_EINVAL, "request %d: unknown kind %d", r, d->kind[r]);
+    FLEXCO_CHECK(d->n_new[r] > 0, FLEXCO_EINVAL, "request %d: n_new must be positive (got %d)", r, d->n_new[r]);
+    FLEXCO_CHECK(d->start_pos[r] >= 0, FLEXCO_EINVAL, "request %d: negative start_pos", r);
+    FLEXCO_CHECK(d->adapter[r] >= -1, FLEXCO_EINVAL, "request %d: adapter id %d", r, d->adapter[r]);
+    const int64_t kv_len = (int64_t)d->start_pos[r] + d->n_new[r];
+    FLEXCO_CHECK(kv_len < (1ll << 30), FLEXCO_EINVAL, "request %d: kv_len too large", r);
+    const int32_t n_have = d->req_page_off[r + 1] - d->req_page_off[r];
+    FLEXCO_CHECK(n_have >= 0, FLEXCO_EINVAL, "request %d: req_page_off not ascending", r);
+    need[r] = (int32_t)((kv_len + page_size - 1) / page_size);
+    FLEXCO_CHECK(need[r] <= n_have, FLEXCO_EPAGE, "request %d: kv_len %lld exceeds its %d pages of %d", r,
+                 (long long)kv_len, n_have, page_size);
+    if (d->kind[r] == FLEXCO_FINETUNE) {
+      FLEXCO_CHECK(b.ft_req < 0, FLEXCO_EUNSUPPORTED,
+                   "more than one finetune request in a batch (requests %d and %d)", b.ft_req, r);
+      b.ft_req = r;
+      b.ft_pos0 = d->start_pos[r];
+    }
+    b.max_pages = std::max(b.max_pages, need[r]);
+    b.max_kv_len = std::max<int32_t>(b.max_kv_len, (int32_t)kv_len);
+    T64 += d->n_new[r];
+  }
+  FLEXCO_CHECK(T64 < (1ll << 24), FLEXCO_EINVAL, "batch of %lld tokens is too large", (long long)T64);
+  b.T = (int32_t)T64;
+  b.req_tok_off.assign(1, 0);
+  b.block_table.assign((size_t)n_req * b.max_pages, -1);
+  std::unordered_set<int64_t> seen;
+  if (!count_only) seen.reserve((size_t)b.T * 2);
+  int32_t prev_adapter = 0;
+  for (int r = 0; r < n_req; ++r) {
+    const int32_t* pages = d->req_pages + d->req_page_off[r];
+    for (int p = 0; p < need[r]; ++p) {
+      if (!count_only)
+        FLEXCO_CHECK(pages[p] >= 0 && pages[p] < num_pages, FLEXCO_EPAGE,
+                     "request %d: page id %d outside [0, %d)", r, pages[p], num_pages);
+      b.block_table[(size_t)r * b.max_pages + p] = pages[p];
+    }
+    const int t_first = (int)b.tok_req.size();
+    for (int i = 0; i < d->n_new[r]; ++i) {
+      const int32_t pos = d->start_pos[r] + i;
+      const int64_t slot = (int64_t)pages[pos / page_size] * page_size + pos % page_size;
+      if (!count_only) {
+        FLEXCO_CHECK(slot < (1ll << 31), FLEXCO_EPAGE, "request %d: slot index overflows int32", r);
+        FLEXCO_CHECK(seen.insert(slot).second, FLEXCO_EPAGE,
+                     "request %d position %d: cache slot %lld is written twice in this batch", r, pos,
+                     (long long)slot);
+      }
+      const int t = (int)b.tok_req.size();
+      if (t == 0 || d->adapter[r] != prev_adapter) {
+        b.seg_off.push_back(t);
+        b.seg_adapter.push_back(d->adapter[r]);
+        prev_adapter = d->adapter[r];
+      }
+      b.tok_req.push_back(r);
+      b.tok_pos.push_back(pos);
+      b.slot.push_back((int32_t)slot);
+      if (d->adapter[r] >= 0) b.lora_tok.push_back(t);
+      if (d->kind[r] == FLEXCO_FINETUNE) b.ft_tok.push_back(t);
+    }
+    b.req_tok_off.push_back((int32_t)b.tok_req.size());
+    b.req_kv_len.push_back(d->start_pos[r] + d->n_new[r]);
+    b.req_kind.push_back(d->kind[r]);
+    // attention work list: column tiles of this request, each cut into key splits
+    for (int t0 = t_first; t0 < (int)b.tok_req.size(); t0 += b.tile_tokens) {
+      const int ntok = std::min<int>(b.tile_tokens, (int)b.tok_req.size() - t0);
+      const int last_pos = b.tok_pos[t0 + ntok - 1];
+      const int vis_pages = last_pos / page_size + 1;
+      const int nsplit = (vis_pages + b.split_pages - 1) / b.split_pages;
+      const int tile = (int)b.tile_req.size();
+      b.tile_req.push_back(r);
+      b.tile_tok0.push_back(t0);
+      b.tile_ntok.push_back(ntok);
+      b.tile_nsplit.push_back(nsplit);
+      b.tile_part0.push_back(b.n_parts);
+      b.n_parts += nsplit;
+      for (int s = 0; s < nsplit; ++s) {
+        b.item_tile.push_back(tile);
+        b.item_split.push_back(s);
+      }
+      for (int i = 0; i < ntok; ++i) b.tok_tile.push_back(tile);
+    }
+  }
+  b.seg_off.push_back(b.T);
+  b.n_seg = (int32_t)b.seg_adapter.size();
+  b.n_ft = (int32_t)b.ft_tok.size();
+  return FLEXCO_OK;
+}
+
+struct BlobWriter {
+  int32_t* blob;
+  size_t cap, used = 0;
+  bool ok = true;
+  const int32_t* put(const std::vector<int32_t>& v) {
+    const size_t n = (v.size() + 3) / 4 * 4;   // keep every array 16-byte aligned
+    if (used + n > cap) { ok = false; return nullptr; }
+    int32_t* p = blob + used;
+    if (!v.empty()) memcpy(p, v.data(), v.size() * sizeof(int32_t));
+    for (size_t i = v.size(); i < n; ++i) p[i] = 0;
+    used += n;
+    return p;
+  }
+};
+
+size_t blob_need(const Built& b) {
+  size_t n = 0;
+  auto add = [&](const std::vector<int32_t>& v) { n += (v.size() + 3) / 4 * 4; };
+  add(b.tok_req); add(b.tok_pos); add(b.slot); add(b.req_tok_off); add(b.req_kv_len); add(b.req_kind);
+  add(b.block_table); add(b.ft_tok); add(b.seg_off); add(b.seg_adapter); add(b.lora_tok); add(b.tile_req);
+  add(b.tile_tok0); add(b.tile_ntok); add(b.tile_nsplit); add(b.tile_part0); add(b.item_tile);
+  add(b.item_split); add(b.tok_tile);
+  return n;
+}
+
+}  // namespace
+}  // namespace flexco
+
+using namespace flexco;
+
+extern "C" const char* flexco_last_error(void) { return g_err; }
+
+extern "C" int32_t flexco_abi_version(void) { return 1; }
+
+extern "C" int32_t flexco_maps_blob_ints(const flexco_batch_desc* desc, int32_t page_size, int32_t n_q_heads,
+                                         int32_t n_kv_heads, int32_t kv_split_pages, size_t* out_ints) {
+  clear_error();
+  FLEXCO_CHECK(out_ints != nullptr, FLEXCO_EINVAL, "out_ints is NULL");
+  int32_t rc = validate_desc(desc, page_size, n_q_heads, n_kv_heads);
+  if (rc) return rc;
+  Built b;
+  rc = build(desc, page_size, 0, n_q_heads, n_kv_heads, kv_split_pages, b, true);
+  if (rc) return rc;
+  *out_ints = blob_need(b);
+  return FLEXCO_OK;
+}
+
+extern "C" int32_t flexco_build_maps(const flexco_batch_desc* desc, int32_t page_size, int32_t num_pages,
+                                     int32_t n_q_heads, int32_t n_kv_heads, int32_t kv_split_pages,
+                                     int32_t* blob, size_t blob_ints, flexco_maps* out) {
+  clear_error();
+  FLEXCO_CHECK(blob != nullptr && out != nullptr, FLEXCO_EINVAL, "blob or out is NULL");
+  FLEXCO_CHECK(num_pages > 0, FLEXCO_EINVAL, "num_pages must be positive (got %d)", num_pages);
+  int32_t rc = validate_desc(desc, page_size, n_q_heads, n_kv_heads);
+  if (rc) return rc;
+  Built b;
+  rc = build(desc, page_size, num_pages, n_q_heads, n_kv_heads, kv_split_pages, b, false);
+  if (rc) return rc;
+  const size_t need = blob_need(b);
+  FLEXCO_CHECK(need <= blob_ints, FLEXCO_EWORKSPACE, "maps need %zu int32 words, blob has %zu", need, blob_ints);
+  BlobWriter w{blob, blob_ints};
+  flexco_maps m;
+  memset(&m, 0, sizeof(m));
+  m.T = b.T; m.n_req = desc->n_req; m.n_ft = b.n_ft; m.n_seg = b.n_seg; m.max_pages = b.max_pages;
+  m.page_size = page_size; m.n_tiles = (int32_t)b.tile_req.size(); m.n_items = (int32_t)b.item_tile.size();
+  m.n_parts = b.n_parts; m.tile_tokens = b.tile_tokens; m.kv_split_pages = b.split_pages;
+  m.ft_req = b.ft_req; m.max_kv_len = b.max_kv_len;
+  m.ft_tok0 = b.ft_req >= 0 ? b.req_tok_off[b.ft_req] : 0; m.ft_pos0 = b.ft_pos0;
+  m.n_lora = (int32_t)b.lora_tok.size();
+  m.tok_req = w.put(b.tok_req); m.tok_pos = w.put(b.tok_pos); m.slot = w.put(b.slot);
+  m.req_tok_off = w.put(b.req_tok_off); m.req_kv_len = w.put(b.req_kv_len); m.req_kind = w.put(b.req_kind);
+  m.block_table = w.put(b.block_table); m.ft_tok = w.put(b.ft_tok); m.seg_off = w.put(b.seg_off);
+  m.seg_adapter = w.put(b.seg_adapter); m.lora_tok = w.put(b.lora_tok); m.tile_req = w.put(b.tile_req);
+  m.tile_tok0 = w.put(b.tile_tok0); m.tile_ntok = w.put(b.tile_ntok); m.tile_nsplit = w.put(b.tile_nsplit);
+  m.tile_part0 = w.put(b.tile_part0); m.item_tile = w.put(b.item_tile); m.item_split = w.put(b.item_split);
+  m.tok_tile = w.put(b.tok_tile);
+  FLEXCO_CHECK(w.ok, FLEXCO_EWORKSPACE, "blob too small");
+  m.blob_ints = (int32_t)w.used;
+  *out = m;
+  return FLEXCO_OK;
+}
+
+extern "C" int32_t flexco_maps_rebase(const flexco_maps* host_maps, const int32_t* host_blob,
+                                      const int32_t* other_blob, flexco_maps* out) {
+  clear_error();
+  FLEXCO_CHECK(host_maps && host_blob && other_blob && out, FLEXCO_EINVAL, "NULL argument");
+  flexco_maps m = *host_maps;
+  const int32_t** fields[] = {&m.tok_req, &m.tok_pos, &m.slot, &m.req_tok_off, &m.req_kv_len, &m.req_kind,
+                              &m.block_table, &m.ft_tok, &m.seg_off, &m.seg_adapter, &m.lora_tok, &m.tile_req,
+                              &m.tile_tok0, &m.tile_ntok, &m.tile_nsplit, &m.tile_part0, &m.item_tile,
+                              &m.item_split, &m.tok_tile};
+  for (auto f : fields) {
+    FLEXCO_CHECK(*f >= host_blob && *f <= host_blob + m.blob_ints, FLEXCO_EINVAL,
+                 "maps do not point into host_blob");
+    *f = other_blob + (*f - host_blob);
+  }
+  *out = m;
+  return FLEXCO_OK;
+}

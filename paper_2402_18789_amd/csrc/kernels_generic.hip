@@ -1,0 +1,533 @@
+// Element-wise, normalisation, RoPE/cache-append, LoRA and type-generic fallback kernels.
+//
+// Everything here computes in fp32 whatever the storage type, one thread block per row or
+// per small tile.  These kernels carry the fp32 configuration end to end and the parts of
+// the bf16 configurations that are bound by HBM traffic or are tiny (norms, RoPE, SwiGLU,
+// rank-r LoRA products).  The dense bf16 contractions live in gemm_mfma.hip /
+// attn_mfma.hip.
+#include "flexco_internal.h"
+#include "device_types.h"
+
+namespace flexco {
+
+// --------------------------------------------------------------------------------------
+// reductions
+// --------------------------------------------------------------------------------------
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ inline float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+// sum over a block of 256 threads; every thread gets the result
+__device__ inline float block_sum256(float v, float* red /* >= 4 floats of LDS */) {
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return red[0] + red[1] + red[2] + red[3];
+}
+
+// --------------------------------------------------------------------------------------
+// RMSNorm forward / backward (one block of 256 threads per row)
+// --------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const T* __restrict__ x, const T* __restrict__ g,
+                                                      T* __restrict__ h, int H, float eps) {
+  __shared__ float red[4];
+  const size_t row = blockIdx.x;
+  const T* xr = x + row * H;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < H; i += 256) { float v = ld(xr + i); ss += v * v; }
+  ss = block_sum256(ss, red);
+  const float rstd = 1.0f / sqrtf(ss / H + eps);
+  for (int i = threadIdx.x; i < H; i += 256) st(h + row * H + i, ld(xr + i) * rstd * ld(g + i));
+}
+
+// dx = rstd * (g * dh) - x * rstd^3 * mean(x * g * dh)  (+ add)
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* __restrict__ x, const T* __restrict__ g,
+                                                          const T* __restrict__ dh, const T* __restrict__ add,
+                                                          T* __restrict__ dx, int H, float eps) {
+  __shared__ float red[4];
+  const size_t row = blockIdx.x;
+  const T* xr = x + row * H;
+  const T* dr = dh + row * H;
+  float ss = 0.f, sd = 0.f;
+  for (int i = threadIdx.x; i < H; i += 256) {
+    float v = ld(xr + i);
+    ss += v * v;
+    sd += v * ld(g + i) * ld(dr + i);
+  }
+  ss = block_sum256(ss, red);
+  sd = block_sum256(sd, red);
+  const float rstd = 1.0f / sqrtf(ss / H + eps);
+  const float coef = rstd * rstd * rstd * sd / H;
+  for (int i = threadIdx.x; i < H; i += 256) {
+    float v = rstd * ld(g + i) * ld(dr + i) - ld(xr + i) * coef;
+    if (add) v += ld(add + row * H + i);
+    st(dx + row * H + i, v);
+  }
+}
+
+// --------------------------------------------------------------------------------------
+// RoPE + cache append (Alg. 2: Forward then Append of Q, K, V).  One block per token.
+//   qkv row = [q heads | k heads | v heads]; q is rotated in place, k is rotated and
+//   written to the K pages, v is written to the (position-minor) V pages, and rows of
+//   the finetune window also store the rotated q in the sequence's Q cache.
+// --------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void rope_append_kernel(T* __restrict__ qkv, const int32_t* __restrict__ tok_pos,
+                                                          const int32_t* __restrict__ slot, T* __restrict__ kp,
+                                                          T* __restrict__ vp, int nq, int nkv, int d, int ps,
+                                                          float theta, int ft_tok0, int n_ft, int ft_pos0,
+                                                          T* __restrict__ q_cache) {
+  extern __shared__ float cs[];   // cos[d/2], sin[d/2]
+  const int t = blockIdx.x;
+  const int pos = tok_pos[t];
+  const int half = d >> 1;
+  for (int i = threadIdx.x; i < half; i += 256) {
+    const double inv = pow((double)theta, -2.0 * (double)i / (double)d);
+    double sn, c;
+    sincos((double)pos * inv, &sn, &c);
+    cs[i] = (float)c;
+    cs[half + i] = (float)sn;
+  }
+  __syncthreads();
+  const int qkv_dim = (nq + 2 * nkv) * d;
+  T* row = qkv + (size_t)t * qkv_dim;
+  const int sl = slot[t];
+  const size_t page = sl / ps;
+  const int pip = sl % ps;
+  const bool is_ft = (t >= ft_tok0 && t < ft_tok0 + n_ft);
+  // rotate q and k heads
+  for (int idx = threadIdx.x; idx < (nq + nkv) * half; idx += 256) {
+    const int head = idx / half, i = idx % half;
+    T* hp = row + head * d;
+    const float lo = ld(hp + i), hi = ld(hp + half + i);
+    const float c = cs[i], sn = cs[half + i];
+    const float rlo = lo * c - hi * sn, rhi = hi * c + lo * sn;
+    if (head < nq) {
+      st(hp + i, rlo);
+      st(hp + half + i, rhi);
+      if (is_ft) {
+        T* qc = q_cache + (size_t)(ft_pos0 + (t - ft_tok0)) * nq * d + head * d;
+        st(qc + i, rlo);
+        st(qc + half + i, rhi);
+      }
+    } else {
+      const int kh = head - nq;
+      T* dst = kp + ((page * nkv + kh) * ps + pip) * (size_t)d;
+      st(dst + i, rlo);
+      st(dst + half + i, rhi);
+    }
+  }
+  const T* vrow = row + (nq + nkv) * d;
+  for (int idx = threadIdx.x; idx < nkv * d; idx += 256) {
+    const int kh = idx / d, i = idx % d;
+    vp[((page * nkv + kh) * (size_t)d + i) * ps + pip] = vrow[idx];
+  }
+}
+
+// Backward of the q/k/v rotation for a window: dqkv[n, (nq+2nkv)d] = [rope^T(dq) | rope^T(dk) | dv]
+// dq rows are in the storage type, dk/dv rows are the (float) accumulator rows of the window.
+template <typename T>
+__global__ __launch_bounds__(256) void rope_bwd_pack_kernel(const T* __restrict__ dq, const float* __restrict__ dk,
+                                                            const float* __restrict__ dv, T* __restrict__ dqkv,
+                                                            int nq, int nkv, int d, float theta, int win_start) {
+  extern __shared__ float cs[];
+  const int r = blockIdx.x;
+  const int pos = win_start + r;
+  const int half = d >> 1;
+  for (int i = threadIdx.x; i < half; i += 256) {
+    const double inv = pow((double)theta, -2.0 * (double)i / (double)d);
+    double sn, c;
+    sincos((double)pos * inv, &sn, &c);
+    cs[i] = (float)c;
+    cs[half + i] = (float)sn;
+  }
+  __syncthreads();
+  T* out = dqkv + (size_t)r * (nq + 2 * nkv) * d;
+  for (int idx = threadIdx.x; idx < (nq + nkv) * half; idx += 256) {
+    const int head = idx / half, i = idx % half;
+    float lo, hi;
+    if (head < nq) {
+      const T* p = dq + (size_t)r * nq * d + head * d;
+      lo = ld(p + i); hi = ld(p + half + i);
+    } else {
+      const float* p = dk + (size_t)r * nkv * d + (head - nq) * d;
+      lo = p[i]; hi = p[half + i];
+    }
+    const float c = cs[i], sn = cs[half + i];
+    // transpose of the rotation: turn by the negative angle
+    st(out + head * d + i, lo * c + hi * sn);
+    st(out + head * d + half + i, hi * c - lo * sn);
+  }
+  for (int idx = threadIdx.x; idx < nkv * d; idx += 256)
+    st(out + (nq + nkv) * d + idx, dv[(size_t)r * nkv * d + idx]);
+}
+
+// --------------------------------------------------------------------------------------
+// SwiGLU forward / backward
+// --------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void swiglu_kernel(const T* __restrict__ gu, T* __restrict__ act, int F) {
+  const size_t row = blockIdx.y;
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= F) return;
+  const float g = ld(gu + row * 2 * F + i), u = ld(gu + row * 2 * F + F + i);
+  st(act + row * F + i, g / (1.0f + __expf(-g)) * u);
+}
+
+// from saved gate, up and dact: dgu = [dgate | dup]; optionally also act (rematerialised)
+template <typename T>
+__global__ __launch_bounds__(256) void swiglu_bwd_kernel(const T* __restrict__ gate, const T* __restrict__ up,
+                                                         const T* __restrict__ dact, T* __restrict__ dgu,
+                                                         int F) {
+  const size_t row = blockIdx.y;
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= F) return;
+  const float g = ld(gate + row * F + i), u = ld(up + row * F + i), da = ld(dact + row * F + i);
+  const float sg = 1.0f / (1.0f + __expf(-g));
+  st(dgu + row * 2 * F + i, da * u * (sg + g * sg * (1.0f - sg)));
+  st(dgu + row * 2 * F + F + i, da * g * sg);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void swiglu_remat_kernel(const T* __restrict__ gate, const T* __restrict__ up,
+                                                           T* __restrict__ act, int F) {
+  const size_t row = blockIdx.y;
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= F) return;
+  const float g = ld(gate + row * F + i), u = ld(up + row * F + i);
+  st(act + row * F + i, g / (1.0f + __expf(-g)) * u);
+}
+
+// --------------------------------------------------------------------------------------
+// strided row copy: dst row i = src row i, `width` units of V (uint4 = 16 bytes, or 4-byte words)
+// --------------------------------------------------------------------------------------
+template <typename V>
+__global__ __launch_bounds__(256) void copy_rows_kernel(const char* __restrict__ src, size_t ld_src,
+                                                        char* __restrict__ dst, size_t ld_dst, int width) {
+  const size_t row = blockIdx.y;
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= width) return;
+  reinterpret_cast<V*>(dst + row * ld_dst)[i] = reinterpret_cast<const V*>(src + row * ld_src)[i];
+}
+
+// --------------------------------------------------------------------------------------
+// LoRA building blocks on a row range.  S(i, j) denotes element (long index i, rank index j)
+// of a LoRA matrix, addressed as S[i * s_i + j * s_j], so that the same kernels serve
+// A [r, in] (s_i = 1, s_j = in) and B [out, r] (s_i = r, s_j = 1).
+// --------------------------------------------------------------------------------------
+// out[m, j] = sum_i X[m, i] * S(i, j)        one block per row m; R = rank bound
+template <typename T, int R>
+__global__ __launch_bounds__(256) void lora_reduce_long_kernel(const T* __restrict__ X, size_t ldx,
+                                                               const T* __restrict__ S, size_t s_i, size_t s_j,
+                                                               float* __restrict__ out, int n_long, int r,
+                                                               const int32_t* __restrict__ row_idx) {
+  __shared__ float red[4][R];
+  const size_t mo = blockIdx.x;
+  const size_t m = row_idx ? (size_t)row_idx[mo] : mo;
+  float acc[R];
+#pragma unroll
+  for (int j = 0; j < R; ++j) acc[j] = 0.f;
+  for (int i = threadIdx.x; i < n_long; i += 256) {
+    const float xv = ld(X + m * ldx + i);
+#pragma unroll
+    for (int j = 0; j < R; ++j)
+      if (j < r) acc[j] += xv * ld(S + (size_t)i * s_i + (size_t)j * s_j);
+  }
+#pragma unroll
+  for (int j = 0; j < R; ++j) {
+    const float v = wave_sum(acc[j]);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6][j] = v;
+  }
+  __syncthreads();
+  if (threadIdx.x < r) out[mo * r + threadIdx.x] = red[0][threadIdx.x] + red[1][threadIdx.x] + red[2][threadIdx.x] + red[3][threadIdx.x];
+}
+
+// Y[m, i] += scale * sum_j U[m, j] * S(i, j)     grid (ceil(n_long/256), ceil(n/16))
+template <typename T, int R>
+__global__ __launch_bounds__(256) void lora_expand_kernel(const float* __restrict__ U, const T* __restrict__ S,
+                                                          size_t s_i, size_t s_j, T* __restrict__ Y, size_t ldy,
+                                                          int n, int n_long, int r, float scale,
+                                                          const int32_t* __restrict__ row_idx) {
+  __shared__ float us[16][R];
+  const int m0 = blockIdx.y * 16;
+  for (int idx = threadIdx.x; idx < 16 * R; idx += 256) {
+    const int mm = idx / R, j = idx % R;
+    us[mm][j] = (m0 + mm < n && j < r) ? U[(size_t)(m0 + mm) * r + j] : 0.f;
+  }
+  __syncthreads();
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= n_long) return;
+  float sv[R];
+#pragma unroll
+  for (int j = 0; j < R; ++j) sv[j] = (j < r) ? ld(S + (size_t)i * s_i + (size_t)j * s_j) : 0.f;
+  for (int mm = 0; mm < 16 && m0 + mm < n; ++mm) {
+    float a = 0.f;
+#pragma unroll
+    for (int j = 0; j < R; ++j) a += us[mm][j] * sv[j];
+    const size_t yr = row_idx ? (size_t)row_idx[m0 + mm] : (size_t)(m0 + mm);
+    T* y = Y + yr * ldy + i;
+    st(y, ld(y) + scale * a);
+  }
+}
+
+// G(i, j) += scale * sum_m X[m, i] * U[m, j]      one thread per long index i, all ranks j
+template <typename T, int R>
+__global__ __launch_bounds__(256) void lora_outer_kernel(const T* __restrict__ X, size_t ldx,
+                                                         const float* __restrict__ U, float* __restrict__ G,
+                                                         size_t g_i, size_t g_j, int n, int n_long, int r,
+                                                         float scale) {
+  __shared__ float us[64][R];
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  float acc[R];
+#pragma unroll
+  for (int j = 0; j < R; ++j) acc[j] = 0.f;
+  for (int m0 = 0; m0 < n; m0 += 64) {
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < 64 * R; idx += 256) {
+      const int mm = idx / R, j = idx % R;
+      us[mm][j] = (m0 + mm < n && j < r) ? U[(size_t)(m0 + mm) * r + j] : 0.f;
+    }
+    __syncthreads();
+    if (i < n_long) {
+      const int mend = min(64, n - m0);
+      for (int mm = 0; mm < mend; ++mm) {
+        const float xv = ld(X + (size_t)(m0 + mm) * ldx + i);
+#pragma unroll
+        for (int j = 0; j < R; ++j) acc[j] += xv * us[mm][j];
+      }
+    }
+  }
+  if (i < n_long) {
+#pragma unroll
+    for (int j = 0; j < R; ++j)
+      if (j < r) G[(size_t)i * g_i + (size_t)j * g_j] += scale * acc[j];
+  }
+}
+
+// --------------------------------------------------------------------------------------
+// type-generic dense projection (fallback and the fp32 configuration)
+//   TRANS_W = false: C[m, n] = sum_k A[m, k] W[n, k]      TRANS_W = true: ... W[k, n]
+// 64 x 64 tile, BK = 16, 256 threads, 4 x 4 outputs per thread, fp32 accumulation.
+// --------------------------------------------------------------------------------------
+template <typename T, bool TRANS_W>
+__global__ __launch_bounds__(256) void gemm_generic_kernel(const T* __restrict__ A, const T* __restrict__ W,
+                                                           T* __restrict__ C, const T* __restrict__ bias,
+                                                           const T* __restrict__ residual, int M, int N, int K,
+                                                           size_t lda, size_t ldw, size_t ldc, size_t ldr) {
+  __shared__ float As[16][64 + 1];
+  __shared__ float Ws[16][64 + 1];
+  const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+  const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
+  float acc[4][4] = {};
+  for (int k0 = 0; k0 < K; k0 += 16) {
+    for (int idx = threadIdx.x; idx < 64 * 16; idx += 256) {
+      const int mm = idx / 16, kk = idx % 16;
+      As[kk][mm] = (m0 + mm < M && k0 + kk < K) ? ld(A + (size_t)(m0 + mm) * lda + k0 + kk) : 0.f;
+      if (!TRANS_W) {
+        Ws[kk][mm] = (n0 + mm < N && k0 + kk < K) ? ld(W + (size_t)(n0 + mm) * ldw + k0 + kk) : 0.f;
+      }
+    }
+    if (TRANS_W) {
+      for (int idx = threadIdx.x; idx < 64 * 16; idx += 256) {
+        const int kk = idx / 64, nn = idx % 64;
+        Ws[kk][nn] = (n0 + nn < N && k0 + kk < K) ? ld(W + (size_t)(k0 + kk) * ldw + n0 + nn) : 0.f;
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk) {
+      float a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { a[i] = As[kk][ty * 4 + i]; b[i] = Ws[kk][tx * 4 + i]; }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] += a[i] * b[j];
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int m = m0 + ty * 4 + i;
+    if (m >= M) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int n = n0 + tx * 4 + j;
+      if (n >= N) continue;
+      float v = acc[i][j];
+      if (bias) v += ld(bias + n);
+      if (residual) v += ld(residual + (size_t)m * ldr + n);
+      st(C + (size_t)m * ldc + n, v);
+    }
+  }
+}
+
+// --------------------------------------------------------------------------------------
+// host launchers
+// --------------------------------------------------------------------------------------
+#define DISPATCH_T(dtype, ...)                                   \
+  do {                                                           \
+    if ((dtype) == FLEXCO_BF16) { using T = bf16_t; __VA_ARGS__; } \
+    else { using T = float; __VA_ARGS__; }                       \
+  } while (0)
+
+static int32_t post_launch(const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(FLEXCO_EHIP, "launch of %s failed: %s", what, hipGetErrorString(e));
+  return FLEXCO_OK;
+}
+
+int32_t launch_gemm_generic(const void* A, const void* W, void* C, const void* bias, const void* residual, int M,
+                            int N, int K, size_t lda, size_t ldw, size_t ldc, size_t ldr, bool trans_w, int dtype,
+                            hipStream_t s) {
+  dim3 grid((N + 63) / 64, (M + 63) / 64);
+  DISPATCH_T(dtype, {
+    if (trans_w)
+      hipLaunchKernelGGL((gemm_generic_kernel<T, true>), grid, dim3(256), 0, s, (const T*)A, (const T*)W, (T*)C,
+                         (const T*)bias, (const T*)residual, M, N, K, lda, ldw, ldc, ldr);
+    else
+      hipLaunchKernelGGL((gemm_generic_kernel<T, false>), grid, dim3(256), 0, s, (const T*)A, (const T*)W, (T*)C,
+                         (const T*)bias, (const T*)residual, M, N, K, lda, ldw, ldc, ldr);
+  });
+  return post_launch("gemm_generic");
+}
+
+int32_t launch_rmsnorm(const void* x, const void* g, void* h, int T_, int H, float eps, int dtype, hipStream_t s) {
+  if (T_ == 0) return FLEXCO_OK;
+  DISPATCH_T(dtype, hipLaunchKernelGGL((rmsnorm_kernel<T>), dim3(T_), dim3(256), 0, s, (const T*)x, (const T*)g,
+                                       (T*)h, H, eps));
+  return post_launch("rmsnorm");
+}
+
+int32_t launch_rmsnorm_bwd(const void* x, const void* g, const void* dh, const void* add, void* dx, int T_, int H,
+                           float eps, int dtype, hipStream_t s) {
+  if (T_ == 0) return FLEXCO_OK;
+  DISPATCH_T(dtype, hipLaunchKernelGGL((rmsnorm_bwd_kernel<T>), dim3(T_), dim3(256), 0, s, (const T*)x,
+                                       (const T*)g, (const T*)dh, (const T*)add, (T*)dx, H, eps));
+  return post_launch("rmsnorm_bwd");
+}
+
+int32_t launch_rope_append(const flexco_layer_cfg& c, void* qkv, const int32_t* tok_pos, const int32_t* slot,
+                           const flexco_kv_pool& pool, int T_, int ft_tok0, int n_ft, int ft_pos0, void* q_cache,
+                           hipStream_t s) {
+  if (T_ == 0) return FLEXCO_OK;
+  const size_t shm = sizeof(float) * c.head_dim;
+  DISPATCH_T(c.dtype, hipLaunchKernelGGL((rope_append_kernel<T>), dim3(T_), dim3(256), shm, s, (T*)qkv, tok_pos,
+                                         slot, (T*)pool.k_pages, (T*)pool.v_pages, c.n_q_heads, c.n_kv_heads,
+                                         c.head_dim, c.page_size, c.rope_theta, ft_tok0, n_ft, ft_pos0,
+                                         (T*)q_cache));
+  return post_launch("rope_append");
+}
+
+int32_t launch_rope_bwd_pack(const flexco_layer_cfg& c, const void* dq, const float* dk_rows, const float* dv_rows,
+                             void* dqkv, int win_start, int n, hipStream_t s) {
+  const size_t shm = sizeof(float) * c.head_dim;
+  DISPATCH_T(c.dtype, hipLaunchKernelGGL((rope_bwd_pack_kernel<T>), dim3(n), dim3(256), shm, s, (const T*)dq,
+                                         dk_rows, dv_rows, (T*)dqkv, c.n_q_heads, c.n_kv_heads, c.head_dim,
+                                         c.rope_theta, win_start));
+  return post_launch("rope_bwd_pack");
+}
+
+int32_t launch_swiglu(const void* gu, void* act, int T_, int F, int dtype, hipStream_t s) {
+  if (T_ == 0) return FLEXCO_OK;
+  DISPATCH_T(dtype, hipLaunchKernelGGL((swiglu_kernel<T>), dim3((F + 255) / 256, T_), dim3(256), 0, s,
+                                       (const T*)gu, (T*)act, F));
+  return post_launch("swiglu");
+}
+
+int32_t launch_swiglu_bwd(const void* gate, const void* up, const void* dact, void* dgu, int n, int F, int dtype,
+                          hipStream_t s) {
+  DISPATCH_T(dtype, hipLaunchKernelGGL((swiglu_bwd_kernel<T>), dim3((F + 255) / 256, n), dim3(256), 0, s,
+                                       (const T*)gate, (const T*)up, (const T*)dact, (T*)dgu, F));
+  return post_launch("swiglu_bwd");
+}
+
+int32_t launch_swiglu_remat(const void* gate, const void* up, void* act, int n, int F, int dtype, hipStream_t s) {
+  DISPATCH_T(dtype, hipLaunchKernelGGL((swiglu_remat_kernel<T>), dim3((F + 255) / 256, n), dim3(256), 0, s,
+                                       (const T*)gate, (const T*)up, (T*)act, F));
+  return post_launch("swiglu_remat");
+}
+
+int32_t launch_copy_rows(const void* src, size_t ld_src_bytes, void* dst, size_t ld_dst_bytes, int n_rows,
+                         size_t width_bytes, hipStream_t s) {
+  if (n_rows == 0 || width_bytes == 0) return FLEXCO_OK;
+  if (width_bytes % 4) return fail(FLEXCO_ESHAPE, "row copy of %zu bytes is not a multiple of 4", width_bytes);
+  const bool v16 = width_bytes % 16 == 0 && ld_src_bytes % 16 == 0 && ld_dst_bytes % 16 == 0 && aligned16(src) &&
+                   aligned16(dst);
+  if (v16) {
+    const int w = (int)(width_bytes / 16);
+    hipLaunchKernelGGL((copy_rows_kernel<uint4>), dim3((w + 255) / 256, n_rows), dim3(256), 0, s, (const char*)src,
+                       ld_src_bytes, (char*)dst, ld_dst_bytes, w);
+  } else {
+    const int w = (int)(width_bytes / 4);
+    hipLaunchKernelGGL((copy_rows_kernel<uint32_t>), dim3((w + 255) / 256, n_rows), dim3(256), 0, s, (const char*)src,
+                       ld_src_bytes, (char*)dst, ld_dst_bytes, w);
+  }
+  return post_launch("copy_rows");
+}
+
+template <int R>
+static int32_t lora_ops(int op, const void* X, size_t ldx, const void* S, size_t s_i, size_t s_j, float* U,
+                        void* Y, size_t ldy, float* G, size_t g_i, size_t g_j, int n, int n_long, int r,
+                        float scale, int dtype, const int32_t* row_idx, hipStream_t s) {
+  DISPATCH_T(dtype, {
+    if (op == 0)
+      hipLaunchKernelGGL((lora_reduce_long_kernel<T, R>), dim3(n), dim3(256), 0, s, (const T*)X, ldx, (const T*)S,
+                         s_i, s_j, U, n_long, r, row_idx);
+    else if (op == 1)
+      hipLaunchKernelGGL((lora_expand_kernel<T, R>), dim3((n_long + 255) / 256, (n + 15) / 16), dim3(256), 0, s, U,
+                         (const T*)S, s_i, s_j, (T*)Y, ldy, n, n_long, r, scale, row_idx);
+    else
+      hipLaunchKernelGGL((lora_outer_kernel<T, R>), dim3((n_long + 255) / 256), dim3(256), 0, s, (const T*)X, ldx,
+                         U, G, g_i, g_j, n, n_long, r, scale);
+  });
+  return post_launch("lora kernel");
+}
+
+static int32_t lora_dispatch(int op, const void* X, size_t ldx, const void* S, size_t s_i, size_t s_j, float* U,
+                             void* Y, size_t ldy, float* G, size_t g_i, size_t g_j, int n, int n_long, int r,
+                             float scale, int dtype, hipStream_t s, const int32_t* row_idx = nullptr) {
+  if (n == 0) return FLEXCO_OK;
+  if (r <= 8) return lora_ops<8>(op, X, ldx, S, s_i, s_j, U, Y, ldy, G, g_i, g_j, n, n_long, r, scale, dtype, row_idx, s);
+  if (r <= 16) return lora_ops<16>(op, X, ldx, S, s_i, s_j, U, Y, ldy, G, g_i, g_j, n, n_long, r, scale, dtype, row_idx, s);
+  if (r <= 32) return lora_ops<32>(op, X, ldx, S, s_i, s_j, U, Y, ldy, G, g_i, g_j, n, n_long, r, scale, dtype, row_idx, s);
+  return lora_ops<64>(op, X, ldx, S, s_i, s_j, U, Y, ldy, G, g_i, g_j, n, n_long, r, scale, dtype, row_idx, s);
+}
+
+// u[n, r] = x[rows, in] A^T,  A [r, in]; rows = row_idx[0..n) or 0..n
+int32_t launch_lora_shrink(const void* x, size_t ldx, const void* A, float* u, int n, int in, int r, int dtype,
+                           const int32_t* row_idx, hipStream_t s) {
+  return lora_dispatch(0, x, ldx, A, 1, (size_t)in, u, nullptr, 0, nullptr, 0, 0, n, in, r, 0.f, dtype, s, row_idx);
+}
+// y[rows, out] += scale * u B^T,  B [out, r]
+int32_t launch_lora_expand(const float* u, const void* B, void* y, size_t ldy, int n, int out, int r, float scale,
+                           int dtype, const int32_t* row_idx, hipStream_t s) {
+  return lora_dispatch(1, nullptr, 0, B, (size_t)r, 1, const_cast<float*>(u), y, ldy, nullptr, 0, 0, n, out, r,
+                       scale, dtype, s, row_idx);
+}
+
+// Gradients of one LoRA bypass on n rows (Sec. 4.1 form y = scale (x A^T) B^T):
+//   u = x A^T; t = dy B; dB += scale dy^T u; dA += scale t^T x; dx += scale t A
+int32_t launch_lora_bwd(const void* x, size_t ldx, const void* dy, size_t lddy, const void* A, const void* B,
+                        float* dA, float* dB, void* dx, size_t lddx, float* u_ws, float* t_ws, int n, int in,
+                        int out, int r, float scale, int dtype, hipStream_t s) {
+  int32_t rc;
+  if ((rc = lora_dispatch(0, x, ldx, A, 1, (size_t)in, u_ws, nullptr, 0, nullptr, 0, 0, n, in, r, 0.f, dtype, s))) return rc;
+  if ((rc = lora_dispatch(0, dy, lddy, B, (size_t)r, 1, t_ws, nullptr, 0, nullptr, 0, 0, n, out, r, 0.f, dtype, s))) return rc;
+  if ((rc = lora_dispatch(2, dy, lddy, nullptr, 0, 0, u_ws, nullptr, 0, dB, (size_t)r, 1, n, out, r, scale, dtype, s))) return rc;
+  if ((rc = lora_dispatch(2, x, ldx, nullptr, 0, 0, t_ws, nullptr, 0, dA, 1, (size_t)in, n, in, r, scale, dtype, s))) return rc;
+  if (dx)
+    if ((rc = lora_dispatch(1, nullptr, 0, A, 1, (size_t)in, t_ws, dx, lddx, nullptr, 0, 0, n, in, r, scale, dtype, s))) return rc;
+  return FLEXCO_OK;
+}
+
+}  // namespace flexco

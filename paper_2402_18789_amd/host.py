@@ -1,0 +1,154 @@
+"""Device-memory owners for the flexco library: weights, KV pool, finetune state, batches.
+
+PyTorch is used for allocation, host<->device copies and layout staging of INPUTS only
+(packing [out, in] weight blocks, scattering seeded prefix rows into pages).  Nothing of
+the layer's computation happens here.
+"""
+import ctypes as C
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16}
+DTYPE_CODE = {"f32": B.FLEXCO_F32, "bf16": B.FLEXCO_BF16}
+
+
+def c_cfg(cfg):
+    mask = sum(1 << B.TARGET_NAMES.index(t) for t in cfg.lora_targets)
+    return B.LayerCfg(cfg.hidden, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.ffn, DTYPE_CODE[cfg.dtype],
+                      cfg.page_size, cfg.lora_rank if mask else 0, mask, cfg.rms_eps, cfg.rope_theta, cfg.lora_scale)
+
+
+def _dev(a, dtype, device):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device=device, dtype=dtype).contiguous()
+
+
+class DeviceLayer:
+    """Frozen weights (+ one LoRA adapter and its gradient buffers) of one layer on the GPU.
+    W: {wq, wk, wv, wo, wg, wu, wd [out, in], g1, g2, optional bq, bk, bv};
+    lora: {target: (A [in, r], B [r, out])} in the paper's orientation (stored transposed)."""
+
+    def __init__(self, cfg, W, lora=None, device="cuda"):
+        self.cfg = cfg
+        self.c = c_cfg(cfg)
+        dt = TORCH_DTYPE[cfg.dtype]
+        self.dtype = dt
+        self.t = {
+            "wqkv": _dev(np.concatenate([W["wq"], W["wk"], W["wv"]], axis=0), dt, device),
+            "wo": _dev(W["wo"], dt, device),
+            "wgu": _dev(np.concatenate([W["wg"], W["wu"]], axis=0), dt, device),
+            "wd": _dev(W["wd"], dt, device),
+            "g1": _dev(W["g1"], dt, device), "g2": _dev(W["g2"], dt, device),
+        }
+        if "bq" in W:
+            self.t["bqkv"] = _dev(np.concatenate([W["bq"], W["bk"], W["bv"]]), dt, device)
+        self.w = B.BaseWeights(self.t["wqkv"].data_ptr(), self.t["bqkv"].data_ptr() if "bqkv" in self.t else None,
+                               self.t["wo"].data_ptr(), self.t["wgu"].data_ptr(), self.t["wd"].data_ptr(),
+                               self.t["g1"].data_ptr(), self.t["g2"].data_ptr())
+        self.lora = None
+        self.A, self.Bm, self.dA, self.dB = {}, {}, {}, {}
+        if lora and cfg.lora_targets:
+            self.lora = B.Lora()
+            for t in cfg.lora_targets:
+                i = B.TARGET_NAMES.index(t)
+                A, Bm = lora[t]
+                self.A[t] = _dev(np.ascontiguousarray(A.T), dt, device)      # [r, in]
+                self.Bm[t] = _dev(np.ascontiguousarray(Bm.T), dt, device)    # [out, r]
+                self.dA[t] = torch.zeros(self.A[t].shape, dtype=torch.float32, device=device)
+                self.dB[t] = torch.zeros(self.Bm[t].shape, dtype=torch.float32, device=device)
+                self.lora.A[i], self.lora.B[i] = self.A[t].data_ptr(), self.Bm[t].data_ptr()
+                self.lora.dA[i], self.lora.dB[i] = self.dA[t].data_ptr(), self.dB[t].data_ptr()
+
+    def zero_grads(self):
+        for t in self.dA:
+            self.dA[t].zero_()
+            self.dB[t].zero_()
+
+    def grads_numpy(self):
+        """{target: (dA [in, r], dB [r, out])} in the paper's orientation, float64"""
+        return {t: (self.dA[t].double().cpu().numpy().T.copy(), self.dB[t].double().cpu().numpy().T.copy())
+                for t in self.dA}
+
+
+class DevicePool:
+    """Paged KV cache of one layer: K [P, nkv, ps, d], V [P, nkv, d, ps]."""
+
+    def __init__(self, cfg, num_pages, device="cuda"):
+        self.cfg, self.num_pages = cfg, num_pages
+        dt = TORCH_DTYPE[cfg.dtype]
+        self.k = torch.zeros((num_pages, cfg.n_kv_heads, cfg.page_size, cfg.head_dim), dtype=dt, device=device)
+        self.v = torch.zeros((num_pages, cfg.n_kv_heads, cfg.head_dim, cfg.page_size), dtype=dt, device=device)
+        self.c = B.KVPool(self.k.data_ptr(), self.v.data_ptr(), num_pages, cfg.page_size)
+
+    def _idx(self, pages, n, start=0):
+        p = torch.arange(start, start + n, device=self.k.device)
+        pg = torch.as_tensor(np.asarray(pages, dtype=np.int64), device=self.k.device)[p // self.cfg.page_size]
+        return pg, p % self.cfg.page_size
+
+    def write_rows(self, pages, k_rows, v_rows, start=0):
+        """Stage logical rows [n, nkv*d] (numpy or tensor) at positions start.. of a sequence."""
+        cfg = self.cfg
+        n = k_rows.shape[0]
+        if n == 0:
+            return
+        pg, off = self._idx(pages, n, start)
+        tk = torch.as_tensor(k_rows).to(device=self.k.device, dtype=self.k.dtype).view(n, cfg.n_kv_heads, cfg.head_dim)
+        tv = torch.as_tensor(v_rows).to(device=self.k.device, dtype=self.k.dtype).view(n, cfg.n_kv_heads, cfg.head_dim)
+        self.k[pg, :, off, :] = tk
+        self.v[pg, :, :, off] = tv
+
+    def read_rows(self, pages, n, start=0):
+        pg, off = self._idx(pages, n, start)
+        k = self.k[pg, :, off, :].reshape(n, -1).double().cpu().numpy()
+        v = self.v[pg, :, :, off].reshape(n, -1).double().cpu().numpy()
+        return k, v
+
+
+class DeviceFtState:
+    def __init__(self, cfg, L, device="cuda"):
+        dt = TORCH_DTYPE[cfg.dtype]
+        z = lambda w, d=dt: torch.zeros((L, w), dtype=d, device=device)
+        self.L = L
+        self.q_cache, self.attn = z(cfg.q_dim), z(cfg.q_dim)
+        self.x, self.x2 = z(cfg.hidden), z(cfg.hidden)
+        self.gate, self.up = z(cfg.ffn), z(cfg.ffn)
+        self.lse = z(cfg.n_q_heads, torch.float32)
+        self.dk_accum, self.dv_accum = z(cfg.kv_dim, torch.float32), z(cfg.kv_dim, torch.float32)
+        self.c = B.FtState(L, self.q_cache.data_ptr(), self.x.data_ptr(), self.x2.data_ptr(), self.gate.data_ptr(),
+                           self.up.data_ptr(), self.attn.data_ptr(), self.lse.data_ptr(), self.dk_accum.data_ptr(),
+                           self.dv_accum.data_ptr())
+
+    def zero_accum(self):
+        self.dk_accum.zero_()
+        self.dv_accum.zero_()
+
+
+class DeviceBatch:
+    """Index maps of a mixed batch: built on the host by the library, uploaded in one copy."""
+
+    def __init__(self, cfg, requests, seq_pages, num_pages, kv_split_pages=0, device="cuda"):
+        self.desc, self._keep = B.make_batch_desc([r.kind for r in requests], [r.start_pos for r in requests],
+                                                  [r.n_new for r in requests], [r.adapter for r in requests],
+                                                  [seq_pages[r.seq_id] for r in requests])
+        self.host_maps, self.blob = B.flexco_build_maps(self.desc, cfg.page_size, num_pages, cfg.n_q_heads,
+                                                        cfg.n_kv_heads, kv_split_pages)
+        self.dev_blob = None
+        self.maps = None
+        if device is not None:
+            self.dev_blob = torch.from_numpy(self.blob).to(device)
+            self.maps = B.flexco_maps_rebase(self.host_maps, self.blob, self.dev_blob)
+
+    def numpy(self):
+        return B.maps_to_numpy(self.host_maps, self.blob)
+
+
+class Workspace:
+    def __init__(self, cfg_c, T_max, n_parts_max, win_max=0, kv_max=0, device="cuda"):
+        self.bytes = B.flexco_workspace_bytes(cfg_c, T_max, n_parts_max, win_max, kv_max)
+        self.buf = torch.empty(max(self.bytes, 256), dtype=torch.uint8, device=device)
+
+    @property
+    def ptr(self):
+        return self.buf.data_ptr()

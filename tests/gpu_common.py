@@ -1,0 +1,107 @@
+"""Runs the same seeded mixed batch through the CPU oracle and through the HIP library
+(via the C ABI) and hands both results to the parity tests.  Holds no arithmetic of the
+method: the oracle side calls oracle/, the GPU side calls paper_2402_18789_amd."""
+import numpy as np
+import torch
+
+from oracle import layer as OL
+from oracle.maps import build_maps
+from workload import gen
+from workload.configs import KIND_FINETUNE
+import paper_2402_18789_amd.binding as B
+from paper_2402_18789_amd import host as HH
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def rel_err(a, b):
+    """max |a - b| / max |b|  (b = oracle)"""
+    a, b = np.asarray(a, dtype=np.float64), np.asarray(b, dtype=np.float64)
+    den = float(np.max(np.abs(b)))
+    return float(np.max(np.abs(a - b))) / (den if den > 0 else 1.0)
+
+
+def to_np(t):
+    return t.detach().double().cpu().numpy()
+
+
+class Case:
+    """One layer, one pool, at most one finetune sequence; both sides in lock step."""
+
+    def __init__(self, cfg, batch, seed=0, layer=0, kv_split_pages=0, pool_dtype=np.float64, weights=None, lora=None):
+        self.cfg, self.seed, self.layer_id = cfg, seed, layer
+        self.W = weights if weights is not None else gen.layer_weights(cfg, seed, layer)
+        self.lora = lora if lora is not None else gen.lora_weights(cfg, seed, layer)
+        self.batch = batch
+        self.split = kv_split_pages
+        # oracle state
+        self.o_pool = OL.KVPool(batch.num_pages, cfg.page_size, cfg.kv_dim, dtype=pool_dtype)
+        self.o_ft = {}
+        # device state
+        self.dev = HH.DeviceLayer(cfg, self.W, self.lora)
+        self.d_pool = HH.DevicePool(cfg, batch.num_pages)
+        self.d_ft = {}
+        for r in batch.requests:
+            if r.kind == KIND_FINETUNE:
+                L = batch.seq_capacity[r.seq_id]
+                self.o_ft[r.seq_id] = OL.FtState(cfg, L)
+                self.d_ft[r.seq_id] = HH.DeviceFtState(cfg, L)
+        self.fill_prefixes(batch)
+
+    def fill_prefixes(self, batch):
+        """Seeded K/V rows for every position already cached when the batch starts."""
+        for r in batch.requests:
+            if r.start_pos == 0:
+                continue
+            k, v = gen.kv_prefix(self.cfg, self.seed, self.layer_id, r.seq_id, r.start_pos)
+            pages = batch.seq_pages[r.seq_id]
+            slots = self.o_pool.slots(pages, r.start_pos)
+            self.o_pool.k[slots], self.o_pool.v[slots] = k, v
+            self.d_pool.write_rows(pages, k, v)
+
+    def forward(self, batch, x, oracle=True, return_all=False):
+        """-> (y_gpu, y_oracle or None, device batch)"""
+        cfg = self.cfg
+        db = HH.DeviceBatch(cfg, batch.requests, batch.seq_pages, batch.num_pages, self.split)
+        ws = HH.Workspace(self.dev.c, db.host_maps.T, db.host_maps.n_parts)
+        dt = HH.TORCH_DTYPE[cfg.dtype]
+        x_d = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to("cuda", dt)
+        y_d = torch.empty_like(x_d)
+        ft_seq = [r.seq_id for r in batch.requests if r.kind == KIND_FINETUNE]
+        ft_c = self.d_ft[ft_seq[0]].c if ft_seq else None
+        B.flexco_layer_forward(self.dev.c, self.dev.w, self.dev.lora, db.maps, x_d, y_d, self.d_pool.c, ft_c,
+                               ws.ptr, ws.bytes)
+        torch.cuda.synchronize()
+        y_o = None
+        if oracle:
+            om = build_maps(batch.requests, batch.seq_pages, batch.page_size, batch.num_pages)
+            y_o = OL.layer_forward_mixed(cfg, self.W, self.lora, om, x, self.o_pool, self.o_ft,
+                                         return_all=return_all)
+        return to_np(y_d), y_o, db
+
+    def backward_window(self, seq_id, win_start, win_len, dY, grads_o, need_dx=True):
+        """One token-window backward step on both sides -> (dX_gpu, dX_oracle)"""
+        cfg = self.cfg
+        pages = self.batch.seq_pages[seq_id]
+        l = win_start + win_len
+        st_d, st_o = self.d_ft[seq_id], self.o_ft[seq_id]
+        ws = HH.Workspace(self.dev.c, 0, 0, win_len, l)
+        dt = HH.TORCH_DTYPE[cfg.dtype]
+        dY_d = torch.from_numpy(np.ascontiguousarray(dY, dtype=np.float32)).to("cuda", dt)
+        dX_d = torch.empty_like(dY_d) if need_dx else None
+        pages_d = torch.from_numpy(np.asarray(pages, dtype=np.int32)).to("cuda")
+        B.flexco_lora_bwd(self.dev.c, self.dev.w, self.dev.lora, self.d_pool.c, pages_d, len(pages), st_d.c,
+                          win_start, win_len, dY_d, dX_d, ws.ptr, ws.bytes)
+        torch.cuda.synchronize()
+        slots = self.o_pool.slots(pages, l)
+        K, V = self.o_pool.k[slots].astype(np.float64), self.o_pool.v[slots].astype(np.float64)
+        dX_o = OL.layer_backward_window(cfg, self.W, self.lora, st_o, K, V, win_start, win_len, dY, grads_o, need_dx)
+        return (to_np(dX_d) if need_dx else None), dX_o
+
+
+def assert_close(name, got, ref, tol, report=None):
+    e = rel_err(got, ref)
+    if report is not None:
+        report.append((name, e))
+    assert e <= tol, "%s: max relative error %.3e > %.1e" % (name, e, tol)
+    return e

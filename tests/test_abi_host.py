@@ -1,0 +1,155 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports what the
+header declares, builds index maps bit-identical to the oracle's, and rejects bad input
+before launching anything."""
+import ctypes as C
+import os
+import re
+from types import SimpleNamespace as NS
+
+import numpy as np
+import pytest
+
+import paper_2402_18789_amd.binding as B
+from oracle.maps import build_maps, check_attention_cover
+from workload import gen, CONFIGS
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+COMMON = ("tok_req", "tok_pos", "slot", "req_tok_off", "req_kv_len", "req_kind", "block_table", "ft_tok", "seg_off",
+          "seg_adapter")
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "flexco.h")).read()
+    declared = set(re.findall(r"\b(flexco_[a-z_0-9]+)\s*\(", header))
+    assert {"flexco_layer_forward", "flexco_attention_mixed", "flexco_lora_fwd", "flexco_lora_bwd"} <= declared
+    lib = C.CDLL(B.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert declared == set(B.EXPORTS)
+    assert B.flexco_abi_version() == B.ABI_VERSION
+
+
+def c_maps(batch, nq, nkv, split=0):
+    desc, keep = B.make_batch_desc([r.kind for r in batch.requests], [r.start_pos for r in batch.requests],
+                                   [r.n_new for r in batch.requests], [r.adapter for r in batch.requests],
+                                   [batch.seq_pages[r.seq_id] for r in batch.requests])
+    m, blob = B.flexco_build_maps(desc, batch.page_size, batch.num_pages, nq, nkv, split)
+    return B.maps_to_numpy(m, blob)
+
+
+def work_items(cm, page_size):
+    items = []
+    for it in range(cm["n_items"]):
+        tile, split = cm["item_tile"][it], cm["item_split"][it]
+        t0, n = cm["tile_tok0"][tile], cm["tile_ntok"][tile]
+        k0 = split * cm["kv_split_pages"] * page_size
+        items.append((t0, t0 + n, k0, k0 + cm["kv_split_pages"] * page_size))
+    return items
+
+
+@pytest.mark.parametrize("name,nq,nkv,split", [("c1", 4, 4, 2), ("c1", 4, 4, 0), ("c2", 32, 8, 0), ("c2", 40, 8, 8),
+                                               ("scaled", 8, 2, 4)])
+def test_maps_bit_exact_vs_oracle(name, nq, nkv, split):
+    batch = {"c1": gen.batch_c1(0), "c2": gen.batch_c2(0),
+             "scaled": gen.batch_scaled(3, 9, 5, 300, [(0, 37, 37), (64, 50, 130)], [(96, 33, 129)])}[name]
+    om = build_maps(batch.requests, batch.seq_pages, batch.page_size, batch.num_pages)
+    cm = c_maps(batch, nq, nkv, split)
+    for k in ("T", "n_req", "n_ft", "n_seg", "max_pages"):
+        assert cm[k] == om[k], k
+    for k in COMMON:
+        assert cm[k].dtype == np.int32 and np.array_equal(cm[k], om[k]), k
+    assert np.array_equal(cm["lora_tok"], np.nonzero(np.repeat(om["seg_adapter"], np.diff(om["seg_off"])) >= 0)[0])
+    # the work list covers every (token, visible position) exactly once
+    assert check_attention_cover(om, work_items(cm, batch.page_size))
+    # tiles partition the tokens of each request; partial rows are numbered densely
+    assert np.array_equal(np.repeat(np.arange(cm["n_tiles"]), cm["tile_ntok"]), cm["tok_tile"])
+    assert cm["n_parts"] == cm["tile_nsplit"].sum() == cm["n_items"]
+    assert np.array_equal(cm["tile_part0"], np.concatenate([[0], np.cumsum(cm["tile_nsplit"])[:-1]]))
+    assert cm["tile_tokens"] == max(1, 16 // (nq // nkv))
+
+
+def test_work_list_is_deterministic():
+    a, b = c_maps(gen.batch_c2(0), 32, 8), c_maps(gen.batch_c2(0), 32, 8)
+    for k in a:
+        assert np.array_equal(a[k], b[k])
+
+
+def R(kind, seq, start, n, adapter=-1):
+    return NS(kind=kind, seq_id=seq, start_pos=start, n_new=n, adapter=adapter)
+
+
+@pytest.mark.parametrize("reqs,pages,code", [
+    ([R(0, 0, 8, 1)], {0: [1, 2]}, B.FLEXCO_EPAGE),                       # kv_len 9 needs 3 pages of 4
+    ([R(0, 0, 0, 1)], {0: [4]}, B.FLEXCO_EPAGE),                          # page id out of range
+    ([R(0, 0, 0, 1)], {0: [-1]}, B.FLEXCO_EPAGE),
+    ([R(0, 0, 0, 1), R(0, 1, 0, 1)], {0: [1], 1: [1]}, B.FLEXCO_EPAGE),   # duplicate slot
+    ([R(1, 0, 0, 3), R(1, 0, 2, 2)], {0: [1, 2]}, B.FLEXCO_EPAGE),
+    ([R(0, 0, 0, 0)], {0: [1]}, B.FLEXCO_EINVAL),
+    ([R(3, 0, 0, 1)], {0: [1]}, B.FLEXCO_EINVAL),
+    ([R(0, 0, -1, 1)], {0: [1]}, B.FLEXCO_EINVAL),
+    ([R(2, 0, 0, 1, 0), R(2, 1, 0, 1, 0)], {0: [1], 1: [2]}, B.FLEXCO_EUNSUPPORTED),
+])
+def test_invalid_batches_are_rejected(reqs, pages, code):
+    desc, keep = B.make_batch_desc([r.kind for r in reqs], [r.start_pos for r in reqs], [r.n_new for r in reqs],
+                                   [r.adapter for r in reqs], [pages[r.seq_id] for r in reqs])
+    with pytest.raises(B.FlexcoError) as e:
+        B.flexco_build_maps(desc, 4, 4, 4, 2, 0, blob=np.zeros(4096, dtype=np.int32))
+    assert e.value.code == code and len(str(e.value)) > 20
+
+
+def test_blob_too_small_and_bad_heads():
+    b = gen.batch_c1(0)
+    desc, keep = B.make_batch_desc([r.kind for r in b.requests], [r.start_pos for r in b.requests],
+                                   [r.n_new for r in b.requests], [r.adapter for r in b.requests],
+                                   [b.seq_pages[r.seq_id] for r in b.requests])
+    with pytest.raises(B.FlexcoError) as e:
+        B.flexco_build_maps(desc, 16, b.num_pages, 4, 4, 0, blob=np.zeros(8, dtype=np.int32))
+    assert e.value.code == B.FLEXCO_EWORKSPACE
+    with pytest.raises(B.FlexcoError) as e:
+        B.flexco_build_maps(desc, 16, b.num_pages, 4, 3, 0)
+    assert e.value.code == B.FLEXCO_ESHAPE
+    with pytest.raises(B.FlexcoError) as e:
+        B.flexco_build_maps(desc, 16, b.num_pages, 4, 4, 3)          # odd split
+    assert e.value.code == B.FLEXCO_EINVAL
+
+
+def _cfg(**kw):
+    from paper_2402_18789_amd.host import c_cfg
+    return c_cfg(CONFIGS["c1_tiny_f32"].with_(**kw))
+
+
+def test_workspace_bytes_and_cfg_validation():
+    c = _cfg()
+    small = B.flexco_workspace_bytes(c, 68, 20, 32, 64)
+    big = B.flexco_workspace_bytes(c, 136, 40, 64, 64)
+    assert 0 < small < big
+    for bad in (dict(head_dim=63), dict(n_kv_heads=3), dict(lora_rank=65), dict(hidden=0), dict(head_dim=512)):
+        with pytest.raises(B.FlexcoError):
+            B.flexco_workspace_bytes(_cfg(**bad), 8, 8, 8, 8)
+
+
+def test_entry_points_validate_before_launch():
+    """NULL / misaligned arguments fail on the host: no device is needed (or present) here."""
+    c = _cfg()
+    with pytest.raises(B.FlexcoError) as e:
+        B.flexco_gemm(0, 0, 0, None, None, 4, 4, 4, 0, B.FLEXCO_F32, stream=0)
+    assert e.value.code == B.FLEXCO_EINVAL
+    with pytest.raises(B.FlexcoError) as e:
+        B.flexco_gemm(16, 32, 48, None, None, 4, 0, 4, 0, B.FLEXCO_F32, stream=0)
+    assert e.value.code == B.FLEXCO_EINVAL
+    with pytest.raises(B.FlexcoError) as e:
+        B.flexco_gemm(16, 32, 50, None, None, 4, 4, 4, 0, B.FLEXCO_F32, stream=0)     # misaligned C
+    assert e.value.code == B.FLEXCO_EINVAL
+    w = B.BaseWeights()
+    m = B.Maps()
+    pool = B.KVPool(16, 16, 4, 16)
+    with pytest.raises(B.FlexcoError) as e:
+        B.flexco_layer_forward(c, w, None, m, 16, 32, pool, None, 64, 1 << 20, stream=0)
+    assert e.value.code == B.FLEXCO_EINVAL and "NULL" in str(e.value)
+    # segmented LoRA: segments must tile [0, T)
+    with pytest.raises(B.FlexcoError) as e:
+        B.flexco_lora_fwd(16, 32, 8, 16, 16, 4, 1.0, B.FLEXCO_F32, [48], [64], [0, 5], [0], 80, stream=0)
+    assert e.value.code == B.FLEXCO_ESHAPE
+    with pytest.raises(B.FlexcoError) as e:
+        B.flexco_lora_fwd(16, 32, 8, 16, 16, 4, 1.0, B.FLEXCO_F32, [48], [64], [0, 8], [1], 80, stream=0)
+    assert e.value.code == B.FLEXCO_EINVAL

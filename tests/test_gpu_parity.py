@@ -1,0 +1,270 @@
+"""GPU-vs-oracle parity through the C ABI (run with -m gpu on an MI355X).
+
+Bar: index maps bit-exact (tests/test_abi_host.py); outputs and LoRA gradients within
+1e-4 (fp32 tiny configuration) or 2e-2 (bf16) max relative error per tensor,
+max|gpu - oracle| / max|oracle|.
+"""
+import numpy as np
+import pytest
+import torch
+
+from workload import gen, CONFIGS
+from workload.configs import KIND_FINETUNE
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    import paper_2402_18789_amd.binding as B
+    from paper_2402_18789_amd import host as HH
+    from oracle import ops as OO, layer as OL
+    from oracle.maps import build_maps
+    from gpu_common import Case, rel_err, to_np, TOL, assert_close
+
+C1 = CONFIGS["c1_tiny_f32"]
+C2 = CONFIGS["c2_llama8b_layer"]
+# bf16 shapes small enough for the oracle in seconds, still several tiles and ragged tails
+SMALL_BF16 = C2.with_(name="small_bf16", hidden=512, n_q_heads=8, n_kv_heads=2, head_dim=128, ffn=1408)
+SMALL_BF16_G5 = C2.with_(name="small_bf16_g5", hidden=640, n_q_heads=10, n_kv_heads=2, head_dim=128, ffn=1152,
+                         lora_targets=("q", "k", "v", "o", "gate", "up", "down"), qkv_bias=True, rms_eps=1e-6,
+                         rope_theta=1e6)
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+# ------------------------------------------------------------------------------------------
+# dense projection
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("M,N,K,trans", [(68, 768, 256, 0), (68, 256, 688, 0), (33, 100, 72, 1), (256, 512, 1024, 0),
+                                         (1024, 1536, 512, 0), (300, 1408, 512, 1), (256, 4096, 1024, 1),
+                                         (1, 256, 256, 0), (129, 384, 136, 0)])
+def test_gemm(dtype, M, N, K, trans):
+    say(f"gemm {dtype} M={M} N={N} K={K} trans={trans}")
+    cfg = C1.with_(dtype=dtype)
+    g = gen.rng(5, "gemm", M, N, K, trans)
+    A = gen.storage_round(cfg, g.standard_normal((M, K), dtype=np.float32))
+    W = gen.storage_round(cfg, g.standard_normal((K, N) if trans else (N, K), dtype=np.float32))
+    bias = gen.storage_round(cfg, g.standard_normal(N, dtype=np.float32))
+    res = gen.storage_round(cfg, g.standard_normal((M, N), dtype=np.float32))
+    dt = HH.TORCH_DTYPE[dtype]
+    dev = lambda a: torch.from_numpy(a).to("cuda", dt)
+    A_d, W_d, b_d, r_d = dev(A), dev(W), dev(bias), dev(res)
+    C_d = torch.empty((M, N), dtype=dt, device="cuda")
+    A64, W64 = A.astype(np.float64), W.astype(np.float64)
+    ref = A64 @ (W64 if trans else W64.T)
+    B.flexco_gemm(A_d, W_d, C_d, None, None, M, N, K, trans, HH.DTYPE_CODE[dtype])
+    torch.cuda.synchronize()
+    assert_close("gemm", to_np(C_d), ref, TOL[dtype])
+    if not trans:
+        B.flexco_gemm(A_d, W_d, C_d, b_d, r_d, M, N, K, trans, HH.DTYPE_CODE[dtype])
+        torch.cuda.synchronize()
+        assert_close("gemm+bias+res", to_np(C_d), ref + bias + res, TOL[dtype])
+
+
+# ------------------------------------------------------------------------------------------
+# segmented LoRA forward
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,din,dout,r", [("f32", 256, 688, 8), ("bf16", 512, 1408, 16), ("bf16", 1408, 512, 32),
+                                              ("f32", 72, 40, 3)])
+def test_lora_fwd_segments(dtype, din, dout, r):
+    say(f"lora_fwd {dtype} in={din} out={dout} r={r}")
+    cfg = C1.with_(dtype=dtype)
+    T = 77
+    seg_off, seg_adapter = [0, 9, 30, 31, 60, 77], [-1, 1, 0, -1, 1]
+    g = gen.rng(6, "lora", din, dout, r)
+    rnd = lambda shape, s=1.0: gen.storage_round(cfg, (g.standard_normal(shape) * s).astype(np.float32))
+    x, y0 = rnd((T, din)), rnd((T, dout))
+    As = [rnd((din, r), 0.05) for _ in range(2)]
+    Bs = [rnd((r, dout), 0.05) for _ in range(2)]
+    dt = HH.TORCH_DTYPE[dtype]
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to("cuda", dt)
+    x_d, y_d = dev(x), dev(y0)
+    A_d, B_d = [dev(a.T) for a in As], [dev(b.T) for b in Bs]
+    u = torch.zeros(T * r, dtype=torch.float32, device="cuda")
+    B.flexco_lora_fwd(x_d, y_d, T, din, dout, r, 2.0, HH.DTYPE_CODE[dtype], A_d, B_d, seg_off, seg_adapter, u)
+    torch.cuda.synchronize()
+    ref = y0.astype(np.float64)
+    for s, a in enumerate(seg_adapter):
+        if a >= 0:
+            rows = slice(seg_off[s], seg_off[s + 1])
+            ref[rows] += OO.lora_delta(x[rows].astype(np.float64), As[a].astype(np.float64), Bs[a].astype(np.float64), 2.0)
+    got = to_np(y_d)
+    assert_close("lora_fwd", got, ref, TOL[dtype])
+    for s, a in enumerate(seg_adapter):          # rows without adapter are untouched, bit for bit
+        if a < 0:
+            assert np.array_equal(got[seg_off[s]:seg_off[s + 1]], y0[seg_off[s]:seg_off[s + 1]].astype(np.float64))
+
+
+# ------------------------------------------------------------------------------------------
+# mixed attention alone
+# ------------------------------------------------------------------------------------------
+def attention_case(cfg, batch, split, seed=3):
+    case = Case(cfg, batch, seed=seed, kv_split_pages=split)
+    om = build_maps(batch.requests, batch.seq_pages, batch.page_size, batch.num_pages)
+    T = om["T"]
+    g = gen.rng(seed, "attnq", cfg.name, T)
+    q = gen.storage_round(cfg, g.standard_normal((T, cfg.q_dim), dtype=np.float32))
+    # K/V of the batch's own tokens, seeded, on both sides
+    for r in batch.requests:
+        k, v = gen.kv_prefix(cfg, seed + 1, 0, r.seq_id, r.start_pos + r.n_new)
+        pages = batch.seq_pages[r.seq_id]
+        sl = case.o_pool.slots(pages, r.start_pos + r.n_new)[r.start_pos:]
+        case.o_pool.k[sl], case.o_pool.v[sl] = k[r.start_pos:], v[r.start_pos:]
+        case.d_pool.write_rows(pages, k[r.start_pos:], v[r.start_pos:], start=r.start_pos)
+    db = HH.DeviceBatch(cfg, batch.requests, batch.seq_pages, batch.num_pages, split)
+    ws = HH.Workspace(case.dev.c, T, db.host_maps.n_parts)
+    dt = HH.TORCH_DTYPE[cfg.dtype]
+    q_d = torch.from_numpy(q).to("cuda", dt)
+    out_d = torch.empty_like(q_d)
+    lse_d = torch.empty((T, cfg.n_q_heads), dtype=torch.float32, device="cuda")
+    B.flexco_attention_mixed(case.dev.c, db.maps, q_d, case.d_pool.c, out_d, lse_d, ws.ptr, ws.bytes)
+    torch.cuda.synchronize()
+    a_o, lse_o = OL.attention_mixed(cfg, om, q.astype(np.float64), case.o_pool)
+    return to_np(out_d), a_o, to_np(lse_d), lse_o
+
+
+@pytest.mark.parametrize("name,split", [("c1", 0), ("c1", 2), ("small_bf16", 0), ("small_bf16", 2), ("g5", 4)])
+def test_attention_mixed(name, split):
+    say(f"attention_mixed {name} split={split}")
+    if name == "c1":
+        cfg, batch = C1, gen.batch_c1(0)
+    elif name == "small_bf16":
+        cfg = SMALL_BF16
+        batch = gen.batch_scaled(4, 12, 1, 700, [(0, 150, 150), (200, 77, 300)], [(96, 75, 171)])
+    else:
+        cfg = SMALL_BF16_G5
+        batch = gen.batch_scaled(5, 7, 17, 333, [(0, 40, 40)], [(64, 100, 164)])
+    out, a_o, lse, lse_o = attention_case(cfg, batch, split)
+    assert_close("attention out", out, a_o, TOL[cfg.dtype])
+    assert float(np.max(np.abs(lse - lse_o))) <= (1e-4 if cfg.dtype == "f32" else 2e-2)
+
+
+# ------------------------------------------------------------------------------------------
+# whole layer: forward iterations, then token-window backward
+# ------------------------------------------------------------------------------------------
+def run_layer_case(cfg, batch0, ft_window, prefill_chunk, bwd_windows, seed=0, split=0, need_dx=True):
+    report = []
+    tol = TOL[cfg.dtype]
+    case = Case(cfg, batch0, seed=seed, kv_split_pages=split)
+    batch, it = batch0, 0
+    ft_seq = [r.seq_id for r in batch0.requests if r.kind == KIND_FINETUNE][0]
+    L = batch0.seq_capacity[ft_seq]
+    y_ft_g, y_ft_o = np.zeros((L, cfg.hidden)), np.zeros((L, cfg.hidden))
+    while any(r.kind == KIND_FINETUNE for r in batch.requests):
+        say(f"  forward iteration {it}: T={batch.n_tokens}")
+        x = gen.layer_input(cfg, seed, batch.n_tokens, tag=f"x{it}")
+        y_g, y_o, db = case.forward(batch, x)
+        assert_close(f"y it{it}", y_g, y_o, tol, report)
+        for r, off in zip(batch.requests, np.cumsum([0] + [q.n_new for q in batch.requests])):
+            kg, vg = case.d_pool.read_rows(batch.seq_pages[r.seq_id], r.n_new, r.start_pos)
+            sl = case.o_pool.slots(batch.seq_pages[r.seq_id], r.start_pos + r.n_new)[r.start_pos:]
+            assert_close(f"K append it{it}", kg, case.o_pool.k[sl], tol)
+            assert_close(f"V append it{it}", vg, case.o_pool.v[sl], tol)
+            if r.kind == KIND_FINETUNE:
+                y_ft_g[r.start_pos:r.start_pos + r.n_new] = y_g[off:off + r.n_new]
+                y_ft_o[r.start_pos:r.start_pos + r.n_new] = y_o[off:off + r.n_new]
+        batch = gen.advance(batch, prefill_chunk=prefill_chunk, ft_window=ft_window)
+        it += 1
+    st_d, st_o = case.d_ft[ft_seq], case.o_ft[ft_seq]
+    for name in ("q_cache", "x", "x2", "gate", "up", "attn"):
+        assert_close("saved " + name, to_np(getattr(st_d, name)), getattr(st_o, name), tol, report)
+    assert float(np.max(np.abs(to_np(st_d.lse) - st_o.lse))) <= (1e-4 if cfg.dtype == "f32" else 2e-2)
+    # backward: loss = MSE to seeded targets on the finetune sequence's layer output (oracle's dY on
+    # both sides, so that the backward pass is compared on identical inputs)
+    target = gen.loss_targets(cfg, seed, L).astype(np.float64)
+    _, dY = OL.mse_loss_grad(y_ft_o, target)
+    dY = gen.storage_round(cfg, (dY * L * cfg.hidden).astype(np.float32)).astype(np.float64)   # O(1) magnitudes
+    grads_o = {}
+    case.dev.zero_grads()
+    st_d.zero_accum()
+    l = L
+    dX_g, dX_o = np.zeros((L, cfg.hidden)), np.zeros((L, cfg.hidden))
+    for s in bwd_windows:
+        say(f"  backward window [{l - s}, {l})")
+        g, o = case.backward_window(ft_seq, l - s, s, dY[l - s:l], grads_o, need_dx)
+        if need_dx:
+            dX_g[l - s:l], dX_o[l - s:l] = g, o
+        l -= s
+    assert l == 0
+    if need_dx:
+        assert_close("dX", dX_g, dX_o, tol, report)
+    assert_close("dk_accum", to_np(st_d.dk_accum), st_o.dk_accum, tol, report)
+    assert_close("dv_accum", to_np(st_d.dv_accum), st_o.dv_accum, tol, report)
+    grads_g = case.dev.grads_numpy()
+    assert set(grads_g) == set(grads_o) == set(cfg.lora_targets)
+    for t in cfg.lora_targets:
+        assert_close(f"dA[{t}]", grads_g[t][0], grads_o[t][0], tol, report)
+        assert_close(f"dB[{t}]", grads_g[t][1], grads_o[t][1], tol, report)
+    say("  " + ", ".join(f"{n}={e:.1e}" for n, e in report))
+    return case, report
+
+
+def test_layer_c1_two_iterations_and_backward():
+    say("layer c1")
+    run_layer_case(C1, gen.batch_c1(0), ft_window=32, prefill_chunk=32, bwd_windows=[32, 32])
+
+
+def test_layer_c1_uneven_windows_and_split_keys():
+    say("layer c1 uneven")
+    b = gen.mixed_batch(16, 1, decode_ctx=(1, 17, 64), prefill=[(0, 5, 40)], finetune=[(0, 23, 64)], extra_capacity=3)
+    run_layer_case(C1, b, ft_window=41, prefill_chunk=35, bwd_windows=[1, 40, 23], split=2)
+
+
+def test_layer_c1_no_input_grad_all_targets():
+    say("layer c1 all targets, dX = NULL")
+    cfg = C1.with_(lora_targets=("q", "k", "v", "o", "gate", "up", "down"), qkv_bias=True)
+    run_layer_case(cfg, gen.batch_c1(2), ft_window=32, prefill_chunk=32, bwd_windows=[64], need_dx=False)
+
+
+def test_layer_c1_down_only():
+    say("layer c1 down-only LoRA")
+    cfg = C1.with_(lora_targets=("down",))
+    run_layer_case(cfg, gen.batch_c1(3), ft_window=32, prefill_chunk=32, bwd_windows=[20, 44])
+
+
+def test_layer_small_bf16():
+    say("layer small bf16")
+    b = gen.batch_scaled(7, 10, 3, 600, [(0, 130, 130), (256, 64, 400)], [(0, 100, 260)])
+    run_layer_case(SMALL_BF16, b, ft_window=160, prefill_chunk=70, bwd_windows=[60, 200], seed=7)
+
+
+def test_layer_small_bf16_group5_all_targets():
+    say("layer small bf16 group 5")
+    b = gen.batch_scaled(8, 6, 30, 200, [(0, 50, 50)], [(0, 90, 170)])
+    run_layer_case(SMALL_BF16_G5, b, ft_window=80, prefill_chunk=16, bwd_windows=[170], seed=8, split=4)
+
+
+def test_forward_is_deterministic():
+    say("determinism")
+    case = Case(C1, gen.batch_c1(0))
+    x = gen.layer_input(C1, 0, 68)
+    y1, _, _ = case.forward(gen.batch_c1(0), x, oracle=False)
+    y2, _, _ = case.forward(gen.batch_c1(0), x, oracle=False)
+    assert np.array_equal(y1, y2)
+
+
+def test_error_paths_on_device():
+    say("error paths")
+    case = Case(C1, gen.batch_c1(0))
+    b = gen.batch_c1(0)
+    db = HH.DeviceBatch(C1, b.requests, b.seq_pages, b.num_pages)
+    x = torch.zeros((68, 256), device="cuda")
+    y = torch.zeros_like(x)
+    ws = HH.Workspace(case.dev.c, 68, db.host_maps.n_parts)
+    ft = list(case.d_ft.values())[0]
+    with pytest.raises(B.FlexcoError) as e:        # workspace too small
+        B.flexco_layer_forward(case.dev.c, case.dev.w, case.dev.lora, db.maps, x, y, case.d_pool.c, ft.c, ws.ptr, 1024)
+    assert e.value.code == B.FLEXCO_EWORKSPACE
+    with pytest.raises(B.FlexcoError) as e:        # finetune request without its state
+        B.flexco_layer_forward(case.dev.c, case.dev.w, case.dev.lora, db.maps, x, y, case.d_pool.c, None, ws.ptr, ws.bytes)
+    assert e.value.code == B.FLEXCO_EINVAL
+    with pytest.raises(B.FlexcoError) as e:        # aliasing
+        B.flexco_layer_forward(case.dev.c, case.dev.w, case.dev.lora, db.maps, x, x, case.d_pool.c, ft.c, ws.ptr, ws.bytes)
+    assert e.value.code == B.FLEXCO_EINVAL
+    pages_d = torch.zeros(4, dtype=torch.int32, device="cuda")
+    with pytest.raises(B.FlexcoError) as e:        # window beyond the sequence
+        B.flexco_lora_bwd(case.dev.c, case.dev.w, case.dev.lora, case.d_pool.c, pages_d, 4, ft.c, 60, 10, x, y,
+                          ws.ptr, ws.bytes)
+    assert e.value.code == B.FLEXCO_ESHAPE
