@@ -8,6 +8,7 @@ import ctypes as C
 import os
 
 import numpy as np
+import torch  # noqa: F401  loaded first: the library shares torch's HIP runtime (libamdhip64.so)
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libflexco.so")

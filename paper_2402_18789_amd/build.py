@@ -36,7 +36,12 @@ def build(verbose=True):
         for _, w in results:
             if w:
                 print(w, file=sys.stderr)
-    cmd = [HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + objs
+    # Link against the HIP runtime PyTorch ships (soname libamdhip64.so), so that the library
+    # and torch share one runtime, one set of devices and one set of streams in the process.
+    import torch
+    tlib = os.path.join(os.path.dirname(torch.__file__), "lib")
+    cmd = [HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-no-hip-rt", "-o", LIB] + objs + \
+          ["-L" + tlib, "-lamdhip64", "-Wl,-rpath," + tlib]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n%s\n%s" % (r.stdout, r.stderr))
