@@ -291,6 +291,25 @@ int32_t flexco_attention_window_bwd(const flexco_layer_cfg* cfg, const flexco_kv
 int32_t flexco_gemm(const void* A, const void* W, void* C, const void* bias, const void* residual,
                     int32_t M, int32_t N, int32_t K, int32_t trans_w, int32_t dtype, void* stream);
 
+/* Per-kernel timing with HIP events, for roofline measurement.  While a timer is running the
+ * library records one event before and one after every launch of the kernel class
+ * `kernel_id` on that launch's stream (at most max_launches launches; later ones are not
+ * timed).  flexco_kernel_timer_stop waits for the recorded events, returns the summed
+ * duration in milliseconds and the number of timed launches, and releases the events.
+ * Events are host-side runtime objects; no device memory is allocated.  Not thread-safe:
+ * start / stop from the thread that issues the work. */
+#define FLEXCO_K_GEMM_FWD   0   /* bf16 MFMA projection, forward form              */
+#define FLEXCO_K_GEMM_BWD   1   /* bf16 MFMA projection, input-gradient form       */
+#define FLEXCO_K_ATTN_FWD   2   /* bf16 MFMA mixed paged attention (partials)      */
+#define FLEXCO_K_ATTN_MERGE 3   /* split merge                                     */
+#define FLEXCO_K_ATTN_BWD   4   /* attention window backward (all its kernels)     */
+#define FLEXCO_K_ELEMWISE   5   /* norms, RoPE/append, SwiGLU, row copies          */
+#define FLEXCO_K_LORA       6   /* rank-r LoRA kernels                             */
+#define FLEXCO_K_GENERIC    7   /* type-generic fallbacks (fp32 path)              */
+#define FLEXCO_N_KERNEL_IDS 8
+int32_t flexco_kernel_timer_start(int32_t kernel_id, int32_t max_launches);
+int32_t flexco_kernel_timer_stop(int32_t kernel_id, double* total_ms, int64_t* launches);
+
 #ifdef __cplusplus
 }
 #endif

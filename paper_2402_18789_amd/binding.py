@@ -70,7 +70,7 @@ class FtState(C.Structure):
 
 def _load():
     if not os.path.exists(LIB_PATH):
-        raise ImportError("libflexco.so is not built: run `python -m paper_2402_18789_amd.build` "
+        raise ImportError("libflexco.so is not built: run `python paper_2402_18789_amd/build.py` "
                           "(there is no CPU fallback)")
     lib = C.CDLL(LIB_PATH)
     lib.flexco_last_error.restype = C.c_char_p
@@ -90,6 +90,8 @@ def _load():
         "flexco_lora_bwd": [P(LayerCfg), P(BaseWeights), P(Lora), P(KVPool), vp, i32, P(FtState), i32, i32, vp, vp, vp, sz, vp],
         "flexco_attention_window_bwd": [P(LayerCfg), P(KVPool), vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
         "flexco_gemm": [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp],
+        "flexco_kernel_timer_start": [i32, i32],
+        "flexco_kernel_timer_stop": [i32, P(C.c_double), P(C.c_int64)],
     }
     for name, args in sigs.items():
         fn = getattr(lib, name)
@@ -101,7 +103,10 @@ def _load():
 _lib = _load()
 EXPORTS = ("flexco_last_error", "flexco_abi_version", "flexco_maps_blob_ints", "flexco_build_maps",
            "flexco_maps_rebase", "flexco_workspace_bytes", "flexco_layer_forward", "flexco_attention_mixed",
-           "flexco_lora_fwd", "flexco_lora_bwd", "flexco_attention_window_bwd", "flexco_gemm")
+           "flexco_lora_fwd", "flexco_lora_bwd", "flexco_attention_window_bwd", "flexco_gemm",
+           "flexco_kernel_timer_start", "flexco_kernel_timer_stop")
+KERNEL_IDS = {"gemm_fwd": 0, "gemm_bwd": 1, "attn_fwd": 2, "attn_merge": 3, "attn_bwd": 4, "elemwise": 5, "lora": 6,
+              "generic": 7}
 
 
 def _check(rc):
@@ -239,3 +244,14 @@ def flexco_attention_window_bwd(cfg, pool, seq_pages, n_seq_pages, win_start, wi
 def flexco_gemm(A, W, Cout, bias, residual, M, N, K, trans_w, dtype, stream=None):
     _check(_lib.flexco_gemm(_ptr(A), _ptr(W), _ptr(Cout), _ptr(bias), _ptr(residual), M, N, K, int(trans_w), dtype,
                             _stream(stream)))
+
+
+def flexco_kernel_timer_start(kernel_id, max_launches):
+    _check(_lib.flexco_kernel_timer_start(kernel_id, max_launches))
+
+
+def flexco_kernel_timer_stop(kernel_id):
+    """-> (total milliseconds, timed launches)"""
+    ms, n = C.c_double(0.0), C.c_int64(0)
+    _check(_lib.flexco_kernel_timer_stop(kernel_id, C.byref(ms), C.byref(n)))
+    return ms.value, n.value

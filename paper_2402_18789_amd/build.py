@@ -1,4 +1,5 @@
-"""Builds libflexco.so (gfx950) in-tree with hipcc.  `python -m paper_2402_18789_amd.build`."""
+"""Builds libflexco.so (gfx950) in-tree with hipcc:  `python paper_2402_18789_amd/build.py`
+(run as a script, so that the package - which loads the library - is not imported)."""
 import os
 import subprocess
 import sys

@@ -1,10 +1,206 @@
-// bf16 MFMA mixed attention (placeholder: reports unsupported so that the dispatcher uses
-// the type-generic kernel).
+// Mixed paged attention on the matrix cores: decode tokens, prefill chunks and finetune
+// windows in one launch (Sec. 6.2: finetuning tokens follow the causal pattern of prefill).
+//
+// bf16 storage, head_dim 128, page_size 16, at most 16 query heads per kv head.
+//
+// One wavefront = one work item (tile, key split) x kv head.  A tile has up to 16 columns:
+// (token, query head of this kv group) pairs - for a decode request the group's heads of its
+// single token, for a chunk request tile_tokens tokens x group heads.  All columns share
+// every K/V byte the wavefront loads.
+//
+// The products are laid out so that NO operand ever moves between lanes or through LDS:
+//   S^T[key, col]  = K[key, :] . Q[col, :]      v_mfma_f32_16x16x32_bf16, A = K page rows
+//       read straight from the page (16 keys x 128 d, key-major), B = Q (registers, loaded once)
+//   result: lane (col = lane % 16, g = lane / 16) holds keys 4g..4g+3 of the page.
+//   O^T[d, col]   += V^T[d, keys] . P^T[keys, col]  with a k-dimension of 32 = two pages;
+//       lane (col, g) supplies P of keys {4g..4g+3 of page 0, 4g..4g+3 of page 1}: exactly
+//       the registers the first product left in that lane.  V is stored position-minor
+//       ([d][16 positions] per page), so lane (d, g) fetches the matching 4 + 4 positions
+//       with two 8-byte loads.
+// Online softmax runs per column in the exp2 domain; the running maximum is reduced over the
+// four lanes that share a column with two cross-lane shuffles.  Each work item writes an
+// un-normalised partial (m, l, acc[128]) per column; a merge kernel combines the splits.
+//
+// Key positions beyond a column's own position are masked in the scores; positions beyond
+// the tile's last position may be unwritten cache slots, so their V bits are cleared as well.
 #include "flexco_internal.h"
+#include "device_types.h"
 
 namespace flexco {
-int32_t launch_attention_mfma(const flexco_layer_cfg&, const flexco_maps&, const void*, size_t,
-                              const flexco_kv_pool&, float*, float*, hipStream_t) {
-  return FLEXCO_EUNSUPPORTED;
+
+namespace {
+
+struct FwdArgs {
+  const int32_t *tok_pos, *block_table, *tile_req, *tile_tok0, *tile_ntok, *tile_part0, *item_tile, *item_split;
+  int max_pages, nq, nkv, n_items, split_pages;
+  float scale_log2;   // log2(e) / sqrt(d)
+};
+
+constexpr int D = 128, PS = 16;
+
+__global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(FwdArgs a, const bf16_t* __restrict__ q, size_t ldq,
+                                                            const bf16_t* __restrict__ kp,
+                                                            const bf16_t* __restrict__ vp,
+                                                            float* __restrict__ part_ml,
+                                                            float* __restrict__ part_acc) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int item = blockIdx.x * 4 + wave;
+  if (item >= a.n_items) return;
+  const int kvh = blockIdx.y;
+  const int tile = a.item_tile[item], split = a.item_split[item];
+  const int r = a.tile_req[tile], t0 = a.tile_tok0[tile], ntok = a.tile_ntok[tile];
+  const int group = a.nq / a.nkv;
+  const int c = lane & 15, g = lane >> 4;
+  const bool col_ok = c < ntok * group;
+  const int t_c = col_ok ? t0 + c / group : t0;
+  const int h_c = kvh * group + (col_ok ? c % group : 0);
+  const int pos_c = col_ok ? a.tok_pos[t_c] : -1;
+  const int last_pos = a.tok_pos[t0 + ntok - 1];
+  const int vis_pages = last_pos / PS + 1;
+  const int pb = split * a.split_pages;
+  const int pe = min(pb + a.split_pages, vis_pages);
+  const int32_t* bt = a.block_table + (size_t)r * a.max_pages;
+
+  // Q fragments: lane (col, g) holds d = 32 dc + 8 g .. + 8, dc = 0..3
+  bf16x8 qf[4];
+  {
+    const bf16_t* qr = q + (size_t)t_c * ldq + h_c * D + g * 8;
+#pragma unroll
+    for (int dc = 0; dc < 4; ++dc) qf[dc] = *reinterpret_cast<const bf16x8*>(qr + dc * 32);
+  }
+
+  f32x4 o[8];
+#pragma unroll
+  for (int mt = 0; mt < 8; ++mt) o[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m = -INFINITY, l = 0.f;
+
+  bf16x8 kf[2][4];     // [page of the pair][d chunk]
+  bf16x4 vf[2][8];     // [page of the pair][d tile]
+
+  auto load_pair = [&](int pp, bf16x8 (&kk)[2][4], bf16x4 (&vv)[2][8]) {
+#pragma unroll
+    for (int x = 0; x < 2; ++x) {
+      const int pidx = (pp + x < pe) ? pp + x : pp;
+      const size_t page = (size_t)bt[pidx];
+      const bf16_t* kpage = kp + ((page * a.nkv + kvh) * PS + c) * (size_t)D + g * 8;
+#pragma unroll
+      for (int dc = 0; dc < 4; ++dc) kk[x][dc] = *reinterpret_cast<const bf16x8*>(kpage + dc * 32);
+      const bf16_t* vpage = vp + ((page * a.nkv + kvh) * (size_t)D + c) * PS + g * 4;
+#pragma unroll
+      for (int mt = 0; mt < 8; ++mt) vv[x][mt] = *reinterpret_cast<const bf16x4*>(vpage + mt * 16 * PS);
+    }
+  };
+
+  if (pb < pe) load_pair(pb, kf, vf);
+  for (int pp = pb; pp < pe; pp += 2) {
+    bf16x8 kn[2][4];
+    bf16x4 vn[2][8];
+    const bool has_next = pp + 2 < pe;
+    if (has_next) load_pair(pp + 2, kn, vn);
+
+    // ---- scores of 32 keys x 16 columns -------------------------------------------------
+    float s[8];
+#pragma unroll
+    for (int x = 0; x < 2; ++x) {
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int dc = 0; dc < 4; ++dc) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[x][dc], qf[dc], acc, 0, 0, 0);
+      const bool page_ok = pp + x < pe;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int kpos = (pp + x) * PS + 4 * g + j;
+        s[x * 4 + j] = (page_ok && kpos <= pos_c) ? acc[j] * a.scale_log2 : -INFINITY;
+      }
+    }
+    // ---- online softmax per column -------------------------------------------------------
+    float mx = s[0];
+#pragma unroll
+    for (int j = 1; j < 8; ++j) mx = fmaxf(mx, s[j]);
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m, mx);
+    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f(m - m_use);
+    float p[8], psum = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      p[j] = __builtin_amdgcn_exp2f(s[j] - m_use);
+      psum += p[j];
+    }
+    l = l * alpha + psum;        // per-lane share of the column's sum; reduced at the end
+    m = m_new;
+    bf16x8 pf;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) pf[j] = (bf16_t)p[j];
+    // ---- clear V bits of slots past the tile's last position (may be unwritten) ----------
+    if ((pp + 2) * PS > last_pos + 1) {
+#pragma unroll
+      for (int x = 0; x < 2; ++x)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const bool ok = (pp + x < pe) && ((pp + x) * PS + 4 * g + j <= last_pos);
+          if (!ok) {
+#pragma unroll
+            for (int mt = 0; mt < 8; ++mt) vf[x][mt][j] = (bf16_t)0.f;
+          }
+        }
+    }
+    // ---- O^T = alpha O^T + V^T P^T --------------------------------------------------------
+#pragma unroll
+    for (int mt = 0; mt < 8; ++mt) {
+      bf16x8 vfull;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) { vfull[j] = vf[0][mt][j]; vfull[4 + j] = vf[1][mt][j]; }
+      f32x4 acc = o[mt];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[j] *= alpha;
+      o[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vfull, pf, acc, 0, 0, 0);
+    }
+    if (has_next) {
+#pragma unroll
+      for (int x = 0; x < 2; ++x) {
+#pragma unroll
+        for (int dc = 0; dc < 4; ++dc) kf[x][dc] = kn[x][dc];
+#pragma unroll
+        for (int mt = 0; mt < 8; ++mt) vf[x][mt] = vn[x][mt];
+      }
+    }
+  }
+  // ---- write the partial of this (tile, split, kv head) ----------------------------------
+  l += __shfl_xor(l, 16, 64);
+  l += __shfl_xor(l, 32, 64);
+  if (col_ok) {
+    const int cpt = (16 / group > 1 ? 16 / group : 1) * group;
+    const size_t idx = ((size_t)(a.tile_part0[tile] + split) * a.nkv + kvh) * cpt + c;
+    if (g == 0) {
+      part_ml[idx * 2] = m * 0.6931471805599453f;     // back to the natural-log domain
+      part_ml[idx * 2 + 1] = l;
+    }
+    float* pa = part_acc + idx * D + 4 * g;
+#pragma unroll
+    for (int mt = 0; mt < 8; ++mt) *reinterpret_cast<f32x4*>(pa + mt * 16) = o[mt];
+  }
 }
+
+}  // namespace
+
+int32_t launch_attention_mfma(const flexco_layer_cfg& c, const flexco_maps& m, const void* q, size_t ldq,
+                              const flexco_kv_pool& pool, float* part_ml, float* part_acc, hipStream_t s) {
+  const int group = c.n_q_heads / c.n_kv_heads;
+  if (c.dtype != FLEXCO_BF16 || c.head_dim != D || c.page_size != PS || group > 16 || ldq % 8 != 0)
+    return FLEXCO_EUNSUPPORTED;
+  FwdArgs a;
+  a.tok_pos = m.tok_pos; a.block_table = m.block_table; a.tile_req = m.tile_req; a.tile_tok0 = m.tile_tok0;
+  a.tile_ntok = m.tile_ntok; a.tile_part0 = m.tile_part0; a.item_tile = m.item_tile; a.item_split = m.item_split;
+  a.max_pages = m.max_pages; a.nq = c.n_q_heads; a.nkv = c.n_kv_heads; a.n_items = m.n_items;
+  a.split_pages = m.kv_split_pages;
+  a.scale_log2 = 1.4426950408889634f / sqrtf((float)D);
+  hipLaunchKernelGGL(attn_fwd_mfma_kernel, dim3((m.n_items + 3) / 4, c.n_kv_heads), dim3(256), 0, s, a,
+                     (const bf16_t*)q, ldq, (const bf16_t*)pool.k_pages, (const bf16_t*)pool.v_pages, part_ml,
+                     part_acc);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(FLEXCO_EHIP, "launch of attn_fwd_mfma failed: %s", hipGetErrorString(e));
+  return FLEXCO_OK;
+}
+
 }  // namespace flexco

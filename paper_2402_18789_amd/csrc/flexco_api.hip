@@ -3,10 +3,76 @@
 // (Alg. 2) of a decoder layer.
 #include <cmath>
 #include <cstring>
+#include <vector>
 
 #include "flexco_internal.h"
 
 using namespace flexco;
+
+// ---- per-kernel event timers --------------------------------------------------------------
+namespace flexco {
+struct KTimer {
+  std::vector<hipEvent_t> ev;   // 2 per launch
+  int used = 0;
+  bool on = false;
+};
+static KTimer g_timers[FLEXCO_N_KERNEL_IDS];
+
+KernelTimerScope::KernelTimerScope(int id_, hipStream_t s_) : id(id_), s(s_), slot(-1) {
+  KTimer& t = g_timers[id];
+  if (t.on && 2 * (t.used + 1) <= (int)t.ev.size()) {
+    slot = t.used++;
+    (void)hipEventRecord(t.ev[2 * slot], s);
+  }
+}
+KernelTimerScope::~KernelTimerScope() {
+  if (slot >= 0) (void)hipEventRecord(g_timers[id].ev[2 * slot + 1], s);
+}
+}  // namespace flexco
+
+extern "C" int32_t flexco_kernel_timer_start(int32_t kernel_id, int32_t max_launches) {
+  clear_error();
+  FLEXCO_CHECK(kernel_id >= 0 && kernel_id < FLEXCO_N_KERNEL_IDS, FLEXCO_EINVAL, "unknown kernel id %d", kernel_id);
+  FLEXCO_CHECK(max_launches > 0 && max_launches <= (1 << 20), FLEXCO_EINVAL, "max_launches out of range");
+  KTimer& t = g_timers[kernel_id];
+  FLEXCO_CHECK(!t.on, FLEXCO_EINVAL, "timer %d is already running", kernel_id);
+  t.ev.resize(2 * (size_t)max_launches);
+  for (auto& e : t.ev) {
+    hipError_t rc = hipEventCreate(&e);
+    if (rc != hipSuccess) return fail(FLEXCO_EHIP, "hipEventCreate: %s", hipGetErrorString(rc));
+  }
+  t.used = 0;
+  t.on = true;
+  return FLEXCO_OK;
+}
+
+extern "C" int32_t flexco_kernel_timer_stop(int32_t kernel_id, double* total_ms, int64_t* launches) {
+  clear_error();
+  FLEXCO_CHECK(kernel_id >= 0 && kernel_id < FLEXCO_N_KERNEL_IDS, FLEXCO_EINVAL, "unknown kernel id %d", kernel_id);
+  FLEXCO_CHECK(total_ms && launches, FLEXCO_EINVAL, "NULL output");
+  KTimer& t = g_timers[kernel_id];
+  FLEXCO_CHECK(t.on, FLEXCO_EINVAL, "timer %d is not running", kernel_id);
+  double sum = 0.0;
+  int32_t rc_out = FLEXCO_OK;
+  for (int i = 0; i < t.used; ++i) {
+    float ms = 0.f;
+    hipError_t rc = hipEventSynchronize(t.ev[2 * i + 1]);
+    if (rc == hipSuccess) rc = hipEventElapsedTime(&ms, t.ev[2 * i], t.ev[2 * i + 1]);
+    if (rc != hipSuccess) { rc_out = fail(FLEXCO_EHIP, "event timing: %s", hipGetErrorString(rc)); break; }
+    sum += ms;
+  }
+  *total_ms = sum;
+  *launches = t.used;
+  for (auto& e : t.ev) (void)hipEventDestroy(e);
+  t.ev.clear();
+  t.used = 0;
+  t.on = false;
+  return rc_out;
+}
+
+// launches bracketed by the event timer of their kernel class (stream variable `s` in scope)
+#define EW(expr) do { KernelTimerScope ts_(FLEXCO_K_ELEMWISE, s); FLEXCO_TRY(expr); } while (0)
+#define LR(expr) do { KernelTimerScope ts_(FLEXCO_K_LORA, s); FLEXCO_TRY(expr); } while (0)
 
 namespace {
 
@@ -174,12 +240,18 @@ int32_t lora_apply(const flexco_layer_cfg& c, const flexco_lora* l, int t, const
 int32_t run_attention(const flexco_layer_cfg& c, const flexco_maps& m, const void* q, size_t ldq,
                       const flexco_kv_pool& pool, void* out, size_t ldo, float* lse, float* part_ml, float* part_acc,
                       hipStream_t s) {
-  int32_t rc = launch_attention_mfma(c, m, q, ldq, pool, part_ml, part_acc, s);
+  int32_t rc;
+  {
+    KernelTimerScope ts(FLEXCO_K_ATTN_FWD, s);
+    rc = launch_attention_mfma(c, m, q, ldq, pool, part_ml, part_acc, s);
+  }
   if (rc == FLEXCO_EUNSUPPORTED) {
     clear_error();
+    KernelTimerScope ts(FLEXCO_K_GENERIC, s);
     rc = launch_attention_generic(c, m, q, ldq, pool, part_ml, part_acc, s);
   }
   if (rc) return rc;
+  KernelTimerScope ts(FLEXCO_K_ATTN_MERGE, s);
   return launch_attention_merge(c, m, part_ml, part_acc, out, ldo, lse, s);
 }
 
@@ -190,10 +262,15 @@ int32_t launch_gemm(const void* A, const void* W, void* C, const void* bias, con
                     int K, size_t lda, size_t ldw, size_t ldc, size_t ldr, bool trans_w, int dtype, hipStream_t s) {
   if (M == 0) return FLEXCO_OK;
   if (dtype == FLEXCO_BF16) {
-    int32_t rc = launch_gemm_mfma(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, trans_w, s);
+    int32_t rc;
+    {
+      KernelTimerScope ts(trans_w ? FLEXCO_K_GEMM_BWD : FLEXCO_K_GEMM_FWD, s);
+      rc = launch_gemm_mfma(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, trans_w, s);
+    }
     if (rc != FLEXCO_EUNSUPPORTED) return rc;
     clear_error();
   }
+  KernelTimerScope ts(FLEXCO_K_GENERIC, s);
   return launch_gemm_generic(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, trans_w, dtype, s);
 }
 }  // namespace flexco
@@ -306,34 +383,34 @@ extern "C" int32_t flexco_layer_forward(const flexco_layer_cfg* cfg, const flexc
   const size_t qd = (size_t)c.n_q_heads * c.head_dim, kd = (size_t)c.n_kv_heads * c.head_dim, qkvd = qd + 2 * kd;
 
   // attention side
-  FLEXCO_TRY(launch_rmsnorm(x_in, w->g1, k.h, T, H, c.rms_eps, dt, s));
+  EW(launch_rmsnorm(x_in, w->g1, k.h, T, H, c.rms_eps, dt, s));
   FLEXCO_TRY(launch_gemm(k.h, w->wqkv, k.qkv, w->bqkv, nullptr, T, (int)qkvd, H, H, H, qkvd, 0, false, dt, s));
-  FLEXCO_TRY(lora_apply(c, lora, FLEXCO_T_Q, m, k.h, H, k.qkv, qkvd, 0, k.u, s));
-  FLEXCO_TRY(lora_apply(c, lora, FLEXCO_T_K, m, k.h, H, k.qkv, qkvd, qd, k.u, s));
-  FLEXCO_TRY(lora_apply(c, lora, FLEXCO_T_V, m, k.h, H, k.qkv, qkvd, qd + kd, k.u, s));
-  FLEXCO_TRY(launch_rope_append(c, k.qkv, m.tok_pos, m.slot, *pool, T, m.ft_tok0, m.n_ft, m.ft_pos0,
+  LR(lora_apply(c, lora, FLEXCO_T_Q, m, k.h, H, k.qkv, qkvd, 0, k.u, s));
+  LR(lora_apply(c, lora, FLEXCO_T_K, m, k.h, H, k.qkv, qkvd, qd, k.u, s));
+  LR(lora_apply(c, lora, FLEXCO_T_V, m, k.h, H, k.qkv, qkvd, qd + kd, k.u, s));
+  EW(launch_rope_append(c, k.qkv, m.tok_pos, m.slot, *pool, T, m.ft_tok0, m.n_ft, m.ft_pos0,
                                 ft ? ft->q_cache : nullptr, s));
   FLEXCO_TRY(run_attention(c, m, k.qkv, qkvd, *pool, k.attn, qd, ft ? k.lse : nullptr, k.part_ml, k.part_acc, s));
   FLEXCO_TRY(launch_gemm(k.attn, w->wo, k.x2, nullptr, x_in, T, H, (int)qd, qd, qd, H, H, false, dt, s));
-  FLEXCO_TRY(lora_apply(c, lora, FLEXCO_T_O, m, k.attn, qd, k.x2, H, 0, k.u, s));
+  LR(lora_apply(c, lora, FLEXCO_T_O, m, k.attn, qd, k.x2, H, 0, k.u, s));
   // MLP side
-  FLEXCO_TRY(launch_rmsnorm(k.x2, w->g2, k.h, T, H, c.rms_eps, dt, s));
+  EW(launch_rmsnorm(k.x2, w->g2, k.h, T, H, c.rms_eps, dt, s));
   FLEXCO_TRY(launch_gemm(k.h, w->wgu, k.gu, nullptr, nullptr, T, 2 * F, H, H, H, 2 * (size_t)F, 0, false, dt, s));
-  FLEXCO_TRY(lora_apply(c, lora, FLEXCO_T_GATE, m, k.h, H, k.gu, 2 * (size_t)F, 0, k.u, s));
-  FLEXCO_TRY(lora_apply(c, lora, FLEXCO_T_UP, m, k.h, H, k.gu, 2 * (size_t)F, F, k.u, s));
-  FLEXCO_TRY(launch_swiglu(k.gu, k.act, T, F, dt, s));
+  LR(lora_apply(c, lora, FLEXCO_T_GATE, m, k.h, H, k.gu, 2 * (size_t)F, 0, k.u, s));
+  LR(lora_apply(c, lora, FLEXCO_T_UP, m, k.h, H, k.gu, 2 * (size_t)F, F, k.u, s));
+  EW(launch_swiglu(k.gu, k.act, T, F, dt, s));
   FLEXCO_TRY(launch_gemm(k.act, w->wd, x_out, nullptr, k.x2, T, H, F, F, F, H, H, false, dt, s));
-  FLEXCO_TRY(lora_apply(c, lora, FLEXCO_T_DOWN, m, k.act, F, x_out, H, 0, k.u, s));
+  LR(lora_apply(c, lora, FLEXCO_T_DOWN, m, k.act, F, x_out, H, 0, k.u, s));
   // keep what graph pruning leaves alive for the finetune rows (Alg. 1), at their positions
   if (ft) {
     const int n = m.n_ft;
     const size_t t0 = m.ft_tok0, p0 = m.ft_pos0;
-    FLEXCO_TRY(launch_copy_rows(boff(x_in, t0 * H, e), H * e, boff(ft->saved_x, p0 * H, e), H * e, n, H * e, s));
-    FLEXCO_TRY(launch_copy_rows(boff(k.x2, t0 * H, e), H * e, boff(ft->saved_x2, p0 * H, e), H * e, n, H * e, s));
-    FLEXCO_TRY(launch_copy_rows(boff(k.gu, t0 * 2 * F, e), 2 * F * e, boff(ft->saved_gate, p0 * F, e), F * e, n, F * e, s));
-    FLEXCO_TRY(launch_copy_rows(boff(k.gu, t0 * 2 * F + F, e), 2 * F * e, boff(ft->saved_up, p0 * F, e), F * e, n, F * e, s));
-    FLEXCO_TRY(launch_copy_rows(boff(k.attn, t0 * qd, e), qd * e, boff(ft->saved_attn, p0 * qd, e), qd * e, n, qd * e, s));
-    FLEXCO_TRY(launch_copy_rows(k.lse + t0 * c.n_q_heads, c.n_q_heads * 4, ft->lse + p0 * c.n_q_heads,
+    EW(launch_copy_rows(boff(x_in, t0 * H, e), H * e, boff(ft->saved_x, p0 * H, e), H * e, n, H * e, s));
+    EW(launch_copy_rows(boff(k.x2, t0 * H, e), H * e, boff(ft->saved_x2, p0 * H, e), H * e, n, H * e, s));
+    EW(launch_copy_rows(boff(k.gu, t0 * 2 * F, e), 2 * F * e, boff(ft->saved_gate, p0 * F, e), F * e, n, F * e, s));
+    EW(launch_copy_rows(boff(k.gu, t0 * 2 * F + F, e), 2 * F * e, boff(ft->saved_up, p0 * F, e), F * e, n, F * e, s));
+    EW(launch_copy_rows(boff(k.attn, t0 * qd, e), qd * e, boff(ft->saved_attn, p0 * qd, e), qd * e, n, qd * e, s));
+    EW(launch_copy_rows(k.lse + t0 * c.n_q_heads, c.n_q_heads * 4, ft->lse + p0 * c.n_q_heads,
                                 c.n_q_heads * 4, n, c.n_q_heads * 4, s));
   }
   return FLEXCO_OK;
@@ -343,6 +420,7 @@ static int32_t attention_window_bwd_impl(const flexco_layer_cfg& c, const flexco
                                          const int32_t* seq_pages, int win_start, int win_len, const void* q,
                                          const void* out, const float* lse, const void* dout, void* dq,
                                          float* dk_accum, float* dv_accum, float* delta, hipStream_t s) {
+  KernelTimerScope ts(FLEXCO_K_ATTN_BWD, s);
   FLEXCO_TRY(launch_attention_delta(c, out, dout, delta, win_len, s));
   return launch_attention_bwd_generic(c, pool, seq_pages, win_start, win_len, q, lse, delta, dout, dq, dk_accum,
                                       dv_accum, s);
@@ -406,27 +484,27 @@ extern "C" int32_t flexco_lora_bwd(const flexco_layer_cfg* cfg, const flexco_bas
   // ---- MLP side: down projection, SwiGLU, gate/up projections, second norm -------------
   FLEXCO_TRY(launch_gemm(dY, w->wd, k.dact, nullptr, nullptr, n, F, H, H, F, F, 0, true, dt, s));
   if (has(FLEXCO_T_DOWN)) {
-    FLEXCO_TRY(launch_swiglu_remat(gate_w, up_w, k.act, n, F, dt, s));
-    FLEXCO_TRY(launch_lora_bwd(k.act, F, dY, H, lora->A[FLEXCO_T_DOWN], lora->B[FLEXCO_T_DOWN],
+    EW(launch_swiglu_remat(gate_w, up_w, k.act, n, F, dt, s));
+    LR(launch_lora_bwd(k.act, F, dY, H, lora->A[FLEXCO_T_DOWN], lora->B[FLEXCO_T_DOWN],
                                lora->dA[FLEXCO_T_DOWN], lora->dB[FLEXCO_T_DOWN], k.dact, F, k.u, k.t, n, F, H, r,
                                c.lora_scale, dt, s));
   }
-  FLEXCO_TRY(launch_swiglu_bwd(gate_w, up_w, k.dact, k.dgu, n, F, dt, s));
+  EW(launch_swiglu_bwd(gate_w, up_w, k.dact, k.dgu, n, F, dt, s));
   FLEXCO_TRY(launch_gemm(k.dgu, w->wgu, k.dh, nullptr, nullptr, n, H, 2 * F, 2 * (size_t)F, H, H, 0, true, dt, s));
   if (has(FLEXCO_T_GATE) || has(FLEXCO_T_UP)) {
-    FLEXCO_TRY(launch_rmsnorm(x2_w, w->g2, k.hn, n, H, c.rms_eps, dt, s));
+    EW(launch_rmsnorm(x2_w, w->g2, k.hn, n, H, c.rms_eps, dt, s));
     for (int t : {FLEXCO_T_GATE, FLEXCO_T_UP}) {
       if (!has(t)) continue;
       const void* dy = boff(k.dgu, t == FLEXCO_T_UP ? F : 0, e);
-      FLEXCO_TRY(launch_lora_bwd(k.hn, H, dy, 2 * (size_t)F, lora->A[t], lora->B[t], lora->dA[t], lora->dB[t], k.dh,
+      LR(launch_lora_bwd(k.hn, H, dy, 2 * (size_t)F, lora->A[t], lora->B[t], lora->dA[t], lora->dB[t], k.dh,
                                  H, k.u, k.t, n, H, F, r, c.lora_scale, dt, s));
     }
   }
-  FLEXCO_TRY(launch_rmsnorm_bwd(x2_w, w->g2, k.dh, dY, k.dx2, n, H, c.rms_eps, dt, s));
+  EW(launch_rmsnorm_bwd(x2_w, w->g2, k.dh, dY, k.dx2, n, H, c.rms_eps, dt, s));
   // ---- output projection ------------------------------------------------------------------
   FLEXCO_TRY(launch_gemm(k.dx2, w->wo, k.dattn, nullptr, nullptr, n, (int)qd, H, H, qd, qd, 0, true, dt, s));
   if (has(FLEXCO_T_O))
-    FLEXCO_TRY(launch_lora_bwd(attn_w, qd, k.dx2, H, lora->A[FLEXCO_T_O], lora->B[FLEXCO_T_O], lora->dA[FLEXCO_T_O],
+    LR(launch_lora_bwd(attn_w, qd, k.dx2, H, lora->A[FLEXCO_T_O], lora->B[FLEXCO_T_O], lora->dA[FLEXCO_T_O],
                                lora->dB[FLEXCO_T_O], k.dattn, qd, k.u, k.t, n, (int)qd, H, r, c.lora_scale, dt, s));
   // ---- attention: dQ of the window, dK/dV of every cached row before its end (Sec. 6.1) ---
   FLEXCO_TRY(attention_window_bwd_impl(c, *pool, seq_pages, win_start, win_len, q_w, attn_w, lse_w, k.dattn, k.dq,
@@ -434,20 +512,20 @@ extern "C" int32_t flexco_lora_bwd(const flexco_layer_cfg* cfg, const flexco_bas
   // ---- q/k/v side: the window's accumulator rows are complete now (Sec. 7) ---------------
   const bool qkv_lora = has(FLEXCO_T_Q) || has(FLEXCO_T_K) || has(FLEXCO_T_V);
   if (!dX && !qkv_lora) return FLEXCO_OK;
-  FLEXCO_TRY(launch_rope_bwd_pack(c, k.dq, ft->dk_accum + w0 * kd, ft->dv_accum + w0 * kd, k.dqkv, win_start, n, s));
+  EW(launch_rope_bwd_pack(c, k.dq, ft->dk_accum + w0 * kd, ft->dv_accum + w0 * kd, k.dqkv, win_start, n, s));
   if (dX)
     FLEXCO_TRY(launch_gemm(k.dqkv, w->wqkv, k.dh, nullptr, nullptr, n, H, (int)qkvd, qkvd, H, H, 0, true, dt, s));
   if (qkv_lora) {
-    FLEXCO_TRY(launch_rmsnorm(x_w, w->g1, k.hn, n, H, c.rms_eps, dt, s));
+    EW(launch_rmsnorm(x_w, w->g1, k.hn, n, H, c.rms_eps, dt, s));
     const size_t col0[3] = {0, qd, qd + kd};
     for (int t : {FLEXCO_T_Q, FLEXCO_T_K, FLEXCO_T_V}) {
       if (!has(t)) continue;
       int in, out;
       target_dims(c, t, &in, &out);
-      FLEXCO_TRY(launch_lora_bwd(k.hn, H, boff(k.dqkv, col0[t], e), qkvd, lora->A[t], lora->B[t], lora->dA[t],
+      LR(launch_lora_bwd(k.hn, H, boff(k.dqkv, col0[t], e), qkvd, lora->A[t], lora->B[t], lora->dA[t],
                                  lora->dB[t], dX ? k.dh : nullptr, H, k.u, k.t, n, H, out, r, c.lora_scale, dt, s));
     }
   }
-  if (dX) FLEXCO_TRY(launch_rmsnorm_bwd(x_w, w->g1, k.dh, k.dx2, dX, n, H, c.rms_eps, dt, s));
+  if (dX) EW(launch_rmsnorm_bwd(x_w, w->g1, k.dh, k.dx2, dX, n, H, c.rms_eps, dt, s));
   return FLEXCO_OK;
 }

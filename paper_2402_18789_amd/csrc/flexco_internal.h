@@ -20,6 +20,13 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 inline size_t esize(int dtype) { return dtype == FLEXCO_BF16 ? 2 : 4; }
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// Records a HIP event before and after the launches it brackets when a timer for `id` runs.
+struct KernelTimerScope {
+  int id; hipStream_t s; int slot;
+  KernelTimerScope(int id, hipStream_t s);
+  ~KernelTimerScope();
+};
+
 // ---- launchers: no validation, the entry points have done it -------------------------
 // C[M,N] = A[M,K] W[N,K]^T (+bias) (+residual);  trans_w: W is [K,N].  Leading dimensions in elements.
 int32_t launch_gemm(const void* A, const void* W, void* C, const void* bias, const void* residual, int M, int N,

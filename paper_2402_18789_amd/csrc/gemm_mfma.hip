@@ -1,10 +1,218 @@
-// bf16 MFMA projections (placeholder until the tiled kernel lands: reports unsupported so
-// that the dispatcher uses the type-generic kernel).
+// bf16 projections on the matrix cores (v_mfma_f32_32x32x16_bf16), LDS-staged.
+//
+//   TRANS = false:  C[M, N] = A[M, K] W[N, K]^T (+ bias[N]) (+ residual[M, N])   forward form
+//   TRANS = true :  C[M, N] = A[M, K] W[K, N]                                      input-gradient form
+//
+// The frozen base projections run over ALL tokens of the mixed batch in one launch, so a
+// weight is read from HBM once per iteration whatever the mix of inference and finetuning
+// tokens (the paper's fused forward, Sec. 6.2).  The input-gradient form serves the
+// token-window backward, where weight gradients are pruned away (Alg. 1) and only
+// dX = dY W remains.
+//
+// Tiling: block tile BM x BN x 64, 256 threads = 4 wavefronts in a 2 x 2 grid, each owning
+// (BM/2) x (BN/2) as 32 x 32 MFMA tiles with fp32 accumulators.  Operand tiles are staged
+// through LDS in two buffers: the next tile's global loads are issued before the MFMAs of
+// the current one and written to the other buffer afterwards (one barrier per k-step).
+//   * A tile and the forward W tile are [rows][64] bf16 = 128-byte rows; the eight 16-byte
+//     chunks of a row are XOR-swizzled with (row >> 1) & 7, so that both the 16-byte writes
+//     and the ds_read_b128 operand fetches of 16 consecutive rows hit 64 distinct banks.
+//   * The transposed W tile is [64][BN + 8]: an operand fragment (8 consecutive k for one
+//     column) is gathered with 16-bit LDS reads; the 16-byte row padding puts the two
+//     k-halves of a wavefront on disjoint banks.
+// Work-group ids are remapped so that ids that land on the same XCD (id mod 8) work on
+// neighbouring tiles, M fastest: the W tile they share stays in that XCD's L2.
 #include "flexco_internal.h"
+#include "device_types.h"
 
 namespace flexco {
-int32_t launch_gemm_mfma(const void*, const void*, void*, const void*, const void*, int, int, int, size_t, size_t,
-                         size_t, size_t, bool, hipStream_t) {
-  return FLEXCO_EUNSUPPORTED;
+
+namespace {
+
+constexpr int BK = 64;
+
+__device__ inline int swz(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
+
+template <int BM, int BN, bool TRANS>
+struct Smem {
+  static constexpr int A_ELEMS = BM * BK;
+  static constexpr int B_LD = TRANS ? (BN + 8) : BK;
+  static constexpr int B_ELEMS = TRANS ? BK * (BN + 8) : BN * BK;
+  static constexpr size_t BYTES = 2 * (size_t)(A_ELEMS + B_ELEMS) * sizeof(bf16_t);
+};
+
+template <int BM, int BN, bool TRANS>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
+                                                        bf16_t* __restrict__ C, const bf16_t* __restrict__ bias,
+                                                        const bf16_t* __restrict__ res, int M, int N, int K,
+                                                        size_t lda, size_t ldw, size_t ldc, size_t ldr, int tiles_m,
+                                                        int tiles_n) {
+  constexpr int WM = BM / 2, WN = BN / 2, MT = WM / 32, NT = WN / 32;
+  using S = Smem<BM, BN, TRANS>;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16_t* As = reinterpret_cast<bf16_t*>(smem_raw);                 // [2][BM][64] swizzled
+  bf16_t* Bs = As + 2 * S::A_ELEMS;                                 // [2][...]
+
+  // ---- work-group id -> tile, XCD-aware ------------------------------------------------
+  int lid = blockIdx.x;
+  const int nblk = gridDim.x;
+  if ((nblk & 7) == 0) lid = (blockIdx.x & 7) * (nblk >> 3) + (blockIdx.x >> 3);
+  const int tm = lid % tiles_m, tn = lid / tiles_m;
+  const int m0 = tm * BM, n0 = tn * BN;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm0 = (wave >> 1) * WM, wn0 = (wave & 1) * WN;
+
+  // ---- global -> register staging --------------------------------------------------------
+  constexpr int A_PASSES = BM / 32;                                  // 8 chunks per row, 32 rows per pass
+  constexpr int B_PASSES = TRANS ? (BK * (BN / 8)) / 256 : BN / 32;
+  uint4 ra[A_PASSES], rb[B_PASSES];
+  const int a_c = tid & 7, a_r = tid >> 3;
+  constexpr int BCH = BN / 8;                                        // chunks per row of the transposed W tile
+  const int bt_c = tid % BCH, bt_r = tid / BCH;
+
+  auto load_tiles = [&](int k0) {
+#pragma unroll
+    for (int p = 0; p < A_PASSES; ++p) {
+      const int r = min(m0 + a_r + 32 * p, M - 1);
+      ra[p] = *reinterpret_cast<const uint4*>(A + (size_t)r * lda + k0 + a_c * 8);
+    }
+    if (!TRANS) {
+#pragma unroll
+      for (int p = 0; p < B_PASSES; ++p) {
+        const int r = min(n0 + a_r + 32 * p, N - 1);
+        rb[p] = *reinterpret_cast<const uint4*>(W + (size_t)r * ldw + k0 + a_c * 8);
+      }
+    } else {
+#pragma unroll
+      for (int p = 0; p < B_PASSES; ++p) {
+        const int kr = bt_r + (256 / BCH) * p;
+        int col = n0 + bt_c * 8;
+        if (col >= N) col = 0;                                       // masked at the store
+        rb[p] = *reinterpret_cast<const uint4*>(W + (size_t)(k0 + kr) * ldw + col);
+      }
+    }
+  };
+  auto store_tiles = [&](int buf) {
+    bf16_t* as = As + buf * S::A_ELEMS;
+    bf16_t* bs = Bs + buf * S::B_ELEMS;
+#pragma unroll
+    for (int p = 0; p < A_PASSES; ++p) {
+      const int r = a_r + 32 * p;
+      *reinterpret_cast<uint4*>(as + r * BK + swz(r, a_c) * 8) = ra[p];
+    }
+    if (!TRANS) {
+#pragma unroll
+      for (int p = 0; p < B_PASSES; ++p) {
+        const int r = a_r + 32 * p;
+        *reinterpret_cast<uint4*>(bs + r * BK + swz(r, a_c) * 8) = rb[p];
+      }
+    } else {
+#pragma unroll
+      for (int p = 0; p < B_PASSES; ++p) {
+        const int kr = bt_r + (256 / BCH) * p;
+        *reinterpret_cast<uint4*>(bs + kr * S::B_LD + bt_c * 8) = rb[p];
+      }
+    }
+  };
+
+  f32x16 acc[MT][NT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int nk = K / BK;
+  load_tiles(0);
+  store_tiles(0);
+  __syncthreads();
+  const int l32 = lane & 31, kg = lane >> 5;
+  for (int kt = 0; kt < nk; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < nk) load_tiles((kt + 1) * BK);
+    const bf16_t* as = As + buf * S::A_ELEMS;
+    const bf16_t* bs = Bs + buf * S::B_ELEMS;
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      bf16x8 af[MT], bfr[NT];
+#pragma unroll
+      for (int i = 0; i < MT; ++i) {
+        const int r = wm0 + i * 32 + l32;
+        af[i] = *reinterpret_cast<const bf16x8*>(as + r * BK + swz(r, kk * 2 + kg) * 8);
+      }
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        if (!TRANS) {
+          const int r = wn0 + j * 32 + l32;
+          bfr[j] = *reinterpret_cast<const bf16x8*>(bs + r * BK + swz(r, kk * 2 + kg) * 8);
+        } else {
+          const bf16_t* col = bs + (kk * 16 + kg * 8) * S::B_LD + wn0 + j * 32 + l32;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) bfr[j][e] = col[e * S::B_LD];
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < nk) store_tiles(buf ^ 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue: D[i][j], j = lane % 32, i = 8 (r / 4) + 4 (lane / 32) + r % 4 ---------------
+#pragma unroll
+  for (int i = 0; i < MT; ++i) {
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+      const int col = n0 + wn0 + j * 32 + l32;
+      if (col >= N) continue;
+      const float bv = bias ? (float)bias[col] : 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = m0 + wm0 + i * 32 + 8 * (r >> 2) + 4 * kg + (r & 3);
+        if (row >= M) continue;
+        float v = acc[i][j][r] + bv;
+        if (res) v += (float)res[(size_t)row * ldr + col];
+        C[(size_t)row * ldc + col] = (bf16_t)v;
+      }
+    }
+  }
 }
+
+template <int BM, int BN, bool TRANS>
+int32_t launch_cfg(const void* A, const void* W, void* C, const void* bias, const void* res, int M, int N, int K,
+                   size_t lda, size_t ldw, size_t ldc, size_t ldr, hipStream_t s) {
+  using S = Smem<BM, BN, TRANS>;
+  auto kern = gemm_bf16_kernel<BM, BN, TRANS>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)S::BYTES);
+    if (e != hipSuccess) return fail(FLEXCO_EHIP, "hipFuncSetAttribute(gemm): %s", hipGetErrorString(e));
+    attr_set = true;
+  }
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(256), S::BYTES, s, (const bf16_t*)A, (const bf16_t*)W,
+                     (bf16_t*)C, (const bf16_t*)bias, (const bf16_t*)res, M, N, K, lda, ldw, ldc, ldr, tiles_m, tiles_n);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(FLEXCO_EHIP, "launch of gemm_bf16 failed: %s", hipGetErrorString(e));
+  return FLEXCO_OK;
+}
+
+}  // namespace
+
+int32_t launch_gemm_mfma(const void* A, const void* W, void* C, const void* bias, const void* residual, int M, int N,
+                         int K, size_t lda, size_t ldw, size_t ldc, size_t ldr, bool trans_w, hipStream_t s) {
+  // shapes the tiled kernel covers: K in whole 64-wide steps, 16-byte aligned rows
+  if (K % BK != 0 || lda % 8 != 0 || ldw % 8 != 0 || N % 8 != 0) return FLEXCO_EUNSUPPORTED;
+  if (trans_w) return launch_cfg<128, 128, true>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, s);
+  const long big_tiles = (long)((M + 255) / 256) * ((N + 255) / 256);
+  if (big_tiles >= 192)
+    return launch_cfg<256, 256, false>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, s);
+  return launch_cfg<128, 128, false>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, s);
+}
+
 }  // namespace flexco

@@ -82,6 +82,18 @@ class DevicePool:
         self.v = torch.zeros((num_pages, cfg.n_kv_heads, cfg.head_dim, cfg.page_size), dtype=dt, device=device)
         self.c = B.KVPool(self.k.data_ptr(), self.v.data_ptr(), num_pages, cfg.page_size)
 
+    def fill_random(self, seed):
+        """N(0, 1) in every slot of every page (device generator): stands in for cached prefixes
+        whose values no check reads."""
+        g = torch.Generator(device=self.k.device)
+        g.manual_seed(seed)
+        for t in (self.k, self.v):
+            flat = t.view(-1)
+            step = 1 << 28
+            for o in range(0, flat.numel(), step):
+                n = min(step, flat.numel() - o)
+                flat[o:o + n] = torch.randn(n, generator=g, device=t.device, dtype=torch.float32).to(t.dtype)
+
     def _idx(self, pages, n, start=0):
         p = torch.arange(start, start + n, device=self.k.device)
         pg = torch.as_tensor(np.asarray(pages, dtype=np.int64), device=self.k.device)[p // self.cfg.page_size]

@@ -268,3 +268,66 @@ def test_error_paths_on_device():
         B.flexco_lora_bwd(case.dev.c, case.dev.w, case.dev.lora, case.d_pool.c, pages_d, 4, ft.c, 60, 10, x, y,
                           ws.ptr, ws.bytes)
     assert e.value.code == B.FLEXCO_ESHAPE
+
+
+def test_layer_c2_full_size_sampled():
+    """The 8B-shaped configuration at full size, in the launch configuration bench.py times:
+    the GPU runs the whole 1024-token batch; the oracle recomputes a sample of requests
+    (16 decode, one prefill chunk, the finetune window) one by one from the same inputs."""
+    say("layer c2 full size, sampled")
+    cfg, seed = C2, 0
+    tol = TOL["bf16"]
+    batch = gen.batch_c2(seed)
+    W, lora = gen.layer_weights(cfg, seed, 0), gen.lora_weights(cfg, seed, 0)
+    dev = HH.DeviceLayer(cfg, W, lora)
+    pool = HH.DevicePool(cfg, batch.num_pages)
+    pool.fill_random(seed)
+    sample = gen.sample_requests(batch, 16)
+    o_pool = OL.KVPool(batch.num_pages, cfg.page_size, cfg.kv_dim, dtype=np.float32)
+    for r in sample:
+        if r.start_pos:
+            k, v = gen.kv_prefix(cfg, seed, 0, r.seq_id, r.start_pos)
+            pool.write_rows(batch.seq_pages[r.seq_id], k, v)
+            sl = o_pool.slots(batch.seq_pages[r.seq_id], r.start_pos)
+            o_pool.k[sl], o_pool.v[sl] = k, v
+    ft_req = [r for r in batch.requests if r.kind == KIND_FINETUNE][0]
+    L = batch.seq_capacity[ft_req.seq_id]
+    ft = HH.DeviceFtState(cfg, L)
+    db = HH.DeviceBatch(cfg, batch.requests, batch.seq_pages, batch.num_pages)
+    ws = HH.Workspace(dev.c, db.host_maps.T, db.host_maps.n_parts, ft_req.n_new, L)
+    x_np = gen.layer_input(cfg, seed, db.host_maps.T)
+    x = torch.from_numpy(x_np).to("cuda", torch.bfloat16)
+    y = torch.empty_like(x)
+    say("  gpu forward")
+    B.flexco_layer_forward(dev.c, dev.w, dev.lora, db.maps, x, y, pool.c, ft.c, ws.ptr, ws.bytes)
+    torch.cuda.synchronize()
+    rows = gen.sample_token_rows(batch, sample)
+    om = build_maps(sample, batch.seq_pages, batch.page_size, batch.num_pages)
+    o_ft = {ft_req.seq_id: OL.FtState(cfg, L)}
+    say("  oracle forward on %d sampled tokens" % len(rows))
+    y_o = OL.layer_forward_mixed(cfg, W, lora, om, x_np[rows], o_pool, o_ft)
+    report = []
+    assert_close("y (sampled rows)", to_np(y)[rows], y_o, tol, report)
+    w = slice(ft_req.start_pos, ft_req.start_pos + ft_req.n_new)
+    for name in ("q_cache", "x2", "gate", "up", "attn"):
+        assert_close("saved " + name, to_np(getattr(ft, name))[w], getattr(o_ft[ft_req.seq_id], name)[w], tol, report)
+    say("  backward window")
+    dY_np = gen.layer_input(cfg, seed, ft_req.n_new, tag="dy")
+    dY = torch.from_numpy(dY_np).to("cuda", torch.bfloat16)
+    dX = torch.empty_like(dY)
+    pages_d = torch.from_numpy(np.asarray(batch.seq_pages[ft_req.seq_id], dtype=np.int32)).to("cuda")
+    B.flexco_lora_bwd(dev.c, dev.w, dev.lora, pool.c, pages_d, int(pages_d.numel()), ft.c, ft_req.start_pos,
+                      ft_req.n_new, dY, dX, ws.ptr, ws.bytes)
+    torch.cuda.synchronize()
+    sl = o_pool.slots(batch.seq_pages[ft_req.seq_id], L)
+    grads_o = {}
+    dX_o = OL.layer_backward_window(cfg, W, lora, o_ft[ft_req.seq_id], o_pool.k[sl].astype(np.float64),
+                                    o_pool.v[sl].astype(np.float64), ft_req.start_pos, ft_req.n_new, dY_np, grads_o)
+    assert_close("dX", to_np(dX), dX_o, tol, report)
+    assert_close("dk_accum", to_np(ft.dk_accum), o_ft[ft_req.seq_id].dk_accum, tol, report)
+    assert_close("dv_accum", to_np(ft.dv_accum), o_ft[ft_req.seq_id].dv_accum, tol, report)
+    grads_g = dev.grads_numpy()
+    for t in cfg.lora_targets:
+        assert_close(f"dA[{t}]", grads_g[t][0], grads_o[t][0], tol, report)
+        assert_close(f"dB[{t}]", grads_g[t][1], grads_o[t][1], tol, report)
+    say("  " + ", ".join(f"{n}={e:.1e}" for n, e in report))

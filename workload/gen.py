@@ -200,3 +200,19 @@ def batch_scaled(seed, n_decode, ctx_lo, ctx_hi, prefill, finetune, page_size=16
     """Reduced-size batch of the same structure as batch_c2 (parity tests)."""
     ctx = rng(seed, "scaled", "decode_ctx", n_decode, ctx_lo, ctx_hi).integers(ctx_lo, ctx_hi + 1, size=n_decode)
     return mixed_batch(page_size, seed, decode_ctx=ctx, prefill=prefill, finetune=finetune)
+
+
+def sample_requests(batch: Batch, n_decode: int):
+    """A bounded sample of a batch's requests for checks the oracle runs one by one: the first
+    n_decode decode requests, the first prefill chunk and the finetune window."""
+    dec = [r for r in batch.requests if r.kind == KIND_DECODE][:n_decode]
+    pre = [r for r in batch.requests if r.kind == KIND_PREFILL][:1]
+    ftr = [r for r in batch.requests if r.kind == KIND_FINETUNE]
+    return dec + pre + ftr
+
+
+def sample_token_rows(batch: Batch, sample):
+    """Token indices (in the full batch) of the sampled requests, in sample order."""
+    tok_off = np.cumsum([0] + [r.n_new for r in batch.requests])
+    idx = {id(r): i for i, r in enumerate(batch.requests)}
+    return np.concatenate([np.arange(tok_off[idx[id(r)]], tok_off[idx[id(r)] + 1]) for r in sample])
