@@ -29,6 +29,7 @@ namespace flexco {
 namespace {
 
 constexpr int BK = 64;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ inline int swz(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
 
@@ -65,55 +66,52 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
   // ---- global -> register staging --------------------------------------------------------
   constexpr int A_PASSES = BM / 32;                                  // 8 chunks per row, 32 rows per pass
   constexpr int B_PASSES = TRANS ? (BK * (BN / 8)) / 256 : BN / 32;
-  uint4 ra[A_PASSES], rb[B_PASSES];
+  u32x4 ra[A_PASSES], rb[B_PASSES];
   const int a_c = tid & 7, a_r = tid >> 3;
   constexpr int BCH = BN / 8;                                        // chunks per row of the transposed W tile
   const int bt_c = tid % BCH, bt_r = tid / BCH;
 
-  auto load_tiles = [&](int k0) {
-#pragma unroll
-    for (int p = 0; p < A_PASSES; ++p) {
-      const int r = min(m0 + a_r + 32 * p, M - 1);
-      ra[p] = *reinterpret_cast<const uint4*>(A + (size_t)r * lda + k0 + a_c * 8);
-    }
-    if (!TRANS) {
-#pragma unroll
-      for (int p = 0; p < B_PASSES; ++p) {
-        const int r = min(n0 + a_r + 32 * p, N - 1);
-        rb[p] = *reinterpret_cast<const uint4*>(W + (size_t)r * ldw + k0 + a_c * 8);
-      }
-    } else {
-#pragma unroll
-      for (int p = 0; p < B_PASSES; ++p) {
-        const int kr = bt_r + (256 / BCH) * p;
-        int col = n0 + bt_c * 8;
-        if (col >= N) col = 0;                                       // masked at the store
-        rb[p] = *reinterpret_cast<const uint4*>(W + (size_t)(k0 + kr) * ldw + col);
-      }
-    }
-  };
-  auto store_tiles = [&](int buf) {
-    bf16_t* as = As + buf * S::A_ELEMS;
-    bf16_t* bs = Bs + buf * S::B_ELEMS;
-#pragma unroll
-    for (int p = 0; p < A_PASSES; ++p) {
-      const int r = a_r + 32 * p;
-      *reinterpret_cast<uint4*>(as + r * BK + swz(r, a_c) * 8) = ra[p];
-    }
-    if (!TRANS) {
-#pragma unroll
-      for (int p = 0; p < B_PASSES; ++p) {
-        const int r = a_r + 32 * p;
-        *reinterpret_cast<uint4*>(bs + r * BK + swz(r, a_c) * 8) = rb[p];
-      }
-    } else {
-#pragma unroll
-      for (int p = 0; p < B_PASSES; ++p) {
-        const int kr = bt_r + (256 / BCH) * p;
-        *reinterpret_cast<uint4*>(bs + kr * S::B_LD + bt_c * 8) = rb[p];
-      }
-    }
-  };
+  // (kept as macros on purpose: staging arrays captured by lambdas were left in scratch memory)
+#define FLEXCO_LOAD_TILES(k0_)                                                                        \
+  {                                                                                                   \
+    _Pragma("unroll") for (int p = 0; p < A_PASSES; ++p) {                                            \
+      const int r_ = min(m0 + a_r + 32 * p, M - 1);                                                   \
+      ra[p] = *reinterpret_cast<const u32x4*>(A + (size_t)r_ * lda + (k0_) + a_c * 8);                \
+    }                                                                                                 \
+    if (!TRANS) {                                                                                     \
+      _Pragma("unroll") for (int p = 0; p < B_PASSES; ++p) {                                          \
+        const int r_ = min(n0 + a_r + 32 * p, N - 1);                                                 \
+        rb[p] = *reinterpret_cast<const u32x4*>(W + (size_t)r_ * ldw + (k0_) + a_c * 8);              \
+      }                                                                                               \
+    } else {                                                                                          \
+      _Pragma("unroll") for (int p = 0; p < B_PASSES; ++p) {                                          \
+        const int kr_ = bt_r + (256 / BCH) * p;                                                       \
+        int col_ = n0 + bt_c * 8;                                                                     \
+        if (col_ >= N) col_ = 0; /* masked at the store */                                            \
+        rb[p] = *reinterpret_cast<const u32x4*>(W + (size_t)((k0_) + kr_) * ldw + col_);              \
+      }                                                                                               \
+    }                                                                                                 \
+  }
+#define FLEXCO_STORE_TILES(buf_)                                                                      \
+  {                                                                                                   \
+    bf16_t* as_ = As + (buf_) * S::A_ELEMS;                                                           \
+    bf16_t* bs_ = Bs + (buf_) * S::B_ELEMS;                                                           \
+    _Pragma("unroll") for (int p = 0; p < A_PASSES; ++p) {                                            \
+      const int r_ = a_r + 32 * p;                                                                    \
+      *reinterpret_cast<u32x4*>(as_ + r_ * BK + swz(r_, a_c) * 8) = ra[p];                            \
+    }                                                                                                 \
+    if (!TRANS) {                                                                                     \
+      _Pragma("unroll") for (int p = 0; p < B_PASSES; ++p) {                                          \
+        const int r_ = a_r + 32 * p;                                                                  \
+        *reinterpret_cast<u32x4*>(bs_ + r_ * BK + swz(r_, a_c) * 8) = rb[p];                          \
+      }                                                                                               \
+    } else {                                                                                          \
+      _Pragma("unroll") for (int p = 0; p < B_PASSES; ++p) {                                          \
+        const int kr_ = bt_r + (256 / BCH) * p;                                                       \
+        *reinterpret_cast<u32x4*>(bs_ + kr_ * S::B_LD + bt_c * 8) = rb[p];                            \
+      }                                                                                               \
+    }                                                                                                 \
+  }
 
   f32x16 acc[MT][NT];
 #pragma unroll
@@ -124,13 +122,20 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   const int nk = K / BK;
-  load_tiles(0);
-  store_tiles(0);
-  __syncthreads();
   const int l32 = lane & 31, kg = lane >> 5;
+  // Software pipeline: the registers loaded during step kt are written to LDS at the top of
+  // step kt + 1, so their global-memory latency hides behind the MFMAs of step kt.  One
+  // barrier per step is enough with two LDS buffers: a wavefront that reaches the store of
+  // step kt + 1 has passed the barrier of step kt, which every wavefront reaches only after
+  // it finished reading the other buffer in step kt - 1.
+  FLEXCO_LOAD_TILES(0)
   for (int kt = 0; kt < nk; ++kt) {
     const int buf = kt & 1;
-    if (kt + 1 < nk) load_tiles((kt + 1) * BK);
+    FLEXCO_STORE_TILES(buf)
+    __syncthreads();
+    const int k_next = min(kt + 1, nk - 1) * BK;   // the last step re-reads its own tile (unused)
+    FLEXCO_LOAD_TILES(k_next)
+    __builtin_amdgcn_sched_barrier(0);
     const bf16_t* as = As + buf * S::A_ELEMS;
     const bf16_t* bs = Bs + buf * S::B_ELEMS;
 #pragma unroll
@@ -158,8 +163,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
         for (int j = 0; j < NT; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
     }
-    if (kt + 1 < nk) store_tiles(buf ^ 1);
-    __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
   }
 
   // ---- epilogue: D[i][j], j = lane % 32, i = 8 (r / 4) + 4 (lane / 32) + r % 4 ---------------
