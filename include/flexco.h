@@ -153,6 +153,7 @@ typedef struct flexco_maps {
   const int32_t* item_tile;     /* [n_items]                                              */
   const int32_t* item_split;    /* [n_items]                                              */
   const int32_t* tok_tile;      /* [T] tile of each token                                 */
+  const int32_t* tok_lora;      /* [T] index of the token in lora_tok, -1 without adapter */
 } flexco_maps;
 
 /* Paged KV cache of one layer (device, dtype of cfg).  Sec. 7, memory management.

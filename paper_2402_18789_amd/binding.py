@@ -18,7 +18,7 @@ FLEXCO_OK, FLEXCO_EINVAL, FLEXCO_ESHAPE, FLEXCO_EWORKSPACE, FLEXCO_EPAGE, FLEXCO
 FLEXCO_F32, FLEXCO_BF16 = 0, 1
 TARGET_NAMES = ("q", "k", "v", "o", "gate", "up", "down")
 N_TARGETS = 7
-ABI_VERSION = 1
+ABI_VERSION = 2
 
 
 class FlexcoError(RuntimeError):
@@ -51,7 +51,7 @@ _MAP_SCALARS = ("T", "n_req", "n_ft", "n_seg", "max_pages", "page_size", "n_tile
                 "tile_tokens", "kv_split_pages", "ft_req", "ft_tok0", "ft_pos0", "n_lora", "max_kv_len", "blob_ints")
 _MAP_ARRAYS = ("tok_req", "tok_pos", "slot", "req_tok_off", "req_kv_len", "req_kind", "block_table", "ft_tok",
                "seg_off", "seg_adapter", "lora_tok", "tile_req", "tile_tok0", "tile_ntok", "tile_nsplit",
-               "tile_part0", "item_tile", "item_split", "tok_tile")
+               "tile_part0", "item_tile", "item_split", "tok_tile", "tok_lora")
 
 
 class Maps(C.Structure):
@@ -181,7 +181,7 @@ def maps_to_numpy(m, blob):
             "req_kind": m.n_req, "block_table": m.n_req * m.max_pages, "ft_tok": m.n_ft, "seg_off": m.n_seg + 1,
             "seg_adapter": m.n_seg, "lora_tok": m.n_lora, "tile_req": m.n_tiles, "tile_tok0": m.n_tiles,
             "tile_ntok": m.n_tiles, "tile_nsplit": m.n_tiles, "tile_part0": m.n_tiles, "item_tile": m.n_items,
-            "item_split": m.n_items, "tok_tile": m.T}
+            "item_split": m.n_items, "tok_tile": m.T, "tok_lora": m.T}
     out = {n: getattr(m, n) for n in _MAP_SCALARS}
     for n, ln in lens.items():
         off = (getattr(m, n) - base) // 4

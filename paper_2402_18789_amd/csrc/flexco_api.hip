@@ -76,6 +76,8 @@ extern "C" int32_t flexco_kernel_timer_stop(int32_t kernel_id, double* total_ms,
 
 namespace {
 
+constexpr int KS_MAX = 32;   // largest K split of the LoRA shrink kernel
+
 struct Carver {
   char* base;
   size_t off = 0;
@@ -86,14 +88,35 @@ struct Carver {
   }
 };
 
+// scratch of the bf16 LoRA path for `rows` token rows
+struct LoraWs {
+  float* part[6];     // K-split partial sums, [KS_MAX, rows, r] each
+  float* f32[6];      // reduced [rows, r]
+  bf16_t* ext[3];     // scaled bf16 [rows, r] for the GEMM extension
+  bf16_t* bt[3];      // transposed B, [r, max_out]
+};
+
+void carve_lora(const flexco_layer_cfg& c, int rows, Carver& cv, LoraWs& w) {
+  const int r = c.lora_rank > 0 ? c.lora_rank : 1;
+  const size_t qd = (size_t)c.n_q_heads * c.head_dim;
+  size_t max_out = c.hidden > c.ffn ? c.hidden : c.ffn;
+  if (qd > max_out) max_out = qd;
+  for (int i = 0; i < 6; ++i) w.part[i] = (float*)cv.take(sizeof(float) * KS_MAX * (size_t)rows * r);
+  for (int i = 0; i < 6; ++i) w.f32[i] = (float*)cv.take(sizeof(float) * (size_t)rows * r);
+  for (int i = 0; i < 3; ++i) w.ext[i] = (bf16_t*)cv.take(sizeof(bf16_t) * (size_t)rows * r);
+  for (int i = 0; i < 3; ++i) w.bt[i] = (bf16_t*)cv.take(sizeof(bf16_t) * max_out * r);
+}
+
 struct FwdWs {
   void *h, *qkv, *attn, *x2, *gu, *act;
   float *lse, *u, *part_ml, *part_acc;
+  LoraWs lw;
   size_t bytes;
 };
 struct BwdWs {
   void *hn, *act, *dact, *dgu, *dh, *dx2, *dattn, *dq, *dqkv;
   float *delta, *u, *t;
+  LoraWs lw;
   size_t bytes;
 };
 
@@ -118,6 +141,7 @@ FwdWs carve_fwd(const flexco_layer_cfg& c, int T, int n_parts, void* base) {
   const size_t prow = (size_t)n_parts * c.n_kv_heads * cols_per_tile(c);
   w.part_ml = (float*)cv.take(sizeof(float) * prow * 2);
   w.part_acc = (float*)cv.take(sizeof(float) * prow * c.head_dim);
+  carve_lora(c, T, cv, w.lw);
   w.bytes = cv.off;
   return w;
 }
@@ -140,6 +164,7 @@ BwdWs carve_bwd(const flexco_layer_cfg& c, int n, void* base) {
   const int r = c.lora_rank > 0 ? c.lora_rank : 1;
   w.u = (float*)cv.take(sizeof(float) * n * r);
   w.t = (float*)cv.take(sizeof(float) * n * r);
+  carve_lora(c, n, cv, w.lw);
   w.bytes = cv.off;
   return w;
 }
@@ -205,8 +230,8 @@ int32_t check_maps(const flexco_layer_cfg& c, const flexco_maps* m) {
   const int group = c.n_q_heads / c.n_kv_heads;
   FLEXCO_CHECK(m->tile_tokens == (16 / group > 1 ? 16 / group : 1), FLEXCO_ESHAPE,
                "maps were built for a different n_q_heads / n_kv_heads ratio");
-  FLEXCO_CHECK(m->tok_req && m->tok_pos && m->slot && m->block_table && m->tile_req && m->item_tile && m->tok_tile,
-               FLEXCO_EINVAL, "maps hold a NULL array");
+  FLEXCO_CHECK(m->tok_req && m->tok_pos && m->slot && m->block_table && m->tile_req && m->item_tile && m->tok_tile &&
+                   m->tok_lora, FLEXCO_EINVAL, "maps hold a NULL array");
   return FLEXCO_OK;
 }
 
@@ -225,16 +250,144 @@ void target_dims(const flexco_layer_cfg& c, int t, int* in, int* out) {
 
 inline char* boff(void* p, size_t elems, size_t e) { return (char*)p + elems * e; }
 inline const char* boff(const void* p, size_t elems, size_t e) { return (const char*)p + elems * e; }
+inline bool has_target(const flexco_layer_cfg& c, int t) { return (c.lora_targets >> t & 1) != 0; }
 
-// y[lora rows, col0 : col0 + out] += scale (x[lora rows] A^T) B^T
+// unfused fallback: y[lora rows, col0 : col0 + out] += scale (x[lora rows] A^T) B^T
 int32_t lora_apply(const flexco_layer_cfg& c, const flexco_lora* l, int t, const flexco_maps& m, const void* x,
                    size_t ldx, void* y, size_t ldy, size_t col0, float* u, hipStream_t s) {
-  if (!(c.lora_targets >> t & 1) || m.n_lora == 0) return FLEXCO_OK;
+  if (!has_target(c, t) || m.n_lora == 0) return FLEXCO_OK;
   int in, out;
   target_dims(c, t, &in, &out);
   FLEXCO_TRY(launch_lora_shrink(x, ldx, l->A[t], u, m.n_lora, in, c.lora_rank, c.dtype, m.lora_tok, s));
   return launch_lora_expand(u, l->B[t], boff(y, col0, esize(c.dtype)), ldy, m.n_lora, out, c.lora_rank,
                             c.lora_scale, c.dtype, m.lora_tok, s);
+}
+
+// the bf16 LoRA path needs whole MFMA k-steps in the rank and in the contracted dimensions
+bool lora_mfma_ok(const flexco_layer_cfg& c, int k_dim) {
+  return c.dtype == FLEXCO_BF16 && c.lora_rank % 16 == 0 && k_dim % 128 == 0;
+}
+
+// One projection of the forward pass over all T tokens, with the LoRA bypass of up to three
+// targets that share its input (q/k/v, gate/up) folded in:
+//   y[:, col0_t : col1_t] = x W^T (+bias) (+res)  +  scale (x A_t^T) B_t^T on adapter rows.
+int32_t forward_projection(const flexco_layer_cfg& c, const flexco_lora* lora, const flexco_maps& m, const void* x,
+                           int K, const void* W, const void* bias, const void* res, size_t ldr, void* y, int N,
+                           const int* targets, const int* col0, int n_targets, FwdWs& k, hipStream_t s) {
+  int act[3], nact = 0;
+  for (int i = 0; i < n_targets; ++i)
+    if (m.n_lora > 0 && has_target(c, targets[i])) act[nact++] = i;
+  const int T = m.T, dt = c.dtype, r = c.lora_rank;
+  if (nact > 0 && lora_mfma_ok(c, K)) {
+    LoraShrinkArgs sa;
+    LoraFinalizeArgs fa;
+    GemmExt ext;
+    memset(&sa, 0, sizeof(sa)); memset(&fa, 0, sizeof(fa)); memset(&ext, 0, sizeof(ext));
+    sa.row_idx = m.lora_tok; sa.n = m.n_lora; sa.K = K; sa.KS = lora_shrink_splits(m.n_lora, K); sa.r = r;
+    fa.ext_map = m.tok_lora; fa.ext_rows = T; fa.n = m.n_lora; fa.r = r; fa.KS = sa.KS; fa.scale = c.lora_scale;
+    ext.n = nact; ext.r = r;
+    for (int z = 0; z < nact; ++z) {
+      const int t = targets[act[z]];
+      int in, out;
+      target_dims(c, t, &in, &out);
+      sa.X[z] = (const bf16_t*)x; sa.ldx[z] = K; sa.S[z] = (const bf16_t*)lora->A[t]; sa.lds[z] = K;
+      sa.part[z] = k.lw.part[z];
+      fa.part[z] = k.lw.part[z]; fa.out_f32[z] = nullptr; fa.out_ext[z] = k.lw.ext[z];
+      ext.col0[z] = col0[act[z]]; ext.col1[z] = col0[act[z]] + out;
+      ext.A2[z] = k.lw.ext[z]; ext.W2[z] = (const bf16_t*)lora->B[t]; ext.ldw2[z] = r;
+    }
+    LR(launch_lora_shrink_mfma(sa, nact, s));
+    LR(launch_lora_finalize(fa, nact, s));
+    int32_t rc = launch_gemm(x, W, y, bias, res, T, N, K, K, K, N, ldr, false, dt, s, &ext);
+    if (rc != FLEXCO_EUNSUPPORTED) return rc;
+    clear_error();   // e.g. a target boundary inside a GEMM tile: run the bypass as separate kernels
+  }
+  FLEXCO_TRY(launch_gemm(x, W, y, bias, res, T, N, K, K, K, N, ldr, false, dt, s));
+  for (int z = 0; z < nact; ++z)
+    LR(lora_apply(c, lora, targets[act[z]], m, x, K, y, N, col0[act[z]], k.u, s));
+  return FLEXCO_OK;
+}
+
+// One input-gradient projection of the backward window with the LoRA gradients of up to three
+// targets that feed it:   dx = dy W (+ sum_t scale (dy_t B_t) A_t);
+//   dB_t += scale dy_t^T (x_t A_t^T);   dA_t += scale (dy_t B_t)^T x_t.
+// dy_t = columns [col0_t, col0_t + out_t) of dy; x_t: the target's input rows (in_t wide).
+// dx may be NULL (only the LoRA gradients are wanted).
+int32_t backward_projection(const flexco_layer_cfg& c, const flexco_lora* lora, int n, const void* dy, int K_dy,
+                            const void* W, void* dx, int N_dx, const int* targets, const int* col0,
+                            const void* const* xs, int n_targets, BwdWs& k, hipStream_t s) {
+  const int dt = c.dtype, r = c.lora_rank;
+  const size_t e = esize(dt);
+  int act[3], nact = 0;
+  for (int i = 0; i < n_targets; ++i)
+    if (has_target(c, targets[i])) act[nact++] = i;
+  bool fused = nact > 0 && lora_mfma_ok(c, N_dx);
+  for (int z = 0; z < nact && fused; ++z) {
+    int in, out;
+    target_dims(c, targets[act[z]], &in, &out);
+    if (out % 128 != 0 || in != N_dx) fused = false;
+  }
+  if (fused) {
+    // u_t = x_t A_t^T (one launch: the targets of a group share the input width)
+    LoraShrinkArgs su, st;
+    LoraFinalizeArgs fu, ft;
+    LoraTransposeArgs ta;
+    GemmExt ext;
+    memset(&su, 0, sizeof(su)); memset(&fu, 0, sizeof(fu)); memset(&ta, 0, sizeof(ta)); memset(&ext, 0, sizeof(ext));
+    su.n = n; su.K = N_dx; su.KS = lora_shrink_splits(n, N_dx); su.r = r;
+    fu.n = n; fu.r = r; fu.KS = su.KS; fu.scale = 1.f;
+    ta.r = r;
+    ext.n = nact; ext.r = r;
+    for (int z = 0; z < nact; ++z) {
+      const int t = targets[act[z]];
+      int in, out;
+      target_dims(c, t, &in, &out);
+      su.X[z] = (const bf16_t*)xs[act[z]]; su.ldx[z] = in; su.S[z] = (const bf16_t*)lora->A[t]; su.lds[z] = in;
+      su.part[z] = k.lw.part[z];
+      fu.part[z] = k.lw.part[z]; fu.out_f32[z] = k.lw.f32[z]; fu.out_ext[z] = nullptr;
+      ta.B[z] = (const bf16_t*)lora->B[t]; ta.Bt[z] = k.lw.bt[z]; ta.out[z] = out;
+      ext.A2[z] = k.lw.ext[z]; ext.W2[z] = (const bf16_t*)lora->A[t]; ext.ldw2[z] = in;
+    }
+    LR(launch_lora_shrink_mfma(su, nact, s));
+    LR(launch_lora_finalize(fu, nact, s));
+    LR(launch_lora_transpose(ta, nact, s));
+    // t_t = dy_t B_t (contracted width differs per target: one launch each)
+    for (int z = 0; z < nact; ++z) {
+      const int t = targets[act[z]];
+      int in, out;
+      target_dims(c, t, &in, &out);
+      memset(&st, 0, sizeof(st)); memset(&ft, 0, sizeof(ft));
+      st.n = n; st.K = out; st.KS = lora_shrink_splits(n, out); st.r = r;
+      st.X[0] = (const bf16_t*)boff(dy, col0[act[z]], e); st.ldx[0] = K_dy; st.S[0] = k.lw.bt[z]; st.lds[0] = out;
+      st.part[0] = k.lw.part[3 + z];
+      ft.n = n; ft.r = r; ft.KS = st.KS; ft.scale = c.lora_scale;
+      ft.part[0] = k.lw.part[3 + z]; ft.out_f32[0] = k.lw.f32[3 + z]; ft.out_ext[0] = k.lw.ext[z];
+      LR(launch_lora_shrink_mfma(st, 1, s));
+      LR(launch_lora_finalize(ft, 1, s));
+    }
+    if (dx) {
+      int32_t rc = launch_gemm(dy, W, dx, nullptr, nullptr, n, N_dx, K_dy, K_dy, N_dx, N_dx, 0, true, dt, s, &ext);
+      if (rc) return rc;
+    }
+    for (int z = 0; z < nact; ++z) {
+      const int t = targets[act[z]];
+      int in, out;
+      target_dims(c, t, &in, &out);
+      LR(launch_lora_outer_bf16(boff(dy, col0[act[z]], e), K_dy, k.lw.f32[z], lora->dB[t], r, 1, n, out, r,
+                                c.lora_scale, s));
+      LR(launch_lora_outer_bf16(xs[act[z]], in, k.lw.f32[3 + z], lora->dA[t], 1, in, n, in, r, c.lora_scale, s));
+    }
+    return FLEXCO_OK;
+  }
+  if (dx) FLEXCO_TRY(launch_gemm(dy, W, dx, nullptr, nullptr, n, N_dx, K_dy, K_dy, N_dx, N_dx, 0, true, dt, s));
+  for (int z = 0; z < nact; ++z) {
+    const int t = targets[act[z]];
+    int in, out;
+    target_dims(c, t, &in, &out);
+    LR(launch_lora_bwd(xs[act[z]], in, boff(dy, col0[act[z]], e), K_dy, lora->A[t], lora->B[t], lora->dA[t],
+                       lora->dB[t], dx, N_dx, k.u, k.t, n, in, out, r, c.lora_scale, dt, s));
+  }
+  return FLEXCO_OK;
 }
 
 int32_t run_attention(const flexco_layer_cfg& c, const flexco_maps& m, const void* q, size_t ldq,
@@ -259,17 +412,19 @@ int32_t run_attention(const flexco_layer_cfg& c, const flexco_maps& m, const voi
 
 namespace flexco {
 int32_t launch_gemm(const void* A, const void* W, void* C, const void* bias, const void* residual, int M, int N,
-                    int K, size_t lda, size_t ldw, size_t ldc, size_t ldr, bool trans_w, int dtype, hipStream_t s) {
+                    int K, size_t lda, size_t ldw, size_t ldc, size_t ldr, bool trans_w, int dtype, hipStream_t s,
+                    const GemmExt* ext) {
   if (M == 0) return FLEXCO_OK;
   if (dtype == FLEXCO_BF16) {
     int32_t rc;
     {
       KernelTimerScope ts(trans_w ? FLEXCO_K_GEMM_BWD : FLEXCO_K_GEMM_FWD, s);
-      rc = launch_gemm_mfma(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, trans_w, s);
+      rc = launch_gemm_mfma(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, trans_w, ext, s);
     }
     if (rc != FLEXCO_EUNSUPPORTED) return rc;
     clear_error();
   }
+  if (ext && ext->n > 0) return FLEXCO_EUNSUPPORTED;   // the generic kernel has no rank-r extension
   KernelTimerScope ts(FLEXCO_K_GENERIC, s);
   return launch_gemm_generic(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, trans_w, dtype, s);
 }
@@ -329,24 +484,24 @@ extern "C" int32_t flexco_lora_fwd(const void* x, void* y, int32_t T, int32_t in
   FLEXCO_CHECK(dtype == FLEXCO_F32 || dtype == FLEXCO_BF16, FLEXCO_ESHAPE, "unknown dtype %d", dtype);
   FLEXCO_CHECK(aligned16(x) && aligned16(y) && aligned16(u_ws), FLEXCO_EINVAL, "misaligned pointer");
   FLEXCO_CHECK(seg_off[0] == 0 && seg_off[n_seg] == T, FLEXCO_ESHAPE, "segments must cover rows [0, T)");
-  for (int s = 0; s < n_seg; ++s) {
-    FLEXCO_CHECK(seg_off[s + 1] > seg_off[s], FLEXCO_ESHAPE, "segment %d is empty or descending", s);
-    FLEXCO_CHECK(seg_adapter[s] >= -1 && seg_adapter[s] < n_adapters, FLEXCO_EINVAL,
-                 "segment %d: adapter %d outside [-1, %d)", s, seg_adapter[s], n_adapters);
-    if (seg_adapter[s] >= 0)
-      FLEXCO_CHECK(A_list[seg_adapter[s]] && B_list[seg_adapter[s]], FLEXCO_EINVAL, "adapter %d has a NULL matrix",
-                   seg_adapter[s]);
+  for (int sg = 0; sg < n_seg; ++sg) {
+    FLEXCO_CHECK(seg_off[sg + 1] > seg_off[sg], FLEXCO_ESHAPE, "segment %d is empty or descending", sg);
+    FLEXCO_CHECK(seg_adapter[sg] >= -1 && seg_adapter[sg] < n_adapters, FLEXCO_EINVAL,
+                 "segment %d: adapter %d outside [-1, %d)", sg, seg_adapter[sg], n_adapters);
+    if (seg_adapter[sg] >= 0)
+      FLEXCO_CHECK(A_list[seg_adapter[sg]] && B_list[seg_adapter[sg]], FLEXCO_EINVAL, "adapter %d has a NULL matrix",
+                   seg_adapter[sg]);
   }
   const size_t e = esize(dtype);
-  hipStream_t st = (hipStream_t)stream;
-  for (int s = 0; s < n_seg; ++s) {
-    const int a = seg_adapter[s];
+  hipStream_t s = (hipStream_t)stream;
+  for (int sg = 0; sg < n_seg; ++sg) {
+    const int a = seg_adapter[sg];
     if (a < 0) continue;
-    const int r0 = seg_off[s], n = seg_off[s + 1] - r0;
-    FLEXCO_TRY(launch_lora_shrink(boff(x, (size_t)r0 * in_features, e), in_features, A_list[a], u_ws + (size_t)r0 * rank,
-                                  n, in_features, rank, dtype, nullptr, st));
-    FLEXCO_TRY(launch_lora_expand(u_ws + (size_t)r0 * rank, B_list[a], boff(y, (size_t)r0 * out_features, e),
-                                  out_features, n, out_features, rank, scale, dtype, nullptr, st));
+    const int r0 = seg_off[sg], n = seg_off[sg + 1] - r0;
+    LR(launch_lora_shrink(boff(x, (size_t)r0 * in_features, e), in_features, A_list[a], u_ws + (size_t)r0 * rank, n,
+                          in_features, rank, dtype, nullptr, s));
+    LR(launch_lora_expand(u_ws + (size_t)r0 * rank, B_list[a], boff(y, (size_t)r0 * out_features, e), out_features,
+                          n, out_features, rank, scale, dtype, nullptr, s));
   }
   return FLEXCO_OK;
 }
@@ -380,27 +535,32 @@ extern "C" int32_t flexco_layer_forward(const flexco_layer_cfg* cfg, const flexc
   hipStream_t s = (hipStream_t)stream;
   const int T = m.T, H = c.hidden, F = c.ffn, dt = c.dtype;
   const size_t e = esize(dt);
-  const size_t qd = (size_t)c.n_q_heads * c.head_dim, kd = (size_t)c.n_kv_heads * c.head_dim, qkvd = qd + 2 * kd;
+  const int qd = c.n_q_heads * c.head_dim, kd = c.n_kv_heads * c.head_dim, qkvd = qd + 2 * kd;
 
   // attention side
   EW(launch_rmsnorm(x_in, w->g1, k.h, T, H, c.rms_eps, dt, s));
-  FLEXCO_TRY(launch_gemm(k.h, w->wqkv, k.qkv, w->bqkv, nullptr, T, (int)qkvd, H, H, H, qkvd, 0, false, dt, s));
-  LR(lora_apply(c, lora, FLEXCO_T_Q, m, k.h, H, k.qkv, qkvd, 0, k.u, s));
-  LR(lora_apply(c, lora, FLEXCO_T_K, m, k.h, H, k.qkv, qkvd, qd, k.u, s));
-  LR(lora_apply(c, lora, FLEXCO_T_V, m, k.h, H, k.qkv, qkvd, qd + kd, k.u, s));
+  {
+    const int tg[3] = {FLEXCO_T_Q, FLEXCO_T_K, FLEXCO_T_V}, c0[3] = {0, qd, qd + kd};
+    FLEXCO_TRY(forward_projection(c, lora, m, k.h, H, w->wqkv, w->bqkv, nullptr, 0, k.qkv, qkvd, tg, c0, 3, k, s));
+  }
   EW(launch_rope_append(c, k.qkv, m.tok_pos, m.slot, *pool, T, m.ft_tok0, m.n_ft, m.ft_pos0,
-                                ft ? ft->q_cache : nullptr, s));
+                        ft ? ft->q_cache : nullptr, s));
   FLEXCO_TRY(run_attention(c, m, k.qkv, qkvd, *pool, k.attn, qd, ft ? k.lse : nullptr, k.part_ml, k.part_acc, s));
-  FLEXCO_TRY(launch_gemm(k.attn, w->wo, k.x2, nullptr, x_in, T, H, (int)qd, qd, qd, H, H, false, dt, s));
-  LR(lora_apply(c, lora, FLEXCO_T_O, m, k.attn, qd, k.x2, H, 0, k.u, s));
+  {
+    const int tg[1] = {FLEXCO_T_O}, c0[1] = {0};
+    FLEXCO_TRY(forward_projection(c, lora, m, k.attn, qd, w->wo, nullptr, x_in, H, k.x2, H, tg, c0, 1, k, s));
+  }
   // MLP side
   EW(launch_rmsnorm(k.x2, w->g2, k.h, T, H, c.rms_eps, dt, s));
-  FLEXCO_TRY(launch_gemm(k.h, w->wgu, k.gu, nullptr, nullptr, T, 2 * F, H, H, H, 2 * (size_t)F, 0, false, dt, s));
-  LR(lora_apply(c, lora, FLEXCO_T_GATE, m, k.h, H, k.gu, 2 * (size_t)F, 0, k.u, s));
-  LR(lora_apply(c, lora, FLEXCO_T_UP, m, k.h, H, k.gu, 2 * (size_t)F, F, k.u, s));
+  {
+    const int tg[2] = {FLEXCO_T_GATE, FLEXCO_T_UP}, c0[2] = {0, F};
+    FLEXCO_TRY(forward_projection(c, lora, m, k.h, H, w->wgu, nullptr, nullptr, 0, k.gu, 2 * F, tg, c0, 2, k, s));
+  }
   EW(launch_swiglu(k.gu, k.act, T, F, dt, s));
-  FLEXCO_TRY(launch_gemm(k.act, w->wd, x_out, nullptr, k.x2, T, H, F, F, F, H, H, false, dt, s));
-  LR(lora_apply(c, lora, FLEXCO_T_DOWN, m, k.act, F, x_out, H, 0, k.u, s));
+  {
+    const int tg[1] = {FLEXCO_T_DOWN}, c0[1] = {0};
+    FLEXCO_TRY(forward_projection(c, lora, m, k.act, F, w->wd, nullptr, k.x2, H, x_out, H, tg, c0, 1, k, s));
+  }
   // keep what graph pruning leaves alive for the finetune rows (Alg. 1), at their positions
   if (ft) {
     const int n = m.n_ft;
@@ -410,8 +570,8 @@ extern "C" int32_t flexco_layer_forward(const flexco_layer_cfg* cfg, const flexc
     EW(launch_copy_rows(boff(k.gu, t0 * 2 * F, e), 2 * F * e, boff(ft->saved_gate, p0 * F, e), F * e, n, F * e, s));
     EW(launch_copy_rows(boff(k.gu, t0 * 2 * F + F, e), 2 * F * e, boff(ft->saved_up, p0 * F, e), F * e, n, F * e, s));
     EW(launch_copy_rows(boff(k.attn, t0 * qd, e), qd * e, boff(ft->saved_attn, p0 * qd, e), qd * e, n, qd * e, s));
-    EW(launch_copy_rows(k.lse + t0 * c.n_q_heads, c.n_q_heads * 4, ft->lse + p0 * c.n_q_heads,
-                                c.n_q_heads * 4, n, c.n_q_heads * 4, s));
+    EW(launch_copy_rows(k.lse + t0 * c.n_q_heads, c.n_q_heads * 4, ft->lse + p0 * c.n_q_heads, c.n_q_heads * 4, n,
+                        c.n_q_heads * 4, s));
   }
   return FLEXCO_OK;
 }
@@ -422,6 +582,10 @@ static int32_t attention_window_bwd_impl(const flexco_layer_cfg& c, const flexco
                                          float* dk_accum, float* dv_accum, float* delta, hipStream_t s) {
   KernelTimerScope ts(FLEXCO_K_ATTN_BWD, s);
   FLEXCO_TRY(launch_attention_delta(c, out, dout, delta, win_len, s));
+  int32_t rc = launch_attention_bwd_mfma(c, pool, seq_pages, win_start, win_len, q, lse, delta, dout, dq, dk_accum,
+                                         dv_accum, s);
+  if (rc != FLEXCO_EUNSUPPORTED) return rc;
+  clear_error();
   return launch_attention_bwd_generic(c, pool, seq_pages, win_start, win_len, q, lse, delta, dout, dq, dk_accum,
                                       dv_accum, s);
 }
@@ -469,10 +633,9 @@ extern "C" int32_t flexco_lora_bwd(const flexco_layer_cfg* cfg, const flexco_bas
   FLEXCO_CHECK(k.bytes <= ws_bytes, FLEXCO_EWORKSPACE, "backward needs %zu workspace bytes, got %zu", k.bytes, ws_bytes);
 
   hipStream_t s = (hipStream_t)stream;
-  const int n = win_len, H = c.hidden, F = c.ffn, dt = c.dtype, r = c.lora_rank;
+  const int n = win_len, H = c.hidden, F = c.ffn, dt = c.dtype;
   const size_t e = esize(dt), w0 = win_start;
-  const size_t qd = (size_t)c.n_q_heads * c.head_dim, kd = (size_t)c.n_kv_heads * c.head_dim, qkvd = qd + 2 * kd;
-  auto has = [&](int t) { return (c.lora_targets >> t & 1) != 0; };
+  const int qd = c.n_q_heads * c.head_dim, kd = c.n_kv_heads * c.head_dim, qkvd = qd + 2 * kd;
   const void* x_w = boff(ft->saved_x, w0 * H, e);
   const void* x2_w = boff(ft->saved_x2, w0 * H, e);
   const void* gate_w = boff(ft->saved_gate, w0 * F, e);
@@ -482,49 +645,38 @@ extern "C" int32_t flexco_lora_bwd(const flexco_layer_cfg* cfg, const flexco_bas
   const float* lse_w = ft->lse + w0 * c.n_q_heads;
 
   // ---- MLP side: down projection, SwiGLU, gate/up projections, second norm -------------
-  FLEXCO_TRY(launch_gemm(dY, w->wd, k.dact, nullptr, nullptr, n, F, H, H, F, F, 0, true, dt, s));
-  if (has(FLEXCO_T_DOWN)) {
-    EW(launch_swiglu_remat(gate_w, up_w, k.act, n, F, dt, s));
-    LR(launch_lora_bwd(k.act, F, dY, H, lora->A[FLEXCO_T_DOWN], lora->B[FLEXCO_T_DOWN],
-                               lora->dA[FLEXCO_T_DOWN], lora->dB[FLEXCO_T_DOWN], k.dact, F, k.u, k.t, n, F, H, r,
-                               c.lora_scale, dt, s));
+  if (has_target(c, FLEXCO_T_DOWN)) EW(launch_swiglu_remat(gate_w, up_w, k.act, n, F, dt, s));   // rematerialised
+  {
+    const int tg[1] = {FLEXCO_T_DOWN}, c0[1] = {0};
+    const void* xs[1] = {k.act};
+    FLEXCO_TRY(backward_projection(c, lora, n, dY, H, w->wd, k.dact, F, tg, c0, xs, 1, k, s));
   }
   EW(launch_swiglu_bwd(gate_w, up_w, k.dact, k.dgu, n, F, dt, s));
-  FLEXCO_TRY(launch_gemm(k.dgu, w->wgu, k.dh, nullptr, nullptr, n, H, 2 * F, 2 * (size_t)F, H, H, 0, true, dt, s));
-  if (has(FLEXCO_T_GATE) || has(FLEXCO_T_UP)) {
-    EW(launch_rmsnorm(x2_w, w->g2, k.hn, n, H, c.rms_eps, dt, s));
-    for (int t : {FLEXCO_T_GATE, FLEXCO_T_UP}) {
-      if (!has(t)) continue;
-      const void* dy = boff(k.dgu, t == FLEXCO_T_UP ? F : 0, e);
-      LR(launch_lora_bwd(k.hn, H, dy, 2 * (size_t)F, lora->A[t], lora->B[t], lora->dA[t], lora->dB[t], k.dh,
-                                 H, k.u, k.t, n, H, F, r, c.lora_scale, dt, s));
-    }
+  if (has_target(c, FLEXCO_T_GATE) || has_target(c, FLEXCO_T_UP)) EW(launch_rmsnorm(x2_w, w->g2, k.hn, n, H, c.rms_eps, dt, s));
+  {
+    const int tg[2] = {FLEXCO_T_GATE, FLEXCO_T_UP}, c0[2] = {0, F};
+    const void* xs[2] = {k.hn, k.hn};
+    FLEXCO_TRY(backward_projection(c, lora, n, k.dgu, 2 * F, w->wgu, k.dh, H, tg, c0, xs, 2, k, s));
   }
   EW(launch_rmsnorm_bwd(x2_w, w->g2, k.dh, dY, k.dx2, n, H, c.rms_eps, dt, s));
   // ---- output projection ------------------------------------------------------------------
-  FLEXCO_TRY(launch_gemm(k.dx2, w->wo, k.dattn, nullptr, nullptr, n, (int)qd, H, H, qd, qd, 0, true, dt, s));
-  if (has(FLEXCO_T_O))
-    LR(launch_lora_bwd(attn_w, qd, k.dx2, H, lora->A[FLEXCO_T_O], lora->B[FLEXCO_T_O], lora->dA[FLEXCO_T_O],
-                               lora->dB[FLEXCO_T_O], k.dattn, qd, k.u, k.t, n, (int)qd, H, r, c.lora_scale, dt, s));
+  {
+    const int tg[1] = {FLEXCO_T_O}, c0[1] = {0};
+    const void* xs[1] = {attn_w};
+    FLEXCO_TRY(backward_projection(c, lora, n, k.dx2, H, w->wo, k.dattn, qd, tg, c0, xs, 1, k, s));
+  }
   // ---- attention: dQ of the window, dK/dV of every cached row before its end (Sec. 6.1) ---
   FLEXCO_TRY(attention_window_bwd_impl(c, *pool, seq_pages, win_start, win_len, q_w, attn_w, lse_w, k.dattn, k.dq,
                                        ft->dk_accum, ft->dv_accum, k.delta, s));
   // ---- q/k/v side: the window's accumulator rows are complete now (Sec. 7) ---------------
-  const bool qkv_lora = has(FLEXCO_T_Q) || has(FLEXCO_T_K) || has(FLEXCO_T_V);
+  const bool qkv_lora = has_target(c, FLEXCO_T_Q) || has_target(c, FLEXCO_T_K) || has_target(c, FLEXCO_T_V);
   if (!dX && !qkv_lora) return FLEXCO_OK;
   EW(launch_rope_bwd_pack(c, k.dq, ft->dk_accum + w0 * kd, ft->dv_accum + w0 * kd, k.dqkv, win_start, n, s));
-  if (dX)
-    FLEXCO_TRY(launch_gemm(k.dqkv, w->wqkv, k.dh, nullptr, nullptr, n, H, (int)qkvd, qkvd, H, H, 0, true, dt, s));
-  if (qkv_lora) {
-    EW(launch_rmsnorm(x_w, w->g1, k.hn, n, H, c.rms_eps, dt, s));
-    const size_t col0[3] = {0, qd, qd + kd};
-    for (int t : {FLEXCO_T_Q, FLEXCO_T_K, FLEXCO_T_V}) {
-      if (!has(t)) continue;
-      int in, out;
-      target_dims(c, t, &in, &out);
-      LR(launch_lora_bwd(k.hn, H, boff(k.dqkv, col0[t], e), qkvd, lora->A[t], lora->B[t], lora->dA[t],
-                                 lora->dB[t], dX ? k.dh : nullptr, H, k.u, k.t, n, H, out, r, c.lora_scale, dt, s));
-    }
+  if (qkv_lora) EW(launch_rmsnorm(x_w, w->g1, k.hn, n, H, c.rms_eps, dt, s));
+  {
+    const int tg[3] = {FLEXCO_T_Q, FLEXCO_T_K, FLEXCO_T_V}, c0[3] = {0, qd, qd + kd};
+    const void* xs[3] = {k.hn, k.hn, k.hn};
+    FLEXCO_TRY(backward_projection(c, lora, n, k.dqkv, qkvd, w->wqkv, dX ? k.dh : nullptr, H, tg, c0, xs, 3, k, s));
   }
   if (dX) EW(launch_rmsnorm_bwd(x_w, w->g1, k.dh, k.dx2, dX, n, H, c.rms_eps, dt, s));
   return FLEXCO_OK;

@@ -5,8 +5,35 @@
 #include <stddef.h>
 
 #include "flexco.h"
+#include "device_types.h"
 
 namespace flexco {
+
+// ---- argument blocks of the bf16 LoRA kernels (up to 3 matrices per launch, grid.z) ----------
+struct LoraShrinkArgs {     // part[z][ks][row][rank] = sum over the split's k of X[z][row, k] S[z][rank, k]
+  const bf16_t* X[3]; size_t ldx[3];
+  const bf16_t* S[3]; size_t lds[3];
+  float* part[3];
+  const int32_t* row_idx;   // rows of X to take (NULL: 0..n)
+  int n, K, KS, r;
+};
+struct LoraFinalizeArgs {
+  const float* part[3];
+  float* out_f32[3];        // [n, r] or NULL
+  bf16_t* out_ext[3];       // [rows, r] scaled, or NULL
+  const int32_t* ext_map;   // forward: [ext_rows] index into the n shrunk rows or -1; NULL: identity
+  int ext_rows, n, r, KS;
+  float scale;
+};
+struct LoraTransposeArgs { const bf16_t* B[3]; bf16_t* Bt[3]; int out[3]; int r; };
+// rank-r extension of a projection GEMM (see gemm_mfma.hip)
+struct GemmExt {
+  int n, r;
+  int col0[3], col1[3];
+  const bf16_t* A2[3];
+  const bf16_t* W2[3];
+  size_t ldw2[3];
+};
 
 int32_t fail(int32_t code, const char* fmt, ...);
 void clear_error();
@@ -30,13 +57,21 @@ struct KernelTimerScope {
 // ---- launchers: no validation, the entry points have done it -------------------------
 // C[M,N] = A[M,K] W[N,K]^T (+bias) (+residual);  trans_w: W is [K,N].  Leading dimensions in elements.
 int32_t launch_gemm(const void* A, const void* W, void* C, const void* bias, const void* residual, int M, int N,
-                    int K, size_t lda, size_t ldw, size_t ldc, size_t ldr, bool trans_w, int dtype, hipStream_t s);
+                    int K, size_t lda, size_t ldw, size_t ldc, size_t ldr, bool trans_w, int dtype, hipStream_t s,
+                    const GemmExt* ext = nullptr);
 int32_t launch_gemm_generic(const void* A, const void* W, void* C, const void* bias, const void* residual, int M,
                             int N, int K, size_t lda, size_t ldw, size_t ldc, size_t ldr, bool trans_w, int dtype,
                             hipStream_t s);
 // bf16 MFMA path; returns FLEXCO_EUNSUPPORTED (without launching) for shapes it does not cover
 int32_t launch_gemm_mfma(const void* A, const void* W, void* C, const void* bias, const void* residual, int M,
-                         int N, int K, size_t lda, size_t ldw, size_t ldc, size_t ldr, bool trans_w, hipStream_t s);
+                         int N, int K, size_t lda, size_t ldw, size_t ldc, size_t ldr, bool trans_w,
+                         const GemmExt* ext, hipStream_t s);
+int lora_shrink_splits(int n_rows, int K);
+int32_t launch_lora_shrink_mfma(const LoraShrinkArgs& a, int n_mats, hipStream_t s);
+int32_t launch_lora_finalize(const LoraFinalizeArgs& a, int n_mats, hipStream_t s);
+int32_t launch_lora_transpose(const LoraTransposeArgs& a, int n_mats, hipStream_t s);
+int32_t launch_lora_outer_bf16(const void* X, size_t ldx, const float* U, float* G, size_t g_i, size_t g_j, int n,
+                               int n_long, int r, float scale, hipStream_t s);
 
 int32_t launch_rmsnorm(const void* x, const void* g, void* h, int T, int H, float eps, int dtype, hipStream_t s);
 int32_t launch_rmsnorm_bwd(const void* x, const void* g, const void* dh, const void* add, void* dx, int T, int H,
@@ -66,6 +101,10 @@ int32_t launch_attention_generic(const flexco_layer_cfg& c, const flexco_maps& m
 // bf16, head_dim 128, page_size 16, group <= 16; otherwise FLEXCO_EUNSUPPORTED without launching
 int32_t launch_attention_mfma(const flexco_layer_cfg& c, const flexco_maps& m, const void* q, size_t ldq,
                               const flexco_kv_pool& pool, float* part_ml, float* part_acc, hipStream_t s);
+// bf16 window backward on the matrix cores; FLEXCO_EUNSUPPORTED (nothing launched) for other shapes
+int32_t launch_attention_bwd_mfma(const flexco_layer_cfg& c, const flexco_kv_pool& pool, const int32_t* seq_pages,
+                                  int win_start, int win_len, const void* q, const float* lse, const float* delta,
+                                  const void* dout, void* dq, float* dk_accum, float* dv_accum, hipStream_t s);
 int32_t launch_attention_merge(const flexco_layer_cfg& c, const flexco_maps& m, const float* part_ml,
                                const float* part_acc, void* out, size_t ldo, float* lse, hipStream_t s);
 int32_t launch_attention_delta(const flexco_layer_cfg& c, const void* out, const void* dout, float* delta, int n,

@@ -30,7 +30,7 @@ namespace {
 struct Built {
   std::vector<int32_t> tok_req, tok_pos, slot, req_tok_off, req_kv_len, req_kind, block_table, ft_tok,
       seg_off, seg_adapter, lora_tok, tile_req, tile_tok0, tile_ntok, tile_nsplit, tile_part0, item_tile,
-      item_split, tok_tile;
+      item_split, tok_tile, tok_lora;
   int32_t T = 0, n_ft = 0, n_seg = 0, max_pages = 1, n_parts = 0, ft_req = -1, max_kv_len = 0;
   int32_t tile_tokens = 1, split_pages = 32, ft_pos0 = 0;
 };
@@ -112,6 +112,7 @@ int32_t build(const flexco_batch_desc* d, int32_t page_size, int32_t num_pages, 
       b.tok_req.push_back(r);
       b.tok_pos.push_back(pos);
       b.slot.push_back((int32_t)slot);
+      b.tok_lora.push_back(d->adapter[r] >= 0 ? (int32_t)b.lora_tok.size() : -1);
       if (d->adapter[r] >= 0) b.lora_tok.push_back(t);
       if (d->kind[r] == FLEXCO_FINETUNE) b.ft_tok.push_back(t);
     }
@@ -165,7 +166,7 @@ size_t blob_need(const Built& b) {
   add(b.tok_req); add(b.tok_pos); add(b.slot); add(b.req_tok_off); add(b.req_kv_len); add(b.req_kind);
   add(b.block_table); add(b.ft_tok); add(b.seg_off); add(b.seg_adapter); add(b.lora_tok); add(b.tile_req);
   add(b.tile_tok0); add(b.tile_ntok); add(b.tile_nsplit); add(b.tile_part0); add(b.item_tile);
-  add(b.item_split); add(b.tok_tile);
+  add(b.item_split); add(b.tok_tile); add(b.tok_lora);
   return n;
 }
 
@@ -176,7 +177,7 @@ using namespace flexco;
 
 extern "C" const char* flexco_last_error(void) { return g_err; }
 
-extern "C" int32_t flexco_abi_version(void) { return 1; }
+extern "C" int32_t flexco_abi_version(void) { return 2; }
 
 extern "C" int32_t flexco_maps_blob_ints(const flexco_batch_desc* desc, int32_t page_size, int32_t n_q_heads,
                                          int32_t n_kv_heads, int32_t kv_split_pages, size_t* out_ints) {
@@ -219,7 +220,7 @@ extern "C" int32_t flexco_build_maps(const flexco_batch_desc* desc, int32_t page
   m.seg_adapter = w.put(b.seg_adapter); m.lora_tok = w.put(b.lora_tok); m.tile_req = w.put(b.tile_req);
   m.tile_tok0 = w.put(b.tile_tok0); m.tile_ntok = w.put(b.tile_ntok); m.tile_nsplit = w.put(b.tile_nsplit);
   m.tile_part0 = w.put(b.tile_part0); m.item_tile = w.put(b.item_tile); m.item_split = w.put(b.item_split);
-  m.tok_tile = w.put(b.tok_tile);
+  m.tok_tile = w.put(b.tok_tile); m.tok_lora = w.put(b.tok_lora);
   FLEXCO_CHECK(w.ok, FLEXCO_EWORKSPACE, "blob too small");
   m.blob_ints = (int32_t)w.used;
   *out = m;
@@ -234,7 +235,7 @@ extern "C" int32_t flexco_maps_rebase(const flexco_maps* host_maps, const int32_
   const int32_t** fields[] = {&m.tok_req, &m.tok_pos, &m.slot, &m.req_tok_off, &m.req_kv_len, &m.req_kind,
                               &m.block_table, &m.ft_tok, &m.seg_off, &m.seg_adapter, &m.lora_tok, &m.tile_req,
                               &m.tile_tok0, &m.tile_ntok, &m.tile_nsplit, &m.tile_part0, &m.item_tile,
-                              &m.item_split, &m.tok_tile};
+                              &m.item_split, &m.tok_tile, &m.tok_lora};
   for (auto f : fields) {
     FLEXCO_CHECK(*f >= host_blob && *f <= host_blob + m.blob_ints, FLEXCO_EINVAL,
                  "maps do not point into host_blob");

@@ -46,7 +46,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
                                                         bf16_t* __restrict__ C, const bf16_t* __restrict__ bias,
                                                         const bf16_t* __restrict__ res, int M, int N, int K,
                                                         size_t lda, size_t ldw, size_t ldc, size_t ldr, int tiles_m,
-                                                        int tiles_n) {
+                                                        int tiles_n, GemmExt ext) {
   constexpr int WM = BM / 2, WN = BN / 2, MT = WM / 32, NT = WN / 32;
   using S = Smem<BM, BN, TRANS>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -166,6 +166,40 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
     __builtin_amdgcn_sched_barrier(0);
   }
 
+  // ---- rank-r extension: C += A2 W2^T (forward form; the entry whose column range holds this
+  // block) or C += sum_e A2_e W2_e (input-gradient form; every entry).  This is the LoRA bypass
+  // network (Sec. 4.1) folded into the base projection as extra k-steps of 16, operands read
+  // straight from global memory (they are [rows, r] / [r, cols] matrices of a few KB per tile).
+  for (int e = 0; e < ext.n; ++e) {
+    if (!TRANS && !(n0 >= ext.col0[e] && n0 < ext.col1[e])) continue;
+    const bf16_t* A2 = ext.A2[e];
+    const bf16_t* W2 = ext.W2[e];
+    for (int k2 = 0; k2 < ext.r; k2 += 16) {
+      bf16x8 af[MT], bfr[NT];
+#pragma unroll
+      for (int i = 0; i < MT; ++i) {
+        const int r = min(m0 + wm0 + i * 32 + l32, M - 1);
+        af[i] = *reinterpret_cast<const bf16x8*>(A2 + (size_t)r * ext.r + k2 + kg * 8);
+      }
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        if (!TRANS) {
+          const int c = min(n0 + wn0 + j * 32 + l32, ext.col1[e] - 1) - ext.col0[e];
+          bfr[j] = *reinterpret_cast<const bf16x8*>(W2 + (size_t)c * ext.ldw2[e] + k2 + kg * 8);
+        } else {
+          const int c = min(n0 + wn0 + j * 32 + l32, N - 1);
+#pragma unroll
+          for (int q = 0; q < 8; ++q) bfr[j][q] = W2[(size_t)(k2 + kg * 8 + q) * ext.ldw2[e] + c];
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+  }
+
   // ---- epilogue: D[i][j], j = lane % 32, i = 8 (r / 4) + 4 (lane / 32) + r % 4 ---------------
 #pragma unroll
   for (int i = 0; i < MT; ++i) {
@@ -188,7 +222,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
 
 template <int BM, int BN, bool TRANS>
 int32_t launch_cfg(const void* A, const void* W, void* C, const void* bias, const void* res, int M, int N, int K,
-                   size_t lda, size_t ldw, size_t ldc, size_t ldr, hipStream_t s) {
+                   size_t lda, size_t ldw, size_t ldc, size_t ldr, const GemmExt& ext, hipStream_t s) {
   using S = Smem<BM, BN, TRANS>;
   auto kern = gemm_bf16_kernel<BM, BN, TRANS>;
   static bool attr_set = false;
@@ -200,7 +234,7 @@ int32_t launch_cfg(const void* A, const void* W, void* C, const void* bias, cons
   }
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(256), S::BYTES, s, (const bf16_t*)A, (const bf16_t*)W,
-                     (bf16_t*)C, (const bf16_t*)bias, (const bf16_t*)res, M, N, K, lda, ldw, ldc, ldr, tiles_m, tiles_n);
+                     (bf16_t*)C, (const bf16_t*)bias, (const bf16_t*)res, M, N, K, lda, ldw, ldc, ldr, tiles_m, tiles_n, ext);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(FLEXCO_EHIP, "launch of gemm_bf16 failed: %s", hipGetErrorString(e));
   return FLEXCO_OK;
@@ -208,15 +242,31 @@ int32_t launch_cfg(const void* A, const void* W, void* C, const void* bias, cons
 
 }  // namespace
 
+static bool ext_fits(const GemmExt& ext, bool trans_w, int BN) {
+  if (ext.n == 0) return true;
+  if (ext.r % 16 != 0) return false;
+  if (trans_w) return true;
+  for (int e = 0; e < ext.n; ++e)
+    if (ext.col0[e] % BN != 0 || ext.col1[e] % BN != 0) return false;   // one entry per block
+  return true;
+}
+
 int32_t launch_gemm_mfma(const void* A, const void* W, void* C, const void* bias, const void* residual, int M, int N,
-                         int K, size_t lda, size_t ldw, size_t ldc, size_t ldr, bool trans_w, hipStream_t s) {
+                         int K, size_t lda, size_t ldw, size_t ldc, size_t ldr, bool trans_w, const GemmExt* ext_in,
+                         hipStream_t s) {
   // shapes the tiled kernel covers: K in whole 64-wide steps, 16-byte aligned rows
   if (K % BK != 0 || lda % 8 != 0 || ldw % 8 != 0 || N % 8 != 0) return FLEXCO_EUNSUPPORTED;
-  if (trans_w) return launch_cfg<128, 128, true>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, s);
+  GemmExt ext;
+  if (ext_in) ext = *ext_in; else ext.n = 0;
+  if (trans_w) {
+    if (!ext_fits(ext, true, 128)) return FLEXCO_EUNSUPPORTED;
+    return launch_cfg<128, 128, true>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, ext, s);
+  }
   const long big_tiles = (long)((M + 255) / 256) * ((N + 255) / 256);
-  if (big_tiles >= 192)
-    return launch_cfg<256, 256, false>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, s);
-  return launch_cfg<128, 128, false>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, s);
+  if (big_tiles >= 192 && ext_fits(ext, false, 256))
+    return launch_cfg<256, 256, false>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, ext, s);
+  if (!ext_fits(ext, false, 128)) return FLEXCO_EUNSUPPORTED;
+  return launch_cfg<128, 128, false>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, ext, s);
 }
 
 }  // namespace flexco

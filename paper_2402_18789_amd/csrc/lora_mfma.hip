@@ -1,0 +1,203 @@
+// bf16 LoRA kernels around the projection GEMMs.
+//
+// The bypass network of Sec. 4.1, y = f_B(x) + scale (x A^T) B^T with rank r << in, out, is
+// split so that the large dimension is touched once:
+//   shrink   u = x A^T  (or t = dy B)   skinny product [n, K] x [K, r] on the matrix cores:
+//            one wavefront multiplies 16 rows by up to 64 ranks with v_mfma_f32_16x16x32_bf16,
+//            both operands fetched straight from global memory (8 consecutive k per lane),
+//            K is cut across the 4 wavefronts of a block and across blocks (grid.y); the
+//            per-split partial sums are combined in a fixed order by the finalize kernel,
+//            so results do not depend on scheduling.
+//   expand   is not a kernel: the projection GEMM appends the rank-r product as extra
+//            k-steps (gemm_mfma.hip), reading the bf16 matrix the finalize kernel writes.
+//   outer    dB += scale dy^T u,  dA += scale t^T x : every output element is a sum over
+//            the window's rows only; plain FMA code, 64 consecutive outputs per wavefront,
+//            rows interleaved over the block's 4 wavefronts, fixed-order LDS reduction.
+#include "flexco_internal.h"
+#include "device_types.h"
+
+namespace flexco {
+
+namespace {
+
+template <int RT>   // rank tiles of 16
+__global__ __launch_bounds__(256) void lora_shrink_kernel(LoraShrinkArgs a) {
+  __shared__ float red[4][RT][64][4];
+  const int z = blockIdx.z, tile = blockIdx.x, ks = blockIdx.y;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int m = lane & 15, g = lane >> 4;
+  const bf16_t* X = a.X[z];
+  const bf16_t* S = a.S[z];
+  const int row = tile * 16 + m;
+  const int rclamp = row < a.n ? row : 0;
+  const size_t src_row = a.row_idx ? (size_t)a.row_idx[rclamp] : (size_t)rclamp;
+  const int k_blk = a.K / a.KS, k_wave = k_blk / 4;
+  const int k0 = ks * k_blk + wave * k_wave, k1 = k0 + k_wave;
+  const bf16_t* xp = X + src_row * a.ldx[z] + g * 8;
+  const bf16_t* sp[RT];
+  bool rank_ok[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    rank_ok[rt] = rt * 16 + m < a.r;
+    sp[rt] = S + (size_t)(rank_ok[rt] ? rt * 16 + m : 0) * a.lds[z] + g * 8;
+  }
+  f32x4 acc[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) acc[rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll 4
+  for (int k = k0; k < k1; k += 32) {
+    const bf16x8 xa = *reinterpret_cast<const bf16x8*>(xp + k);
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      bf16x8 sb = *reinterpret_cast<const bf16x8*>(sp[rt] + k);
+      if (!rank_ok[rt]) sb = zero;
+      acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa, sb, acc[rt], 0, 0, 0);
+    }
+  }
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) red[wave][rt][lane][e] = acc[rt][e];
+  __syncthreads();
+  // D[row = 4 (lane / 16) + e][rank = lane % 16]; one (lane, e) pair per thread and rank tile
+  const int ln = threadIdx.x >> 2, e = threadIdx.x & 3;
+  const int orow = tile * 16 + 4 * (ln >> 4) + e;
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    const int rank = rt * 16 + (ln & 15);
+    const float v = red[0][rt][ln][e] + red[1][rt][ln][e] + red[2][rt][ln][e] + red[3][rt][ln][e];
+    if (orow < a.n && rank < a.r) a.part[z][((size_t)ks * a.n + orow) * a.r + rank] = v;
+  }
+}
+
+// sums the K-split partials in split order; writes the float result and/or the scaled bf16 matrix
+// the GEMM extension reads.  With ext_map (forward): one thread per (token, rank), tokens without
+// adapter get zeros.
+__global__ __launch_bounds__(256) void lora_finalize_kernel(LoraFinalizeArgs a) {
+  const int z = blockIdx.z;
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const int rows = a.ext_map ? a.ext_rows : a.n;
+  if (idx >= (size_t)rows * a.r) return;
+  const int row = (int)(idx / a.r), rank = (int)(idx % a.r);
+  const int src = a.ext_map ? a.ext_map[row] : row;
+  float v = 0.f;
+  if (src >= 0)
+    for (int ks = 0; ks < a.KS; ++ks) v += a.part[z][((size_t)ks * a.n + src) * a.r + rank];
+  if (a.out_f32[z] && src >= 0) a.out_f32[z][(size_t)src * a.r + rank] = v;
+  if (a.out_ext[z]) a.out_ext[z][idx] = (bf16_t)(v * a.scale);
+}
+
+// Bt[j][o] = B[o][j]
+__global__ __launch_bounds__(256) void lora_transpose_kernel(LoraTransposeArgs a) {
+  const int z = blockIdx.z;
+  const int o = blockIdx.x * 256 + threadIdx.x;
+  if (o >= a.out[z]) return;
+  for (int j = 0; j < a.r; ++j) a.Bt[z][(size_t)j * a.out[z] + o] = a.B[z][(size_t)o * a.r + j];
+}
+
+// G(i, j) += scale * sum_m X[m, i] U[m, j],  G element (i, j) at G[i * g_i + j * g_j]
+template <int R>
+__global__ __launch_bounds__(256) void lora_outer_mfma_path_kernel(const bf16_t* __restrict__ X, size_t ldx,
+                                                                   const float* __restrict__ U, float* __restrict__ G,
+                                                                   size_t g_i, size_t g_j, int n, int n_long, int r,
+                                                                   float scale) {
+  extern __shared__ float red[];   // [3][64][R] (wavefronts 1..3)
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int i = blockIdx.x * 64 + lane;
+  const int ic = i < n_long ? i : n_long - 1;
+  float acc[R];
+#pragma unroll
+  for (int j = 0; j < R; ++j) acc[j] = 0.f;
+  for (int m = wave; m < n; m += 4) {
+    const float xv = (float)X[(size_t)m * ldx + ic];
+    const float* u = U + (size_t)m * r;      // wave-uniform address: scalar loads
+#pragma unroll
+    for (int j = 0; j < R; ++j)
+      if (j < r) acc[j] += xv * u[j];
+  }
+  if (wave > 0) {
+#pragma unroll
+    for (int j = 0; j < R; ++j) red[((wave - 1) * 64 + lane) * R + j] = acc[j];
+  }
+  __syncthreads();
+  if (wave == 0 && i < n_long) {
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+      if (j < r) {
+        const float v = acc[j] + red[(0 * 64 + lane) * R + j] + red[(1 * 64 + lane) * R + j] + red[(2 * 64 + lane) * R + j];
+        G[(size_t)i * g_i + (size_t)j * g_j] += scale * v;
+      }
+    }
+  }
+}
+
+int32_t post(const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(FLEXCO_EHIP, "launch of %s failed: %s", what, hipGetErrorString(e));
+  return FLEXCO_OK;
+}
+
+}  // namespace
+
+int lora_shrink_splits(int n_rows, int K) {
+  // K / KS must be a multiple of 128 (32 per MFMA step x 4 wavefronts); aim at >= 256 blocks
+  const int units = K / 128;
+  const int tiles = (n_rows + 15) / 16;
+  int best = 1;
+  for (int ks = 1; ks <= units && ks <= 32; ++ks)
+    if (units % ks == 0) {
+      best = ks;
+      if (tiles * ks >= 256) break;
+    }
+  return best;
+}
+
+int32_t launch_lora_shrink_mfma(const LoraShrinkArgs& a, int n_mats, hipStream_t s) {
+  if (a.n == 0 || n_mats == 0) return FLEXCO_OK;
+  const dim3 grid((a.n + 15) / 16, a.KS, n_mats);
+  const int rt = (a.r + 15) / 16;
+  switch (rt) {
+    case 1: hipLaunchKernelGGL(lora_shrink_kernel<1>, grid, dim3(256), 0, s, a); break;
+    case 2: hipLaunchKernelGGL(lora_shrink_kernel<2>, grid, dim3(256), 0, s, a); break;
+    case 3: hipLaunchKernelGGL(lora_shrink_kernel<3>, grid, dim3(256), 0, s, a); break;
+    default: hipLaunchKernelGGL(lora_shrink_kernel<4>, grid, dim3(256), 0, s, a); break;
+  }
+  return post("lora_shrink");
+}
+
+int32_t launch_lora_finalize(const LoraFinalizeArgs& a, int n_mats, hipStream_t s) {
+  const int rows = a.ext_map ? a.ext_rows : a.n;
+  if (rows == 0 || n_mats == 0) return FLEXCO_OK;
+  const size_t total = (size_t)rows * a.r;
+  hipLaunchKernelGGL(lora_finalize_kernel, dim3((unsigned)((total + 255) / 256), 1, n_mats), dim3(256), 0, s, a);
+  return post("lora_finalize");
+}
+
+int32_t launch_lora_transpose(const LoraTransposeArgs& a, int n_mats, hipStream_t s) {
+  int mx = 0;
+  for (int z = 0; z < n_mats; ++z) mx = a.out[z] > mx ? a.out[z] : mx;
+  if (mx == 0) return FLEXCO_OK;
+  hipLaunchKernelGGL(lora_transpose_kernel, dim3((mx + 255) / 256, 1, n_mats), dim3(256), 0, s, a);
+  return post("lora_transpose");
+}
+
+int32_t launch_lora_outer_bf16(const void* X, size_t ldx, const float* U, float* G, size_t g_i, size_t g_j, int n,
+                               int n_long, int r, float scale, hipStream_t s) {
+  if (n == 0) return FLEXCO_OK;
+  const dim3 grid((n_long + 63) / 64);
+  const bf16_t* x = (const bf16_t*)X;
+  if (r <= 16)
+    hipLaunchKernelGGL(lora_outer_mfma_path_kernel<16>, grid, dim3(256), 3 * 64 * 16 * sizeof(float), s, x, ldx, U, G,
+                       g_i, g_j, n, n_long, r, scale);
+  else if (r <= 32)
+    hipLaunchKernelGGL(lora_outer_mfma_path_kernel<32>, grid, dim3(256), 3 * 64 * 32 * sizeof(float), s, x, ldx, U, G,
+                       g_i, g_j, n, n_long, r, scale);
+  else
+    hipLaunchKernelGGL(lora_outer_mfma_path_kernel<64>, grid, dim3(256), 3 * 64 * 64 * sizeof(float), s, x, ldx, U, G,
+                       g_i, g_j, n, n_long, r, scale);
+  return post("lora_outer");
+}
+
+}  // namespace flexco
