@@ -203,10 +203,4 @@ int32_t launch_attention_mfma(const flexco_layer_cfg& c, const flexco_maps& m, c
   return FLEXCO_OK;
 }
 
-int32_t launch_attention_bwd_mfma(const flexco_layer_cfg&, const flexco_kv_pool&, const int32_t*, int, int,
-                                  const void*, const float*, const float*, const void*, void*, float*, float*,
-                                  hipStream_t) {
-  return FLEXCO_EUNSUPPORTED;
-}
-
 }  // namespace flexco
