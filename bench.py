@@ -7,11 +7,12 @@ uniform in 512..4096, two prefill chunks of 256, the last 256-token window of a 
 finetune sequence) followed by flexco_lora_bwd of that finetune window.  Inputs are resident
 in HBM before the timed region.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--calib-copy]
 """
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -20,8 +21,13 @@ sys.path.insert(0, ROOT)
 
 import numpy as np  # noqa: E402
 
-HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16
+KERNEL_NAMES = {"gemm_fwd": "gemm_bf16_kernel<BM,BN,false> (forward projections)",
+                "gemm_bwd": "gemm_bf16_kernel<128,128,true> (input-gradient projections)",
+                "attn_fwd": "attn_fwd_mfma_kernel", "attn_merge": "attn_merge_kernel",
+                "attn_bwd": "attn_delta + attn_bwd_dq_mfma + attn_bwd_dkv_mfma", "elemwise": "norm/rope/swiglu/copy kernels",
+                "lora": "lora_shrink/finalize/transpose/outer kernels", "generic": "type-generic fallbacks"}
 
 
 def log(*a):
@@ -37,7 +43,9 @@ def main():
                     help="independent copies of the layer weights cycled between steps, so that the "
                          "436 MB weight set is never served from the 256 MB last-level cache")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-decode", type=int, default=16)
+    ap.add_argument("--cpu-sample-decode", type=int, default=32)
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--seed", type=int, default=0)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -59,8 +67,8 @@ def main():
     lora = gen.lora_weights(cfg, seed, 0)
     layers = [HH.DeviceLayer(cfg, W, lora) for _ in range(max(1, args.weight_copies))]
     pool = HH.DevicePool(cfg, batch.num_pages)
-    # cached prefixes: N(0,1) values for every page (device generator), then the sampled sequences the
-    # CPU baseline also reads are overwritten with the host generator's rows
+    # cached prefixes: N(0,1) values in every page (device generator); the sampled sequences the CPU
+    # baseline also reads are overwritten with the host generator's rows
     pool.fill_random(seed)
     ft_req = [r for r in batch.requests if r.kind == 2][0]
     L = batch.seq_capacity[ft_req.seq_id]
@@ -84,6 +92,13 @@ def main():
     log("setup %.1fs: T=%d (ft %d), requests=%d, pages=%d, attention items=%d" %
         (time.time() - t_setup, T, n_ft, hm.n_req, batch.num_pages, hm.n_items))
 
+    if args.calib_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     def step(i):
         ly = layers[i % len(layers)]
         B.flexco_layer_forward(ly.c, ly.w, ly.lora, db.maps, x, y, pool.c, ft.c, ws.ptr, ws.bytes)
@@ -94,21 +109,21 @@ def main():
         step(i)
     torch.cuda.synchronize()
 
-    # ---- which kernel class dominates?  a short pass with every class timed --------------------
+    # ---- which kernel class dominates?  a short pass with every class bracketed by events -------
     probe_steps = 3
     for name, kid in B.KERNEL_IDS.items():
         B.flexco_kernel_timer_start(kid, 64 * probe_steps)
     for i in range(probe_steps):
         step(i)
     torch.cuda.synchronize()
-    breakdown = {}
+    probe = {}
     for name, kid in B.KERNEL_IDS.items():
         ms, n = B.flexco_kernel_timer_stop(kid)
-        breakdown[name] = {"ms_per_step": ms / probe_steps, "launches_per_step": n / probe_steps}
-    dominant = max(breakdown, key=lambda k: breakdown[k]["ms_per_step"])
-    log("per-step kernel classes (ms): " + ", ".join("%s=%.3f" % (k, v["ms_per_step"]) for k, v in breakdown.items()))
+        probe[name] = (ms / probe_steps, n / probe_steps)
+    dominant = max(probe, key=lambda k: probe[k][0])
+    log("per-step kernel classes (ms): " + ", ".join("%s=%.3f" % (k, v[0]) for k, v in probe.items()))
 
-    # ---- the timed region: K steps, with the dominant class bracketed by events -----------------
+    # ---- the timed region: K steps, the dominant class bracketed by events ---------------------
     B.flexco_kernel_timer_start(B.KERNEL_IDS[dominant], 64 * args.steps)
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
@@ -124,7 +139,14 @@ def main():
     ms_per_step = max(wall_ms, gpu_ms) / args.steps
     value = T / (ms_per_step * 1e-3)
 
-    roofline = roofline_for(dominant, dom_ms, dom_launches, args.steps, cfg, batch, hm)
+    work = algorithmic_work(cfg, batch, hm)
+    roofline = roofline_entry(dominant, dom_ms / max(1, dom_launches), dom_launches / args.steps, work)
+    classes = {}
+    for name, (ms, n) in probe.items():
+        if n > 0:
+            e = roofline_entry(name, ms / n, n, work)
+            classes[name] = {"ms_per_step": round(ms, 4), "launches_per_step": n, "achieved": e["achieved"],
+                             "unit": e["unit"], "frac": e["frac"], "bound": e["bound"]}
     out = {
         "metric": "co-served tokens/s per layer iteration",
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -137,7 +159,7 @@ def main():
                    "cached_positions": int(sum(r.start_pos + r.n_new for r in batch.requests)),
                    "weight_copies_cycled": len(layers)},
         "roofline": roofline,
-        "kernel_classes_ms_per_step": {k: round(v["ms_per_step"], 4) for k, v in breakdown.items()},
+        "kernel_classes": classes,
         "gpu_event_ms_per_step": gpu_ms / args.steps,
     }
     if not args.no_cpu_baseline:
@@ -145,52 +167,59 @@ def main():
     print(json.dumps(out), flush=True)
 
 
-def roofline_for(dominant, dom_ms, dom_launches, steps, cfg, batch, hm):
-    """Algorithmic work of the dominant kernel class per launch / its measured mean duration."""
+def algorithmic_work(cfg, batch, hm):
+    """Algorithmic flops / bytes per STEP of each kernel class (what the method must do)."""
     H, F = cfg.hidden, cfg.ffn
     qd, kd = cfg.q_dim, cfg.kv_dim
     T, n_ft = hm.T, hm.n_ft
-    avg_ms = dom_ms / max(1, dom_launches)
-    if dominant == "attn_fwd":
-        # every cached position visible to a token group is read once per kv head: K row + V row, bf16.
-        # decode: contexts; chunks: each tile of tile_tokens tokens reads [0, last position of the tile]
-        bytes_ = 0
-        for r in batch.requests:
-            if r.kind == 0:
-                bytes_ += (r.start_pos + 1) * 2 * kd * 2
-        decode_bytes = bytes_
-        # prefill / finetune tiles re-read their prefix per tile: algorithmic minimum is once per request
-        for r in batch.requests:
-            if r.kind != 0:
-                bytes_ += (r.start_pos + r.n_new) * 2 * kd * 2
-        per_launch = bytes_
-        ach = per_launch / (avg_ms * 1e-3) / 1e9
-        return {"kernel": "attn_fwd_mfma_kernel", "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": ach / HBM_PEAK_GBS, "traffic": None, "avg_launch_ms": avg_ms,
-                "algorithmic_bytes_per_launch": per_launch, "decode_kv_bytes": decode_bytes,
-                "launches_per_step": dom_launches / steps}
-    if dominant in ("gemm_fwd", "gemm_bwd"):
-        p_base = (qd + 2 * kd) * H + qd * H + 3 * H * F
-        rows = T if dominant == "gemm_fwd" else n_ft
-        flops_step = 2.0 * p_base * rows
-        per_launch = flops_step * steps / max(1, dom_launches)
-        ach = per_launch / (avg_ms * 1e-3) / 1e12
-        return {"kernel": "gemm_bf16_kernel (%s)" % dominant, "bound": "mfma", "achieved": ach,
-                "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
-                "avg_launch_ms": avg_ms, "algorithmic_flops_per_launch": per_launch,
-                "launches_per_step": dom_launches / steps}
-    if dominant == "attn_bwd":
-        l = max(r.start_pos + r.n_new for r in batch.requests if r.kind == 2)
-        s = n_ft
-        # 5 products of [s x l(avg visible)] x d per head, causal inside the window
+    p_base = (qd + 2 * kd) * H + qd * H + 3 * H * F
+    # attention forward: every cached position a request sees is read once, K row + V row of every kv head
+    kv_bytes = sum((r.start_pos + r.n_new) * 2 * kd * 2 for r in batch.requests)
+    ftr = [r for r in batch.requests if r.kind == 2]
+    bwd_flops = 0.0
+    for r in ftr:
+        s, l = r.n_new, r.start_pos + r.n_new
         vis = s * (l - s) + s * (s + 1) / 2
-        flops = 10.0 * cfg.n_q_heads * cfg.head_dim * vis
-        ach = flops / (avg_ms * 1e-3) / 1e12
-        return {"kernel": "attention window backward", "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "avg_launch_ms": avg_ms,
-                "algorithmic_flops_per_launch": flops, "launches_per_step": dom_launches / steps}
-    return {"kernel": dominant, "bound": "hbm", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None,
-            "traffic": None, "avg_launch_ms": avg_ms, "launches_per_step": dom_launches / steps}
+        bwd_flops += 10.0 * cfg.n_q_heads * cfg.head_dim * vis
+    return {
+        "gemm_fwd": ("mfma", 2.0 * p_base * T),
+        "gemm_bwd": ("mfma", 2.0 * p_base * n_ft),
+        "attn_fwd": ("hbm", float(kv_bytes)),
+        "attn_bwd": ("mfma", bwd_flops),
+        "weights_bytes": 2.0 * p_base,
+    }
+
+
+def measured_traffic(kernel_class):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", "traffic_%s_c2.txt" % kernel_class)
+    if not os.path.exists(path):
+        return None
+    m = re.search(r"hbm_bytes_per_launch\s*=\s*([0-9.eE+]+)", open(path).read())
+    return float(m.group(1)) if m else None
+
+
+def roofline_entry(name, avg_launch_ms, launches_per_step, work):
+    kind, per_step = work.get(name, ("hbm", None))
+    base = {"kernel": KERNEL_NAMES.get(name, name), "class": name, "avg_launch_ms": avg_launch_ms,
+            "launches_per_step": launches_per_step, "traffic": measured_traffic(name)}
+    if per_step is None or launches_per_step == 0:
+        base.update({"bound": "hbm", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None})
+        return base
+    per_launch = per_step / launches_per_step
+    if kind == "mfma":
+        ach = per_launch / (avg_launch_ms * 1e-3) / 1e12
+        base.update({"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": ach / MFMA_BF16_PEAK_TFLOPS, "algorithmic_flops_per_launch": per_launch})
+        if name == "gemm_bwd":   # below the ridge the weight stream bounds it: report that too
+            gbs = work["weights_bytes"] / launches_per_step / (avg_launch_ms * 1e-3) / 1e9
+            base["weight_stream_GBs"] = gbs
+            base["weight_stream_frac_of_hbm"] = gbs / HBM_PEAK_GBS
+    else:
+        ach = per_launch / (avg_launch_ms * 1e-3) / 1e9
+        base.update({"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+                     "algorithmic_bytes_per_launch": per_launch})
+    return base
 
 
 def cpu_baseline(cfg, batch, sample, W, lora, seed, x_np, ft_req, L):
@@ -212,19 +241,24 @@ def cpu_baseline(cfg, batch, sample, W, lora, seed, x_np, ft_req, L):
     st = {ft_req.seq_id: OL.FtState(cfg, L)}
     threads = sum(p.get("num_threads", 0) for p in threadpoolctl.threadpool_info() if p.get("user_api") == "blas") or os.cpu_count()
     log("cpu baseline: oracle on %d sampled tokens (%d requests), %d BLAS threads" % (len(rows), len(sample), threads))
-    t0 = time.perf_counter()
-    OL.layer_forward_mixed(cfg, W, lora, om, x_np[rows], pool, st)
-    t_f = time.perf_counter() - t0
     dY = gen.layer_input(cfg, seed, ft_req.n_new, tag="dy")
     sl = pool.slots(batch.seq_pages[ft_req.seq_id], L)
-    t0 = time.perf_counter()
-    OL.layer_backward_window(cfg, W, lora, st[ft_req.seq_id], pool.k[sl].astype(np.float64), pool.v[sl].astype(np.float64),
-                             ft_req.start_pos, ft_req.n_new, dY, {})
-    t_b = time.perf_counter() - t0
-    log("cpu baseline: forward %.1fs, backward %.1fs, total incl. setup %.1fs" % (t_f, t_b, time.time() - t_all))
-    return {"value": len(rows) / (t_f + t_b), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": "%d of 1024 tokens: %d decode requests, one 256-token prefill chunk, the 256-token finetune "
-                      "window (forward) + that window's backward; numpy fp64" % (len(rows), len(sample) - 2),
+    # repeat the sample until about 10 s of oracle time have been spent (at most 6 passes)
+    t_f = t_b = 0.0
+    reps = 0
+    while reps < 6 and (t_f + t_b) < 10.0:
+        t0 = time.perf_counter()
+        OL.layer_forward_mixed(cfg, W, lora, om, x_np[rows], pool, st)
+        t_f += time.perf_counter() - t0
+        t0 = time.perf_counter()
+        OL.layer_backward_window(cfg, W, lora, st[ft_req.seq_id], pool.k[sl].astype(np.float64),
+                                 pool.v[sl].astype(np.float64), ft_req.start_pos, ft_req.n_new, dY, {})
+        t_b += time.perf_counter() - t0
+        reps += 1
+    log("cpu baseline: %d passes, forward %.1fs, backward %.1fs, total incl. setup %.1fs" % (reps, t_f, t_b, time.time() - t_all))
+    return {"value": reps * len(rows) / (t_f + t_b), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": "%d of 1024 tokens (%d decode requests, one 256-token prefill chunk, the 256-token finetune "
+                      "window): forward + that window's backward, %d passes; numpy fp64" % (len(rows), len(sample) - 2, reps),
             "seconds": t_f + t_b, "host_cpus": os.cpu_count()}
 
 

@@ -110,18 +110,19 @@ __global__ __launch_bounds__(256) void lora_outer_mfma_path_kernel(const bf16_t*
   float acc[R];
 #pragma unroll
   for (int j = 0; j < R; ++j) acc[j] = 0.f;
-  // each wavefront takes 8 consecutive rows per round; the 8 loads are issued together so that
-  // their latency overlaps (one dependent load per row made this kernel latency-bound)
-  for (int m0 = wave * 8; m0 < n; m0 += 32) {
-    float xv[8];
+  // each wavefront takes RB consecutive rows per round; their loads are issued together so that
+  // the latencies overlap (one dependent load per row made this kernel latency-bound)
+  constexpr int RB = 32;
+  for (int m0 = wave * RB; m0 < n; m0 += 4 * RB) {
+    float xv[RB];
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
+    for (int q = 0; q < RB; ++q) {
       const int m = m0 + q < n ? m0 + q : n - 1;
       xv[q] = (float)X[(size_t)m * ldx + ic];
       if (m0 + q >= n) xv[q] = 0.f;
     }
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
+    for (int q = 0; q < RB; ++q) {
       const int m = m0 + q < n ? m0 + q : n - 1;
       const float* u = U + (size_t)m * r;      // wave-uniform address: scalar loads
 #pragma unroll
