@@ -97,49 +97,52 @@ __global__ __launch_bounds__(256) void lora_transpose_kernel(LoraTransposeArgs a
 }
 
 // G(i, j) += scale * sum_m X[m, i] U[m, j],  G element (i, j) at G[i * g_i + j * g_j]
+// Rows are taken in chunks of 128: the chunk's U rows are staged in LDS (broadcast reads), each
+// wavefront owns 32 rows of the chunk and issues their 32 loads of X together.
 template <int R>
 __global__ __launch_bounds__(256) void lora_outer_mfma_path_kernel(const bf16_t* __restrict__ X, size_t ldx,
                                                                    const float* __restrict__ U, float* __restrict__ G,
                                                                    size_t g_i, size_t g_j, int n, int n_long, int r,
                                                                    float scale) {
-  extern __shared__ float red[];   // [3][64][R] (wavefronts 1..3)
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  extern __shared__ float smem[];   // us[128][R], later reused as red[3][64][R]
+  constexpr int CH = 128, RB = 32;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int i = blockIdx.x * 64 + lane;
   const int ic = i < n_long ? i : n_long - 1;
   float acc[R];
 #pragma unroll
   for (int j = 0; j < R; ++j) acc[j] = 0.f;
-  // each wavefront takes RB consecutive rows per round; their loads are issued together so that
-  // the latencies overlap (one dependent load per row made this kernel latency-bound)
-  constexpr int RB = 32;
-  for (int m0 = wave * RB; m0 < n; m0 += 4 * RB) {
+  for (int mb = 0; mb < n; mb += CH) {
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < CH * R; idx += 256) {
+      const int mm = idx / R, j = idx % R;
+      smem[idx] = (mb + mm < n && j < r) ? U[(size_t)(mb + mm) * r + j] : 0.f;
+    }
+    __syncthreads();
     float xv[RB];
 #pragma unroll
     for (int q = 0; q < RB; ++q) {
-      const int m = m0 + q < n ? m0 + q : n - 1;
-      xv[q] = (float)X[(size_t)m * ldx + ic];
-      if (m0 + q >= n) xv[q] = 0.f;
+      const int m = mb + wave * RB + q;
+      xv[q] = (float)X[(size_t)(m < n ? m : n - 1) * ldx + ic];   // rows past n meet zero U rows
     }
 #pragma unroll
     for (int q = 0; q < RB; ++q) {
-      const int m = m0 + q < n ? m0 + q : n - 1;
-      const float* u = U + (size_t)m * r;      // wave-uniform address: scalar loads
+      const float* u = smem + (wave * RB + q) * R;
 #pragma unroll
-      for (int j = 0; j < R; ++j)
-        if (j < r) acc[j] += xv[q] * u[j];
+      for (int j = 0; j < R; ++j) acc[j] += xv[q] * u[j];
     }
   }
+  __syncthreads();
   if (wave > 0) {
 #pragma unroll
-    for (int j = 0; j < R; ++j) red[((wave - 1) * 64 + lane) * R + j] = acc[j];
+    for (int j = 0; j < R; ++j) smem[((wave - 1) * 64 + lane) * R + j] = acc[j];
   }
   __syncthreads();
   if (wave == 0 && i < n_long) {
 #pragma unroll
     for (int j = 0; j < R; ++j) {
       if (j < r) {
-        const float v = acc[j] + red[(0 * 64 + lane) * R + j] + red[(1 * 64 + lane) * R + j] + red[(2 * 64 + lane) * R + j];
+        const float v = acc[j] + smem[(0 * 64 + lane) * R + j] + smem[(1 * 64 + lane) * R + j] + smem[(2 * 64 + lane) * R + j];
         G[(size_t)i * g_i + (size_t)j * g_j] += scale * v;
       }
     }
@@ -202,13 +205,13 @@ int32_t launch_lora_outer_bf16(const void* X, size_t ldx, const float* U, float*
   const dim3 grid((n_long + 63) / 64);
   const bf16_t* x = (const bf16_t*)X;
   if (r <= 16)
-    hipLaunchKernelGGL(lora_outer_mfma_path_kernel<16>, grid, dim3(256), 3 * 64 * 16 * sizeof(float), s, x, ldx, U, G,
+    hipLaunchKernelGGL(lora_outer_mfma_path_kernel<16>, grid, dim3(256), 192 * 16 * sizeof(float), s, x, ldx, U, G,
                        g_i, g_j, n, n_long, r, scale);
   else if (r <= 32)
-    hipLaunchKernelGGL(lora_outer_mfma_path_kernel<32>, grid, dim3(256), 3 * 64 * 32 * sizeof(float), s, x, ldx, U, G,
+    hipLaunchKernelGGL(lora_outer_mfma_path_kernel<32>, grid, dim3(256), 192 * 32 * sizeof(float), s, x, ldx, U, G,
                        g_i, g_j, n, n_long, r, scale);
   else
-    hipLaunchKernelGGL(lora_outer_mfma_path_kernel<64>, grid, dim3(256), 3 * 64 * 64 * sizeof(float), s, x, ldx, U, G,
+    hipLaunchKernelGGL(lora_outer_mfma_path_kernel<64>, grid, dim3(256), 192 * 64 * sizeof(float), s, x, ldx, U, G,
                        g_i, g_j, n, n_long, r, scale);
   return post("lora_outer");
 }
