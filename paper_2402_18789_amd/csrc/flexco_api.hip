@@ -77,6 +77,7 @@ extern "C" int32_t flexco_kernel_timer_stop(int32_t kernel_id, double* total_ms,
 namespace {
 
 constexpr int KS_MAX = 32;   // largest K split of the LoRA shrink kernel
+constexpr size_t SPLITK_COLS = 32768;   // split-K scratch of the backward GEMMs: rows x this many floats
 
 struct Carver {
   char* base;
@@ -116,6 +117,8 @@ struct FwdWs {
 struct BwdWs {
   void *hn, *act, *dact, *dgu, *dh, *dx2, *dattn, *dq, *dqkv;
   float *delta, *u, *t;
+  float* gemm_part;        // split-K partial sums of the input-gradient GEMMs
+  size_t gemm_part_elems;
   LoraWs lw;
   size_t bytes;
 };
@@ -164,6 +167,8 @@ BwdWs carve_bwd(const flexco_layer_cfg& c, int n, void* base) {
   const int r = c.lora_rank > 0 ? c.lora_rank : 1;
   w.u = (float*)cv.take(sizeof(float) * n * r);
   w.t = (float*)cv.take(sizeof(float) * n * r);
+  w.gemm_part_elems = c.dtype == FLEXCO_BF16 ? (size_t)n * SPLITK_COLS : 0;
+  w.gemm_part = (float*)cv.take(sizeof(float) * w.gemm_part_elems);
   carve_lora(c, n, cv, w.lw);
   w.bytes = cv.off;
   return w;
@@ -366,7 +371,8 @@ int32_t backward_projection(const flexco_layer_cfg& c, const flexco_lora* lora, 
       LR(launch_lora_finalize(ft, 1, s));
     }
     if (dx) {
-      int32_t rc = launch_gemm(dy, W, dx, nullptr, nullptr, n, N_dx, K_dy, K_dy, N_dx, N_dx, 0, true, dt, s, &ext);
+      int32_t rc = launch_gemm(dy, W, dx, nullptr, nullptr, n, N_dx, K_dy, K_dy, N_dx, N_dx, 0, true, dt, s, &ext,
+                               k.gemm_part, k.gemm_part_elems);
       if (rc) return rc;
     }
     for (int z = 0; z < nact; ++z) {
@@ -379,7 +385,8 @@ int32_t backward_projection(const flexco_layer_cfg& c, const flexco_lora* lora, 
     }
     return FLEXCO_OK;
   }
-  if (dx) FLEXCO_TRY(launch_gemm(dy, W, dx, nullptr, nullptr, n, N_dx, K_dy, K_dy, N_dx, N_dx, 0, true, dt, s));
+  if (dx) FLEXCO_TRY(launch_gemm(dy, W, dx, nullptr, nullptr, n, N_dx, K_dy, K_dy, N_dx, N_dx, 0, true, dt, s, nullptr,
+                                 k.gemm_part, k.gemm_part_elems));
   for (int z = 0; z < nact; ++z) {
     const int t = targets[act[z]];
     int in, out;
@@ -413,13 +420,13 @@ int32_t run_attention(const flexco_layer_cfg& c, const flexco_maps& m, const voi
 namespace flexco {
 int32_t launch_gemm(const void* A, const void* W, void* C, const void* bias, const void* residual, int M, int N,
                     int K, size_t lda, size_t ldw, size_t ldc, size_t ldr, bool trans_w, int dtype, hipStream_t s,
-                    const GemmExt* ext) {
+                    const GemmExt* ext, float* part, size_t part_elems) {
   if (M == 0) return FLEXCO_OK;
   if (dtype == FLEXCO_BF16) {
     int32_t rc;
     {
       KernelTimerScope ts(trans_w ? FLEXCO_K_GEMM_BWD : FLEXCO_K_GEMM_FWD, s);
-      rc = launch_gemm_mfma(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, trans_w, ext, s);
+      rc = launch_gemm_mfma(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, trans_w, ext, s, part, part_elems);
     }
     if (rc != FLEXCO_EUNSUPPORTED) return rc;
     clear_error();

@@ -56,16 +56,17 @@ struct KernelTimerScope {
 
 // ---- launchers: no validation, the entry points have done it -------------------------
 // C[M,N] = A[M,K] W[N,K]^T (+bias) (+residual);  trans_w: W is [K,N].  Leading dimensions in elements.
+// part / part_elems: optional fp32 scratch for split-K partial sums (input-gradient form)
 int32_t launch_gemm(const void* A, const void* W, void* C, const void* bias, const void* residual, int M, int N,
                     int K, size_t lda, size_t ldw, size_t ldc, size_t ldr, bool trans_w, int dtype, hipStream_t s,
-                    const GemmExt* ext = nullptr);
+                    const GemmExt* ext = nullptr, float* part = nullptr, size_t part_elems = 0);
 int32_t launch_gemm_generic(const void* A, const void* W, void* C, const void* bias, const void* residual, int M,
                             int N, int K, size_t lda, size_t ldw, size_t ldc, size_t ldr, bool trans_w, int dtype,
                             hipStream_t s);
 // bf16 MFMA path; returns FLEXCO_EUNSUPPORTED (without launching) for shapes it does not cover
 int32_t launch_gemm_mfma(const void* A, const void* W, void* C, const void* bias, const void* residual, int M,
                          int N, int K, size_t lda, size_t ldw, size_t ldc, size_t ldr, bool trans_w,
-                         const GemmExt* ext, hipStream_t s);
+                         const GemmExt* ext, hipStream_t s, float* part = nullptr, size_t part_elems = 0);
 int lora_shrink_splits(int n_rows, int K);
 int32_t launch_lora_shrink_mfma(const LoraShrinkArgs& a, int n_mats, hipStream_t s);
 int32_t launch_lora_finalize(const LoraFinalizeArgs& a, int n_mats, hipStream_t s);

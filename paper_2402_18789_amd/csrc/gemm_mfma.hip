@@ -46,7 +46,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
                                                         bf16_t* __restrict__ C, const bf16_t* __restrict__ bias,
                                                         const bf16_t* __restrict__ res, int M, int N, int K,
                                                         size_t lda, size_t ldw, size_t ldc, size_t ldr, int tiles_m,
-                                                        int tiles_n, GemmExt ext) {
+                                                        int tiles_n, GemmExt ext, float* __restrict__ part,
+                                                        int k_chunk) {
   constexpr int WM = BM / 2, WN = BN / 2, MT = WM / 32, NT = WN / 32;
   using S = Smem<BM, BN, TRANS>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -121,19 +122,21 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int nk = K / BK;
+  // split-K: blockIdx.y owns k in [kbeg, kbeg + k_chunk) and writes fp32 partial sums to `part`
+  const int kbeg = blockIdx.y * k_chunk;
+  const int nk = k_chunk / BK;
   const int l32 = lane & 31, kg = lane >> 5;
   // Software pipeline: the registers loaded during step kt are written to LDS at the top of
   // step kt + 1, so their global-memory latency hides behind the MFMAs of step kt.  One
   // barrier per step is enough with two LDS buffers: a wavefront that reaches the store of
   // step kt + 1 has passed the barrier of step kt, which every wavefront reaches only after
   // it finished reading the other buffer in step kt - 1.
-  FLEXCO_LOAD_TILES(0)
+  FLEXCO_LOAD_TILES(kbeg)
   for (int kt = 0; kt < nk; ++kt) {
     const int buf = kt & 1;
     FLEXCO_STORE_TILES(buf)
     __syncthreads();
-    const int k_next = min(kt + 1, nk - 1) * BK;   // the last step re-reads its own tile (unused)
+    const int k_next = kbeg + min(kt + 1, nk - 1) * BK;   // the last step re-reads its own tile (unused)
     FLEXCO_LOAD_TILES(k_next)
     __builtin_amdgcn_sched_barrier(0);
     const bf16_t* as = As + buf * S::A_ELEMS;
@@ -170,7 +173,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
   // block) or C += sum_e A2_e W2_e (input-gradient form; every entry).  This is the LoRA bypass
   // network (Sec. 4.1) folded into the base projection as extra k-steps of 16, operands read
   // straight from global memory (they are [rows, r] / [r, cols] matrices of a few KB per tile).
-  for (int e = 0; e < ext.n; ++e) {
+  for (int e = 0; e < (blockIdx.y == 0 ? ext.n : 0); ++e) {
     if (!TRANS && !(n0 >= ext.col0[e] && n0 < ext.col1[e])) continue;
     const bf16_t* A2 = ext.A2[e];
     const bf16_t* W2 = ext.W2[e];
@@ -201,6 +204,22 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
   }
 
   // ---- epilogue: D[i][j], j = lane % 32, i = 8 (r / 4) + 4 (lane / 32) + r % 4 ---------------
+  if (part) {
+    float* P = part + (size_t)blockIdx.y * M * N;
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        const int col = n0 + wn0 + j * 32 + l32;
+        if (col >= N) continue;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = m0 + wm0 + i * 32 + 8 * (r >> 2) + 4 * kg + (r & 3);
+          if (row < M) P[(size_t)row * N + col] = acc[i][j][r];
+        }
+      }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < MT; ++i) {
 #pragma unroll
@@ -220,9 +239,35 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
   }
 }
 
+// C[row, col] = sum over splits of part[split][row][col] (+ bias) (+ residual), fixed order
+__global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(const float* __restrict__ part, int splits,
+                                                                 bf16_t* __restrict__ C, const bf16_t* __restrict__ bias,
+                                                                 const bf16_t* __restrict__ res, int M, int N,
+                                                                 size_t ldc, size_t ldr) {
+  const size_t idx = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (idx >= (size_t)M * N) return;
+  const int row = (int)(idx / N), col = (int)(idx % N);     // N % 8 == 0: the 4 elements share a row
+  f32x4 v = *reinterpret_cast<const f32x4*>(part + idx);
+  for (int sp = 1; sp < splits; ++sp) {
+    const f32x4 w = *reinterpret_cast<const f32x4*>(part + (size_t)sp * M * N + idx);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] += w[j];
+  }
+  bf16x4 o;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    float x = v[j];
+    if (bias) x += (float)bias[col + j];
+    if (res) x += (float)res[(size_t)row * ldr + col + j];
+    o[j] = (bf16_t)x;
+  }
+  *reinterpret_cast<bf16x4*>(C + (size_t)row * ldc + col) = o;
+}
+
 template <int BM, int BN, bool TRANS>
 int32_t launch_cfg(const void* A, const void* W, void* C, const void* bias, const void* res, int M, int N, int K,
-                   size_t lda, size_t ldw, size_t ldc, size_t ldr, const GemmExt& ext, hipStream_t s) {
+                   size_t lda, size_t ldw, size_t ldc, size_t ldr, const GemmExt& ext, hipStream_t s,
+                   float* part = nullptr, int splits = 1) {
   using S = Smem<BM, BN, TRANS>;
   auto kern = gemm_bf16_kernel<BM, BN, TRANS>;
   static bool attr_set = false;
@@ -233,8 +278,14 @@ int32_t launch_cfg(const void* A, const void* W, void* C, const void* bias, cons
     attr_set = true;
   }
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(256), S::BYTES, s, (const bf16_t*)A, (const bf16_t*)W,
-                     (bf16_t*)C, (const bf16_t*)bias, (const bf16_t*)res, M, N, K, lda, ldw, ldc, ldr, tiles_m, tiles_n, ext);
+  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n, splits), dim3(256), S::BYTES, s, (const bf16_t*)A, (const bf16_t*)W,
+                     (bf16_t*)C, (const bf16_t*)bias, (const bf16_t*)res, M, N, K, lda, ldw, ldc, ldr, tiles_m, tiles_n,
+                     ext, splits > 1 ? part : nullptr, K / splits);
+  if (splits > 1) {
+    const size_t quads = ((size_t)M * N + 3) / 4;
+    hipLaunchKernelGGL(gemm_splitk_reduce_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s, part, splits,
+                       (bf16_t*)C, (const bf16_t*)bias, (const bf16_t*)res, M, N, ldc, ldr);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(FLEXCO_EHIP, "launch of gemm_bf16 failed: %s", hipGetErrorString(e));
   return FLEXCO_OK;
@@ -251,16 +302,33 @@ static bool ext_fits(const GemmExt& ext, bool trans_w, int BN) {
   return true;
 }
 
+// Largest split count <= want that cuts K into whole 64-wide steps and fits the partial buffer.
+static int pick_splits(int M, int N, int K, int tiles, size_t part_elems) {
+  if (part_elems == 0 || tiles >= 384) return 1;
+  int best = 1;
+  for (int sp = 2; sp <= 16; ++sp) {
+    if (K % (sp * BK) != 0 || K / sp < 4 * BK) continue;
+    if ((size_t)sp * M * N > part_elems) break;
+    best = sp;
+    if (tiles * sp >= 512) break;
+  }
+  return best;
+}
+
 int32_t launch_gemm_mfma(const void* A, const void* W, void* C, const void* bias, const void* residual, int M, int N,
                          int K, size_t lda, size_t ldw, size_t ldc, size_t ldr, bool trans_w, const GemmExt* ext_in,
-                         hipStream_t s) {
+                         hipStream_t s, float* part, size_t part_elems) {
   // shapes the tiled kernel covers: K in whole 64-wide steps, 16-byte aligned rows
   if (K % BK != 0 || lda % 8 != 0 || ldw % 8 != 0 || N % 8 != 0) return FLEXCO_EUNSUPPORTED;
   GemmExt ext;
   if (ext_in) ext = *ext_in; else ext.n = 0;
   if (trans_w) {
     if (!ext_fits(ext, true, 128)) return FLEXCO_EUNSUPPORTED;
-    return launch_cfg<128, 128, true>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, ext, s);
+    // few row tiles (a finetune window) and a long contraction: cut K across blocks so that the
+    // weight stream is spread over the whole chip; partial sums are reduced in split order
+    const int tiles = ((M + 127) / 128) * ((N + 127) / 128);
+    const int sp = part ? pick_splits(M, N, K, tiles, part_elems) : 1;
+    return launch_cfg<128, 128, true>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, ext, s, part, sp);
   }
   const long big_tiles = (long)((M + 255) / 256) * ((N + 255) / 256);
   if (big_tiles >= 192 && ext_fits(ext, false, 256))
