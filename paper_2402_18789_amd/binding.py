@@ -11,7 +11,7 @@ import numpy as np
 import torch  # noqa: F401  loaded first: the library shares torch's HIP runtime (libamdhip64.so)
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libflexco.so")
+LIB_PATH = os.environ.get("FLEXCO_LIB_PATH", os.path.join(_HERE, "libflexco.so"))
 
 FLEXCO_OK, FLEXCO_EINVAL, FLEXCO_ESHAPE, FLEXCO_EWORKSPACE, FLEXCO_EPAGE, FLEXCO_EUNSUPPORTED, FLEXCO_EHIP = \
     0, -1, -2, -3, -4, -5, -6

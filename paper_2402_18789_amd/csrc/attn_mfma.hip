@@ -77,11 +77,15 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(FwdArgs a, const bf1
   bf16x8 kf[2][4];     // [page of the pair][d chunk]
   bf16x4 vf[2][8];     // [page of the pair][d tile]
 
-  auto load_pair = [&](int pp, bf16x8 (&kk)[2][4], bf16x4 (&vv)[2][8]) {
+  // page ids of the whole split, one per lane (split_pages <= 64): no dependent table load per step
+  const int npg = pe - pb;
+  const int my_page = a.block_table[(size_t)r * a.max_pages + (lane < npg ? pb + lane : pb)];
+
+  auto load_pair = [&](int rel, bf16x8 (&kk)[2][4], bf16x4 (&vv)[2][8]) {
 #pragma unroll
     for (int x = 0; x < 2; ++x) {
-      const int pidx = (pp + x < pe) ? pp + x : pp;
-      const size_t page = (size_t)bt[pidx];
+      const int pidx = (rel + x < npg) ? rel + x : rel;
+      const size_t page = (size_t)__builtin_amdgcn_readlane(my_page, pidx);
       const bf16_t* kpage = kp + ((page * a.nkv + kvh) * PS + c) * (size_t)D + g * 8;
 #pragma unroll
       for (int dc = 0; dc < 4; ++dc) kk[x][dc] = *reinterpret_cast<const bf16x8*>(kpage + dc * 32);
@@ -91,13 +95,8 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(FwdArgs a, const bf1
     }
   };
 
-  if (pb < pe) load_pair(pb, kf, vf);
-  for (int pp = pb; pp < pe; pp += 2) {
-    bf16x8 kn[2][4];
-    bf16x4 vn[2][8];
-    const bool has_next = pp + 2 < pe;
-    if (has_next) load_pair(pp + 2, kn, vn);
-
+  // one step = 32 keys (two pages) against the 16 columns, operands in (kf, vf)
+  auto step = [&](int pp, bf16x8 (&kf)[2][4], bf16x4 (&vf)[2][8]) {
     // ---- scores of 32 keys x 16 columns -------------------------------------------------
     float s[8];
 #pragma unroll
@@ -156,15 +155,20 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(FwdArgs a, const bf1
       for (int j = 0; j < 4; ++j) acc[j] *= alpha;
       o[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vfull, pf, acc, 0, 0, 0);
     }
-    if (has_next) {
-#pragma unroll
-      for (int x = 0; x < 2; ++x) {
-#pragma unroll
-        for (int dc = 0; dc < 4; ++dc) kf[x][dc] = kn[x][dc];
-#pragma unroll
-        for (int mt = 0; mt < 8; ++mt) vf[x][mt] = vn[x][mt];
-      }
-    }
+  };
+
+  // Two register sets used in turn: while one pair of pages is multiplied, the next pair is in
+  // flight into the other set.  The prefetch is unconditional (past the end it re-reads the current
+  // pair, unused), so the number of loads in flight is the same on every path and the wait before a
+  // step's MFMAs covers only loads issued one step earlier.
+  bf16x8 k1[2][4];
+  bf16x4 v1[2][8];
+  if (npg > 0) load_pair(0, kf, vf);
+  for (int rel = 0; rel < npg; rel += 4) {
+    load_pair(rel + 2 < npg ? rel + 2 : rel, k1, v1);
+    step(pb + rel, kf, vf);
+    load_pair(rel + 4 < npg ? rel + 4 : rel, kf, vf);
+    if (rel + 2 < npg) step(pb + rel + 2, k1, v1);
   }
   // ---- write the partial of this (tile, split, kv head) ----------------------------------
   l += __shfl_xor(l, 16, 64);
@@ -187,7 +191,8 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(FwdArgs a, const bf1
 int32_t launch_attention_mfma(const flexco_layer_cfg& c, const flexco_maps& m, const void* q, size_t ldq,
                               const flexco_kv_pool& pool, float* part_ml, float* part_acc, hipStream_t s) {
   const int group = c.n_q_heads / c.n_kv_heads;
-  if (c.dtype != FLEXCO_BF16 || c.head_dim != D || c.page_size != PS || group > 16 || ldq % 8 != 0)
+  if (c.dtype != FLEXCO_BF16 || c.head_dim != D || c.page_size != PS || group > 16 || ldq % 8 != 0 ||
+      m.kv_split_pages > 64)
     return FLEXCO_EUNSUPPORTED;
   FwdArgs a;
   a.tok_pos = m.tok_pos; a.block_table = m.block_table; a.tile_req = m.tile_req; a.tile_tok0 = m.tile_tok0;

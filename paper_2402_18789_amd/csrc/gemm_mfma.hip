@@ -67,13 +67,13 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
   // ---- global -> register staging --------------------------------------------------------
   constexpr int A_PASSES = BM / 32;                                  // 8 chunks per row, 32 rows per pass
   constexpr int B_PASSES = TRANS ? (BK * (BN / 8)) / 256 : BN / 32;
-  u32x4 ra[A_PASSES], rb[B_PASSES];
+  u32x4 sa0[A_PASSES], sb0[B_PASSES], sa1[A_PASSES], sb1[B_PASSES];   // two sets of staging registers
   const int a_c = tid & 7, a_r = tid >> 3;
   constexpr int BCH = BN / 8;                                        // chunks per row of the transposed W tile
   const int bt_c = tid % BCH, bt_r = tid / BCH;
 
   // (kept as macros on purpose: staging arrays captured by lambdas were left in scratch memory)
-#define FLEXCO_LOAD_TILES(k0_)                                                                        \
+#define FLEXCO_LOAD_TILES(k0_, ra, rb)                                                                      \
   {                                                                                                   \
     _Pragma("unroll") for (int p = 0; p < A_PASSES; ++p) {                                            \
       const int r_ = min(m0 + a_r + 32 * p, M - 1);                                                   \
@@ -93,7 +93,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
       }                                                                                               \
     }                                                                                                 \
   }
-#define FLEXCO_STORE_TILES(buf_)                                                                      \
+#define FLEXCO_STORE_TILES(buf_, ra, rb)                                                                    \
   {                                                                                                   \
     bf16_t* as_ = As + (buf_) * S::A_ELEMS;                                                           \
     bf16_t* bs_ = Bs + (buf_) * S::B_ELEMS;                                                           \
@@ -126,48 +126,72 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
   const int kbeg = blockIdx.y * k_chunk;
   const int nk = k_chunk / BK;
   const int l32 = lane & 31, kg = lane >> 5;
-  // Software pipeline: the registers loaded during step kt are written to LDS at the top of
-  // step kt + 1, so their global-memory latency hides behind the MFMAs of step kt.  One
-  // barrier per step is enough with two LDS buffers: a wavefront that reaches the store of
-  // step kt + 1 has passed the barrier of step kt, which every wavefront reaches only after
-  // it finished reading the other buffer in step kt - 1.
-  FLEXCO_LOAD_TILES(kbeg)
-  for (int kt = 0; kt < nk; ++kt) {
-    const int buf = kt & 1;
-    FLEXCO_STORE_TILES(buf)
-    __syncthreads();
-    const int k_next = kbeg + min(kt + 1, nk - 1) * BK;   // the last step re-reads its own tile (unused)
-    FLEXCO_LOAD_TILES(k_next)
-    __builtin_amdgcn_sched_barrier(0);
-    const bf16_t* as = As + buf * S::A_ELEMS;
-    const bf16_t* bs = Bs + buf * S::B_ELEMS;
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 af[MT], bfr[NT];
-#pragma unroll
-      for (int i = 0; i < MT; ++i) {
-        const int r = wm0 + i * 32 + l32;
-        af[i] = *reinterpret_cast<const bf16x8*>(as + r * BK + swz(r, kk * 2 + kg) * 8);
-      }
-#pragma unroll
-      for (int j = 0; j < NT; ++j) {
-        if (!TRANS) {
-          const int r = wn0 + j * 32 + l32;
-          bfr[j] = *reinterpret_cast<const bf16x8*>(bs + r * BK + swz(r, kk * 2 + kg) * 8);
-        } else {
-          const bf16_t* col = bs + (kk * 16 + kg * 8) * S::B_LD + wn0 + j * 32 + l32;
-#pragma unroll
-          for (int e = 0; e < 8; ++e) bfr[j][e] = col[e * S::B_LD];
-        }
-      }
-#pragma unroll
-      for (int i = 0; i < MT; ++i)
-#pragma unroll
-        for (int j = 0; j < NT; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
+
+#define FLEXCO_LOAD_FRAGS(kk_, af_, bf_)                                                              \
+  {                                                                                                   \
+    _Pragma("unroll") for (int i = 0; i < MT; ++i) {                                                  \
+      const int r_ = wm0 + i * 32 + l32;                                                              \
+      af_[i] = *reinterpret_cast<const bf16x8*>(as + r_ * BK + swz(r_, (kk_) * 2 + kg) * 8);          \
+    }                                                                                                 \
+    _Pragma("unroll") for (int j = 0; j < NT; ++j) {                                                  \
+      if (!TRANS) {                                                                                   \
+        const int r_ = wn0 + j * 32 + l32;                                                            \
+        bf_[j] = *reinterpret_cast<const bf16x8*>(bs + r_ * BK + swz(r_, (kk_) * 2 + kg) * 8);        \
+      } else {                                                                                        \
+        const bf16_t* col_ = bs + ((kk_) * 16 + kg * 8) * S::B_LD + wn0 + j * 32 + l32;               \
+        _Pragma("unroll") for (int e = 0; e < 8; ++e) bf_[j][e] = col_[e * S::B_LD];                  \
+      }                                                                                               \
+    }                                                                                                 \
   }
+#define FLEXCO_MFMAS(af_, bf_)                                                                        \
+  {                                                                                                   \
+    _Pragma("unroll") for (int i = 0; i < MT; ++i)                                                    \
+      _Pragma("unroll") for (int j = 0; j < NT; ++j)                                                  \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af_[i], bf_[j], acc[i][j], 0, 0, 0);      \
+  }
+
+  // Software pipeline over k-steps of 64 with two LDS buffers and two sets of staging registers,
+  // so that a tile's global loads have two whole steps to arrive:
+  //   step kt, first half : MFMAs of k-slices 0, 1 of tile kt (LDS buffer kt & 1)
+  //   step kt, middle     : the staging set that holds tile kt + 1 (loaded in the middle of step
+  //                         kt - 2) is written to the other LDS buffer and reloaded with tile kt + 3
+  //   step kt, second half: MFMAs of k-slices 2, 3 - they run while the LDS writes drain
+  //   one barrier at the end of the step: the other buffer is complete, this one is free.
+  // The other buffer was last read in step kt - 1, which every wavefront left through that
+  // step's barrier, so the mid-step writes race with nothing.  Past the last tile the indices are
+  // clamped: the extra loads and writes repeat tile nk - 1 and are never read.
+#define FLEXCO_STEP(kt_, ra_, rb_)                                                                    \
+  {                                                                                                   \
+    const int buf = (kt_) & 1;                                                                        \
+    const bf16_t* as = As + buf * S::A_ELEMS;                                                         \
+    const bf16_t* bs = Bs + buf * S::B_ELEMS;                                                         \
+    bf16x8 af[MT], bfr[NT], af2[MT], bfr2[NT];                                                        \
+    FLEXCO_LOAD_FRAGS(0, af, bfr)                                                                     \
+    FLEXCO_MFMAS(af, bfr)                                                                             \
+    FLEXCO_LOAD_FRAGS(1, af, bfr)                                                                     \
+    FLEXCO_MFMAS(af, bfr)                                                                             \
+    __builtin_amdgcn_sched_barrier(0);                                                                \
+    FLEXCO_LOAD_FRAGS(2, af2, bfr2)                                                                   \
+    FLEXCO_STORE_TILES(buf ^ 1, ra_, rb_)                                                             \
+    FLEXCO_LOAD_TILES(kbeg + min((kt_) + 3, nk - 1) * BK, ra_, rb_)                                   \
+    __builtin_amdgcn_sched_barrier(0);                                                                \
+    FLEXCO_MFMAS(af2, bfr2)                                                                           \
+    FLEXCO_LOAD_FRAGS(3, af, bfr)                                                                     \
+    FLEXCO_MFMAS(af, bfr)                                                                             \
+    __builtin_amdgcn_sched_barrier(0);                                                                \
+    __syncthreads();                                                                                  \
+  }
+  FLEXCO_LOAD_TILES(kbeg, sa0, sb0)
+  FLEXCO_STORE_TILES(0, sa0, sb0)
+  __syncthreads();
+  FLEXCO_LOAD_TILES(kbeg + min(1, nk - 1) * BK, sa0, sb0)
+  FLEXCO_LOAD_TILES(kbeg + min(2, nk - 1) * BK, sa1, sb1)
+  int kt = 0;
+  for (; kt + 1 < nk; kt += 2) {
+    FLEXCO_STEP(kt, sa0, sb0)
+    FLEXCO_STEP(kt + 1, sa1, sb1)
+  }
+  if (kt < nk) FLEXCO_STEP(kt, sa0, sb0)
 
   // ---- rank-r extension: C += A2 W2^T (forward form; the entry whose column range holds this
   // block) or C += sum_e A2_e W2_e (input-gradient form; every entry).  This is the LoRA bypass
