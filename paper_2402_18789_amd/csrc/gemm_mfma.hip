@@ -9,16 +9,20 @@
 // token-window backward, where weight gradients are pruned away (Alg. 1) and only
 // dX = dY W remains.
 //
-// Tiling: block tile BM x BN x 64, 256 threads = 4 wavefronts in a 2 x 2 grid, each owning
-// (BM/2) x (BN/2) as 32 x 32 MFMA tiles with fp32 accumulators.  Operand tiles are staged
-// through LDS in two buffers: the next tile's global loads are issued before the MFMAs of
-// the current one and written to the other buffer afterwards (one barrier per k-step).
-//   * A tile and the forward W tile are [rows][64] bf16 = 128-byte rows; the eight 16-byte
-//     chunks of a row are XOR-swizzled with (row >> 1) & 7, so that both the 16-byte writes
-//     and the ds_read_b128 operand fetches of 16 consecutive rows hit 64 distinct banks.
-//   * The transposed W tile is [64][BN + 8]: an operand fragment (8 consecutive k for one
-//     column) is gathered with 16-bit LDS reads; the 16-byte row padding puts the two
-//     k-halves of a wavefront on disjoint banks.
+// Tiling: block tile BM x BN, 256 threads = 4 wavefronts in a 2 x 2 grid, each owning
+// (BM/2) x (BN/2) as 32 x 32 MFMA tiles with fp32 accumulators.
+//   * Forward form: operand tiles go from global memory straight into LDS
+//     (global_load_lds_dwordx4: one wavefront instruction fills 1 KB; lane l lands at
+//     base + 16 l), no staging registers and no LDS write instructions.  LDS is a ring of four
+//     32 KB stages, so two to three stages of loads are in flight while one is multiplied; the
+//     per-stage barrier carries no memory fence, the wait in front of it names exactly the
+//     loads that must have landed.  Rows are XOR-swizzled in 16-byte chunks (applied to the
+//     global address a lane fetches) so that the ds_read_b128 operand fetches of 16 consecutive
+//     rows hit 64 distinct banks.
+//   * Input-gradient form: k-steps of 64, two LDS buffers filled through two sets of staging
+//     registers; the W tile is [64][BN + 8] (k-major as in memory), an operand fragment (8
+//     consecutive k for one column) is gathered with 16-bit LDS reads; the 16-byte row padding
+//     puts the two k-halves of a wavefront on disjoint banks.
 // Work-group ids are remapped so that ids that land on the same XCD (id mod 8) work on
 // neighbouring tiles, M fastest: the W tile they share stays in that XCD's L2.
 #include "flexco_internal.h"
@@ -31,13 +35,17 @@ namespace {
 constexpr int BK = 64;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
+#define FLEXCO_GP(p) ((const __attribute__((address_space(1))) void*)(p))
+#define FLEXCO_LP(p) ((__attribute__((address_space(3))) void*)(p))
+
 __device__ inline int swz(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
 
-template <int BM, int BN, bool TRANS>
-struct Smem {
+// dynamic LDS of the input-gradient form
+template <int BM, int BN>
+struct SmemT {
   static constexpr int A_ELEMS = BM * BK;
-  static constexpr int B_LD = TRANS ? (BN + 8) : BK;
-  static constexpr int B_ELEMS = TRANS ? BK * (BN + 8) : BN * BK;
+  static constexpr int B_LD = BN + 8;
+  static constexpr int B_ELEMS = BK * (BN + 8);
   static constexpr size_t BYTES = 2 * (size_t)(A_ELEMS + B_ELEMS) * sizeof(bf16_t);
 };
 
@@ -49,10 +57,6 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
                                                         int tiles_n, GemmExt ext, float* __restrict__ part,
                                                         int k_chunk) {
   constexpr int WM = BM / 2, WN = BN / 2, MT = WM / 32, NT = WN / 32;
-  using S = Smem<BM, BN, TRANS>;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  bf16_t* As = reinterpret_cast<bf16_t*>(smem_raw);                 // [2][BM][64] swizzled
-  bf16_t* Bs = As + 2 * S::A_ELEMS;                                 // [2][...]
 
   // ---- work-group id -> tile, XCD-aware ------------------------------------------------
   int lid = blockIdx.x;
@@ -63,56 +67,6 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm0 = (wave >> 1) * WM, wn0 = (wave & 1) * WN;
-
-  // ---- global -> register staging --------------------------------------------------------
-  constexpr int A_PASSES = BM / 32;                                  // 8 chunks per row, 32 rows per pass
-  constexpr int B_PASSES = TRANS ? (BK * (BN / 8)) / 256 : BN / 32;
-  u32x4 sa0[A_PASSES], sb0[B_PASSES], sa1[A_PASSES], sb1[B_PASSES];   // two sets of staging registers
-  const int a_c = tid & 7, a_r = tid >> 3;
-  constexpr int BCH = BN / 8;                                        // chunks per row of the transposed W tile
-  const int bt_c = tid % BCH, bt_r = tid / BCH;
-
-  // (kept as macros on purpose: staging arrays captured by lambdas were left in scratch memory)
-#define FLEXCO_LOAD_TILES(k0_, ra, rb)                                                                      \
-  {                                                                                                   \
-    _Pragma("unroll") for (int p = 0; p < A_PASSES; ++p) {                                            \
-      const int r_ = min(m0 + a_r + 32 * p, M - 1);                                                   \
-      ra[p] = *reinterpret_cast<const u32x4*>(A + (size_t)r_ * lda + (k0_) + a_c * 8);                \
-    }                                                                                                 \
-    if (!TRANS) {                                                                                     \
-      _Pragma("unroll") for (int p = 0; p < B_PASSES; ++p) {                                          \
-        const int r_ = min(n0 + a_r + 32 * p, N - 1);                                                 \
-        rb[p] = *reinterpret_cast<const u32x4*>(W + (size_t)r_ * ldw + (k0_) + a_c * 8);              \
-      }                                                                                               \
-    } else {                                                                                          \
-      _Pragma("unroll") for (int p = 0; p < B_PASSES; ++p) {                                          \
-        const int kr_ = bt_r + (256 / BCH) * p;                                                       \
-        int col_ = n0 + bt_c * 8;                                                                     \
-        if (col_ >= N) col_ = 0; /* masked at the store */                                            \
-        rb[p] = *reinterpret_cast<const u32x4*>(W + (size_t)((k0_) + kr_) * ldw + col_);              \
-      }                                                                                               \
-    }                                                                                                 \
-  }
-#define FLEXCO_STORE_TILES(buf_, ra, rb)                                                                    \
-  {                                                                                                   \
-    bf16_t* as_ = As + (buf_) * S::A_ELEMS;                                                           \
-    bf16_t* bs_ = Bs + (buf_) * S::B_ELEMS;                                                           \
-    _Pragma("unroll") for (int p = 0; p < A_PASSES; ++p) {                                            \
-      const int r_ = a_r + 32 * p;                                                                    \
-      *reinterpret_cast<u32x4*>(as_ + r_ * BK + swz(r_, a_c) * 8) = ra[p];                            \
-    }                                                                                                 \
-    if (!TRANS) {                                                                                     \
-      _Pragma("unroll") for (int p = 0; p < B_PASSES; ++p) {                                          \
-        const int r_ = a_r + 32 * p;                                                                  \
-        *reinterpret_cast<u32x4*>(bs_ + r_ * BK + swz(r_, a_c) * 8) = rb[p];                          \
-      }                                                                                               \
-    } else {                                                                                          \
-      _Pragma("unroll") for (int p = 0; p < B_PASSES; ++p) {                                          \
-        const int kr_ = bt_r + (256 / BCH) * p;                                                       \
-        *reinterpret_cast<u32x4*>(bs_ + kr_ * S::B_LD + bt_c * 8) = rb[p];                            \
-      }                                                                                               \
-    }                                                                                                 \
-  }
 
   f32x16 acc[MT][NT];
 #pragma unroll
@@ -127,22 +81,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
   const int nk = k_chunk / BK;
   const int l32 = lane & 31, kg = lane >> 5;
 
-#define FLEXCO_LOAD_FRAGS(kk_, af_, bf_)                                                              \
-  {                                                                                                   \
-    _Pragma("unroll") for (int i = 0; i < MT; ++i) {                                                  \
-      const int r_ = wm0 + i * 32 + l32;                                                              \
-      af_[i] = *reinterpret_cast<const bf16x8*>(as + r_ * BK + swz(r_, (kk_) * 2 + kg) * 8);          \
-    }                                                                                                 \
-    _Pragma("unroll") for (int j = 0; j < NT; ++j) {                                                  \
-      if (!TRANS) {                                                                                   \
-        const int r_ = wn0 + j * 32 + l32;                                                            \
-        bf_[j] = *reinterpret_cast<const bf16x8*>(bs + r_ * BK + swz(r_, (kk_) * 2 + kg) * 8);        \
-      } else {                                                                                        \
-        const bf16_t* col_ = bs + ((kk_) * 16 + kg * 8) * S::B_LD + wn0 + j * 32 + l32;               \
-        _Pragma("unroll") for (int e = 0; e < 8; ++e) bf_[j][e] = col_[e * S::B_LD];                  \
-      }                                                                                               \
-    }                                                                                                 \
-  }
+  // (the pipelines are macros on purpose: register arrays captured by lambdas were left in
+  // scratch memory)
 #define FLEXCO_MFMAS(af_, bf_)                                                                        \
   {                                                                                                   \
     _Pragma("unroll") for (int i = 0; i < MT; ++i)                                                    \
@@ -150,16 +90,210 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af_[i], bf_[j], acc[i][j], 0, 0, 0);      \
   }
 
-  // Software pipeline over k-steps of 64 with two LDS buffers and two sets of staging registers,
-  // so that a tile's global loads have two whole steps to arrive:
-  //   step kt, first half : MFMAs of k-slices 0, 1 of tile kt (LDS buffer kt & 1)
-  //   step kt, middle     : the staging set that holds tile kt + 1 (loaded in the middle of step
-  //                         kt - 2) is written to the other LDS buffer and reloaded with tile kt + 3
-  //   step kt, second half: MFMAs of k-slices 2, 3 - they run while the LDS writes drain
-  //   one barrier at the end of the step: the other buffer is complete, this one is free.
-  // The other buffer was last read in step kt - 1, which every wavefront left through that
-  // step's barrier, so the mid-step writes race with nothing.  Past the last tile the indices are
-  // clamped: the extra loads and writes repeat tile nk - 1 and are never read.
+  if constexpr (!TRANS) {
+    // ======================= forward form: global memory -> LDS directly =======================
+    // A ring of four stages; a stage holds BKS = 16384 / (BM + BN) k-columns of both tiles
+    // (32 KB: [BM + BN][BKS] bf16, A rows first), so three stages can be in flight or waiting
+    // while one is multiplied.  The stages are four separate arrays, not one indexed buffer:
+    // the compiler then sees that loads in flight target an array no ds_read of that moment
+    // touches, and inserts no wait of its own.
+    constexpr int BKS = 16384 / (BM + BN);
+    constexpr int CPR = BKS / 8;                 // 16-byte chunks per row
+    constexpr int RPI = 64 / CPR;                // rows one wavefront load instruction fills (1 KB)
+    constexpr int SL = BKS / 16;                 // MFMA k-slices per stage
+    constexpr int PA = BM / (4 * RPI), PB = BN / (4 * RPI);   // load instructions per wavefront and stage
+    constexpr int ST_ELEMS = (BM + BN) * BKS;
+    static_assert(BKS == 32 || BKS == 64, "stage depth");
+    __shared__ __attribute__((aligned(1024))) bf16_t ring0[ST_ELEMS];
+    __shared__ __attribute__((aligned(1024))) bf16_t ring1[ST_ELEMS];
+    __shared__ __attribute__((aligned(1024))) bf16_t ring2[ST_ELEMS];
+    __shared__ __attribute__((aligned(1024))) bf16_t ring3[ST_ELEMS];
+    // Rows are BKS bf16 wide; chunk c of row r is stored at chunk c ^ key(r), key(r) = (r >> 1) & 7
+    // for 128-byte rows and (r >> 2) & 3 for 64-byte rows: the ds_read_b128 operand fetches of 16
+    // consecutive rows then hit 64 distinct banks.
+#define FLEXCO_KEY(r_) (CPR == 8 ? (((r_) >> 1) & 7) : (((r_) >> 2) & 3))
+    // Load instruction p of wavefront w fills rows RPI (4 p + w) .. + RPI of a tile; lane l lands
+    // at base + 16 l, i.e. physical chunk l % CPR of row l / CPR, so it fetches the logical chunk
+    // (l % CPR) ^ key(row) from global memory.  key(row) does not depend on p.
+    const int d_row = lane / CPR;
+    const int d_c = (lane % CPR) ^ FLEXCO_KEY(wave * RPI + d_row);
+    const bf16_t* ga[PA];
+    const bf16_t* gw[PB];
+#pragma unroll
+    for (int p = 0; p < PA; ++p)
+      ga[p] = A + (size_t)min(m0 + (p * 4 + wave) * RPI + d_row, M - 1) * lda + kbeg + d_c * 8;
+#pragma unroll
+    for (int p = 0; p < PB; ++p)
+      gw[p] = W + (size_t)min(n0 + (p * 4 + wave) * RPI + d_row, N - 1) * ldw + kbeg + d_c * 8;
+    const int ns = k_chunk / BKS;                // stages of this block
+
+    // stage index past the end: clamped, the loads repeat the last stage into a free buffer
+#define FLEXCO_DMA(ring_, s_)                                                                         \
+  {                                                                                                   \
+    const int koff_ = min((s_), ns - 1) * BKS;                                                        \
+    _Pragma("unroll") for (int p = 0; p < PA; ++p)                                                    \
+      __builtin_amdgcn_global_load_lds(FLEXCO_GP(ga[p] + koff_),                                      \
+                                       FLEXCO_LP(ring_ + (p * 4 + wave) * RPI * BKS), 16, 0, 0);      \
+    _Pragma("unroll") for (int p = 0; p < PB; ++p)                                                    \
+      __builtin_amdgcn_global_load_lds(FLEXCO_GP(gw[p] + koff_),                                      \
+                                       FLEXCO_LP(ring_ + (BM + (p * 4 + wave) * RPI) * BKS), 16, 0, 0); \
+  }
+#define FLEXCO_FRAGS(ring_, kk_, af_, bf_)                                                            \
+  {                                                                                                   \
+    _Pragma("unroll") for (int i = 0; i < MT; ++i) {                                                  \
+      const int r_ = wm0 + i * 32 + l32;                                                              \
+      af_[i] = *reinterpret_cast<const bf16x8*>(ring_ + r_ * BKS + (((kk_) * 2 + kg) ^ FLEXCO_KEY(r_)) * 8); \
+    }                                                                                                 \
+    _Pragma("unroll") for (int j = 0; j < NT; ++j) {                                                  \
+      const int r_ = wn0 + j * 32 + l32;                                                              \
+      bf_[j] = *reinterpret_cast<const bf16x8*>(ring_ + (BM + r_) * BKS + (((kk_) * 2 + kg) ^ FLEXCO_KEY(r_)) * 8); \
+    }                                                                                                 \
+  }
+    // Barrier without the memory fences of __syncthreads (those would drain every load in
+    // flight): the wait before it covers exactly the stage that has to be complete, and the
+    // empty asm statements keep the compiler from moving LDS accesses across it.
+#define FLEXCO_WAIT_BARRIER(imm_)                                                                     \
+  {                                                                                                   \
+    __builtin_amdgcn_sched_barrier(0);                                                                \
+    __builtin_amdgcn_s_waitcnt(imm_);                                                                 \
+    asm volatile("" ::: "memory");                                                                    \
+    __builtin_amdgcn_s_barrier();                                                                     \
+    asm volatile("" ::: "memory");                                                                    \
+    __builtin_amdgcn_sched_barrier(0);                                                                \
+  }
+    // Stage s (ring buffer cur_) enters with its slice-0 fragments in set 0.  Slices alternate
+    // between the two fragment sets, each fetched one slice ahead.  In the last slice:
+    //   wait until this wavefront's loads of stage s + 1 have landed (those of stage s + 2 may
+    //   stay in flight: vmcnt <= loads of one stage), barrier -> stage s + 1 is complete for
+    //   everyone, and everyone has finished reading stage s - 1 (its MFMAs were issued);
+    //   start the loads of stage s + 3 into the buffer stage s - 1 used; fetch slice 0 of stage
+    //   s + 1; then the last slice's MFMAs cover those latencies.
+#define FLEXCO_STAGE(cur_, nxt_, free_, s_)                                                           \
+  {                                                                                                   \
+    _Pragma("unroll") for (int kk = 0; kk < SL; kk += 2) {                                            \
+      FLEXCO_FRAGS(cur_, kk + 1, af1, bf1)                                                            \
+      FLEXCO_MFMAS(af0, bf0)                                                                          \
+      FLEXCO_ORDER_READS_FIRST                                                                        \
+      __builtin_amdgcn_sched_barrier(0);                                                              \
+      if (kk + 2 < SL) {                                                                              \
+        FLEXCO_FRAGS(cur_, kk + 2, af0, bf0)                                                          \
+        FLEXCO_MFMAS(af1, bf1)                                                                        \
+        FLEXCO_ORDER_READS_FIRST                                                                      \
+      } else {                                                                                        \
+        FLEXCO_WAIT_BARRIER(WAIT_ONE_STAGE)                                                           \
+        FLEXCO_DMA(free_, (s_) + 3)                                                                   \
+        FLEXCO_FRAGS(nxt_, 0, af0, bf0)                                                               \
+        FLEXCO_MFMAS(af1, bf1)                                                                        \
+        FLEXCO_ORDER_LOADS_READS_FIRST                                                                \
+      }                                                                                               \
+      __builtin_amdgcn_sched_barrier(0);                                                              \
+    }                                                                                                 \
+  }
+    // Instruction order inside a slice, imposed on the scheduler (it otherwise sinks the fragment
+    // reads behind the MFMAs, right in front of their first use): one LDS read - or one global
+    // load and one LDS read - ahead of each of the first MFMAs, the remaining MFMAs after.
+    // Masks: 0x008 MFMA, 0x020 VMEM read, 0x100 DS read.
+#define FLEXCO_ORDER_READS_FIRST                                                                      \
+  {                                                                                                   \
+    _Pragma("unroll") for (int q = 0; q < MT + NT; ++q) {                                             \
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                              \
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                              \
+    }                                                                                                 \
+    if (MT * NT > MT + NT) __builtin_amdgcn_sched_group_barrier(0x008, MT * NT - (MT + NT) > 0 ? MT * NT - (MT + NT) : 1, 0); \
+  }
+#define FLEXCO_ORDER_LOADS_READS_FIRST                                                                \
+  {                                                                                                   \
+    _Pragma("unroll") for (int q = 0; q < MT + NT; ++q) {                                             \
+      __builtin_amdgcn_sched_group_barrier(0x020, NLD / (MT + NT), 0);                                \
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                              \
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                              \
+    }                                                                                                 \
+    if (MT * NT > MT + NT) __builtin_amdgcn_sched_group_barrier(0x008, MT * NT - (MT + NT) > 0 ? MT * NT - (MT + NT) : 1, 0); \
+  }
+    // s_waitcnt immediates: vmcnt in bits 3:0 and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at
+    // their maxima (no wait)
+    constexpr int NLD = PA + PB;
+    static_assert(NLD <= 15 && NLD % (MT + NT) == 0, "loads per stage: vmcnt encoding, even spread over the slice");
+    constexpr int WAIT_ONE_STAGE = 0x0F70 | NLD;                     // vmcnt(NLD)
+    constexpr int WAIT_TWO_STAGES = 0x0F70 | ((2 * NLD) & 15) | (((2 * NLD) >> 4) << 14);
+    bf16x8 af0[MT], bf0[NT], af1[MT], bf1[NT];
+    FLEXCO_DMA(ring0, 0)
+    FLEXCO_DMA(ring1, 1)
+    FLEXCO_DMA(ring2, 2)
+    FLEXCO_WAIT_BARRIER(WAIT_TWO_STAGES)
+    FLEXCO_FRAGS(ring0, 0, af0, bf0)
+    int st = 0;
+    for (; st + 3 < ns; st += 4) {
+      FLEXCO_STAGE(ring0, ring1, ring3, st)
+      FLEXCO_STAGE(ring1, ring2, ring0, st + 1)
+      FLEXCO_STAGE(ring2, ring3, ring1, st + 2)
+      FLEXCO_STAGE(ring3, ring0, ring2, st + 3)
+    }
+    if (st < ns) FLEXCO_STAGE(ring0, ring1, ring3, st)
+    if (st + 1 < ns) FLEXCO_STAGE(ring1, ring2, ring0, st + 1)
+    if (st + 2 < ns) FLEXCO_STAGE(ring2, ring3, ring1, st + 2)
+    __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0): nothing may land in LDS after the block ends
+  } else {
+    // ================== input-gradient form: staged through registers ==========================
+    using S = SmemT<BM, BN>;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    bf16_t* As = reinterpret_cast<bf16_t*>(smem_raw);                 // [2][BM][64] swizzled
+    bf16_t* Bs = As + 2 * S::A_ELEMS;                                 // [2][64][BN + 8]
+    constexpr int A_PASSES = BM / 32;                                  // 8 chunks per row, 32 rows per pass
+    constexpr int B_PASSES = (BK * (BN / 8)) / 256;
+    u32x4 sa0[A_PASSES], sb0[B_PASSES], sa1[A_PASSES], sb1[B_PASSES];   // two sets of staging registers
+    const int a_c = tid & 7, a_r = tid >> 3;
+    constexpr int BCH = BN / 8;                                        // chunks per row of the W tile
+    const int bt_c = tid % BCH, bt_r = tid / BCH;
+
+#define FLEXCO_LOAD_TILES(k0_, ra, rb)                                                                \
+  {                                                                                                   \
+    _Pragma("unroll") for (int p = 0; p < A_PASSES; ++p) {                                            \
+      const int r_ = min(m0 + a_r + 32 * p, M - 1);                                                   \
+      ra[p] = *reinterpret_cast<const u32x4*>(A + (size_t)r_ * lda + (k0_) + a_c * 8);                \
+    }                                                                                                 \
+    _Pragma("unroll") for (int p = 0; p < B_PASSES; ++p) {                                            \
+      const int kr_ = bt_r + (256 / BCH) * p;                                                         \
+      int col_ = n0 + bt_c * 8;                                                                       \
+      if (col_ >= N) col_ = 0; /* masked at the store */                                              \
+      rb[p] = *reinterpret_cast<const u32x4*>(W + (size_t)((k0_) + kr_) * ldw + col_);                \
+    }                                                                                                 \
+  }
+#define FLEXCO_STORE_TILES(buf_, ra, rb)                                                              \
+  {                                                                                                   \
+    bf16_t* as_ = As + (buf_) * S::A_ELEMS;                                                           \
+    bf16_t* bs_ = Bs + (buf_) * S::B_ELEMS;                                                           \
+    _Pragma("unroll") for (int p = 0; p < A_PASSES; ++p) {                                            \
+      const int r_ = a_r + 32 * p;                                                                    \
+      *reinterpret_cast<u32x4*>(as_ + r_ * BK + swz(r_, a_c) * 8) = ra[p];                            \
+    }                                                                                                 \
+    _Pragma("unroll") for (int p = 0; p < B_PASSES; ++p) {                                            \
+      const int kr_ = bt_r + (256 / BCH) * p;                                                         \
+      *reinterpret_cast<u32x4*>(bs_ + kr_ * S::B_LD + bt_c * 8) = rb[p];                              \
+    }                                                                                                 \
+  }
+#define FLEXCO_LOAD_FRAGS(kk_, af_, bf_)                                                              \
+  {                                                                                                   \
+    _Pragma("unroll") for (int i = 0; i < MT; ++i) {                                                  \
+      const int r_ = wm0 + i * 32 + l32;                                                              \
+      af_[i] = *reinterpret_cast<const bf16x8*>(as + r_ * BK + swz(r_, (kk_) * 2 + kg) * 8);          \
+    }                                                                                                 \
+    _Pragma("unroll") for (int j = 0; j < NT; ++j) {                                                  \
+      const bf16_t* col_ = bs + ((kk_) * 16 + kg * 8) * S::B_LD + wn0 + j * 32 + l32;                 \
+      _Pragma("unroll") for (int e = 0; e < 8; ++e) bf_[j][e] = col_[e * S::B_LD];                    \
+    }                                                                                                 \
+  }
+    // Software pipeline over k-steps of 64 with two LDS buffers and two sets of staging
+    // registers, so that a tile's global loads have two whole steps to arrive:
+    //   step kt, first half : MFMAs of k-slices 0, 1 of tile kt (LDS buffer kt & 1)
+    //   step kt, middle     : the staging set that holds tile kt + 1 (loaded in the middle of
+    //                         step kt - 2) is written to the other LDS buffer and reloaded with
+    //                         tile kt + 3
+    //   step kt, second half: MFMAs of k-slices 2, 3 - they run while the LDS writes drain
+    //   one barrier at the end of the step: the other buffer is complete, this one is free.
+    // The other buffer was last read in step kt - 1, which every wavefront left through that
+    // step's barrier, so the mid-step writes race with nothing.  Past the last tile the indices
+    // are clamped: the extra loads and writes repeat tile nk - 1 and are never read.
 #define FLEXCO_STEP(kt_, ra_, rb_)                                                                    \
   {                                                                                                   \
     const int buf = (kt_) & 1;                                                                        \
@@ -181,17 +315,18 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
     __builtin_amdgcn_sched_barrier(0);                                                                \
     __syncthreads();                                                                                  \
   }
-  FLEXCO_LOAD_TILES(kbeg, sa0, sb0)
-  FLEXCO_STORE_TILES(0, sa0, sb0)
-  __syncthreads();
-  FLEXCO_LOAD_TILES(kbeg + min(1, nk - 1) * BK, sa0, sb0)
-  FLEXCO_LOAD_TILES(kbeg + min(2, nk - 1) * BK, sa1, sb1)
-  int kt = 0;
-  for (; kt + 1 < nk; kt += 2) {
-    FLEXCO_STEP(kt, sa0, sb0)
-    FLEXCO_STEP(kt + 1, sa1, sb1)
+    FLEXCO_LOAD_TILES(kbeg, sa0, sb0)
+    FLEXCO_STORE_TILES(0, sa0, sb0)
+    __syncthreads();
+    FLEXCO_LOAD_TILES(kbeg + min(1, nk - 1) * BK, sa0, sb0)
+    FLEXCO_LOAD_TILES(kbeg + min(2, nk - 1) * BK, sa1, sb1)
+    int kt = 0;
+    for (; kt + 1 < nk; kt += 2) {
+      FLEXCO_STEP(kt, sa0, sb0)
+      FLEXCO_STEP(kt + 1, sa1, sb1)
+    }
+    if (kt < nk) FLEXCO_STEP(kt, sa0, sb0)
   }
-  if (kt < nk) FLEXCO_STEP(kt, sa0, sb0)
 
   // ---- rank-r extension: C += A2 W2^T (forward form; the entry whose column range holds this
   // block) or C += sum_e A2_e W2_e (input-gradient form; every entry).  This is the LoRA bypass
@@ -292,17 +427,17 @@ template <int BM, int BN, bool TRANS>
 int32_t launch_cfg(const void* A, const void* W, void* C, const void* bias, const void* res, int M, int N, int K,
                    size_t lda, size_t ldw, size_t ldc, size_t ldr, const GemmExt& ext, hipStream_t s,
                    float* part = nullptr, int splits = 1) {
-  using S = Smem<BM, BN, TRANS>;
+  constexpr size_t LDS_BYTES = TRANS ? SmemT<BM, BN>::BYTES : 0;   // the forward form's LDS is static
   auto kern = gemm_bf16_kernel<BM, BN, TRANS>;
   static bool attr_set = false;
-  if (!attr_set) {
+  if (!attr_set && LDS_BYTES > 0) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)S::BYTES);
+                                       (int)LDS_BYTES);
     if (e != hipSuccess) return fail(FLEXCO_EHIP, "hipFuncSetAttribute(gemm): %s", hipGetErrorString(e));
     attr_set = true;
   }
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n, splits), dim3(256), S::BYTES, s, (const bf16_t*)A, (const bf16_t*)W,
+  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n, splits), dim3(256), LDS_BYTES, s, (const bf16_t*)A, (const bf16_t*)W,
                      (bf16_t*)C, (const bf16_t*)bias, (const bf16_t*)res, M, N, K, lda, ldw, ldc, ldr, tiles_m, tiles_n,
                      ext, splits > 1 ? part : nullptr, K / splits);
   if (splits > 1) {
