@@ -89,23 +89,34 @@ struct Carver {
   }
 };
 
-// scratch of the bf16 LoRA path for `rows` token rows
+void target_dims(const flexco_layer_cfg& c, int t, int* in, int* out);
+
+// scratch of the bf16 LoRA path for `rows` token rows, one slot per target
 struct LoraWs {
-  float* part[6];     // K-split partial sums, [KS_MAX, rows, r] each
-  float* f32[6];      // reduced [rows, r]
-  bf16_t* ext[3];     // scaled bf16 [rows, r] for the GEMM extension
-  bf16_t* bt[3];      // transposed B, [r, max_out]
+  float* part_u[LORA_MATS];   // K-split partial sums of u_t = x_t A_t^T, [KS_MAX, rows, r]
+  bf16_t* ext[LORA_MATS];     // scaled bf16 [rows, r] operand of the GEMM extension
+  // backward only
+  float* part_t[LORA_MATS];   // K-split partial sums of t_t = dy_t B_t
+  float* u[LORA_MATS];        // [rows, r]
+  float* t[LORA_MATS];        // [rows, r]
+  bf16_t* bt[LORA_MATS];      // transposed B_t, [r, out_t]
 };
 
-void carve_lora(const flexco_layer_cfg& c, int rows, Carver& cv, LoraWs& w) {
+void carve_lora(const flexco_layer_cfg& c, int rows, bool backward, Carver& cv, LoraWs& w) {
   const int r = c.lora_rank > 0 ? c.lora_rank : 1;
-  const size_t qd = (size_t)c.n_q_heads * c.head_dim;
-  size_t max_out = c.hidden > c.ffn ? c.hidden : c.ffn;
-  if (qd > max_out) max_out = qd;
-  for (int i = 0; i < 6; ++i) w.part[i] = (float*)cv.take(sizeof(float) * KS_MAX * (size_t)rows * r);
-  for (int i = 0; i < 6; ++i) w.f32[i] = (float*)cv.take(sizeof(float) * (size_t)rows * r);
-  for (int i = 0; i < 3; ++i) w.ext[i] = (bf16_t*)cv.take(sizeof(bf16_t) * (size_t)rows * r);
-  for (int i = 0; i < 3; ++i) w.bt[i] = (bf16_t*)cv.take(sizeof(bf16_t) * max_out * r);
+  memset(&w, 0, sizeof(w));
+  for (int t = 0; t < LORA_MATS; ++t) {
+    if (!(c.lora_targets >> t & 1)) continue;
+    int in, out;
+    target_dims(c, t, &in, &out);
+    w.part_u[t] = (float*)cv.take(sizeof(float) * KS_MAX * (size_t)rows * r);
+    w.ext[t] = (bf16_t*)cv.take(sizeof(bf16_t) * (size_t)rows * r);
+    if (!backward) continue;
+    w.part_t[t] = (float*)cv.take(sizeof(float) * KS_MAX * (size_t)rows * r);
+    w.u[t] = (float*)cv.take(sizeof(float) * (size_t)rows * r);
+    w.t[t] = (float*)cv.take(sizeof(float) * (size_t)rows * r);
+    w.bt[t] = (bf16_t*)cv.take(sizeof(bf16_t) * (size_t)out * r);
+  }
 }
 
 struct FwdWs {
@@ -115,7 +126,7 @@ struct FwdWs {
   size_t bytes;
 };
 struct BwdWs {
-  void *hn, *act, *dact, *dgu, *dh, *dx2, *dattn, *dq, *dqkv;
+  void *hn, *hn2, *act, *dact, *dgu, *dh, *dx2, *dattn, *dq, *dqkv;   // hn = norm1(x), hn2 = norm2(x2)
   float *delta, *u, *t;
   float* gemm_part;        // split-K partial sums of the input-gradient GEMMs
   size_t gemm_part_elems;
@@ -144,7 +155,7 @@ FwdWs carve_fwd(const flexco_layer_cfg& c, int T, int n_parts, void* base) {
   const size_t prow = (size_t)n_parts * c.n_kv_heads * cols_per_tile(c);
   w.part_ml = (float*)cv.take(sizeof(float) * prow * 2);
   w.part_acc = (float*)cv.take(sizeof(float) * prow * c.head_dim);
-  carve_lora(c, T, cv, w.lw);
+  carve_lora(c, T, false, cv, w.lw);
   w.bytes = cv.off;
   return w;
 }
@@ -155,6 +166,7 @@ BwdWs carve_bwd(const flexco_layer_cfg& c, int n, void* base) {
   Carver cv{(char*)base};
   BwdWs w;
   w.hn = cv.take(e * n * c.hidden);
+  w.hn2 = cv.take(e * n * c.hidden);
   w.act = cv.take(e * n * c.ffn);
   w.dact = cv.take(e * n * c.ffn);
   w.dgu = cv.take(e * n * 2 * c.ffn);
@@ -169,7 +181,7 @@ BwdWs carve_bwd(const flexco_layer_cfg& c, int n, void* base) {
   w.t = (float*)cv.take(sizeof(float) * n * r);
   w.gemm_part_elems = c.dtype == FLEXCO_BF16 ? (size_t)n * SPLITK_COLS : 0;
   w.gemm_part = (float*)cv.take(sizeof(float) * w.gemm_part_elems);
-  carve_lora(c, n, cv, w.lw);
+  carve_lora(c, n, true, cv, w.lw);
   w.bytes = cv.off;
   return w;
 }
@@ -288,18 +300,19 @@ int32_t forward_projection(const flexco_layer_cfg& c, const flexco_lora* lora, c
     LoraFinalizeArgs fa;
     GemmExt ext;
     memset(&sa, 0, sizeof(sa)); memset(&fa, 0, sizeof(fa)); memset(&ext, 0, sizeof(ext));
-    sa.row_idx = m.lora_tok; sa.n = m.n_lora; sa.K = K; sa.KS = lora_shrink_splits(m.n_lora, K); sa.r = r;
-    fa.ext_map = m.tok_lora; fa.ext_rows = T; fa.n = m.n_lora; fa.r = r; fa.KS = sa.KS; fa.scale = c.lora_scale;
+    sa.row_idx = m.lora_tok; sa.n = m.n_lora; sa.r = r;
+    fa.ext_map = m.tok_lora; fa.ext_rows = T; fa.n = m.n_lora; fa.r = r; fa.scale = c.lora_scale;
     ext.n = nact; ext.r = r;
     for (int z = 0; z < nact; ++z) {
       const int t = targets[act[z]];
       int in, out;
       target_dims(c, t, &in, &out);
       sa.X[z] = (const bf16_t*)x; sa.ldx[z] = K; sa.S[z] = (const bf16_t*)lora->A[t]; sa.lds[z] = K;
-      sa.part[z] = k.lw.part[z];
-      fa.part[z] = k.lw.part[z]; fa.out_f32[z] = nullptr; fa.out_ext[z] = k.lw.ext[z];
+      sa.K[z] = K; sa.KS[z] = lora_shrink_splits(m.n_lora, K);
+      sa.part[z] = k.lw.part_u[t];
+      fa.part[z] = k.lw.part_u[t]; fa.KS[z] = sa.KS[z]; fa.out_f32[z] = nullptr; fa.out_ext[z] = k.lw.ext[t];
       ext.col0[z] = col0[act[z]]; ext.col1[z] = col0[act[z]] + out;
-      ext.A2[z] = k.lw.ext[z]; ext.W2[z] = (const bf16_t*)lora->B[t]; ext.ldw2[z] = r;
+      ext.A2[z] = k.lw.ext[t]; ext.W2[z] = (const bf16_t*)lora->B[t]; ext.ldw2[z] = r;
     }
     LR(launch_lora_shrink_mfma(sa, nact, s));
     LR(launch_lora_finalize(fa, nact, s));
@@ -313,85 +326,116 @@ int32_t forward_projection(const flexco_layer_cfg& c, const flexco_lora* lora, c
   return FLEXCO_OK;
 }
 
-// One input-gradient projection of the backward window with the LoRA gradients of up to three
-// targets that feed it:   dx = dy W (+ sum_t scale (dy_t B_t) A_t);
+// A group = the targets that feed one input-gradient projection (down | gate, up | o | q, k, v).
+struct BwdGroup {
+  int n_targets;
+  int targets[3], col0[3];
+  const void* xs[3];     // the targets' input rows
+  int N_dx;              // width of the projection's input = in_t of every target
+  bool fused;            // bf16 matrix-core path: LoRA folded into the GEMM, gradients batched
+  int act[3], nact;      // active targets (indices into targets[])
+};
+
+void plan_group(const flexco_layer_cfg& c, BwdGroup& g) {
+  g.nact = 0;
+  for (int i = 0; i < g.n_targets; ++i)
+    if (has_target(c, g.targets[i])) g.act[g.nact++] = i;
+  g.fused = g.nact > 0 && lora_mfma_ok(c, g.N_dx);
+  for (int z = 0; z < g.nact && g.fused; ++z) {
+    int in, out;
+    target_dims(c, g.targets[g.act[z]], &in, &out);
+    if (out % 128 != 0 || in != g.N_dx) g.fused = false;
+  }
+}
+
+// Start of a backward window, fused groups only: u_t = x_t A_t^T of every target in one launch
+// (+ its reduction), and the transposed B_t the t_t = dy_t B_t products contract against.
+int32_t lora_bwd_prepare(const flexco_layer_cfg& c, const flexco_lora* lora, int n, const BwdGroup* groups,
+                         int n_groups, BwdWs& k, hipStream_t s) {
+  LoraShrinkArgs su;
+  LoraFinalizeArgs fu;
+  LoraTransposeArgs ta;
+  memset(&su, 0, sizeof(su)); memset(&fu, 0, sizeof(fu)); memset(&ta, 0, sizeof(ta));
+  const int r = c.lora_rank;
+  su.n = n; su.r = r;
+  fu.n = n; fu.r = r; fu.scale = 1.f;
+  ta.r = r;
+  int nz = 0;
+  for (int gi = 0; gi < n_groups; ++gi) {
+    const BwdGroup& g = groups[gi];
+    if (!g.fused) continue;
+    for (int a = 0; a < g.nact; ++a, ++nz) {
+      const int t = g.targets[g.act[a]];
+      int in, out;
+      target_dims(c, t, &in, &out);
+      su.X[nz] = (const bf16_t*)g.xs[g.act[a]]; su.ldx[nz] = in; su.S[nz] = (const bf16_t*)lora->A[t]; su.lds[nz] = in;
+      su.K[nz] = in; su.KS[nz] = lora_shrink_splits(n, in);
+      su.part[nz] = k.lw.part_u[t];
+      fu.part[nz] = k.lw.part_u[t]; fu.KS[nz] = su.KS[nz]; fu.out_f32[nz] = k.lw.u[t]; fu.out_ext[nz] = nullptr;
+      ta.B[nz] = (const bf16_t*)lora->B[t]; ta.Bt[nz] = k.lw.bt[t]; ta.out[nz] = out;
+    }
+  }
+  if (nz == 0) return FLEXCO_OK;
+  LR(launch_lora_shrink_mfma(su, nz, s));
+  LR(launch_lora_finalize(fu, nz, s));
+  LR(launch_lora_transpose(ta, nz, s));
+  return FLEXCO_OK;
+}
+
+// One input-gradient projection of the backward window with the LoRA gradients of the targets
+// that feed it:   dx = dy W (+ sum_t scale (dy_t B_t) A_t);
 //   dB_t += scale dy_t^T (x_t A_t^T);   dA_t += scale (dy_t B_t)^T x_t.
 // dy_t = columns [col0_t, col0_t + out_t) of dy; x_t: the target's input rows (in_t wide).
-// dx may be NULL (only the LoRA gradients are wanted).
+// dx may be NULL (only the LoRA gradients are wanted).  On the fused path the dA / dB products are
+// only queued in `outer` (one launch for the whole window at its end): dy, x_t and the u_t, t_t
+// buffers stay untouched until then.
 int32_t backward_projection(const flexco_layer_cfg& c, const flexco_lora* lora, int n, const void* dy, int K_dy,
-                            const void* W, void* dx, int N_dx, const int* targets, const int* col0,
-                            const void* const* xs, int n_targets, BwdWs& k, hipStream_t s) {
-  const int dt = c.dtype, r = c.lora_rank;
+                            const void* W, void* dx, const BwdGroup& g, BwdWs& k, LoraOuterArgs& outer,
+                            hipStream_t s) {
+  const int dt = c.dtype, r = c.lora_rank, N_dx = g.N_dx;
   const size_t e = esize(dt);
-  int act[3], nact = 0;
-  for (int i = 0; i < n_targets; ++i)
-    if (has_target(c, targets[i])) act[nact++] = i;
-  bool fused = nact > 0 && lora_mfma_ok(c, N_dx);
-  for (int z = 0; z < nact && fused; ++z) {
-    int in, out;
-    target_dims(c, targets[act[z]], &in, &out);
-    if (out % 128 != 0 || in != N_dx) fused = false;
-  }
-  if (fused) {
-    // u_t = x_t A_t^T (one launch: the targets of a group share the input width)
-    LoraShrinkArgs su, st;
-    LoraFinalizeArgs fu, ft;
-    LoraTransposeArgs ta;
+  if (g.fused) {
+    // t_t = dy_t B_t of the group's targets in one launch (+ its reduction, which also writes the
+    // scaled bf16 copy the GEMM extension reads)
+    LoraShrinkArgs st;
+    LoraFinalizeArgs ft;
     GemmExt ext;
-    memset(&su, 0, sizeof(su)); memset(&fu, 0, sizeof(fu)); memset(&ta, 0, sizeof(ta)); memset(&ext, 0, sizeof(ext));
-    su.n = n; su.K = N_dx; su.KS = lora_shrink_splits(n, N_dx); su.r = r;
-    fu.n = n; fu.r = r; fu.KS = su.KS; fu.scale = 1.f;
-    ta.r = r;
-    ext.n = nact; ext.r = r;
-    for (int z = 0; z < nact; ++z) {
-      const int t = targets[act[z]];
+    memset(&st, 0, sizeof(st)); memset(&ft, 0, sizeof(ft)); memset(&ext, 0, sizeof(ext));
+    st.n = n; st.r = r;
+    ft.n = n; ft.r = r; ft.scale = c.lora_scale;
+    ext.n = g.nact; ext.r = r;
+    for (int z = 0; z < g.nact; ++z) {
+      const int t = g.targets[g.act[z]];
       int in, out;
       target_dims(c, t, &in, &out);
-      su.X[z] = (const bf16_t*)xs[act[z]]; su.ldx[z] = in; su.S[z] = (const bf16_t*)lora->A[t]; su.lds[z] = in;
-      su.part[z] = k.lw.part[z];
-      fu.part[z] = k.lw.part[z]; fu.out_f32[z] = k.lw.f32[z]; fu.out_ext[z] = nullptr;
-      ta.B[z] = (const bf16_t*)lora->B[t]; ta.Bt[z] = k.lw.bt[z]; ta.out[z] = out;
-      ext.A2[z] = k.lw.ext[z]; ext.W2[z] = (const bf16_t*)lora->A[t]; ext.ldw2[z] = in;
+      st.X[z] = (const bf16_t*)boff(dy, g.col0[g.act[z]], e); st.ldx[z] = K_dy; st.S[z] = k.lw.bt[t]; st.lds[z] = out;
+      st.K[z] = out; st.KS[z] = lora_shrink_splits(n, out);
+      st.part[z] = k.lw.part_t[t];
+      ft.part[z] = k.lw.part_t[t]; ft.KS[z] = st.KS[z]; ft.out_f32[z] = k.lw.t[t]; ft.out_ext[z] = k.lw.ext[t];
+      ext.A2[z] = k.lw.ext[t]; ext.W2[z] = (const bf16_t*)lora->A[t]; ext.ldw2[z] = in;
+      // dB_t[o, j] += scale sum_m dy_t[m, o] u_t[m, j];   dA_t[j, i] += scale sum_m x_t[m, i] t_t[m, j]
+      int q = outer.count;
+      outer.X[q] = (const bf16_t*)boff(dy, g.col0[g.act[z]], e); outer.ldx[q] = K_dy; outer.U[q] = k.lw.u[t];
+      outer.G[q] = lora->dB[t]; outer.g_i[q] = r; outer.g_j[q] = 1; outer.n_long[q] = out;
+      ++q;
+      outer.X[q] = (const bf16_t*)g.xs[g.act[z]]; outer.ldx[q] = in; outer.U[q] = k.lw.t[t];
+      outer.G[q] = lora->dA[t]; outer.g_i[q] = 1; outer.g_j[q] = in; outer.n_long[q] = in;
+      outer.count = q + 1;
     }
-    LR(launch_lora_shrink_mfma(su, nact, s));
-    LR(launch_lora_finalize(fu, nact, s));
-    LR(launch_lora_transpose(ta, nact, s));
-    // t_t = dy_t B_t (contracted width differs per target: one launch each)
-    for (int z = 0; z < nact; ++z) {
-      const int t = targets[act[z]];
-      int in, out;
-      target_dims(c, t, &in, &out);
-      memset(&st, 0, sizeof(st)); memset(&ft, 0, sizeof(ft));
-      st.n = n; st.K = out; st.KS = lora_shrink_splits(n, out); st.r = r;
-      st.X[0] = (const bf16_t*)boff(dy, col0[act[z]], e); st.ldx[0] = K_dy; st.S[0] = k.lw.bt[z]; st.lds[0] = out;
-      st.part[0] = k.lw.part[3 + z];
-      ft.n = n; ft.r = r; ft.KS = st.KS; ft.scale = c.lora_scale;
-      ft.part[0] = k.lw.part[3 + z]; ft.out_f32[0] = k.lw.f32[3 + z]; ft.out_ext[0] = k.lw.ext[z];
-      LR(launch_lora_shrink_mfma(st, 1, s));
-      LR(launch_lora_finalize(ft, 1, s));
-    }
-    if (dx) {
-      int32_t rc = launch_gemm(dy, W, dx, nullptr, nullptr, n, N_dx, K_dy, K_dy, N_dx, N_dx, 0, true, dt, s, &ext,
-                               k.gemm_part, k.gemm_part_elems);
-      if (rc) return rc;
-    }
-    for (int z = 0; z < nact; ++z) {
-      const int t = targets[act[z]];
-      int in, out;
-      target_dims(c, t, &in, &out);
-      LR(launch_lora_outer_bf16(boff(dy, col0[act[z]], e), K_dy, k.lw.f32[z], lora->dB[t], r, 1, n, out, r,
-                                c.lora_scale, s));
-      LR(launch_lora_outer_bf16(xs[act[z]], in, k.lw.f32[3 + z], lora->dA[t], 1, in, n, in, r, c.lora_scale, s));
-    }
+    LR(launch_lora_shrink_mfma(st, g.nact, s));
+    LR(launch_lora_finalize(ft, g.nact, s));
+    if (dx)
+      return launch_gemm(dy, W, dx, nullptr, nullptr, n, N_dx, K_dy, K_dy, N_dx, N_dx, 0, true, dt, s, &ext,
+                         k.gemm_part, k.gemm_part_elems);
     return FLEXCO_OK;
   }
   if (dx) FLEXCO_TRY(launch_gemm(dy, W, dx, nullptr, nullptr, n, N_dx, K_dy, K_dy, N_dx, N_dx, 0, true, dt, s, nullptr,
                                  k.gemm_part, k.gemm_part_elems));
-  for (int z = 0; z < nact; ++z) {
-    const int t = targets[act[z]];
+  for (int z = 0; z < g.nact; ++z) {
+    const int t = g.targets[g.act[z]];
     int in, out;
     target_dims(c, t, &in, &out);
-    LR(launch_lora_bwd(xs[act[z]], in, boff(dy, col0[act[z]], e), K_dy, lora->A[t], lora->B[t], lora->dA[t],
+    LR(launch_lora_bwd(g.xs[g.act[z]], in, boff(dy, g.col0[g.act[z]], e), K_dy, lora->A[t], lora->B[t], lora->dA[t],
                        lora->dB[t], dx, N_dx, k.u, k.t, n, in, out, r, c.lora_scale, dt, s));
   }
   return FLEXCO_OK;
@@ -651,40 +695,45 @@ extern "C" int32_t flexco_lora_bwd(const flexco_layer_cfg* cfg, const flexco_bas
   const void* q_w = boff(ft->q_cache, w0 * qd, e);
   const float* lse_w = ft->lse + w0 * c.n_q_heads;
 
+  // ---- the four projection groups and what their LoRA gradients need ----------------------
+  const bool qkv_lora = has_target(c, FLEXCO_T_Q) || has_target(c, FLEXCO_T_K) || has_target(c, FLEXCO_T_V);
+  const bool gu_lora = has_target(c, FLEXCO_T_GATE) || has_target(c, FLEXCO_T_UP);
+  BwdGroup grp[4];
+  memset(grp, 0, sizeof(grp));
+  grp[0].n_targets = 1; grp[0].targets[0] = FLEXCO_T_DOWN; grp[0].xs[0] = k.act; grp[0].N_dx = F;
+  grp[1].n_targets = 2; grp[1].targets[0] = FLEXCO_T_GATE; grp[1].targets[1] = FLEXCO_T_UP; grp[1].col0[1] = F;
+  grp[1].xs[0] = grp[1].xs[1] = k.hn2; grp[1].N_dx = H;
+  grp[2].n_targets = 1; grp[2].targets[0] = FLEXCO_T_O; grp[2].xs[0] = attn_w; grp[2].N_dx = qd;
+  grp[3].n_targets = 3; grp[3].targets[0] = FLEXCO_T_Q; grp[3].targets[1] = FLEXCO_T_K; grp[3].targets[2] = FLEXCO_T_V;
+  grp[3].col0[1] = qd; grp[3].col0[2] = qd + kd; grp[3].xs[0] = grp[3].xs[1] = grp[3].xs[2] = k.hn; grp[3].N_dx = H;
+  for (int gi = 0; gi < 4; ++gi) plan_group(c, grp[gi]);
+  LoraOuterArgs outer;
+  memset(&outer, 0, sizeof(outer));
+  outer.n = n; outer.r = c.lora_rank; outer.scale = c.lora_scale;
+
+  // inputs of the adapted projections: rematerialised SwiGLU output (Alg. 1), the two norms
+  if (has_target(c, FLEXCO_T_DOWN)) EW(launch_swiglu_remat(gate_w, up_w, k.act, n, F, dt, s));
+  if (gu_lora) EW(launch_rmsnorm(x2_w, w->g2, k.hn2, n, H, c.rms_eps, dt, s));
+  if (qkv_lora) EW(launch_rmsnorm(x_w, w->g1, k.hn, n, H, c.rms_eps, dt, s));
+  FLEXCO_TRY(lora_bwd_prepare(c, lora, n, grp, 4, k, s));
+
   // ---- MLP side: down projection, SwiGLU, gate/up projections, second norm -------------
-  if (has_target(c, FLEXCO_T_DOWN)) EW(launch_swiglu_remat(gate_w, up_w, k.act, n, F, dt, s));   // rematerialised
-  {
-    const int tg[1] = {FLEXCO_T_DOWN}, c0[1] = {0};
-    const void* xs[1] = {k.act};
-    FLEXCO_TRY(backward_projection(c, lora, n, dY, H, w->wd, k.dact, F, tg, c0, xs, 1, k, s));
-  }
+  FLEXCO_TRY(backward_projection(c, lora, n, dY, H, w->wd, k.dact, grp[0], k, outer, s));
   EW(launch_swiglu_bwd(gate_w, up_w, k.dact, k.dgu, n, F, dt, s));
-  if (has_target(c, FLEXCO_T_GATE) || has_target(c, FLEXCO_T_UP)) EW(launch_rmsnorm(x2_w, w->g2, k.hn, n, H, c.rms_eps, dt, s));
-  {
-    const int tg[2] = {FLEXCO_T_GATE, FLEXCO_T_UP}, c0[2] = {0, F};
-    const void* xs[2] = {k.hn, k.hn};
-    FLEXCO_TRY(backward_projection(c, lora, n, k.dgu, 2 * F, w->wgu, k.dh, H, tg, c0, xs, 2, k, s));
-  }
+  FLEXCO_TRY(backward_projection(c, lora, n, k.dgu, 2 * F, w->wgu, k.dh, grp[1], k, outer, s));
   EW(launch_rmsnorm_bwd(x2_w, w->g2, k.dh, dY, k.dx2, n, H, c.rms_eps, dt, s));
   // ---- output projection ------------------------------------------------------------------
-  {
-    const int tg[1] = {FLEXCO_T_O}, c0[1] = {0};
-    const void* xs[1] = {attn_w};
-    FLEXCO_TRY(backward_projection(c, lora, n, k.dx2, H, w->wo, k.dattn, qd, tg, c0, xs, 1, k, s));
-  }
+  FLEXCO_TRY(backward_projection(c, lora, n, k.dx2, H, w->wo, k.dattn, grp[2], k, outer, s));
   // ---- attention: dQ of the window, dK/dV of every cached row before its end (Sec. 6.1) ---
   FLEXCO_TRY(attention_window_bwd_impl(c, *pool, seq_pages, win_start, win_len, q_w, attn_w, lse_w, k.dattn, k.dq,
                                        ft->dk_accum, ft->dv_accum, k.delta, s));
   // ---- q/k/v side: the window's accumulator rows are complete now (Sec. 7) ---------------
-  const bool qkv_lora = has_target(c, FLEXCO_T_Q) || has_target(c, FLEXCO_T_K) || has_target(c, FLEXCO_T_V);
-  if (!dX && !qkv_lora) return FLEXCO_OK;
-  EW(launch_rope_bwd_pack(c, k.dq, ft->dk_accum + w0 * kd, ft->dv_accum + w0 * kd, k.dqkv, win_start, n, s));
-  if (qkv_lora) EW(launch_rmsnorm(x_w, w->g1, k.hn, n, H, c.rms_eps, dt, s));
-  {
-    const int tg[3] = {FLEXCO_T_Q, FLEXCO_T_K, FLEXCO_T_V}, c0[3] = {0, qd, qd + kd};
-    const void* xs[3] = {k.hn, k.hn, k.hn};
-    FLEXCO_TRY(backward_projection(c, lora, n, k.dqkv, qkvd, w->wqkv, dX ? k.dh : nullptr, H, tg, c0, xs, 3, k, s));
+  if (dX || qkv_lora) {
+    EW(launch_rope_bwd_pack(c, k.dq, ft->dk_accum + w0 * kd, ft->dv_accum + w0 * kd, k.dqkv, win_start, n, s));
+    FLEXCO_TRY(backward_projection(c, lora, n, k.dqkv, qkvd, w->wqkv, dX ? k.dh : nullptr, grp[3], k, outer, s));
   }
+  // ---- every queued dA / dB product of the window in one launch ----------------------------
+  LR(launch_lora_outer_batch(outer, s));
   if (dX) EW(launch_rmsnorm_bwd(x_w, w->g1, k.dh, k.dx2, dX, n, H, c.rms_eps, dt, s));
   return FLEXCO_OK;
 }

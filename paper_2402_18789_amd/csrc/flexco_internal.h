@@ -10,22 +10,35 @@
 namespace flexco {
 
 // ---- argument blocks of the bf16 LoRA kernels (up to 3 matrices per launch, grid.z) ----------
+constexpr int LORA_MATS = 7;   // matrices one LoRA launch can batch: one per target (q, k, v, o, gate, up, down)
 struct LoraShrinkArgs {     // part[z][ks][row][rank] = sum over the split's k of X[z][row, k] S[z][rank, k]
-  const bf16_t* X[3]; size_t ldx[3];
-  const bf16_t* S[3]; size_t lds[3];
-  float* part[3];
+  const bf16_t* X[LORA_MATS]; size_t ldx[LORA_MATS];
+  const bf16_t* S[LORA_MATS]; size_t lds[LORA_MATS];
+  float* part[LORA_MATS];
+  int K[LORA_MATS], KS[LORA_MATS];   // contracted width and its split count, per matrix
   const int32_t* row_idx;   // rows of X to take (NULL: 0..n)
-  int n, K, KS, r;
+  int n, r;
 };
 struct LoraFinalizeArgs {
-  const float* part[3];
-  float* out_f32[3];        // [n, r] or NULL
-  bf16_t* out_ext[3];       // [rows, r] scaled, or NULL
+  const float* part[LORA_MATS];
+  float* out_f32[LORA_MATS];        // [n, r] or NULL
+  bf16_t* out_ext[LORA_MATS];       // [rows, r] scaled, or NULL
+  int KS[LORA_MATS];
   const int32_t* ext_map;   // forward: [ext_rows] index into the n shrunk rows or -1; NULL: identity
-  int ext_rows, n, r, KS;
+  int ext_rows, n, r;
   float scale;
 };
-struct LoraTransposeArgs { const bf16_t* B[3]; bf16_t* Bt[3]; int out[3]; int r; };
+struct LoraTransposeArgs { const bf16_t* B[LORA_MATS]; bf16_t* Bt[LORA_MATS]; int out[LORA_MATS]; int r; };
+// batch of rank-r gradient products  G_e(i, j) += scale * sum_m X_e[m, i] U_e[m, j], m < n, i < n_long_e, j < r
+constexpr int LORA_OUTER_MAX = 2 * LORA_MATS;
+struct LoraOuterArgs {
+  const bf16_t* X[LORA_OUTER_MAX]; size_t ldx[LORA_OUTER_MAX];
+  const float* U[LORA_OUTER_MAX];            // [n, r]
+  float* G[LORA_OUTER_MAX]; size_t g_i[LORA_OUTER_MAX], g_j[LORA_OUTER_MAX];   // element (i, j) at G[i g_i + j g_j]
+  int n_long[LORA_OUTER_MAX];
+  int count, n, r;
+  float scale;
+};
 // rank-r extension of a projection GEMM (see gemm_mfma.hip)
 struct GemmExt {
   int n, r;
@@ -71,6 +84,7 @@ int lora_shrink_splits(int n_rows, int K);
 int32_t launch_lora_shrink_mfma(const LoraShrinkArgs& a, int n_mats, hipStream_t s);
 int32_t launch_lora_finalize(const LoraFinalizeArgs& a, int n_mats, hipStream_t s);
 int32_t launch_lora_transpose(const LoraTransposeArgs& a, int n_mats, hipStream_t s);
+int32_t launch_lora_outer_batch(const LoraOuterArgs& a, hipStream_t s);
 int32_t launch_lora_outer_bf16(const void* X, size_t ldx, const float* U, float* G, size_t g_i, size_t g_j, int n,
                                int n_long, int r, float scale, hipStream_t s);
 

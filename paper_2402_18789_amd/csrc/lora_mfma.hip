@@ -13,6 +13,7 @@
 //   outer    dB += scale dy^T u,  dA += scale t^T x : every output element is a sum over
 //            the window's rows only; plain FMA code, 64 consecutive outputs per wavefront,
 //            rows interleaved over the block's 4 wavefronts, fixed-order LDS reduction.
+#include <cstring>
 #include "flexco_internal.h"
 #include "device_types.h"
 
@@ -31,7 +32,8 @@ __global__ __launch_bounds__(256) void lora_shrink_kernel(LoraShrinkArgs a) {
   const int row = tile * 16 + m;
   const int rclamp = row < a.n ? row : 0;
   const size_t src_row = a.row_idx ? (size_t)a.row_idx[rclamp] : (size_t)rclamp;
-  const int k_blk = a.K / a.KS, k_wave = k_blk / 4;
+  if (ks >= a.KS[z]) return;   // matrices of one launch may be split differently
+  const int k_blk = a.K[z] / a.KS[z], k_wave = k_blk / 4;
   const int k0 = ks * k_blk + wave * k_wave, k1 = k0 + k_wave;
   const bf16_t* xp = X + src_row * a.ldx[z] + g * 8;
   const bf16_t* sp[RT];
@@ -83,7 +85,7 @@ __global__ __launch_bounds__(256) void lora_finalize_kernel(LoraFinalizeArgs a) 
   const int src = a.ext_map ? a.ext_map[row] : row;
   float v = 0.f;
   if (src >= 0)
-    for (int ks = 0; ks < a.KS; ++ks) v += a.part[z][((size_t)ks * a.n + src) * a.r + rank];
+    for (int ks = 0; ks < a.KS[z]; ++ks) v += a.part[z][((size_t)ks * a.n + src) * a.r + rank];
   if (a.out_f32[z] && src >= 0) a.out_f32[z][(size_t)src * a.r + rank] = v;
   if (a.out_ext[z]) a.out_ext[z][idx] = (bf16_t)(v * a.scale);
 }
@@ -100,10 +102,15 @@ __global__ __launch_bounds__(256) void lora_transpose_kernel(LoraTransposeArgs a
 // Rows are taken in chunks of 128: the chunk's U rows are staged in LDS (broadcast reads), each
 // wavefront owns 32 rows of the chunk and issues their 32 loads of X together.
 template <int R>
-__global__ __launch_bounds__(256) void lora_outer_mfma_path_kernel(const bf16_t* __restrict__ X, size_t ldx,
-                                                                   const float* __restrict__ U, float* __restrict__ G,
-                                                                   size_t g_i, size_t g_j, int n, int n_long, int r,
-                                                                   float scale) {
+__global__ __launch_bounds__(256) void lora_outer_mfma_path_kernel(LoraOuterArgs a) {
+  const int e = blockIdx.y;
+  const int n = a.n, r = a.r, n_long = a.n_long[e];
+  if ((int)blockIdx.x * 64 >= n_long) return;   // entries of one launch differ in width
+  const bf16_t* __restrict__ X = a.X[e];
+  const float* __restrict__ U = a.U[e];
+  float* __restrict__ G = a.G[e];
+  const size_t ldx = a.ldx[e], g_i = a.g_i[e], g_j = a.g_j[e];
+  const float scale = a.scale;
   extern __shared__ float smem[];   // us[128][R], later reused as red[3][64][R]
   constexpr int CH = 128, RB = 32;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -172,7 +179,9 @@ int lora_shrink_splits(int n_rows, int K) {
 
 int32_t launch_lora_shrink_mfma(const LoraShrinkArgs& a, int n_mats, hipStream_t s) {
   if (a.n == 0 || n_mats == 0) return FLEXCO_OK;
-  const dim3 grid((a.n + 15) / 16, a.KS, n_mats);
+  int ks_max = 1;
+  for (int z = 0; z < n_mats; ++z) ks_max = a.KS[z] > ks_max ? a.KS[z] : ks_max;
+  const dim3 grid((a.n + 15) / 16, ks_max, n_mats);
   const int rt = (a.r + 15) / 16;
   switch (rt) {
     case 1: hipLaunchKernelGGL(lora_shrink_kernel<1>, grid, dim3(256), 0, s, a); break;
@@ -199,21 +208,27 @@ int32_t launch_lora_transpose(const LoraTransposeArgs& a, int n_mats, hipStream_
   return post("lora_transpose");
 }
 
+int32_t launch_lora_outer_batch(const LoraOuterArgs& a, hipStream_t s) {
+  if (a.n == 0 || a.count == 0) return FLEXCO_OK;
+  int mx = 0;
+  for (int e = 0; e < a.count; ++e) mx = a.n_long[e] > mx ? a.n_long[e] : mx;
+  const dim3 grid((mx + 63) / 64, a.count);
+  if (a.r <= 16)
+    hipLaunchKernelGGL(lora_outer_mfma_path_kernel<16>, grid, dim3(256), 192 * 16 * sizeof(float), s, a);
+  else if (a.r <= 32)
+    hipLaunchKernelGGL(lora_outer_mfma_path_kernel<32>, grid, dim3(256), 192 * 32 * sizeof(float), s, a);
+  else
+    hipLaunchKernelGGL(lora_outer_mfma_path_kernel<64>, grid, dim3(256), 192 * 64 * sizeof(float), s, a);
+  return post("lora_outer");
+}
+
 int32_t launch_lora_outer_bf16(const void* X, size_t ldx, const float* U, float* G, size_t g_i, size_t g_j, int n,
                                int n_long, int r, float scale, hipStream_t s) {
-  if (n == 0) return FLEXCO_OK;
-  const dim3 grid((n_long + 63) / 64);
-  const bf16_t* x = (const bf16_t*)X;
-  if (r <= 16)
-    hipLaunchKernelGGL(lora_outer_mfma_path_kernel<16>, grid, dim3(256), 192 * 16 * sizeof(float), s, x, ldx, U, G,
-                       g_i, g_j, n, n_long, r, scale);
-  else if (r <= 32)
-    hipLaunchKernelGGL(lora_outer_mfma_path_kernel<32>, grid, dim3(256), 192 * 32 * sizeof(float), s, x, ldx, U, G,
-                       g_i, g_j, n, n_long, r, scale);
-  else
-    hipLaunchKernelGGL(lora_outer_mfma_path_kernel<64>, grid, dim3(256), 192 * 64 * sizeof(float), s, x, ldx, U, G,
-                       g_i, g_j, n, n_long, r, scale);
-  return post("lora_outer");
+  LoraOuterArgs a;
+  memset(&a, 0, sizeof(a));
+  a.X[0] = (const bf16_t*)X; a.ldx[0] = ldx; a.U[0] = U; a.G[0] = G; a.g_i[0] = g_i; a.g_j[0] = g_j; a.n_long[0] = n_long;
+  a.count = 1; a.n = n; a.r = r; a.scale = scale;
+  return launch_lora_outer_batch(a, s);
 }
 
 }  // namespace flexco
