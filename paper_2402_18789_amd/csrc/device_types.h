@@ -16,4 +16,36 @@ __device__ inline float ld(const bf16_t* p) { return (float)*p; }
 __device__ inline void st(float* p, float v) { *p = v; }
 __device__ inline void st(bf16_t* p, float v) { *p = (bf16_t)v; }   // round to nearest even
 
+
+// 16-byte row accesses of the element-wise kernels: N consecutive elements as floats
+template <typename T> struct Vec;
+template <> struct Vec<float> {
+  static constexpr int N = 4;
+  __device__ static void load(const float* p, float* v) {
+    const f32x4 t = *reinterpret_cast<const f32x4*>(p);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = t[i];
+  }
+  __device__ static void store(float* p, const float* v) {
+    f32x4 t;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) t[i] = v[i];
+    *reinterpret_cast<f32x4*>(p) = t;
+  }
+};
+template <> struct Vec<bf16_t> {
+  static constexpr int N = 8;
+  __device__ static void load(const bf16_t* p, float* v) {
+    const bf16x8 t = *reinterpret_cast<const bf16x8*>(p);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = (float)t[i];
+  }
+  __device__ static void store(bf16_t* p, const float* v) {
+    bf16x8 t;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) t[i] = (bf16_t)v[i];   // round to nearest even
+    *reinterpret_cast<bf16x8*>(p) = t;
+  }
+};
+
 }  // namespace flexco

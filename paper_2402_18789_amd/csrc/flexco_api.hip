@@ -616,13 +616,21 @@ extern "C" int32_t flexco_layer_forward(const flexco_layer_cfg* cfg, const flexc
   if (ft) {
     const int n = m.n_ft;
     const size_t t0 = m.ft_tok0, p0 = m.ft_pos0;
-    EW(launch_copy_rows(boff(x_in, t0 * H, e), H * e, boff(ft->saved_x, p0 * H, e), H * e, n, H * e, s));
-    EW(launch_copy_rows(boff(k.x2, t0 * H, e), H * e, boff(ft->saved_x2, p0 * H, e), H * e, n, H * e, s));
-    EW(launch_copy_rows(boff(k.gu, t0 * 2 * F, e), 2 * F * e, boff(ft->saved_gate, p0 * F, e), F * e, n, F * e, s));
-    EW(launch_copy_rows(boff(k.gu, t0 * 2 * F + F, e), 2 * F * e, boff(ft->saved_up, p0 * F, e), F * e, n, F * e, s));
-    EW(launch_copy_rows(boff(k.attn, t0 * qd, e), qd * e, boff(ft->saved_attn, p0 * qd, e), qd * e, n, qd * e, s));
-    EW(launch_copy_rows(k.lse + t0 * c.n_q_heads, c.n_q_heads * 4, ft->lse + p0 * c.n_q_heads, c.n_q_heads * 4, n,
-                        c.n_q_heads * 4, s));
+    CopyRowsBatch cb;
+    size_t wb[8];
+    memset(&cb, 0, sizeof(cb));
+    auto add = [&](const void* src, size_t ld_src, void* dst, size_t ld_dst, size_t width) {
+      const int q = cb.count++;
+      cb.src[q] = (const char*)src; cb.ld_src[q] = ld_src; cb.dst[q] = (char*)dst; cb.ld_dst[q] = ld_dst;
+      cb.width16[q] = (int)(width / 16); wb[q] = width;
+    };
+    add(boff(x_in, t0 * H, e), H * e, boff(ft->saved_x, p0 * H, e), H * e, H * e);
+    add(boff(k.x2, t0 * H, e), H * e, boff(ft->saved_x2, p0 * H, e), H * e, H * e);
+    add(boff(k.gu, t0 * 2 * F, e), 2 * F * e, boff(ft->saved_gate, p0 * F, e), F * e, F * e);
+    add(boff(k.gu, t0 * 2 * F + F, e), 2 * F * e, boff(ft->saved_up, p0 * F, e), F * e, F * e);
+    add(boff(k.attn, t0 * qd, e), qd * e, boff(ft->saved_attn, p0 * qd, e), qd * e, qd * e);
+    add(k.lse + t0 * c.n_q_heads, c.n_q_heads * 4, ft->lse + p0 * c.n_q_heads, c.n_q_heads * 4, (size_t)c.n_q_heads * 4);
+    EW(launch_copy_rows_batch(cb, n, wb, s));
   }
   return FLEXCO_OK;
 }

@@ -100,6 +100,13 @@ int32_t launch_swiglu(const void* gu, void* act, int T, int F, int dtype, hipStr
 int32_t launch_swiglu_bwd(const void* gate, const void* up, const void* dact, void* dgu, int n, int F, int dtype,
                           hipStream_t s);
 int32_t launch_swiglu_remat(const void* gate, const void* up, void* act, int n, int F, int dtype, hipStream_t s);
+struct CopyRowsBatch {
+  const char* src[8]; size_t ld_src[8];
+  char* dst[8]; size_t ld_dst[8];
+  int width16[8];       // row width in 16-byte units
+  int count;
+};
+int32_t launch_copy_rows_batch(const CopyRowsBatch& b, int n_rows, size_t const* width_bytes, hipStream_t s);
 int32_t launch_copy_rows(const void* src, size_t ld_src_bytes, void* dst, size_t ld_dst_bytes, int n_rows,
                          size_t width_bytes, hipStream_t s);
 

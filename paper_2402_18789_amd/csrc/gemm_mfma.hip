@@ -20,9 +20,8 @@
 //     global address a lane fetches) so that the ds_read_b128 operand fetches of 16 consecutive
 //     rows hit 64 distinct banks.
 //   * Input-gradient form: k-steps of 64, two LDS buffers filled through two sets of staging
-//     registers; the W tile is [64][BN + 8] (k-major as in memory), an operand fragment (8
-//     consecutive k for one column) is gathered with 16-bit LDS reads; the 16-byte row padding
-//     puts the two k-halves of a wavefront on disjoint banks.
+//     registers; the W tile is [64][BN + 32] (k-major as in memory), an operand fragment (8
+//     consecutive k for one column) comes from two transposing LDS reads (ds_read_b64_tr_b16).
 // Work-group ids are remapped so that ids that land on the same XCD (id mod 8) work on
 // neighbouring tiles, M fastest: the W tile they share stays in that XCD's L2.
 #include "flexco_internal.h"
@@ -34,6 +33,8 @@ namespace {
 
 constexpr int BK = 64;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+#define FLEXCO_LDS __attribute__((address_space(3)))
 
 #define FLEXCO_GP(p) ((const __attribute__((address_space(1))) void*)(p))
 #define FLEXCO_LP(p) ((__attribute__((address_space(3))) void*)(p))
@@ -44,8 +45,8 @@ __device__ inline int swz(int row, int chunk) { return chunk ^ ((row >> 1) & 7);
 template <int BM, int BN>
 struct SmemT {
   static constexpr int A_ELEMS = BM * BK;
-  static constexpr int B_LD = BN + 8;
-  static constexpr int B_ELEMS = BK * (BN + 8);
+  static constexpr int B_LD = BN + 32;   // 64 bytes of row padding: 4 consecutive rows x 64 bytes tile the 64 banks
+  static constexpr int B_ELEMS = BK * (BN + 32);
   static constexpr size_t BYTES = 2 * (size_t)(A_ELEMS + B_ELEMS) * sizeof(bf16_t);
 };
 
@@ -238,13 +239,20 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
     using S = SmemT<BM, BN>;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     bf16_t* As = reinterpret_cast<bf16_t*>(smem_raw);                 // [2][BM][64] swizzled
-    bf16_t* Bs = As + 2 * S::A_ELEMS;                                 // [2][64][BN + 8]
+    bf16_t* Bs = As + 2 * S::A_ELEMS;                                 // [2][64][BN + 32]
     constexpr int A_PASSES = BM / 32;                                  // 8 chunks per row, 32 rows per pass
     constexpr int B_PASSES = (BK * (BN / 8)) / 256;
     u32x4 sa0[A_PASSES], sb0[B_PASSES], sa1[A_PASSES], sb1[B_PASSES];   // two sets of staging registers
     const int a_c = tid & 7, a_r = tid >> 3;
     constexpr int BCH = BN / 8;                                        // chunks per row of the W tile
     const int bt_c = tid % BCH, bt_r = tid / BCH;
+    // Operand fragments of W come from transposing LDS reads (ds_read_b64_tr_b16): within a group
+    // of 16 lanes, lane s hands in the address of 4 consecutive columns, 4 (s % 4), of row s / 4,
+    // and lane i receives column i of those 4 rows - i.e. 4 consecutive k for one column, the
+    // MFMA operand order.  Group g of the wavefront covers columns 16 (g % 2) .. + 16 and the
+    // k-half g / 2; two reads (rows 0..3 and 4..7) make the 8 k of a fragment.
+    const int tr_k = 8 * (lane >> 5) + ((lane & 15) >> 2);
+    const int tr_n = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
 
 #define FLEXCO_LOAD_TILES(k0_, ra, rb)                                                                \
   {                                                                                                   \
@@ -279,8 +287,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
       af_[i] = *reinterpret_cast<const bf16x8*>(as + r_ * BK + swz(r_, (kk_) * 2 + kg) * 8);          \
     }                                                                                                 \
     _Pragma("unroll") for (int j = 0; j < NT; ++j) {                                                  \
-      const bf16_t* col_ = bs + ((kk_) * 16 + kg * 8) * S::B_LD + wn0 + j * 32 + l32;                 \
-      _Pragma("unroll") for (int e = 0; e < 8; ++e) bf_[j][e] = col_[e * S::B_LD];                    \
+      const bf16_t* blk_ = bs + ((kk_) * 16 + tr_k) * S::B_LD + wn0 + j * 32 + tr_n;                  \
+      const s16x4 lo_ = __builtin_amdgcn_ds_read_tr16_b64_v4i16((FLEXCO_LDS s16x4*)blk_);             \
+      const s16x4 hi_ = __builtin_amdgcn_ds_read_tr16_b64_v4i16((FLEXCO_LDS s16x4*)(blk_ + 4 * S::B_LD)); \
+      bf_[j] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo_, hi_, 0, 1, 2, 3, 4, 5, 6, 7)); \
     }                                                                                                 \
   }
     // Software pipeline over k-steps of 64 with two LDS buffers and two sets of staging

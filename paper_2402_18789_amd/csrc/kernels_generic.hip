@@ -5,6 +5,7 @@
 // the bf16 configurations that are bound by HBM traffic or are tiny (norms, RoPE, SwiGLU,
 // rank-r LoRA products).  The dense bf16 contractions live in gemm_mfma.hip /
 // attn_mfma.hip.
+#include <initializer_list>
 #include "flexco_internal.h"
 #include "device_types.h"
 
@@ -35,42 +36,93 @@ __device__ inline float block_sum256(float v, float* red /* >= 4 floats of LDS *
 // --------------------------------------------------------------------------------------
 // RMSNorm forward / backward (one block of 256 threads per row)
 // --------------------------------------------------------------------------------------
-template <typename T>
+// VEC: rows are read and written in 16-byte pieces (the host picks it when H is a multiple of the
+// vector width and every pointer and row pitch is 16-byte aligned).
+template <typename T, bool VEC>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const T* __restrict__ x, const T* __restrict__ g,
                                                       T* __restrict__ h, int H, float eps) {
   __shared__ float red[4];
+  constexpr int N = Vec<T>::N;
   const size_t row = blockIdx.x;
   const T* xr = x + row * H;
   float ss = 0.f;
-  for (int i = threadIdx.x; i < H; i += 256) { float v = ld(xr + i); ss += v * v; }
+  if (VEC) {
+    for (int i = threadIdx.x * N; i < H; i += 256 * N) {
+      float v[N];
+      Vec<T>::load(xr + i, v);
+#pragma unroll
+      for (int j = 0; j < N; ++j) ss += v[j] * v[j];
+    }
+  } else {
+    for (int i = threadIdx.x; i < H; i += 256) { float v = ld(xr + i); ss += v * v; }
+  }
   ss = block_sum256(ss, red);
   const float rstd = 1.0f / sqrtf(ss / H + eps);
-  for (int i = threadIdx.x; i < H; i += 256) st(h + row * H + i, ld(xr + i) * rstd * ld(g + i));
+  if (VEC) {
+    for (int i = threadIdx.x * N; i < H; i += 256 * N) {
+      float v[N], gv[N];
+      Vec<T>::load(xr + i, v);
+      Vec<T>::load(g + i, gv);
+#pragma unroll
+      for (int j = 0; j < N; ++j) v[j] = v[j] * rstd * gv[j];
+      Vec<T>::store(h + row * H + i, v);
+    }
+  } else {
+    for (int i = threadIdx.x; i < H; i += 256) st(h + row * H + i, ld(xr + i) * rstd * ld(g + i));
+  }
 }
 
 // dx = rstd * (g * dh) - x * rstd^3 * mean(x * g * dh)  (+ add)
-template <typename T>
+template <typename T, bool VEC>
 __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* __restrict__ x, const T* __restrict__ g,
                                                           const T* __restrict__ dh, const T* __restrict__ add,
                                                           T* __restrict__ dx, int H, float eps) {
   __shared__ float red[4];
+  constexpr int N = Vec<T>::N;
   const size_t row = blockIdx.x;
   const T* xr = x + row * H;
   const T* dr = dh + row * H;
   float ss = 0.f, sd = 0.f;
-  for (int i = threadIdx.x; i < H; i += 256) {
-    float v = ld(xr + i);
-    ss += v * v;
-    sd += v * ld(g + i) * ld(dr + i);
+  if (VEC) {
+    for (int i = threadIdx.x * N; i < H; i += 256 * N) {
+      float v[N], gv[N], dv[N];
+      Vec<T>::load(xr + i, v);
+      Vec<T>::load(g + i, gv);
+      Vec<T>::load(dr + i, dv);
+#pragma unroll
+      for (int j = 0; j < N; ++j) { ss += v[j] * v[j]; sd += v[j] * gv[j] * dv[j]; }
+    }
+  } else {
+    for (int i = threadIdx.x; i < H; i += 256) {
+      float v = ld(xr + i);
+      ss += v * v;
+      sd += v * ld(g + i) * ld(dr + i);
+    }
   }
   ss = block_sum256(ss, red);
   sd = block_sum256(sd, red);
   const float rstd = 1.0f / sqrtf(ss / H + eps);
   const float coef = rstd * rstd * rstd * sd / H;
-  for (int i = threadIdx.x; i < H; i += 256) {
-    float v = rstd * ld(g + i) * ld(dr + i) - ld(xr + i) * coef;
-    if (add) v += ld(add + row * H + i);
-    st(dx + row * H + i, v);
+  if (VEC) {
+    for (int i = threadIdx.x * N; i < H; i += 256 * N) {
+      float v[N], gv[N], dv[N], av[N];
+      Vec<T>::load(xr + i, v);
+      Vec<T>::load(g + i, gv);
+      Vec<T>::load(dr + i, dv);
+      if (add) Vec<T>::load(add + row * H + i, av);
+#pragma unroll
+      for (int j = 0; j < N; ++j) {
+        v[j] = rstd * gv[j] * dv[j] - v[j] * coef;
+        if (add) v[j] += av[j];
+      }
+      Vec<T>::store(dx + row * H + i, v);
+    }
+  } else {
+    for (int i = threadIdx.x; i < H; i += 256) {
+      float v = rstd * ld(g + i) * ld(dr + i) - ld(xr + i) * coef;
+      if (add) v += ld(add + row * H + i);
+      st(dx + row * H + i, v);
+    }
   }
 }
 
@@ -174,42 +226,71 @@ __global__ __launch_bounds__(256) void rope_bwd_pack_kernel(const T* __restrict_
 // --------------------------------------------------------------------------------------
 // SwiGLU forward / backward
 // --------------------------------------------------------------------------------------
-template <typename T>
+template <typename T, bool VEC>
 __global__ __launch_bounds__(256) void swiglu_kernel(const T* __restrict__ gu, T* __restrict__ act, int F) {
+  constexpr int N = VEC ? Vec<T>::N : 1;
   const size_t row = blockIdx.y;
-  const int i = blockIdx.x * 256 + threadIdx.x;
+  const int i = (blockIdx.x * 256 + threadIdx.x) * N;
   if (i >= F) return;
-  const float g = ld(gu + row * 2 * F + i), u = ld(gu + row * 2 * F + F + i);
-  st(act + row * F + i, g / (1.0f + __expf(-g)) * u);
+  float g[N], u[N];
+  if (VEC) { Vec<T>::load(gu + row * 2 * F + i, g); Vec<T>::load(gu + row * 2 * F + F + i, u); }
+  else { g[0] = ld(gu + row * 2 * F + i); u[0] = ld(gu + row * 2 * F + F + i); }
+#pragma unroll
+  for (int j = 0; j < N; ++j) g[j] = g[j] / (1.0f + __expf(-g[j])) * u[j];
+  if (VEC) Vec<T>::store(act + row * F + i, g); else st(act + row * F + i, g[0]);
 }
 
-// from saved gate, up and dact: dgu = [dgate | dup]; optionally also act (rematerialised)
-template <typename T>
+// from saved gate, up and dact: dgu = [dgate | dup]
+template <typename T, bool VEC>
 __global__ __launch_bounds__(256) void swiglu_bwd_kernel(const T* __restrict__ gate, const T* __restrict__ up,
                                                          const T* __restrict__ dact, T* __restrict__ dgu,
                                                          int F) {
+  constexpr int N = VEC ? Vec<T>::N : 1;
   const size_t row = blockIdx.y;
-  const int i = blockIdx.x * 256 + threadIdx.x;
+  const int i = (blockIdx.x * 256 + threadIdx.x) * N;
   if (i >= F) return;
-  const float g = ld(gate + row * F + i), u = ld(up + row * F + i), da = ld(dact + row * F + i);
-  const float sg = 1.0f / (1.0f + __expf(-g));
-  st(dgu + row * 2 * F + i, da * u * (sg + g * sg * (1.0f - sg)));
-  st(dgu + row * 2 * F + F + i, da * g * sg);
+  float g[N], u[N], da[N];
+  if (VEC) { Vec<T>::load(gate + row * F + i, g); Vec<T>::load(up + row * F + i, u); Vec<T>::load(dact + row * F + i, da); }
+  else { g[0] = ld(gate + row * F + i); u[0] = ld(up + row * F + i); da[0] = ld(dact + row * F + i); }
+  float dg[N], du[N];
+#pragma unroll
+  for (int j = 0; j < N; ++j) {
+    const float sg = 1.0f / (1.0f + __expf(-g[j]));
+    dg[j] = da[j] * u[j] * (sg + g[j] * sg * (1.0f - sg));
+    du[j] = da[j] * g[j] * sg;
+  }
+  if (VEC) { Vec<T>::store(dgu + row * 2 * F + i, dg); Vec<T>::store(dgu + row * 2 * F + F + i, du); }
+  else { st(dgu + row * 2 * F + i, dg[0]); st(dgu + row * 2 * F + F + i, du[0]); }
 }
 
-template <typename T>
+// act = silu(gate) * up from the saved gate and up (rematerialisation, Alg. 1)
+template <typename T, bool VEC>
 __global__ __launch_bounds__(256) void swiglu_remat_kernel(const T* __restrict__ gate, const T* __restrict__ up,
                                                            T* __restrict__ act, int F) {
+  constexpr int N = VEC ? Vec<T>::N : 1;
   const size_t row = blockIdx.y;
-  const int i = blockIdx.x * 256 + threadIdx.x;
+  const int i = (blockIdx.x * 256 + threadIdx.x) * N;
   if (i >= F) return;
-  const float g = ld(gate + row * F + i), u = ld(up + row * F + i);
-  st(act + row * F + i, g / (1.0f + __expf(-g)) * u);
+  float g[N], u[N];
+  if (VEC) { Vec<T>::load(gate + row * F + i, g); Vec<T>::load(up + row * F + i, u); }
+  else { g[0] = ld(gate + row * F + i); u[0] = ld(up + row * F + i); }
+#pragma unroll
+  for (int j = 0; j < N; ++j) g[j] = g[j] / (1.0f + __expf(-g[j])) * u[j];
+  if (VEC) Vec<T>::store(act + row * F + i, g); else st(act + row * F + i, g[0]);
 }
 
 // --------------------------------------------------------------------------------------
 // strided row copy: dst row i = src row i, `width` units of V (uint4 = 16 bytes, or 4-byte words)
 // --------------------------------------------------------------------------------------
+// several strided row copies in one launch (blockIdx.z picks the copy); widths in 16-byte units
+__global__ __launch_bounds__(256) void copy_rows_batch_kernel(CopyRowsBatch b) {
+  const int e = blockIdx.z;
+  const size_t row = blockIdx.y;
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= b.width16[e]) return;
+  reinterpret_cast<uint4*>(b.dst[e] + row * b.ld_dst[e])[i] = reinterpret_cast<const uint4*>(b.src[e] + row * b.ld_src[e])[i];
+}
+
 template <typename V>
 __global__ __launch_bounds__(256) void copy_rows_kernel(const char* __restrict__ src, size_t ld_src,
                                                         char* __restrict__ dst, size_t ld_dst, int width) {
@@ -401,18 +482,34 @@ int32_t launch_gemm_generic(const void* A, const void* W, void* C, const void* b
   return post_launch("gemm_generic");
 }
 
+// 16-byte row accesses are possible when the width is a multiple of 16 bytes and everything is aligned
+static bool vec_ok(int dtype, int width, std::initializer_list<const void*> ptrs) {
+  const int nvec = dtype == FLEXCO_BF16 ? 8 : 4;
+  if (width % nvec != 0) return false;
+  for (const void* p : ptrs)
+    if (p && !aligned16(p)) return false;
+  return true;
+}
+#define DISPATCH_TV(dtype, vec, ...)                                  \
+  do {                                                               \
+    if (vec) { constexpr bool VEC = true; DISPATCH_T(dtype, __VA_ARGS__); }  \
+    else { constexpr bool VEC = false; DISPATCH_T(dtype, __VA_ARGS__); }     \
+  } while (0)
+
 int32_t launch_rmsnorm(const void* x, const void* g, void* h, int T_, int H, float eps, int dtype, hipStream_t s) {
   if (T_ == 0) return FLEXCO_OK;
-  DISPATCH_T(dtype, hipLaunchKernelGGL((rmsnorm_kernel<T>), dim3(T_), dim3(256), 0, s, (const T*)x, (const T*)g,
-                                       (T*)h, H, eps));
+  const bool vec = vec_ok(dtype, H, {x, g, h});
+  DISPATCH_TV(dtype, vec, hipLaunchKernelGGL((rmsnorm_kernel<T, VEC>), dim3(T_), dim3(256), 0, s, (const T*)x,
+                                             (const T*)g, (T*)h, H, eps));
   return post_launch("rmsnorm");
 }
 
 int32_t launch_rmsnorm_bwd(const void* x, const void* g, const void* dh, const void* add, void* dx, int T_, int H,
                            float eps, int dtype, hipStream_t s) {
   if (T_ == 0) return FLEXCO_OK;
-  DISPATCH_T(dtype, hipLaunchKernelGGL((rmsnorm_bwd_kernel<T>), dim3(T_), dim3(256), 0, s, (const T*)x,
-                                       (const T*)g, (const T*)dh, (const T*)add, (T*)dx, H, eps));
+  const bool vec = vec_ok(dtype, H, {x, g, dh, add, dx});
+  DISPATCH_TV(dtype, vec, hipLaunchKernelGGL((rmsnorm_bwd_kernel<T, VEC>), dim3(T_), dim3(256), 0, s, (const T*)x,
+                                             (const T*)g, (const T*)dh, (const T*)add, (T*)dx, H, eps));
   return post_launch("rmsnorm_bwd");
 }
 
@@ -439,22 +536,50 @@ int32_t launch_rope_bwd_pack(const flexco_layer_cfg& c, const void* dq, const fl
 
 int32_t launch_swiglu(const void* gu, void* act, int T_, int F, int dtype, hipStream_t s) {
   if (T_ == 0) return FLEXCO_OK;
-  DISPATCH_T(dtype, hipLaunchKernelGGL((swiglu_kernel<T>), dim3((F + 255) / 256, T_), dim3(256), 0, s,
-                                       (const T*)gu, (T*)act, F));
+  const bool vec = vec_ok(dtype, F, {gu, act});
+  const int per = 256 * (vec ? (dtype == FLEXCO_BF16 ? 8 : 4) : 1);
+  DISPATCH_TV(dtype, vec, hipLaunchKernelGGL((swiglu_kernel<T, VEC>), dim3((F + per - 1) / per, T_), dim3(256), 0, s,
+                                             (const T*)gu, (T*)act, F));
   return post_launch("swiglu");
 }
 
 int32_t launch_swiglu_bwd(const void* gate, const void* up, const void* dact, void* dgu, int n, int F, int dtype,
                           hipStream_t s) {
-  DISPATCH_T(dtype, hipLaunchKernelGGL((swiglu_bwd_kernel<T>), dim3((F + 255) / 256, n), dim3(256), 0, s,
-                                       (const T*)gate, (const T*)up, (const T*)dact, (T*)dgu, F));
+  if (n == 0) return FLEXCO_OK;
+  const bool vec = vec_ok(dtype, F, {gate, up, dact, dgu});
+  const int per = 256 * (vec ? (dtype == FLEXCO_BF16 ? 8 : 4) : 1);
+  DISPATCH_TV(dtype, vec, hipLaunchKernelGGL((swiglu_bwd_kernel<T, VEC>), dim3((F + per - 1) / per, n), dim3(256), 0,
+                                             s, (const T*)gate, (const T*)up, (const T*)dact, (T*)dgu, F));
   return post_launch("swiglu_bwd");
 }
 
 int32_t launch_swiglu_remat(const void* gate, const void* up, void* act, int n, int F, int dtype, hipStream_t s) {
-  DISPATCH_T(dtype, hipLaunchKernelGGL((swiglu_remat_kernel<T>), dim3((F + 255) / 256, n), dim3(256), 0, s,
-                                       (const T*)gate, (const T*)up, (T*)act, F));
+  if (n == 0) return FLEXCO_OK;
+  const bool vec = vec_ok(dtype, F, {gate, up, act});
+  const int per = 256 * (vec ? (dtype == FLEXCO_BF16 ? 8 : 4) : 1);
+  DISPATCH_TV(dtype, vec, hipLaunchKernelGGL((swiglu_remat_kernel<T, VEC>), dim3((F + per - 1) / per, n), dim3(256), 0,
+                                             s, (const T*)gate, (const T*)up, (T*)act, F));
   return post_launch("swiglu_remat");
+}
+
+// Several row copies with the same row count in one launch; falls back to one launch per copy when
+// a copy is not made of aligned 16-byte pieces.
+int32_t launch_copy_rows_batch(const CopyRowsBatch& b, int n_rows, size_t const* width_bytes, hipStream_t s) {
+  if (n_rows == 0 || b.count == 0) return FLEXCO_OK;
+  bool v16 = true;
+  int wmax = 0;
+  for (int e = 0; e < b.count; ++e) {
+    v16 = v16 && width_bytes[e] % 16 == 0 && b.ld_src[e] % 16 == 0 && b.ld_dst[e] % 16 == 0 && aligned16(b.src[e]) &&
+          aligned16(b.dst[e]);
+    wmax = b.width16[e] > wmax ? b.width16[e] : wmax;
+  }
+  if (!v16) {
+    for (int e = 0; e < b.count; ++e)
+      FLEXCO_TRY(launch_copy_rows(b.src[e], b.ld_src[e], b.dst[e], b.ld_dst[e], n_rows, width_bytes[e], s));
+    return FLEXCO_OK;
+  }
+  hipLaunchKernelGGL(copy_rows_batch_kernel, dim3((wmax + 255) / 256, n_rows, b.count), dim3(256), 0, s, b);
+  return post_launch("copy_rows_batch");
 }
 
 int32_t launch_copy_rows(const void* src, size_t ld_src_bytes, void* dst, size_t ld_dst_bytes, int n_rows,
