@@ -6,17 +6,24 @@
 // and rematerialises P).  With delta_i = sum_d dO_id O_id:
 //     P_ij = exp(q_i . k_j / sqrt(d) - lse_i)           (j <= position of i)
 //     dP_ij = dO_i . v_j ,   dS_ij = P_ij (dP_ij - delta_i)
-//     dQ_i = sum_j dS_ij k_j / sqrt(d)                   -> kernel A, one block per 64 rows x head
+//     dQ_i = sum_j dS_ij k_j / sqrt(d)                   -> kernel A, one block per 32 rows x head
 //     dK_j = sum_i dS_ij q_i / sqrt(d),  dV_j = sum_i P_ij dO_i   summed over the window's rows
 //            and over the query heads of the kv group     -> kernel B, one block per 64 keys x kv head
 // Two kernels, each owning its outputs: no atomics, results do not depend on scheduling.  dK/dV are
 // added into the KV-gradient accumulator rows [0, l) (Sec. 7).
 //
-// bf16, head_dim 128, page_size 16.  All products are v_mfma_f32_16x16x32_bf16.  Operands whose
-// contracted index is contiguous in memory (K rows, Q rows, dO rows) are used as they are;
-// operands that must be read "across" their rows (V and K^T in kernel A; Q^T, dO^T in kernel B)
-// are staged in LDS once per block and gathered with 16-bit reads; row strides are padded so
-// that the four k-groups of a wavefront fall on disjoint banks.
+// bf16, head_dim 128, page_size 16.  All products are v_mfma_f32_16x16x32_bf16.
+//   * The tiles a block walks over (K and V pages in kernel A; Q and dO rows in kernel B) go from
+//     global memory straight into LDS (global_load_lds_dwordx4, lane l lands at base + 16 l) in two
+//     buffer sets: the loads of step i + 1 are in flight while step i is multiplied, one barrier
+//     per step.
+//   * Operands whose contracted index is contiguous in memory are fetched with ds_read_b128;
+//     operands that must be read "across" rows (V and K^T in kernel A; Q^T, dO^T in kernel B) come
+//     from transposing LDS reads (ds_read_b64_tr_b16: in a group of 16 lanes, lane s hands in the
+//     address of 4 consecutive elements, 4 (s % 4) .., of row s / 4, and lane i receives element i
+//     of each of those 4 rows).
+//   * No padding: 16-byte chunks are XOR-swizzled (applied to the global address a lane fetches)
+//     so that both access patterns are free of bank conflicts.
 #include "flexco_internal.h"
 #include "device_types.h"
 
@@ -25,9 +32,13 @@ namespace flexco {
 namespace {
 
 constexpr int D = 128, PS = 16;
-constexpr int LDR = D + 8;   // padded row of a staged [rows][128] tile (272 bytes)
+constexpr int TILE16 = 16 * D;          // elements of 16 rows of 128
+constexpr int VPAGE = D * PS;           // elements of one V page, [128 d][16 keys]
 constexpr float LOG2E = 1.4426950408889634f;
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+#define FLEXCO_GP(p) ((const __attribute__((address_space(1))) void*)(p))
+#define FLEXCO_LP(p) ((__attribute__((address_space(3))) void*)(p))
+#define FLEXCO_LDS __attribute__((address_space(3)))
 
 struct BwdArgs {
   const bf16_t *q, *dout;
@@ -40,30 +51,53 @@ struct BwdArgs {
   float scale, scale_log2;
 };
 
-// byte offset of element (d, key) of a staged V page: [d][16 keys] rows of 32 bytes, every group of
-// 8 rows shifted by 64 bytes so that d, d + 8, d + 16, d + 24 land on different banks
-__device__ inline int vs_off(int d, int key) { return d * 32 + (d >> 3) * 64 + key * 2; }
-constexpr int VS_PAGE_BYTES = D * 32 + (D / 8) * 64;   // 5120
+// [rows][128] bf16 tiles (256-byte rows = sixteen 16-byte chunks): chunk cc of row r is stored at
+// chunk cc ^ rsw(r).  The 16 rows of a ds_read_b128 pass get 16 different chunks; the 8 rows of a
+// transposing-read pass get 8 different chunk pairs.
+__device__ inline int rsw(int r) { return ((r & 7) << 1) | ((r >> 3) & 1); }
 
-__device__ inline bf16x8 zero8() { return bf16x8{0, 0, 0, 0, 0, 0, 0, 0}; }
+// wait for this wavefront's loads, then a barrier without memory fences (those would also drain
+// loads issued after the wait); the empty asm statements keep LDS accesses on their side of it
+#define FLEXCO_WAIT_ALL_BARRIER                  \
+  {                                              \
+    __builtin_amdgcn_s_waitcnt(0x0F70);          \
+    asm volatile("" ::: "memory");               \
+    __builtin_amdgcn_s_barrier();                \
+    asm volatile("" ::: "memory");               \
+  }
+
+// 8 consecutive "row" values of one column as an MFMA operand: 4 rows at a and the next 4 at b
+// (a, b already hold the lane's row, chunk and half-chunk)
+__device__ inline bf16x8 tr_pair(const bf16_t* a, const bf16_t* b) {
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((FLEXCO_LDS s16x4*)a);
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((FLEXCO_LDS s16x4*)b);
+  return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
 
 // ---------------------------------------------------------------------------------------------
-// kernel A: dQ.  grid (ceil(s / 64), nq); wavefront w of a block owns rows [64 b + 16 w, + 16).
+// kernel A: dQ.  grid (ceil(s / 32), nq).  Wavefront w: rows [32 b + 16 (w % 2), + 16), and of the
+// four pages a step stages, pages 2 (w / 2) and 2 (w / 2) + 1; the two key halves are added in a
+// fixed order at the end.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(BwdArgs a) {
-  __shared__ __attribute__((aligned(16))) bf16_t Ks[32 * LDR];
-  __shared__ __attribute__((aligned(16))) unsigned char Vs[2 * VS_PAGE_BYTES];
+  __shared__ __attribute__((aligned(1024))) bf16_t kb0[4 * TILE16];
+  __shared__ __attribute__((aligned(1024))) bf16_t kb1[4 * TILE16];
+  __shared__ __attribute__((aligned(1024))) bf16_t vb0[4 * VPAGE];
+  __shared__ __attribute__((aligned(1024))) bf16_t vb1[4 * VPAGE];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int c = lane & 15, g = lane >> 4;
+  const int rt = wave & 1, kh = wave >> 1;
   const int h = blockIdx.y, group = a.nq / a.nkv, kvh = h / group;
-  const int i0 = blockIdx.x * 64 + wave * 16;
+  const int i0 = blockIdx.x * 32 + rt * 16;
   const int row_c = i0 + c;
   const bool row_ok = row_c < a.s;
   const int rcl = row_ok ? row_c : a.s - 1;
   const int pos_c = row_ok ? a.w0 + row_c : -1;
   const int wave_last_pos = a.w0 + min(i0 + 15, a.s - 1);      // may be < first key if the tile is empty
-  const int blk_last_row = min(blockIdx.x * 64 + 63, a.s - 1);
+  const int blk_last_row = min(blockIdx.x * 32 + 31, a.s - 1);
   const int np = (a.w0 + blk_last_row) / PS + 1;                 // pages visible to the block
+  const int nit = (np + 3) / 4;
+  const int last_page = (a.l - 1) / PS, last_key = (a.l - 1) % PS;
 
   bf16x8 qf[4], dof[4];
   {
@@ -82,93 +116,134 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(BwdArgs a) {
 #pragma unroll
   for (int mt = 0; mt < 8; ++mt) dq[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  for (int pp = 0; pp < np; pp += 2) {
-    __syncthreads();
-    // ---- stage the K and V rows of two pages; slots at or beyond l (never written) become zero ----
-#pragma unroll
-    for (int e = 0; e < 2; ++e) {
-      const int qid = tid + 256 * e;
-      const int x = qid >> 8, rem = qid & 255;
-      const bool pg_ok = pp + x < np;
-      const size_t page = (size_t)a.pages[pg_ok ? pp + x : pp];
-      {   // K chunk: key = rem / 16, 16-byte chunk rem % 16
-        const int key = rem >> 4, ch = rem & 15;
-        u32x4 v = *reinterpret_cast<const u32x4*>(a.kp + ((page * a.nkv + kvh) * PS + key) * (size_t)D + ch * 8);
-        if (!pg_ok || (pp + x) * PS + key >= a.l) v = u32x4{0, 0, 0, 0};
-        *reinterpret_cast<u32x4*>(Ks + (x * 16 + key) * LDR + ch * 8) = v;
-      }
-      {   // V chunk: d = rem / 2, keys 8 (rem % 2) .. + 8
-        const int d = rem >> 1, half = rem & 1;
-        bf16x8 v = *reinterpret_cast<const bf16x8*>(a.vp + ((page * a.nkv + kvh) * (size_t)D + d) * PS + half * 8);
-        const int kbase = (pp + x) * PS + half * 8;
-        if (!pg_ok || kbase + 8 > a.l) {
-#pragma unroll
-          for (int j = 0; j < 8; ++j)
-            if (!pg_ok || kbase + j >= a.l) v[j] = (bf16_t)0.f;
-        }
-        *reinterpret_cast<bf16x8*>(Vs + x * VS_PAGE_BYTES + vs_off(d, half * 8)) = v;
-      }
-    }
-    __syncthreads();
-    if (pp * PS > wave_last_pos) continue;     // nothing visible to this wavefront's rows (uniform)
-
-    float ds[8];
-#pragma unroll
-    for (int x = 0; x < 2; ++x) {
-      f32x4 sacc = {0.f, 0.f, 0.f, 0.f}, pacc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int dc = 0; dc < 4; ++dc) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(Ks + (x * 16 + c) * LDR + dc * 32 + g * 8);
-        sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[dc], sacc, 0, 0, 0);
-        bf16x8 vf;
-#pragma unroll
-        for (int j = 0; j < 8; ++j)
-          vf[j] = *reinterpret_cast<const bf16_t*>(Vs + x * VS_PAGE_BYTES + vs_off(dc * 32 + g * 8 + j, c));
-        pacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, dof[dc], pacc, 0, 0, 0);
-      }
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int kpos = (pp + x) * PS + 4 * g + j;
-        const bool ok = kpos <= pos_c;
-        const float p = __builtin_amdgcn_exp2f(sacc[j] * a.scale_log2 - lse2);
-        ds[x * 4 + j] = ok ? p * (pacc[j] - delta) : 0.f;
-      }
-    }
-    bf16x8 dsf;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) dsf[j] = (bf16_t)ds[j];
-    // dQ^T[d, row] += K^T[d, keys] dS^T[keys, row];  lane (d, g) gathers keys {4g..4g+3} of both pages
-#pragma unroll
-    for (int mt = 0; mt < 8; ++mt) {
-      bf16x8 kt;
-      const bf16_t* col = Ks + mt * 16 + c;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        kt[j] = col[(4 * g + j) * LDR];
-        kt[4 + j] = col[(16 + 4 * g + j) * LDR];
-      }
-      dq[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kt, dsf, dq[mt], 0, 0, 0);
-    }
+  // ---- loads: wavefront w brings in page slot w of a step, K rows and V ---------------------
+  // K: instruction q fills rows 4 q .. + 4 of the slot; lane -> row 4 q + lane / 16, physical chunk
+  //    lane % 16.  Rows at or past l were never written: their address is moved to row l - 1, so
+  //    that what lands is finite (those keys are masked, but 0 x NaN would still poison dQ).
+  // V: a page is [128 d][16 keys] = 256 chunks; instruction q fills physical chunks 64 q .. + 64;
+  //    physical chunk P holds logical chunk P ^ (8 if bit 4 of P): rows d and d + 8 of a
+  //    transposing read then sit 128 bytes apart (mod 256).
+  const int k_rin = lane >> 4, k_pc = lane & 15;
+  const int v_lc = lane ^ (((lane >> 4) & 1) << 3);
+  int page_nxt;
+#define FLEXCO_ISSUE(kb_, vb_, it_, page_)                                                            \
+  {                                                                                                   \
+    const int slot_ = 4 * (it_) + wave;                                                               \
+    const size_t pb_ = ((size_t)(page_) * a.nkv + kvh);                                               \
+    _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                                   \
+      const int key_ = 4 * q + k_rin;                                                                 \
+      const int keff_ = slot_ * PS + key_ < a.l ? key_ : last_key;                                    \
+      const bf16_t* src_ = a.kp + (pb_ * PS + keff_) * (size_t)D + ((k_pc ^ rsw(key_)) * 8);          \
+      __builtin_amdgcn_global_load_lds(FLEXCO_GP(src_), FLEXCO_LP(kb_ + wave * TILE16 + q * 4 * D), 16, 0, 0); \
+    }                                                                                                 \
+    _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                                   \
+      const bf16_t* src_ = a.vp + pb_ * (size_t)VPAGE + (64 * q + v_lc) * 8;                          \
+      __builtin_amdgcn_global_load_lds(FLEXCO_GP(src_), FLEXCO_LP(vb_ + wave * VPAGE + q * 512), 16, 0, 0); \
+    }                                                                                                 \
   }
-  if (row_ok) {
+
+  // ---- per-lane offsets of the LDS reads -------------------------------------------------------
+  // K rows as A operand of S^T = K Q^T: lane (key c, g) reads chunk 4 dc + g of row c
+  const int krow_off = c * D;
+  const int krow_sw = rsw(c);
+  // transposing reads: source lane s = lane % 16 of group g
+  const int s4 = c >> 2, sc = c & 3;
+  // K^T as A operand of dQ^T += K^T dS^T: rows (keys) 4 g + s / 4 of a slot, columns 16 mt + 4 (s % 4)
+  const int kt_row = 4 * g + s4;
+  const int kt_base = kt_row * D + (sc & 1) * 4;
+  const int kt_sw = rsw(kt_row), kt_hi = sc >> 1;
+  // V as A operand of dP^T = V dO^T: rows d = 32 dc + 8 g + 4 hh + s / 4, keys 4 (s % 4) ..;
+  // logical chunk 2 d + (s % 4) / 2, physical = logical ^ (8 if bit 3 of d, i.e. g odd)
+  const int v_base = (((2 * (8 * g + s4) + (sc >> 1)) ^ ((g & 1) << 3)) * 8) + (sc & 1) * 4;
+
+#define FLEXCO_DQ_COMPUTE(kb_, vb_, it_)                                                              \
+  if ((4 * (it_) + 2 * kh) * PS <= wave_last_pos) { /* else: nothing visible to these rows (uniform) */ \
+    float ds[8];                                                                                      \
+    _Pragma("unroll") for (int xx = 0; xx < 2; ++xx) {                                                \
+      const bf16_t* kt_ = kb_ + (2 * kh + xx) * TILE16;                                               \
+      const bf16_t* vt_ = vb_ + (2 * kh + xx) * VPAGE;                                                \
+      f32x4 sacc = {0.f, 0.f, 0.f, 0.f}, pacc = {0.f, 0.f, 0.f, 0.f};                                 \
+      _Pragma("unroll") for (int dc = 0; dc < 4; ++dc) {                                              \
+        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kt_ + krow_off + (((dc * 4 + g) ^ krow_sw) * 8)); \
+        sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[dc], sacc, 0, 0, 0);                    \
+        /* rows d + 4: 8 logical chunks on = bit 3 of the chunk index = bit 6 of the element offset */ \
+        const bf16x8 vf = tr_pair(vt_ + dc * 512 + v_base, vt_ + dc * 512 + (v_base ^ 64));           \
+        pacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, dof[dc], pacc, 0, 0, 0);                   \
+      }                                                                                               \
+      _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                 \
+        const int kpos = (4 * (it_) + 2 * kh + xx) * PS + 4 * g + j;                                  \
+        const bool ok = kpos <= pos_c;                                                                \
+        const float p = __builtin_amdgcn_exp2f(sacc[j] * a.scale_log2 - lse2);                        \
+        ds[xx * 4 + j] = ok ? p * (pacc[j] - delta) : 0.f;                                            \
+      }                                                                                               \
+    }                                                                                                 \
+    bf16x8 dsf;                                                                                       \
+    _Pragma("unroll") for (int j = 0; j < 8; ++j) dsf[j] = (bf16_t)ds[j];                             \
+    /* dQ^T[d, row] += K^T[d, keys] dS^T[keys, row]; lane (d, g): keys 4g..4g+3 of both pages */       \
+    _Pragma("unroll") for (int mt = 0; mt < 8; ++mt) {                                                \
+      const int off_ = kt_base + (((mt * 2 + kt_hi) ^ kt_sw) * 8);                                    \
+      const bf16x8 kt = tr_pair(kb_ + (2 * kh) * TILE16 + off_, kb_ + (2 * kh + 1) * TILE16 + off_);  \
+      dq[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kt, dsf, dq[mt], 0, 0, 0);                     \
+    }                                                                                                 \
+  }
+
+  // step it: my loads of step it have landed -> barrier -> everyone's have, and everyone is done
+  // with the other buffer set -> start the loads of step it + 1 into it -> multiply step it
+#define FLEXCO_DQ_STEP(kb_, vb_, kn_, vn_, it_)                                                       \
+  {                                                                                                   \
+    FLEXCO_WAIT_ALL_BARRIER                                                                           \
+    if ((it_) + 1 < nit) {                                                                            \
+      FLEXCO_ISSUE(kn_, vn_, (it_) + 1, page_nxt)                                                     \
+      page_nxt = a.pages[min(4 * ((it_) + 2) + wave, last_page)];                                     \
+    }                                                                                                 \
+    FLEXCO_DQ_COMPUTE(kb_, vb_, it_)                                                                  \
+  }
+
+  {
+    const int page0 = a.pages[min(wave, last_page)];
+    FLEXCO_ISSUE(kb0, vb0, 0, page0)
+    page_nxt = a.pages[min(4 + wave, last_page)];
+  }
+  int it = 0;
+  for (; it + 1 < nit; it += 2) {
+    FLEXCO_DQ_STEP(kb0, vb0, kb1, vb1, it)
+    FLEXCO_DQ_STEP(kb1, vb1, kb0, vb0, it + 1)
+  }
+  if (it < nit) FLEXCO_DQ_STEP(kb0, vb0, kb1, vb1, it)
+
+  // ---- add the two key halves (kh = 0 first), scale, store --------------------------------------
+  __syncthreads();
+  float* red = reinterpret_cast<float*>(kb0);                    // [2 rt][32][64 lanes] floats = 16 KB
+  if (kh == 1) {
+#pragma unroll
+    for (int mt = 0; mt < 8; ++mt)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) red[((rt * 8 + mt) * 4 + j) * 64 + lane] = dq[mt][j];
+  }
+  __syncthreads();
+  if (kh == 0 && row_ok) {
     bf16_t* out = a.dq + ((size_t)row_c * a.nq + h) * D + 4 * g;
 #pragma unroll
     for (int mt = 0; mt < 8; ++mt) {
       bf16x4 v;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) v[j] = (bf16_t)(dq[mt][j] * a.scale);
+      for (int j = 0; j < 4; ++j) v[j] = (bf16_t)((dq[mt][j] + red[((rt * 8 + mt) * 4 + j) * 64 + lane]) * a.scale);
       *reinterpret_cast<bf16x4*>(out + mt * 16) = v;
     }
   }
 }
 
 // ---------------------------------------------------------------------------------------------
-// kernel B: dK, dV.  grid (ceil(l / 64), nkv); wavefront w owns the page (16 keys) 4 b + w.
+// kernel B: dK, dV.  grid (ceil(l / 64), nkv); wavefront w owns the page (16 keys) 4 b + w and
+// walks over the query heads of the kv group and the window's rows, 32 rows per step.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(BwdArgs a) {
-  __shared__ __attribute__((aligned(16))) bf16_t Qs[32 * LDR];
-  __shared__ __attribute__((aligned(16))) bf16_t Os[32 * LDR];
-  __shared__ float lse_s[32], delta_s[32];
+  __shared__ __attribute__((aligned(1024))) bf16_t qb0[2 * TILE16];
+  __shared__ __attribute__((aligned(1024))) bf16_t qb1[2 * TILE16];
+  __shared__ __attribute__((aligned(1024))) bf16_t ob0[2 * TILE16];
+  __shared__ __attribute__((aligned(1024))) bf16_t ob1[2 * TILE16];
+  __shared__ __attribute__((aligned(256))) float ld0[64];       // lse[32] | delta[32] of the step's rows
+  __shared__ __attribute__((aligned(256))) float ld1[64];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int c = lane & 15, g = lane >> 4;
   const int kvh = blockIdx.y, group = a.nq / a.nkv;
@@ -198,71 +273,88 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(BwdArgs a) {
 
   const int blk_key0 = blockIdx.x * 64;
   const int first_row = max(0, blk_key0 - a.w0) & ~31;       // first window row that sees the block's keys
-  for (int hg = 0; hg < group; ++hg) {
-    const int h = kvh * group + hg;
-    for (int r0 = first_row; r0 < a.s; r0 += 32) {
-      __syncthreads();
-      // ---- stage 32 rows of Q and dO of head h (rows beyond the window repeat the last row; masked) ----
-#pragma unroll
-      for (int e = 0; e < 2; ++e) {
-        const int qid = tid + 256 * e;           // 512 chunks: row = qid / 16, chunk qid % 16
-        const int row = qid >> 4, ch = qid & 15;
-        const int rcl = min(r0 + row, a.s - 1);
-        const size_t src = ((size_t)rcl * a.nq + h) * D + ch * 8;
-        *reinterpret_cast<u32x4*>(Qs + row * LDR + ch * 8) = *reinterpret_cast<const u32x4*>(a.q + src);
-        *reinterpret_cast<u32x4*>(Os + row * LDR + ch * 8) = *reinterpret_cast<const u32x4*>(a.dout + src);
-      }
-      if (tid < 32) {
-        const int rcl = min(r0 + tid, a.s - 1);
-        lse_s[tid] = a.lse[(size_t)rcl * a.nq + h] * LOG2E;
-        delta_s[tid] = a.delta[(size_t)rcl * a.nq + h];
-      }
-      __syncthreads();
-      if (!page_ok || key0 > a.w0 + min(r0 + 31, a.s - 1)) continue;   // no row of the pair sees this page
+  const int nrb = (a.s - first_row + 31) / 32;               // row blocks per head
+  const int nit = group * nrb;
 
-      float p[8], ds[8];
-#pragma unroll
-      for (int x = 0; x < 2; ++x) {
-        f32x4 sacc = {0.f, 0.f, 0.f, 0.f}, pacc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int dc = 0; dc < 4; ++dc) {
-          const bf16x8 qa = *reinterpret_cast<const bf16x8*>(Qs + (x * 16 + c) * LDR + dc * 32 + g * 8);
-          const bf16x8 oa = *reinterpret_cast<const bf16x8*>(Os + (x * 16 + c) * LDR + dc * 32 + g * 8);
-          sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa, kf[dc], sacc, 0, 0, 0);   // S[row, key]
-          pacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(oa, vf[dc], pacc, 0, 0, 0);   // dP[row, key]
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int rl = x * 16 + 4 * g + j;            // lane (key c, g) holds rows 4g..4g+3 of tile x
-          const int row = r0 + rl;
-          const bool ok = key_ok && row < a.s && kpos <= a.w0 + row;
-          const float pv = __builtin_amdgcn_exp2f(sacc[j] * a.scale_log2 - lse_s[rl]);
-          p[x * 4 + j] = ok ? pv : 0.f;
-          ds[x * 4 + j] = ok ? pv * (pacc[j] - delta_s[rl]) : 0.f;
-        }
-      }
-      bf16x8 pf, dsf;
-#pragma unroll
-      for (int j = 0; j < 8; ++j) { pf[j] = (bf16_t)p[j]; dsf[j] = (bf16_t)ds[j]; }
-      // dV^T[d, key] += dO^T[d, rows] P[rows, key];  dK^T[d, key] += Q^T[d, rows] dS[rows, key]
-      // lane (d, g) gathers rows {4g..4g+3} of both row tiles at column d
-#pragma unroll
-      for (int mt = 0; mt < 8; ++mt) {
-        bf16x8 ot, qt;
-        const bf16_t* ocol = Os + mt * 16 + c;
-        const bf16_t* qcol = Qs + mt * 16 + c;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          ot[j] = ocol[(4 * g + j) * LDR];
-          ot[4 + j] = ocol[(16 + 4 * g + j) * LDR];
-          qt[j] = qcol[(4 * g + j) * LDR];
-          qt[4 + j] = qcol[(16 + 4 * g + j) * LDR];
-        }
-        dv[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ot, pf, dv[mt], 0, 0, 0);
-        dk[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qt, dsf, dk[mt], 0, 0, 0);
-      }
-    }
+  // ---- loads: 8 instructions per 32-row tile (4 rows each); wavefront w issues 2 w, 2 w + 1 of the
+  // Q tile and of the dO tile; wavefront 0 also brings in the rows' lse (lanes 0..31) and delta
+  // (lanes 32..63), 4 bytes per lane.  Rows past the window repeat its last row (masked later).
+  const int t_rin = lane >> 4, t_pc = lane & 15;
+#define FLEXCO_ISSUE_QO(qb_, ob_, ld_, it_)                                                           \
+  {                                                                                                   \
+    const int h_ = kvh * group + (it_) / nrb;                                                         \
+    const int r0_ = first_row + 32 * ((it_) % nrb);                                                   \
+    _Pragma("unroll") for (int e = 0; e < 2; ++e) {                                                   \
+      const int row_ = 4 * (2 * wave + e) + t_rin;                                                    \
+      const size_t src_ = ((size_t)min(r0_ + row_, a.s - 1) * a.nq + h_) * D + ((t_pc ^ rsw(row_)) * 8); \
+      __builtin_amdgcn_global_load_lds(FLEXCO_GP(a.q + src_), FLEXCO_LP(qb_ + (2 * wave + e) * 4 * D), 16, 0, 0); \
+      __builtin_amdgcn_global_load_lds(FLEXCO_GP(a.dout + src_), FLEXCO_LP(ob_ + (2 * wave + e) * 4 * D), 16, 0, 0); \
+    }                                                                                                 \
+    if (wave == 0) {                                                                                  \
+      const size_t idx_ = (size_t)min(r0_ + (lane & 31), a.s - 1) * a.nq + h_;                        \
+      const float* src_ = (lane < 32 ? a.lse : a.delta) + idx_;                                       \
+      __builtin_amdgcn_global_load_lds(FLEXCO_GP(src_), FLEXCO_LP(ld_), 4, 0, 0);                     \
+    }                                                                                                 \
   }
+
+  const int row_off = c * D, row_sw = rsw(c);
+  const int s4 = c >> 2, sc = c & 3;
+  const int tr_row = 4 * g + s4;
+  const int tr_base = tr_row * D + (sc & 1) * 4;
+  const int tr_sw = rsw(tr_row), tr_hi = sc >> 1;
+
+#define FLEXCO_DKV_COMPUTE(qb_, ob_, ld_, it_)                                                        \
+  {                                                                                                   \
+    const int r0 = first_row + 32 * ((it_) % nrb);                                                    \
+    if (page_ok && key0 <= a.w0 + min(r0 + 31, a.s - 1)) { /* else no row of the step sees this page */ \
+      float p[8], ds[8];                                                                              \
+      _Pragma("unroll") for (int x = 0; x < 2; ++x) {                                                 \
+        f32x4 sacc = {0.f, 0.f, 0.f, 0.f}, pacc = {0.f, 0.f, 0.f, 0.f};                               \
+        _Pragma("unroll") for (int dc = 0; dc < 4; ++dc) {                                            \
+          const int off_ = x * TILE16 + row_off + (((dc * 4 + g) ^ row_sw) * 8);                      \
+          const bf16x8 qa = *reinterpret_cast<const bf16x8*>(qb_ + off_);                             \
+          const bf16x8 oa = *reinterpret_cast<const bf16x8*>(ob_ + off_);                             \
+          sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa, kf[dc], sacc, 0, 0, 0);   /* S[row, key] */  \
+          pacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(oa, vf[dc], pacc, 0, 0, 0);   /* dP[row, key] */ \
+        }                                                                                             \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                               \
+          const int rl = x * 16 + 4 * g + j;            /* lane (key c, g) holds rows 4g..4g+3 of tile x */ \
+          const int row = r0 + rl;                                                                    \
+          const bool ok = key_ok && row < a.s && kpos <= a.w0 + row;                                  \
+          const float pv = __builtin_amdgcn_exp2f(sacc[j] * a.scale_log2 - ld_[rl] * LOG2E);          \
+          p[x * 4 + j] = ok ? pv : 0.f;                                                               \
+          ds[x * 4 + j] = ok ? pv * (pacc[j] - ld_[32 + rl]) : 0.f;                                   \
+        }                                                                                             \
+      }                                                                                               \
+      bf16x8 pf, dsf;                                                                                 \
+      _Pragma("unroll") for (int j = 0; j < 8; ++j) { pf[j] = (bf16_t)p[j]; dsf[j] = (bf16_t)ds[j]; } \
+      /* dV^T[d, key] += dO^T[d, rows] P[rows, key];  dK^T[d, key] += Q^T[d, rows] dS[rows, key] */    \
+      /* lane (d, g): rows 4g..4g+3 of both row tiles at column d */                                   \
+      _Pragma("unroll") for (int mt = 0; mt < 8; ++mt) {                                              \
+        const int off_ = tr_base + (((mt * 2 + tr_hi) ^ tr_sw) * 8);                                  \
+        const bf16x8 ot = tr_pair(ob_ + off_, ob_ + TILE16 + off_);                                   \
+        const bf16x8 qt = tr_pair(qb_ + off_, qb_ + TILE16 + off_);                                   \
+        dv[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ot, pf, dv[mt], 0, 0, 0);                    \
+        dk[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qt, dsf, dk[mt], 0, 0, 0);                   \
+      }                                                                                               \
+    }                                                                                                 \
+  }
+#define FLEXCO_DKV_STEP(qb_, ob_, ld_, qn_, on_, ln_, it_)                                            \
+  {                                                                                                   \
+    FLEXCO_WAIT_ALL_BARRIER                                                                           \
+    if ((it_) + 1 < nit) FLEXCO_ISSUE_QO(qn_, on_, ln_, (it_) + 1)                                    \
+    FLEXCO_DKV_COMPUTE(qb_, ob_, ld_, it_)                                                            \
+  }
+
+  FLEXCO_ISSUE_QO(qb0, ob0, ld0, 0)
+  int it = 0;
+  for (; it + 1 < nit; it += 2) {
+    FLEXCO_DKV_STEP(qb0, ob0, ld0, qb1, ob1, ld1, it)
+    FLEXCO_DKV_STEP(qb1, ob1, ld1, qb0, ob0, ld0, it + 1)
+  }
+  if (it < nit) FLEXCO_DKV_STEP(qb0, ob0, ld0, qb1, ob1, ld1, it)
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // nothing may land in LDS after the block ends
+
   if (key_ok) {
     float* dkp = a.dk_accum + ((size_t)kpos * a.nkv + kvh) * D + 4 * g;
     float* dvp = a.dv_accum + ((size_t)kpos * a.nkv + kvh) * D + 4 * g;
@@ -290,7 +382,7 @@ int32_t launch_attention_bwd_mfma(const flexco_layer_cfg& c, const flexco_kv_poo
   a.w0 = win_start; a.s = win_len; a.l = win_start + win_len; a.nq = c.n_q_heads; a.nkv = c.n_kv_heads;
   a.scale = 1.0f / sqrtf((float)D);
   a.scale_log2 = a.scale * LOG2E;
-  hipLaunchKernelGGL(attn_bwd_dq_mfma_kernel, dim3((a.s + 63) / 64, a.nq), dim3(256), 0, s, a);
+  hipLaunchKernelGGL(attn_bwd_dq_mfma_kernel, dim3((a.s + 31) / 32, a.nq), dim3(256), 0, s, a);
   hipLaunchKernelGGL(attn_bwd_dkv_mfma_kernel, dim3((a.l + 63) / 64, a.nkv), dim3(256), 0, s, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(FLEXCO_EHIP, "launch of attn_bwd_mfma failed: %s", hipGetErrorString(e));

@@ -142,6 +142,60 @@ def test_attention_mixed(name, split):
 
 
 # ------------------------------------------------------------------------------------------
+# attention backward of one token window alone (Sec. 6.1): dQ of the window, dK/dV accumulated
+# into every cached row before the window's end
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("cfg_name,win_start,win_len", [
+    ("small_bf16", 0, 40),          # the first window: every row sees only the window itself, ragged page
+    ("small_bf16", 96, 75),         # ragged start and end, l = 171 (not a multiple of 16)
+    ("small_bf16", 448, 64),        # aligned, several key blocks of 64 before the window
+    ("small_bf16", 301, 131),       # window longer than a row block, odd everything
+    ("g5", 130, 33),                # kv group of 5 query heads
+    ("c1", 5, 6),                   # fp32 generic path
+])
+def test_attention_window_bwd(cfg_name, win_start, win_len):
+    say(f"attention_window_bwd {cfg_name} window [{win_start}, +{win_len})")
+    cfg = {"small_bf16": SMALL_BF16, "g5": SMALL_BF16_G5, "c1": C1}[cfg_name]
+    l = win_start + win_len
+    ps = cfg.page_size
+    n_pages = (l + ps - 1) // ps
+    g = gen.rng(11, "attnbwd", cfg.name, win_start, win_len)
+    pages = (g.permutation(n_pages + 3)[:n_pages] + 1).astype(np.int32)      # scattered, page 0 unused
+    k_rows, v_rows = gen.kv_prefix(cfg, 12, 0, 0, l)
+    q = gen.storage_round(cfg, g.standard_normal((win_len, cfg.q_dim), dtype=np.float32)).astype(np.float64)
+    dout = gen.storage_round(cfg, g.standard_normal((win_len, cfg.q_dim), dtype=np.float32)).astype(np.float64)
+    q_pos = np.arange(win_start, l)
+    kk, vv = k_rows.astype(np.float64), v_rows.astype(np.float64)
+    out_o, lse_o = OO.attention(q, q_pos, kk, vv, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim)
+    dq_o, dk_o, dv_o = OO.attention_bwd(q, q_pos, kk, vv, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, dout)
+
+    dcfg = HH.c_cfg(cfg)
+    pool = HH.DevicePool(cfg, n_pages + 4)
+    pool.fill_random(5)                     # slots that are never written hold arbitrary finite values
+    pool.write_rows(pages, k_rows, v_rows)
+    dt = HH.TORCH_DTYPE[cfg.dtype]
+    dev = lambda a, d=dt: torch.from_numpy(np.ascontiguousarray(a)).to("cuda", d)
+    q_d, out_d, dout_d = dev(q), dev(gen.storage_round(cfg, out_o.astype(np.float32))), dev(dout)
+    lse_d = dev(lse_o, torch.float32)
+    dq_d = torch.empty_like(q_d)
+    # accumulators start from a seeded non-zero state: the call must add, not overwrite
+    base_k = g.standard_normal((l + 3, cfg.kv_dim), dtype=np.float32)
+    base_v = g.standard_normal((l + 3, cfg.kv_dim), dtype=np.float32)
+    dk_d, dv_d = dev(base_k, torch.float32), dev(base_v, torch.float32)
+    ws = torch.empty(win_len * cfg.n_q_heads * 4 + 1024, dtype=torch.uint8, device="cuda")
+    pages_d = torch.from_numpy(pages).to("cuda")
+    B.flexco_attention_window_bwd(dcfg, pool.c, pages_d, n_pages, win_start, win_len, q_d, out_d, lse_d, dout_d, dq_d,
+                                  dk_d, dv_d, ws, ws.numel())
+    torch.cuda.synchronize()
+    tol = TOL[cfg.dtype]
+    assert_close("dq", to_np(dq_d), dq_o, tol)
+    assert_close("dk_accum", to_np(dk_d)[:l] - base_k[:l], dk_o, tol)
+    assert_close("dv_accum", to_np(dv_d)[:l] - base_v[:l], dv_o, tol)
+    assert np.array_equal(to_np(dk_d)[l:], base_k[l:].astype(np.float64))   # rows past the window's end untouched
+    assert np.array_equal(to_np(dv_d)[l:], base_v[l:].astype(np.float64))
+
+
+# ------------------------------------------------------------------------------------------
 # whole layer: forward iterations, then token-window backward
 # ------------------------------------------------------------------------------------------
 def run_layer_case(cfg, batch0, ft_window, prefill_chunk, bwd_windows, seed=0, split=0, need_dx=True):
