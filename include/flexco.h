@@ -150,7 +150,7 @@ typedef struct flexco_maps {
   const int32_t* tile_ntok;     /* [n_tiles] tokens in the tile                           */
   const int32_t* tile_nsplit;   /* [n_tiles]                                              */
   const int32_t* tile_part0;    /* [n_tiles] first partial-result row of the tile         */
-  const int32_t* item_tile;     /* [n_items]                                              */
+  const int32_t* item_tile;     /* [n_items] work items (tile, split), longest key range first */
   const int32_t* item_split;    /* [n_items]                                              */
   const int32_t* tok_tile;      /* [T] tile of each token                                 */
   const int32_t* tok_lora;      /* [T] index of the token in lora_tok, -1 without adapter */

@@ -139,6 +139,24 @@ int32_t build(const flexco_batch_desc* d, int32_t page_size, int32_t num_pages, 
       for (int i = 0; i < ntok; ++i) b.tok_tile.push_back(tile);
     }
   }
+  // Longest items first (ties keep batch order): the attention grid is dispatched in item order and
+  // ends with its last wavefront, and the four items of a block then have similar lengths.
+  {
+    const size_t n = b.item_tile.size();
+    std::vector<int32_t> len(n), order(n);
+    for (size_t i = 0; i < n; ++i) {
+      const int tile = b.item_tile[i];
+      const int vis_pages = b.tok_pos[b.tile_tok0[tile] + b.tile_ntok[tile] - 1] / page_size + 1;
+      const int pb = b.item_split[i] * b.split_pages;
+      len[i] = std::min(pb + b.split_pages, vis_pages) - pb;
+      order[i] = (int32_t)i;
+    }
+    std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return len[x] > len[y]; });
+    std::vector<int32_t> it(n), is(n);
+    for (size_t i = 0; i < n; ++i) { it[i] = b.item_tile[order[i]]; is[i] = b.item_split[order[i]]; }
+    b.item_tile.swap(it);
+    b.item_split.swap(is);
+  }
   b.seg_off.push_back(b.T);
   b.n_seg = (int32_t)b.seg_adapter.size();
   b.n_ft = (int32_t)b.ft_tok.size();
