@@ -294,42 +294,66 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
     }                                                                                                 \
   }
     // Software pipeline over k-steps of 64 with two LDS buffers and two sets of staging
-    // registers, so that a tile's global loads have two whole steps to arrive:
-    //   step kt, first half : MFMAs of k-slices 0, 1 of tile kt (LDS buffer kt & 1)
-    //   step kt, middle     : the staging set that holds tile kt + 1 (loaded in the middle of
-    //                         step kt - 2) is written to the other LDS buffer and reloaded with
-    //                         tile kt + 3
-    //   step kt, second half: MFMAs of k-slices 2, 3 - they run while the LDS writes drain
-    //   one barrier at the end of the step: the other buffer is complete, this one is free.
-    // The other buffer was last read in step kt - 1, which every wavefront left through that
-    // step's barrier, so the mid-step writes race with nothing.  Past the last tile the indices
-    // are clamped: the extra loads and writes repeat tile nk - 1 and are never read.
+    // registers, so that a tile's global loads have two whole steps to arrive.  Fragments are
+    // fetched one k-slice ahead into two sets used in turn (a step enters with slice 0 in set 0):
+    //   slice 0: fetch slice 1, MFMAs of slice 0
+    //   slice 1: fetch slice 2, MFMAs of slice 1; the staging set that holds tile kt + 1 (loaded
+    //            in step kt - 2) is written to the other LDS buffer and reloaded with tile kt + 3
+    //   slice 2: fetch slice 3, MFMAs of slice 2
+    //   barrier: the other buffer is complete for everyone, this one is free
+    //   slice 3: fetch slice 0 of the next tile, MFMAs of slice 3
+    // Hazards: every read of tile kt - 1 (slices 1..3 in step kt - 1, slice 0 in step kt - 2) is
+    // issued, and waited for, before the barrier of step kt - 1, so the writes of tile kt + 1 into
+    // the same buffer in the middle of step kt race with nothing; those writes are complete for
+    // everyone at the barrier of step kt, after which slice 0 of tile kt + 1 is read.  Past the
+    // last tile the indices are clamped: the extra loads and writes repeat tile nk - 1, and the
+    // fragments fetched from them are never used.
+#define FLEXCO_ORDER_T                                                                                \
+  {                                                                                                   \
+    _Pragma("unroll") for (int q = 0; q < MT * NT; ++q) {                                             \
+      __builtin_amdgcn_sched_group_barrier(0x100, (MT + 2 * NT + MT * NT - 1) / (MT * NT), 0);        \
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                              \
+    }                                                                                                 \
+  }
 #define FLEXCO_STEP(kt_, ra_, rb_)                                                                    \
   {                                                                                                   \
     const int buf = (kt_) & 1;                                                                        \
     const bf16_t* as = As + buf * S::A_ELEMS;                                                         \
     const bf16_t* bs = Bs + buf * S::B_ELEMS;                                                         \
-    bf16x8 af[MT], bfr[NT], af2[MT], bfr2[NT];                                                        \
-    FLEXCO_LOAD_FRAGS(0, af, bfr)                                                                     \
-    FLEXCO_MFMAS(af, bfr)                                                                             \
-    FLEXCO_LOAD_FRAGS(1, af, bfr)                                                                     \
-    FLEXCO_MFMAS(af, bfr)                                                                             \
+    FLEXCO_LOAD_FRAGS(1, af1, bfr1)                                                                   \
+    FLEXCO_MFMAS(af0, bfr0)                                                                           \
+    FLEXCO_ORDER_T                                                                                    \
     __builtin_amdgcn_sched_barrier(0);                                                                \
-    FLEXCO_LOAD_FRAGS(2, af2, bfr2)                                                                   \
+    FLEXCO_LOAD_FRAGS(2, af0, bfr0)                                                                   \
     FLEXCO_STORE_TILES(buf ^ 1, ra_, rb_)                                                             \
     FLEXCO_LOAD_TILES(kbeg + min((kt_) + 3, nk - 1) * BK, ra_, rb_)                                   \
+    FLEXCO_MFMAS(af1, bfr1)                                                                           \
     __builtin_amdgcn_sched_barrier(0);                                                                \
-    FLEXCO_MFMAS(af2, bfr2)                                                                           \
-    FLEXCO_LOAD_FRAGS(3, af, bfr)                                                                     \
-    FLEXCO_MFMAS(af, bfr)                                                                             \
+    FLEXCO_LOAD_FRAGS(3, af1, bfr1)                                                                   \
+    FLEXCO_MFMAS(af0, bfr0)                                                                           \
+    FLEXCO_ORDER_T                                                                                    \
     __builtin_amdgcn_sched_barrier(0);                                                                \
     __syncthreads();                                                                                  \
+    {                                                                                                 \
+      const bf16_t* as = As + (buf ^ 1) * S::A_ELEMS;                                                 \
+      const bf16_t* bs = Bs + (buf ^ 1) * S::B_ELEMS;                                                 \
+      FLEXCO_LOAD_FRAGS(0, af0, bfr0)                                                                 \
+    }                                                                                                 \
+    FLEXCO_MFMAS(af1, bfr1)                                                                           \
+    FLEXCO_ORDER_T                                                                                    \
+    __builtin_amdgcn_sched_barrier(0);                                                                \
   }
+    bf16x8 af0[MT], bfr0[NT], af1[MT], bfr1[NT];
     FLEXCO_LOAD_TILES(kbeg, sa0, sb0)
     FLEXCO_STORE_TILES(0, sa0, sb0)
     __syncthreads();
     FLEXCO_LOAD_TILES(kbeg + min(1, nk - 1) * BK, sa0, sb0)
     FLEXCO_LOAD_TILES(kbeg + min(2, nk - 1) * BK, sa1, sb1)
+    {
+      const bf16_t* as = As;
+      const bf16_t* bs = Bs;
+      FLEXCO_LOAD_FRAGS(0, af0, bfr0)
+    }
     int kt = 0;
     for (; kt + 1 < nk; kt += 2) {
       FLEXCO_STEP(kt, sa0, sb0)
