@@ -47,6 +47,8 @@ def main():
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--kv-split-pages", type=int, default=0,
+                    help="pages per attention work item (0 = the library's default)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on exactly one GPU (no collectives, no sharding); got --gpus %d" % args.gpus)
@@ -78,7 +80,7 @@ def main():
             k, v = gen.kv_prefix(cfg, seed, 0, r.seq_id, r.start_pos)
             pool.write_rows(batch.seq_pages[r.seq_id], k, v)
     ft = HH.DeviceFtState(cfg, L)
-    db = HH.DeviceBatch(cfg, batch.requests, batch.seq_pages, batch.num_pages)
+    db = HH.DeviceBatch(cfg, batch.requests, batch.seq_pages, batch.num_pages, args.kv_split_pages)
     hm = db.host_maps
     T, n_ft = hm.T, hm.n_ft
     ws = HH.Workspace(layers[0].c, T, hm.n_parts, n_ft, L)

@@ -44,9 +44,12 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(FwdArgs a, const bf1
                                                             float* __restrict__ part_ml,
                                                             float* __restrict__ part_acc) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int item = blockIdx.x * 4 + wave;
+  // consecutive wavefronts take the kv heads of one item: the K (and V) blocks they read are the
+  // consecutive 4 KB pieces of the same pages, fetched at about the same time
+  const int unit = blockIdx.x * 4 + wave;
+  const int item = unit / a.nkv;
   if (item >= a.n_items) return;
-  const int kvh = blockIdx.y;
+  const int kvh = unit % a.nkv;
   const int tile = a.item_tile[item], split = a.item_split[item];
   const int r = a.tile_req[tile], t0 = a.tile_tok0[tile], ntok = a.tile_ntok[tile];
   const int group = a.nq / a.nkv;
@@ -200,7 +203,7 @@ int32_t launch_attention_mfma(const flexco_layer_cfg& c, const flexco_maps& m, c
   a.max_pages = m.max_pages; a.nq = c.n_q_heads; a.nkv = c.n_kv_heads; a.n_items = m.n_items;
   a.split_pages = m.kv_split_pages;
   a.scale_log2 = 1.4426950408889634f / sqrtf((float)D);
-  hipLaunchKernelGGL(attn_fwd_mfma_kernel, dim3((m.n_items + 3) / 4, c.n_kv_heads), dim3(256), 0, s, a,
+  hipLaunchKernelGGL(attn_fwd_mfma_kernel, dim3((m.n_items * c.n_kv_heads + 3) / 4), dim3(256), 0, s, a,
                      (const bf16_t*)q, ldq, (const bf16_t*)pool.k_pages, (const bf16_t*)pool.v_pages, part_ml,
                      part_acc);
   hipError_t e = hipGetLastError();

@@ -32,7 +32,7 @@ struct Built {
       seg_off, seg_adapter, lora_tok, tile_req, tile_tok0, tile_ntok, tile_nsplit, tile_part0, item_tile,
       item_split, tok_tile, tok_lora;
   int32_t T = 0, n_ft = 0, n_seg = 0, max_pages = 1, n_parts = 0, ft_req = -1, max_kv_len = 0;
-  int32_t tile_tokens = 1, split_pages = 32, ft_pos0 = 0;
+  int32_t tile_tokens = 1, split_pages = 64, ft_pos0 = 0;
 };
 
 int32_t validate_desc(const flexco_batch_desc* d, int32_t page_size, int32_t nq, int32_t nkv) {
@@ -51,7 +51,7 @@ int32_t build(const flexco_batch_desc* d, int32_t page_size, int32_t num_pages, 
               int32_t kv_split_pages, Built& b, bool count_only) {
   const int group = nq / nkv;
   b.tile_tokens = std::max(1, 16 / group);
-  b.split_pages = kv_split_pages > 0 ? kv_split_pages : 32;
+  b.split_pages = kv_split_pages > 0 ? kv_split_pages : 64;
   FLEXCO_CHECK(b.split_pages % 2 == 0, FLEXCO_EINVAL, "kv_split_pages must be even (got %d)", b.split_pages);
   const int n_req = d->n_req;
   std::vector<int32_t> need(n_req);
