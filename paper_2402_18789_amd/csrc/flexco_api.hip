@@ -76,7 +76,6 @@ extern "C" int32_t flexco_kernel_timer_stop(int32_t kernel_id, double* total_ms,
 
 namespace {
 
-constexpr int KS_MAX = 32;   // largest K split of the LoRA shrink kernel
 constexpr size_t SPLITK_COLS = 32768;   // split-K scratch of the backward GEMMs: rows x this many floats
 
 struct Carver {
@@ -93,10 +92,8 @@ void target_dims(const flexco_layer_cfg& c, int t, int* in, int* out);
 
 // scratch of the bf16 LoRA path for `rows` token rows, one slot per target
 struct LoraWs {
-  float* part_u[LORA_MATS];   // K-split partial sums of u_t = x_t A_t^T, [KS_MAX, rows, r]
   bf16_t* ext[LORA_MATS];     // scaled bf16 [rows, r] operand of the GEMM extension
   // backward only
-  float* part_t[LORA_MATS];   // K-split partial sums of t_t = dy_t B_t
   float* u[LORA_MATS];        // [rows, r]
   float* t[LORA_MATS];        // [rows, r]
   bf16_t* bt[LORA_MATS];      // transposed B_t, [r, out_t]
@@ -109,10 +106,8 @@ void carve_lora(const flexco_layer_cfg& c, int rows, bool backward, Carver& cv, 
     if (!(c.lora_targets >> t & 1)) continue;
     int in, out;
     target_dims(c, t, &in, &out);
-    w.part_u[t] = (float*)cv.take(sizeof(float) * KS_MAX * (size_t)rows * r);
     w.ext[t] = (bf16_t*)cv.take(sizeof(bf16_t) * (size_t)rows * r);
     if (!backward) continue;
-    w.part_t[t] = (float*)cv.take(sizeof(float) * KS_MAX * (size_t)rows * r);
     w.u[t] = (float*)cv.take(sizeof(float) * (size_t)rows * r);
     w.t[t] = (float*)cv.take(sizeof(float) * (size_t)rows * r);
     w.bt[t] = (bf16_t*)cv.take(sizeof(bf16_t) * (size_t)out * r);
@@ -297,25 +292,21 @@ int32_t forward_projection(const flexco_layer_cfg& c, const flexco_lora* lora, c
   const int T = m.T, dt = c.dtype, r = c.lora_rank;
   if (nact > 0 && lora_mfma_ok(c, K)) {
     LoraShrinkArgs sa;
-    LoraFinalizeArgs fa;
     GemmExt ext;
-    memset(&sa, 0, sizeof(sa)); memset(&fa, 0, sizeof(fa)); memset(&ext, 0, sizeof(ext));
-    sa.row_idx = m.lora_tok; sa.n = m.n_lora; sa.r = r;
-    fa.ext_map = m.tok_lora; fa.ext_rows = T; fa.n = m.n_lora; fa.r = r; fa.scale = c.lora_scale;
+    memset(&sa, 0, sizeof(sa)); memset(&ext, 0, sizeof(ext));
+    // u_t = scale x A_t^T for every token row (zero rows where the token has no adapter)
+    sa.row_map = m.tok_lora; sa.rows = T; sa.r = r; sa.scale = c.lora_scale;
     ext.n = nact; ext.r = r;
     for (int z = 0; z < nact; ++z) {
       const int t = targets[act[z]];
       int in, out;
       target_dims(c, t, &in, &out);
-      sa.X[z] = (const bf16_t*)x; sa.ldx[z] = K; sa.S[z] = (const bf16_t*)lora->A[t]; sa.lds[z] = K;
-      sa.K[z] = K; sa.KS[z] = lora_shrink_splits(m.n_lora, K);
-      sa.part[z] = k.lw.part_u[t];
-      fa.part[z] = k.lw.part_u[t]; fa.KS[z] = sa.KS[z]; fa.out_f32[z] = nullptr; fa.out_ext[z] = k.lw.ext[t];
+      sa.X[z] = (const bf16_t*)x; sa.ldx[z] = K; sa.S[z] = (const bf16_t*)lora->A[t]; sa.lds[z] = K; sa.K[z] = K;
+      sa.out_f32[z] = nullptr; sa.out_ext[z] = k.lw.ext[t];
       ext.col0[z] = col0[act[z]]; ext.col1[z] = col0[act[z]] + out;
       ext.A2[z] = k.lw.ext[t]; ext.W2[z] = (const bf16_t*)lora->B[t]; ext.ldw2[z] = r;
     }
     LR(launch_lora_shrink_mfma(sa, nact, s));
-    LR(launch_lora_finalize(fa, nact, s));
     int32_t rc = launch_gemm(x, W, y, bias, res, T, N, K, K, K, N, ldr, false, dt, s, &ext);
     if (rc != FLEXCO_EUNSUPPORTED) return rc;
     clear_error();   // e.g. a target boundary inside a GEMM tile: run the bypass as separate kernels
@@ -348,17 +339,15 @@ void plan_group(const flexco_layer_cfg& c, BwdGroup& g) {
   }
 }
 
-// Start of a backward window, fused groups only: u_t = x_t A_t^T of every target in one launch
-// (+ its reduction), and the transposed B_t the t_t = dy_t B_t products contract against.
+// Start of a backward window, fused groups only: u_t = x_t A_t^T of every target in one launch,
+// and the transposed B_t the t_t = dy_t B_t products contract against.
 int32_t lora_bwd_prepare(const flexco_layer_cfg& c, const flexco_lora* lora, int n, const BwdGroup* groups,
                          int n_groups, BwdWs& k, hipStream_t s) {
   LoraShrinkArgs su;
-  LoraFinalizeArgs fu;
   LoraTransposeArgs ta;
-  memset(&su, 0, sizeof(su)); memset(&fu, 0, sizeof(fu)); memset(&ta, 0, sizeof(ta));
+  memset(&su, 0, sizeof(su)); memset(&ta, 0, sizeof(ta));
   const int r = c.lora_rank;
-  su.n = n; su.r = r;
-  fu.n = n; fu.r = r; fu.scale = 1.f;
+  su.rows = n; su.r = r; su.scale = 1.f;
   ta.r = r;
   int nz = 0;
   for (int gi = 0; gi < n_groups; ++gi) {
@@ -369,15 +358,12 @@ int32_t lora_bwd_prepare(const flexco_layer_cfg& c, const flexco_lora* lora, int
       int in, out;
       target_dims(c, t, &in, &out);
       su.X[nz] = (const bf16_t*)g.xs[g.act[a]]; su.ldx[nz] = in; su.S[nz] = (const bf16_t*)lora->A[t]; su.lds[nz] = in;
-      su.K[nz] = in; su.KS[nz] = lora_shrink_splits(n, in);
-      su.part[nz] = k.lw.part_u[t];
-      fu.part[nz] = k.lw.part_u[t]; fu.KS[nz] = su.KS[nz]; fu.out_f32[nz] = k.lw.u[t]; fu.out_ext[nz] = nullptr;
+      su.K[nz] = in; su.out_f32[nz] = k.lw.u[t]; su.out_ext[nz] = nullptr;
       ta.B[nz] = (const bf16_t*)lora->B[t]; ta.Bt[nz] = k.lw.bt[t]; ta.out[nz] = out;
     }
   }
   if (nz == 0) return FLEXCO_OK;
   LR(launch_lora_shrink_mfma(su, nz, s));
-  LR(launch_lora_finalize(fu, nz, s));
   LR(launch_lora_transpose(ta, nz, s));
   return FLEXCO_OK;
 }
@@ -395,23 +381,19 @@ int32_t backward_projection(const flexco_layer_cfg& c, const flexco_lora* lora, 
   const int dt = c.dtype, r = c.lora_rank, N_dx = g.N_dx;
   const size_t e = esize(dt);
   if (g.fused) {
-    // t_t = dy_t B_t of the group's targets in one launch (+ its reduction, which also writes the
-    // scaled bf16 copy the GEMM extension reads)
+    // t_t = dy_t B_t of the group's targets in one launch (fp32, and the scaled bf16 copy the GEMM
+    // extension reads)
     LoraShrinkArgs st;
-    LoraFinalizeArgs ft;
     GemmExt ext;
-    memset(&st, 0, sizeof(st)); memset(&ft, 0, sizeof(ft)); memset(&ext, 0, sizeof(ext));
-    st.n = n; st.r = r;
-    ft.n = n; ft.r = r; ft.scale = c.lora_scale;
+    memset(&st, 0, sizeof(st)); memset(&ext, 0, sizeof(ext));
+    st.rows = n; st.r = r; st.scale = c.lora_scale;
     ext.n = g.nact; ext.r = r;
     for (int z = 0; z < g.nact; ++z) {
       const int t = g.targets[g.act[z]];
       int in, out;
       target_dims(c, t, &in, &out);
       st.X[z] = (const bf16_t*)boff(dy, g.col0[g.act[z]], e); st.ldx[z] = K_dy; st.S[z] = k.lw.bt[t]; st.lds[z] = out;
-      st.K[z] = out; st.KS[z] = lora_shrink_splits(n, out);
-      st.part[z] = k.lw.part_t[t];
-      ft.part[z] = k.lw.part_t[t]; ft.KS[z] = st.KS[z]; ft.out_f32[z] = k.lw.t[t]; ft.out_ext[z] = k.lw.ext[t];
+      st.K[z] = out; st.out_f32[z] = k.lw.t[t]; st.out_ext[z] = k.lw.ext[t];
       ext.A2[z] = k.lw.ext[t]; ext.W2[z] = (const bf16_t*)lora->A[t]; ext.ldw2[z] = in;
       // dB_t[o, j] += scale sum_m dy_t[m, o] u_t[m, j];   dA_t[j, i] += scale sum_m x_t[m, i] t_t[m, j]
       int q = outer.count;
@@ -423,7 +405,6 @@ int32_t backward_projection(const flexco_layer_cfg& c, const flexco_lora* lora, 
       outer.count = q + 1;
     }
     LR(launch_lora_shrink_mfma(st, g.nact, s));
-    LR(launch_lora_finalize(ft, g.nact, s));
     if (dx)
       return launch_gemm(dy, W, dx, nullptr, nullptr, n, N_dx, K_dy, K_dy, N_dx, N_dx, 0, true, dt, s, &ext,
                          k.gemm_part, k.gemm_part_elems);

@@ -11,21 +11,14 @@ namespace flexco {
 
 // ---- argument blocks of the bf16 LoRA kernels (up to 3 matrices per launch, grid.z) ----------
 constexpr int LORA_MATS = 7;   // matrices one LoRA launch can batch: one per target (q, k, v, o, gate, up, down)
-struct LoraShrinkArgs {     // part[z][ks][row][rank] = sum over the split's k of X[z][row, k] S[z][rank, k]
+struct LoraShrinkArgs {     // out[z][row][rank] = sum_k X[z][row, k] S[z][rank, k]   (skinny product with a rank-r matrix)
   const bf16_t* X[LORA_MATS]; size_t ldx[LORA_MATS];
   const bf16_t* S[LORA_MATS]; size_t lds[LORA_MATS];
-  float* part[LORA_MATS];
-  int K[LORA_MATS], KS[LORA_MATS];   // contracted width and its split count, per matrix
-  const int32_t* row_idx;   // rows of X to take (NULL: 0..n)
-  int n, r;
-};
-struct LoraFinalizeArgs {
-  const float* part[LORA_MATS];
-  float* out_f32[LORA_MATS];        // [n, r] or NULL
-  bf16_t* out_ext[LORA_MATS];       // [rows, r] scaled, or NULL
-  int KS[LORA_MATS];
-  const int32_t* ext_map;   // forward: [ext_rows] index into the n shrunk rows or -1; NULL: identity
-  int ext_rows, n, r;
+  int K[LORA_MATS];                 // contracted width, per matrix
+  float* out_f32[LORA_MATS];        // [rows, r] or NULL
+  bf16_t* out_ext[LORA_MATS];       // [rows, r], scaled by `scale`, or NULL (operand of the GEMM extension)
+  const int32_t* row_map;   // [rows] or NULL: rows with row_map[row] < 0 have no adapter, their out_ext rows are zero
+  int rows, r;
   float scale;
 };
 struct LoraTransposeArgs { const bf16_t* B[LORA_MATS]; bf16_t* Bt[LORA_MATS]; int out[LORA_MATS]; int r; };
@@ -80,9 +73,7 @@ int32_t launch_gemm_generic(const void* A, const void* W, void* C, const void* b
 int32_t launch_gemm_mfma(const void* A, const void* W, void* C, const void* bias, const void* residual, int M,
                          int N, int K, size_t lda, size_t ldw, size_t ldc, size_t ldr, bool trans_w,
                          const GemmExt* ext, hipStream_t s, float* part = nullptr, size_t part_elems = 0);
-int lora_shrink_splits(int n_rows, int K);
 int32_t launch_lora_shrink_mfma(const LoraShrinkArgs& a, int n_mats, hipStream_t s);
-int32_t launch_lora_finalize(const LoraFinalizeArgs& a, int n_mats, hipStream_t s);
 int32_t launch_lora_transpose(const LoraTransposeArgs& a, int n_mats, hipStream_t s);
 int32_t launch_lora_outer_batch(const LoraOuterArgs& a, hipStream_t s);
 int32_t launch_lora_outer_bf16(const void* X, size_t ldx, const float* U, float* G, size_t g_i, size_t g_j, int n,

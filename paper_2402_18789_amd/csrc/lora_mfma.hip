@@ -5,11 +5,11 @@
 //   shrink   u = x A^T  (or t = dy B)   skinny product [n, K] x [K, r] on the matrix cores:
 //            one wavefront multiplies 16 rows by up to 64 ranks with v_mfma_f32_16x16x32_bf16,
 //            both operands fetched straight from global memory (8 consecutive k per lane),
-//            K is cut across the 4 wavefronts of a block and across blocks (grid.y); the
-//            per-split partial sums are combined in a fixed order by the finalize kernel,
-//            so results do not depend on scheduling.
+//            K is cut across the up to 16 wavefronts of a block, whose partial sums are added
+//            in wavefront order through LDS, so results do not depend on scheduling; the block
+//            writes the fp32 result and/or the scaled bf16 operand of the GEMM extension.
 //   expand   is not a kernel: the projection GEMM appends the rank-r product as extra
-//            k-steps (gemm_mfma.hip), reading the bf16 matrix the finalize kernel writes.
+//            k-steps (gemm_mfma.hip), reading the bf16 matrix the shrink kernel writes.
 //   outer    dB += scale dy^T u,  dA += scale t^T x : every output element is a sum over
 //            the window's rows only; plain FMA code, 64 consecutive outputs per wavefront,
 //            rows interleaved over the block's 4 wavefronts, fixed-order LDS reduction.
@@ -21,20 +21,29 @@ namespace flexco {
 
 namespace {
 
+// One block per 16 rows and matrix; K is cut across the block's wavefronts (blockDim.x / 64, a
+// power of two <= 16), whose partial sums are added in wavefront order through LDS.
 template <int RT>   // rank tiles of 16
-__global__ __launch_bounds__(256) void lora_shrink_kernel(LoraShrinkArgs a) {
-  __shared__ float red[4][RT][64][4];
-  const int z = blockIdx.z, tile = blockIdx.x, ks = blockIdx.y;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+__global__ __launch_bounds__(1024) void lora_shrink_kernel(LoraShrinkArgs a) {
+  __shared__ float red[16][RT][64][4];
+  const int z = blockIdx.y, tile = blockIdx.x;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = blockDim.x >> 6;
   const int m = lane & 15, g = lane >> 4;
+  const int row = tile * 16 + m;
+  const bool row_ok = row < a.rows && (!a.row_map || a.row_map[row] >= 0);
+  // every wavefront looks at the same 16 rows, so this is the same for the whole block
+  const bool any_row = __ballot(row_ok) != 0;
+  if (!any_row) {   // a tile without adapter rows: only its zero rows of the GEMM operand are due
+    if (a.out_ext[z])
+      for (int idx = threadIdx.x; idx < 16 * a.r; idx += blockDim.x)
+        if (tile * 16 + idx / a.r < a.rows) a.out_ext[z][(size_t)tile * 16 * a.r + idx] = (bf16_t)0.f;
+    return;
+  }
   const bf16_t* X = a.X[z];
   const bf16_t* S = a.S[z];
-  const int row = tile * 16 + m;
-  const int rclamp = row < a.n ? row : 0;
-  const size_t src_row = a.row_idx ? (size_t)a.row_idx[rclamp] : (size_t)rclamp;
-  if (ks >= a.KS[z]) return;   // matrices of one launch may be split differently
-  const int k_blk = a.K[z] / a.KS[z], k_wave = k_blk / 4;
-  const int k0 = ks * k_blk + wave * k_wave, k1 = k0 + k_wave;
+  const size_t src_row = row_ok ? (size_t)row : 0;   // rows without adapter read row 0; their results are dropped
+  const int k_wave = a.K[z] / nw;
+  const int k0 = wave * k_wave, k1 = k0 + k_wave;
   const bf16_t* xp = X + src_row * a.ldx[z] + g * 8;
   const bf16_t* sp[RT];
   bool rank_ok[RT];
@@ -47,47 +56,48 @@ __global__ __launch_bounds__(256) void lora_shrink_kernel(LoraShrinkArgs a) {
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) acc[rt] = f32x4{0.f, 0.f, 0.f, 0.f};
   const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll 4
-  for (int k = k0; k < k1; k += 32) {
-    const bf16x8 xa = *reinterpret_cast<const bf16x8*>(xp + k);
-#pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-      bf16x8 sb = *reinterpret_cast<const bf16x8*>(sp[rt] + k);
-      if (!rank_ok[rt]) sb = zero;
-      acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa, sb, acc[rt], 0, 0, 0);
-    }
+  // This kernel lives on memory latency: the loads of U steps are issued together, then multiplied.
+  // k_wave is a multiple of 128 (4 steps); chunks of 8 steps while they fit (narrow ranks only).
+#define FLEXCO_SHRINK_CHUNK(U_)                                                                       \
+  {                                                                                                   \
+    bf16x8 xa_[U_], sb_[U_][RT];                                                                      \
+    _Pragma("unroll") for (int u = 0; u < U_; ++u) {                                                  \
+      xa_[u] = *reinterpret_cast<const bf16x8*>(xp + k + 32 * u);                                     \
+      _Pragma("unroll") for (int rt = 0; rt < RT; ++rt)                                               \
+        sb_[u][rt] = *reinterpret_cast<const bf16x8*>(sp[rt] + k + 32 * u);                           \
+    }                                                                                                 \
+    _Pragma("unroll") for (int u = 0; u < U_; ++u)                                                    \
+      _Pragma("unroll") for (int rt = 0; rt < RT; ++rt)                                               \
+        acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa_[u], rank_ok[rt] ? sb_[u][rt] : zero, acc[rt], 0, 0, 0); \
+    k += 32 * U_;                                                                                     \
   }
+  int k = k0;
+  if (RT <= 2)
+    while (k + 256 <= k1) FLEXCO_SHRINK_CHUNK(8)
+  while (k < k1) FLEXCO_SHRINK_CHUNK(4)
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
-    for (int e = 0; e < 4; ++e) red[wave][rt][lane][e] = acc[rt][e];
+    for (int q = 0; q < 4; ++q) red[wave][rt][lane][q] = acc[rt][q];
   __syncthreads();
-  // D[row = 4 (lane / 16) + e][rank = lane % 16]; one (lane, e) pair per thread and rank tile
-  const int ln = threadIdx.x >> 2, e = threadIdx.x & 3;
-  const int orow = tile * 16 + 4 * (ln >> 4) + e;
+  // D[row = 4 (lane / 16) + e][rank = lane % 16]: the 256 (lane, e) pairs of a rank tile are shared
+  // out over the block's threads
+  for (int idx = threadIdx.x; idx < 256; idx += blockDim.x) {
+    const int ln = idx >> 2, e = idx & 3;
+    const int orow = tile * 16 + 4 * (ln >> 4) + e;
+    if (orow >= a.rows) continue;
+    const bool out_ok = !a.row_map || a.row_map[orow] >= 0;
 #pragma unroll
-  for (int rt = 0; rt < RT; ++rt) {
-    const int rank = rt * 16 + (ln & 15);
-    const float v = red[0][rt][ln][e] + red[1][rt][ln][e] + red[2][rt][ln][e] + red[3][rt][ln][e];
-    if (orow < a.n && rank < a.r) a.part[z][((size_t)ks * a.n + orow) * a.r + rank] = v;
+    for (int rt = 0; rt < RT; ++rt) {
+      const int rank = rt * 16 + (ln & 15);
+      if (rank >= a.r) continue;
+      float v = 0.f;
+      for (int w = 0; w < nw; ++w) v += red[w][rt][ln][e];
+      const size_t o = (size_t)orow * a.r + rank;
+      if (a.out_f32[z] && out_ok) a.out_f32[z][o] = v;
+      if (a.out_ext[z]) a.out_ext[z][o] = (bf16_t)(out_ok ? v * a.scale : 0.f);
+    }
   }
-}
-
-// sums the K-split partials in split order; writes the float result and/or the scaled bf16 matrix
-// the GEMM extension reads.  With ext_map (forward): one thread per (token, rank), tokens without
-// adapter get zeros.
-__global__ __launch_bounds__(256) void lora_finalize_kernel(LoraFinalizeArgs a) {
-  const int z = blockIdx.z;
-  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-  const int rows = a.ext_map ? a.ext_rows : a.n;
-  if (idx >= (size_t)rows * a.r) return;
-  const int row = (int)(idx / a.r), rank = (int)(idx % a.r);
-  const int src = a.ext_map ? a.ext_map[row] : row;
-  float v = 0.f;
-  if (src >= 0)
-    for (int ks = 0; ks < a.KS[z]; ++ks) v += a.part[z][((size_t)ks * a.n + src) * a.r + rank];
-  if (a.out_f32[z] && src >= 0) a.out_f32[z][(size_t)src * a.r + rank] = v;
-  if (a.out_ext[z]) a.out_ext[z][idx] = (bf16_t)(v * a.scale);
 }
 
 // Bt[j][o] = B[o][j]
@@ -164,40 +174,23 @@ int32_t post(const char* what) {
 
 }  // namespace
 
-int lora_shrink_splits(int n_rows, int K) {
-  // K / KS must be a multiple of 128 (32 per MFMA step x 4 wavefronts); aim at >= 256 blocks
-  const int units = K / 128;
-  const int tiles = (n_rows + 15) / 16;
-  int best = 1;
-  for (int ks = 1; ks <= units && ks <= 32; ++ks)
-    if (units % ks == 0) {
-      best = ks;
-      if (tiles * ks >= 256) break;
-    }
-  return best;
-}
-
 int32_t launch_lora_shrink_mfma(const LoraShrinkArgs& a, int n_mats, hipStream_t s) {
-  if (a.n == 0 || n_mats == 0) return FLEXCO_OK;
-  int ks_max = 1;
-  for (int z = 0; z < n_mats; ++z) ks_max = a.KS[z] > ks_max ? a.KS[z] : ks_max;
-  const dim3 grid((a.n + 15) / 16, ks_max, n_mats);
+  if (a.rows == 0 || n_mats == 0) return FLEXCO_OK;
+  // wavefronts per block: the largest power of two <= 16 that cuts every K into whole groups of 4 MFMA steps
+  int nw = 16;
+  for (int z = 0; z < n_mats; ++z)
+    while (nw > 1 && a.K[z] % (128 * nw) != 0) nw >>= 1;
+  for (int z = 0; z < n_mats; ++z)
+    if (a.K[z] % (128 * nw) != 0) return fail(FLEXCO_ESHAPE, "LoRA shrink: K = %d is not a multiple of 128", a.K[z]);
+  const dim3 grid((a.rows + 15) / 16, n_mats), block(64 * nw);
   const int rt = (a.r + 15) / 16;
   switch (rt) {
-    case 1: hipLaunchKernelGGL(lora_shrink_kernel<1>, grid, dim3(256), 0, s, a); break;
-    case 2: hipLaunchKernelGGL(lora_shrink_kernel<2>, grid, dim3(256), 0, s, a); break;
-    case 3: hipLaunchKernelGGL(lora_shrink_kernel<3>, grid, dim3(256), 0, s, a); break;
-    default: hipLaunchKernelGGL(lora_shrink_kernel<4>, grid, dim3(256), 0, s, a); break;
+    case 1: hipLaunchKernelGGL(lora_shrink_kernel<1>, grid, block, 0, s, a); break;
+    case 2: hipLaunchKernelGGL(lora_shrink_kernel<2>, grid, block, 0, s, a); break;
+    case 3: hipLaunchKernelGGL(lora_shrink_kernel<3>, grid, block, 0, s, a); break;
+    default: hipLaunchKernelGGL(lora_shrink_kernel<4>, grid, block, 0, s, a); break;
   }
   return post("lora_shrink");
-}
-
-int32_t launch_lora_finalize(const LoraFinalizeArgs& a, int n_mats, hipStream_t s) {
-  const int rows = a.ext_map ? a.ext_rows : a.n;
-  if (rows == 0 || n_mats == 0) return FLEXCO_OK;
-  const size_t total = (size_t)rows * a.r;
-  hipLaunchKernelGGL(lora_finalize_kernel, dim3((unsigned)((total + 255) / 256), 1, n_mats), dim3(256), 0, s, a);
-  return post("lora_finalize");
 }
 
 int32_t launch_lora_transpose(const LoraTransposeArgs& a, int n_mats, hipStream_t s) {
