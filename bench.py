@@ -47,6 +47,10 @@ def main():
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--overlap", action="store_true",
+                    help="co-serving as in Sec. 6.2 of the paper: the window backward runs on a second stream, "
+                         "concurrently with the forward of the batch, on a finetune sequence of its own")
+    ap.add_argument("--no-two-stream", action="store_true", help="skip the additional two-stream measurement")
     ap.add_argument("--kv-split-pages", type=int, default=0,
                     help="pages per attention work item (0 = the library's default)")
     args = ap.parse_args()
@@ -68,7 +72,8 @@ def main():
     W = gen.layer_weights(cfg, seed, 0)
     lora = gen.lora_weights(cfg, seed, 0)
     layers = [HH.DeviceLayer(cfg, W, lora) for _ in range(max(1, args.weight_copies))]
-    pool = HH.DevicePool(cfg, batch.num_pages)
+    n_seq_pages = len(batch.seq_pages[[r for r in batch.requests if r.kind == 2][0].seq_id])
+    pool = HH.DevicePool(cfg, batch.num_pages + n_seq_pages)   # + room for the two-stream run's own sequence
     # cached prefixes: N(0,1) values in every page (device generator); the sampled sequences the CPU
     # baseline also reads are overwritten with the host generator's rows
     pool.fill_random(seed)
@@ -101,11 +106,41 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    def step(i):
+    def step_serial(i):
         ly = layers[i % len(layers)]
         B.flexco_layer_forward(ly.c, ly.w, ly.lora, db.maps, x, y, pool.c, ft.c, ws.ptr, ws.bytes)
         B.flexco_lora_bwd(ly.c, ly.w, ly.lora, pool.c, ft_pages, n_ft_pages, ft.c, ft_req.start_pos, ft_req.n_new,
                           dY, dX, ws.ptr, ws.bytes)
+
+    def make_overlap_step():
+        # The backward window of an iteration belongs to a sequence whose forward passes ran in earlier
+        # iterations (Alg. 2: all forward windows, then the backward windows).  That sequence gets pages
+        # and finetune state of its own - copies of what one forward of the batch leaves behind - so the
+        # two streams touch disjoint data, the frozen weights and LoRA factors (both only read) apart.
+        ly = layers[0]
+        B.flexco_layer_forward(ly.c, ly.w, ly.lora, db.maps, x, y, pool.c, ft.c, ws.ptr, ws.bytes)
+        torch.cuda.synchronize()
+        src_pages = ft_pages.long()
+        bwd_pages = torch.arange(batch.num_pages, batch.num_pages + n_ft_pages, device="cuda")
+        pool.k[bwd_pages] = pool.k[src_pages]
+        pool.v[bwd_pages] = pool.v[src_pages]
+        ft_b = HH.DeviceFtState(cfg, L)
+        for name in ("q_cache", "attn", "x", "x2", "gate", "up", "lse"):
+            getattr(ft_b, name).copy_(getattr(ft, name))
+        bwd_pages = bwd_pages.to(torch.int32)
+        ws_b = HH.Workspace(layers[0].c, T, hm.n_parts, n_ft, L)
+        side = torch.cuda.Stream()
+        torch.cuda.synchronize()
+
+        def step_two_streams(i):
+            ly = layers[i % len(layers)]
+            B.flexco_layer_forward(ly.c, ly.w, ly.lora, db.maps, x, y, pool.c, ft.c, ws.ptr, ws.bytes)
+            B.flexco_lora_bwd(ly.c, ly.w, ly.lora, pool.c, bwd_pages, n_ft_pages, ft_b.c, ft_req.start_pos,
+                              ft_req.n_new, dY, dX, ws_b.ptr, ws_b.bytes, stream=side)
+        step_two_streams.keep = (ft_b, ws_b, bwd_pages, side)
+        return step_two_streams
+
+    step = make_overlap_step() if args.overlap else step_serial
 
     for i in range(args.warmup):
         step(i)
@@ -116,7 +151,7 @@ def main():
     for name, kid in B.KERNEL_IDS.items():
         B.flexco_kernel_timer_start(kid, 64 * probe_steps)
     for i in range(probe_steps):
-        step(i)
+        step_serial(i)      # one stream: every class's launches run alone, durations are the kernels' own
     torch.cuda.synchronize()
     probe = {}
     for name, kid in B.KERNEL_IDS.items():
@@ -138,7 +173,8 @@ def main():
     wall_ms = (time.perf_counter() - t0) * 1e3
     gpu_ms = ev0.elapsed_time(ev1)
     dom_ms, dom_launches = B.flexco_kernel_timer_stop(B.KERNEL_IDS[dominant])
-    ms_per_step = max(wall_ms, gpu_ms) / args.steps
+    # with two streams the events on the forward's stream do not bracket the backward: wall clock only
+    ms_per_step = (wall_ms if args.overlap else max(wall_ms, gpu_ms)) / args.steps
     value = T / (ms_per_step * 1e-3)
 
     work = algorithmic_work(cfg, batch, hm)
@@ -159,11 +195,27 @@ def main():
                                "tokens + LoRA r16 (q,k,v,o,down) window backward",
                    "tokens": T, "finetune_tokens": n_ft, "requests": hm.n_req,
                    "cached_positions": int(sum(r.start_pos + r.n_new for r in batch.requests)),
-                   "weight_copies_cycled": len(layers)},
+                   "weight_copies_cycled": len(layers),
+                   "streams": "forward and window backward concurrent on two streams" if args.overlap else "one stream"},
         "roofline": roofline,
         "kernel_classes": classes,
         "gpu_event_ms_per_step": gpu_ms / args.steps,
     }
+    if not args.overlap and not args.no_two_stream:
+        # the same K steps again with the window backward on a second stream (reported beside the
+        # one-stream figures above, which stay the headline: their kernel durations are undisturbed)
+        step2 = make_overlap_step()
+        for i in range(args.warmup):
+            step2(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step2(i)
+        torch.cuda.synchronize()
+        ms2 = (time.perf_counter() - t0) * 1e3 / args.steps
+        out["two_streams"] = {"value": T / (ms2 * 1e-3), "unit": "tokens/s", "ms_per_step": ms2,
+                              "what": "same steps, the window backward on a second stream concurrent with the "
+                                      "forward (Sec. 6.2 of the paper), on a finetune sequence of its own"}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, batch, sample, W, lora, seed, x_np, ft_req, L)
     print(json.dumps(out), flush=True)
