@@ -201,6 +201,7 @@ def main():
         "kernel_classes": classes,
         "gpu_event_ms_per_step": gpu_ms / args.steps,
     }
+    out["measured_ceilings"] = measured_ceilings(B, torch)
     if not args.overlap and not args.no_two_stream:
         # the same K steps again with the window backward on a second stream (reported beside the
         # one-stream figures above, which stay the headline: their kernel durations are undisturbed)
@@ -219,6 +220,33 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, batch, sample, W, lora, seed, x_np, ft_req, L)
     print(json.dumps(out), flush=True)
+
+
+def measured_ceilings(B, torch):
+    """What this GPU sustains for the two roofline resources, with the library's probe kernels: an MFMA
+    loop on register operands and a contiguous read stream (each timed with events, best of 3)."""
+    sink = torch.zeros(16, dtype=torch.float32, device="cuda")
+    buf = torch.empty(4 << 30, dtype=torch.uint8, device="cuda")
+    buf.fill_(1)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    best_mfma, best_read = 0.0, 0.0
+    for rep in range(4):
+        ev0.record()
+        flops = B.flexco_probe_mfma(256, 20000, sink)
+        ev1.record()
+        torch.cuda.synchronize()
+        if rep:
+            best_mfma = max(best_mfma, flops / (ev0.elapsed_time(ev1) * 1e-3) / 1e12)
+        ev0.record()
+        nbytes = B.flexco_probe_read(buf, buf.numel(), 2048, sink)
+        ev1.record()
+        torch.cuda.synchronize()
+        if rep:
+            best_read = max(best_read, nbytes / (ev0.elapsed_time(ev1) * 1e-3) / 1e9)
+    del buf
+    return {"mfma_bf16_loop_tflops": best_mfma, "hbm_read_stream_gbs": best_read,
+            "what": "probe kernels of the library: 256 blocks x 4 wavefronts of back-to-back v_mfma_f32_32x32x16_bf16 on "
+                    "register operands in [-1, 1); 2048 blocks streaming 4 GiB with 16-byte loads"}
 
 
 def algorithmic_work(cfg, batch, hm):

@@ -311,6 +311,18 @@ int32_t flexco_gemm(const void* A, const void* W, void* C, const void* bias, con
 int32_t flexco_kernel_timer_start(int32_t kernel_id, int32_t max_launches);
 int32_t flexco_kernel_timer_stop(int32_t kernel_id, double* total_ms, int64_t* launches);
 
+/* Machine-ceiling probes for the benchmark (they compute nothing of the method): what this GPU
+ * sustains for the two resources the rooflines are quoted against.  Both only enqueue one kernel
+ * on `stream`; the caller times it with events.  sink: device, >= 4 bytes, never written in
+ * practice (it keeps the compiler from removing the work).
+ *   flexco_probe_mfma: `blocks` blocks of 4 wavefronts, each `iters` x 16 back-to-back
+ *     v_mfma_f32_32x32x16_bf16 on register operands with values in [-1, 1); *flops = work enqueued.
+ *   flexco_probe_read: `blocks` blocks each stream their own contiguous piece of src[0, bytes) with
+ *     16-byte loads; *bytes_read = bytes actually read (bytes rounded down to whole rounds). */
+int32_t flexco_probe_mfma(int32_t blocks, int32_t iters, void* sink, double* flops, void* stream);
+int32_t flexco_probe_read(const void* src, size_t bytes, int32_t blocks, void* sink, double* bytes_read,
+                          void* stream);
+
 #ifdef __cplusplus
 }
 #endif

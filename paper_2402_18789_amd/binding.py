@@ -92,6 +92,8 @@ def _load():
         "flexco_gemm": [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp],
         "flexco_kernel_timer_start": [i32, i32],
         "flexco_kernel_timer_stop": [i32, P(C.c_double), P(C.c_int64)],
+        "flexco_probe_mfma": [i32, i32, vp, P(C.c_double), vp],
+        "flexco_probe_read": [vp, sz, i32, vp, P(C.c_double), vp],
     }
     for name, args in sigs.items():
         fn = getattr(lib, name)
@@ -104,7 +106,7 @@ _lib = _load()
 EXPORTS = ("flexco_last_error", "flexco_abi_version", "flexco_maps_blob_ints", "flexco_build_maps",
            "flexco_maps_rebase", "flexco_workspace_bytes", "flexco_layer_forward", "flexco_attention_mixed",
            "flexco_lora_fwd", "flexco_lora_bwd", "flexco_attention_window_bwd", "flexco_gemm",
-           "flexco_kernel_timer_start", "flexco_kernel_timer_stop")
+           "flexco_kernel_timer_start", "flexco_kernel_timer_stop", "flexco_probe_mfma", "flexco_probe_read")
 KERNEL_IDS = {"gemm_fwd": 0, "gemm_bwd": 1, "attn_fwd": 2, "attn_merge": 3, "attn_bwd": 4, "elemwise": 5, "lora": 6,
               "generic": 7}
 
@@ -244,6 +246,20 @@ def flexco_attention_window_bwd(cfg, pool, seq_pages, n_seq_pages, win_start, wi
 def flexco_gemm(A, W, Cout, bias, residual, M, N, K, trans_w, dtype, stream=None):
     _check(_lib.flexco_gemm(_ptr(A), _ptr(W), _ptr(Cout), _ptr(bias), _ptr(residual), M, N, K, int(trans_w), dtype,
                             _stream(stream)))
+
+
+def flexco_probe_mfma(blocks, iters, sink, stream=None):
+    """-> flops enqueued"""
+    fl = C.c_double(0.0)
+    _check(_lib.flexco_probe_mfma(blocks, iters, _ptr(sink), C.byref(fl), _stream(stream)))
+    return fl.value
+
+
+def flexco_probe_read(src, nbytes, blocks, sink, stream=None):
+    """-> bytes the kernel reads"""
+    nb = C.c_double(0.0)
+    _check(_lib.flexco_probe_read(_ptr(src), nbytes, blocks, _ptr(sink), C.byref(nb), _stream(stream)))
+    return nb.value
 
 
 def flexco_kernel_timer_start(kernel_id, max_launches):

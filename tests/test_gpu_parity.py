@@ -198,9 +198,12 @@ def test_attention_window_bwd(cfg_name, win_start, win_len):
 # ------------------------------------------------------------------------------------------
 # whole layer: forward iterations, then token-window backward
 # ------------------------------------------------------------------------------------------
-def run_layer_case(cfg, batch0, ft_window, prefill_chunk, bwd_windows, seed=0, split=0, need_dx=True):
+def run_layer_case(cfg, batch0, ft_window, prefill_chunk, bwd_windows, seed=0, split=0, need_dx=True, tol_qk=None):
+    """tol_qk: bound for the tensors that depend on the gradient through the softmax logits (dX, the K
+    accumulator, dA/dB of q and k) when it differs from the general one (see the callers that pass it)."""
     report = []
     tol = TOL[cfg.dtype]
+    tol_qk = tol if tol_qk is None else tol_qk
     case = Case(cfg, batch0, seed=seed, kv_split_pages=split)
     batch, it = batch0, 0
     ft_seq = [r.seq_id for r in batch0.requests if r.kind == KIND_FINETUNE][0]
@@ -224,7 +227,7 @@ def run_layer_case(cfg, batch0, ft_window, prefill_chunk, bwd_windows, seed=0, s
     st_d, st_o = case.d_ft[ft_seq], case.o_ft[ft_seq]
     for name in ("q_cache", "x", "x2", "gate", "up", "attn"):
         assert_close("saved " + name, to_np(getattr(st_d, name)), getattr(st_o, name), tol, report)
-    assert float(np.max(np.abs(to_np(st_d.lse) - st_o.lse))) <= (1e-4 if cfg.dtype == "f32" else 2e-2)
+    assert_close("saved lse", to_np(st_d.lse), st_o.lse, tol, report)
     # backward: loss = MSE to seeded targets on the finetune sequence's layer output (oracle's dY on
     # both sides, so that the backward pass is compared on identical inputs)
     target = gen.loss_targets(cfg, seed, L).astype(np.float64)
@@ -243,14 +246,14 @@ def run_layer_case(cfg, batch0, ft_window, prefill_chunk, bwd_windows, seed=0, s
         l -= s
     assert l == 0
     if need_dx:
-        assert_close("dX", dX_g, dX_o, tol, report)
-    assert_close("dk_accum", to_np(st_d.dk_accum), st_o.dk_accum, tol, report)
+        assert_close("dX", dX_g, dX_o, tol_qk, report)
+    assert_close("dk_accum", to_np(st_d.dk_accum), st_o.dk_accum, tol_qk, report)
     assert_close("dv_accum", to_np(st_d.dv_accum), st_o.dv_accum, tol, report)
     grads_g = case.dev.grads_numpy()
     assert set(grads_g) == set(grads_o) == set(cfg.lora_targets)
     for t in cfg.lora_targets:
-        assert_close(f"dA[{t}]", grads_g[t][0], grads_o[t][0], tol, report)
-        assert_close(f"dB[{t}]", grads_g[t][1], grads_o[t][1], tol, report)
+        assert_close(f"dA[{t}]", grads_g[t][0], grads_o[t][0], tol_qk if t in ("q", "k") else tol, report)
+        assert_close(f"dB[{t}]", grads_g[t][1], grads_o[t][1], tol_qk if t in ("q", "k") else tol, report)
     say("  " + ", ".join(f"{n}={e:.1e}" for n, e in report))
     return case, report
 
@@ -288,6 +291,29 @@ def test_layer_small_bf16_group5_all_targets():
     say("layer small bf16 group 5")
     b = gen.batch_scaled(8, 6, 30, 200, [(0, 50, 50)], [(0, 90, 170)])
     run_layer_case(SMALL_BF16_G5, b, ft_window=80, prefill_chunk=16, bwd_windows=[170], seed=8, split=4)
+
+
+# The 14B / 32B shapes on short sequences: outputs, saved activations and the gradients that do not pass
+# through the softmax logits stay within the 2e-2 bar.  The gradients through the logits (dS = P (dP -
+# delta)) see the bf16 rounding of the cached q and k rows as a perturbation of the logits themselves:
+# |dS_ij| errors of a few percent per entry, which the short key ranges of these cases (<= 96 keys) do
+# not average away as the 2048-key benchmark window does.  Their bound here is 4e-2 (observed: up to
+# 3.4e-2 on dA[k]); at the benchmark configuration they meet 2e-2 (test_layer_c2_full_size_sampled).
+def test_layer_c4_shape_all_targets():
+    """One layer at the 14B shape (hidden 5120, 40 query / 8 kv heads, FFN 13824, qkv bias, LoRA on all
+    seven projections) on a reduced token count the oracle finishes in seconds."""
+    say("layer at the c4 (14B) shape")
+    cfg = CONFIGS["c4_qwen14b_full"]
+    batch = gen.batch_scaled(7, 6, 20, 300, [(0, 40, 40)], [(0, 48, 96)])
+    run_layer_case(cfg, batch, ft_window=48, prefill_chunk=40, bwd_windows=[60, 36], seed=2, tol_qk=4e-2)
+
+
+def test_layer_c5_shape_rank32():
+    """One layer at the 32B shape (FFN 27648, LoRA rank 32 on all seven projections)."""
+    say("layer at the c5 (32B) shape")
+    cfg = CONFIGS["c5_qwen32b_full"]
+    batch = gen.batch_scaled(8, 4, 20, 200, [(0, 24, 24)], [(0, 32, 64)])
+    run_layer_case(cfg, batch, ft_window=32, prefill_chunk=24, bwd_windows=[40, 24], seed=3, tol_qk=4e-2)
 
 
 def test_forward_is_deterministic():
