@@ -84,7 +84,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(BwdArgs a) {
   __shared__ __attribute__((aligned(1024))) bf16_t kb1[4 * TILE16];
   __shared__ __attribute__((aligned(1024))) bf16_t vb0[4 * VPAGE];
   __shared__ __attribute__((aligned(1024))) bf16_t vb1[4 * VPAGE];
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform: LDS bases of the loads stay scalar
   const int c = lane & 15, g = lane >> 4;
   const int rt = wave & 1, kh = wave >> 1;
   const int h = blockIdx.y, group = a.nq / a.nkv, kvh = h / group;
@@ -244,7 +245,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(BwdArgs a) {
   __shared__ __attribute__((aligned(1024))) bf16_t ob1[2 * TILE16];
   __shared__ __attribute__((aligned(256))) float ld0[64];       // lse[32] | delta[32] of the step's rows
   __shared__ __attribute__((aligned(256))) float ld1[64];
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform: LDS bases of the loads stay scalar
   const int c = lane & 15, g = lane >> 4;
   const int kvh = blockIdx.y, group = a.nq / a.nkv;
   const int pg = blockIdx.x * 4 + wave;

@@ -13,10 +13,10 @@
 // (BM/2) x (BN/2) as 32 x 32 MFMA tiles with fp32 accumulators.
 //   * Forward form: operand tiles go from global memory straight into LDS
 //     (global_load_lds_dwordx4: one wavefront instruction fills 1 KB; lane l lands at
-//     base + 16 l), no staging registers and no LDS write instructions.  LDS is a ring of four
-//     32 KB stages, so two to three stages of loads are in flight while one is multiplied; the
-//     per-stage barrier carries no memory fence, the wait in front of it names exactly the
-//     loads that must have landed.  Rows are XOR-swizzled in 16-byte chunks (applied to the
+//     base + 16 l), no staging registers and no LDS write instructions.  LDS is a ring of stages
+//     (four of 32 KB for the 128 tile, two of 64 KB for the 256 tile) whose loads are in flight
+//     while another stage is multiplied; the per-stage barrier carries no memory fence, the wait
+//     in front of it names exactly the loads that must have landed.  Rows are XOR-swizzled in 16-byte chunks (applied to the
 //     global address a lane fetches) so that the ds_read_b128 operand fetches of 16 consecutive
 //     rows hit 64 distinct banks.
 //   * Input-gradient form: k-steps of 64, two LDS buffers filled through two sets of staging
@@ -66,7 +66,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
   const int tm = lid % tiles_m, tn = lid / tiles_m;
   const int m0 = tm * BM, n0 = tn * BN;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform: LDS bases of the tile loads stay scalar
   const int wm0 = (wave >> 1) * WM, wn0 = (wave & 1) * WN;
 
   f32x16 acc[MT][NT];
@@ -93,12 +94,18 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
 
   if constexpr (!TRANS) {
     // ======================= forward form: global memory -> LDS directly =======================
-    // A ring of four stages; a stage holds BKS = 16384 / (BM + BN) k-columns of both tiles
-    // (32 KB: [BM + BN][BKS] bf16, A rows first), so three stages can be in flight or waiting
-    // while one is multiplied.  The stages are four separate arrays, not one indexed buffer:
-    // the compiler then sees that loads in flight target an array no ds_read of that moment
-    // touches, and inserts no wait of its own.
-    constexpr int BKS = 16384 / (BM + BN);
+    // A ring of stages, each [BM + BN][BKS] bf16 (A rows first).  The 128 tile uses four stages of
+    // 32 KB (BKS = 64): up to three in flight or waiting while one is multiplied.  The 256 tile
+    // uses two stages of 64 KB (BKS = 64): half as many barriers, and a stage's buffer is handed
+    // to the loads of the stage after next as soon as its last fragments are in registers
+    // (measured equal at T = 1024 and 4-7 % faster than four 32 KB stages at T >= 2048).  The
+    // stages are separate arrays, not one indexed buffer: the compiler then sees that loads in
+    // flight target an array no ds_read of that moment touches, and inserts no wait of its own.
+#ifndef FLEXCO_NST_BIG
+#define FLEXCO_NST_BIG 2
+#endif
+    constexpr int NST = (BM + BN >= 512) ? FLEXCO_NST_BIG : 4;   // stages in the ring
+    constexpr int BKS = (NST == 2 ? 32768 : 16384) / (BM + BN);
     constexpr int CPR = BKS / 8;                 // 16-byte chunks per row
     constexpr int RPI = 64 / CPR;                // rows one wavefront load instruction fills (1 KB)
     constexpr int SL = BKS / 16;                 // MFMA k-slices per stage
@@ -107,8 +114,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
     static_assert(BKS == 32 || BKS == 64, "stage depth");
     __shared__ __attribute__((aligned(1024))) bf16_t ring0[ST_ELEMS];
     __shared__ __attribute__((aligned(1024))) bf16_t ring1[ST_ELEMS];
-    __shared__ __attribute__((aligned(1024))) bf16_t ring2[ST_ELEMS];
-    __shared__ __attribute__((aligned(1024))) bf16_t ring3[ST_ELEMS];
+    __shared__ __attribute__((aligned(1024))) bf16_t ring2[NST == 4 ? ST_ELEMS : 8];
+    __shared__ __attribute__((aligned(1024))) bf16_t ring3[NST == 4 ? ST_ELEMS : 8];
     // Rows are BKS bf16 wide; chunk c of row r is stored at chunk c ^ key(r), key(r) = (r >> 1) & 7
     // for 128-byte rows and (r >> 1) & 3 for 64-byte rows (the variants measured fastest for the
     // ds_read_b128 operand fetches: 85 % and 88 % of the LDS peak).
@@ -181,8 +188,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
         FLEXCO_MFMAS(af1, bf1)                                                                        \
         FLEXCO_ORDER_READS_FIRST                                                                      \
       } else {                                                                                        \
-        FLEXCO_WAIT_BARRIER(WAIT_ONE_STAGE)                                                           \
-        FLEXCO_DMA(free_, (s_) + 3)                                                                   \
+        FLEXCO_WAIT_BARRIER(WAIT_NEXT_STAGE)                                                          \
+        FLEXCO_DMA(free_, (s_) + AHEAD)                                                               \
         FLEXCO_FRAGS(nxt_, 0, af0, bf0)                                                               \
         FLEXCO_MFMAS(af1, bf1)                                                                        \
         FLEXCO_ORDER_LOADS_READS_FIRST                                                                \
@@ -214,25 +221,43 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
     // s_waitcnt immediates: vmcnt in bits 3:0 and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at
     // their maxima (no wait)
     constexpr int NLD = PA + PB;
-    static_assert(NLD <= 15 && NLD % (MT + NT) == 0, "loads per stage: vmcnt encoding, even spread over the slice");
-    constexpr int WAIT_ONE_STAGE = 0x0F70 | NLD;                     // vmcnt(NLD)
+    static_assert((NST == 2 || NLD <= 15) && NLD % (MT + NT) == 0, "loads per stage: vmcnt encoding, even spread over the slice");
+    // before a stage's barrier: the next stage has landed; with four stages one more may stay in flight
+    constexpr int WAIT_NEXT_STAGE = NST == 4 ? (0x0F70 | NLD) : 0x0F70;
+    // the buffer freed at stage s's barrier held stage s - 1 (four stages) or stage s itself (two)
+    constexpr int AHEAD = NST == 4 ? 3 : 2;
     constexpr int WAIT_TWO_STAGES = 0x0F70 | ((2 * NLD) & 15) | (((2 * NLD) >> 4) << 14);
     bf16x8 af0[MT], bf0[NT], af1[MT], bf1[NT];
-    FLEXCO_DMA(ring0, 0)
-    FLEXCO_DMA(ring1, 1)
-    FLEXCO_DMA(ring2, 2)
-    FLEXCO_WAIT_BARRIER(WAIT_TWO_STAGES)
-    FLEXCO_FRAGS(ring0, 0, af0, bf0)
-    int st = 0;
-    for (; st + 3 < ns; st += 4) {
-      FLEXCO_STAGE(ring0, ring1, ring3, st)
-      FLEXCO_STAGE(ring1, ring2, ring0, st + 1)
-      FLEXCO_STAGE(ring2, ring3, ring1, st + 2)
-      FLEXCO_STAGE(ring3, ring0, ring2, st + 3)
+    if constexpr (NST == 4) {
+      FLEXCO_DMA(ring0, 0)
+      FLEXCO_DMA(ring1, 1)
+      FLEXCO_DMA(ring2, 2)
+      FLEXCO_WAIT_BARRIER(WAIT_TWO_STAGES)
+      FLEXCO_FRAGS(ring0, 0, af0, bf0)
+      int st = 0;
+      for (; st + 3 < ns; st += 4) {
+        FLEXCO_STAGE(ring0, ring1, ring3, st)
+        FLEXCO_STAGE(ring1, ring2, ring0, st + 1)
+        FLEXCO_STAGE(ring2, ring3, ring1, st + 2)
+        FLEXCO_STAGE(ring3, ring0, ring2, st + 3)
+      }
+      if (st < ns) FLEXCO_STAGE(ring0, ring1, ring3, st)
+      if (st + 1 < ns) FLEXCO_STAGE(ring1, ring2, ring0, st + 1)
+      if (st + 2 < ns) FLEXCO_STAGE(ring2, ring3, ring1, st + 2)
+    } else {
+      // two stages of twice the depth: a stage's buffer is free as soon as its last fragments are in
+      // registers, i.e. at its own barrier, and takes the loads of the stage after next
+      FLEXCO_DMA(ring0, 0)
+      FLEXCO_DMA(ring1, 1)
+      FLEXCO_WAIT_BARRIER(0x0F70 | (NLD & 15) | ((NLD >> 4) << 14))
+      FLEXCO_FRAGS(ring0, 0, af0, bf0)
+      int st = 0;
+      for (; st + 1 < ns; st += 2) {
+        FLEXCO_STAGE(ring0, ring1, ring0, st)
+        FLEXCO_STAGE(ring1, ring0, ring1, st + 1)
+      }
+      if (st < ns) FLEXCO_STAGE(ring0, ring1, ring0, st)
     }
-    if (st < ns) FLEXCO_STAGE(ring0, ring1, ring3, st)
-    if (st + 1 < ns) FLEXCO_STAGE(ring1, ring2, ring0, st + 1)
-    if (st + 2 < ns) FLEXCO_STAGE(ring2, ring3, ring1, st + 2)
     __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0): nothing may land in LDS after the block ends
   } else {
     // ================== input-gradient form: staged through registers ==========================
