@@ -311,6 +311,53 @@ int32_t flexco_gemm(const void* A, const void* W, void* C, const void* bias, con
 int32_t flexco_kernel_timer_start(int32_t kernel_id, int32_t max_launches);
 int32_t flexco_kernel_timer_stop(int32_t kernel_id, double* total_ms, int64_t* launches);
 
+/* ---- Hybrid token scheduler (Sec. 6.2), host only ------------------------------------------
+ * Stage 1 chooses the inference work of an iteration (iteration-level scheduling with chunked
+ * prefill); stage 2 appends the largest finetuning window that keeps the estimated iteration
+ * latency within the SLO:  s = argmax f(c, s) <= SLO, c = inference tokens of the iteration, f from
+ * offline profiling.  Conventions the paper leaves open: f is a table over a (c, s) grid,
+ * interpolated bilinearly (beyond the grid the nearest segment is extended linearly); candidate
+ * windows are the multiples of `quantum` up to s_avail, and s_avail itself; requests are served in
+ * arrival (index) order; an iteration lists its decode entries first, then its prefill chunks. */
+typedef struct flexco_latency_model {
+  int32_t n_c, n_s;          /* grid sizes, each >= 2                                           */
+  const int32_t* c_grid;     /* [n_c] inference-token counts, strictly ascending (host)         */
+  const int32_t* s_grid;     /* [n_s] finetune-token counts, strictly ascending (host)          */
+  const float* ms;           /* [n_c, n_s] profiled latency of one iteration, any unit (host)   */
+} flexco_latency_model;
+
+#define FLEXCO_REQ_WAITING  0
+#define FLEXCO_REQ_RUNNING  1
+#define FLEXCO_REQ_FINISHED 2
+
+/* f(c, s) in double precision.  Errors: EINVAL (null, grids too short or not ascending). */
+int32_t flexco_latency_estimate(const flexco_latency_model* model, int32_t c, int32_t s, double* out_ms);
+
+/* Stage 2: *out_s = the largest candidate s <= s_avail with f(c, s) <= slo_ms, 0 if none.  Every
+ * candidate is evaluated (a profiled table need not be monotone).  Errors: EINVAL. */
+int32_t flexco_sched_window(const flexco_latency_model* model, int32_t c, double slo_ms, int32_t s_avail,
+                            int32_t quantum, int32_t* out_s);
+
+/* Stage 1, one iteration.  The five request arrays (host, n_req entries, arrival order) hold each
+ * request's prompt length (> 0), prompt tokens already processed, tokens to generate, tokens
+ * generated, and FLEXCO_REQ_* state; `state` is updated (waiting requests are admitted while fewer
+ * than max_batch run).  Every running request past its prompt gets one decode token at position
+ * prompt_len + generated; running requests still in their prompt get chunks of at most `chunk`
+ * tokens, in order, while the iteration's token_budget lasts.  The entries (request index, kind,
+ * start_pos, n_new) go to the four out arrays of out_capacity entries each; *out_n = their number,
+ * *out_tokens = c.  Errors: EINVAL, EWORKSPACE (out_capacity too small). */
+int32_t flexco_sched_inference(int32_t n_req, const int32_t* prompt_len, const int32_t* prefilled,
+                               const int32_t* gen_len, const int32_t* generated, int32_t* state,
+                               int32_t max_batch, int32_t token_budget, int32_t chunk,
+                               int32_t* out_req, int32_t* out_kind, int32_t* out_start_pos, int32_t* out_n_new,
+                               int32_t out_capacity, int32_t* out_n, int32_t* out_tokens);
+
+/* Books an executed iteration: prefilled / generated advance by what the entries processed, and a
+ * request with its prompt done and nothing left to generate becomes FLEXCO_REQ_FINISHED. */
+int32_t flexco_sched_advance(int32_t n_entries, const int32_t* req, const int32_t* kind, const int32_t* n_new,
+                             int32_t n_req, const int32_t* prompt_len, int32_t* prefilled,
+                             const int32_t* gen_len, int32_t* generated, int32_t* state);
+
 /* Machine-ceiling probes for the benchmark (they compute nothing of the method): what this GPU
  * sustains for the two resources the rooflines are quoted against.  Both only enqueue one kernel
  * on `stream`; the caller times it with events.  sink: device, >= 4 bytes, never written in

@@ -68,6 +68,11 @@ class FtState(C.Structure):
                                             "lse", "dk_accum", "dv_accum")]
 
 
+class LatencyModel(C.Structure):
+    _fields_ = [("n_c", C.c_int32), ("n_s", C.c_int32), ("c_grid", C.c_void_p), ("s_grid", C.c_void_p),
+                ("ms", C.c_void_p)]
+
+
 def _load():
     if not os.path.exists(LIB_PATH):
         raise ImportError("libflexco.so is not built: run `python paper_2402_18789_amd/build.py` "
@@ -94,6 +99,10 @@ def _load():
         "flexco_kernel_timer_stop": [i32, P(C.c_double), P(C.c_int64)],
         "flexco_probe_mfma": [i32, i32, vp, P(C.c_double), vp],
         "flexco_probe_read": [vp, sz, i32, vp, P(C.c_double), vp],
+        "flexco_latency_estimate": [P(LatencyModel), i32, i32, P(C.c_double)],
+        "flexco_sched_window": [P(LatencyModel), i32, C.c_double, i32, i32, P(i32)],
+        "flexco_sched_inference": [i32, vp, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, i32, P(i32), P(i32)],
+        "flexco_sched_advance": [i32, vp, vp, vp, i32, vp, vp, vp, vp, vp],
     }
     for name, args in sigs.items():
         fn = getattr(lib, name)
@@ -106,7 +115,8 @@ _lib = _load()
 EXPORTS = ("flexco_last_error", "flexco_abi_version", "flexco_maps_blob_ints", "flexco_build_maps",
            "flexco_maps_rebase", "flexco_workspace_bytes", "flexco_layer_forward", "flexco_attention_mixed",
            "flexco_lora_fwd", "flexco_lora_bwd", "flexco_attention_window_bwd", "flexco_gemm",
-           "flexco_kernel_timer_start", "flexco_kernel_timer_stop", "flexco_probe_mfma", "flexco_probe_read")
+           "flexco_kernel_timer_start", "flexco_kernel_timer_stop", "flexco_probe_mfma", "flexco_probe_read",
+           "flexco_latency_estimate", "flexco_sched_window", "flexco_sched_inference", "flexco_sched_advance")
 KERNEL_IDS = {"gemm_fwd": 0, "gemm_bwd": 1, "attn_fwd": 2, "attn_merge": 3, "attn_bwd": 4, "elemwise": 5, "lora": 6,
               "generic": 7}
 
@@ -260,6 +270,50 @@ def flexco_probe_read(src, nbytes, blocks, sink, stream=None):
     nb = C.c_double(0.0)
     _check(_lib.flexco_probe_read(_ptr(src), nbytes, blocks, _ptr(sink), C.byref(nb), _stream(stream)))
     return nb.value
+
+
+class HostLatencyModel:
+    """Owns the host arrays of a flexco_latency_model."""
+
+    def __init__(self, c_grid, s_grid, ms):
+        self.c_grid, self.s_grid = _i32(c_grid), _i32(s_grid)
+        self.ms = np.ascontiguousarray(ms, dtype=np.float32)
+        assert self.ms.shape == (self.c_grid.size, self.s_grid.size)
+        self.c = LatencyModel(self.c_grid.size, self.s_grid.size, self.c_grid.ctypes.data, self.s_grid.ctypes.data,
+                              self.ms.ctypes.data)
+
+
+def flexco_latency_estimate(model, c, s):
+    out = C.c_double(0.0)
+    _check(_lib.flexco_latency_estimate(C.byref(model.c), c, s, C.byref(out)))
+    return out.value
+
+
+def flexco_sched_window(model, c, slo_ms, s_avail, quantum):
+    out = C.c_int32(0)
+    _check(_lib.flexco_sched_window(C.byref(model.c), c, slo_ms, s_avail, quantum, C.byref(out)))
+    return out.value
+
+
+def flexco_sched_inference(prompt_len, prefilled, gen_len, generated, state, max_batch, token_budget, chunk):
+    """The five arrays are np.int32 (state is updated in place).  -> (entries [n, 4] = request, kind,
+    start_pos, n_new; c)"""
+    n = int(state.size)
+    cap = max(1, n)
+    out = np.zeros((4, cap), dtype=np.int32)
+    n_out, c = C.c_int32(0), C.c_int32(0)
+    _check(_lib.flexco_sched_inference(n, prompt_len.ctypes.data, prefilled.ctypes.data, gen_len.ctypes.data,
+                                       generated.ctypes.data, state.ctypes.data, max_batch, token_budget, chunk,
+                                       out[0].ctypes.data, out[1].ctypes.data, out[2].ctypes.data, out[3].ctypes.data,
+                                       cap, C.byref(n_out), C.byref(c)))
+    return out[:, :n_out.value].T.copy(), c.value
+
+
+def flexco_sched_advance(entries, prompt_len, prefilled, gen_len, generated, state):
+    e = np.ascontiguousarray(entries.T, dtype=np.int32) if len(entries) else np.zeros((4, 0), dtype=np.int32)
+    _check(_lib.flexco_sched_advance(e.shape[1], e[0].ctypes.data, e[1].ctypes.data, e[3].ctypes.data, int(state.size),
+                                     prompt_len.ctypes.data, prefilled.ctypes.data, gen_len.ctypes.data,
+                                     generated.ctypes.data, state.ctypes.data))
 
 
 def flexco_kernel_timer_start(kernel_id, max_launches):
