@@ -16,6 +16,8 @@ LIB_PATH = os.environ.get("FLEXCO_LIB_PATH", os.path.join(_HERE, "libflexco.so")
 FLEXCO_OK, FLEXCO_EINVAL, FLEXCO_ESHAPE, FLEXCO_EWORKSPACE, FLEXCO_EPAGE, FLEXCO_EUNSUPPORTED, FLEXCO_EHIP = \
     0, -1, -2, -3, -4, -5, -6
 FLEXCO_F32, FLEXCO_BF16 = 0, 1
+FLEXCO_DECODE, FLEXCO_PREFILL, FLEXCO_FINETUNE = 0, 1, 2
+FLEXCO_REQ_WAITING, FLEXCO_REQ_RUNNING, FLEXCO_REQ_FINISHED = 0, 1, 2
 TARGET_NAMES = ("q", "k", "v", "o", "gate", "up", "down")
 N_TARGETS = 7
 ABI_VERSION = 2
