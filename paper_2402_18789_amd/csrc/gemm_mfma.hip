@@ -19,9 +19,9 @@
 //     in front of it names exactly the loads that must have landed.  Rows are XOR-swizzled in 16-byte chunks (applied to the
 //     global address a lane fetches) so that the ds_read_b128 operand fetches of 16 consecutive
 //     rows hit 64 distinct banks.
-//   * Input-gradient form: k-steps of 64, two LDS buffers filled through two sets of staging
-//     registers; the W tile is [64][BN + 32] (k-major as in memory), an operand fragment (8
-//     consecutive k for one column) comes from two transposing LDS reads (ds_read_b64_tr_b16).
+//   * Input-gradient form: the same ring; the W tile is [64][BN] (k-major as in memory), loaded
+//     the same way, and an MFMA operand (8 consecutive k of one column) comes from two
+//     transposing LDS reads (ds_read_b64_tr_b16).
 // Work-group ids are remapped so that ids that land on the same XCD (id mod 8) work on
 // neighbouring tiles, M fastest: the W tile they share stays in that XCD's L2.
 #include "flexco_internal.h"
@@ -40,15 +40,6 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 #define FLEXCO_LP(p) ((__attribute__((address_space(3))) void*)(p))
 
 __device__ inline int swz(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
-
-// dynamic LDS of the input-gradient form
-template <int BM, int BN>
-struct SmemT {
-  static constexpr int A_ELEMS = BM * BK;
-  static constexpr int B_LD = BN + 32;   // 64 bytes of row padding: 4 consecutive rows x 64 bytes tile the 64 banks
-  static constexpr int B_ELEMS = BK * (BN + 32);
-  static constexpr size_t BYTES = 2 * (size_t)(A_ELEMS + B_ELEMS) * sizeof(bf16_t);
-};
 
 template <int BM, int BN, bool TRANS>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
@@ -80,7 +71,6 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
 
   // split-K: blockIdx.y owns k in [kbeg, kbeg + k_chunk) and writes fp32 partial sums to `part`
   const int kbeg = blockIdx.y * k_chunk;
-  const int nk = k_chunk / BK;
   const int l32 = lane & 31, kg = lane >> 5;
 
   // (the pipelines are macros on purpose: register arrays captured by lambdas were left in
@@ -92,74 +82,97 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af_[i], bf_[j], acc[i][j], 0, 0, 0);      \
   }
 
-  if constexpr (!TRANS) {
-    // ======================= forward form: global memory -> LDS directly =======================
-    // A ring of stages, each [BM + BN][BKS] bf16 (A rows first).  The 128 tile uses four stages of
-    // 32 KB (BKS = 64): up to three in flight or waiting while one is multiplied.  The 256 tile
-    // uses two stages of 64 KB (BKS = 64): half as many barriers, and a stage's buffer is handed
-    // to the loads of the stage after next as soon as its last fragments are in registers
-    // (measured equal at T = 1024 and 4-7 % faster than four 32 KB stages at T >= 2048).  The
-    // stages are separate arrays, not one indexed buffer: the compiler then sees that loads in
-    // flight target an array no ds_read of that moment touches, and inserts no wait of its own.
-#ifndef FLEXCO_NST_BIG
-#define FLEXCO_NST_BIG 2
-#endif
-    constexpr int NST = (BM + BN >= 512) ? FLEXCO_NST_BIG : 4;   // stages in the ring
-    constexpr int BKS = (NST == 2 ? 32768 : 16384) / (BM + BN);
-    constexpr int CPR = BKS / 8;                 // 16-byte chunks per row
-    constexpr int RPI = 64 / CPR;                // rows one wavefront load instruction fills (1 KB)
-    constexpr int SL = BKS / 16;                 // MFMA k-slices per stage
-    constexpr int PA = BM / (4 * RPI), PB = BN / (4 * RPI);   // load instructions per wavefront and stage
-    constexpr int ST_ELEMS = (BM + BN) * BKS;
-    static_assert(BKS == 32 || BKS == 64, "stage depth");
-    __shared__ __attribute__((aligned(1024))) bf16_t ring0[ST_ELEMS];
-    __shared__ __attribute__((aligned(1024))) bf16_t ring1[ST_ELEMS];
-    __shared__ __attribute__((aligned(1024))) bf16_t ring2[NST == 4 ? ST_ELEMS : 8];
-    __shared__ __attribute__((aligned(1024))) bf16_t ring3[NST == 4 ? ST_ELEMS : 8];
-    // Rows are BKS bf16 wide; chunk c of row r is stored at chunk c ^ key(r), key(r) = (r >> 1) & 7
-    // for 128-byte rows and (r >> 1) & 3 for 64-byte rows (the variants measured fastest for the
-    // ds_read_b128 operand fetches: 85 % and 88 % of the LDS peak).
-#define FLEXCO_KEY(r_) (CPR == 8 ? (((r_) >> 1) & 7) : (((r_) >> 1) & 3))
-    // Load instruction p of wavefront w fills rows RPI (4 p + w) .. + RPI of a tile; lane l lands
-    // at base + 16 l, i.e. physical chunk l % CPR of row l / CPR, so it fetches the logical chunk
-    // (l % CPR) ^ key(row) from global memory.  key(row) does not depend on p.
-    const int d_row = lane / CPR;
-    const int d_c = (lane % CPR) ^ FLEXCO_KEY(wave * RPI + d_row);
-    const bf16_t* ga[PA];
-    const bf16_t* gw[PB];
+  // ===================== operand tiles: global memory -> LDS directly ==========================
+  // A ring of stages of 64 k-columns; a stage holds the A tile [BM][64] and the W tile ([BN][64]
+  // in the forward form, [64][BN] in the input-gradient form), A first.  The 128 x 128 forward
+  // tile uses four stages of 32 KB: up to three in flight or waiting while one is multiplied.
+  // The 256 x 256 tile uses two stages of 64 KB: half as many barriers, and a stage's buffer is
+  // handed to the loads of the stage after next as soon as its last fragments are in registers
+  // (measured equal at T = 1024 and 4-7 % faster than four 32 KB stages at T >= 2048).  The
+  // input-gradient form uses two stages of 32 KB, so that two blocks share a CU (its grids are
+  // K-split into more blocks than CUs).  The stages are separate arrays, not one indexed
+  // buffer: the compiler then sees that loads in flight target an array no ds_read of that
+  // moment touches, and inserts no wait of its own.
+  constexpr int NST = TRANS ? 2 : ((BM + BN >= 512) ? 2 : 4);      // stages in the ring
+  constexpr int SL = BK / 16;                                       // MFMA k-slices per stage
+  constexpr int PA = BM / 32, PB = BN / 32;                         // 1 KB load instructions per wavefront and stage
+  constexpr int ST_ELEMS = (BM + BN) * BK;
+  static_assert(!TRANS || BN == 128, "the input-gradient form's W tile swizzle assumes 256-byte rows");
+  __shared__ __attribute__((aligned(1024))) bf16_t ring0[ST_ELEMS];
+  __shared__ __attribute__((aligned(1024))) bf16_t ring1[ST_ELEMS];
+  __shared__ __attribute__((aligned(1024))) bf16_t ring2[NST == 4 ? ST_ELEMS : 8];
+  __shared__ __attribute__((aligned(1024))) bf16_t ring3[NST == 4 ? ST_ELEMS : 8];
+  // [rows][64] tiles (128-byte rows): chunk c of row r is stored at chunk c ^ ((r >> 1) & 7) (the
+  // variant measured fastest for the ds_read_b128 operand fetches: 85 % of the LDS peak).
+  // [64][128] W tile of the input-gradient form (256-byte rows, read by transposing LDS reads of
+  // 4 consecutive rows x 64 bytes per pass): chunk c of row r is stored at chunk c ^ (4 (r & 3)),
+  // which puts the four rows of a pass on the four 64-byte quarters of the banks.
+#define FLEXCO_KEY(r_) (((r_) >> 1) & 7)
+  // Load instruction p of wavefront w fills 1 KB = rows 8 (4 p + w) .. + 8 of a [rows][64] tile (rows
+  // 4 (4 p + w) .. + 4 of the [64][128] tile); lane l lands at base + 16 l, so it fetches from global
+  // memory the logical chunk that belongs at its physical chunk.  The keys do not depend on p.
+  const int d_row = lane >> 3;
+  const int d_c = (lane & 7) ^ FLEXCO_KEY(wave * 8 + d_row);
+  const int t_row = lane >> 4;
+  const int t_c = (lane & 15) ^ (t_row << 2);
+  const bf16_t* ga[PA];
+  const bf16_t* gw[PB];
 #pragma unroll
-    for (int p = 0; p < PA; ++p)
-      ga[p] = A + (size_t)min(m0 + (p * 4 + wave) * RPI + d_row, M - 1) * lda + kbeg + d_c * 8;
+  for (int p = 0; p < PA; ++p)
+    ga[p] = A + (size_t)min(m0 + (p * 4 + wave) * 8 + d_row, M - 1) * lda + kbeg + d_c * 8;
 #pragma unroll
-    for (int p = 0; p < PB; ++p)
-      gw[p] = W + (size_t)min(n0 + (p * 4 + wave) * RPI + d_row, N - 1) * ldw + kbeg + d_c * 8;
-    const int ns = k_chunk / BKS;                // stages of this block
+  for (int p = 0; p < PB; ++p) {
+    if (!TRANS) {
+      gw[p] = W + (size_t)min(n0 + (p * 4 + wave) * 8 + d_row, N - 1) * ldw + kbeg + d_c * 8;
+    } else {
+      int col = n0 + t_c * 8;
+      if (col >= N) col = 0;   // masked at the store
+      gw[p] = W + (size_t)(kbeg + (p * 4 + wave) * 4 + t_row) * ldw + col;
+    }
+  }
+  const int ns = k_chunk / BK;                   // stages of this block
 
-    // stage index past the end: clamped, the loads repeat the last stage into a free buffer
+  // stage index past the end: clamped, the loads repeat the last stage into a free buffer
 #define FLEXCO_DMA(ring_, s_)                                                                         \
   {                                                                                                   \
-    const int koff_ = min((s_), ns - 1) * BKS;                                                        \
+    const int koff_ = min((s_), ns - 1) * BK;                                                         \
     _Pragma("unroll") for (int p = 0; p < PA; ++p)                                                    \
       __builtin_amdgcn_global_load_lds(FLEXCO_GP(ga[p] + koff_),                                      \
-                                       FLEXCO_LP(ring_ + (p * 4 + wave) * RPI * BKS), 16, 0, 0);      \
+                                       FLEXCO_LP(ring_ + (p * 4 + wave) * 512), 16, 0, 0);            \
     _Pragma("unroll") for (int p = 0; p < PB; ++p)                                                    \
-      __builtin_amdgcn_global_load_lds(FLEXCO_GP(gw[p] + koff_),                                      \
-                                       FLEXCO_LP(ring_ + (BM + (p * 4 + wave) * RPI) * BKS), 16, 0, 0); \
+      __builtin_amdgcn_global_load_lds(FLEXCO_GP(gw[p] + (TRANS ? (size_t)koff_ * ldw : (size_t)koff_)), \
+                                       FLEXCO_LP(ring_ + BM * BK + (p * 4 + wave) * 512), 16, 0, 0);  \
   }
+  // Operand fragments of W in the input-gradient form come from transposing LDS reads
+  // (ds_read_b64_tr_b16): within a group of 16 lanes, lane s hands in the address of 4 consecutive
+  // columns, 4 (s % 4) .., of row s / 4, and lane i receives column i of those 4 rows - i.e. 4
+  // consecutive k for one column, the MFMA operand order.  Group g of the wavefront covers columns
+  // 16 (g % 2) .. + 16 and the k-half g / 2; two reads (rows 0..3 and 4..7) make the 8 k of a fragment.
+  const int tr_k = 8 * (lane >> 5) + ((lane & 15) >> 2);
+  const int tr_n = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  const int tr_sw = ((lane & 15) >> 2) << 2;     // 4 (row & 3): the fragment's rows are tr_k + multiples of 4
 #define FLEXCO_FRAGS(ring_, kk_, af_, bf_)                                                            \
   {                                                                                                   \
     _Pragma("unroll") for (int i = 0; i < MT; ++i) {                                                  \
       const int r_ = wm0 + i * 32 + l32;                                                              \
-      af_[i] = *reinterpret_cast<const bf16x8*>(ring_ + r_ * BKS + (((kk_) * 2 + kg) ^ FLEXCO_KEY(r_)) * 8); \
+      af_[i] = *reinterpret_cast<const bf16x8*>(ring_ + r_ * BK + (((kk_) * 2 + kg) ^ FLEXCO_KEY(r_)) * 8); \
     }                                                                                                 \
     _Pragma("unroll") for (int j = 0; j < NT; ++j) {                                                  \
-      const int r_ = wn0 + j * 32 + l32;                                                              \
-      bf_[j] = *reinterpret_cast<const bf16x8*>(ring_ + (BM + r_) * BKS + (((kk_) * 2 + kg) ^ FLEXCO_KEY(r_)) * 8); \
+      if (!TRANS) {                                                                                   \
+        const int r_ = wn0 + j * 32 + l32;                                                            \
+        bf_[j] = *reinterpret_cast<const bf16x8*>(ring_ + (BM + r_) * BK + (((kk_) * 2 + kg) ^ FLEXCO_KEY(r_)) * 8); \
+      } else {                                                                                        \
+        const int col_ = wn0 + j * 32 + tr_n;                                                         \
+        const bf16_t* blk_ = ring_ + BM * BK + ((kk_) * 16 + tr_k) * BN + (((col_ >> 3) ^ tr_sw) * 8) + (col_ & 7); \
+        const s16x4 lo_ = __builtin_amdgcn_ds_read_tr16_b64_v4i16((FLEXCO_LDS s16x4*)blk_);           \
+        const s16x4 hi_ = __builtin_amdgcn_ds_read_tr16_b64_v4i16((FLEXCO_LDS s16x4*)(blk_ + 4 * BN)); \
+        bf_[j] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo_, hi_, 0, 1, 2, 3, 4, 5, 6, 7)); \
+      }                                                                                               \
     }                                                                                                 \
   }
-    // Barrier without the memory fences of __syncthreads (those would drain every load in
-    // flight): the wait before it covers exactly the stage that has to be complete, and the
-    // empty asm statements keep the compiler from moving LDS accesses across it.
+  // Barrier without the memory fences of __syncthreads (those would drain every load in
+  // flight): the wait before it covers exactly the stage that has to be complete, and the
+  // empty asm statements keep the compiler from moving LDS accesses across it.
 #define FLEXCO_WAIT_BARRIER(imm_)                                                                     \
   {                                                                                                   \
     __builtin_amdgcn_sched_barrier(0);                                                                \
@@ -169,13 +182,13 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
     asm volatile("" ::: "memory");                                                                    \
     __builtin_amdgcn_sched_barrier(0);                                                                \
   }
-    // Stage s (ring buffer cur_) enters with its slice-0 fragments in set 0.  Slices alternate
-    // between the two fragment sets, each fetched one slice ahead.  In the last slice:
-    //   wait until this wavefront's loads of stage s + 1 have landed (those of stage s + 2 may
-    //   stay in flight: vmcnt <= loads of one stage), barrier -> stage s + 1 is complete for
-    //   everyone, and everyone has finished reading stage s - 1 (its MFMAs were issued);
-    //   start the loads of stage s + 3 into the buffer stage s - 1 used; fetch slice 0 of stage
-    //   s + 1; then the last slice's MFMAs cover those latencies.
+  // Stage s (ring buffer cur_) enters with its slice-0 fragments in set 0.  Slices alternate
+  // between the two fragment sets, each fetched one slice ahead.  In the last slice:
+  //   wait until this wavefront's loads of stage s + 1 have landed (with four stages those of
+  //   stage s + 2 may stay in flight), barrier -> stage s + 1 is complete for everyone, and
+  //   everyone has the last fragments of stage s in registers; start the loads of the stage
+  //   that takes over the freed buffer; fetch slice 0 of stage s + 1; then the last slice's
+  //   MFMAs cover those latencies.
 #define FLEXCO_STAGE(cur_, nxt_, free_, s_)                                                           \
   {                                                                                                   \
     _Pragma("unroll") for (int kk = 0; kk < SL; kk += 2) {                                            \
@@ -197,195 +210,65 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
       __builtin_amdgcn_sched_barrier(0);                                                              \
     }                                                                                                 \
   }
-    // Instruction order inside a slice, imposed on the scheduler (it otherwise sinks the fragment
-    // reads behind the MFMAs, right in front of their first use): one LDS read - or one global
-    // load and one LDS read - ahead of each of the first MFMAs, the remaining MFMAs after.
-    // Masks: 0x008 MFMA, 0x020 VMEM read, 0x100 DS read.
+  // Instruction order inside a slice, imposed on the scheduler (it otherwise sinks the fragment
+  // reads behind the MFMAs, right in front of their first use): LDS reads - or global loads and
+  // LDS reads - ahead of each MFMA until they are used up, the remaining MFMAs after.
+  // Masks: 0x008 MFMA, 0x020 VMEM read, 0x100 DS read.
+  constexpr int NRD = MT + (TRANS ? 2 * NT : NT);                  // LDS reads of one slice
+  constexpr int NMF = MT * NT;                                     // its MFMAs
+  constexpr int NLD = PA + PB;                                     // loads of one stage
 #define FLEXCO_ORDER_READS_FIRST                                                                      \
   {                                                                                                   \
-    _Pragma("unroll") for (int q = 0; q < MT + NT; ++q) {                                             \
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                              \
+    _Pragma("unroll") for (int q = 0; q < NMF; ++q) {                                                 \
+      __builtin_amdgcn_sched_group_barrier(0x100, (NRD + NMF - 1) / NMF, 0);                          \
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                              \
     }                                                                                                 \
-    if (MT * NT > MT + NT) __builtin_amdgcn_sched_group_barrier(0x008, MT * NT - (MT + NT) > 0 ? MT * NT - (MT + NT) : 1, 0); \
   }
 #define FLEXCO_ORDER_LOADS_READS_FIRST                                                                \
   {                                                                                                   \
-    _Pragma("unroll") for (int q = 0; q < MT + NT; ++q) {                                             \
-      __builtin_amdgcn_sched_group_barrier(0x020, NLD / (MT + NT), 0);                                \
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                              \
+    _Pragma("unroll") for (int q = 0; q < NMF; ++q) {                                                 \
+      __builtin_amdgcn_sched_group_barrier(0x020, (NLD + NMF - 1) / NMF, 0);                          \
+      __builtin_amdgcn_sched_group_barrier(0x100, (NRD + NMF - 1) / NMF, 0);                          \
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                              \
     }                                                                                                 \
-    if (MT * NT > MT + NT) __builtin_amdgcn_sched_group_barrier(0x008, MT * NT - (MT + NT) > 0 ? MT * NT - (MT + NT) : 1, 0); \
   }
-    // s_waitcnt immediates: vmcnt in bits 3:0 and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at
-    // their maxima (no wait)
-    constexpr int NLD = PA + PB;
-    static_assert((NST == 2 || NLD <= 15) && NLD % (MT + NT) == 0, "loads per stage: vmcnt encoding, even spread over the slice");
-    // before a stage's barrier: the next stage has landed; with four stages one more may stay in flight
-    constexpr int WAIT_NEXT_STAGE = NST == 4 ? (0x0F70 | NLD) : 0x0F70;
-    // the buffer freed at stage s's barrier held stage s - 1 (four stages) or stage s itself (two)
-    constexpr int AHEAD = NST == 4 ? 3 : 2;
-    constexpr int WAIT_TWO_STAGES = 0x0F70 | ((2 * NLD) & 15) | (((2 * NLD) >> 4) << 14);
-    bf16x8 af0[MT], bf0[NT], af1[MT], bf1[NT];
-    if constexpr (NST == 4) {
-      FLEXCO_DMA(ring0, 0)
-      FLEXCO_DMA(ring1, 1)
-      FLEXCO_DMA(ring2, 2)
-      FLEXCO_WAIT_BARRIER(WAIT_TWO_STAGES)
-      FLEXCO_FRAGS(ring0, 0, af0, bf0)
-      int st = 0;
-      for (; st + 3 < ns; st += 4) {
-        FLEXCO_STAGE(ring0, ring1, ring3, st)
-        FLEXCO_STAGE(ring1, ring2, ring0, st + 1)
-        FLEXCO_STAGE(ring2, ring3, ring1, st + 2)
-        FLEXCO_STAGE(ring3, ring0, ring2, st + 3)
-      }
-      if (st < ns) FLEXCO_STAGE(ring0, ring1, ring3, st)
-      if (st + 1 < ns) FLEXCO_STAGE(ring1, ring2, ring0, st + 1)
-      if (st + 2 < ns) FLEXCO_STAGE(ring2, ring3, ring1, st + 2)
-    } else {
-      // two stages of twice the depth: a stage's buffer is free as soon as its last fragments are in
-      // registers, i.e. at its own barrier, and takes the loads of the stage after next
-      FLEXCO_DMA(ring0, 0)
-      FLEXCO_DMA(ring1, 1)
-      FLEXCO_WAIT_BARRIER(0x0F70 | (NLD & 15) | ((NLD >> 4) << 14))
-      FLEXCO_FRAGS(ring0, 0, af0, bf0)
-      int st = 0;
-      for (; st + 1 < ns; st += 2) {
-        FLEXCO_STAGE(ring0, ring1, ring0, st)
-        FLEXCO_STAGE(ring1, ring0, ring1, st + 1)
-      }
-      if (st < ns) FLEXCO_STAGE(ring0, ring1, ring0, st)
+  // s_waitcnt immediates: vmcnt in bits 3:0 and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at
+  // their maxima (no wait)
+#define FLEXCO_VMCNT(n_) (0x0F70 | ((n_) & 15) | (((n_) >> 4) << 14))
+  // before a stage's barrier: the next stage has landed; with four stages one more may stay in flight
+  constexpr int WAIT_NEXT_STAGE = NST == 4 ? FLEXCO_VMCNT(NLD) : FLEXCO_VMCNT(0);
+  // the buffer freed at stage s's barrier held stage s - 1 (four stages) or stage s itself (two)
+  constexpr int AHEAD = NST == 4 ? 3 : 2;
+  bf16x8 af0[MT], bf0[NT], af1[MT], bf1[NT];
+  if constexpr (NST == 4) {
+    FLEXCO_DMA(ring0, 0)
+    FLEXCO_DMA(ring1, 1)
+    FLEXCO_DMA(ring2, 2)
+    FLEXCO_WAIT_BARRIER(FLEXCO_VMCNT(2 * NLD))
+    FLEXCO_FRAGS(ring0, 0, af0, bf0)
+    int st = 0;
+    for (; st + 3 < ns; st += 4) {
+      FLEXCO_STAGE(ring0, ring1, ring3, st)
+      FLEXCO_STAGE(ring1, ring2, ring0, st + 1)
+      FLEXCO_STAGE(ring2, ring3, ring1, st + 2)
+      FLEXCO_STAGE(ring3, ring0, ring2, st + 3)
     }
-    __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0): nothing may land in LDS after the block ends
+    if (st < ns) FLEXCO_STAGE(ring0, ring1, ring3, st)
+    if (st + 1 < ns) FLEXCO_STAGE(ring1, ring2, ring0, st + 1)
+    if (st + 2 < ns) FLEXCO_STAGE(ring2, ring3, ring1, st + 2)
   } else {
-    // ================== input-gradient form: staged through registers ==========================
-    using S = SmemT<BM, BN>;
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    bf16_t* As = reinterpret_cast<bf16_t*>(smem_raw);                 // [2][BM][64] swizzled
-    bf16_t* Bs = As + 2 * S::A_ELEMS;                                 // [2][64][BN + 32]
-    constexpr int A_PASSES = BM / 32;                                  // 8 chunks per row, 32 rows per pass
-    constexpr int B_PASSES = (BK * (BN / 8)) / 256;
-    u32x4 sa0[A_PASSES], sb0[B_PASSES], sa1[A_PASSES], sb1[B_PASSES];   // two sets of staging registers
-    const int a_c = tid & 7, a_r = tid >> 3;
-    constexpr int BCH = BN / 8;                                        // chunks per row of the W tile
-    const int bt_c = tid % BCH, bt_r = tid / BCH;
-    // Operand fragments of W come from transposing LDS reads (ds_read_b64_tr_b16): within a group
-    // of 16 lanes, lane s hands in the address of 4 consecutive columns, 4 (s % 4), of row s / 4,
-    // and lane i receives column i of those 4 rows - i.e. 4 consecutive k for one column, the
-    // MFMA operand order.  Group g of the wavefront covers columns 16 (g % 2) .. + 16 and the
-    // k-half g / 2; two reads (rows 0..3 and 4..7) make the 8 k of a fragment.
-    const int tr_k = 8 * (lane >> 5) + ((lane & 15) >> 2);
-    const int tr_n = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-
-#define FLEXCO_LOAD_TILES(k0_, ra, rb)                                                                \
-  {                                                                                                   \
-    _Pragma("unroll") for (int p = 0; p < A_PASSES; ++p) {                                            \
-      const int r_ = min(m0 + a_r + 32 * p, M - 1);                                                   \
-      ra[p] = *reinterpret_cast<const u32x4*>(A + (size_t)r_ * lda + (k0_) + a_c * 8);                \
-    }                                                                                                 \
-    _Pragma("unroll") for (int p = 0; p < B_PASSES; ++p) {                                            \
-      const int kr_ = bt_r + (256 / BCH) * p;                                                         \
-      int col_ = n0 + bt_c * 8;                                                                       \
-      if (col_ >= N) col_ = 0; /* masked at the store */                                              \
-      rb[p] = *reinterpret_cast<const u32x4*>(W + (size_t)((k0_) + kr_) * ldw + col_);                \
-    }                                                                                                 \
-  }
-#define FLEXCO_STORE_TILES(buf_, ra, rb)                                                              \
-  {                                                                                                   \
-    bf16_t* as_ = As + (buf_) * S::A_ELEMS;                                                           \
-    bf16_t* bs_ = Bs + (buf_) * S::B_ELEMS;                                                           \
-    _Pragma("unroll") for (int p = 0; p < A_PASSES; ++p) {                                            \
-      const int r_ = a_r + 32 * p;                                                                    \
-      *reinterpret_cast<u32x4*>(as_ + r_ * BK + swz(r_, a_c) * 8) = ra[p];                            \
-    }                                                                                                 \
-    _Pragma("unroll") for (int p = 0; p < B_PASSES; ++p) {                                            \
-      const int kr_ = bt_r + (256 / BCH) * p;                                                         \
-      *reinterpret_cast<u32x4*>(bs_ + kr_ * S::B_LD + bt_c * 8) = rb[p];                              \
-    }                                                                                                 \
-  }
-#define FLEXCO_LOAD_FRAGS(kk_, af_, bf_)                                                              \
-  {                                                                                                   \
-    _Pragma("unroll") for (int i = 0; i < MT; ++i) {                                                  \
-      const int r_ = wm0 + i * 32 + l32;                                                              \
-      af_[i] = *reinterpret_cast<const bf16x8*>(as + r_ * BK + swz(r_, (kk_) * 2 + kg) * 8);          \
-    }                                                                                                 \
-    _Pragma("unroll") for (int j = 0; j < NT; ++j) {                                                  \
-      const bf16_t* blk_ = bs + ((kk_) * 16 + tr_k) * S::B_LD + wn0 + j * 32 + tr_n;                  \
-      const s16x4 lo_ = __builtin_amdgcn_ds_read_tr16_b64_v4i16((FLEXCO_LDS s16x4*)blk_);             \
-      const s16x4 hi_ = __builtin_amdgcn_ds_read_tr16_b64_v4i16((FLEXCO_LDS s16x4*)(blk_ + 4 * S::B_LD)); \
-      bf_[j] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo_, hi_, 0, 1, 2, 3, 4, 5, 6, 7)); \
-    }                                                                                                 \
-  }
-    // Software pipeline over k-steps of 64 with two LDS buffers and two sets of staging
-    // registers, so that a tile's global loads have two whole steps to arrive.  Fragments are
-    // fetched one k-slice ahead into two sets used in turn (a step enters with slice 0 in set 0):
-    //   slice 0: fetch slice 1, MFMAs of slice 0
-    //   slice 1: fetch slice 2, MFMAs of slice 1; the staging set that holds tile kt + 1 (loaded
-    //            in step kt - 2) is written to the other LDS buffer and reloaded with tile kt + 3
-    //   slice 2: fetch slice 3, MFMAs of slice 2
-    //   barrier: the other buffer is complete for everyone, this one is free
-    //   slice 3: fetch slice 0 of the next tile, MFMAs of slice 3
-    // Hazards: every read of tile kt - 1 (slices 1..3 in step kt - 1, slice 0 in step kt - 2) is
-    // issued, and waited for, before the barrier of step kt - 1, so the writes of tile kt + 1 into
-    // the same buffer in the middle of step kt race with nothing; those writes are complete for
-    // everyone at the barrier of step kt, after which slice 0 of tile kt + 1 is read.  Past the
-    // last tile the indices are clamped: the extra loads and writes repeat tile nk - 1, and the
-    // fragments fetched from them are never used.
-#define FLEXCO_ORDER_T                                                                                \
-  {                                                                                                   \
-    _Pragma("unroll") for (int q = 0; q < MT * NT; ++q) {                                             \
-      __builtin_amdgcn_sched_group_barrier(0x100, (MT + 2 * NT + MT * NT - 1) / (MT * NT), 0);        \
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                              \
-    }                                                                                                 \
-  }
-#define FLEXCO_STEP(kt_, ra_, rb_)                                                                    \
-  {                                                                                                   \
-    const int buf = (kt_) & 1;                                                                        \
-    const bf16_t* as = As + buf * S::A_ELEMS;                                                         \
-    const bf16_t* bs = Bs + buf * S::B_ELEMS;                                                         \
-    FLEXCO_LOAD_FRAGS(1, af1, bfr1)                                                                   \
-    FLEXCO_MFMAS(af0, bfr0)                                                                           \
-    FLEXCO_ORDER_T                                                                                    \
-    __builtin_amdgcn_sched_barrier(0);                                                                \
-    FLEXCO_LOAD_FRAGS(2, af0, bfr0)                                                                   \
-    FLEXCO_STORE_TILES(buf ^ 1, ra_, rb_)                                                             \
-    FLEXCO_LOAD_TILES(kbeg + min((kt_) + 3, nk - 1) * BK, ra_, rb_)                                   \
-    FLEXCO_MFMAS(af1, bfr1)                                                                           \
-    __builtin_amdgcn_sched_barrier(0);                                                                \
-    FLEXCO_LOAD_FRAGS(3, af1, bfr1)                                                                   \
-    FLEXCO_MFMAS(af0, bfr0)                                                                           \
-    FLEXCO_ORDER_T                                                                                    \
-    __builtin_amdgcn_sched_barrier(0);                                                                \
-    __syncthreads();                                                                                  \
-    {                                                                                                 \
-      const bf16_t* as = As + (buf ^ 1) * S::A_ELEMS;                                                 \
-      const bf16_t* bs = Bs + (buf ^ 1) * S::B_ELEMS;                                                 \
-      FLEXCO_LOAD_FRAGS(0, af0, bfr0)                                                                 \
-    }                                                                                                 \
-    FLEXCO_MFMAS(af1, bfr1)                                                                           \
-    FLEXCO_ORDER_T                                                                                    \
-    __builtin_amdgcn_sched_barrier(0);                                                                \
-  }
-    bf16x8 af0[MT], bfr0[NT], af1[MT], bfr1[NT];
-    FLEXCO_LOAD_TILES(kbeg, sa0, sb0)
-    FLEXCO_STORE_TILES(0, sa0, sb0)
-    __syncthreads();
-    FLEXCO_LOAD_TILES(kbeg + min(1, nk - 1) * BK, sa0, sb0)
-    FLEXCO_LOAD_TILES(kbeg + min(2, nk - 1) * BK, sa1, sb1)
-    {
-      const bf16_t* as = As;
-      const bf16_t* bs = Bs;
-      FLEXCO_LOAD_FRAGS(0, af0, bfr0)
+    FLEXCO_DMA(ring0, 0)
+    FLEXCO_DMA(ring1, 1)
+    FLEXCO_WAIT_BARRIER(FLEXCO_VMCNT(NLD))
+    FLEXCO_FRAGS(ring0, 0, af0, bf0)
+    int st = 0;
+    for (; st + 1 < ns; st += 2) {
+      FLEXCO_STAGE(ring0, ring1, ring0, st)
+      FLEXCO_STAGE(ring1, ring0, ring1, st + 1)
     }
-    int kt = 0;
-    for (; kt + 1 < nk; kt += 2) {
-      FLEXCO_STEP(kt, sa0, sb0)
-      FLEXCO_STEP(kt + 1, sa1, sb1)
-    }
-    if (kt < nk) FLEXCO_STEP(kt, sa0, sb0)
+    if (st < ns) FLEXCO_STAGE(ring0, ring1, ring0, st)
   }
+  __builtin_amdgcn_s_waitcnt(FLEXCO_VMCNT(0));   // nothing may land in LDS after the block ends
 
   // ---- rank-r extension: C += A2 W2^T (forward form; the entry whose column range holds this
   // block) or C += sum_e A2_e W2_e (input-gradient form; every entry).  This is the LoRA bypass
@@ -486,17 +369,9 @@ template <int BM, int BN, bool TRANS>
 int32_t launch_cfg(const void* A, const void* W, void* C, const void* bias, const void* res, int M, int N, int K,
                    size_t lda, size_t ldw, size_t ldc, size_t ldr, const GemmExt& ext, hipStream_t s,
                    float* part = nullptr, int splits = 1) {
-  constexpr size_t LDS_BYTES = TRANS ? SmemT<BM, BN>::BYTES : 0;   // the forward form's LDS is static
-  auto kern = gemm_bf16_kernel<BM, BN, TRANS>;
-  static bool attr_set = false;
-  if (!attr_set && LDS_BYTES > 0) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)LDS_BYTES);
-    if (e != hipSuccess) return fail(FLEXCO_EHIP, "hipFuncSetAttribute(gemm): %s", hipGetErrorString(e));
-    attr_set = true;
-  }
+  auto kern = gemm_bf16_kernel<BM, BN, TRANS>;   // all LDS is static
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n, splits), dim3(256), LDS_BYTES, s, (const bf16_t*)A, (const bf16_t*)W,
+  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n, splits), dim3(256), 0, s, (const bf16_t*)A, (const bf16_t*)W,
                      (bf16_t*)C, (const bf16_t*)bias, (const bf16_t*)res, M, N, K, lda, ldw, ldc, ldr, tiles_m, tiles_n,
                      ext, splits > 1 ? part : nullptr, K / splits);
   if (splits > 1) {
