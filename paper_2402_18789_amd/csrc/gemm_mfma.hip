@@ -396,14 +396,20 @@ static bool ext_fits(const GemmExt& ext, bool trans_w, int BN) {
 }
 
 // Largest split count <= want that cuts K into whole 64-wide steps and fits the partial buffer.
-static int pick_splits(int M, int N, int K, int tiles, size_t part_elems) {
-  if (part_elems == 0 || tiles >= 384) return 1;
+// Split count for a grid of `tiles` output tiles: the one with the least estimated time,
+// rounds of `want` resident blocks (resident blocks per CU x 256) times the k-range of a block, plus a
+// small charge per split for the partial sums it writes and the reduction reads back.  Splits cut K
+// into whole 64-wide stages, at least four per block, and must fit the partial buffer.
+static int pick_splits(int M, int N, int K, int tiles, size_t part_elems, int want) {
+  if (part_elems == 0) return 1;
   int best = 1;
-  for (int sp = 2; sp <= 16; ++sp) {
-    if (K % (sp * BK) != 0 || K / sp < 4 * BK) continue;
-    if ((size_t)sp * M * N > part_elems) break;
-    best = sp;
-    if (tiles * sp >= 512) break;
+  double best_cost = 1e30;
+  for (int sp = 1; sp <= 16; ++sp) {
+    if (K % (sp * BK) != 0 || (sp > 1 && K / sp < 4 * BK)) continue;
+    if (sp > 1 && (size_t)sp * M * N > part_elems) break;
+    const int rounds = (tiles * sp + want - 1) / want;
+    const double cost = (double)rounds / sp + 0.02 * (sp - 1);
+    if (cost < best_cost - 1e-12) { best_cost = cost; best = sp; }
   }
   return best;
 }
@@ -419,8 +425,9 @@ int32_t launch_gemm_mfma(const void* A, const void* W, void* C, const void* bias
     if (!ext_fits(ext, true, 128)) return FLEXCO_EUNSUPPORTED;
     // few row tiles (a finetune window) and a long contraction: cut K across blocks so that the
     // weight stream is spread over the whole chip; partial sums are reduced in split order
+    // (256 x 128 tiles, one block per CU, were measured slower than two co-resident 128 x 128 blocks)
     const int tiles = ((M + 127) / 128) * ((N + 127) / 128);
-    const int sp = part ? pick_splits(M, N, K, tiles, part_elems) : 1;
+    const int sp = part ? pick_splits(M, N, K, tiles, part_elems, 512) : 1;
     return launch_cfg<128, 128, true>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, ext, s, part, sp);
   }
   const long big_tiles = (long)((M + 255) / 256) * ((N + 255) / 256);
