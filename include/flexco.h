@@ -358,6 +358,40 @@ int32_t flexco_sched_advance(int32_t n_entries, const int32_t* req, const int32_
                              int32_t n_req, const int32_t* prompt_len, int32_t* prefilled,
                              const int32_t* gen_len, int32_t* generated, int32_t* state);
 
+/* ---- The two ends of a finetuning step around the decoder layers ----------------------------
+ * Generative loss of a forward window (Alg. 2, forward loop) and the gradient its backward pass
+ * starts from.  Reading (the paper names neither head nor normalisation): next-token cross-entropy
+ * through a final RMSNorm and an LM head,
+ *     h = rmsnorm(x; g_final),  z = h w_lm^T,  loss_i = logsumexp(z_i) - z_i[targets_i],
+ * over the rows with targets_i >= 0 (negative: the row has no next token and contributes neither
+ * loss nor gradient), times `scale` (1 / tokens of the whole sequence makes the windows of a
+ * sequence add up to its mean loss). */
+typedef struct flexco_lm_head {
+  int32_t hidden, vocab, dtype;   /* dtype: FLEXCO_F32 | FLEXCO_BF16 (storage of g_final, w_lm, x, dX) */
+  float   rms_eps;
+  const void* g_final;            /* [hidden]         device */
+  const void* w_lm;               /* [vocab, hidden]  device, frozen */
+} flexco_lm_head;
+
+int32_t flexco_lm_loss_workspace_bytes(const flexco_lm_head* head, int32_t n_max, size_t* out_bytes);
+
+/* x: device [n, hidden], the window's rows of the last layer's output; targets: device int32 [n];
+ * loss_accum: device float[1], scale * sum_i loss_i is ADDED to it (rows summed in a fixed order);
+ * dX: device [n, hidden], written = d(scale * sum loss_i) / dx, what flexco_lora_bwd of the last
+ * layer takes as dY.  ws: device workspace of flexco_lm_loss_workspace_bytes(head, >= n) bytes.
+ * Errors: EINVAL, EWORKSPACE, EHIP. */
+int32_t flexco_lm_loss(const flexco_lm_head* head, const void* x, const int32_t* targets, int32_t n,
+                       float scale, float* loss_accum, void* dX, void* ws, size_t ws_bytes, void* stream);
+
+/* One Adam update (Kingma & Ba, with bias correction, no weight decay; the optimizer named in the
+ * paper's setup) of n parameters:  m <- b1 m + (1 - b1) g,  v <- b2 v + (1 - b2) g^2,
+ * p <- p - lr (m / (1 - b1^step)) / (sqrt(v / (1 - b2^step)) + eps).  param: device, dtype (bf16
+ * or f32); master: device float[n] or NULL - with a master copy the update is applied to it in
+ * fp32 and param receives its rounded value; grad, m, v: device float[n].  step counts from 1. */
+int32_t flexco_adam_step(void* param, float* master, const float* grad, float* m, float* v, size_t n,
+                         int32_t dtype, float lr, float beta1, float beta2, float eps, int32_t step,
+                         void* stream);
+
 /* Machine-ceiling probes for the benchmark (they compute nothing of the method): what this GPU
  * sustains for the two resources the rooflines are quoted against.  Both only enqueue one kernel
  * on `stream`; the caller times it with events.  sink: device, >= 4 bytes, never written in

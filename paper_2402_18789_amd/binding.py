@@ -70,6 +70,11 @@ class FtState(C.Structure):
                                             "lse", "dk_accum", "dv_accum")]
 
 
+class LmHead(C.Structure):
+    _fields_ = [("hidden", C.c_int32), ("vocab", C.c_int32), ("dtype", C.c_int32), ("rms_eps", C.c_float),
+                ("g_final", C.c_void_p), ("w_lm", C.c_void_p)]
+
+
 class LatencyModel(C.Structure):
     _fields_ = [("n_c", C.c_int32), ("n_s", C.c_int32), ("c_grid", C.c_void_p), ("s_grid", C.c_void_p),
                 ("ms", C.c_void_p)]
@@ -105,6 +110,9 @@ def _load():
         "flexco_sched_window": [P(LatencyModel), i32, C.c_double, i32, i32, P(i32)],
         "flexco_sched_inference": [i32, vp, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, i32, P(i32), P(i32)],
         "flexco_sched_advance": [i32, vp, vp, vp, i32, vp, vp, vp, vp, vp],
+        "flexco_lm_loss_workspace_bytes": [P(LmHead), i32, P(sz)],
+        "flexco_lm_loss": [P(LmHead), vp, vp, i32, f32, vp, vp, vp, sz, vp],
+        "flexco_adam_step": [vp, vp, vp, vp, vp, sz, i32, f32, f32, f32, f32, i32, vp],
     }
     for name, args in sigs.items():
         fn = getattr(lib, name)
@@ -118,7 +126,8 @@ EXPORTS = ("flexco_last_error", "flexco_abi_version", "flexco_maps_blob_ints", "
            "flexco_maps_rebase", "flexco_workspace_bytes", "flexco_layer_forward", "flexco_attention_mixed",
            "flexco_lora_fwd", "flexco_lora_bwd", "flexco_attention_window_bwd", "flexco_gemm",
            "flexco_kernel_timer_start", "flexco_kernel_timer_stop", "flexco_probe_mfma", "flexco_probe_read",
-           "flexco_latency_estimate", "flexco_sched_window", "flexco_sched_inference", "flexco_sched_advance")
+           "flexco_latency_estimate", "flexco_sched_window", "flexco_sched_inference", "flexco_sched_advance",
+           "flexco_lm_loss_workspace_bytes", "flexco_lm_loss", "flexco_adam_step")
 KERNEL_IDS = {"gemm_fwd": 0, "gemm_bwd": 1, "attn_fwd": 2, "attn_merge": 3, "attn_bwd": 4, "elemwise": 5, "lora": 6,
               "generic": 7}
 
@@ -272,6 +281,22 @@ def flexco_probe_read(src, nbytes, blocks, sink, stream=None):
     nb = C.c_double(0.0)
     _check(_lib.flexco_probe_read(_ptr(src), nbytes, blocks, _ptr(sink), C.byref(nb), _stream(stream)))
     return nb.value
+
+
+def flexco_lm_loss_workspace_bytes(head, n_max):
+    out = C.c_size_t(0)
+    _check(_lib.flexco_lm_loss_workspace_bytes(C.byref(head), n_max, C.byref(out)))
+    return out.value
+
+
+def flexco_lm_loss(head, x, targets, n, scale, loss_accum, dX, ws, ws_bytes, stream=None):
+    _check(_lib.flexco_lm_loss(C.byref(head), _ptr(x), _ptr(targets), n, scale, _ptr(loss_accum), _ptr(dX), _ptr(ws),
+                               ws_bytes, _stream(stream)))
+
+
+def flexco_adam_step(param, master, grad, m, v, n, dtype, lr, beta1, beta2, eps, step, stream=None):
+    _check(_lib.flexco_adam_step(_ptr(param), _ptr(master), _ptr(grad), _ptr(m), _ptr(v), n, dtype, lr, beta1, beta2, eps,
+                                 step, _stream(stream)))
 
 
 class HostLatencyModel:
