@@ -52,3 +52,39 @@ def adam_step(p, grad, m, v, step, lr, beta1=0.9, beta2=0.999, eps=1e-8):
     mhat = m / (1.0 - beta1 ** step)
     vhat = v / (1.0 - beta2 ** step)
     return p - lr * mhat / (np.sqrt(vhat) + eps), m, v
+
+
+def training_step_whole_seq(cfg, layers, loras, g_final, w_lm, x, targets, scale, opt, step, lr,
+                            beta1=0.9, beta2=0.999, eps=1e-8, dtype=np.float64):
+    """One sequence-level finetuning step of a stack of decoder layers, written out as its definition:
+    forward of the whole sequence through every layer, the generative loss on the top output, backward
+    through the layers from the top, then Adam on every bypass matrix.  This is what the token-level
+    schedule of Alg. 2 must reproduce whatever its windows (Sec. 6.1).
+
+      layers, loras : per layer the frozen weights and {target: (A, B)}
+      x             : [L, H] input rows of the first layer (the frozen embedding's output)
+      targets       : [L] next-token ids, negative where a row has none
+      opt           : per layer {target: (mA, vA, mB, vB)}; None starts from zeros
+    Returns (loss, grads per layer {target: (dA, dB)}, new loras, new opt)."""
+    from . import layer as OL
+    h = np.asarray(x, dtype=dtype)
+    inputs = []
+    for W, lo in zip(layers, loras):
+        inputs.append(h)
+        h = OL.layer_forward_seq(cfg, W, lo, h, dtype)["y"]
+    loss, dY = generative_loss(h, np.asarray(g_final, dtype=dtype), np.asarray(w_lm, dtype=dtype), targets, scale, cfg.rms_eps)
+    grads = [None] * len(layers)
+    for n in range(len(layers) - 1, -1, -1):
+        dY, grads[n], _, _ = OL.layer_backward_seq(cfg, layers[n], loras[n], inputs[n], dY, dtype)
+    new_loras, new_opt = [], []
+    for n, lo in enumerate(loras):
+        nl, no = {}, {}
+        for t, (A, B) in lo.items():
+            A, B = np.asarray(A, dtype=dtype), np.asarray(B, dtype=dtype)
+            mA, vA, mB, vB = opt[n][t] if opt is not None else (np.zeros_like(A), np.zeros_like(A), np.zeros_like(B), np.zeros_like(B))
+            A1, mA, vA = adam_step(A, grads[n][t][0], mA, vA, step, lr, beta1, beta2, eps)
+            B1, mB, vB = adam_step(B, grads[n][t][1], mB, vB, step, lr, beta1, beta2, eps)
+            nl[t], no[t] = (A1, B1), (mA, vA, mB, vB)
+        new_loras.append(nl)
+        new_opt.append(no)
+    return loss, grads, new_loras, new_opt

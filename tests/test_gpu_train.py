@@ -108,3 +108,122 @@ def test_adam_steps(dtype):
     assert_close("param", to_np(p_d), p_o, TOL[dtype])
     with pytest.raises(B.FlexcoError):
         B.flexco_adam_step(p_d, master, m_d, m_d, v_d, n, HH.DTYPE_CODE[dtype], 1e-3, 0.9, 0.999, 1e-8, 0)
+
+
+# ------------------------------------------------------------------------------------------
+# Alg. 2 end to end: co-served forward windows through a stack of layers, the generative loss per
+# window, token-level backward through the stack from the top, Adam -- against the sequence-level
+# step written out as its definition (Sec. 6.1: the two are the same computation)
+# ------------------------------------------------------------------------------------------
+def run_training_step(cfg, n_layers, batch0, ft_window, prefill_chunk, bwd_windows, V, seed, lr, adam):
+    from gpu_common import Case
+    from workload.configs import KIND_FINETUNE
+    tol = TOL[cfg.dtype]
+    dt = HH.TORCH_DTYPE[cfg.dtype]
+    ft_seq = [r.seq_id for r in batch0.requests if r.kind == KIND_FINETUNE][0]
+    L, H = batch0.seq_capacity[ft_seq], cfg.hidden
+    assert sum(bwd_windows) == L
+    g = gen.rng(seed, "gputrain", "e2e", cfg.name, n_layers)
+    x_seq = gen.storage_round(cfg, g.standard_normal((L, H), dtype=np.float32))
+    gain = gen.storage_round(cfg, (1.0 + 0.05 * g.standard_normal(H)).astype(np.float32))
+    w_lm = gen.storage_round(cfg, (0.05 * g.standard_normal((V, H))).astype(np.float32))
+    targets = g.integers(0, V, L).astype(np.int32)
+    targets[-1] = -1                                           # the last position has no next token
+    layers = [gen.layer_weights(cfg, seed, n) for n in range(n_layers)]
+    loras = [gen.lora_weights(cfg, seed, n, b_std=0.02) for n in range(n_layers)]
+    cases = [Case(cfg, batch0, seed=seed, layer=n, weights=layers[n], lora=loras[n]) for n in range(n_layers)]
+
+    g_d = torch.from_numpy(gain).to("cuda", dt)
+    w_d = torch.from_numpy(w_lm).to("cuda", dt)
+    head = B.LmHead(H, V, HH.DTYPE_CODE[cfg.dtype], cfg.rms_eps, g_d.data_ptr(), w_d.data_ptr())
+    hb = B.flexco_lm_loss_workspace_bytes(head, L)
+    hws = torch.empty(hb, dtype=torch.uint8, device="cuda")
+    loss_d = torch.zeros(1, dtype=torch.float32, device="cuda")
+    dtop = torch.zeros((L, H), dtype=dt, device="cuda")
+    tgt_d = torch.from_numpy(targets).to("cuda")
+
+    # ---- forward: iterations of the mixed batch until the finetune sequence is through ----------------
+    batch, it = batch0, 0
+    while any(r.kind == KIND_FINETUNE for r in batch.requests):
+        x = gen.layer_input(cfg, seed, batch.n_tokens, tag=f"e2e{it}")
+        offs = np.cumsum([0] + [r.n_new for r in batch.requests])
+        ft = [(r, int(o)) for r, o in zip(batch.requests, offs) if r.kind == KIND_FINETUNE][0]
+        r, off = ft
+        print(f"  forward iteration {it}: T={batch.n_tokens}, finetune rows [{r.start_pos}, {r.start_pos + r.n_new})", flush=True)
+        x[off:off + r.n_new] = x_seq[r.start_pos:r.start_pos + r.n_new]
+        for n in range(n_layers):
+            x = cases[n].forward(batch, x, oracle=False)[0]
+        top = torch.from_numpy(np.ascontiguousarray(x[off:off + r.n_new], dtype=np.float32)).to("cuda", dt)
+        dwin = torch.empty_like(top)
+        B.flexco_lm_loss(head, top, tgt_d[r.start_pos:r.start_pos + r.n_new], r.n_new, 1.0 / L, loss_d, dwin, hws, hb)
+        dtop[r.start_pos:r.start_pos + r.n_new] = dwin
+        batch = gen.advance(batch, prefill_chunk=prefill_chunk, ft_window=ft_window)
+        it += 1
+    assert it >= 2
+
+    # ---- backward: layers from the top, each over the windows from the sequence's end -----------------
+    pages = batch0.seq_pages[ft_seq]
+    pages_d = torch.from_numpy(np.asarray(pages, dtype=np.int32)).to("cuda")
+    dcur = dtop
+    for n in range(n_layers - 1, -1, -1):
+        case = cases[n]
+        case.dev.zero_grads()
+        case.d_ft[ft_seq].zero_accum()
+        dnext = torch.zeros_like(dcur) if n > 0 else None          # nothing trainable below the first layer
+        l = L
+        for s in bwd_windows:
+            print(f"  backward layer {n} window [{l - s}, {l})", flush=True)
+            ws = HH.Workspace(case.dev.c, 0, 0, s, l)
+            B.flexco_lora_bwd(case.dev.c, case.dev.w, case.dev.lora, case.d_pool.c, pages_d, len(pages), case.d_ft[ft_seq].c,
+                              l - s, s, dcur[l - s:l], dnext[l - s:l] if dnext is not None else None, ws.ptr, ws.bytes)
+            l -= s
+        torch.cuda.synchronize()
+        dcur = dnext
+
+    # ---- the definition -------------------------------------------------------------------------------
+    loss_o, grads_o, new_loras, new_opt = OT.training_step_whole_seq(cfg, layers, loras, gain, w_lm, x_seq, targets, 1.0 / L,
+                                                                     None, 1, lr)
+    got_loss = float(loss_d.item())
+    print(f"  loss {got_loss:.6f} vs {loss_o:.6f}", flush=True)
+    assert abs(got_loss - loss_o) <= tol * abs(loss_o)
+    worst = 0.0
+    for n in range(n_layers):
+        gg = cases[n].dev.grads_numpy()
+        assert set(gg) == set(cfg.lora_targets)
+        for t in cfg.lora_targets:
+            worst = max(worst, assert_close(f"layer {n} dA[{t}]", gg[t][0], grads_o[n][t][0], tol))
+            worst = max(worst, assert_close(f"layer {n} dB[{t}]", gg[t][1], grads_o[n][t][1], tol))
+    print(f"  worst gradient error {worst:.2e}", flush=True)
+    if not adam:
+        return
+    # ---- Adam on every bypass matrix (fp32 parameters: no master copy) --------------------------------
+    for n in range(n_layers):
+        dev = cases[n].dev
+        for t in cfg.lora_targets:
+            for P, G, k in ((dev.A[t], dev.dA[t], 0), (dev.Bm[t], dev.dB[t], 1)):
+                m_d, v_d = torch.zeros_like(G), torch.zeros_like(G)
+                B.flexco_adam_step(P, None, G, m_d, v_d, P.numel(), HH.DTYPE_CODE[cfg.dtype], lr, 0.9, 0.999, 1e-8, 1)
+                torch.cuda.synchronize()
+                # a gradient entry within rounding of zero may take its step in either direction: compare
+                # where the oracle's gradient is well away from zero, and bound the move everywhere
+                go = grads_o[n][t][k]
+                new_o, old_o = new_loras[n][t][k], np.asarray(loras[n][t][k], dtype=np.float64)
+                got = to_np(P).T
+                sure = np.abs(go) > 1e-3 * np.abs(go).max()
+                assert sure.mean() > 0.5
+                assert np.abs(got - new_o)[sure].max() <= 1e-4 * np.abs(new_o).max(), (n, t, k)
+                assert np.abs(got - old_o).max() <= lr * (1 + 1e-5)
+                assert_close(f"layer {n} m[{t}]", to_np(m_d).T, new_opt[n][t][2 * k], tol)
+
+
+def test_training_step_end_to_end_three_layers_f32():
+    print("training step, 3 layers, fp32", flush=True)
+    b = gen.mixed_batch(16, 11, decode_ctx=(1, 17, 40), prefill=[(0, 5, 40)], finetune=[(0, 24, 64)], extra_capacity=3)
+    run_training_step(C1, 3, b, ft_window=24, prefill_chunk=20, bwd_windows=[40, 24], V=203, seed=11, lr=1e-3, adam=True)
+
+
+def test_training_step_end_to_end_two_layers_bf16():
+    print("training step, 2 layers, bf16", flush=True)
+    cfg = CONFIGS["c2_llama8b_layer"].with_(name="small_bf16", hidden=512, n_q_heads=8, n_kv_heads=2, head_dim=128, ffn=1408)
+    b = gen.batch_scaled(12, 6, 30, 300, [(0, 50, 50)], [(0, 100, 230)])
+    run_training_step(cfg, 2, b, ft_window=100, prefill_chunk=32, bwd_windows=[30, 200], V=1000, seed=12, lr=1e-3, adam=False)

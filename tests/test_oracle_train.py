@@ -85,3 +85,49 @@ def test_adam_minimises_a_quadratic_and_rejects_step_zero():
     assert np.abs(p - target).max() < 1e-3
     with pytest.raises(ValueError):
         T.adam_step(p, p, m, v, 0, lr=0.1)
+
+
+def test_whole_sequence_step_gradients_match_central_differences_through_two_layers():
+    """Pins the composition (layer order, the loss head on top, gradients routed to the right layer and
+    matrix): d loss / d(entry of A or B) by central differences of the loss alone."""
+    from workload import CONFIGS
+    cfg = CONFIGS["c1_tiny_f32"].with_(hidden=32, n_q_heads=2, n_kv_heads=1, head_dim=16, ffn=40, lora_rank=2,
+                                       lora_targets=("q", "v", "o", "down"))
+    L, V = 9, 31
+    layers = [gen.layer_weights(cfg, 5, n) for n in range(2)]
+    loras = [gen.lora_weights(cfg, 5, n, b_std=0.05) for n in range(2)]
+    layers = [{k: v.astype(np.float64) for k, v in W.items()} for W in layers]
+    loras = [{t: (A.astype(np.float64), B.astype(np.float64)) for t, (A, B) in lo.items()} for lo in loras]
+    g = gen.rng(5, "train", "step")
+    x = g.standard_normal((L, cfg.hidden))
+    gain = 1.0 + 0.1 * g.standard_normal(cfg.hidden)
+    w = 0.3 * g.standard_normal((V, cfg.hidden))
+    y = g.integers(0, V, L)
+    y[-1] = -1
+    loss, grads, new_loras, new_opt = T.training_step_whole_seq(cfg, layers, loras, gain, w, x, y, 1.0 / L, None, 1, 1e-2)
+
+    def loss_with(n, t, which, idx, delta):
+        lo2 = [{k: (A.copy(), B.copy()) for k, (A, B) in lo.items()} for lo in loras]
+        lo2[n][t][which][idx] += delta
+        return T.training_step_whole_seq(cfg, layers, lo2, gain, w, x, y, 1.0 / L, None, 1, 1e-2)[0]
+
+    h = 1e-5
+    checked = 0
+    for n in range(2):
+        for t in cfg.lora_targets:
+            for which in (0, 1):
+                shape = loras[n][t][which].shape
+                for _ in range(2):
+                    idx = (int(g.integers(0, shape[0])), int(g.integers(0, shape[1])))
+                    num = (loss_with(n, t, which, idx, h) - loss_with(n, t, which, idx, -h)) / (2 * h)
+                    got = grads[n][t][which][idx]
+                    assert abs(got - num) <= 1e-6 * max(1e-3, abs(num)) + 1e-10, (n, t, which, idx, got, num)
+                    checked += 1
+    assert checked == 32
+    # first Adam step from zero state: m_hat = g, v_hat = g^2, so every entry moves by lr g / (|g| + eps)
+    for n in range(2):
+        for t in cfg.lora_targets:
+            for which in (0, 1):
+                gr = grads[n][t][which]
+                moved = new_loras[n][t][which] - loras[n][t][which]
+                assert np.allclose(moved, -1e-2 * gr / (np.abs(gr) + 1e-8), rtol=1e-9, atol=1e-15)
