@@ -294,8 +294,8 @@ int32_t flexco_gemm(const void* A, const void* W, void* C, const void* bias, con
 
 /* Per-kernel timing with HIP events, for roofline measurement.  While a timer is running the
  * library records one event before and one after every launch of the kernel class
- * `kernel_id` on that launch's stream (at most max_launches launches; later ones are not
- * timed).  flexco_kernel_timer_stop waits for the recorded events, returns the summed
+ * `kernel_id` on that launch's stream (the bf16 GEMM kernels carry the two events in their own
+ * dispatch; at most max_launches launches, later ones are not timed).  flexco_kernel_timer_stop waits for the recorded events, returns the summed
  * duration in milliseconds and the number of timed launches, and releases the events.
  * Events are host-side runtime objects; no device memory is allocated.  Not thread-safe:
  * start / stop from the thread that issues the work. */
@@ -310,6 +310,11 @@ int32_t flexco_gemm(const void* A, const void* W, void* C, const void* bias, con
 #define FLEXCO_N_KERNEL_IDS 8
 int32_t flexco_kernel_timer_start(int32_t kernel_id, int32_t max_launches);
 int32_t flexco_kernel_timer_stop(int32_t kernel_id, double* total_ms, int64_t* launches);
+/* From the next start on, only every stride-th launch of the class is timed (1, the initial
+ * setting: all of them); stop then returns the sum and the count of the timed launches.  A timed
+ * launch holds its neighbours on the stream apart by a few microseconds, which a caller that also
+ * measures end-to-end time may not want on every launch. */
+int32_t flexco_kernel_timer_sample(int32_t kernel_id, int32_t stride);
 
 /* ---- Hybrid token scheduler (Sec. 6.2), host only ------------------------------------------
  * Stage 1 chooses the inference work of an iteration (iteration-level scheduling with chunked

@@ -104,6 +104,7 @@ def _load():
         "flexco_gemm": [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp],
         "flexco_kernel_timer_start": [i32, i32],
         "flexco_kernel_timer_stop": [i32, P(C.c_double), P(C.c_int64)],
+        "flexco_kernel_timer_sample": [i32, i32],
         "flexco_probe_mfma": [i32, i32, vp, P(C.c_double), vp],
         "flexco_probe_read": [vp, sz, i32, vp, P(C.c_double), vp],
         "flexco_latency_estimate": [P(LatencyModel), i32, i32, P(C.c_double)],
@@ -125,7 +126,7 @@ _lib = _load()
 EXPORTS = ("flexco_last_error", "flexco_abi_version", "flexco_maps_blob_ints", "flexco_build_maps",
            "flexco_maps_rebase", "flexco_workspace_bytes", "flexco_layer_forward", "flexco_attention_mixed",
            "flexco_lora_fwd", "flexco_lora_bwd", "flexco_attention_window_bwd", "flexco_gemm",
-           "flexco_kernel_timer_start", "flexco_kernel_timer_stop", "flexco_probe_mfma", "flexco_probe_read",
+           "flexco_kernel_timer_start", "flexco_kernel_timer_stop", "flexco_kernel_timer_sample", "flexco_probe_mfma", "flexco_probe_read",
            "flexco_latency_estimate", "flexco_sched_window", "flexco_sched_inference", "flexco_sched_advance",
            "flexco_lm_loss_workspace_bytes", "flexco_lm_loss", "flexco_adam_step")
 KERNEL_IDS = {"gemm_fwd": 0, "gemm_bwd": 1, "attn_fwd": 2, "attn_merge": 3, "attn_bwd": 4, "elemwise": 5, "lora": 6,
@@ -345,6 +346,10 @@ def flexco_sched_advance(entries, prompt_len, prefilled, gen_len, generated, sta
 
 def flexco_kernel_timer_start(kernel_id, max_launches):
     _check(_lib.flexco_kernel_timer_start(kernel_id, max_launches))
+
+
+def flexco_kernel_timer_sample(kernel_id, stride):
+    _check(_lib.flexco_kernel_timer_sample(kernel_id, stride))
 
 
 def flexco_kernel_timer_stop(kernel_id):

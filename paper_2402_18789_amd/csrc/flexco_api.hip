@@ -13,17 +13,35 @@ using namespace flexco;
 namespace flexco {
 struct KTimer {
   std::vector<hipEvent_t> ev;   // 2 per launch
-  int used = 0;
+  int used = 0;       // event pairs taken
+  int launches = 0;   // timed launches of the class they belong to
+  int seen = 0;       // launches of the class since the timer started
+  int stride = 1;     // every stride-th launch is timed
+  bool take = false;  // the current launch is a timed one
   bool on = false;
+  bool begin_launch() {             // a new launch of the class: is it a timed one?
+    take = on && (seen++ % stride == 0) && 2 * (used + 1) <= (int)ev.size();
+    if (take) ++launches;
+    return take;
+  }
 };
 static KTimer g_timers[FLEXCO_N_KERNEL_IDS];
 
 KernelTimerScope::KernelTimerScope(int id_, hipStream_t s_) : id(id_), s(s_), slot(-1) {
   KTimer& t = g_timers[id];
-  if (t.on && 2 * (t.used + 1) <= (int)t.ev.size()) {
+  if (t.begin_launch()) {
     slot = t.used++;
     (void)hipEventRecord(t.ev[2 * slot], s);
   }
+}
+bool kernel_timer_pair(int id, hipEvent_t* start, hipEvent_t* stop, bool first_of_call) {
+  KTimer& t = g_timers[id];
+  if (first_of_call) (void)t.begin_launch();
+  if (!t.on || !t.take || 2 * (t.used + 1) > (int)t.ev.size()) return false;
+  const int slot = t.used++;
+  *start = t.ev[2 * slot];
+  *stop = t.ev[2 * slot + 1];
+  return true;
 }
 KernelTimerScope::~KernelTimerScope() {
   if (slot >= 0) (void)hipEventRecord(g_timers[id].ev[2 * slot + 1], s);
@@ -42,7 +60,19 @@ extern "C" int32_t flexco_kernel_timer_start(int32_t kernel_id, int32_t max_laun
     if (rc != hipSuccess) return fail(FLEXCO_EHIP, "hipEventCreate: %s", hipGetErrorString(rc));
   }
   t.used = 0;
+  t.launches = 0;
+  t.seen = 0;
+  t.take = false;
   t.on = true;
+  return FLEXCO_OK;
+}
+
+extern "C" int32_t flexco_kernel_timer_sample(int32_t kernel_id, int32_t stride) {
+  clear_error();
+  FLEXCO_CHECK(kernel_id >= 0 && kernel_id < FLEXCO_N_KERNEL_IDS, FLEXCO_EINVAL, "unknown kernel id %d", kernel_id);
+  FLEXCO_CHECK(stride >= 1, FLEXCO_EINVAL, "stride must be at least 1");
+  FLEXCO_CHECK(!g_timers[kernel_id].on, FLEXCO_EINVAL, "timer %d is running", kernel_id);
+  g_timers[kernel_id].stride = stride;
   return FLEXCO_OK;
 }
 
@@ -62,7 +92,7 @@ extern "C" int32_t flexco_kernel_timer_stop(int32_t kernel_id, double* total_ms,
     sum += ms;
   }
   *total_ms = sum;
-  *launches = t.used;
+  *launches = t.launches;
   for (auto& e : t.ev) (void)hipEventDestroy(e);
   t.ev.clear();
   t.used = 0;
@@ -448,11 +478,8 @@ int32_t launch_gemm(const void* A, const void* W, void* C, const void* bias, con
                     const GemmExt* ext, float* part, size_t part_elems) {
   if (M == 0) return FLEXCO_OK;
   if (dtype == FLEXCO_BF16) {
-    int32_t rc;
-    {
-      KernelTimerScope ts(trans_w ? FLEXCO_K_GEMM_BWD : FLEXCO_K_GEMM_FWD, s);
-      rc = launch_gemm_mfma(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, trans_w, ext, s, part, part_elems);
-    }
+    const int32_t rc = launch_gemm_mfma(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, trans_w, ext, s, part,
+                                        part_elems, trans_w ? FLEXCO_K_GEMM_BWD : FLEXCO_K_GEMM_FWD);
     if (rc != FLEXCO_EUNSUPPORTED) return rc;
     clear_error();
   }

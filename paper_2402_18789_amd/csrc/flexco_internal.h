@@ -1,6 +1,7 @@
 // Internal declarations shared by the host API and the kernel launchers.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include <stddef.h>
 
@@ -60,6 +61,13 @@ struct KernelTimerScope {
   ~KernelTimerScope();
 };
 
+// Event pair for ONE kernel launch of class `id` while its timer runs (false: no timer, or its slots are
+// used up).  The launch hands the pair to hipExtLaunchKernelGGL, which stamps the kernel's own start and
+// end: no marker packets go on the stream, so the neighbouring kernels are not held apart.
+// first_of_call: counts a new launch of the class (a call that issues several kernels passes false for
+// the later ones; their durations add to the same launch).
+bool kernel_timer_pair(int id, hipEvent_t* start, hipEvent_t* stop, bool first_of_call);
+
 // ---- launchers: no validation, the entry points have done it -------------------------
 // C[M,N] = A[M,K] W[N,K]^T (+bias) (+residual);  trans_w: W is [K,N].  Leading dimensions in elements.
 // part / part_elems: optional fp32 scratch for split-K partial sums (input-gradient form)
@@ -72,7 +80,8 @@ int32_t launch_gemm_generic(const void* A, const void* W, void* C, const void* b
 // bf16 MFMA path; returns FLEXCO_EUNSUPPORTED (without launching) for shapes it does not cover
 int32_t launch_gemm_mfma(const void* A, const void* W, void* C, const void* bias, const void* residual, int M,
                          int N, int K, size_t lda, size_t ldw, size_t ldc, size_t ldr, bool trans_w,
-                         const GemmExt* ext, hipStream_t s, float* part = nullptr, size_t part_elems = 0);
+                         const GemmExt* ext, hipStream_t s, float* part = nullptr, size_t part_elems = 0,
+                         int timer_id = -1);
 int32_t launch_lora_shrink_mfma(const LoraShrinkArgs& a, int n_mats, hipStream_t s);
 int32_t launch_lora_transpose(const LoraTransposeArgs& a, int n_mats, hipStream_t s);
 int32_t launch_lora_outer_batch(const LoraOuterArgs& a, hipStream_t s);

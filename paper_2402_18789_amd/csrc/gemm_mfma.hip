@@ -73,13 +73,15 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
   const int kbeg = blockIdx.y * k_chunk;
   const int l32 = lane & 31, kg = lane >> 5;
 
+  // The W fragment is the MFMA's first operand: a lane then holds, for ONE output row (lane % 32), runs
+  // of 4 consecutive output columns, so the epilogue moves 8 bytes per lane and instruction.
   // (the pipelines are macros on purpose: register arrays captured by lambdas were left in
   // scratch memory)
 #define FLEXCO_MFMAS(af_, bf_)                                                                        \
   {                                                                                                   \
     _Pragma("unroll") for (int i = 0; i < MT; ++i)                                                    \
       _Pragma("unroll") for (int j = 0; j < NT; ++j)                                                  \
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af_[i], bf_[j], acc[i][j], 0, 0, 0);      \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf_[j], af_[i], acc[i][j], 0, 0, 0);      \
   }
 
   // ===================== operand tiles: global memory -> LDS directly ==========================
@@ -300,42 +302,61 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
       for (int i = 0; i < MT; ++i)
 #pragma unroll
         for (int j = 0; j < NT; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
     }
   }
 
-  // ---- epilogue: D[i][j], j = lane % 32, i = 8 (r / 4) + 4 (lane / 32) + r % 4 ---------------
+  // ---- epilogue: register 4 q + e of acc[i][j] is row lane % 32, column 8 q + 4 (lane / 32) + e of
+  // the 32 x 32 block ------------------------------------------------------------------------------
   if (part) {
     float* P = part + (size_t)blockIdx.y * M * N;
 #pragma unroll
-    for (int i = 0; i < MT; ++i)
+    for (int i = 0; i < MT; ++i) {
+      const int row = m0 + wm0 + i * 32 + l32;
 #pragma unroll
-      for (int j = 0; j < NT; ++j) {
-        const int col = n0 + wn0 + j * 32 + l32;
-        if (col >= N) continue;
+      for (int j = 0; j < NT; ++j)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = m0 + wm0 + i * 32 + 8 * (r >> 2) + 4 * kg + (r & 3);
-          if (row < M) P[(size_t)row * N + col] = acc[i][j][r];
+        for (int q = 0; q < 4; ++q) {
+          const int col = n0 + wn0 + j * 32 + 8 * q + 4 * kg;
+          if (row >= M || col >= N) continue;     // N % 8 == 0: a run of 4 is inside or outside as a whole
+          f32x4 v;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * q + e];
+          *reinterpret_cast<f32x4*>(P + (size_t)row * N + col) = v;
         }
-      }
+    }
     return;
   }
 #pragma unroll
   for (int i = 0; i < MT; ++i) {
+    const int row = m0 + wm0 + i * 32 + l32;
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
-      const int col = n0 + wn0 + j * 32 + l32;
-      if (col >= N) continue;
-      const float bv = bias ? (float)bias[col] : 0.f;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = m0 + wm0 + i * 32 + 8 * (r >> 2) + 4 * kg + (r & 3);
-        if (row >= M) continue;
-        float v = acc[i][j][r] + bv;
-        if (res) v += (float)res[(size_t)row * ldr + col];
-        C[(size_t)row * ldc + col] = (bf16_t)v;
+      for (int q = 0; q < 4; ++q) {
+        const int col = n0 + wn0 + j * 32 + 8 * q + 4 * kg;
+        if (row >= M || col >= N) continue;
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * q + e];
+        if (bias) {
+          const bf16x4 b4 = *reinterpret_cast<const bf16x4*>(bias + col);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] += (float)b4[e];
+        }
+        if (res) {
+          const bf16x4 r4 = *reinterpret_cast<const bf16x4*>(res + (size_t)row * ldr + col);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] += (float)r4[e];
+        }
+        bf16x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = (bf16_t)v[e];
+        *reinterpret_cast<bf16x4*>(C + (size_t)row * ldc + col) = o;
       }
+      // (keeps the scheduler from gathering the loads of the whole tile up front, which costs more
+      // registers than the large tile has left)
+      if (MT * NT > 4) __builtin_amdgcn_sched_barrier(0);
     }
   }
 }
@@ -368,16 +389,22 @@ __global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(const float* __
 template <int BM, int BN, bool TRANS>
 int32_t launch_cfg(const void* A, const void* W, void* C, const void* bias, const void* res, int M, int N, int K,
                    size_t lda, size_t ldw, size_t ldc, size_t ldr, const GemmExt& ext, hipStream_t s,
-                   float* part = nullptr, int splits = 1) {
+                   int timer_id, float* part = nullptr, int splits = 1) {
   auto kern = gemm_bf16_kernel<BM, BN, TRANS>;   // all LDS is static
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n, splits), dim3(256), 0, s, (const bf16_t*)A, (const bf16_t*)W,
-                     (bf16_t*)C, (const bf16_t*)bias, (const bf16_t*)res, M, N, K, lda, ldw, ldc, ldr, tiles_m, tiles_n,
-                     ext, splits > 1 ? part : nullptr, K / splits);
+  // while the class's timer runs, the kernels carry an event pair of their own (start and end stamps of
+  // the dispatch itself)
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  if (timer_id >= 0) (void)kernel_timer_pair(timer_id, &e0, &e1, true);
+  hipExtLaunchKernelGGL(kern, dim3(tiles_m * tiles_n, splits), dim3(256), 0, s, e0, e1, 0, (const bf16_t*)A,
+                        (const bf16_t*)W, (bf16_t*)C, (const bf16_t*)bias, (const bf16_t*)res, M, N, K, lda, ldw, ldc, ldr,
+                        tiles_m, tiles_n, ext, splits > 1 ? part : nullptr, K / splits);
   if (splits > 1) {
     const size_t quads = ((size_t)M * N + 3) / 4;
-    hipLaunchKernelGGL(gemm_splitk_reduce_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s, part, splits,
-                       (bf16_t*)C, (const bf16_t*)bias, (const bf16_t*)res, M, N, ldc, ldr);
+    e0 = e1 = nullptr;
+    if (timer_id >= 0) (void)kernel_timer_pair(timer_id, &e0, &e1, false);
+    hipExtLaunchKernelGGL(gemm_splitk_reduce_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s, e0, e1, 0,
+                          part, splits, (bf16_t*)C, (const bf16_t*)bias, (const bf16_t*)res, M, N, ldc, ldr);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(FLEXCO_EHIP, "launch of gemm_bf16 failed: %s", hipGetErrorString(e));
@@ -416,9 +443,12 @@ static int pick_splits(int M, int N, int K, int tiles, size_t part_elems, int wa
 
 int32_t launch_gemm_mfma(const void* A, const void* W, void* C, const void* bias, const void* residual, int M, int N,
                          int K, size_t lda, size_t ldw, size_t ldc, size_t ldr, bool trans_w, const GemmExt* ext_in,
-                         hipStream_t s, float* part, size_t part_elems) {
+                         hipStream_t s, float* part, size_t part_elems, int timer_id) {
   // shapes the tiled kernel covers: K in whole 64-wide steps, 16-byte aligned rows
-  if (K % BK != 0 || lda % 8 != 0 || ldw % 8 != 0 || N % 8 != 0) return FLEXCO_EUNSUPPORTED;
+  // (and 8-byte aligned runs of 4 output columns in C, bias and residual)
+  if (K % BK != 0 || lda % 8 != 0 || ldw % 8 != 0 || N % 8 != 0 || ldc % 4 != 0 || (residual && ldr % 4 != 0) ||
+      ((uintptr_t)C & 7) || ((uintptr_t)bias & 7) || ((uintptr_t)residual & 7))
+    return FLEXCO_EUNSUPPORTED;
   GemmExt ext;
   if (ext_in) ext = *ext_in; else ext.n = 0;
   if (trans_w) {
@@ -428,13 +458,13 @@ int32_t launch_gemm_mfma(const void* A, const void* W, void* C, const void* bias
     // (256 x 128 tiles, one block per CU, were measured slower than two co-resident 128 x 128 blocks)
     const int tiles = ((M + 127) / 128) * ((N + 127) / 128);
     const int sp = part ? pick_splits(M, N, K, tiles, part_elems, 512) : 1;
-    return launch_cfg<128, 128, true>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, ext, s, part, sp);
+    return launch_cfg<128, 128, true>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, ext, s, timer_id, part, sp);
   }
   const long big_tiles = (long)((M + 255) / 256) * ((N + 255) / 256);
   if (big_tiles >= 192 && ext_fits(ext, false, 256))
-    return launch_cfg<256, 256, false>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, ext, s);
+    return launch_cfg<256, 256, false>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, ext, s, timer_id);
   if (!ext_fits(ext, false, 128)) return FLEXCO_EUNSUPPORTED;
-  return launch_cfg<128, 128, false>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, ext, s);
+  return launch_cfg<128, 128, false>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, ext, s, timer_id);
 }
 
 }  // namespace flexco
