@@ -24,6 +24,7 @@
 //     transposing LDS reads (ds_read_b64_tr_b16).
 // Work-group ids are remapped so that ids that land on the same XCD (id mod 8) work on
 // neighbouring tiles, M fastest: the W tile they share stays in that XCD's L2.
+#include <algorithm>
 #include "flexco_internal.h"
 #include "device_types.h"
 
@@ -86,16 +87,17 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
 
   // ===================== operand tiles: global memory -> LDS directly ==========================
   // A ring of stages of 64 k-columns; a stage holds the A tile [BM][64] and the W tile ([BN][64]
-  // in the forward form, [64][BN] in the input-gradient form), A first.  The 128 x 128 forward
-  // tile uses four stages of 32 KB: up to three in flight or waiting while one is multiplied.
-  // The 256 x 256 tile uses two stages of 64 KB: half as many barriers, and a stage's buffer is
+  // in the forward form, [64][BN] in the input-gradient form), A first.  The 128-row forward
+  // tiles use four stages (32 KB each at 128 columns, 40 KB - all of the LDS - at 192): up to
+  // three in flight or waiting while one is multiplied.
+  // The 256-row tiles use two stages (64 KB at 256 columns, 56 KB at 192): half as many barriers, and a stage's buffer is
   // handed to the loads of the stage after next as soon as its last fragments are in registers
   // (measured equal at T = 1024 and 4-7 % faster than four 32 KB stages at T >= 2048).  The
   // input-gradient form uses two stages of 32 KB, so that two blocks share a CU (its grids are
   // K-split into more blocks than CUs).  The stages are separate arrays, not one indexed
   // buffer: the compiler then sees that loads in flight target an array no ds_read of that
   // moment touches, and inserts no wait of its own.
-  constexpr int NST = TRANS ? 2 : ((BM + BN >= 512) ? 2 : 4);      // stages in the ring
+  constexpr int NST = TRANS ? 2 : ((BM + BN) * BK * 2 * 4 <= 160 * 1024 ? 4 : 2);   // stages in the ring
   constexpr int SL = BK / 16;                                       // MFMA k-slices per stage
   constexpr int PA = BM / 32, PB = BN / 32;                         // 1 KB load instructions per wavefront and stage
   constexpr int ST_ELEMS = (BM + BN) * BK;
@@ -277,7 +279,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
   // network (Sec. 4.1) folded into the base projection as extra k-steps of 16, operands read
   // straight from global memory (they are [rows, r] / [r, cols] matrices of a few KB per tile).
   for (int e = 0; e < (blockIdx.y == 0 ? ext.n : 0); ++e) {
-    if (!TRANS && !(n0 >= ext.col0[e] && n0 < ext.col1[e])) continue;
+    // forward form: an entry covers a column range whose ends are multiples of 32, so each 32-column
+    // fragment of the tile belongs to at most one entry; fragments outside this entry multiply zeros
+    if (!TRANS && (n0 + BN <= ext.col0[e] || n0 >= ext.col1[e])) continue;
     const bf16_t* A2 = ext.A2[e];
     const bf16_t* W2 = ext.W2[e];
     for (int k2 = 0; k2 < ext.r; k2 += 16) {
@@ -290,8 +294,14 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
 #pragma unroll
       for (int j = 0; j < NT; ++j) {
         if (!TRANS) {
-          const int c = min(n0 + wn0 + j * 32 + l32, ext.col1[e] - 1) - ext.col0[e];
-          bfr[j] = *reinterpret_cast<const bf16x8*>(W2 + (size_t)c * ext.ldw2[e] + k2 + kg * 8);
+          const int cj = n0 + wn0 + j * 32;
+          if (cj >= ext.col0[e] && cj < ext.col1[e]) {
+            const int c = min(cj + l32, ext.col1[e] - 1) - ext.col0[e];
+            bfr[j] = *reinterpret_cast<const bf16x8*>(W2 + (size_t)c * ext.ldw2[e] + k2 + kg * 8);
+          } else {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) bfr[j][q] = (bf16_t)0.f;
+          }
         } else {
           const int c = min(n0 + wn0 + j * 32 + l32, N - 1);
 #pragma unroll
@@ -389,13 +399,13 @@ __global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(const float* __
 template <int BM, int BN, bool TRANS>
 int32_t launch_cfg(const void* A, const void* W, void* C, const void* bias, const void* res, int M, int N, int K,
                    size_t lda, size_t ldw, size_t ldc, size_t ldr, const GemmExt& ext, hipStream_t s,
-                   int timer_id, float* part = nullptr, int splits = 1) {
+                   int timer_id, float* part = nullptr, int splits = 1, bool first_of_call = true) {
   auto kern = gemm_bf16_kernel<BM, BN, TRANS>;   // all LDS is static
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   // while the class's timer runs, the kernels carry an event pair of their own (start and end stamps of
   // the dispatch itself)
   hipEvent_t e0 = nullptr, e1 = nullptr;
-  if (timer_id >= 0) (void)kernel_timer_pair(timer_id, &e0, &e1, true);
+  if (timer_id >= 0) (void)kernel_timer_pair(timer_id, &e0, &e1, first_of_call);
   hipExtLaunchKernelGGL(kern, dim3(tiles_m * tiles_n, splits), dim3(256), 0, s, e0, e1, 0, (const bf16_t*)A,
                         (const bf16_t*)W, (bf16_t*)C, (const bf16_t*)bias, (const bf16_t*)res, M, N, K, lda, ldw, ldc, ldr,
                         tiles_m, tiles_n, ext, splits > 1 ? part : nullptr, K / splits);
@@ -413,13 +423,32 @@ int32_t launch_cfg(const void* A, const void* W, void* C, const void* bias, cons
 
 }  // namespace
 
-static bool ext_fits(const GemmExt& ext, bool trans_w, int BN) {
+static bool ext_fits(const GemmExt& ext, bool trans_w, int N) {
   if (ext.n == 0) return true;
   if (ext.r % 16 != 0) return false;
   if (trans_w) return true;
-  for (int e = 0; e < ext.n; ++e)
-    if (ext.col0[e] % BN != 0 || ext.col1[e] % BN != 0) return false;   // one entry per block
+  for (int e = 0; e < ext.n; ++e)      // whole 32-column fragments per entry
+    if (ext.col0[e] % 32 != 0 || (ext.col1[e] % 32 != 0 && ext.col1[e] != N)) return false;
   return true;
+}
+
+// The entries of `ext` restricted to output columns [c0, c1), in the coordinates of a GEMM over those
+// columns only.
+static GemmExt sub_ext(const GemmExt& ext, int c0, int c1) {
+  GemmExt o;
+  o.n = 0;
+  o.r = ext.r;
+  for (int e = 0; e < ext.n; ++e) {
+    const int lo = std::max(ext.col0[e], c0), hi = std::min(ext.col1[e], c1);
+    if (lo >= hi) continue;
+    o.col0[o.n] = lo - c0;
+    o.col1[o.n] = hi - c0;
+    o.A2[o.n] = ext.A2[e];
+    o.W2[o.n] = ext.W2[e] + (size_t)(lo - ext.col0[e]) * ext.ldw2[e];
+    o.ldw2[o.n] = ext.ldw2[e];
+    ++o.n;
+  }
+  return o;
 }
 
 // Largest split count <= want that cuts K into whole 64-wide steps and fits the partial buffer.
@@ -452,7 +481,7 @@ int32_t launch_gemm_mfma(const void* A, const void* W, void* C, const void* bias
   GemmExt ext;
   if (ext_in) ext = *ext_in; else ext.n = 0;
   if (trans_w) {
-    if (!ext_fits(ext, true, 128)) return FLEXCO_EUNSUPPORTED;
+    if (!ext_fits(ext, true, N)) return FLEXCO_EUNSUPPORTED;
     // few row tiles (a finetune window) and a long contraction: cut K across blocks so that the
     // weight stream is spread over the whole chip; partial sums are reduced in split order
     // (256 x 128 tiles, one block per CU, were measured slower than two co-resident 128 x 128 blocks)
@@ -460,11 +489,43 @@ int32_t launch_gemm_mfma(const void* A, const void* W, void* C, const void* bias
     const int sp = part ? pick_splits(M, N, K, tiles, part_elems, 512) : 1;
     return launch_cfg<128, 128, true>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, ext, s, timer_id, part, sp);
   }
-  const long big_tiles = (long)((M + 255) / 256) * ((N + 255) / 256);
-  if (big_tiles >= 192 && ext_fits(ext, false, 256))
-    return launch_cfg<256, 256, false>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, ext, s, timer_id);
-  if (!ext_fits(ext, false, 128)) return FLEXCO_EUNSUPPORTED;
-  return launch_cfg<128, 128, false>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, ext, s, timer_id);
+  if (!ext_fits(ext, false, N)) return FLEXCO_EUNSUPPORTED;
+  // Forward form: tile shapes by estimated time.  A launch runs in rounds of one block per CU; a round
+  // costs the tile's area over the rate its kernel sustains with the chip full (measured, relative:
+  // 256 x 256 tiles 1.24, 256 x 192 1.09, 128 x 192 1.0, 128 x 128 0.875).  Candidates: one shape for
+  // the whole matrix, or columns [0, 256 a) in 256-wide tiles and the rest in 192-wide ones, as two
+  // launches (a partial last round of wide tiles is what the narrower ones avoid).
+  const int CU = 256;
+  auto rounds = [&](long tiles) { return (double)((tiles + CU - 1) / CU); };
+  const long tm256 = (M + 255) / 256, tm128 = (M + 127) / 128;
+  const double c256 = 256.0 * 256 / 1.24, c256n = 256.0 * 192 / 1.09, c128n = 128.0 * 192 / 1.0, c128 = 128.0 * 128 / 0.875;
+  double best = rounds(tm128 * ((N + 127) / 128)) * c128;
+  int shape = 0, a_best = 0;                        // 0: 128 x 128, 1: 128 x 192, 2: 256-wide (a tiles) + 192-wide
+  {
+    const double t = rounds(tm128 * ((N + 191) / 192)) * c128n;
+    if (t < best) { best = t; shape = 1; }
+  }
+  const int n256 = (N + 255) / 256;
+  for (int a = n256; a >= 0; --a) {
+    const int rest = N - 256 * a;                   // columns left for 192-wide tiles
+    if (rest < 0 && a != n256) continue;
+    const long b = rest > 0 ? (rest + 191) / 192 : 0;
+    const double t = (a ? rounds(tm256 * a) * c256 : 0.0) + (b ? rounds(tm256 * b) * c256n : 0.0);
+    if (t < best - 1e-9) { best = t; shape = 2; a_best = a; }
+  }
+  if (shape == 0) return launch_cfg<128, 128, false>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, ext, s, timer_id);
+  if (shape == 1) return launch_cfg<128, 192, false>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, ext, s, timer_id);
+  const int n1 = std::min(N, 256 * a_best);
+  if (n1 > 0)
+    FLEXCO_TRY((launch_cfg<256, 256, false>(A, W, C, bias, residual, M, n1, K, lda, ldw, ldc, ldr, sub_ext(ext, 0, n1), s,
+                                            timer_id)));
+  if (n1 < N) {
+    const bf16_t* W1 = (const bf16_t*)W + (size_t)n1 * ldw;
+    return launch_cfg<256, 192, false>(A, W1, (bf16_t*)C + n1, bias ? (const bf16_t*)bias + n1 : nullptr,
+                                       residual ? (const bf16_t*)residual + n1 : nullptr, M, N - n1, K, lda, ldw, ldc, ldr,
+                                       sub_ext(ext, n1, N), s, timer_id, nullptr, 1, n1 == 0);
+  }
+  return FLEXCO_OK;
 }
 
 }  // namespace flexco

@@ -42,7 +42,10 @@ def say(msg):
                                          (1, 256, 256, 0), (129, 384, 136, 0),
                                          # >= 192 tiles of 256 x 256: the large-tile kernel, ragged in M and N,
                                          # odd and even numbers of k-stages
-                                         (300, 49160, 320, 0), (520, 24584, 192, 0), (256, 49152, 64, 0)])
+                                         (300, 49160, 320, 0), (520, 24584, 192, 0), (256, 49152, 64, 0),
+                                         # 192-wide tiles (one round of 128 x 192), ragged in N; 256-wide and
+                                         # 192-wide tiles side by side in one product
+                                         (1024, 6152, 128, 0), (1024, 28672, 64, 0), (1000, 28680, 128, 0)])
 def test_gemm(dtype, M, N, K, trans):
     say(f"gemm {dtype} M={M} N={N} K={K} trans={trans}")
     cfg = C1.with_(dtype=dtype)
