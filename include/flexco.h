@@ -172,6 +172,9 @@ typedef struct flexco_kv_pool {
  * x, x2 (input of the second norm), gate, up; the attention output and the softmax
  * log-sum-exp are kept in addition (8 KB + 128 B per token at 8B shape) so that the
  * backward pass needs no second forward pass over the keys.
+ * saved_u[t] (optional, NULL = not kept): the rank-r product x_t A_t^T of LoRA target t in fp32
+ * (4 r bytes per token and target): with it the backward pass does not multiply the saved inputs
+ * by A_t again for the dB_t gradient.  Either every target of cfg.lora_targets has one or none.
  * dk_accum / dv_accum: the statically allocated KV-gradient accumulator of Sec. 7. */
 typedef struct flexco_ft_state {
   int32_t seq_len;
@@ -184,6 +187,7 @@ typedef struct flexco_ft_state {
   float* lse;         /* [L, nq]                      */
   float* dk_accum;    /* [L, nkv d] float             */
   float* dv_accum;    /* [L, nkv d] float             */
+  float* saved_u[FLEXCO_N_TARGETS];   /* [L, r] float or NULL */
 } flexco_ft_state;
 
 /* Message for the last failing call on this thread ("" if none). */

@@ -67,7 +67,7 @@ class KVPool(C.Structure):
 class FtState(C.Structure):
     _fields_ = [("seq_len", C.c_int32)] + [(n, C.c_void_p) for n in
                                            ("q_cache", "saved_x", "saved_x2", "saved_gate", "saved_up", "saved_attn",
-                                            "lse", "dk_accum", "dv_accum")]
+                                            "lse", "dk_accum", "dv_accum")] + [("saved_u", C.c_void_p * 7)]
 
 
 class LmHead(C.Structure):

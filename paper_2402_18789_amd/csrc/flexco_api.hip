@@ -310,12 +310,26 @@ bool lora_mfma_ok(const flexco_layer_cfg& c, int k_dim) {
   return c.dtype == FLEXCO_BF16 && c.lora_rank % 16 == 0 && k_dim % 128 == 0;
 }
 
+// saved_u: kept for every LoRA target of the configuration or for none; 16-byte aligned
+int32_t check_saved_u(const flexco_layer_cfg& c, const flexco_ft_state* ft) {
+  int have = 0, want = 0;
+  for (int t = 0; t < FLEXCO_N_TARGETS; ++t) {
+    if (!has_target(c, t)) continue;
+    ++want;
+    if (ft->saved_u[t]) ++have;
+    FLEXCO_CHECK(aligned16(ft->saved_u[t]), FLEXCO_EINVAL, "ft state: saved_u[%d] is misaligned", t);
+  }
+  FLEXCO_CHECK(have == 0 || have == want, FLEXCO_EINVAL, "ft state keeps saved_u for %d of %d LoRA targets", have, want);
+  return FLEXCO_OK;
+}
+
 // One projection of the forward pass over all T tokens, with the LoRA bypass of up to three
 // targets that share its input (q/k/v, gate/up) folded in:
 //   y[:, col0_t : col1_t] = x W^T (+bias) (+res)  +  scale (x A_t^T) B_t^T on adapter rows.
 int32_t forward_projection(const flexco_layer_cfg& c, const flexco_lora* lora, const flexco_maps& m, const void* x,
                            int K, const void* W, const void* bias, const void* res, size_t ldr, void* y, int N,
-                           const int* targets, const int* col0, int n_targets, FwdWs& k, hipStream_t s) {
+                           const int* targets, const int* col0, int n_targets, FwdWs& k,
+                           const flexco_ft_state* ft, hipStream_t s) {
   int act[3], nact = 0;
   for (int i = 0; i < n_targets; ++i)
     if (m.n_lora > 0 && has_target(c, targets[i])) act[nact++] = i;
@@ -326,13 +340,16 @@ int32_t forward_projection(const flexco_layer_cfg& c, const flexco_lora* lora, c
     memset(&sa, 0, sizeof(sa)); memset(&ext, 0, sizeof(ext));
     // u_t = scale x A_t^T for every token row (zero rows where the token has no adapter)
     sa.row_map = m.tok_lora; sa.rows = T; sa.r = r; sa.scale = c.lora_scale;
+    // the finetune window's rows of the unscaled product are kept for the backward pass (dB_t)
+    const bool keep_u = ft && m.n_ft > 0 && ft->saved_u[targets[act[0]]] != nullptr;
+    sa.f32_lo = m.ft_tok0; sa.f32_hi = keep_u ? m.ft_tok0 + m.n_ft : m.ft_tok0;
     ext.n = nact; ext.r = r;
     for (int z = 0; z < nact; ++z) {
       const int t = targets[act[z]];
       int in, out;
       target_dims(c, t, &in, &out);
       sa.X[z] = (const bf16_t*)x; sa.ldx[z] = K; sa.S[z] = (const bf16_t*)lora->A[t]; sa.lds[z] = K; sa.K[z] = K;
-      sa.out_f32[z] = nullptr; sa.out_ext[z] = k.lw.ext[t];
+      sa.out_f32[z] = keep_u ? ft->saved_u[t] + (size_t)m.ft_pos0 * r : nullptr; sa.out_ext[z] = k.lw.ext[t];
       ext.col0[z] = col0[act[z]]; ext.col1[z] = col0[act[z]] + out;
       ext.A2[z] = k.lw.ext[t]; ext.W2[z] = (const bf16_t*)lora->B[t]; ext.ldw2[z] = r;
     }
@@ -371,15 +388,16 @@ void plan_group(const flexco_layer_cfg& c, BwdGroup& g) {
 
 // Start of a backward window, fused groups only: u_t = x_t A_t^T of every target in one launch,
 // and the transposed B_t the t_t = dy_t B_t products contract against.
+// Where the forward pass kept u_t (ft->saved_u), its window rows are used as they are.
 int32_t lora_bwd_prepare(const flexco_layer_cfg& c, const flexco_lora* lora, int n, const BwdGroup* groups,
-                         int n_groups, BwdWs& k, hipStream_t s) {
+                         int n_groups, BwdWs& k, const flexco_ft_state* ft, int win_start, hipStream_t s) {
   LoraShrinkArgs su;
   LoraTransposeArgs ta;
   memset(&su, 0, sizeof(su)); memset(&ta, 0, sizeof(ta));
   const int r = c.lora_rank;
-  su.rows = n; su.r = r; su.scale = 1.f;
+  su.rows = n; su.r = r; su.scale = 1.f; su.f32_lo = 0; su.f32_hi = n;
   ta.r = r;
-  int nz = 0;
+  int nz = 0, nu = 0;
   for (int gi = 0; gi < n_groups; ++gi) {
     const BwdGroup& g = groups[gi];
     if (!g.fused) continue;
@@ -387,14 +405,18 @@ int32_t lora_bwd_prepare(const flexco_layer_cfg& c, const flexco_lora* lora, int
       const int t = g.targets[g.act[a]];
       int in, out;
       target_dims(c, t, &in, &out);
-      su.X[nz] = (const bf16_t*)g.xs[g.act[a]]; su.ldx[nz] = in; su.S[nz] = (const bf16_t*)lora->A[t]; su.lds[nz] = in;
-      su.K[nz] = in; su.out_f32[nz] = k.lw.u[t]; su.out_ext[nz] = nullptr;
       ta.B[nz] = (const bf16_t*)lora->B[t]; ta.Bt[nz] = k.lw.bt[t]; ta.out[nz] = out;
+      if (ft->saved_u[t]) {
+        k.lw.u[t] = ft->saved_u[t] + (size_t)win_start * r;
+        continue;
+      }
+      su.X[nu] = (const bf16_t*)g.xs[g.act[a]]; su.ldx[nu] = in; su.S[nu] = (const bf16_t*)lora->A[t]; su.lds[nu] = in;
+      su.K[nu] = in; su.out_f32[nu] = k.lw.u[t]; su.out_ext[nu] = nullptr;
+      ++nu;
     }
   }
-  if (nz == 0) return FLEXCO_OK;
-  LR(launch_lora_shrink_mfma(su, nz, s));
-  LR(launch_lora_transpose(ta, nz, s));
+  if (nu > 0) LR(launch_lora_shrink_mfma(su, nu, s));
+  if (nz > 0) LR(launch_lora_transpose(ta, nz, s));
   return FLEXCO_OK;
 }
 
@@ -416,7 +438,7 @@ int32_t backward_projection(const flexco_layer_cfg& c, const flexco_lora* lora, 
     LoraShrinkArgs st;
     GemmExt ext;
     memset(&st, 0, sizeof(st)); memset(&ext, 0, sizeof(ext));
-    st.rows = n; st.r = r; st.scale = c.lora_scale;
+    st.rows = n; st.r = r; st.scale = c.lora_scale; st.f32_lo = 0; st.f32_hi = n;
     ext.n = g.nact; ext.r = r;
     for (int z = 0; z < g.nact; ++z) {
       const int t = g.targets[g.act[z]];
@@ -585,6 +607,7 @@ extern "C" int32_t flexco_layer_forward(const flexco_layer_cfg* cfg, const flexc
   if (ft) {
     FLEXCO_CHECK(ft->q_cache && ft->saved_x && ft->saved_x2 && ft->saved_gate && ft->saved_up && ft->saved_attn &&
                      ft->lse, FLEXCO_EINVAL, "ft state has a NULL buffer");
+    FLEXCO_TRY(check_saved_u(c, ft));
     FLEXCO_CHECK(m.ft_pos0 + m.n_ft <= ft->seq_len, FLEXCO_ESHAPE,
                  "finetune window [%d, %d) exceeds the state's seq_len %d", m.ft_pos0, m.ft_pos0 + m.n_ft, ft->seq_len);
   }
@@ -600,25 +623,25 @@ extern "C" int32_t flexco_layer_forward(const flexco_layer_cfg* cfg, const flexc
   EW(launch_rmsnorm(x_in, w->g1, k.h, T, H, c.rms_eps, dt, s));
   {
     const int tg[3] = {FLEXCO_T_Q, FLEXCO_T_K, FLEXCO_T_V}, c0[3] = {0, qd, qd + kd};
-    FLEXCO_TRY(forward_projection(c, lora, m, k.h, H, w->wqkv, w->bqkv, nullptr, 0, k.qkv, qkvd, tg, c0, 3, k, s));
+    FLEXCO_TRY(forward_projection(c, lora, m, k.h, H, w->wqkv, w->bqkv, nullptr, 0, k.qkv, qkvd, tg, c0, 3, k, ft, s));
   }
   EW(launch_rope_append(c, k.qkv, m.tok_pos, m.slot, *pool, T, m.ft_tok0, m.n_ft, m.ft_pos0,
                         ft ? ft->q_cache : nullptr, s));
   FLEXCO_TRY(run_attention(c, m, k.qkv, qkvd, *pool, k.attn, qd, ft ? k.lse : nullptr, k.part_ml, k.part_acc, s));
   {
     const int tg[1] = {FLEXCO_T_O}, c0[1] = {0};
-    FLEXCO_TRY(forward_projection(c, lora, m, k.attn, qd, w->wo, nullptr, x_in, H, k.x2, H, tg, c0, 1, k, s));
+    FLEXCO_TRY(forward_projection(c, lora, m, k.attn, qd, w->wo, nullptr, x_in, H, k.x2, H, tg, c0, 1, k, ft, s));
   }
   // MLP side
   EW(launch_rmsnorm(k.x2, w->g2, k.h, T, H, c.rms_eps, dt, s));
   {
     const int tg[2] = {FLEXCO_T_GATE, FLEXCO_T_UP}, c0[2] = {0, F};
-    FLEXCO_TRY(forward_projection(c, lora, m, k.h, H, w->wgu, nullptr, nullptr, 0, k.gu, 2 * F, tg, c0, 2, k, s));
+    FLEXCO_TRY(forward_projection(c, lora, m, k.h, H, w->wgu, nullptr, nullptr, 0, k.gu, 2 * F, tg, c0, 2, k, ft, s));
   }
   EW(launch_swiglu(k.gu, k.act, T, F, dt, s));
   {
     const int tg[1] = {FLEXCO_T_DOWN}, c0[1] = {0};
-    FLEXCO_TRY(forward_projection(c, lora, m, k.act, F, w->wd, nullptr, k.x2, H, x_out, H, tg, c0, 1, k, s));
+    FLEXCO_TRY(forward_projection(c, lora, m, k.act, F, w->wd, nullptr, k.x2, H, x_out, H, tg, c0, 1, k, ft, s));
   }
   // keep what graph pruning leaves alive for the finetune rows (Alg. 1), at their positions
   if (ft) {
@@ -690,6 +713,7 @@ extern "C" int32_t flexco_lora_bwd(const flexco_layer_cfg* cfg, const flexco_bas
   FLEXCO_CHECK(ft && seq_pages && dY && ws, FLEXCO_EINVAL, "NULL argument");
   FLEXCO_CHECK(ft->q_cache && ft->saved_x && ft->saved_x2 && ft->saved_gate && ft->saved_up && ft->saved_attn &&
                    ft->lse && ft->dk_accum && ft->dv_accum, FLEXCO_EINVAL, "ft state has a NULL buffer");
+  FLEXCO_TRY(check_saved_u(c, ft));
   FLEXCO_CHECK(win_start >= 0 && win_len > 0, FLEXCO_EINVAL, "window [%d, +%d) is invalid", win_start, win_len);
   const int l = win_start + win_len;
   FLEXCO_CHECK(l <= ft->seq_len, FLEXCO_ESHAPE, "window end %d exceeds seq_len %d", l, ft->seq_len);
@@ -731,7 +755,7 @@ extern "C" int32_t flexco_lora_bwd(const flexco_layer_cfg* cfg, const flexco_bas
   if (has_target(c, FLEXCO_T_DOWN)) EW(launch_swiglu_remat(gate_w, up_w, k.act, n, F, dt, s));
   if (gu_lora) EW(launch_rmsnorm(x2_w, w->g2, k.hn2, n, H, c.rms_eps, dt, s));
   if (qkv_lora) EW(launch_rmsnorm(x_w, w->g1, k.hn, n, H, c.rms_eps, dt, s));
-  FLEXCO_TRY(lora_bwd_prepare(c, lora, n, grp, 4, k, s));
+  FLEXCO_TRY(lora_bwd_prepare(c, lora, n, grp, 4, k, ft, win_start, s));
 
   // ---- MLP side: down projection, SwiGLU, gate/up projections, second norm -------------
   FLEXCO_TRY(backward_projection(c, lora, n, dY, H, w->wd, k.dact, grp[0], k, outer, s));

@@ -16,10 +16,11 @@ struct LoraShrinkArgs {     // out[z][row][rank] = sum_k X[z][row, k] S[z][rank,
   const bf16_t* X[LORA_MATS]; size_t ldx[LORA_MATS];
   const bf16_t* S[LORA_MATS]; size_t lds[LORA_MATS];
   int K[LORA_MATS];                 // contracted width, per matrix
-  float* out_f32[LORA_MATS];        // [rows, r] or NULL
+  float* out_f32[LORA_MATS];        // or NULL: rows [f32_lo, f32_hi) are written, row m at out_f32[(m - f32_lo) * r ..]
   bf16_t* out_ext[LORA_MATS];       // [rows, r], scaled by `scale`, or NULL (operand of the GEMM extension)
   const int32_t* row_map;   // [rows] or NULL: rows with row_map[row] < 0 have no adapter, their out_ext rows are zero
   int rows, r;
+  int f32_lo, f32_hi;
   float scale;
 };
 struct LoraTransposeArgs { const bf16_t* B[LORA_MATS]; bf16_t* Bt[LORA_MATS]; int out[LORA_MATS]; int r; };

@@ -94,7 +94,8 @@ __global__ __launch_bounds__(1024) void lora_shrink_kernel(LoraShrinkArgs a) {
       float v = 0.f;
       for (int w = 0; w < nw; ++w) v += red[w][rt][ln][e];
       const size_t o = (size_t)orow * a.r + rank;
-      if (a.out_f32[z] && out_ok) a.out_f32[z][o] = v;
+      if (a.out_f32[z] && out_ok && orow >= a.f32_lo && orow < a.f32_hi)
+        a.out_f32[z][(size_t)(orow - a.f32_lo) * a.r + rank] = v;
       if (a.out_ext[z]) a.out_ext[z][o] = (bf16_t)(out_ok ? v * a.scale : 0.f);
     }
   }

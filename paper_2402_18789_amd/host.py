@@ -119,7 +119,7 @@ class DevicePool:
 
 
 class DeviceFtState:
-    def __init__(self, cfg, L, device="cuda"):
+    def __init__(self, cfg, L, device="cuda", keep_u=True):
         dt = TORCH_DTYPE[cfg.dtype]
         z = lambda w, d=dt: torch.zeros((L, w), dtype=d, device=device)
         self.L = L
@@ -131,6 +131,12 @@ class DeviceFtState:
         self.c = B.FtState(L, self.q_cache.data_ptr(), self.x.data_ptr(), self.x2.data_ptr(), self.gate.data_ptr(),
                            self.up.data_ptr(), self.attn.data_ptr(), self.lse.data_ptr(), self.dk_accum.data_ptr(),
                            self.dv_accum.data_ptr())
+        # rank-r products x_t A_t^T of the forward pass, kept for the backward pass
+        self.u = {}
+        if keep_u and cfg.lora_targets:
+            for t in cfg.lora_targets:
+                self.u[t] = z(cfg.lora_rank, torch.float32)
+                self.c.saved_u[B.TARGET_NAMES.index(t)] = self.u[t].data_ptr()
 
     def zero_accum(self):
         self.dk_accum.zero_()

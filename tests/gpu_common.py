@@ -28,7 +28,8 @@ def to_np(t):
 class Case:
     """One layer, one pool, at most one finetune sequence; both sides in lock step."""
 
-    def __init__(self, cfg, batch, seed=0, layer=0, kv_split_pages=0, pool_dtype=np.float64, weights=None, lora=None):
+    def __init__(self, cfg, batch, seed=0, layer=0, kv_split_pages=0, pool_dtype=np.float64, weights=None, lora=None,
+                 keep_u=True):
         self.cfg, self.seed, self.layer_id = cfg, seed, layer
         self.W = weights if weights is not None else gen.layer_weights(cfg, seed, layer)
         self.lora = lora if lora is not None else gen.lora_weights(cfg, seed, layer)
@@ -45,7 +46,7 @@ class Case:
             if r.kind == KIND_FINETUNE:
                 L = batch.seq_capacity[r.seq_id]
                 self.o_ft[r.seq_id] = OL.FtState(cfg, L)
-                self.d_ft[r.seq_id] = HH.DeviceFtState(cfg, L)
+                self.d_ft[r.seq_id] = HH.DeviceFtState(cfg, L, keep_u=keep_u)
         self.fill_prefixes(batch)
 
     def fill_prefixes(self, batch):

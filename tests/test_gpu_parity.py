@@ -204,13 +204,14 @@ def test_attention_window_bwd(cfg_name, win_start, win_len):
 # ------------------------------------------------------------------------------------------
 # whole layer: forward iterations, then token-window backward
 # ------------------------------------------------------------------------------------------
-def run_layer_case(cfg, batch0, ft_window, prefill_chunk, bwd_windows, seed=0, split=0, need_dx=True, tol_qk=None):
+def run_layer_case(cfg, batch0, ft_window, prefill_chunk, bwd_windows, seed=0, split=0, need_dx=True, tol_qk=None,
+                   keep_u=True):
     """tol_qk: bound for the tensors that depend on the gradient through the softmax logits (dX, the K
     accumulator, dA/dB of q and k) when it differs from the general one (see the callers that pass it)."""
     report = []
     tol = TOL[cfg.dtype]
     tol_qk = tol if tol_qk is None else tol_qk
-    case = Case(cfg, batch0, seed=seed, kv_split_pages=split)
+    case = Case(cfg, batch0, seed=seed, kv_split_pages=split, keep_u=keep_u)
     batch, it = batch0, 0
     ft_seq = [r.seq_id for r in batch0.requests if r.kind == KIND_FINETUNE][0]
     L = batch0.seq_capacity[ft_seq]
@@ -297,6 +298,13 @@ def test_layer_small_bf16_group5_all_targets():
     say("layer small bf16 group 5")
     b = gen.batch_scaled(8, 6, 30, 200, [(0, 50, 50)], [(0, 90, 170)])
     run_layer_case(SMALL_BF16_G5, b, ft_window=80, prefill_chunk=16, bwd_windows=[170], seed=8, split=4)
+
+
+def test_layer_small_bf16_without_kept_rank_products():
+    """The state does not keep x A^T of the forward pass: the backward pass multiplies again."""
+    say("layer small bf16, saved_u = NULL")
+    b = gen.batch_scaled(9, 5, 3, 300, [(0, 40, 40)], [(0, 100, 260)])
+    run_layer_case(SMALL_BF16, b, ft_window=160, prefill_chunk=70, bwd_windows=[60, 200], seed=9, keep_u=False)
 
 
 # The 14B / 32B shapes on short sequences: outputs, saved activations and the gradients that do not pass
