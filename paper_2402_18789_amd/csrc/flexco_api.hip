@@ -123,6 +123,7 @@ void target_dims(const flexco_layer_cfg& c, int t, int* in, int* out);
 // scratch of the bf16 LoRA path for `rows` token rows, one slot per target
 struct LoraWs {
   bf16_t* ext[LORA_MATS];     // scaled bf16 [rows, r] operand of the GEMM extension
+  float* part;                // partial products of a shrink cut over several blocks
   // backward only
   float* u[LORA_MATS];        // [rows, r]
   float* t[LORA_MATS];        // [rows, r]
@@ -137,6 +138,7 @@ void carve_lora(const flexco_layer_cfg& c, int rows, bool backward, Carver& cv, 
     int in, out;
     target_dims(c, t, &in, &out);
     w.ext[t] = (bf16_t*)cv.take(sizeof(bf16_t) * (size_t)rows * r);
+    if (!w.part) w.part = (float*)cv.take(sizeof(float) * LORA_SHRINK_SPLITS * 3 * (size_t)rows * r);   // <= 3 targets per launch
     if (!backward) continue;
     w.u[t] = (float*)cv.take(sizeof(float) * (size_t)rows * r);
     w.t[t] = (float*)cv.take(sizeof(float) * (size_t)rows * r);
@@ -339,7 +341,7 @@ int32_t forward_projection(const flexco_layer_cfg& c, const flexco_lora* lora, c
     GemmExt ext;
     memset(&sa, 0, sizeof(sa)); memset(&ext, 0, sizeof(ext));
     // u_t = scale x A_t^T for every token row (zero rows where the token has no adapter)
-    sa.row_map = m.tok_lora; sa.rows = T; sa.r = r; sa.scale = c.lora_scale;
+    sa.row_map = m.tok_lora; sa.rows = T; sa.r = r; sa.scale = c.lora_scale; sa.part = k.lw.part;
     // the finetune window's rows of the unscaled product are kept for the backward pass (dB_t)
     const bool keep_u = ft && m.n_ft > 0 && ft->saved_u[targets[act[0]]] != nullptr;
     sa.f32_lo = m.ft_tok0; sa.f32_hi = keep_u ? m.ft_tok0 + m.n_ft : m.ft_tok0;
@@ -395,7 +397,7 @@ int32_t lora_bwd_prepare(const flexco_layer_cfg& c, const flexco_lora* lora, int
   LoraTransposeArgs ta;
   memset(&su, 0, sizeof(su)); memset(&ta, 0, sizeof(ta));
   const int r = c.lora_rank;
-  su.rows = n; su.r = r; su.scale = 1.f; su.f32_lo = 0; su.f32_hi = n;
+  su.rows = n; su.r = r; su.scale = 1.f; su.f32_lo = 0; su.f32_hi = n;   // (up to 7 matrices: no split scratch)
   ta.r = r;
   int nz = 0, nu = 0;
   for (int gi = 0; gi < n_groups; ++gi) {
@@ -438,7 +440,7 @@ int32_t backward_projection(const flexco_layer_cfg& c, const flexco_lora* lora, 
     LoraShrinkArgs st;
     GemmExt ext;
     memset(&st, 0, sizeof(st)); memset(&ext, 0, sizeof(ext));
-    st.rows = n; st.r = r; st.scale = c.lora_scale; st.f32_lo = 0; st.f32_hi = n;
+    st.rows = n; st.r = r; st.scale = c.lora_scale; st.f32_lo = 0; st.f32_hi = n; st.part = k.lw.part;
     ext.n = g.nact; ext.r = r;
     for (int z = 0; z < g.nact; ++z) {
       const int t = g.targets[g.act[z]];

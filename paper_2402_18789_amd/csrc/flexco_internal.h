@@ -22,7 +22,12 @@ struct LoraShrinkArgs {     // out[z][row][rank] = sum_k X[z][row, k] S[z][rank,
   int rows, r;
   int f32_lo, f32_hi;
   float scale;
+  // optional scratch of LORA_SHRINK_SPLITS * n_mats * rows * r floats: long contractions are then cut
+  // over several blocks per row tile, whose partial products a second kernel adds in block order
+  float* part;
+  int ksplit;               // set by the launcher
 };
+constexpr int LORA_SHRINK_SPLITS = 8;
 struct LoraTransposeArgs { const bf16_t* B[LORA_MATS]; bf16_t* Bt[LORA_MATS]; int out[LORA_MATS]; int r; };
 // batch of rank-r gradient products  G_e(i, j) += scale * sum_m X_e[m, i] U_e[m, j], m < n, i < n_long_e, j < r
 constexpr int LORA_OUTER_MAX = 2 * LORA_MATS;

@@ -34,7 +34,7 @@ __global__ __launch_bounds__(1024) void lora_shrink_kernel(LoraShrinkArgs a) {
   // every wavefront looks at the same 16 rows, so this is the same for the whole block
   const bool any_row = __ballot(row_ok) != 0;
   if (!any_row) {   // a tile without adapter rows: only its zero rows of the GEMM operand are due
-    if (a.out_ext[z])
+    if (a.out_ext[z] && blockIdx.z == 0)
       for (int idx = threadIdx.x; idx < 16 * a.r; idx += blockDim.x)
         if (tile * 16 + idx / a.r < a.rows) a.out_ext[z][(size_t)tile * 16 * a.r + idx] = (bf16_t)0.f;
     return;
@@ -42,8 +42,8 @@ __global__ __launch_bounds__(1024) void lora_shrink_kernel(LoraShrinkArgs a) {
   const bf16_t* X = a.X[z];
   const bf16_t* S = a.S[z];
   const size_t src_row = row_ok ? (size_t)row : 0;   // rows without adapter read row 0; their results are dropped
-  const int k_wave = a.K[z] / nw;
-  const int k0 = wave * k_wave, k1 = k0 + k_wave;
+  const int k_wave = a.K[z] / (nw * a.ksplit);
+  const int k0 = (blockIdx.z * nw + wave) * k_wave, k1 = k0 + k_wave;
   const bf16_t* xp = X + src_row * a.ldx[z] + g * 8;
   const bf16_t* sp[RT];
   bool rank_ok[RT];
@@ -94,11 +94,31 @@ __global__ __launch_bounds__(1024) void lora_shrink_kernel(LoraShrinkArgs a) {
       float v = 0.f;
       for (int w = 0; w < nw; ++w) v += red[w][rt][ln][e];
       const size_t o = (size_t)orow * a.r + rank;
+      if (a.ksplit > 1) {   // partial product of this block's k range; the finalize kernel adds them up
+        a.part[((size_t)(z * a.ksplit + blockIdx.z) * a.rows) * a.r + o] = v;
+        continue;
+      }
       if (a.out_f32[z] && out_ok && orow >= a.f32_lo && orow < a.f32_hi)
         a.out_f32[z][(size_t)(orow - a.f32_lo) * a.r + rank] = v;
       if (a.out_ext[z]) a.out_ext[z][o] = (bf16_t)(out_ok ? v * a.scale : 0.f);
     }
   }
+}
+
+// Second step of a shrink whose contraction was cut over several blocks: out = sum of the partial
+// products in block order, written like the one-step kernel writes it.
+__global__ __launch_bounds__(256) void lora_shrink_finalize_kernel(LoraShrinkArgs a) {
+  const int z = blockIdx.y;
+  const size_t o = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (o >= (size_t)a.rows * a.r) return;
+  const int orow = (int)(o / a.r), rank = (int)(o % a.r);
+  const bool out_ok = !a.row_map || a.row_map[orow] >= 0;
+  float v = 0.f;
+  if (out_ok)   // (a tile without any adapter row wrote no partial products)
+    for (int ks = 0; ks < a.ksplit; ++ks) v += a.part[((size_t)(z * a.ksplit + ks) * a.rows) * a.r + o];
+  if (a.out_f32[z] && out_ok && orow >= a.f32_lo && orow < a.f32_hi)
+    a.out_f32[z][(size_t)(orow - a.f32_lo) * a.r + rank] = v;
+  if (a.out_ext[z]) a.out_ext[z][o] = (bf16_t)(out_ok ? v * a.scale : 0.f);
 }
 
 // Bt[j][o] = B[o][j]
@@ -175,15 +195,24 @@ int32_t post(const char* what) {
 
 }  // namespace
 
-int32_t launch_lora_shrink_mfma(const LoraShrinkArgs& a, int n_mats, hipStream_t s) {
+int32_t launch_lora_shrink_mfma(const LoraShrinkArgs& a_in, int n_mats, hipStream_t s) {
+  LoraShrinkArgs a = a_in;
   if (a.rows == 0 || n_mats == 0) return FLEXCO_OK;
-  // wavefronts per block: the largest power of two <= 16 that cuts every K into whole groups of 4 MFMA steps
-  int nw = 16;
   for (int z = 0; z < n_mats; ++z)
-    while (nw > 1 && a.K[z] % (128 * nw) != 0) nw >>= 1;
+    if (a.K[z] % 128 != 0) return fail(FLEXCO_ESHAPE, "LoRA shrink: K = %d is not a multiple of 128", a.K[z]);
+  // K is cut into whole groups of 4 MFMA steps (128 columns), first over the wavefronts of a block (a
+  // power of two <= 16), and - long contractions with scratch at hand - over several blocks per row tile,
+  // so that more than rows / 16 CUs pull the operands in
+  int kmin = a.K[0], kmax = a.K[0];
+  for (int z = 1; z < n_mats; ++z) { kmin = a.K[z] < kmin ? a.K[z] : kmin; kmax = a.K[z] > kmax ? a.K[z] : kmax; }
+  a.ksplit = 1;
+  if (a.part && kmin == kmax && kmax >= 8192)
+    for (int sp = LORA_SHRINK_SPLITS; sp > 1; --sp)
+      if (kmax % (128 * sp) == 0 && kmax / sp >= 1024) { a.ksplit = sp; break; }
+  int nw = a.ksplit > 1 ? 8 : 16;
   for (int z = 0; z < n_mats; ++z)
-    if (a.K[z] % (128 * nw) != 0) return fail(FLEXCO_ESHAPE, "LoRA shrink: K = %d is not a multiple of 128", a.K[z]);
-  const dim3 grid((a.rows + 15) / 16, n_mats), block(64 * nw);
+    while (nw > 1 && a.K[z] % (128 * nw * a.ksplit) != 0) nw >>= 1;
+  const dim3 grid((a.rows + 15) / 16, n_mats, a.ksplit), block(64 * nw);
   const int rt = (a.r + 15) / 16;
   switch (rt) {
     case 1: hipLaunchKernelGGL(lora_shrink_kernel<1>, grid, block, 0, s, a); break;
@@ -191,6 +220,9 @@ int32_t launch_lora_shrink_mfma(const LoraShrinkArgs& a, int n_mats, hipStream_t
     case 3: hipLaunchKernelGGL(lora_shrink_kernel<3>, grid, block, 0, s, a); break;
     default: hipLaunchKernelGGL(lora_shrink_kernel<4>, grid, block, 0, s, a); break;
   }
+  if (a.ksplit > 1)
+    hipLaunchKernelGGL(lora_shrink_finalize_kernel, dim3((unsigned)(((size_t)a.rows * a.r + 255) / 256), n_mats), dim3(256),
+                       0, s, a);
   return post("lora_shrink");
 }
 
