@@ -64,6 +64,9 @@ extern "C" {
 #define FLEXCO_PREFILL  1
 #define FLEXCO_FINETUNE 2
 
+/* Adapter ids of a batch are indices into the adapter array of the forward call: 0 .. 7. */
+#define FLEXCO_MAX_ADAPTERS 8
+
 typedef struct flexco_layer_cfg {
   int32_t hidden;        /* H                                             */
   int32_t n_q_heads;     /* nq                                            */
@@ -119,7 +122,8 @@ typedef struct flexco_batch_desc {
  * n_new; slot = pages[pos / page_size] * page_size + pos % page_size; block_table row r
  * = the first ceil(kv_len_r / page_size) pages of request r padded with -1 to max_pages
  * (>= 1) columns; ft_tok = ascending indices of finetune tokens; LoRA segments = maximal
- * runs of tokens with equal adapter id.
+ * runs of tokens with equal adapter id; adapter ids are -1 (base model only) or
+ * 0 .. FLEXCO_MAX_ADAPTERS - 1.
  *
  * The attention work list is a pure function of the batch: each request's tokens are cut
  * into column tiles of tile_tokens = max(1, 16 / (nq / nkv)) tokens (a decode request is
@@ -134,6 +138,9 @@ typedef struct flexco_maps {
   int32_t n_lora;                      /* tokens whose segment has adapter >= 0           */
   int32_t max_kv_len;
   int32_t blob_ints;                   /* int32 words used in the blob                    */
+  int32_t n_adapters;                  /* 1 + the largest adapter id of the batch (0: none) */
+  int32_t ft_adapter;                  /* adapter id of the finetune request (-1: none)   */
+  int32_t adapter_tok_off[FLEXCO_MAX_ADAPTERS + 1];   /* lora_tok[off[a] .. off[a+1]) = tokens of adapter a */
   const int32_t* tok_req;       /* [T]                                                    */
   const int32_t* tok_pos;       /* [T]                                                    */
   const int32_t* slot;          /* [T]                                                    */
@@ -144,7 +151,8 @@ typedef struct flexco_maps {
   const int32_t* ft_tok;        /* [n_ft]                                                 */
   const int32_t* seg_off;       /* [n_seg + 1]                                            */
   const int32_t* seg_adapter;   /* [n_seg]                                                */
-  const int32_t* lora_tok;      /* [n_lora] ascending indices of tokens with adapter >= 0 */
+  const int32_t* lora_tok;      /* [n_lora] tokens with adapter >= 0, grouped by adapter id
+                                   (ascending), ascending inside a group                  */
   const int32_t* tile_req;      /* [n_tiles]                                              */
   const int32_t* tile_tok0;     /* [n_tiles] first token of the tile                      */
   const int32_t* tile_ntok;     /* [n_tiles] tokens in the tile                           */
@@ -154,6 +162,7 @@ typedef struct flexco_maps {
   const int32_t* item_split;    /* [n_items]                                              */
   const int32_t* tok_tile;      /* [T] tile of each token                                 */
   const int32_t* tok_lora;      /* [T] index of the token in lora_tok, -1 without adapter */
+  const int32_t* tok_adapter;   /* [T] adapter id of the token's request                  */
 } flexco_maps;
 
 /* Paged KV cache of one layer (device, dtype of cfg).  Sec. 7, memory management.
@@ -236,6 +245,18 @@ int32_t flexco_layer_forward(const flexco_layer_cfg* cfg, const flexco_base_weig
                              const flexco_lora* lora, const flexco_maps* maps,
                              const void* x_in, void* x_out, const flexco_kv_pool* pool,
                              const flexco_ft_state* ft, void* ws, size_t ws_bytes, void* stream);
+
+/* The same forward pass with the requests of the batch served by several LoRA adapters (Sec. 6.2:
+ * the inference requests co-served with a finetuning job may belong to different PEFT models of
+ * the one backbone): a request with adapter id a >= 0 uses adapters[a], a < n_adapters <=
+ * FLEXCO_MAX_ADAPTERS; id -1 is the base model alone.  All adapters have cfg's rank, targets and
+ * scale.  The finetune window's rows use the adapter of its request, which is the one
+ * flexco_lora_bwd then trains.  (flexco_layer_forward applies its one adapter to every request
+ * with an id >= 0.) */
+int32_t flexco_layer_forward_multi(const flexco_layer_cfg* cfg, const flexco_base_weights* w,
+                                   const flexco_lora* adapters, int32_t n_adapters, const flexco_maps* maps,
+                                   const void* x_in, void* x_out, const flexco_kv_pool* pool,
+                                   const flexco_ft_state* ft, void* ws, size_t ws_bytes, void* stream);
 
 /* Mixed attention (Sec. 6.2): every token attends to positions 0..own position of its
  * own sequence through the block table; decode tokens, prefill chunks and finetune

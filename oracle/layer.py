@@ -32,14 +32,18 @@ def _cast(tree, dtype):
 
 
 def _proj(cfg, W, lora, target, wname, bname, xin, lora_rows):
-    """Base projection plus the bypass network on the rows that carry an adapter."""
+    """Base projection plus the bypass network on the rows that carry an adapter.
+    lora / lora_rows: one adapter and its row mask, or lists of both (several adapters in one
+    batch, each on its own rows)."""
     y = xin @ W[wname].T
     if bname is not None and bname in W:
         y = y + W[bname]
-    if lora is not None and target in lora and lora_rows is not None and np.any(lora_rows):
-        A, B = lora[target]
-        y = y.copy()
-        y[lora_rows] += ops.lora_delta(xin[lora_rows], A, B, cfg.lora_scale)
+    pairs = zip(lora, lora_rows) if isinstance(lora, list) else [(lora, lora_rows)]
+    for lo, rows in pairs:
+        if lo is not None and target in lo and rows is not None and np.any(rows):
+            A, B = lo[target]
+            y = y.copy()
+            y[rows] += ops.lora_delta(xin[rows], A, B, cfg.lora_scale)
     return y
 
 
@@ -148,15 +152,23 @@ def layer_forward_mixed(cfg, W, lora, maps, x, pool, ft_states=None, dtype=np.fl
     """One forward iteration of the layer over a mixed token batch, through the
     caches.  maps: oracle.maps.build_maps output.  pool: KVPool (new K/V rows are
     appended at the tokens' slots).  ft_states: {seq_id: FtState}; rows of finetune
-    windows store Q and the pruned activation set there.  LoRA applies to the rows
-    whose segment has adapter >= 0."""
-    W, lora, x = _cast(W, dtype), (_cast(lora, dtype) if lora else None), np.asarray(x, dtype=dtype)
+    windows store Q and the pruned activation set there.  lora: one adapter {target: (A, B)},
+    applied to the rows whose segment has adapter >= 0; or, with several adapters served in one
+    batch (Sec. 6.2: the inference requests of a batch may belong to different PEFT models), a
+    list of adapters indexed by adapter id, each applied to the rows of its own requests."""
+    W, x = _cast(W, dtype), np.asarray(x, dtype=dtype)
     T = maps["T"]
     assert x.shape[0] == T
-    rows = np.zeros(T, dtype=bool)
-    for s in range(maps["n_seg"]):
-        if maps["seg_adapter"][s] >= 0:
-            rows[maps["seg_off"][s]:maps["seg_off"][s + 1]] = True
+    if isinstance(lora, list):
+        lora = [_cast(lo, dtype) if lo else None for lo in lora]
+        assert int(maps["tok_adapter"].max()) < len(lora)
+        rows = [maps["tok_adapter"] == a for a in range(len(lora))]
+    else:
+        lora = _cast(lora, dtype) if lora else None
+        rows = np.zeros(T, dtype=bool)
+        for s in range(maps["n_seg"]):
+            if maps["seg_adapter"][s] >= 0:
+                rows[maps["seg_off"][s]:maps["seg_off"][s + 1]] = True
     pos = maps["tok_pos"]
     h1 = ops.rmsnorm(x, W["g1"], cfg.rms_eps)
     q0 = _proj(cfg, W, lora, "q", "wq", "bq", h1, rows)

@@ -13,7 +13,8 @@ index arrays, so the conventions are fixed here:
   * block_table row r = the first ceil(kv_len_r / page_size) pages of the request's
     sequence, padded with -1 up to the longest row of the batch (at least 1 column)
   * ft_tok = ascending indices of the tokens whose request is a finetune window
-  * LoRA segments = maximal runs of consecutive tokens with equal adapter id
+  * LoRA segments = maximal runs of consecutive tokens with equal adapter id; tok_adapter = the
+    adapter id of each token's request (-1: base model only)
 
 All outputs are int32.  Invalid descriptions raise ValueError.
 """
@@ -83,7 +84,7 @@ def build_maps(requests, seq_pages, page_size, num_pages=None):
         "req_tok_off": i32(req_tok_off), "req_kv_len": i32(req_kv_len),
         "req_kind": i32(req_kind), "req_seq": i32(req_seq),
         "block_table": block_table, "ft_tok": i32(ft_tok),
-        "seg_off": i32(seg_off), "seg_adapter": i32(seg_adapter),
+        "seg_off": i32(seg_off), "seg_adapter": i32(seg_adapter), "tok_adapter": i32(tok_adapter),
     }
 
 

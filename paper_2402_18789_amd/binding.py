@@ -50,14 +50,16 @@ class BatchDesc(C.Structure):
 
 
 _MAP_SCALARS = ("T", "n_req", "n_ft", "n_seg", "max_pages", "page_size", "n_tiles", "n_items", "n_parts",
-                "tile_tokens", "kv_split_pages", "ft_req", "ft_tok0", "ft_pos0", "n_lora", "max_kv_len", "blob_ints")
+                "tile_tokens", "kv_split_pages", "ft_req", "ft_tok0", "ft_pos0", "n_lora", "max_kv_len", "blob_ints", "n_adapters", "ft_adapter")
 _MAP_ARRAYS = ("tok_req", "tok_pos", "slot", "req_tok_off", "req_kv_len", "req_kind", "block_table", "ft_tok",
                "seg_off", "seg_adapter", "lora_tok", "tile_req", "tile_tok0", "tile_ntok", "tile_nsplit",
-               "tile_part0", "item_tile", "item_split", "tok_tile", "tok_lora")
+               "tile_part0", "item_tile", "item_split", "tok_tile", "tok_lora", "tok_adapter")
+MAX_ADAPTERS = 8
 
 
 class Maps(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in _MAP_SCALARS] + [(n, C.c_void_p) for n in _MAP_ARRAYS]
+    _fields_ = [(n, C.c_int32) for n in _MAP_SCALARS] + [("adapter_tok_off", C.c_int32 * (MAX_ADAPTERS + 1))] + \
+               [(n, C.c_void_p) for n in _MAP_ARRAYS]
 
 
 class KVPool(C.Structure):
@@ -97,6 +99,8 @@ def _load():
         "flexco_maps_rebase": [P(Maps), vp, vp, P(Maps)],
         "flexco_workspace_bytes": [P(LayerCfg), i32, i32, i32, i32, P(sz)],
         "flexco_layer_forward": [P(LayerCfg), P(BaseWeights), P(Lora), P(Maps), vp, vp, P(KVPool), P(FtState), vp, sz, vp],
+        "flexco_layer_forward_multi": [P(LayerCfg), P(BaseWeights), P(Lora), i32, P(Maps), vp, vp, P(KVPool), P(FtState), vp,
+                                       sz, vp],
         "flexco_attention_mixed": [P(LayerCfg), P(Maps), vp, P(KVPool), vp, vp, vp, sz, vp],
         "flexco_lora_fwd": [vp, vp, i32, i32, i32, i32, f32, i32, P(vp), P(vp), i32, P(i32), P(i32), i32, vp, vp],
         "flexco_lora_bwd": [P(LayerCfg), P(BaseWeights), P(Lora), P(KVPool), vp, i32, P(FtState), i32, i32, vp, vp, vp, sz, vp],
@@ -124,7 +128,7 @@ def _load():
 
 _lib = _load()
 EXPORTS = ("flexco_last_error", "flexco_abi_version", "flexco_maps_blob_ints", "flexco_build_maps",
-           "flexco_maps_rebase", "flexco_workspace_bytes", "flexco_layer_forward", "flexco_attention_mixed",
+           "flexco_maps_rebase", "flexco_workspace_bytes", "flexco_layer_forward", "flexco_layer_forward_multi", "flexco_attention_mixed",
            "flexco_lora_fwd", "flexco_lora_bwd", "flexco_attention_window_bwd", "flexco_gemm",
            "flexco_kernel_timer_start", "flexco_kernel_timer_stop", "flexco_kernel_timer_sample", "flexco_probe_mfma", "flexco_probe_read",
            "flexco_latency_estimate", "flexco_sched_window", "flexco_sched_inference", "flexco_sched_advance",
@@ -205,8 +209,9 @@ def maps_to_numpy(m, blob):
             "req_kind": m.n_req, "block_table": m.n_req * m.max_pages, "ft_tok": m.n_ft, "seg_off": m.n_seg + 1,
             "seg_adapter": m.n_seg, "lora_tok": m.n_lora, "tile_req": m.n_tiles, "tile_tok0": m.n_tiles,
             "tile_ntok": m.n_tiles, "tile_nsplit": m.n_tiles, "tile_part0": m.n_tiles, "item_tile": m.n_items,
-            "item_split": m.n_items, "tok_tile": m.T, "tok_lora": m.T}
+            "item_split": m.n_items, "tok_tile": m.T, "tok_lora": m.T, "tok_adapter": m.T}
     out = {n: getattr(m, n) for n in _MAP_SCALARS}
+    out["adapter_tok_off"] = np.array(list(m.adapter_tok_off), dtype=np.int32)
     for n, ln in lens.items():
         off = (getattr(m, n) - base) // 4
         out[n] = blob[off:off + ln].copy()
@@ -228,6 +233,13 @@ def flexco_workspace_bytes(cfg, T_max, n_parts_max, win_max, kv_max):
 
 def _opt(struct):
     return C.byref(struct) if struct is not None else None
+
+
+def flexco_layer_forward_multi(cfg, w, adapters, maps, x_in, x_out, pool, ft, ws, ws_bytes, stream=None):
+    """adapters: sequence of Lora structs, indexed by adapter id"""
+    arr = (Lora * len(adapters))(*adapters)
+    _check(_lib.flexco_layer_forward_multi(C.byref(cfg), C.byref(w), arr, len(adapters), C.byref(maps), _ptr(x_in),
+                                           _ptr(x_out), C.byref(pool), _opt(ft), _ptr(ws), ws_bytes, _stream(stream)))
 
 
 def flexco_layer_forward(cfg, w, lora, maps, x_in, x_out, pool, ft, ws, ws_bytes, stream=None):

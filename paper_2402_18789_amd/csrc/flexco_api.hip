@@ -121,8 +121,10 @@ struct Carver {
 void target_dims(const flexco_layer_cfg& c, int t, int* in, int* out);
 
 // scratch of the bf16 LoRA path for `rows` token rows, one slot per target
+constexpr int FUSED_ADAPTERS = 4;   // adapters of one batch the matrix-core LoRA path folds into a projection
+constexpr int PART_SLOTS = 4;       // products of one shrink launch that may be cut over several blocks
 struct LoraWs {
-  bf16_t* ext[LORA_MATS];     // scaled bf16 [rows, r] operand of the GEMM extension
+  bf16_t* ext[LORA_MATS];     // scaled bf16 [rows, r] operands of the GEMM extension (forward: one per adapter)
   float* part;                // partial products of a shrink cut over several blocks
   // backward only
   float* u[LORA_MATS];        // [rows, r]
@@ -137,8 +139,8 @@ void carve_lora(const flexco_layer_cfg& c, int rows, bool backward, Carver& cv, 
     if (!(c.lora_targets >> t & 1)) continue;
     int in, out;
     target_dims(c, t, &in, &out);
-    w.ext[t] = (bf16_t*)cv.take(sizeof(bf16_t) * (size_t)rows * r);
-    if (!w.part) w.part = (float*)cv.take(sizeof(float) * LORA_SHRINK_SPLITS * 3 * (size_t)rows * r);   // <= 3 targets per launch
+    w.ext[t] = (bf16_t*)cv.take(sizeof(bf16_t) * (size_t)rows * r * (backward ? 1 : FUSED_ADAPTERS));
+    if (!w.part) w.part = (float*)cv.take(sizeof(float) * LORA_SHRINK_SPLITS * PART_SLOTS * (size_t)rows * r);
     if (!backward) continue;
     w.u[t] = (float*)cv.take(sizeof(float) * (size_t)rows * r);
     w.t[t] = (float*)cv.take(sizeof(float) * (size_t)rows * r);
@@ -296,15 +298,15 @@ inline char* boff(void* p, size_t elems, size_t e) { return (char*)p + elems * e
 inline const char* boff(const void* p, size_t elems, size_t e) { return (const char*)p + elems * e; }
 inline bool has_target(const flexco_layer_cfg& c, int t) { return (c.lora_targets >> t & 1) != 0; }
 
-// unfused fallback: y[lora rows, col0 : col0 + out] += scale (x[lora rows] A^T) B^T
-int32_t lora_apply(const flexco_layer_cfg& c, const flexco_lora* l, int t, const flexco_maps& m, const void* x,
+// unfused fallback: y[rows, col0 : col0 + out] += scale (x[rows] A^T) B^T for the n rows listed in row_idx
+int32_t lora_apply(const flexco_layer_cfg& c, const flexco_lora* l, int t, const int32_t* row_idx, int n, const void* x,
                    size_t ldx, void* y, size_t ldy, size_t col0, float* u, hipStream_t s) {
-  if (!has_target(c, t) || m.n_lora == 0) return FLEXCO_OK;
+  if (!has_target(c, t) || n == 0) return FLEXCO_OK;
   int in, out;
   target_dims(c, t, &in, &out);
-  FLEXCO_TRY(launch_lora_shrink(x, ldx, l->A[t], u, m.n_lora, in, c.lora_rank, c.dtype, m.lora_tok, s));
-  return launch_lora_expand(u, l->B[t], boff(y, col0, esize(c.dtype)), ldy, m.n_lora, out, c.lora_rank,
-                            c.lora_scale, c.dtype, m.lora_tok, s);
+  FLEXCO_TRY(launch_lora_shrink(x, ldx, l->A[t], u, n, in, c.lora_rank, c.dtype, row_idx, s));
+  return launch_lora_expand(u, l->B[t], boff(y, col0, esize(c.dtype)), ldy, n, out, c.lora_rank, c.lora_scale, c.dtype,
+                            row_idx, s);
 }
 
 // the bf16 LoRA path needs whole MFMA k-steps in the rank and in the contracted dimensions
@@ -325,44 +327,89 @@ int32_t check_saved_u(const flexco_layer_cfg& c, const flexco_ft_state* ft) {
   return FLEXCO_OK;
 }
 
+// The adapters of a forward call: ads[a] serves the requests with adapter id a; with any_id (one
+// adapter given) ads[0] serves every request with an id >= 0.
+struct Adapters {
+  const flexco_lora* ads;
+  int n;
+  bool any_id;
+};
+
 // One projection of the forward pass over all T tokens, with the LoRA bypass of up to three
 // targets that share its input (q/k/v, gate/up) folded in:
-//   y[:, col0_t : col1_t] = x W^T (+bias) (+res)  +  scale (x A_t^T) B_t^T on adapter rows.
-int32_t forward_projection(const flexco_layer_cfg& c, const flexco_lora* lora, const flexco_maps& m, const void* x,
+//   y[:, col0_t : col1_t] = x W^T (+bias) (+res)  +  scale (x A_t^T) B_t^T on adapter rows,
+// A_t, B_t those of each row's own adapter.
+int32_t forward_projection(const flexco_layer_cfg& c, const Adapters& ad, const flexco_maps& m, const void* x,
                            int K, const void* W, const void* bias, const void* res, size_t ldr, void* y, int N,
                            const int* targets, const int* col0, int n_targets, FwdWs& k,
                            const flexco_ft_state* ft, hipStream_t s) {
   int act[3], nact = 0;
   for (int i = 0; i < n_targets; ++i)
     if (m.n_lora > 0 && has_target(c, targets[i])) act[nact++] = i;
+  // adapters with rows in this batch
+  int used[FLEXCO_MAX_ADAPTERS], nused = 0;
+  if (ad.any_id) { if (m.n_lora > 0) used[nused++] = 0; }
+  else
+    for (int a = 0; a < ad.n; ++a)
+      if (m.adapter_tok_off[a + 1] > m.adapter_tok_off[a]) used[nused++] = a;
   const int T = m.T, dt = c.dtype, r = c.lora_rank;
-  if (nact > 0 && lora_mfma_ok(c, K)) {
+  if (nact > 0 && nused > 0 && nused <= FUSED_ADAPTERS && lora_mfma_ok(c, K)) {
     LoraShrinkArgs sa;
     GemmExt ext;
     memset(&sa, 0, sizeof(sa)); memset(&ext, 0, sizeof(ext));
-    // u_t = scale x A_t^T for every token row (zero rows where the token has no adapter)
-    sa.row_map = m.tok_lora; sa.rows = T; sa.r = r; sa.scale = c.lora_scale; sa.part = k.lw.part;
+    // u_{t,a} = scale x A_{t,a}^T for every token row (zero rows where the token is not served by adapter a)
+    sa.row_adapter = m.tok_adapter; sa.rows = T; sa.r = r; sa.scale = c.lora_scale;
+    sa.part = k.lw.part; sa.part_slots = PART_SLOTS;
     // the finetune window's rows of the unscaled product are kept for the backward pass (dB_t)
+    const int ft_ad = ad.any_id ? 0 : m.ft_adapter;
     const bool keep_u = ft && m.n_ft > 0 && ft->saved_u[targets[act[0]]] != nullptr;
     sa.f32_lo = m.ft_tok0; sa.f32_hi = keep_u ? m.ft_tok0 + m.n_ft : m.ft_tok0;
-    ext.n = nact; ext.r = r;
-    for (int z = 0; z < nact; ++z) {
-      const int t = targets[act[z]];
-      int in, out;
-      target_dims(c, t, &in, &out);
-      sa.X[z] = (const bf16_t*)x; sa.ldx[z] = K; sa.S[z] = (const bf16_t*)lora->A[t]; sa.lds[z] = K; sa.K[z] = K;
-      sa.out_f32[z] = keep_u ? ft->saved_u[t] + (size_t)m.ft_pos0 * r : nullptr; sa.out_ext[z] = k.lw.ext[t];
-      ext.col0[z] = col0[act[z]]; ext.col1[z] = col0[act[z]] + out;
-      ext.A2[z] = k.lw.ext[t]; ext.W2[z] = (const bf16_t*)lora->B[t]; ext.ldw2[z] = r;
-    }
-    LR(launch_lora_shrink_mfma(sa, nact, s));
+    ext.r = r;
+    int z = 0;
+    for (int ia = 0; ia < nact; ++ia)
+      for (int iu = 0; iu < nused; ++iu, ++z) {
+        const int t = targets[act[ia]], a = used[iu];
+        const flexco_lora& l = ad.ads[a];
+        int in, out;
+        target_dims(c, t, &in, &out);
+        bf16_t* ext_ta = k.lw.ext[t] + (size_t)iu * T * r;
+        sa.X[z] = (const bf16_t*)x; sa.ldx[z] = K; sa.S[z] = (const bf16_t*)l.A[t]; sa.lds[z] = K; sa.K[z] = K;
+        sa.want[z] = ad.any_id ? -1 : a;
+        sa.out_f32[z] = (keep_u && a == ft_ad) ? ft->saved_u[t] + (size_t)m.ft_pos0 * r : nullptr;
+        sa.out_ext[z] = ext_ta;
+        ext.col0[z] = col0[act[ia]]; ext.col1[z] = col0[act[ia]] + out;
+        ext.A2[z] = ext_ta; ext.W2[z] = (const bf16_t*)l.B[t]; ext.ldw2[z] = r;
+      }
+    ext.n = z;
+    LR(launch_lora_shrink_mfma(sa, z, s));
     int32_t rc = launch_gemm(x, W, y, bias, res, T, N, K, K, K, N, ldr, false, dt, s, &ext);
     if (rc != FLEXCO_EUNSUPPORTED) return rc;
-    clear_error();   // e.g. a target boundary inside a GEMM tile: run the bypass as separate kernels
+    clear_error();   // e.g. a target boundary inside a 32-column fragment: run the bypass as separate kernels
   }
   FLEXCO_TRY(launch_gemm(x, W, y, bias, res, T, N, K, K, K, N, ldr, false, dt, s));
-  for (int z = 0; z < nact; ++z)
-    LR(lora_apply(c, lora, targets[act[z]], m, x, K, y, N, col0[act[z]], k.u, s));
+  // more adapters than the folded path takes: the backward pass (which folds whenever it can) still
+  // expects the finetune rows' rank-r products where the state keeps them
+  if (nact > 0 && nused > FUSED_ADAPTERS && lora_mfma_ok(c, K) && ft && m.n_ft > 0 && ft->saved_u[targets[act[0]]]) {
+    LoraShrinkArgs sa;
+    memset(&sa, 0, sizeof(sa));
+    const int a = ad.any_id ? 0 : m.ft_adapter;
+    sa.row_adapter = m.tok_adapter; sa.rows = T; sa.r = r; sa.scale = 1.f;
+    sa.f32_lo = m.ft_tok0; sa.f32_hi = m.ft_tok0 + m.n_ft;
+    for (int z = 0; z < nact; ++z) {
+      const int t = targets[act[z]];
+      sa.X[z] = (const bf16_t*)x; sa.ldx[z] = K; sa.S[z] = (const bf16_t*)ad.ads[a].A[t]; sa.lds[z] = K; sa.K[z] = K;
+      sa.want[z] = ad.any_id ? -1 : a;
+      sa.out_f32[z] = ft->saved_u[t] + (size_t)m.ft_pos0 * r;
+    }
+    LR(launch_lora_shrink_mfma(sa, nact, s));
+  }
+  for (int ia = 0; ia < nact; ++ia)
+    for (int iu = 0; iu < nused; ++iu) {
+      const int a = used[iu];
+      const int32_t* rows = ad.any_id ? m.lora_tok : m.lora_tok + m.adapter_tok_off[a];
+      const int n = ad.any_id ? m.n_lora : m.adapter_tok_off[a + 1] - m.adapter_tok_off[a];
+      LR(lora_apply(c, &ad.ads[a], targets[act[ia]], rows, n, x, K, y, N, col0[act[ia]], k.u, s));
+    }
   return FLEXCO_OK;
 }
 
@@ -440,7 +487,7 @@ int32_t backward_projection(const flexco_layer_cfg& c, const flexco_lora* lora, 
     LoraShrinkArgs st;
     GemmExt ext;
     memset(&st, 0, sizeof(st)); memset(&ext, 0, sizeof(ext));
-    st.rows = n; st.r = r; st.scale = c.lora_scale; st.f32_lo = 0; st.f32_hi = n; st.part = k.lw.part;
+    st.rows = n; st.r = r; st.scale = c.lora_scale; st.f32_lo = 0; st.f32_hi = n; st.part = k.lw.part; st.part_slots = PART_SLOTS;
     ext.n = g.nact; ext.r = r;
     for (int z = 0; z < g.nact; ++z) {
       const int t = g.targets[g.act[z]];
@@ -589,18 +636,22 @@ extern "C" int32_t flexco_lora_fwd(const void* x, void* y, int32_t T, int32_t in
   return FLEXCO_OK;
 }
 
-extern "C" int32_t flexco_layer_forward(const flexco_layer_cfg* cfg, const flexco_base_weights* w,
-                                        const flexco_lora* lora, const flexco_maps* maps, const void* x_in,
-                                        void* x_out, const flexco_kv_pool* pool, const flexco_ft_state* ft, void* ws,
-                                        size_t ws_bytes, void* stream) {
-  clear_error();
+static int32_t layer_forward_impl(const flexco_layer_cfg* cfg, const flexco_base_weights* w, const Adapters& ad,
+                                  const flexco_maps* maps, const void* x_in, void* x_out, const flexco_kv_pool* pool,
+                                  const flexco_ft_state* ft, void* ws, size_t ws_bytes, void* stream) {
   FLEXCO_TRY(check_cfg(cfg));
   FLEXCO_TRY(check_weights(w));
   FLEXCO_TRY(check_maps(*cfg, maps));
   FLEXCO_TRY(check_pool(*cfg, pool));
   const flexco_layer_cfg& c = *cfg;
   const flexco_maps& m = *maps;
-  if (m.n_lora > 0) FLEXCO_TRY(check_lora(c, lora, false));
+  if (m.n_lora > 0) {
+    FLEXCO_CHECK(ad.ads != nullptr && ad.n >= 1, FLEXCO_EINVAL, "the batch has adapter tokens but no adapter is given");
+    FLEXCO_CHECK(ad.any_id || m.n_adapters <= ad.n, FLEXCO_EINVAL, "the batch uses adapter id %d, %d adapters are given",
+                 m.n_adapters - 1, ad.n);
+    for (int a = 0; a < ad.n; ++a)
+      if (ad.any_id || m.adapter_tok_off[a + 1] > m.adapter_tok_off[a]) FLEXCO_TRY(check_lora(c, &ad.ads[a], false));
+  }
   FLEXCO_CHECK(x_in && x_out && ws, FLEXCO_EINVAL, "x_in, x_out or ws is NULL");
   FLEXCO_CHECK(x_in != x_out, FLEXCO_EINVAL, "x_out may not alias x_in");
   FLEXCO_CHECK(aligned16(x_in) && aligned16(x_out) && aligned16(ws), FLEXCO_EINVAL, "misaligned pointer");
@@ -610,6 +661,8 @@ extern "C" int32_t flexco_layer_forward(const flexco_layer_cfg* cfg, const flexc
     FLEXCO_CHECK(ft->q_cache && ft->saved_x && ft->saved_x2 && ft->saved_gate && ft->saved_up && ft->saved_attn &&
                      ft->lse, FLEXCO_EINVAL, "ft state has a NULL buffer");
     FLEXCO_TRY(check_saved_u(c, ft));
+    FLEXCO_CHECK(c.lora_targets == 0 || m.ft_adapter >= 0, FLEXCO_EINVAL,
+                 "the finetune request carries no adapter id (its window trains one)");
     FLEXCO_CHECK(m.ft_pos0 + m.n_ft <= ft->seq_len, FLEXCO_ESHAPE,
                  "finetune window [%d, %d) exceeds the state's seq_len %d", m.ft_pos0, m.ft_pos0 + m.n_ft, ft->seq_len);
   }
@@ -625,25 +678,25 @@ extern "C" int32_t flexco_layer_forward(const flexco_layer_cfg* cfg, const flexc
   EW(launch_rmsnorm(x_in, w->g1, k.h, T, H, c.rms_eps, dt, s));
   {
     const int tg[3] = {FLEXCO_T_Q, FLEXCO_T_K, FLEXCO_T_V}, c0[3] = {0, qd, qd + kd};
-    FLEXCO_TRY(forward_projection(c, lora, m, k.h, H, w->wqkv, w->bqkv, nullptr, 0, k.qkv, qkvd, tg, c0, 3, k, ft, s));
+    FLEXCO_TRY(forward_projection(c, ad, m, k.h, H, w->wqkv, w->bqkv, nullptr, 0, k.qkv, qkvd, tg, c0, 3, k, ft, s));
   }
   EW(launch_rope_append(c, k.qkv, m.tok_pos, m.slot, *pool, T, m.ft_tok0, m.n_ft, m.ft_pos0,
                         ft ? ft->q_cache : nullptr, s));
   FLEXCO_TRY(run_attention(c, m, k.qkv, qkvd, *pool, k.attn, qd, ft ? k.lse : nullptr, k.part_ml, k.part_acc, s));
   {
     const int tg[1] = {FLEXCO_T_O}, c0[1] = {0};
-    FLEXCO_TRY(forward_projection(c, lora, m, k.attn, qd, w->wo, nullptr, x_in, H, k.x2, H, tg, c0, 1, k, ft, s));
+    FLEXCO_TRY(forward_projection(c, ad, m, k.attn, qd, w->wo, nullptr, x_in, H, k.x2, H, tg, c0, 1, k, ft, s));
   }
   // MLP side
   EW(launch_rmsnorm(k.x2, w->g2, k.h, T, H, c.rms_eps, dt, s));
   {
     const int tg[2] = {FLEXCO_T_GATE, FLEXCO_T_UP}, c0[2] = {0, F};
-    FLEXCO_TRY(forward_projection(c, lora, m, k.h, H, w->wgu, nullptr, nullptr, 0, k.gu, 2 * F, tg, c0, 2, k, ft, s));
+    FLEXCO_TRY(forward_projection(c, ad, m, k.h, H, w->wgu, nullptr, nullptr, 0, k.gu, 2 * F, tg, c0, 2, k, ft, s));
   }
   EW(launch_swiglu(k.gu, k.act, T, F, dt, s));
   {
     const int tg[1] = {FLEXCO_T_DOWN}, c0[1] = {0};
-    FLEXCO_TRY(forward_projection(c, lora, m, k.act, F, w->wd, nullptr, k.x2, H, x_out, H, tg, c0, 1, k, ft, s));
+    FLEXCO_TRY(forward_projection(c, ad, m, k.act, F, w->wd, nullptr, k.x2, H, x_out, H, tg, c0, 1, k, ft, s));
   }
   // keep what graph pruning leaves alive for the finetune rows (Alg. 1), at their positions
   if (ft) {
@@ -666,6 +719,28 @@ extern "C" int32_t flexco_layer_forward(const flexco_layer_cfg* cfg, const flexc
     EW(launch_copy_rows_batch(cb, n, wb, s));
   }
   return FLEXCO_OK;
+}
+
+extern "C" int32_t flexco_layer_forward(const flexco_layer_cfg* cfg, const flexco_base_weights* w,
+                                        const flexco_lora* lora, const flexco_maps* maps, const void* x_in,
+                                        void* x_out, const flexco_kv_pool* pool, const flexco_ft_state* ft, void* ws,
+                                        size_t ws_bytes, void* stream) {
+  clear_error();
+  const Adapters ad{lora, lora ? 1 : 0, true};
+  return layer_forward_impl(cfg, w, ad, maps, x_in, x_out, pool, ft, ws, ws_bytes, stream);
+}
+
+extern "C" int32_t flexco_layer_forward_multi(const flexco_layer_cfg* cfg, const flexco_base_weights* w,
+                                              const flexco_lora* adapters, int32_t n_adapters,
+                                              const flexco_maps* maps, const void* x_in, void* x_out,
+                                              const flexco_kv_pool* pool, const flexco_ft_state* ft, void* ws,
+                                              size_t ws_bytes, void* stream) {
+  clear_error();
+  FLEXCO_CHECK(n_adapters >= 0 && n_adapters <= FLEXCO_MAX_ADAPTERS, FLEXCO_EINVAL, "n_adapters %d outside [0, %d]",
+               n_adapters, FLEXCO_MAX_ADAPTERS);
+  FLEXCO_CHECK(n_adapters == 0 || adapters != nullptr, FLEXCO_EINVAL, "adapters is NULL");
+  const Adapters ad{adapters, n_adapters, false};
+  return layer_forward_impl(cfg, w, ad, maps, x_in, x_out, pool, ft, ws, ws_bytes, stream);
 }
 
 static int32_t attention_window_bwd_impl(const flexco_layer_cfg& c, const flexco_kv_pool& pool,

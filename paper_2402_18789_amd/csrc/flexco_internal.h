@@ -12,19 +12,24 @@ namespace flexco {
 
 // ---- argument blocks of the bf16 LoRA kernels (up to 3 matrices per launch, grid.z) ----------
 constexpr int LORA_MATS = 7;   // matrices one LoRA launch can batch: one per target (q, k, v, o, gate, up, down)
+constexpr int LORA_SLOTS = 12;   // products of one shrink launch: (target, adapter) pairs or the 7 targets
 struct LoraShrinkArgs {     // out[z][row][rank] = sum_k X[z][row, k] S[z][rank, k]   (skinny product with a rank-r matrix)
-  const bf16_t* X[LORA_MATS]; size_t ldx[LORA_MATS];
-  const bf16_t* S[LORA_MATS]; size_t lds[LORA_MATS];
-  int K[LORA_MATS];                 // contracted width, per matrix
-  float* out_f32[LORA_MATS];        // or NULL: rows [f32_lo, f32_hi) are written, row m at out_f32[(m - f32_lo) * r ..]
-  bf16_t* out_ext[LORA_MATS];       // [rows, r], scaled by `scale`, or NULL (operand of the GEMM extension)
-  const int32_t* row_map;   // [rows] or NULL: rows with row_map[row] < 0 have no adapter, their out_ext rows are zero
+  const bf16_t* X[LORA_SLOTS]; size_t ldx[LORA_SLOTS];
+  const bf16_t* S[LORA_SLOTS]; size_t lds[LORA_SLOTS];
+  int K[LORA_SLOTS];                 // contracted width, per matrix
+  float* out_f32[LORA_SLOTS];        // or NULL: rows [f32_lo, f32_hi) are written, row m at out_f32[(m - f32_lo) * r ..]
+  bf16_t* out_ext[LORA_SLOTS];       // [rows, r], scaled by `scale`, or NULL (operand of the GEMM extension)
+  // [rows] or NULL: adapter id per row.  A row takes part in product z iff its id is >= 0 and, where
+  // want[z] >= 0, equals want[z]; the out_ext rows of the others are zero, their out_f32 rows untouched.
+  const int32_t* row_adapter;
+  int want[LORA_SLOTS];
   int rows, r;
   int f32_lo, f32_hi;
   float scale;
-  // optional scratch of LORA_SHRINK_SPLITS * n_mats * rows * r floats: long contractions are then cut
+  // optional scratch of LORA_SHRINK_SPLITS * part_slots * rows * r floats: long contractions are then cut
   // over several blocks per row tile, whose partial products a second kernel adds in block order
   float* part;
+  int part_slots;           // products the scratch is sized for
   int ksplit;               // set by the launcher
 };
 constexpr int LORA_SHRINK_SPLITS = 8;
@@ -40,12 +45,13 @@ struct LoraOuterArgs {
   float scale;
 };
 // rank-r extension of a projection GEMM (see gemm_mfma.hip)
+constexpr int GEMM_EXT_MAX = 12;   // (targets sharing a projection: <= 3) x (adapters on the matrix-core path: <= 4)
 struct GemmExt {
   int n, r;
-  int col0[3], col1[3];
-  const bf16_t* A2[3];
-  const bf16_t* W2[3];
-  size_t ldw2[3];
+  int col0[GEMM_EXT_MAX], col1[GEMM_EXT_MAX];
+  const bf16_t* A2[GEMM_EXT_MAX];
+  const bf16_t* W2[GEMM_EXT_MAX];
+  size_t ldw2[GEMM_EXT_MAX];
 };
 
 int32_t fail(int32_t code, const char* fmt, ...);

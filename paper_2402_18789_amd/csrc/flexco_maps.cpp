@@ -30,7 +30,8 @@ namespace {
 struct Built {
   std::vector<int32_t> tok_req, tok_pos, slot, req_tok_off, req_kv_len, req_kind, block_table, ft_tok,
       seg_off, seg_adapter, lora_tok, tile_req, tile_tok0, tile_ntok, tile_nsplit, tile_part0, item_tile,
-      item_split, tok_tile, tok_lora;
+      item_split, tok_tile, tok_lora, tok_adapter;
+  int32_t n_adapters = 0, adapter_tok_off[FLEXCO_MAX_ADAPTERS + 1] = {0};
   int32_t T = 0, n_ft = 0, n_seg = 0, max_pages = 1, n_parts = 0, ft_req = -1, max_kv_len = 0;
   int32_t tile_tokens = 1, split_pages = 64, ft_pos0 = 0;
 };
@@ -60,7 +61,8 @@ int32_t build(const flexco_batch_desc* d, int32_t page_size, int32_t num_pages, 
     FLEXCO_CHECK(d->kind[r] >= 0 && d->kind[r] <= 2, FLEXCO_EINVAL, "request %d: unknown kind %d", r, d->kind[r]);
     FLEXCO_CHECK(d->n_new[r] > 0, FLEXCO_EINVAL, "request %d: n_new must be positive (got %d)", r, d->n_new[r]);
     FLEXCO_CHECK(d->start_pos[r] >= 0, FLEXCO_EINVAL, "request %d: negative start_pos", r);
-    FLEXCO_CHECK(d->adapter[r] >= -1, FLEXCO_EINVAL, "request %d: adapter id %d", r, d->adapter[r]);
+    FLEXCO_CHECK(d->adapter[r] >= -1 && d->adapter[r] < FLEXCO_MAX_ADAPTERS, FLEXCO_EINVAL,
+                 "request %d: adapter id %d outside [-1, %d)", r, d->adapter[r], FLEXCO_MAX_ADAPTERS);
     const int64_t kv_len = (int64_t)d->start_pos[r] + d->n_new[r];
     FLEXCO_CHECK(kv_len < (1ll << 30), FLEXCO_EINVAL, "request %d: kv_len too large", r);
     const int32_t n_have = d->req_page_off[r + 1] - d->req_page_off[r];
@@ -112,8 +114,7 @@ int32_t build(const flexco_batch_desc* d, int32_t page_size, int32_t num_pages, 
       b.tok_req.push_back(r);
       b.tok_pos.push_back(pos);
       b.slot.push_back((int32_t)slot);
-      b.tok_lora.push_back(d->adapter[r] >= 0 ? (int32_t)b.lora_tok.size() : -1);
-      if (d->adapter[r] >= 0) b.lora_tok.push_back(t);
+      b.tok_adapter.push_back(d->adapter[r]);
       if (d->kind[r] == FLEXCO_FINETUNE) b.ft_tok.push_back(t);
     }
     b.req_tok_off.push_back((int32_t)b.tok_req.size());
@@ -180,6 +181,18 @@ int32_t build(const flexco_batch_desc* d, int32_t page_size, int32_t num_pages, 
     b.item_tile.swap(it);
     b.item_split.swap(is);
   }
+  // tokens with an adapter, grouped by adapter id: the rows each adapter's bypass network works on
+  b.tok_lora.assign(b.tok_adapter.size(), -1);
+  for (int a = 0; a < FLEXCO_MAX_ADAPTERS; ++a) {
+    b.adapter_tok_off[a] = (int32_t)b.lora_tok.size();
+    for (size_t t = 0; t < b.tok_adapter.size(); ++t)
+      if (b.tok_adapter[t] == a) {
+        b.tok_lora[t] = (int32_t)b.lora_tok.size();
+        b.lora_tok.push_back((int32_t)t);
+        b.n_adapters = a + 1;
+      }
+  }
+  b.adapter_tok_off[FLEXCO_MAX_ADAPTERS] = (int32_t)b.lora_tok.size();
   b.seg_off.push_back(b.T);
   b.n_seg = (int32_t)b.seg_adapter.size();
   b.n_ft = (int32_t)b.ft_tok.size();
@@ -207,7 +220,7 @@ size_t blob_need(const Built& b) {
   add(b.tok_req); add(b.tok_pos); add(b.slot); add(b.req_tok_off); add(b.req_kv_len); add(b.req_kind);
   add(b.block_table); add(b.ft_tok); add(b.seg_off); add(b.seg_adapter); add(b.lora_tok); add(b.tile_req);
   add(b.tile_tok0); add(b.tile_ntok); add(b.tile_nsplit); add(b.tile_part0); add(b.item_tile);
-  add(b.item_split); add(b.tok_tile); add(b.tok_lora);
+  add(b.item_split); add(b.tok_tile); add(b.tok_lora); add(b.tok_adapter);
   return n;
 }
 
@@ -255,13 +268,16 @@ extern "C" int32_t flexco_build_maps(const flexco_batch_desc* desc, int32_t page
   m.ft_req = b.ft_req; m.max_kv_len = b.max_kv_len;
   m.ft_tok0 = b.ft_req >= 0 ? b.req_tok_off[b.ft_req] : 0; m.ft_pos0 = b.ft_pos0;
   m.n_lora = (int32_t)b.lora_tok.size();
+  m.n_adapters = b.n_adapters;
+  m.ft_adapter = b.ft_req >= 0 ? desc->adapter[b.ft_req] : -1;
+  memcpy(m.adapter_tok_off, b.adapter_tok_off, sizeof(m.adapter_tok_off));
   m.tok_req = w.put(b.tok_req); m.tok_pos = w.put(b.tok_pos); m.slot = w.put(b.slot);
   m.req_tok_off = w.put(b.req_tok_off); m.req_kv_len = w.put(b.req_kv_len); m.req_kind = w.put(b.req_kind);
   m.block_table = w.put(b.block_table); m.ft_tok = w.put(b.ft_tok); m.seg_off = w.put(b.seg_off);
   m.seg_adapter = w.put(b.seg_adapter); m.lora_tok = w.put(b.lora_tok); m.tile_req = w.put(b.tile_req);
   m.tile_tok0 = w.put(b.tile_tok0); m.tile_ntok = w.put(b.tile_ntok); m.tile_nsplit = w.put(b.tile_nsplit);
   m.tile_part0 = w.put(b.tile_part0); m.item_tile = w.put(b.item_tile); m.item_split = w.put(b.item_split);
-  m.tok_tile = w.put(b.tok_tile); m.tok_lora = w.put(b.tok_lora);
+  m.tok_tile = w.put(b.tok_tile); m.tok_lora = w.put(b.tok_lora); m.tok_adapter = w.put(b.tok_adapter);
   FLEXCO_CHECK(w.ok, FLEXCO_EWORKSPACE, "blob too small");
   m.blob_ints = (int32_t)w.used;
   *out = m;
@@ -276,7 +292,7 @@ extern "C" int32_t flexco_maps_rebase(const flexco_maps* host_maps, const int32_
   const int32_t** fields[] = {&m.tok_req, &m.tok_pos, &m.slot, &m.req_tok_off, &m.req_kv_len, &m.req_kind,
                               &m.block_table, &m.ft_tok, &m.seg_off, &m.seg_adapter, &m.lora_tok, &m.tile_req,
                               &m.tile_tok0, &m.tile_ntok, &m.tile_nsplit, &m.tile_part0, &m.item_tile,
-                              &m.item_split, &m.tok_tile, &m.tok_lora};
+                              &m.item_split, &m.tok_tile, &m.tok_lora, &m.tok_adapter};
   for (auto f : fields) {
     FLEXCO_CHECK(*f >= host_blob && *f <= host_blob + m.blob_ints, FLEXCO_EINVAL,
                  "maps do not point into host_blob");

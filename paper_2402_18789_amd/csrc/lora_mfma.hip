@@ -30,7 +30,9 @@ __global__ __launch_bounds__(1024) void lora_shrink_kernel(LoraShrinkArgs a) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = blockDim.x >> 6;
   const int m = lane & 15, g = lane >> 4;
   const int row = tile * 16 + m;
-  const bool row_ok = row < a.rows && (!a.row_map || a.row_map[row] >= 0);
+  const int want = a.want[z];
+  const int row_ad = (row < a.rows && a.row_adapter) ? a.row_adapter[row] : 0;
+  const bool row_ok = row < a.rows && row_ad >= 0 && (want < 0 || row_ad == want);
   // every wavefront looks at the same 16 rows, so this is the same for the whole block
   const bool any_row = __ballot(row_ok) != 0;
   if (!any_row) {   // a tile without adapter rows: only its zero rows of the GEMM operand are due
@@ -86,7 +88,8 @@ __global__ __launch_bounds__(1024) void lora_shrink_kernel(LoraShrinkArgs a) {
     const int ln = idx >> 2, e = idx & 3;
     const int orow = tile * 16 + 4 * (ln >> 4) + e;
     if (orow >= a.rows) continue;
-    const bool out_ok = !a.row_map || a.row_map[orow] >= 0;
+    const int o_ad = a.row_adapter ? a.row_adapter[orow] : 0;
+    const bool out_ok = o_ad >= 0 && (want < 0 || o_ad == want);
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
       const int rank = rt * 16 + (ln & 15);
@@ -112,7 +115,8 @@ __global__ __launch_bounds__(256) void lora_shrink_finalize_kernel(LoraShrinkArg
   const size_t o = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (o >= (size_t)a.rows * a.r) return;
   const int orow = (int)(o / a.r), rank = (int)(o % a.r);
-  const bool out_ok = !a.row_map || a.row_map[orow] >= 0;
+  const int o_ad = a.row_adapter ? a.row_adapter[orow] : 0;
+  const bool out_ok = o_ad >= 0 && (a.want[z] < 0 || o_ad == a.want[z]);
   float v = 0.f;
   if (out_ok)   // (a tile without any adapter row wrote no partial products)
     for (int ks = 0; ks < a.ksplit; ++ks) v += a.part[((size_t)(z * a.ksplit + ks) * a.rows) * a.r + o];
@@ -206,7 +210,7 @@ int32_t launch_lora_shrink_mfma(const LoraShrinkArgs& a_in, int n_mats, hipStrea
   int kmin = a.K[0], kmax = a.K[0];
   for (int z = 1; z < n_mats; ++z) { kmin = a.K[z] < kmin ? a.K[z] : kmin; kmax = a.K[z] > kmax ? a.K[z] : kmax; }
   a.ksplit = 1;
-  if (a.part && kmin == kmax && kmax >= 8192)
+  if (a.part && n_mats <= a.part_slots && kmin == kmax && kmax >= 8192)
     for (int sp = LORA_SHRINK_SPLITS; sp > 1; --sp)
       if (kmax % (128 * sp) == 0 && kmax / sp >= 1024) { a.ksplit = sp; break; }
   int nw = a.ksplit > 1 ? 8 : 16;

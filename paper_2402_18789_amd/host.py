@@ -25,6 +25,25 @@ def _dev(a, dtype, device):
     return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device=device, dtype=dtype).contiguous()
 
 
+class DeviceLora:
+    """One LoRA adapter and its gradient buffers on the GPU.  lora: {target: (A [in, r], B [r, out])} in the
+    paper's orientation (stored transposed: A [r, in], B [out, r])."""
+
+    def __init__(self, cfg, lora, device="cuda"):
+        dt = TORCH_DTYPE[cfg.dtype]
+        self.c = B.Lora()
+        self.A, self.Bm, self.dA, self.dB = {}, {}, {}, {}
+        for t in cfg.lora_targets:
+            i = B.TARGET_NAMES.index(t)
+            A, Bm = lora[t]
+            self.A[t] = _dev(np.ascontiguousarray(A.T), dt, device)      # [r, in]
+            self.Bm[t] = _dev(np.ascontiguousarray(Bm.T), dt, device)    # [out, r]
+            self.dA[t] = torch.zeros(self.A[t].shape, dtype=torch.float32, device=device)
+            self.dB[t] = torch.zeros(self.Bm[t].shape, dtype=torch.float32, device=device)
+            self.c.A[i], self.c.B[i] = self.A[t].data_ptr(), self.Bm[t].data_ptr()
+            self.c.dA[i], self.c.dB[i] = self.dA[t].data_ptr(), self.dB[t].data_ptr()
+
+
 class DeviceLayer:
     """Frozen weights (+ one LoRA adapter and its gradient buffers) of one layer on the GPU.
     W: {wq, wk, wv, wo, wg, wu, wd [out, in], g1, g2, optional bq, bk, bv};
@@ -50,16 +69,8 @@ class DeviceLayer:
         self.lora = None
         self.A, self.Bm, self.dA, self.dB = {}, {}, {}, {}
         if lora and cfg.lora_targets:
-            self.lora = B.Lora()
-            for t in cfg.lora_targets:
-                i = B.TARGET_NAMES.index(t)
-                A, Bm = lora[t]
-                self.A[t] = _dev(np.ascontiguousarray(A.T), dt, device)      # [r, in]
-                self.Bm[t] = _dev(np.ascontiguousarray(Bm.T), dt, device)    # [out, r]
-                self.dA[t] = torch.zeros(self.A[t].shape, dtype=torch.float32, device=device)
-                self.dB[t] = torch.zeros(self.Bm[t].shape, dtype=torch.float32, device=device)
-                self.lora.A[i], self.lora.B[i] = self.A[t].data_ptr(), self.Bm[t].data_ptr()
-                self.lora.dA[i], self.lora.dB[i] = self.dA[t].data_ptr(), self.dB[t].data_ptr()
+            dl = DeviceLora(cfg, lora, device)
+            self.lora, self.A, self.Bm, self.dA, self.dB = dl.c, dl.A, dl.Bm, dl.dA, dl.dB
 
     def zero_grads(self):
         for t in self.dA:

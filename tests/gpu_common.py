@@ -29,7 +29,9 @@ class Case:
     """One layer, one pool, at most one finetune sequence; both sides in lock step."""
 
     def __init__(self, cfg, batch, seed=0, layer=0, kv_split_pages=0, pool_dtype=np.float64, weights=None, lora=None,
-                 keep_u=True):
+                 keep_u=True, adapters=None):
+        """adapters: optional list of LoRA weight sets indexed by adapter id (several adapters served in one
+        batch); `lora` (default: adapter 0's seeded weights) is then adapters[ft adapter], the one trained."""
         self.cfg, self.seed, self.layer_id = cfg, seed, layer
         self.W = weights if weights is not None else gen.layer_weights(cfg, seed, layer)
         self.lora = lora if lora is not None else gen.lora_weights(cfg, seed, layer)
@@ -40,6 +42,16 @@ class Case:
         self.o_ft = {}
         # device state
         self.dev = HH.DeviceLayer(cfg, self.W, self.lora)
+        self.adapters_o, self.adapters_d, self._keep = None, None, []
+        if adapters is not None:
+            self.adapters_o, self.adapters_d = adapters, []
+            for lo in adapters:
+                if lo is self.lora:
+                    self.adapters_d.append(self.dev.lora)        # the trained adapter: gradients land in self.dev
+                else:
+                    dl = HH.DeviceLora(cfg, lo)
+                    self._keep.append(dl)
+                    self.adapters_d.append(dl.c)
         self.d_pool = HH.DevicePool(cfg, batch.num_pages)
         self.d_ft = {}
         for r in batch.requests:
@@ -70,14 +82,18 @@ class Case:
         y_d = torch.empty_like(x_d)
         ft_seq = [r.seq_id for r in batch.requests if r.kind == KIND_FINETUNE]
         ft_c = self.d_ft[ft_seq[0]].c if ft_seq else None
-        B.flexco_layer_forward(self.dev.c, self.dev.w, self.dev.lora, db.maps, x_d, y_d, self.d_pool.c, ft_c,
-                               ws.ptr, ws.bytes)
+        if self.adapters_d is not None:
+            B.flexco_layer_forward_multi(self.dev.c, self.dev.w, self.adapters_d, db.maps, x_d, y_d, self.d_pool.c, ft_c,
+                                         ws.ptr, ws.bytes)
+        else:
+            B.flexco_layer_forward(self.dev.c, self.dev.w, self.dev.lora, db.maps, x_d, y_d, self.d_pool.c, ft_c,
+                                   ws.ptr, ws.bytes)
         torch.cuda.synchronize()
         y_o = None
         if oracle:
             om = build_maps(batch.requests, batch.seq_pages, batch.page_size, batch.num_pages)
-            y_o = OL.layer_forward_mixed(cfg, self.W, self.lora, om, x, self.o_pool, self.o_ft,
-                                         return_all=return_all)
+            y_o = OL.layer_forward_mixed(cfg, self.W, self.adapters_o if self.adapters_o is not None else self.lora, om, x,
+                                         self.o_pool, self.o_ft, return_all=return_all)
         return to_np(y_d), y_o, db
 
     def backward_window(self, seq_id, win_start, win_len, dY, grads_o, need_dx=True):

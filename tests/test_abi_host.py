@@ -15,7 +15,7 @@ from workload import gen, CONFIGS
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 COMMON = ("tok_req", "tok_pos", "slot", "req_tok_off", "req_kv_len", "req_kind", "block_table", "ft_tok", "seg_off",
-          "seg_adapter")
+          "seg_adapter", "tok_adapter")
 
 
 def test_library_exports_every_declared_symbol():
@@ -58,7 +58,12 @@ def test_maps_bit_exact_vs_oracle(name, nq, nkv, split):
         assert cm[k] == om[k], k
     for k in COMMON:
         assert cm[k].dtype == np.int32 and np.array_equal(cm[k], om[k]), k
-    assert np.array_equal(cm["lora_tok"], np.nonzero(np.repeat(om["seg_adapter"], np.diff(om["seg_off"])) >= 0)[0])
+    # tokens with an adapter, grouped by adapter id; the offsets of the groups are host scalars
+    groups = [np.nonzero(om["tok_adapter"] == a)[0] for a in range(8)]
+    assert np.array_equal(cm["lora_tok"], np.concatenate(groups))
+    assert cm["adapter_tok_off"].tolist() == np.concatenate([[0], np.cumsum([len(g) for g in groups])]).tolist()
+    assert cm["n_adapters"] == int(om["tok_adapter"].max()) + 1
+    assert np.array_equal(cm["lora_tok"][cm["tok_lora"][om["tok_adapter"] >= 0]], np.nonzero(om["tok_adapter"] >= 0)[0])
     # the work list covers every (token, visible position) exactly once
     assert check_attention_cover(om, work_items(cm, batch.page_size))
     # tiles partition the tokens of each request; partial rows are numbered densely

@@ -205,13 +205,14 @@ def test_attention_window_bwd(cfg_name, win_start, win_len):
 # whole layer: forward iterations, then token-window backward
 # ------------------------------------------------------------------------------------------
 def run_layer_case(cfg, batch0, ft_window, prefill_chunk, bwd_windows, seed=0, split=0, need_dx=True, tol_qk=None,
-                   keep_u=True):
+                   keep_u=True, adapters=None, ft_adapter=0):
     """tol_qk: bound for the tensors that depend on the gradient through the softmax logits (dX, the K
     accumulator, dA/dB of q and k) when it differs from the general one (see the callers that pass it)."""
     report = []
     tol = TOL[cfg.dtype]
     tol_qk = tol if tol_qk is None else tol_qk
-    case = Case(cfg, batch0, seed=seed, kv_split_pages=split, keep_u=keep_u)
+    case = Case(cfg, batch0, seed=seed, kv_split_pages=split, keep_u=keep_u, adapters=adapters,
+                lora=adapters[ft_adapter] if adapters is not None else None)
     batch, it = batch0, 0
     ft_seq = [r.seq_id for r in batch0.requests if r.kind == KIND_FINETUNE][0]
     L = batch0.seq_capacity[ft_seq]
@@ -305,6 +306,49 @@ def test_layer_small_bf16_without_kept_rank_products():
     say("layer small bf16, saved_u = NULL")
     b = gen.batch_scaled(9, 5, 3, 300, [(0, 40, 40)], [(0, 100, 260)])
     run_layer_case(SMALL_BF16, b, ft_window=160, prefill_chunk=70, bwd_windows=[60, 200], seed=9, keep_u=False)
+
+
+# Several adapters served in one batch (Sec. 6.2): decode and prefill requests under adapters 1, 2, 3 and
+# under none, the finetune sequence under the adapter being trained; then that adapter's backward pass.
+@pytest.mark.parametrize("name,n_adapters,ft_adapter", [("c1", 3, 0), ("small_bf16", 4, 2), ("small_bf16", 6, 0)])
+def test_layer_with_several_adapters_in_one_batch(name, n_adapters, ft_adapter):
+    say(f"layer {name}, {n_adapters} adapters in one batch, finetune on adapter {ft_adapter}")
+    if name == "c1":
+        cfg = C1
+        b = gen.mixed_batch(16, 21, decode_ctx=(16, 32, 48, 64, 7, 20), prefill=[(0, 32, 64), (5, 20, 40)],
+                            finetune=[(0, 32, 64)], extra_capacity=2, ft_adapter=ft_adapter)
+        kw = dict(ft_window=32, prefill_chunk=32, bwd_windows=[40, 24])
+    else:
+        cfg = SMALL_BF16
+        b = gen.mixed_batch(16, 22, decode_ctx=tuple(range(30, 400, 37)), prefill=[(0, 130, 130), (256, 64, 400)],
+                            finetune=[(0, 100, 260)], extra_capacity=3, ft_adapter=ft_adapter)
+        kw = dict(ft_window=160, prefill_chunk=70, bwd_windows=[60, 200])
+    ids = [-1] + [a for a in range(n_adapters)]                    # inference requests cycle through none, 0, 1, ...
+    b = gen.with_adapters(b, ids)
+    adapters = [gen.lora_weights(cfg, 23, 0, adapter=a, b_std=0.02) for a in range(n_adapters)]
+    run_layer_case(cfg, b, seed=23, adapters=adapters, ft_adapter=ft_adapter, **kw)
+
+
+def test_several_adapters_error_paths():
+    cfg = C1
+    b = gen.with_adapters(gen.batch_c1(0), [2, -1])              # adapter id 2 is used
+    case = Case(cfg, b, seed=1)
+    db = HH.DeviceBatch(cfg, b.requests, b.seq_pages, b.num_pages)
+    assert db.host_maps.n_adapters == 3 and db.host_maps.ft_adapter == 0
+    ws = HH.Workspace(case.dev.c, db.host_maps.T, db.host_maps.n_parts)
+    x = torch.zeros((db.host_maps.T, cfg.hidden), device="cuda")
+    y = torch.empty_like(x)
+    ft = case.d_ft[[r.seq_id for r in b.requests if r.kind == KIND_FINETUNE][0]].c
+    with pytest.raises(B.FlexcoError):                            # two adapters given, id 2 asked for
+        B.flexco_layer_forward_multi(case.dev.c, case.dev.w, [case.dev.lora, case.dev.lora], db.maps, x, y, case.d_pool.c, ft,
+                                     ws.ptr, ws.bytes)
+    with pytest.raises(B.FlexcoError):                            # adapter 2 has a NULL matrix
+        B.flexco_layer_forward_multi(case.dev.c, case.dev.w, [case.dev.lora, case.dev.lora, B.Lora()], db.maps, x, y,
+                                     case.d_pool.c, ft, ws.ptr, ws.bytes)
+    # adapter 1 has no tokens in this batch: it is not looked at
+    B.flexco_layer_forward_multi(case.dev.c, case.dev.w, [case.dev.lora, B.Lora(), case.dev.lora], db.maps, x, y, case.d_pool.c,
+                                 ft, ws.ptr, ws.bytes)
+    torch.cuda.synchronize()
 
 
 # The 14B / 32B shapes on short sequences: outputs, saved activations and the gradients that do not pass

@@ -263,6 +263,40 @@ def test_mixed_batch_rows_equal_per_sequence_definition():
     assert np.array_equal(y_b[:7], y[:7]) and not np.array_equal(y_b[7:], y[7:])
 
 
+def test_several_adapters_in_one_batch_equal_each_sequence_with_its_own_adapter():
+    """Requests served by different adapters (and by none) in ONE batch: every request's rows equal the
+    whole-sequence definition of its sequence under its own adapter (Sec. 6.2, co-served PEFT models)."""
+    cfg = SMALL
+    W, lo0 = small_layer()
+    lo1 = {t: (A[::-1].copy() * 1.5, B[:, ::-1].copy() * -2.0) for t, (A, B) in lo0.items()}
+    lo2 = {t: (A * -0.7, B * 3.0) for t, (A, B) in lo0.items()}
+    adapters = [lo0, lo1, lo2]
+    ps = 4
+    lens = {0: 9, 1: 6, 2: 8, 3: 5}
+    xs = {s: seq_input(cfg, n, seed=30 + s) for s, n in lens.items()}
+    pages = {0: [4, 1, 6], 1: [0, 5], 2: [3, 2], 3: [7, 8]}
+    pool = L.KVPool(9, ps, cfg.kv_dim)
+    # iteration 0: prefixes under each sequence's adapter (seq 0: adapter 1, seq 3: adapter 2)
+    m0 = build_maps([NS(kind=1, seq_id=0, start_pos=0, n_new=8, adapter=1),
+                     NS(kind=1, seq_id=3, start_pos=0, n_new=4, adapter=2),
+                     NS(kind=2, seq_id=2, start_pos=0, n_new=4, adapter=0)], pages, ps)
+    st = {2: L.FtState(cfg, 8)}
+    L.layer_forward_mixed(cfg, W, adapters, m0, np.concatenate([xs[0][:8], xs[3][:4], xs[2][:4]]), pool, st)
+    # iteration 1: decode of seq 0 (adapter 1), prefill of seq 1 (no adapter), decode of seq 3 (adapter 2),
+    # finetune window of seq 2 (adapter 0)
+    m1 = build_maps([NS(kind=0, seq_id=0, start_pos=8, n_new=1, adapter=1),
+                     NS(kind=1, seq_id=1, start_pos=0, n_new=6, adapter=-1),
+                     NS(kind=0, seq_id=3, start_pos=4, n_new=1, adapter=2),
+                     NS(kind=2, seq_id=2, start_pos=4, n_new=4, adapter=0)], pages, ps)
+    y = L.layer_forward_mixed(cfg, W, adapters, m1, np.concatenate([xs[0][8:], xs[1], xs[3][4:], xs[2][4:]]), pool, st)
+    assert rel_err(y[0:1], L.layer_forward_seq(cfg, W, lo1, xs[0])["y"][8:]) < 1e-12
+    assert rel_err(y[1:7], L.layer_forward_seq(cfg, W, None, xs[1])["y"]) < 1e-12
+    assert rel_err(y[7:8], L.layer_forward_seq(cfg, W, lo2, xs[3])["y"][4:]) < 1e-12
+    assert rel_err(y[8:], L.layer_forward_seq(cfg, W, lo0, xs[2])["y"][4:]) < 1e-12
+    # a wrong assignment is visible: seq 0 under adapter 2 differs
+    assert rel_err(y[0:1], L.layer_forward_seq(cfg, W, lo2, xs[0])["y"][8:]) > 1e-6
+
+
 def test_rope_makes_attention_shift_invariant():
     """Shifting every position of a sequence by a constant leaves the attention
     output unchanged (rotary embedding is relative)."""

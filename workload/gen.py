@@ -157,6 +157,14 @@ def mixed_batch(page_size, seed, decode_ctx=(), prefill=(), finetune=(), permute
     return Batch(reqs, pages, caps, num_pages, page_size)
 
 
+def with_adapters(batch: Batch, ids) -> Batch:
+    """The same batch with the inference requests served by different adapters: request i (finetune
+    requests aside) gets ids[i % len(ids)] (-1: base model only)."""
+    reqs = [r if r.kind == KIND_FINETUNE else Request(r.kind, r.seq_id, r.start_pos, r.n_new, int(ids[i % len(ids)]))
+            for i, r in enumerate(batch.requests)]
+    return Batch(reqs, batch.seq_pages, batch.seq_capacity, batch.num_pages, batch.page_size)
+
+
 def advance(batch: Batch, prefill_chunk=None, ft_window=None) -> Batch:
     """The next iteration of the same sequences: every decode request moves on one
     token; prefill / finetune requests continue with the given chunk / window
