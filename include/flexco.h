@@ -64,6 +64,9 @@ extern "C" {
 #define FLEXCO_PREFILL  1
 #define FLEXCO_FINETUNE 2
 
+/* Column tiles one attention work item carries at most (neighbouring tiles of one request). */
+#define FLEXCO_ATTN_ITEM_TILES 4
+
 /* Adapter ids of a batch are indices into the adapter array of the forward call: 0 .. 7. */
 #define FLEXCO_MAX_ADAPTERS 8
 
@@ -128,7 +131,10 @@ typedef struct flexco_batch_desc {
  * The attention work list is a pure function of the batch: each request's tokens are cut
  * into column tiles of tile_tokens = max(1, 16 / (nq / nkv)) tokens (a decode request is
  * one tile); a tile's visible key range [0, last position of the tile] is cut into splits
- * of kv_split_pages pages; one work item = (tile, split). */
+ * of kv_split_pages pages and has one partial-result row per split.  A work item = up to
+ * FLEXCO_ATTN_ITEM_TILES neighbouring tiles of one request x one split of the last of these
+ * tiles' key range (an earlier tile of the item whose own range ends before that split has no
+ * partial row for it).  Order of the items: see flexco_build_maps. */
 typedef struct flexco_maps {
   int32_t T, n_req, n_ft, n_seg, max_pages, page_size;
   int32_t n_tiles, n_items, n_parts;   /* n_parts = sum over tiles of their split count   */
@@ -158,11 +164,12 @@ typedef struct flexco_maps {
   const int32_t* tile_ntok;     /* [n_tiles] tokens in the tile                           */
   const int32_t* tile_nsplit;   /* [n_tiles]                                              */
   const int32_t* tile_part0;    /* [n_tiles] first partial-result row of the tile         */
-  const int32_t* item_tile;     /* [n_items] work items (tile, split), longest key range first */
-  const int32_t* item_split;    /* [n_items]                                              */
+  const int32_t* item_tile;     /* [n_items] first tile of the work item                  */
+  const int32_t* item_split;    /* [n_items] its key split                                */
   const int32_t* tok_tile;      /* [T] tile of each token                                 */
   const int32_t* tok_lora;      /* [T] index of the token in lora_tok, -1 without adapter */
   const int32_t* tok_adapter;   /* [T] adapter id of the token's request                  */
+  const int32_t* item_ntiles;   /* [n_items] tiles of the work item: item_tile .. + ntiles */
 } flexco_maps;
 
 /* Paged KV cache of one layer (device, dtype of cfg).  Sec. 7, memory management.

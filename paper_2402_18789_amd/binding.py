@@ -53,7 +53,7 @@ _MAP_SCALARS = ("T", "n_req", "n_ft", "n_seg", "max_pages", "page_size", "n_tile
                 "tile_tokens", "kv_split_pages", "ft_req", "ft_tok0", "ft_pos0", "n_lora", "max_kv_len", "blob_ints", "n_adapters", "ft_adapter")
 _MAP_ARRAYS = ("tok_req", "tok_pos", "slot", "req_tok_off", "req_kv_len", "req_kind", "block_table", "ft_tok",
                "seg_off", "seg_adapter", "lora_tok", "tile_req", "tile_tok0", "tile_ntok", "tile_nsplit",
-               "tile_part0", "item_tile", "item_split", "tok_tile", "tok_lora", "tok_adapter")
+               "tile_part0", "item_tile", "item_split", "tok_tile", "tok_lora", "tok_adapter", "item_ntiles")
 MAX_ADAPTERS = 8
 
 
@@ -209,7 +209,7 @@ def maps_to_numpy(m, blob):
             "req_kind": m.n_req, "block_table": m.n_req * m.max_pages, "ft_tok": m.n_ft, "seg_off": m.n_seg + 1,
             "seg_adapter": m.n_seg, "lora_tok": m.n_lora, "tile_req": m.n_tiles, "tile_tok0": m.n_tiles,
             "tile_ntok": m.n_tiles, "tile_nsplit": m.n_tiles, "tile_part0": m.n_tiles, "item_tile": m.n_items,
-            "item_split": m.n_items, "tok_tile": m.T, "tok_lora": m.T, "tok_adapter": m.T}
+            "item_split": m.n_items, "tok_tile": m.T, "tok_lora": m.T, "tok_adapter": m.T, "item_ntiles": m.n_items}
     out = {n: getattr(m, n) for n in _MAP_SCALARS}
     out["adapter_tok_off"] = np.array(list(m.adapter_tok_off), dtype=np.int32)
     for n, ln in lens.items():

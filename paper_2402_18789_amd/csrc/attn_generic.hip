@@ -24,7 +24,8 @@ __device__ inline float wmax(float v) {
 }
 
 struct AttnArgs {
-  const int32_t *tok_pos, *block_table, *tile_req, *tile_tok0, *tile_ntok, *tile_part0, *item_tile, *item_split;
+  const int32_t *tok_pos, *block_table, *tile_req, *tile_tok0, *tile_ntok, *tile_nsplit, *tile_part0, *item_tile,
+      *item_split, *item_ntiles;
   int max_pages, nq, nkv, d, ps, split_keys, cols_per_tile;
   float scale;
 };
@@ -38,8 +39,11 @@ __global__ __launch_bounds__(256) void attn_fwd_generic_kernel(AttnArgs a, const
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   float* qs = smem + wave * (a.d + a.split_keys);
   float* sc = qs + a.d;
+  // one block per tile of the work item that has this split (blockIdx.z = tile within the item)
   const int item = blockIdx.x, kvh = blockIdx.y;
-  const int tile = a.item_tile[item], split = a.item_split[item];
+  if ((int)blockIdx.z >= a.item_ntiles[item]) return;
+  const int tile = a.item_tile[item] + blockIdx.z, split = a.item_split[item];
+  if (split >= a.tile_nsplit[tile]) return;
   const int r = a.tile_req[tile], t0 = a.tile_tok0[tile], ntok = a.tile_ntok[tile];
   const int group = a.nq / a.nkv;
   const int part = a.tile_part0[tile] + split;
@@ -285,14 +289,15 @@ int32_t launch_attention_generic(const flexco_layer_cfg& c, const flexco_maps& m
                                  const flexco_kv_pool& pool, float* part_ml, float* part_acc, hipStream_t s) {
   AttnArgs a;
   a.tok_pos = m.tok_pos; a.block_table = m.block_table; a.tile_req = m.tile_req; a.tile_tok0 = m.tile_tok0;
-  a.tile_ntok = m.tile_ntok; a.tile_part0 = m.tile_part0; a.item_tile = m.item_tile; a.item_split = m.item_split;
+  a.tile_ntok = m.tile_ntok; a.tile_nsplit = m.tile_nsplit; a.tile_part0 = m.tile_part0; a.item_tile = m.item_tile;
+  a.item_split = m.item_split; a.item_ntiles = m.item_ntiles;
   a.max_pages = m.max_pages; a.nq = c.n_q_heads; a.nkv = c.n_kv_heads; a.d = c.head_dim; a.ps = c.page_size;
   a.split_keys = m.kv_split_pages * c.page_size;
   a.cols_per_tile = m.tile_tokens * (c.n_q_heads / c.n_kv_heads);
   a.scale = 1.0f / sqrtf((float)c.head_dim);
   const size_t shm = 4 * sizeof(float) * (size_t)(a.d + a.split_keys);
   if (shm > 64 * 1024) return fail(FLEXCO_EUNSUPPORTED, "kv_split_pages * page_size = %d keys is too large for the generic attention kernel", a.split_keys);
-  DISPATCH_T(c.dtype, hipLaunchKernelGGL((attn_fwd_generic_kernel<T>), dim3(m.n_items, c.n_kv_heads), dim3(256), shm,
+  DISPATCH_T(c.dtype, hipLaunchKernelGGL((attn_fwd_generic_kernel<T>), dim3(m.n_items, c.n_kv_heads, FLEXCO_ATTN_ITEM_TILES), dim3(256), shm,
                                          s, a, (const T*)q, ldq, (const T*)pool.k_pages, (const T*)pool.v_pages,
                                          part_ml, part_acc));
   return post_launch("attn_fwd_generic");

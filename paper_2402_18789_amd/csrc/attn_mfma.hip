@@ -31,13 +31,20 @@ namespace flexco {
 namespace {
 
 struct FwdArgs {
-  const int32_t *tok_pos, *block_table, *tile_req, *tile_tok0, *tile_ntok, *tile_part0, *item_tile, *item_split;
+  const int32_t *tok_pos, *block_table, *tile_req, *tile_tok0, *tile_ntok, *tile_nsplit, *tile_part0, *item_tile,
+      *item_split, *item_ntiles;
   int max_pages, nq, nkv, n_items, split_pages;
   float scale_log2;   // log2(e) / sqrt(d)
 };
 
 constexpr int D = 128, PS = 16;
+constexpr int NC = FLEXCO_ATTN_ITEM_TILES;   // column tiles one work item may carry
 
+// A work item carries 1 .. NC neighbouring column tiles of one request (a decode token: one).  The
+// wavefront loads every K/V page of the item's key range once and multiplies it against each tile in
+// turn: a chunk of 16 / group * NC tokens re-reads its prefix from the caches NC times less often
+// than tile by tile.  Each tile keeps its own running maximum, sum and accumulator and its own partial
+// row, so the merge kernel sees tiles as before.
 __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(FwdArgs a, const bf16_t* __restrict__ q, size_t ldq,
                                                             const bf16_t* __restrict__ kp,
                                                             const bf16_t* __restrict__ vp,
@@ -50,32 +57,41 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(FwdArgs a, const bf1
   const int item = unit / a.nkv;
   if (item >= a.n_items) return;
   const int kvh = unit % a.nkv;
-  const int tile = a.item_tile[item], split = a.item_split[item];
-  const int r = a.tile_req[tile], t0 = a.tile_tok0[tile], ntok = a.tile_ntok[tile];
+  const int tile0 = a.item_tile[item], split = a.item_split[item];
+  const int ntl = __builtin_amdgcn_readfirstlane(a.item_ntiles[item]);
+  const int r = a.tile_req[tile0];
   const int group = a.nq / a.nkv;
   const int c = lane & 15, g = lane >> 4;
-  const bool col_ok = c < ntok * group;
-  const int t_c = col_ok ? t0 + c / group : t0;
-  const int h_c = kvh * group + (col_ok ? c % group : 0);
-  const int pos_c = col_ok ? a.tok_pos[t_c] : -1;
-  const int last_pos = a.tok_pos[t0 + ntok - 1];
+  // the item's keys: up to the last position of its last tile
+  const int tl = tile0 + ntl - 1;
+  const int last_pos = a.tok_pos[a.tile_tok0[tl] + a.tile_ntok[tl] - 1];
   const int vis_pages = last_pos / PS + 1;
   const int pb = split * a.split_pages;
   const int pe = min(pb + a.split_pages, vis_pages);
-  const int32_t* bt = a.block_table + (size_t)r * a.max_pages;
 
-  // Q fragments: lane (col, g) holds d = 32 dc + 8 g .. + 8, dc = 0..3
-  bf16x8 qf[4];
-  {
-    const bf16_t* qr = q + (size_t)t_c * ldq + h_c * D + g * 8;
+  // per tile: Q fragments (lane (col, g) holds d = 32 dc + 8 g .. + 8, dc = 0..3), own position, state
+  bf16x8 qf[NC][4];
+  int pos_c[NC];
+  f32x4 o[NC][8];
+  float m[NC], l[NC];
 #pragma unroll
-    for (int dc = 0; dc < 4; ++dc) qf[dc] = *reinterpret_cast<const bf16x8*>(qr + dc * 32);
+  for (int cs = 0; cs < NC; ++cs) {
+    pos_c[cs] = -1;
+    m[cs] = -INFINITY;
+    l[cs] = 0.f;
+#pragma unroll
+    for (int mt = 0; mt < 8; ++mt) o[cs][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (cs < ntl) {
+      const int t0 = a.tile_tok0[tile0 + cs], ntok = a.tile_ntok[tile0 + cs];
+      const bool col_ok = c < ntok * group;
+      const int t_c = col_ok ? t0 + c / group : t0;
+      const int h_c = kvh * group + (col_ok ? c % group : 0);
+      pos_c[cs] = col_ok ? a.tok_pos[t_c] : -1;
+      const bf16_t* qr = q + (size_t)t_c * ldq + h_c * D + g * 8;
+#pragma unroll
+      for (int dc = 0; dc < 4; ++dc) qf[cs][dc] = *reinterpret_cast<const bf16x8*>(qr + dc * 32);
+    }
   }
-
-  f32x4 o[8];
-#pragma unroll
-  for (int mt = 0; mt < 8; ++mt) o[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-  float m = -INFINITY, l = 0.f;
 
   bf16x8 kf[2][4];     // [page of the pair][d chunk]
   bf16x4 vf[2][8];     // [page of the pair][d tile]
@@ -98,43 +114,9 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(FwdArgs a, const bf1
     }
   };
 
-  // one step = 32 keys (two pages) against the 16 columns, operands in (kf, vf)
+  // one step = 32 keys (two pages) against the columns of every tile, operands in (kf, vf)
   auto step = [&](int pp, bf16x8 (&kf)[2][4], bf16x4 (&vf)[2][8]) {
-    // ---- scores of 32 keys x 16 columns -------------------------------------------------
-    float s[8];
-#pragma unroll
-    for (int x = 0; x < 2; ++x) {
-      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int dc = 0; dc < 4; ++dc) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[x][dc], qf[dc], acc, 0, 0, 0);
-      const bool page_ok = pp + x < pe;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int kpos = (pp + x) * PS + 4 * g + j;
-        s[x * 4 + j] = (page_ok && kpos <= pos_c) ? acc[j] * a.scale_log2 : -INFINITY;
-      }
-    }
-    // ---- online softmax per column -------------------------------------------------------
-    float mx = s[0];
-#pragma unroll
-    for (int j = 1; j < 8; ++j) mx = fmaxf(mx, s[j]);
-    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m, mx);
-    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f(m - m_use);
-    float p[8], psum = 0.f;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      p[j] = __builtin_amdgcn_exp2f(s[j] - m_use);
-      psum += p[j];
-    }
-    l = l * alpha + psum;        // per-lane share of the column's sum; reduced at the end
-    m = m_new;
-    bf16x8 pf;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) pf[j] = (bf16_t)p[j];
-    // ---- clear V bits of slots past the tile's last position (may be unwritten) ----------
+    // ---- clear V bits of slots past the item's last position (may be unwritten) ----------
     if ((pp + 2) * PS > last_pos + 1) {
 #pragma unroll
       for (int x = 0; x < 2; ++x)
@@ -147,16 +129,54 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(FwdArgs a, const bf1
           }
         }
     }
-    // ---- O^T = alpha O^T + V^T P^T --------------------------------------------------------
 #pragma unroll
-    for (int mt = 0; mt < 8; ++mt) {
-      bf16x8 vfull;
+    for (int cs = 0; cs < NC; ++cs) {
+      if (cs >= ntl) break;                    // wavefront-uniform
+      // ---- scores of 32 keys x 16 columns -------------------------------------------------
+      float s[8];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) { vfull[j] = vf[0][mt][j]; vfull[4 + j] = vf[1][mt][j]; }
-      f32x4 acc = o[mt];
+      for (int x = 0; x < 2; ++x) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int j = 0; j < 4; ++j) acc[j] *= alpha;
-      o[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vfull, pf, acc, 0, 0, 0);
+        for (int dc = 0; dc < 4; ++dc) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[x][dc], qf[cs][dc], acc, 0, 0, 0);
+        const bool page_ok = pp + x < pe;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int kpos = (pp + x) * PS + 4 * g + j;
+          s[x * 4 + j] = (page_ok && kpos <= pos_c[cs]) ? acc[j] * a.scale_log2 : -INFINITY;
+        }
+      }
+      // ---- online softmax per column -------------------------------------------------------
+      float mx = s[0];
+#pragma unroll
+      for (int j = 1; j < 8; ++j) mx = fmaxf(mx, s[j]);
+      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m[cs], mx);
+      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f(m[cs] - m_use);
+      float p[8], psum = 0.f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        p[j] = __builtin_amdgcn_exp2f(s[j] - m_use);
+        psum += p[j];
+      }
+      l[cs] = l[cs] * alpha + psum;        // per-lane share of the column's sum; reduced at the end
+      m[cs] = m_new;
+      bf16x8 pf;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) pf[j] = (bf16_t)p[j];
+      // ---- O^T = alpha O^T + V^T P^T --------------------------------------------------------
+#pragma unroll
+      for (int mt = 0; mt < 8; ++mt) {
+        bf16x8 vfull;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { vfull[j] = vf[0][mt][j]; vfull[4 + j] = vf[1][mt][j]; }
+        f32x4 acc = o[cs][mt];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[j] *= alpha;
+        o[cs][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vfull, pf, acc, 0, 0, 0);
+      }
     }
   };
 
@@ -173,19 +193,26 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(FwdArgs a, const bf1
     load_pair(rel + 4 < npg ? rel + 4 : rel, kf, vf);
     if (rel + 2 < npg) step(pb + rel + 2, k1, v1);
   }
-  // ---- write the partial of this (tile, split, kv head) ----------------------------------
-  l += __shfl_xor(l, 16, 64);
-  l += __shfl_xor(l, 32, 64);
-  if (col_ok) {
-    const int cpt = (16 / group > 1 ? 16 / group : 1) * group;
-    const size_t idx = ((size_t)(a.tile_part0[tile] + split) * a.nkv + kvh) * cpt + c;
-    if (g == 0) {
-      part_ml[idx * 2] = m * 0.6931471805599453f;     // back to the natural-log domain
-      part_ml[idx * 2 + 1] = l;
-    }
-    float* pa = part_acc + idx * D + 4 * g;
+  // ---- write the partial of every (tile, split, kv head) that has this split -------------
+  const int cpt = (16 / group > 1 ? 16 / group : 1) * group;
 #pragma unroll
-    for (int mt = 0; mt < 8; ++mt) *reinterpret_cast<f32x4*>(pa + mt * 16) = o[mt];
+  for (int cs = 0; cs < NC; ++cs) {
+    if (cs >= ntl) break;
+    const int tile = tile0 + cs;
+    if (split >= a.tile_nsplit[tile]) continue;   // the tile's own keys end before this split
+    float lsum = l[cs];
+    lsum += __shfl_xor(lsum, 16, 64);
+    lsum += __shfl_xor(lsum, 32, 64);
+    if (c < a.tile_ntok[tile] * group) {
+      const size_t idx = ((size_t)(a.tile_part0[tile] + split) * a.nkv + kvh) * cpt + c;
+      if (g == 0) {
+        part_ml[idx * 2] = m[cs] * 0.6931471805599453f;     // back to the natural-log domain
+        part_ml[idx * 2 + 1] = lsum;
+      }
+      float* pa = part_acc + idx * D + 4 * g;
+#pragma unroll
+      for (int mt = 0; mt < 8; ++mt) *reinterpret_cast<f32x4*>(pa + mt * 16) = o[cs][mt];
+    }
   }
 }
 
@@ -199,7 +226,8 @@ int32_t launch_attention_mfma(const flexco_layer_cfg& c, const flexco_maps& m, c
     return FLEXCO_EUNSUPPORTED;
   FwdArgs a;
   a.tok_pos = m.tok_pos; a.block_table = m.block_table; a.tile_req = m.tile_req; a.tile_tok0 = m.tile_tok0;
-  a.tile_ntok = m.tile_ntok; a.tile_part0 = m.tile_part0; a.item_tile = m.item_tile; a.item_split = m.item_split;
+  a.tile_ntok = m.tile_ntok; a.tile_nsplit = m.tile_nsplit; a.tile_part0 = m.tile_part0; a.item_tile = m.item_tile;
+  a.item_split = m.item_split; a.item_ntiles = m.item_ntiles;
   a.max_pages = m.max_pages; a.nq = c.n_q_heads; a.nkv = c.n_kv_heads; a.n_items = m.n_items;
   a.split_pages = m.kv_split_pages;
   a.scale_log2 = 1.4426950408889634f / sqrtf((float)D);

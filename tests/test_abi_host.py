@@ -40,10 +40,11 @@ def c_maps(batch, nq, nkv, split=0):
 def work_items(cm, page_size):
     items = []
     for it in range(cm["n_items"]):
-        tile, split = cm["item_tile"][it], cm["item_split"][it]
-        t0, n = cm["tile_tok0"][tile], cm["tile_ntok"][tile]
+        tile, split, ntl = cm["item_tile"][it], cm["item_split"][it], cm["item_ntiles"][it]
+        last = tile + ntl - 1
+        t0, t1 = cm["tile_tok0"][tile], cm["tile_tok0"][last] + cm["tile_ntok"][last]
         k0 = split * cm["kv_split_pages"] * page_size
-        items.append((t0, t0 + n, k0, k0 + cm["kv_split_pages"] * page_size))
+        items.append((t0, t1, k0, k0 + cm["kv_split_pages"] * page_size))
     return items
 
 
@@ -68,7 +69,14 @@ def test_maps_bit_exact_vs_oracle(name, nq, nkv, split):
     assert check_attention_cover(om, work_items(cm, batch.page_size))
     # tiles partition the tokens of each request; partial rows are numbered densely
     assert np.array_equal(np.repeat(np.arange(cm["n_tiles"]), cm["tile_ntok"]), cm["tok_tile"])
-    assert cm["n_parts"] == cm["tile_nsplit"].sum() == cm["n_items"]
+    assert cm["n_parts"] == cm["tile_nsplit"].sum()
+    # an item = a run of 1..4 tiles of one request x one split of the run's last tile; the runs partition the tiles
+    runs = sorted(set(zip(cm["item_tile"].tolist(), cm["item_ntiles"].tolist())))
+    assert [t for t, n in runs] == np.concatenate([[0], np.cumsum([n for t, n in runs])[:-1]]).tolist()
+    assert sum(n for t, n in runs) == cm["n_tiles"] and all(1 <= n <= 4 for t, n in runs)
+    for t, n in runs:
+        assert len(set(cm["tile_req"][t:t + n].tolist())) == 1
+    assert cm["n_items"] == sum(cm["tile_nsplit"][t + n - 1] for t, n in runs)
     assert np.array_equal(cm["tile_part0"], np.concatenate([[0], np.cumsum(cm["tile_nsplit"])[:-1]]))
     assert cm["tile_tokens"] == max(1, 16 // (nq // nkv))
 
