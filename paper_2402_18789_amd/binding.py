@@ -20,7 +20,7 @@ FLEXCO_DECODE, FLEXCO_PREFILL, FLEXCO_FINETUNE = 0, 1, 2
 FLEXCO_REQ_WAITING, FLEXCO_REQ_RUNNING, FLEXCO_REQ_FINISHED = 0, 1, 2
 TARGET_NAMES = ("q", "k", "v", "o", "gate", "up", "down")
 N_TARGETS = 7
-ABI_VERSION = 2
+ABI_VERSION = 3
 
 
 class FlexcoError(RuntimeError):

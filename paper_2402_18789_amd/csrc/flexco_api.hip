@@ -277,7 +277,8 @@ int32_t check_maps(const flexco_layer_cfg& c, const flexco_maps* m) {
   FLEXCO_CHECK(m->tile_tokens == (16 / group > 1 ? 16 / group : 1), FLEXCO_ESHAPE,
                "maps were built for a different n_q_heads / n_kv_heads ratio");
   FLEXCO_CHECK(m->tok_req && m->tok_pos && m->slot && m->block_table && m->tile_req && m->item_tile && m->tok_tile &&
-                   m->tok_lora, FLEXCO_EINVAL, "maps hold a NULL array");
+                   m->tok_lora && m->tok_adapter && m->item_ntiles && m->item_split && m->tile_nsplit && m->tile_part0,
+               FLEXCO_EINVAL, "maps hold a NULL array");
   return FLEXCO_OK;
 }
 
