@@ -235,21 +235,27 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(BwdArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// kernel B: dK, dV.  grid (ceil(l / 64), nkv); wavefront w owns the page (16 keys) 4 b + w and
-// walks over the query heads of the kv group and the window's rows, 32 rows per step.
+// kernel B: dK, dV.  grid (ceil(l / 64), nkv), 8 wavefronts.  Wavefront w owns the page (16 keys)
+// 4 b + w % 4 and walks over the window's rows, 32 rows per step, for every second query head of the
+// kv group (w / 4 = 0: heads 0, 2, ..; 1: heads 1, 3, ..): the two halves of a block multiply different
+// heads at the same time and their sums are added in a fixed order at the end.  (The grid has one
+// block per CU or fewer, and a step is a chain of dependent LDS reads and MFMAs: the second half's
+// chains fill the first half's waits.)
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(BwdArgs a) {
-  __shared__ __attribute__((aligned(1024))) bf16_t qb0[2 * TILE16];
-  __shared__ __attribute__((aligned(1024))) bf16_t qb1[2 * TILE16];
-  __shared__ __attribute__((aligned(1024))) bf16_t ob0[2 * TILE16];
-  __shared__ __attribute__((aligned(1024))) bf16_t ob1[2 * TILE16];
-  __shared__ __attribute__((aligned(256))) float ld0[64];       // lse[32] | delta[32] of the step's rows
-  __shared__ __attribute__((aligned(256))) float ld1[64];
+__global__ __launch_bounds__(512) void attn_bwd_dkv_mfma_kernel(BwdArgs a) {
+  __shared__ __attribute__((aligned(1024))) bf16_t qb0[2][2 * TILE16];
+  __shared__ __attribute__((aligned(1024))) bf16_t qb1[2][2 * TILE16];
+  __shared__ __attribute__((aligned(1024))) bf16_t ob0[2][2 * TILE16];
+  __shared__ __attribute__((aligned(1024))) bf16_t ob1[2][2 * TILE16];
+  __shared__ __attribute__((aligned(256))) float ld0[2][64];    // lse[32] | delta[32] of the step's rows
+  __shared__ __attribute__((aligned(256))) float ld1[2][64];
+  __shared__ float red[4][8 * 4 * 64];                          // sums of the second half, one output at a time
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform: LDS bases of the loads stay scalar
+  const int pw = wave & 3, hg = wave >> 2;
   const int c = lane & 15, g = lane >> 4;
   const int kvh = blockIdx.y, group = a.nq / a.nkv;
-  const int pg = blockIdx.x * 4 + wave;
+  const int pg = blockIdx.x * 4 + pw;
   const int key0 = pg * PS;
   const bool page_ok = key0 < a.l;
   const size_t page = (size_t)a.pages[page_ok ? pg : (a.l - 1) / PS];
@@ -276,26 +282,27 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(BwdArgs a) {
   const int blk_key0 = blockIdx.x * 64;
   const int first_row = max(0, blk_key0 - a.w0) & ~31;       // first window row that sees the block's keys
   const int nrb = (a.s - first_row + 31) / 32;               // row blocks per head
-  const int nit = group * nrb;
+  const int nit = ((group + 1) / 2) * nrb;                   // steps: heads 2 (it / nrb) + hg
 
-  // ---- loads: 8 instructions per 32-row tile (4 rows each); wavefront w issues 2 w, 2 w + 1 of the
-  // Q tile and of the dO tile; wavefront 0 also brings in the rows' lse (lanes 0..31) and delta
-  // (lanes 32..63), 4 bytes per lane.  Rows past the window repeat its last row (masked later).
+  // ---- loads: 8 instructions per 32-row tile (4 rows each); wavefront (pw, hg) issues 2 pw, 2 pw + 1
+  // of its half's Q tile and dO tile; wavefront pw = 0 also brings in the rows' lse (lanes 0..31) and
+  // delta (lanes 32..63), 4 bytes per lane.  Rows past the window repeat its last row, a head past the
+  // group repeats the group's last head (both masked later).
   const int t_rin = lane >> 4, t_pc = lane & 15;
 #define FLEXCO_ISSUE_QO(qb_, ob_, ld_, it_)                                                           \
   {                                                                                                   \
-    const int h_ = kvh * group + (it_) / nrb;                                                         \
+    const int h_ = kvh * group + min(2 * ((it_) / nrb) + hg, group - 1);                              \
     const int r0_ = first_row + 32 * ((it_) % nrb);                                                   \
     _Pragma("unroll") for (int e = 0; e < 2; ++e) {                                                   \
-      const int row_ = 4 * (2 * wave + e) + t_rin;                                                    \
+      const int row_ = 4 * (2 * pw + e) + t_rin;                                                      \
       const size_t src_ = ((size_t)min(r0_ + row_, a.s - 1) * a.nq + h_) * D + ((t_pc ^ rsw(row_)) * 8); \
-      __builtin_amdgcn_global_load_lds(FLEXCO_GP(a.q + src_), FLEXCO_LP(qb_ + (2 * wave + e) * 4 * D), 16, 0, 0); \
-      __builtin_amdgcn_global_load_lds(FLEXCO_GP(a.dout + src_), FLEXCO_LP(ob_ + (2 * wave + e) * 4 * D), 16, 0, 0); \
+      __builtin_amdgcn_global_load_lds(FLEXCO_GP(a.q + src_), FLEXCO_LP(qb_[hg] + (2 * pw + e) * 4 * D), 16, 0, 0); \
+      __builtin_amdgcn_global_load_lds(FLEXCO_GP(a.dout + src_), FLEXCO_LP(ob_[hg] + (2 * pw + e) * 4 * D), 16, 0, 0); \
     }                                                                                                 \
-    if (wave == 0) {                                                                                  \
+    if (pw == 0) {                                                                                    \
       const size_t idx_ = (size_t)min(r0_ + (lane & 31), a.s - 1) * a.nq + h_;                        \
       const float* src_ = (lane < 32 ? a.lse : a.delta) + idx_;                                       \
-      __builtin_amdgcn_global_load_lds(FLEXCO_GP(src_), FLEXCO_LP(ld_), 4, 0, 0);                     \
+      __builtin_amdgcn_global_load_lds(FLEXCO_GP(src_), FLEXCO_LP(ld_[hg]), 4, 0, 0);                 \
     }                                                                                                 \
   }
 
@@ -308,14 +315,18 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(BwdArgs a) {
 #define FLEXCO_DKV_COMPUTE(qb_, ob_, ld_, it_)                                                        \
   {                                                                                                   \
     const int r0 = first_row + 32 * ((it_) % nrb);                                                    \
-    if (page_ok && key0 <= a.w0 + min(r0 + 31, a.s - 1)) { /* else no row of the step sees this page */ \
+    const bool head_ok = 2 * ((it_) / nrb) + hg < group;                                              \
+    if (head_ok && page_ok && key0 <= a.w0 + min(r0 + 31, a.s - 1)) { /* else nothing to add (uniform) */ \
+      const bf16_t* qt_ = qb_[hg];                                                                    \
+      const bf16_t* ot_ = ob_[hg];                                                                    \
+      const float* lt_ = ld_[hg];                                                                     \
       float p[8], ds[8];                                                                              \
       _Pragma("unroll") for (int x = 0; x < 2; ++x) {                                                 \
         f32x4 sacc = {0.f, 0.f, 0.f, 0.f}, pacc = {0.f, 0.f, 0.f, 0.f};                               \
         _Pragma("unroll") for (int dc = 0; dc < 4; ++dc) {                                            \
           const int off_ = x * TILE16 + row_off + (((dc * 4 + g) ^ row_sw) * 8);                      \
-          const bf16x8 qa = *reinterpret_cast<const bf16x8*>(qb_ + off_);                             \
-          const bf16x8 oa = *reinterpret_cast<const bf16x8*>(ob_ + off_);                             \
+          const bf16x8 qa = *reinterpret_cast<const bf16x8*>(qt_ + off_);                             \
+          const bf16x8 oa = *reinterpret_cast<const bf16x8*>(ot_ + off_);                             \
           sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa, kf[dc], sacc, 0, 0, 0);   /* S[row, key] */  \
           pacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(oa, vf[dc], pacc, 0, 0, 0);   /* dP[row, key] */ \
         }                                                                                             \
@@ -323,9 +334,9 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(BwdArgs a) {
           const int rl = x * 16 + 4 * g + j;            /* lane (key c, g) holds rows 4g..4g+3 of tile x */ \
           const int row = r0 + rl;                                                                    \
           const bool ok = key_ok && row < a.s && kpos <= a.w0 + row;                                  \
-          const float pv = __builtin_amdgcn_exp2f(sacc[j] * a.scale_log2 - ld_[rl] * LOG2E);          \
+          const float pv = __builtin_amdgcn_exp2f(sacc[j] * a.scale_log2 - lt_[rl] * LOG2E);          \
           p[x * 4 + j] = ok ? pv : 0.f;                                                               \
-          ds[x * 4 + j] = ok ? pv * (pacc[j] - ld_[32 + rl]) : 0.f;                                   \
+          ds[x * 4 + j] = ok ? pv * (pacc[j] - lt_[32 + rl]) : 0.f;                                   \
         }                                                                                             \
       }                                                                                               \
       bf16x8 pf, dsf;                                                                                 \
@@ -334,8 +345,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(BwdArgs a) {
       /* lane (d, g): rows 4g..4g+3 of both row tiles at column d */                                   \
       _Pragma("unroll") for (int mt = 0; mt < 8; ++mt) {                                              \
         const int off_ = tr_base + (((mt * 2 + tr_hi) ^ tr_sw) * 8);                                  \
-        const bf16x8 ot = tr_pair(ob_ + off_, ob_ + TILE16 + off_);                                   \
-        const bf16x8 qt = tr_pair(qb_ + off_, qb_ + TILE16 + off_);                                   \
+        const bf16x8 ot = tr_pair(ot_ + off_, ot_ + TILE16 + off_);                                   \
+        const bf16x8 qt = tr_pair(qt_ + off_, qt_ + TILE16 + off_);                                   \
         dv[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ot, pf, dv[mt], 0, 0, 0);                    \
         dk[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qt, dsf, dk[mt], 0, 0, 0);                   \
       }                                                                                               \
@@ -357,7 +368,28 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(BwdArgs a) {
   if (it < nit) FLEXCO_DKV_STEP(qb0, ob0, ld0, qb1, ob1, ld1, it)
   __builtin_amdgcn_s_waitcnt(0x0F70);   // nothing may land in LDS after the block ends
 
-  if (key_ok) {
+  // ---- the second half's sums join the first half's (dK, then dV), which adds them to the accumulator ----
+#pragma unroll
+  for (int which = 0; which < 2; ++which) {
+    __syncthreads();
+    if (hg == 1) {
+#pragma unroll
+      for (int mt = 0; mt < 8; ++mt)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) red[pw][(mt * 4 + j) * 64 + lane] = which == 0 ? dk[mt][j] : dv[mt][j];
+    }
+    __syncthreads();
+    if (hg == 0) {
+#pragma unroll
+      for (int mt = 0; mt < 8; ++mt)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float v = red[pw][(mt * 4 + j) * 64 + lane];
+          if (which == 0) dk[mt][j] += v; else dv[mt][j] += v;
+        }
+    }
+  }
+  if (hg == 0 && key_ok) {
     float* dkp = a.dk_accum + ((size_t)kpos * a.nkv + kvh) * D + 4 * g;
     float* dvp = a.dv_accum + ((size_t)kpos * a.nkv + kvh) * D + 4 * g;
 #pragma unroll
@@ -385,7 +417,7 @@ int32_t launch_attention_bwd_mfma(const flexco_layer_cfg& c, const flexco_kv_poo
   a.scale = 1.0f / sqrtf((float)D);
   a.scale_log2 = a.scale * LOG2E;
   hipLaunchKernelGGL(attn_bwd_dq_mfma_kernel, dim3((a.s + 31) / 32, a.nq), dim3(256), 0, s, a);
-  hipLaunchKernelGGL(attn_bwd_dkv_mfma_kernel, dim3((a.l + 63) / 64, a.nkv), dim3(256), 0, s, a);
+  hipLaunchKernelGGL(attn_bwd_dkv_mfma_kernel, dim3((a.l + 63) / 64, a.nkv), dim3(512), 0, s, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(FLEXCO_EHIP, "launch of attn_bwd_mfma failed: %s", hipGetErrorString(e));
   return FLEXCO_OK;
