@@ -75,15 +75,17 @@ __device__ inline bf16x8 tr_pair(const bf16_t* a, const bf16_t* b) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// kernel A: dQ.  grid (ceil(s / 32), nq).  Wavefront w: rows [32 b + 16 (w % 2), + 16), and of the
-// four pages a step stages, pages 2 (w / 2) and 2 (w / 2) + 1; the two key halves are added in a
-// fixed order at the end.
+// kernel A: dQ.  grid (ceil(s / 32), nq), 8 wavefronts.  Wavefront w: rows [32 b + 16 (w % 2), + 16), and
+// of the eight pages a step stages, pages 2 (w / 2) and 2 (w / 2) + 1; the four key quarters are added
+// in a fixed order at the end.  (The grid has one block per CU or fewer and a step is a chain of
+// dependent LDS reads and MFMAs: eight wavefronts halve the number of steps.)
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(BwdArgs a) {
-  __shared__ __attribute__((aligned(1024))) bf16_t kb0[4 * TILE16];
-  __shared__ __attribute__((aligned(1024))) bf16_t kb1[4 * TILE16];
-  __shared__ __attribute__((aligned(1024))) bf16_t vb0[4 * VPAGE];
-  __shared__ __attribute__((aligned(1024))) bf16_t vb1[4 * VPAGE];
+__global__ __launch_bounds__(512) void attn_bwd_dq_mfma_kernel(BwdArgs a) {
+  constexpr int SP = 8;                                          // pages a step stages, one per wavefront
+  __shared__ __attribute__((aligned(1024))) bf16_t kb0[SP * TILE16];
+  __shared__ __attribute__((aligned(1024))) bf16_t kb1[SP * TILE16];
+  __shared__ __attribute__((aligned(1024))) bf16_t vb0[SP * VPAGE];
+  __shared__ __attribute__((aligned(1024))) bf16_t vb1[SP * VPAGE];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform: LDS bases of the loads stay scalar
   const int c = lane & 15, g = lane >> 4;
@@ -97,7 +99,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(BwdArgs a) {
   const int wave_last_pos = a.w0 + min(i0 + 15, a.s - 1);      // may be < first key if the tile is empty
   const int blk_last_row = min(blockIdx.x * 32 + 31, a.s - 1);
   const int np = (a.w0 + blk_last_row) / PS + 1;                 // pages visible to the block
-  const int nit = (np + 3) / 4;
+  const int nit = (np + SP - 1) / SP;
   const int last_page = (a.l - 1) / PS, last_key = (a.l - 1) % PS;
 
   bf16x8 qf[4], dof[4];
@@ -129,7 +131,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(BwdArgs a) {
   int page_nxt;
 #define FLEXCO_ISSUE(kb_, vb_, it_, page_)                                                            \
   {                                                                                                   \
-    const int slot_ = 4 * (it_) + wave;                                                               \
+    const int slot_ = SP * (it_) + wave;                                                              \
     const size_t pb_ = ((size_t)(page_) * a.nkv + kvh);                                               \
     _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                                   \
       const int key_ = 4 * q + k_rin;                                                                 \
@@ -158,7 +160,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(BwdArgs a) {
   const int v_base = (((2 * (8 * g + s4) + (sc >> 1)) ^ ((g & 1) << 3)) * 8) + (sc & 1) * 4;
 
 #define FLEXCO_DQ_COMPUTE(kb_, vb_, it_)                                                              \
-  if ((4 * (it_) + 2 * kh) * PS <= wave_last_pos) { /* else: nothing visible to these rows (uniform) */ \
+  if ((SP * (it_) + 2 * kh) * PS <= wave_last_pos) { /* else: nothing visible to these rows (uniform) */ \
     float ds[8];                                                                                      \
     _Pragma("unroll") for (int xx = 0; xx < 2; ++xx) {                                                \
       const bf16_t* kt_ = kb_ + (2 * kh + xx) * TILE16;                                               \
@@ -172,7 +174,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(BwdArgs a) {
         pacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, dof[dc], pacc, 0, 0, 0);                   \
       }                                                                                               \
       _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                 \
-        const int kpos = (4 * (it_) + 2 * kh + xx) * PS + 4 * g + j;                                  \
+        const int kpos = (SP * (it_) + 2 * kh + xx) * PS + 4 * g + j;                                 \
         const bool ok = kpos <= pos_c;                                                                \
         const float p = __builtin_amdgcn_exp2f(sacc[j] * a.scale_log2 - lse2);                        \
         ds[xx * 4 + j] = ok ? p * (pacc[j] - delta) : 0.f;                                            \
@@ -195,7 +197,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(BwdArgs a) {
     FLEXCO_WAIT_ALL_BARRIER                                                                           \
     if ((it_) + 1 < nit) {                                                                            \
       FLEXCO_ISSUE(kn_, vn_, (it_) + 1, page_nxt)                                                     \
-      page_nxt = a.pages[min(4 * ((it_) + 2) + wave, last_page)];                                     \
+      page_nxt = a.pages[min(SP * ((it_) + 2) + wave, last_page)];                                    \
     }                                                                                                 \
     FLEXCO_DQ_COMPUTE(kb_, vb_, it_)                                                                  \
   }
@@ -203,7 +205,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(BwdArgs a) {
   {
     const int page0 = a.pages[min(wave, last_page)];
     FLEXCO_ISSUE(kb0, vb0, 0, page0)
-    page_nxt = a.pages[min(4 + wave, last_page)];
+    page_nxt = a.pages[min(SP + wave, last_page)];
   }
   int it = 0;
   for (; it + 1 < nit; it += 2) {
@@ -212,23 +214,32 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(BwdArgs a) {
   }
   if (it < nit) FLEXCO_DQ_STEP(kb0, vb0, kb1, vb1, it)
 
-  // ---- add the two key halves (kh = 0 first), scale, store --------------------------------------
-  __syncthreads();
+  // ---- add the four key quarters (kh = 0, 1, 2, 3 in this order), scale, store -------------------
   float* red = reinterpret_cast<float*>(kb0);                    // [2 rt][32][64 lanes] floats = 16 KB
-  if (kh == 1) {
+#pragma unroll 1
+  for (int src = 1; src < 4; ++src) {
+    __syncthreads();
+    if (kh == src) {
 #pragma unroll
-    for (int mt = 0; mt < 8; ++mt)
+      for (int mt = 0; mt < 8; ++mt)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) red[((rt * 8 + mt) * 4 + j) * 64 + lane] = dq[mt][j];
+        for (int j = 0; j < 4; ++j) red[((rt * 8 + mt) * 4 + j) * 64 + lane] = dq[mt][j];
+    }
+    __syncthreads();
+    if (kh == 0) {
+#pragma unroll
+      for (int mt = 0; mt < 8; ++mt)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) dq[mt][j] += red[((rt * 8 + mt) * 4 + j) * 64 + lane];
+    }
   }
-  __syncthreads();
   if (kh == 0 && row_ok) {
     bf16_t* out = a.dq + ((size_t)row_c * a.nq + h) * D + 4 * g;
 #pragma unroll
     for (int mt = 0; mt < 8; ++mt) {
       bf16x4 v;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) v[j] = (bf16_t)((dq[mt][j] + red[((rt * 8 + mt) * 4 + j) * 64 + lane]) * a.scale);
+      for (int j = 0; j < 4; ++j) v[j] = (bf16_t)(dq[mt][j] * a.scale);
       *reinterpret_cast<bf16x4*>(out + mt * 16) = v;
     }
   }
@@ -416,7 +427,7 @@ int32_t launch_attention_bwd_mfma(const flexco_layer_cfg& c, const flexco_kv_poo
   a.w0 = win_start; a.s = win_len; a.l = win_start + win_len; a.nq = c.n_q_heads; a.nkv = c.n_kv_heads;
   a.scale = 1.0f / sqrtf((float)D);
   a.scale_log2 = a.scale * LOG2E;
-  hipLaunchKernelGGL(attn_bwd_dq_mfma_kernel, dim3((a.s + 31) / 32, a.nq), dim3(256), 0, s, a);
+  hipLaunchKernelGGL(attn_bwd_dq_mfma_kernel, dim3((a.s + 31) / 32, a.nq), dim3(512), 0, s, a);
   hipLaunchKernelGGL(attn_bwd_dkv_mfma_kernel, dim3((a.l + 63) / 64, a.nkv), dim3(512), 0, s, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(FLEXCO_EHIP, "launch of attn_bwd_mfma failed: %s", hipGetErrorString(e));
