@@ -830,16 +830,27 @@ extern "C" int32_t flexco_lora_bwd(const flexco_layer_cfg* cfg, const flexco_bas
   outer.n = n; outer.r = c.lora_rank; outer.scale = c.lora_scale;
 
   // inputs of the adapted projections: rematerialised SwiGLU output (Alg. 1), the two norms
-  if (has_target(c, FLEXCO_T_DOWN)) EW(launch_swiglu_remat(gate_w, up_w, k.act, n, F, dt, s));
-  if (gu_lora) EW(launch_rmsnorm(x2_w, w->g2, k.hn2, n, H, c.rms_eps, dt, s));
-  if (qkv_lora) EW(launch_rmsnorm(x_w, w->g1, k.hn, n, H, c.rms_eps, dt, s));
+  // Where the state keeps the rank-r products of the forward pass, these inputs are only read by the
+  // dA products at the window's end, and the kernels that walk the same rows anyway (SwiGLU backward,
+  // the two norm backwards) write them as a by-product; otherwise they are needed up front.
+  bool late_inputs = true;
+  for (int t = 0; t < FLEXCO_N_TARGETS; ++t)
+    if (has_target(c, t) && !ft->saved_u[t]) late_inputs = false;
+  for (int gi = 0; gi < 4; ++gi)
+    if (grp[gi].nact > 0 && !grp[gi].fused) late_inputs = false;   // the unfused path multiplies by A up front
+  const bool act_late = late_inputs && has_target(c, FLEXCO_T_DOWN);
+  const bool hn2_late = late_inputs && gu_lora;
+  const bool hn_late = late_inputs && qkv_lora && dX != nullptr;
+  if (has_target(c, FLEXCO_T_DOWN) && !act_late) EW(launch_swiglu_remat(gate_w, up_w, k.act, n, F, dt, s));
+  if (gu_lora && !hn2_late) EW(launch_rmsnorm(x2_w, w->g2, k.hn2, n, H, c.rms_eps, dt, s));
+  if (qkv_lora && !hn_late) EW(launch_rmsnorm(x_w, w->g1, k.hn, n, H, c.rms_eps, dt, s));
   FLEXCO_TRY(lora_bwd_prepare(c, lora, n, grp, 4, k, ft, win_start, s));
 
   // ---- MLP side: down projection, SwiGLU, gate/up projections, second norm -------------
   FLEXCO_TRY(backward_projection(c, lora, n, dY, H, w->wd, k.dact, grp[0], k, outer, s));
-  EW(launch_swiglu_bwd(gate_w, up_w, k.dact, k.dgu, n, F, dt, s));
+  EW(launch_swiglu_bwd(gate_w, up_w, k.dact, k.dgu, n, F, dt, s, act_late ? k.act : nullptr));
   FLEXCO_TRY(backward_projection(c, lora, n, k.dgu, 2 * F, w->wgu, k.dh, grp[1], k, outer, s));
-  EW(launch_rmsnorm_bwd(x2_w, w->g2, k.dh, dY, k.dx2, n, H, c.rms_eps, dt, s));
+  EW(launch_rmsnorm_bwd(x2_w, w->g2, k.dh, dY, k.dx2, n, H, c.rms_eps, dt, s, hn2_late ? k.hn2 : nullptr));
   // ---- output projection ------------------------------------------------------------------
   FLEXCO_TRY(backward_projection(c, lora, n, k.dx2, H, w->wo, k.dattn, grp[2], k, outer, s));
   // ---- attention: dQ of the window, dK/dV of every cached row before its end (Sec. 6.1) ---
@@ -851,7 +862,7 @@ extern "C" int32_t flexco_lora_bwd(const flexco_layer_cfg* cfg, const flexco_bas
     FLEXCO_TRY(backward_projection(c, lora, n, k.dqkv, qkvd, w->wqkv, dX ? k.dh : nullptr, grp[3], k, outer, s));
   }
   // ---- every queued dA / dB product of the window in one launch ----------------------------
+  if (dX) EW(launch_rmsnorm_bwd(x_w, w->g1, k.dh, k.dx2, dX, n, H, c.rms_eps, dt, s, hn_late ? k.hn : nullptr));
   LR(launch_lora_outer_batch(outer, s));
-  if (dX) EW(launch_rmsnorm_bwd(x_w, w->g1, k.dh, k.dx2, dX, n, H, c.rms_eps, dt, s));
   return FLEXCO_OK;
 }

@@ -102,7 +102,7 @@ int32_t launch_lora_outer_bf16(const void* X, size_t ldx, const float* U, float*
 
 int32_t launch_rmsnorm(const void* x, const void* g, void* h, int T, int H, float eps, int dtype, hipStream_t s);
 int32_t launch_rmsnorm_bwd(const void* x, const void* g, const void* dh, const void* add, void* dx, int T, int H,
-                           float eps, int dtype, hipStream_t s);
+                           float eps, int dtype, hipStream_t s, void* hn = nullptr);
 int32_t launch_rope_append(const flexco_layer_cfg& c, void* qkv, const int32_t* tok_pos, const int32_t* slot,
                            const flexco_kv_pool& pool, int T, int ft_tok0, int n_ft, int ft_pos0, void* q_cache,
                            hipStream_t s);
@@ -110,7 +110,7 @@ int32_t launch_rope_bwd_pack(const flexco_layer_cfg& c, const void* dq, const fl
                              void* dqkv, int win_start, int n, hipStream_t s);
 int32_t launch_swiglu(const void* gu, void* act, int T, int F, int dtype, hipStream_t s);
 int32_t launch_swiglu_bwd(const void* gate, const void* up, const void* dact, void* dgu, int n, int F, int dtype,
-                          hipStream_t s);
+                          hipStream_t s, void* act = nullptr);
 int32_t launch_swiglu_remat(const void* gate, const void* up, void* act, int n, int F, int dtype, hipStream_t s);
 struct CopyRowsBatch {
   const char* src[8]; size_t ld_src[8];

@@ -72,11 +72,12 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const T* __restrict__ x, c
   }
 }
 
-// dx = rstd * (g * dh) - x * rstd^3 * mean(x * g * dh)  (+ add)
+// dx = rstd * (g * dh) - x * rstd^3 * mean(x * g * dh)  (+ add);  hn (optional) = x rstd g, the row
+// the forward norm produced (same arithmetic, same bits), for callers that need it again
 template <typename T, bool VEC>
 __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* __restrict__ x, const T* __restrict__ g,
                                                           const T* __restrict__ dh, const T* __restrict__ add,
-                                                          T* __restrict__ dx, int H, float eps) {
+                                                          T* __restrict__ dx, T* __restrict__ hn, int H, float eps) {
   __shared__ float red[4];
   constexpr int N = Vec<T>::N;
   const size_t row = blockIdx.x;
@@ -110,6 +111,12 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* __restrict__ 
       Vec<T>::load(g + i, gv);
       Vec<T>::load(dr + i, dv);
       if (add) Vec<T>::load(add + row * H + i, av);
+      if (hn) {
+        float hv[N];
+#pragma unroll
+        for (int j = 0; j < N; ++j) hv[j] = v[j] * rstd * gv[j];
+        Vec<T>::store(hn + row * H + i, hv);
+      }
 #pragma unroll
       for (int j = 0; j < N; ++j) {
         v[j] = rstd * gv[j] * dv[j] - v[j] * coef;
@@ -119,6 +126,7 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* __restrict__ 
     }
   } else {
     for (int i = threadIdx.x; i < H; i += 256) {
+      if (hn) st(hn + row * H + i, ld(xr + i) * rstd * ld(g + i));
       float v = rstd * ld(g + i) * ld(dr + i) - ld(xr + i) * coef;
       if (add) v += ld(add + row * H + i);
       st(dx + row * H + i, v);
@@ -244,7 +252,7 @@ __global__ __launch_bounds__(256) void swiglu_kernel(const T* __restrict__ gu, T
 template <typename T, bool VEC>
 __global__ __launch_bounds__(256) void swiglu_bwd_kernel(const T* __restrict__ gate, const T* __restrict__ up,
                                                          const T* __restrict__ dact, T* __restrict__ dgu,
-                                                         int F) {
+                                                         T* __restrict__ act, int F) {
   constexpr int N = VEC ? Vec<T>::N : 1;
   const size_t row = blockIdx.y;
   const int i = (blockIdx.x * 256 + threadIdx.x) * N;
@@ -261,6 +269,11 @@ __global__ __launch_bounds__(256) void swiglu_bwd_kernel(const T* __restrict__ g
   }
   if (VEC) { Vec<T>::store(dgu + row * 2 * F + i, dg); Vec<T>::store(dgu + row * 2 * F + F + i, du); }
   else { st(dgu + row * 2 * F + i, dg[0]); st(dgu + row * 2 * F + F + i, du[0]); }
+  if (act) {   // the rematerialised SwiGLU output (as swiglu_remat_kernel computes it), for callers that need it again
+#pragma unroll
+    for (int j = 0; j < N; ++j) g[j] = g[j] / (1.0f + __expf(-g[j])) * u[j];
+    if (VEC) Vec<T>::store(act + row * F + i, g); else st(act + row * F + i, g[0]);
+  }
 }
 
 // act = silu(gate) * up from the saved gate and up (rematerialisation, Alg. 1)
@@ -505,11 +518,11 @@ int32_t launch_rmsnorm(const void* x, const void* g, void* h, int T_, int H, flo
 }
 
 int32_t launch_rmsnorm_bwd(const void* x, const void* g, const void* dh, const void* add, void* dx, int T_, int H,
-                           float eps, int dtype, hipStream_t s) {
+                           float eps, int dtype, hipStream_t s, void* hn) {
   if (T_ == 0) return FLEXCO_OK;
-  const bool vec = vec_ok(dtype, H, {x, g, dh, add, dx});
+  const bool vec = vec_ok(dtype, H, {x, g, dh, add, dx, hn});
   DISPATCH_TV(dtype, vec, hipLaunchKernelGGL((rmsnorm_bwd_kernel<T, VEC>), dim3(T_), dim3(256), 0, s, (const T*)x,
-                                             (const T*)g, (const T*)dh, (const T*)add, (T*)dx, H, eps));
+                                             (const T*)g, (const T*)dh, (const T*)add, (T*)dx, (T*)hn, H, eps));
   return post_launch("rmsnorm_bwd");
 }
 
@@ -544,12 +557,12 @@ int32_t launch_swiglu(const void* gu, void* act, int T_, int F, int dtype, hipSt
 }
 
 int32_t launch_swiglu_bwd(const void* gate, const void* up, const void* dact, void* dgu, int n, int F, int dtype,
-                          hipStream_t s) {
+                          hipStream_t s, void* act) {
   if (n == 0) return FLEXCO_OK;
-  const bool vec = vec_ok(dtype, F, {gate, up, dact, dgu});
+  const bool vec = vec_ok(dtype, F, {gate, up, dact, dgu, act});
   const int per = 256 * (vec ? (dtype == FLEXCO_BF16 ? 8 : 4) : 1);
   DISPATCH_TV(dtype, vec, hipLaunchKernelGGL((swiglu_bwd_kernel<T, VEC>), dim3((F + per - 1) / per, n), dim3(256), 0,
-                                             s, (const T*)gate, (const T*)up, (const T*)dact, (T*)dgu, F));
+                                             s, (const T*)gate, (const T*)up, (const T*)dact, (T*)dgu, (T*)act, F));
   return post_launch("swiglu_bwd");
 }
 

@@ -134,8 +134,9 @@ __global__ __launch_bounds__(256) void lora_transpose_kernel(LoraTransposeArgs a
 }
 
 // G(i, j) += scale * sum_m X[m, i] U[m, j],  G element (i, j) at G[i * g_i + j * g_j]
-// Rows are taken in chunks of 128: the chunk's U rows are staged in LDS (broadcast reads), each
-// wavefront owns 32 rows of the chunk and issues their 32 loads of X together.
+// Rows are taken in chunks of 256: the chunk's U rows are staged in LDS (broadcast reads), each
+// wavefront owns 64 rows of the chunk and issues their 64 loads of X together (a 256-row window is one
+// chunk: one wait for U, one for X).
 template <int R>
 __global__ __launch_bounds__(256) void lora_outer_mfma_path_kernel(LoraOuterArgs a) {
   const int e = blockIdx.y;
@@ -146,8 +147,8 @@ __global__ __launch_bounds__(256) void lora_outer_mfma_path_kernel(LoraOuterArgs
   float* __restrict__ G = a.G[e];
   const size_t ldx = a.ldx[e], g_i = a.g_i[e], g_j = a.g_j[e];
   const float scale = a.scale;
-  extern __shared__ float smem[];   // us[128][R], later reused as red[3][64][R]
-  constexpr int CH = 128, RB = 32;
+  extern __shared__ float smem[];   // us[256][R], later reused as red[3][64][R]
+  constexpr int CH = 256, RB = 64;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int i = blockIdx.x * 64 + lane;
   const int ic = i < n_long ? i : n_long - 1;
@@ -181,11 +182,15 @@ __global__ __launch_bounds__(256) void lora_outer_mfma_path_kernel(LoraOuterArgs
   }
   __syncthreads();
   if (wave == 0 && i < n_long) {
+    // all loads of the accumulated gradient first, then the stores (one round trip, not R in a row)
+    float gv[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) gv[j] = j < r ? G[(size_t)i * g_i + (size_t)j * g_j] : 0.f;
 #pragma unroll
     for (int j = 0; j < R; ++j) {
       if (j < r) {
         const float v = acc[j] + smem[(0 * 64 + lane) * R + j] + smem[(1 * 64 + lane) * R + j] + smem[(2 * 64 + lane) * R + j];
-        G[(size_t)i * g_i + (size_t)j * g_j] += scale * v;
+        G[(size_t)i * g_i + (size_t)j * g_j] = gv[j] + scale * v;
       }
     }
   }
@@ -244,11 +249,11 @@ int32_t launch_lora_outer_batch(const LoraOuterArgs& a, hipStream_t s) {
   for (int e = 0; e < a.count; ++e) mx = a.n_long[e] > mx ? a.n_long[e] : mx;
   const dim3 grid((mx + 63) / 64, a.count);
   if (a.r <= 16)
-    hipLaunchKernelGGL(lora_outer_mfma_path_kernel<16>, grid, dim3(256), 192 * 16 * sizeof(float), s, a);
+    hipLaunchKernelGGL(lora_outer_mfma_path_kernel<16>, grid, dim3(256), 256 * 16 * sizeof(float), s, a);
   else if (a.r <= 32)
-    hipLaunchKernelGGL(lora_outer_mfma_path_kernel<32>, grid, dim3(256), 192 * 32 * sizeof(float), s, a);
+    hipLaunchKernelGGL(lora_outer_mfma_path_kernel<32>, grid, dim3(256), 256 * 32 * sizeof(float), s, a);
   else
-    hipLaunchKernelGGL(lora_outer_mfma_path_kernel<64>, grid, dim3(256), 192 * 64 * sizeof(float), s, a);
+    hipLaunchKernelGGL(lora_outer_mfma_path_kernel<64>, grid, dim3(256), 256 * 64 * sizeof(float), s, a);
   return post("lora_outer");
 }
 
