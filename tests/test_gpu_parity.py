@@ -29,6 +29,11 @@ SMALL_BF16_G5 = C2.with_(name="small_bf16_g5", hidden=640, n_q_heads=10, n_kv_he
                          rope_theta=1e6)
 
 
+# kv groups of one (every query head has its own kv head) and of eight query heads
+SMALL_BF16_MHA = C2.with_(name="small_bf16_mha", hidden=512, n_q_heads=4, n_kv_heads=4, head_dim=128, ffn=1408)
+SMALL_BF16_G8 = C2.with_(name="small_bf16_g8", hidden=1024, n_q_heads=8, n_kv_heads=1, head_dim=128, ffn=1408)
+
+
 def say(msg):
     print(msg, flush=True)
 
@@ -131,7 +136,8 @@ def attention_case(cfg, batch, split, seed=3):
     return to_np(out_d), a_o, to_np(lse_d), lse_o
 
 
-@pytest.mark.parametrize("name,split", [("c1", 0), ("c1", 2), ("small_bf16", 0), ("small_bf16", 2), ("g5", 4)])
+@pytest.mark.parametrize("name,split", [("c1", 0), ("c1", 2), ("small_bf16", 0), ("small_bf16", 2), ("g5", 4), ("mha", 2),
+                                        ("g8", 4)])
 def test_attention_mixed(name, split):
     say(f"attention_mixed {name} split={split}")
     if name == "c1":
@@ -139,9 +145,15 @@ def test_attention_mixed(name, split):
     elif name == "small_bf16":
         cfg = SMALL_BF16
         batch = gen.batch_scaled(4, 12, 1, 700, [(0, 150, 150), (200, 77, 300)], [(96, 75, 171)])
-    else:
+    elif name == "g5":
         cfg = SMALL_BF16_G5
         batch = gen.batch_scaled(5, 7, 17, 333, [(0, 40, 40)], [(64, 100, 164)])
+    elif name == "mha":
+        cfg = SMALL_BF16_MHA                 # 16 tokens per tile, 64 per work item
+        batch = gen.batch_scaled(6, 5, 9, 200, [(0, 150, 150), (40, 77, 117)], [(30, 100, 130)])
+    else:
+        cfg = SMALL_BF16_G8                  # 2 tokens per tile
+        batch = gen.batch_scaled(7, 6, 20, 260, [(0, 45, 45)], [(64, 37, 101)])
     out, a_o, lse, lse_o = attention_case(cfg, batch, split)
     assert_close("attention out", out, a_o, TOL[cfg.dtype])
     assert float(np.max(np.abs(lse - lse_o))) <= (1e-4 if cfg.dtype == "f32" else 2e-2)
@@ -157,11 +169,13 @@ def test_attention_mixed(name, split):
     ("small_bf16", 448, 64),        # aligned, several key blocks of 64 before the window
     ("small_bf16", 301, 131),       # window longer than a row block, odd everything
     ("g5", 130, 33),                # kv group of 5 query heads
+    ("mha", 70, 90),                # kv group of 1: the second half of a dK/dV block has no head of its own
+    ("g8", 17, 50),                 # kv group of 8
     ("c1", 5, 6),                   # fp32 generic path
 ])
 def test_attention_window_bwd(cfg_name, win_start, win_len):
     say(f"attention_window_bwd {cfg_name} window [{win_start}, +{win_len})")
-    cfg = {"small_bf16": SMALL_BF16, "g5": SMALL_BF16_G5, "c1": C1}[cfg_name]
+    cfg = {"small_bf16": SMALL_BF16, "g5": SMALL_BF16_G5, "mha": SMALL_BF16_MHA, "g8": SMALL_BF16_G8, "c1": C1}[cfg_name]
     l = win_start + win_len
     ps = cfg.page_size
     n_pages = (l + ps - 1) // ps
