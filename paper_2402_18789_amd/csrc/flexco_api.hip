@@ -328,6 +328,27 @@ int32_t check_saved_u(const flexco_layer_cfg& c, const flexco_ft_state* ft) {
   return FLEXCO_OK;
 }
 
+// Gated form of the gate/up projection: where the bf16 kernels cover it, the projection writes
+// act = silu(gate) * up straight away (`done` is set) and gate / up only for the finetune rows, into the
+// sequence's saved buffers; otherwise y receives [gate | up] as usual and the caller runs SwiGLU.
+struct GluOut {
+  void* act;
+  size_t ld_act;
+  bool done;
+};
+
+int32_t gated_gemm(const flexco_layer_cfg& c, const flexco_maps& m, const void* x, int K, const void* W, int F,
+                   const GemmExt* ext, const flexco_ft_state* ft, GluOut& glu, hipStream_t s) {
+  if (c.dtype != FLEXCO_BF16) return FLEXCO_EUNSUPPORTED;
+  const size_t e = esize(c.dtype);
+  const int32_t rc = launch_gemm_glu_mfma(x, W, glu.act, m.T, F, K, K, K, glu.ld_act, ext,
+                                          ft ? (void*)boff(ft->saved_gate, (size_t)m.ft_pos0 * F, e) : nullptr,
+                                          ft ? (void*)boff(ft->saved_up, (size_t)m.ft_pos0 * F, e) : nullptr, m.ft_tok0,
+                                          ft ? m.n_ft : 0, F, s, FLEXCO_K_GEMM_FWD);
+  if (rc == FLEXCO_OK) glu.done = true;
+  return rc;
+}
+
 // The adapters of a forward call: ads[a] serves the requests with adapter id a; with any_id (one
 // adapter given) ads[0] serves every request with an id >= 0.
 struct Adapters {
@@ -343,7 +364,7 @@ struct Adapters {
 int32_t forward_projection(const flexco_layer_cfg& c, const Adapters& ad, const flexco_maps& m, const void* x,
                            int K, const void* W, const void* bias, const void* res, size_t ldr, void* y, int N,
                            const int* targets, const int* col0, int n_targets, FwdWs& k,
-                           const flexco_ft_state* ft, hipStream_t s) {
+                           const flexco_ft_state* ft, hipStream_t s, GluOut* glu = nullptr) {
   int act[3], nact = 0;
   for (int i = 0; i < n_targets; ++i)
     if (m.n_lora > 0 && has_target(c, targets[i])) act[nact++] = i;
@@ -383,9 +404,19 @@ int32_t forward_projection(const flexco_layer_cfg& c, const Adapters& ad, const 
       }
     ext.n = z;
     LR(launch_lora_shrink_mfma(sa, z, s));
+    if (glu) {
+      const int32_t rc = gated_gemm(c, m, x, K, W, N / 2, &ext, ft, *glu, s);
+      if (rc != FLEXCO_EUNSUPPORTED) return rc;
+      clear_error();
+    }
     int32_t rc = launch_gemm(x, W, y, bias, res, T, N, K, K, K, N, ldr, false, dt, s, &ext);
     if (rc != FLEXCO_EUNSUPPORTED) return rc;
     clear_error();   // e.g. a target boundary inside a 32-column fragment: run the bypass as separate kernels
+  }
+  if (glu && nact == 0) {
+    const int32_t rc = gated_gemm(c, m, x, K, W, N / 2, nullptr, ft, *glu, s);
+    if (rc != FLEXCO_EUNSUPPORTED) return rc;
+    clear_error();
   }
   FLEXCO_TRY(launch_gemm(x, W, y, bias, res, T, N, K, K, K, N, ldr, false, dt, s));
   // more adapters than the folded path takes: the backward pass (which folds whenever it can) still
@@ -690,11 +721,12 @@ static int32_t layer_forward_impl(const flexco_layer_cfg* cfg, const flexco_base
   }
   // MLP side
   EW(launch_rmsnorm(k.x2, w->g2, k.h, T, H, c.rms_eps, dt, s));
+  GluOut glu{k.act, (size_t)F, false};
   {
     const int tg[2] = {FLEXCO_T_GATE, FLEXCO_T_UP}, c0[2] = {0, F};
-    FLEXCO_TRY(forward_projection(c, ad, m, k.h, H, w->wgu, nullptr, nullptr, 0, k.gu, 2 * F, tg, c0, 2, k, ft, s));
+    FLEXCO_TRY(forward_projection(c, ad, m, k.h, H, w->wgu, nullptr, nullptr, 0, k.gu, 2 * F, tg, c0, 2, k, ft, s, &glu));
   }
-  EW(launch_swiglu(k.gu, k.act, T, F, dt, s));
+  if (!glu.done) EW(launch_swiglu(k.gu, k.act, T, F, dt, s));
   {
     const int tg[1] = {FLEXCO_T_DOWN}, c0[1] = {0};
     FLEXCO_TRY(forward_projection(c, ad, m, k.act, F, w->wd, nullptr, k.x2, H, x_out, H, tg, c0, 1, k, ft, s));
@@ -713,8 +745,10 @@ static int32_t layer_forward_impl(const flexco_layer_cfg* cfg, const flexco_base
     };
     add(boff(x_in, t0 * H, e), H * e, boff(ft->saved_x, p0 * H, e), H * e, H * e);
     add(boff(k.x2, t0 * H, e), H * e, boff(ft->saved_x2, p0 * H, e), H * e, H * e);
-    add(boff(k.gu, t0 * 2 * F, e), 2 * F * e, boff(ft->saved_gate, p0 * F, e), F * e, F * e);
-    add(boff(k.gu, t0 * 2 * F + F, e), 2 * F * e, boff(ft->saved_up, p0 * F, e), F * e, F * e);
+    if (!glu.done) {   // (the gated projection has written them itself)
+      add(boff(k.gu, t0 * 2 * F, e), 2 * F * e, boff(ft->saved_gate, p0 * F, e), F * e, F * e);
+      add(boff(k.gu, t0 * 2 * F + F, e), 2 * F * e, boff(ft->saved_up, p0 * F, e), F * e, F * e);
+    }
     add(boff(k.attn, t0 * qd, e), qd * e, boff(ft->saved_attn, p0 * qd, e), qd * e, qd * e);
     add(k.lse + t0 * c.n_q_heads, c.n_q_heads * 4, ft->lse + p0 * c.n_q_heads, c.n_q_heads * 4, (size_t)c.n_q_heads * 4);
     EW(launch_copy_rows_batch(cb, n, wb, s));

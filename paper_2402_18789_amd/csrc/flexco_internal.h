@@ -54,6 +54,19 @@ struct GemmExt {
   size_t ldw2[GEMM_EXT_MAX];
 };
 
+// Gated-linear-unit form of the forward GEMM: W = [gate rows ; up rows] ([2F, K]); the kernel multiplies
+// both halves for the same F output columns and writes act = silu(gate) * up, plus - for rows
+// [save_row0, save_row0 + save_rows) - the gate and up values themselves (the activations graph
+// pruning keeps for the finetune rows).
+struct GemmGlu {
+  int F;                // columns of act = rows of each half of W
+  int col0;             // first act column of this launch
+  bf16_t* save_gate;    // [save_rows, ld_save] or NULL
+  bf16_t* save_up;
+  int save_row0, save_rows;
+  size_t ld_save;
+};
+
 int32_t fail(int32_t code, const char* fmt, ...);
 void clear_error();
 
@@ -94,6 +107,11 @@ int32_t launch_gemm_mfma(const void* A, const void* W, void* C, const void* bias
                          int N, int K, size_t lda, size_t ldw, size_t ldc, size_t ldr, bool trans_w,
                          const GemmExt* ext, hipStream_t s, float* part = nullptr, size_t part_elems = 0,
                          int timer_id = -1);
+// act[M, F] = silu(A Wg^T + ext) * (A Wu^T + ext), W = [Wg ; Wu]; ext entries address the 2F columns
+// [gate | up].  Returns FLEXCO_EUNSUPPORTED (without launching) for shapes it does not cover.
+int32_t launch_gemm_glu_mfma(const void* A, const void* W, void* act, int M, int F, int K, size_t lda, size_t ldw,
+                             size_t ld_act, const GemmExt* ext, void* save_gate, void* save_up, int save_row0,
+                             int save_rows, size_t ld_save, hipStream_t s, int timer_id);
 int32_t launch_lora_shrink_mfma(const LoraShrinkArgs& a, int n_mats, hipStream_t s);
 int32_t launch_lora_transpose(const LoraTransposeArgs& a, int n_mats, hipStream_t s);
 int32_t launch_lora_outer_batch(const LoraOuterArgs& a, hipStream_t s);

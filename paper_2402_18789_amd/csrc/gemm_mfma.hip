@@ -25,6 +25,7 @@
 // Work-group ids are remapped so that ids that land on the same XCD (id mod 8) work on
 // neighbouring tiles, M fastest: the W tile they share stays in that XCD's L2.
 #include <algorithm>
+#include <cstring>
 #include "flexco_internal.h"
 #include "device_types.h"
 
@@ -42,13 +43,13 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 
 __device__ inline int swz(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
 
-template <int BM, int BN, bool TRANS>
+template <int BM, int BN, bool TRANS, bool GLU = false>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
                                                         bf16_t* __restrict__ C, const bf16_t* __restrict__ bias,
                                                         const bf16_t* __restrict__ res, int M, int N, int K,
                                                         size_t lda, size_t ldw, size_t ldc, size_t ldr, int tiles_m,
                                                         int tiles_n, GemmExt ext, float* __restrict__ part,
-                                                        int k_chunk) {
+                                                        int k_chunk, GemmGlu glu) {
   constexpr int WM = BM / 2, WN = BN / 2, MT = WM / 32, NT = WN / 32;
 
   // ---- work-group id -> tile, XCD-aware ------------------------------------------------
@@ -126,7 +127,14 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
     ga[p] = A + (size_t)min(m0 + (p * 4 + wave) * 8 + d_row, M - 1) * lda + kbeg + d_c * 8;
 #pragma unroll
   for (int p = 0; p < PB; ++p) {
-    if (!TRANS) {
+    if (GLU) {
+      // W-tile rows alternate between the two halves of W in runs of 16: rows 32 f .. + 16 are gate rows
+      // (act columns tile + 16 f .. + 16), rows 32 f + 16 .. + 16 the up rows of the same columns, so that
+      // a lane's accumulators of one fragment hold gate and up of the same 4 + 4 act columns
+      const int rr = (p * 4 + wave) * 8 + d_row;
+      const int ac = glu.col0 + tn * (BN / 2) + (rr >> 5) * 16 + (rr & 15);
+      gw[p] = W + ((size_t)((rr >> 4) & 1) * glu.F + min(ac, glu.F - 1)) * ldw + kbeg + d_c * 8;
+    } else if (!TRANS) {
       gw[p] = W + (size_t)min(n0 + (p * 4 + wave) * 8 + d_row, N - 1) * ldw + kbeg + d_c * 8;
     } else {
       int col = n0 + t_c * 8;
@@ -281,7 +289,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
   for (int e = 0; e < (blockIdx.y == 0 ? ext.n : 0); ++e) {
     // forward form: an entry covers a column range whose ends are multiples of 32, so each 32-column
     // fragment of the tile belongs to at most one entry; fragments outside this entry multiply zeros
-    if (!TRANS && (n0 + BN <= ext.col0[e] || n0 >= ext.col1[e])) continue;
+    if (!TRANS && !GLU && (n0 + BN <= ext.col0[e] || n0 >= ext.col1[e])) continue;
     const bf16_t* A2 = ext.A2[e];
     const bf16_t* W2 = ext.W2[e];
     for (int k2 = 0; k2 < ext.r; k2 += 16) {
@@ -293,7 +301,17 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
       }
 #pragma unroll
       for (int j = 0; j < NT; ++j) {
-        if (!TRANS) {
+        if (GLU) {
+          // this lane's W-tile row is a gate or an up row: column of the [gate | up] range the entries address
+          const int ac = glu.col0 + tn * (BN / 2) + ((wn0 + j * 32) >> 1) + (l32 & 15);
+          const int lc = (l32 >> 4) * glu.F + ac;
+          if (ac < glu.F && lc >= ext.col0[e] && lc < ext.col1[e]) {
+            bfr[j] = *reinterpret_cast<const bf16x8*>(W2 + (size_t)(lc - ext.col0[e]) * ext.ldw2[e] + k2 + kg * 8);
+          } else {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) bfr[j][q] = (bf16_t)0.f;
+          }
+        } else if (!TRANS) {
           const int cj = n0 + wn0 + j * 32;
           if (cj >= ext.col0[e] && cj < ext.col1[e]) {
             const int c = min(cj + l32, ext.col1[e] - 1) - ext.col0[e];
@@ -318,6 +336,41 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
 
   // ---- epilogue: register 4 q + e of acc[i][j] is row lane % 32, column 8 q + 4 (lane / 32) + e of
   // the 32 x 32 block ------------------------------------------------------------------------------
+  if (GLU) {
+    // registers 4 qq + e (gate) and 8 + 4 qq + e (up) of acc[i][j] belong to act column 8 qq + 4 (lane / 32) + e
+    // of the fragment's 16
+    const int ac_end = min(glu.col0 + N / 2, glu.F);
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+      const int row = m0 + wm0 + i * 32 + l32;
+      const bool save = glu.save_gate && row >= glu.save_row0 && row < glu.save_row0 + glu.save_rows;
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+#pragma unroll
+        for (int qq = 0; qq < 2; ++qq) {
+          const int ac = glu.col0 + tn * (BN / 2) + ((wn0 + j * 32) >> 1) + 8 * qq + 4 * kg;
+          if (row >= M || ac >= ac_end) continue;
+          bf16x4 o, gs, us;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            // gate and up pass through the storage type first (they are what the backward pass reads back)
+            gs[e] = (bf16_t)acc[i][j][4 * qq + e];
+            us[e] = (bf16_t)acc[i][j][8 + 4 * qq + e];
+            const float gv = (float)gs[e], uv = (float)us[e];
+            o[e] = (bf16_t)(gv / (1.0f + __expf(-gv)) * uv);
+          }
+          *reinterpret_cast<bf16x4*>(C + (size_t)row * ldc + ac) = o;
+          if (save) {
+            const size_t so = (size_t)(row - glu.save_row0) * glu.ld_save + ac;
+            *reinterpret_cast<bf16x4*>(glu.save_gate + so) = gs;
+            *reinterpret_cast<bf16x4*>(glu.save_up + so) = us;
+          }
+        }
+        if (MT * NT > 4) __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    return;
+  }
   if (part) {
     float* P = part + (size_t)blockIdx.y * M * N;
 #pragma unroll
@@ -396,11 +449,14 @@ __global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(const float* __
   *reinterpret_cast<bf16x4*>(C + (size_t)row * ldc + col) = o;
 }
 
-template <int BM, int BN, bool TRANS>
+template <int BM, int BN, bool TRANS, bool GLU = false>
 int32_t launch_cfg(const void* A, const void* W, void* C, const void* bias, const void* res, int M, int N, int K,
                    size_t lda, size_t ldw, size_t ldc, size_t ldr, const GemmExt& ext, hipStream_t s,
-                   int timer_id, float* part = nullptr, int splits = 1, bool first_of_call = true) {
-  auto kern = gemm_bf16_kernel<BM, BN, TRANS>;   // all LDS is static
+                   int timer_id, float* part = nullptr, int splits = 1, bool first_of_call = true,
+                   const GemmGlu* glu_in = nullptr) {
+  auto kern = gemm_bf16_kernel<BM, BN, TRANS, GLU>;   // all LDS is static
+  GemmGlu glu;
+  if (glu_in) glu = *glu_in; else memset(&glu, 0, sizeof(glu));
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   // while the class's timer runs, the kernels carry an event pair of their own (start and end stamps of
   // the dispatch itself)
@@ -408,7 +464,7 @@ int32_t launch_cfg(const void* A, const void* W, void* C, const void* bias, cons
   if (timer_id >= 0) (void)kernel_timer_pair(timer_id, &e0, &e1, first_of_call);
   hipExtLaunchKernelGGL(kern, dim3(tiles_m * tiles_n, splits), dim3(256), 0, s, e0, e1, 0, (const bf16_t*)A,
                         (const bf16_t*)W, (bf16_t*)C, (const bf16_t*)bias, (const bf16_t*)res, M, N, K, lda, ldw, ldc, ldr,
-                        tiles_m, tiles_n, ext, splits > 1 ? part : nullptr, K / splits);
+                        tiles_m, tiles_n, ext, splits > 1 ? part : nullptr, K / splits, glu);
   if (splits > 1) {
     const size_t quads = ((size_t)M * N + 3) / 4;
     e0 = e1 = nullptr;
@@ -524,6 +580,56 @@ int32_t launch_gemm_mfma(const void* A, const void* W, void* C, const void* bias
     return launch_cfg<256, 192, false>(A, W1, (bf16_t*)C + n1, bias ? (const bf16_t*)bias + n1 : nullptr,
                                        residual ? (const bf16_t*)residual + n1 : nullptr, M, N - n1, K, lda, ldw, ldc, ldr,
                                        sub_ext(ext, n1, N), s, timer_id, nullptr, 1, n1 == 0);
+  }
+  return FLEXCO_OK;
+}
+
+// Gated form: the planner of the forward form over the 2F interleaved columns; a tile of BN W-rows covers
+// BN / 2 act columns.
+int32_t launch_gemm_glu_mfma(const void* A, const void* W, void* act, int M, int F, int K, size_t lda, size_t ldw,
+                             size_t ld_act, const GemmExt* ext_in, void* save_gate, void* save_up, int save_row0,
+                             int save_rows, size_t ld_save, hipStream_t s, int timer_id) {
+  if (K % BK != 0 || lda % 8 != 0 || ldw % 8 != 0 || F % 8 != 0 || ld_act % 4 != 0 || ld_save % 4 != 0 ||
+      ((uintptr_t)act & 7) || ((uintptr_t)save_gate & 7) || ((uintptr_t)save_up & 7))
+    return FLEXCO_EUNSUPPORTED;
+  GemmExt ext;
+  if (ext_in) ext = *ext_in; else ext.n = 0;
+  if (ext.n > 0 && ext.r % 16 != 0) return FLEXCO_EUNSUPPORTED;
+  GemmGlu glu;
+  glu.F = F; glu.col0 = 0; glu.save_gate = (bf16_t*)save_gate; glu.save_up = (bf16_t*)save_up;
+  glu.save_row0 = save_row0; glu.save_rows = save_gate ? save_rows : 0; glu.ld_save = ld_save;
+  const int N = 2 * F, CU = 256;
+  auto rounds = [&](long tiles) { return (double)((tiles + CU - 1) / CU); };
+  const long tm256 = (M + 255) / 256, tm128 = (M + 127) / 128;
+  const double c256 = 256.0 * 256 / 1.24, c256n = 256.0 * 192 / 1.09, c128n = 128.0 * 192 / 1.0, c128 = 128.0 * 128 / 0.875;
+  double best = rounds(tm128 * ((N + 127) / 128)) * c128;
+  int shape = 0, a_best = 0;
+  {
+    const double t = rounds(tm128 * ((N + 191) / 192)) * c128n;
+    if (t < best) { best = t; shape = 1; }
+  }
+  const int n256 = (N + 255) / 256;
+  for (int a = n256; a >= 0; --a) {
+    const int rest = N - 256 * a;
+    if (rest < 0 && a != n256) continue;
+    const long b = rest > 0 ? (rest + 191) / 192 : 0;
+    const double t = (a ? rounds(tm256 * a) * c256 : 0.0) + (b ? rounds(tm256 * b) * c256n : 0.0);
+    if (t < best - 1e-9) { best = t; shape = 2; a_best = a; }
+  }
+  if (shape == 0)
+    return launch_cfg<128, 128, false, true>(A, W, act, nullptr, nullptr, M, N, K, lda, ldw, ld_act, 0, ext, s, timer_id,
+                                             nullptr, 1, true, &glu);
+  if (shape == 1)
+    return launch_cfg<128, 192, false, true>(A, W, act, nullptr, nullptr, M, N, K, lda, ldw, ld_act, 0, ext, s, timer_id,
+                                             nullptr, 1, true, &glu);
+  const int n1 = std::min(N, 256 * a_best);        // interleaved columns of the 256-wide tiles = 2 x their act columns
+  if (n1 > 0)
+    FLEXCO_TRY((launch_cfg<256, 256, false, true>(A, W, act, nullptr, nullptr, M, n1, K, lda, ldw, ld_act, 0, ext, s,
+                                                  timer_id, nullptr, 1, true, &glu)));
+  if (n1 < N) {
+    glu.col0 = n1 / 2;
+    return launch_cfg<256, 192, false, true>(A, W, act, nullptr, nullptr, M, N - n1, K, lda, ldw, ld_act, 0, ext, s,
+                                             timer_id, nullptr, 1, n1 == 0, &glu);
   }
   return FLEXCO_OK;
 }
