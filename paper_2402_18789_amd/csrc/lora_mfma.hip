@@ -11,8 +11,9 @@
 //   expand   is not a kernel: the projection GEMM appends the rank-r product as extra
 //            k-steps (gemm_mfma.hip), reading the bf16 matrix the shrink kernel writes.
 //   outer    dB += scale dy^T u,  dA += scale t^T x : every output element is a sum over
-//            the window's rows only; plain FMA code, 64 consecutive outputs per wavefront,
-//            rows interleaved over the block's 4 wavefronts, fixed-order LDS reduction.
+//            the window's rows only; on the matrix cores (u, t as bf16, the rows of x / dy through
+//            transposing LDS reads), 64 output columns per block, rows shared out over its 4
+//            wavefronts, fixed-order LDS reduction; a plain FMA kernel covers unaligned shapes.
 #include <cstring>
 #include "flexco_internal.h"
 #include "device_types.h"
@@ -196,6 +197,127 @@ __global__ __launch_bounds__(256) void lora_outer_mfma_path_kernel(LoraOuterArgs
   }
 }
 
+// The same products on the matrix cores: G^T[j, i] += scale sum_m U[m, j] X[m, i] with
+// v_mfma_f32_16x16x32_bf16, D rows = 16 ranks, D columns = 16 of the block's 64 columns i, k = 32 rows m.
+//   * U^T (bf16, row pitch padded) is staged in LDS once per 256-row chunk; a lane reads its 8
+//     consecutive m of one rank with one ds_read_b128.
+//   * X: wavefront w owns rows 64 w .. + 64 of the chunk, two [32 rows][64 columns] tiles that go from
+//     global memory straight into its own LDS buffers; the operand (8 consecutive rows of one column)
+//     comes from two transposing reads (ds_read_b64_tr_b16).  32-byte column pairs are XOR-swizzled
+//     with row % 4 so that the four rows of a read sit on different banks.
+//   * the four wavefronts' sums are added in wavefront order through LDS.
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+#define FLEXCO_GP(p) ((const __attribute__((address_space(1))) void*)(p))
+#define FLEXCO_LP(p) ((__attribute__((address_space(3))) void*)(p))
+#define FLEXCO_LDS __attribute__((address_space(3)))
+__device__ inline bf16x8 tr_pair(const bf16_t* a, const bf16_t* b) {
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((FLEXCO_LDS s16x4*)a);
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((FLEXCO_LDS s16x4*)b);
+  return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+template <int RT>   // rank tiles of 16
+__global__ __launch_bounds__(256) void lora_outer_mfma_kernel(LoraOuterArgs a) {
+  constexpr int UP = 264;                                                   // row pitch of U^T in elements
+  __shared__ __attribute__((aligned(1024))) bf16_t xt[4][2][32 * 64];       // per wavefront: two X tiles
+  __shared__ __attribute__((aligned(16))) bf16_t ut[RT * 16 * UP];          // U^T of the chunk, [rank][row]
+  __shared__ __attribute__((aligned(16))) float red[3][RT][4][64][4];       // sums of wavefronts 1..3
+  const int e = blockIdx.y;
+  const int n = a.n, r = a.r, n_long = a.n_long[e];
+  const int i0 = blockIdx.x * 64;
+  if (i0 >= n_long) return;   // entries of one launch differ in width
+  const bf16_t* __restrict__ X = a.X[e];
+  const float* __restrict__ U = a.U[e];
+  float* __restrict__ G = a.G[e];
+  const size_t ldx = a.ldx[e], g_i = a.g_i[e], g_j = a.g_j[e];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int c = lane & 15, g = lane >> 4;
+
+  f32x4 acc[RT][4];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+    for (int cg = 0; cg < 4; ++cg) acc[rt][cg] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // tile loads: instruction q fills rows 8 q .. + 8 of a tile; lane -> row 8 q + lane / 8, physical chunk
+  // lane % 8; it fetches the logical chunk that belongs there (pair = physical pair ^ row % 4)
+  const int d_row = lane >> 3, d_pc = lane & 7;
+  const int d_lch = ((((d_pc >> 1) ^ (d_row & 3)) << 1) | (d_pc & 1));
+  const int d_col = min(i0 + d_lch * 8, n_long - 8);
+  // transposing reads: source lane c of group g -> row 8 g + c / 4 (+ 4), columns 16 cg + 4 (c % 4) ..
+  const int t_row = 8 * g + (c >> 2);
+  const int t_k = (c >> 2) & 3;
+
+  for (int mb = 0; mb < n; mb += 256) {
+    __syncthreads();   // the previous chunk's reads of ut are done
+    for (int idx = tid; idx < 256 * RT * 16; idx += 256) {
+      const int m = idx / (RT * 16), j = idx % (RT * 16);
+      ut[j * UP + m] = (bf16_t)((mb + m < n && j < r) ? U[(size_t)(mb + m) * r + j] : 0.f);
+    }
+    const int mw = mb + 64 * wave;
+#pragma unroll
+    for (int st = 0; st < 2; ++st)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int row = min(mw + 32 * st + 8 * q + d_row, n - 1);   // rows past n meet zero U
+        __builtin_amdgcn_global_load_lds(FLEXCO_GP(X + (size_t)row * ldx + d_col), FLEXCO_LP(&xt[wave][st][q * 512]), 16, 0, 0);
+      }
+    __syncthreads();   // ut is complete; the barrier's wait also covers this wavefront's tile loads
+    if (mw < n) {
+#pragma unroll
+      for (int st = 0; st < 2; ++st) {
+        bf16x8 af[RT];
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+          af[rt] = *reinterpret_cast<const bf16x8*>(&ut[(rt * 16 + c) * UP + 64 * wave + 32 * st + 8 * g]);
+#pragma unroll
+        for (int cg = 0; cg < 4; ++cg) {
+          const bf16_t* p = &xt[wave][st][t_row * 64 + ((cg ^ t_k) << 4) + 4 * (c & 3)];
+          const bf16x8 xf = tr_pair(p, p + 4 * 64);
+#pragma unroll
+          for (int rt = 0; rt < RT; ++rt) acc[rt][cg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[rt], xf, acc[rt][cg], 0, 0, 0);
+        }
+      }
+    }
+  }
+  // lane (column c of group cg, g) holds ranks 16 rt + 4 g .. + 4
+  if (wave > 0) {
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+      for (int cg = 0; cg < 4; ++cg) *reinterpret_cast<f32x4*>(red[wave - 1][rt][cg][lane]) = acc[rt][cg];
+  }
+  __syncthreads();
+  if (wave == 0) {
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+      for (int cg = 0; cg < 4; ++cg) {
+        const int i = i0 + 16 * cg + c;
+        if (i >= n_long) continue;
+        f32x4 v = acc[rt][cg];
+#pragma unroll
+        for (int w = 0; w < 3; ++w) {
+          const f32x4 o = *reinterpret_cast<const f32x4*>(red[w][rt][cg][lane]);
+#pragma unroll
+          for (int q = 0; q < 4; ++q) v[q] += o[q];
+        }
+        float gv[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int j = rt * 16 + 4 * g + q;
+          gv[q] = j < r ? G[(size_t)i * g_i + (size_t)j * g_j] : 0.f;
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int j = rt * 16 + 4 * g + q;
+          if (j < r) G[(size_t)i * g_i + (size_t)j * g_j] = gv[q] + a.scale * v[q];
+        }
+      }
+  }
+}
+
 int32_t post(const char* what) {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(FLEXCO_EHIP, "launch of %s failed: %s", what, hipGetErrorString(e));
@@ -246,8 +368,21 @@ int32_t launch_lora_transpose(const LoraTransposeArgs& a, int n_mats, hipStream_
 int32_t launch_lora_outer_batch(const LoraOuterArgs& a, hipStream_t s) {
   if (a.n == 0 || a.count == 0) return FLEXCO_OK;
   int mx = 0;
-  for (int e = 0; e < a.count; ++e) mx = a.n_long[e] > mx ? a.n_long[e] : mx;
+  bool tiles_ok = a.r <= 64;     // whole 16-byte column chunks, rows and base pointers 16-byte aligned
+  for (int e = 0; e < a.count; ++e) {
+    mx = a.n_long[e] > mx ? a.n_long[e] : mx;
+    tiles_ok = tiles_ok && a.n_long[e] % 8 == 0 && a.n_long[e] >= 8 && a.ldx[e] % 8 == 0 && aligned16(a.X[e]);
+  }
   const dim3 grid((mx + 63) / 64, a.count);
+  if (tiles_ok) {
+    switch ((a.r + 15) / 16) {
+      case 1: hipLaunchKernelGGL(lora_outer_mfma_kernel<1>, grid, dim3(256), 0, s, a); break;
+      case 2: hipLaunchKernelGGL(lora_outer_mfma_kernel<2>, grid, dim3(256), 0, s, a); break;
+      case 3: hipLaunchKernelGGL(lora_outer_mfma_kernel<3>, grid, dim3(256), 0, s, a); break;
+      default: hipLaunchKernelGGL(lora_outer_mfma_kernel<4>, grid, dim3(256), 0, s, a); break;
+    }
+    return post("lora_outer");
+  }
   if (a.r <= 16)
     hipLaunchKernelGGL(lora_outer_mfma_path_kernel<16>, grid, dim3(256), 256 * 16 * sizeof(float), s, a);
   else if (a.r <= 32)
