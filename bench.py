@@ -157,7 +157,10 @@ def main():
     for name, kid in B.KERNEL_IDS.items():
         ms, n = B.flexco_kernel_timer_stop(kid)
         probe[name] = (ms / probe_steps, n / probe_steps)
-    dominant = max(probe, key=lambda k: probe[k][0])
+    # the dominant kernel = the class whose single launch takes longest (the forward projections are four
+    # launches of different shapes that together take about as long as the one attention launch; picking
+    # by the class total would flip between the two from run to run)
+    dominant = max(probe, key=lambda k: probe[k][0] / max(1.0, probe[k][1]))
     log("per-step kernel classes (ms): " + ", ".join("%s=%.3f" % (k, v[0]) for k, v in probe.items()))
 
     # ---- the timed region: K steps, the dominant class bracketed by events ---------------------
