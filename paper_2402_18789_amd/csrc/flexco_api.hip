@@ -677,7 +677,7 @@ static int32_t layer_forward_impl(const flexco_layer_cfg* cfg, const flexco_base
   FLEXCO_TRY(check_pool(*cfg, pool));
   const flexco_layer_cfg& c = *cfg;
   const flexco_maps& m = *maps;
-  if (m.n_lora > 0) {
+  if (m.n_lora > 0 && c.lora_targets != 0) {
     FLEXCO_CHECK(ad.ads != nullptr && ad.n >= 1, FLEXCO_EINVAL, "the batch has adapter tokens but no adapter is given");
     FLEXCO_CHECK(ad.any_id || m.n_adapters <= ad.n, FLEXCO_EINVAL, "the batch uses adapter id %d, %d adapters are given",
                  m.n_adapters - 1, ad.n);

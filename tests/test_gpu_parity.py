@@ -388,6 +388,87 @@ def test_layer_c5_shape_rank32():
     run_layer_case(cfg, batch, ft_window=32, prefill_chunk=24, bwd_windows=[40, 24], seed=3, tol_qk=4e-2)
 
 
+# ------------------------------------------------------------------------------------------
+# degenerate batches
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("cfg_name", ["c1", "small_bf16"])
+def test_layer_inference_only_batches(cfg_name):
+    """No finetune request in the batch (ft state = NULL): decode + prefill, then a single decode token."""
+    cfg = C1 if cfg_name == "c1" else SMALL_BF16
+    say(f"layer {cfg_name}: inference-only batches")
+    tol = TOL[cfg.dtype]
+    b = gen.mixed_batch(16, 31, decode_ctx=(1, 16, 17, 130), prefill=[(0, 33, 70), (48, 20, 90)], extra_capacity=2)
+    b = gen.with_adapters(b, [0, -1])                                 # some inference requests use the adapter
+    case = Case(cfg, b, seed=31)
+    x = gen.layer_input(cfg, 31, b.n_tokens)
+    y_g, y_o, _ = case.forward(b, x)
+    assert_close("y", y_g, y_o, tol)
+    one = gen.mixed_batch(16, 32, decode_ctx=(37,))                   # T = 1
+    case = Case(cfg, one, seed=32)
+    x = gen.layer_input(cfg, 32, 1)
+    y_g, y_o, _ = case.forward(one, x)
+    assert_close("y of a single token", y_g, y_o, tol)
+    base = gen.mixed_batch(16, 33, decode_ctx=(5, 40), prefill=[(0, 18, 18)])   # nobody uses an adapter
+    case = Case(cfg, base, seed=33)
+    x = gen.layer_input(cfg, 33, base.n_tokens)
+    y_g, y_o, _ = case.forward(base, x)
+    assert_close("y without adapters", y_g, y_o, tol)
+
+
+@pytest.mark.parametrize("cfg_name", ["c1", "small_bf16"])
+def test_layer_finetune_only_windows_of_one_and_many(cfg_name):
+    """The finetune sequence alone in the batch; forward windows 1 + 32 + rest, backward windows rest + 1 + 32."""
+    cfg = C1 if cfg_name == "c1" else SMALL_BF16
+    say(f"layer {cfg_name}: finetune-only batch, one-row windows")
+    L = 49
+    b = gen.mixed_batch(16, 34, finetune=[(0, 1, L)])
+    tol = TOL[cfg.dtype]
+    case = Case(cfg, b, seed=34)
+    ft_seq = b.requests[0].seq_id
+    x_seq = gen.layer_input(cfg, 34, L, tag="ftonly")
+    y_g, y_o = np.zeros((L, cfg.hidden)), np.zeros((L, cfg.hidden))
+    start = 0
+    for n_new in (1, 32, L - 33):
+        bb = gen.Batch([gen.Request(KIND_FINETUNE, ft_seq, start, n_new, 0)], b.seq_pages, b.seq_capacity, b.num_pages,
+                       b.page_size)
+        g, o, _ = case.forward(bb, x_seq[start:start + n_new])
+        y_g[start:start + n_new], y_o[start:start + n_new] = g, o
+        start += n_new
+    assert_close("y", y_g, y_o, tol)
+    dY = gen.storage_round(cfg, gen.layer_input(cfg, 35, L, tag="dy"))
+    grads_o = {}
+    case.dev.zero_grads()
+    case.d_ft[ft_seq].zero_accum()
+    l = L
+    dX_g, dX_o = np.zeros((L, cfg.hidden)), np.zeros((L, cfg.hidden))
+    for s_ in (L - 33, 1, 32):
+        g, o = case.backward_window(ft_seq, l - s_, s_, dY[l - s_:l], grads_o)
+        dX_g[l - s_:l], dX_o[l - s_:l] = g, o
+        l -= s_
+    assert l == 0
+    assert_close("dX", dX_g, dX_o, tol)
+    grads_g = case.dev.grads_numpy()
+    for t in cfg.lora_targets:
+        assert_close(f"dA[{t}]", grads_g[t][0], grads_o[t][0], tol)
+        assert_close(f"dB[{t}]", grads_g[t][1], grads_o[t][1], tol)
+
+
+def test_layer_without_lora_targets():
+    """cfg.lora_targets empty: the base model alone, forward and input gradient (lora = NULL)."""
+    cfg = SMALL_BF16.with_(lora_targets=())
+    say("layer small bf16 without LoRA targets")
+    b = gen.batch_scaled(36, 4, 3, 200, [(0, 40, 40)], [(0, 70, 70)])
+    case = Case(cfg, b, seed=36)
+    x = gen.layer_input(cfg, 36, b.n_tokens)
+    y_g, y_o, _ = case.forward(b, x)
+    assert_close("y", y_g, y_o, TOL["bf16"])
+    ft_seq = [r.seq_id for r in b.requests if r.kind == KIND_FINETUNE][0]
+    dY = gen.storage_round(cfg, gen.layer_input(cfg, 37, 70, tag="dy"))
+    case.d_ft[ft_seq].zero_accum()
+    g, o = case.backward_window(ft_seq, 0, 70, dY, {})
+    assert_close("dX", g, o, TOL["bf16"])
+
+
 def test_forward_is_deterministic():
     say("determinism")
     case = Case(C1, gen.batch_c1(0))
