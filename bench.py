@@ -175,12 +175,18 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     ev0.record()
+    marks = []                                     # one event per step end (one-stream mode): median / min per step
     for i in range(args.steps):
         step(i)
+        if not args.overlap:
+            e = torch.cuda.Event(enable_timing=True)
+            e.record()
+            marks.append(e)
     ev1.record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     gpu_ms = ev0.elapsed_time(ev1)
+    per_step = [a.elapsed_time(b) for a, b in zip([ev0] + marks[:-1], marks)]
     dom_ms, dom_timed = B.flexco_kernel_timer_stop(B.KERNEL_IDS[dominant])
     B.flexco_kernel_timer_sample(B.KERNEL_IDS[dominant], 1)
     # with two streams the events on the forward's stream do not bracket the backward: wall clock only
@@ -213,6 +219,9 @@ def main():
         "kernel_classes": classes,
         "gpu_event_ms_per_step": gpu_ms / args.steps,
     }
+    if per_step:
+        out["ms_per_step_median"] = float(np.median(per_step))
+        out["ms_per_step_min"] = float(np.min(per_step))
     out["measured_ceilings"] = measured_ceilings(B, torch)
     if not args.overlap and not args.no_two_stream:
         # the same K steps again with the window backward on a second stream (reported beside the
@@ -255,10 +264,21 @@ def measured_ceilings(B, torch):
         torch.cuda.synchronize()
         if rep:
             best_read = max(best_read, nbytes / (ev0.elapsed_time(ev1) * 1e-3) / 1e9)
-    del buf
-    return {"mfma_bf16_loop_tflops": best_mfma, "hbm_read_stream_gbs": best_read,
+    # plain device-to-device copy of 1 GiB (read + write counted)
+    src, dst = buf[:1 << 30], buf[1 << 30:2 << 30]
+    best_copy = 0.0
+    for rep in range(4):
+        ev0.record()
+        dst.copy_(src)
+        ev1.record()
+        torch.cuda.synchronize()
+        if rep:
+            best_copy = max(best_copy, 2.0 * (1 << 30) / (ev0.elapsed_time(ev1) * 1e-3) / 1e9)
+    del src, dst, buf
+    return {"mfma_bf16_loop_tflops": best_mfma, "hbm_read_stream_gbs": best_read, "device_copy_gbs": best_copy,
             "what": "probe kernels of the library: 256 blocks x 4 wavefronts of back-to-back v_mfma_f32_32x32x16_bf16 on "
-                    "register operands in [-1, 1); 2048 blocks streaming 4 GiB with 16-byte loads"}
+                    "register operands in [-1, 1); 2048 blocks streaming 4 GiB with 16-byte loads; a 1 GiB device-to-device "
+                    "copy (bytes read + bytes written)"}
 
 
 def algorithmic_work(cfg, batch, hm):
