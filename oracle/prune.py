@@ -18,7 +18,11 @@ Readings where the listing is loose:
     always count as stored, so the outcome does not depend on iteration order;
   * Cost(n) < threshold  :=  n is elementwise, a norm, or a rank-r matmul;
   * attention is one operator whose backward reads Q, K, V and recomputes the
-    softmax probabilities internally.
+    softmax probabilities internally;
+  * other bypass networks (Sec. 4.1 names (IA)^3 and bottleneck adapters beside LoRA) need two more
+    operator kinds: `mul`, the elementwise product with a learned vector, and `relu`, whose backward
+    reads only the sign of its output: 'm:<t>' denotes that sign bitmask of tensor t (the compressed
+    form Sec. 5.2 mentions for ReLU), which a tensor needed by nobody else is stored as.
 The worked example of the paper's pruning figure (MLP with LoRA) is not available
 in the text: that example is parity unpinned; the tests pin this code against an
 independent demand-driven reachability search instead.
@@ -31,7 +35,7 @@ from typing import Dict, List, Set, Tuple
 @dataclass
 class Op:
     name: str
-    kind: str                 # matmul | add | rmsnorm | rope | attention | swiglu | source
+    kind: str                 # matmul | add | rmsnorm | rope | attention | swiglu | mul | relu | source
     inputs: Tuple[str, ...]
     outputs: Tuple[str, ...]
     cheap: bool = False
@@ -59,6 +63,11 @@ def grad_rules(op: Op) -> Dict[str, Set[str]]:
     if op.kind == "swiglu":           # act = silu(gate) * up
         g, u = i
         return {g: {"d:" + o, g, u}, u: {"d:" + o, g}}
+    if op.kind == "mul":              # y = a * b, elementwise
+        a, b = i
+        return {a: {"d:" + o, b}, b: {"d:" + o, a}}
+    if op.kind == "relu":             # y = max(x, 0): the gradient passes where y > 0
+        return {i[0]: {"d:" + o, "m:" + o}}
     raise ValueError(op.kind)
 
 
@@ -66,6 +75,13 @@ def prune(ops: List[Op], base_weights: Set[str], trainable: Set[str], graph_outp
           need_input_grad: Set[str] = frozenset()):
     """Returns (A, R, A_step1).  trainable: LoRA weights; need_input_grad: source
     tensors whose gradient is handed to a layer below."""
+    A, R, A1, _ = prune_with_masks(ops, base_weights, trainable, graph_output, need_input_grad)
+    return A, R, A1
+
+
+def prune_with_masks(ops: List[Op], base_weights: Set[str], trainable: Set[str], graph_output: str,
+                     need_input_grad: Set[str] = frozenset()):
+    """Returns (A, R, A_step1, M): M = forward tensors of which only the sign bitmask is read."""
     fwd_out = {t for op in ops for t in op.outputs}
     producer = {t: op for op in ops for t in op.outputs}
     weights = set(base_weights) | set(trainable)
@@ -110,6 +126,7 @@ def prune(ops: List[Op], base_weights: Set[str], trainable: Set[str], graph_outp
                 b_out[name].discard(t)
                 shrink(name)
     A1 = {t for t in fwd_out if any(t in b_in[u] for u in b_in)}
+    M = {t for t in fwd_out if t not in A1 and any("m:" + t in b_in[u] for u in b_in)}
     # ---- step 2: rematerialization ---------------------------------------------
     A, R = set(A1), set()
     for t in sorted(A1):
@@ -117,7 +134,7 @@ def prune(ops: List[Op], base_weights: Set[str], trainable: Set[str], graph_outp
         if n.kind != "source" and n.cheap and all((x in A1) or (x in weights) for x in n.inputs):
             A.discard(t)
             R.add(t)
-    return A, R, A1
+    return A, R, A1, M
 
 
 def decoder_layer_graph(lora_targets, rank_cheap=True):

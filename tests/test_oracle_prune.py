@@ -50,7 +50,7 @@ def demand_closure(ops, base, train, need_input_grad):
         for t in op.inputs:
             consumers.setdefault(t, []).append(op)
     fwd_out = {t for op in ops for t in op.outputs}
-    need_fwd, seen = set(), set()
+    need_fwd, need_mask, seen = set(), set(), set()
 
     def need_grad(t):
         if t in seen:
@@ -60,11 +60,14 @@ def demand_closure(ops, base, train, need_input_grad):
             for dep in P.grad_rules(op)[t]:
                 if dep.startswith("d:"):
                     need_grad(dep[2:])
+                elif dep.startswith("m:"):
+                    need_mask.add(dep[2:])
                 elif dep in fwd_out:
                     need_fwd.add(dep)
 
     for t in list(train) + list(need_input_grad):
         need_grad(t)
+    demand_closure.masks = need_mask - need_fwd
     return need_fwd
 
 
@@ -95,3 +98,48 @@ def test_mlp_with_lora_toy_graph():
            P.Op("add", "add", ("z0", "zl"), ("z",), cheap=True)]
     A, R, A1 = P.prune(ops, {"W1", "W2"}, {"A", "B"}, "z")
     assert A1 == {"h", "u"} and A == {"h"} and R == {"u"}
+
+
+def ia3_graph():
+    """(IA)^3 on the keys of a frozen projection, k = (h Wk) * l_k with l_k learned, followed by a frozen
+    consumer; and a frozen ReLU MLP above it."""
+    return [P.Op("in", "source", (), ("h",)),
+            P.Op("k_base", "matmul", ("h", "Wk"), ("k0",)),
+            P.Op("k_scale", "mul", ("k0", "l_k"), ("k",), cheap=True),
+            P.Op("fc1", "matmul", ("k", "W1"), ("z1",)),
+            P.Op("act", "relu", ("z1",), ("r1",), cheap=True),
+            P.Op("fc2", "matmul", ("r1", "W2"), ("y",))]
+
+
+def test_ia3_and_relu_bitmask():
+    """The gradient of l_k is sum over rows of dk * k0: k0 is kept in full.  The frozen ReLU MLP above
+    only passes the gradient through: of r1 only the sign bitmask is kept, z1 and k not at all."""
+    A, R, A1, M = P.prune_with_masks(ia3_graph(), {"Wk", "W1", "W2"}, {"l_k"}, "y")
+    assert A1 == {"k0"} and A == {"k0"} and R == set() and M == {"r1"}
+    # with a trainable layer below, h is still not needed (dh = dk0 Wk^T reads only the weight)
+    A, R, A1, M = P.prune_with_masks(ia3_graph(), {"Wk", "W1", "W2"}, {"l_k"}, "y", need_input_grad={"h"})
+    assert A1 == {"k0"} and M == {"r1"}
+
+
+def test_bottleneck_adapter_keeps_its_relu_output_in_full():
+    """Adapter y = x1 + relu(x1 Wd) Wu on top of a frozen projection x1 = x W: dWu needs relu's output in
+    full (so no bitmask), dWd needs x1; x itself is needed by nobody."""
+    ops = [P.Op("in", "source", (), ("x",)),
+           P.Op("base", "matmul", ("x", "W"), ("x1",)),
+           P.Op("down", "matmul", ("x1", "Wd"), ("z",), cheap=True),
+           P.Op("act", "relu", ("z",), ("r",), cheap=True),
+           P.Op("up", "matmul", ("r", "Wu"), ("a",), cheap=True),
+           P.Op("add", "add", ("x1", "a"), ("y",), cheap=True)]
+    A, R, A1, M = P.prune_with_masks(ops, {"W"}, {"Wd", "Wu"}, "y")
+    assert A1 == {"x1", "r"} and M == set()
+    # r = relu(z) is cheap but its input z is not stored: it stays stored itself
+    assert A == {"x1", "r"} and R == set()
+
+
+@pytest.mark.parametrize("need_dx", [True, False])
+def test_step1_equals_demand_driven_search_with_masks(need_dx):
+    ops = ia3_graph()
+    nig = {"h"} if need_dx else set()
+    _, _, A1, M = P.prune_with_masks(ops, {"Wk", "W1", "W2"}, {"l_k"}, "y", need_input_grad=nig)
+    assert A1 == demand_closure(ops, {"Wk", "W1", "W2"}, {"l_k"}, nig)
+    assert M == demand_closure.masks
