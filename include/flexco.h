@@ -348,6 +348,45 @@ int32_t flexco_kernel_timer_stop(int32_t kernel_id, double* total_ms, int64_t* l
  * measures end-to-end time may not want on every launch. */
 int32_t flexco_kernel_timer_sample(int32_t kernel_id, int32_t stride);
 
+/* ---- Static graph pruning (Alg. 1, Sec. 5.2), host only -------------------------------------
+ * The forward graph of a PEFT model as integer arrays: operator o has kind op_kind[o], one output
+ * tensor op_out[o] and the input tensors op_in[op_in_off[o] .. op_in_off[o + 1]) in the order of
+ * its kind (matmul: x, w; rmsnorm: x, gain; swiglu: gate, up; mul: a, b; attention: q, k, v; add:
+ * any number; rope, relu: one; source: none - a tensor that enters the graph).  op_cheap[o] != 0
+ * marks operators whose output may be recomputed rather than stored (Alg. 1's cost threshold:
+ * elementwise operators, norms, rank-r products).  tensor_class says which tensors are frozen base
+ * weights (their gradients are what pruning removes), which are trainable (bypass-network) weights;
+ * need_grad[t] != 0 marks tensors whose gradient is handed on outside the graph (the graph input
+ * when a trainable layer sits below).
+ * Result, per tensor: what the backward pass needs of it.  Deterministic; no device work. */
+#define FLEXCO_OP_SOURCE    0
+#define FLEXCO_OP_MATMUL    1
+#define FLEXCO_OP_ADD       2
+#define FLEXCO_OP_RMSNORM   3
+#define FLEXCO_OP_ROPE      4
+#define FLEXCO_OP_ATTENTION 5
+#define FLEXCO_OP_SWIGLU    6
+#define FLEXCO_OP_MUL       7   /* elementwise product, e.g. the learned scaling vectors of (IA)^3 */
+#define FLEXCO_OP_RELU      8   /* backward reads only the sign of the output                       */
+#define FLEXCO_TENSOR_ACTIVATION 0
+#define FLEXCO_TENSOR_FROZEN     1
+#define FLEXCO_TENSOR_TRAINABLE  2
+#define FLEXCO_KEEP_NONE    0   /* not needed by the backward pass (or a weight)                     */
+#define FLEXCO_KEEP_STORE   1   /* store the activation                                              */
+#define FLEXCO_KEEP_REMAT   2   /* recompute it from stored tensors and weights                      */
+#define FLEXCO_KEEP_BITMASK 3   /* store its sign bitmask only (1 bit per element; Sec. 5.2)         */
+typedef struct flexco_graph {
+  int32_t n_ops, n_tensors;
+  const int32_t* op_kind;       /* [n_ops]                        */
+  const int32_t* op_cheap;      /* [n_ops]                        */
+  const int32_t* op_in_off;     /* [n_ops + 1]                    */
+  const int32_t* op_in;         /* [op_in_off[n_ops]] tensor ids  */
+  const int32_t* op_out;        /* [n_ops] tensor ids             */
+  const int32_t* tensor_class;  /* [n_tensors]                    */
+  const int32_t* need_grad;     /* [n_tensors]                    */
+} flexco_graph;
+int32_t flexco_prune_graph(const flexco_graph* graph, int32_t* keep /* [n_tensors], FLEXCO_KEEP_* */);
+
 /* ---- Hybrid token scheduler (Sec. 6.2), host only ------------------------------------------
  * Stage 1 chooses the inference work of an iteration (iteration-level scheduling with chunked
  * prefill); stage 2 appends the largest finetuning window that keeps the estimated iteration

@@ -72,6 +72,16 @@ class FtState(C.Structure):
                                             "lse", "dk_accum", "dv_accum")] + [("saved_u", C.c_void_p * 7)]
 
 
+class Graph(C.Structure):
+    _fields_ = [("n_ops", C.c_int32), ("n_tensors", C.c_int32)] + [(n, C.c_void_p) for n in
+                ("op_kind", "op_cheap", "op_in_off", "op_in", "op_out", "tensor_class", "need_grad")]
+
+
+OP_KINDS = {"source": 0, "matmul": 1, "add": 2, "rmsnorm": 3, "rope": 4, "attention": 5, "swiglu": 6, "mul": 7, "relu": 8}
+TENSOR_ACTIVATION, TENSOR_FROZEN, TENSOR_TRAINABLE = 0, 1, 2
+KEEP_NONE, KEEP_STORE, KEEP_REMAT, KEEP_BITMASK = 0, 1, 2, 3
+
+
 class LmHead(C.Structure):
     _fields_ = [("hidden", C.c_int32), ("vocab", C.c_int32), ("dtype", C.c_int32), ("rms_eps", C.c_float),
                 ("g_final", C.c_void_p), ("w_lm", C.c_void_p)]
@@ -106,6 +116,7 @@ def _load():
         "flexco_lora_bwd": [P(LayerCfg), P(BaseWeights), P(Lora), P(KVPool), vp, i32, P(FtState), i32, i32, vp, vp, vp, sz, vp],
         "flexco_attention_window_bwd": [P(LayerCfg), P(KVPool), vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
         "flexco_gemm": [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp],
+        "flexco_prune_graph": [P(Graph), vp],
         "flexco_kernel_timer_start": [i32, i32],
         "flexco_kernel_timer_stop": [i32, P(C.c_double), P(C.c_int64)],
         "flexco_kernel_timer_sample": [i32, i32],
@@ -132,7 +143,7 @@ EXPORTS = ("flexco_last_error", "flexco_abi_version", "flexco_maps_blob_ints", "
            "flexco_lora_fwd", "flexco_lora_bwd", "flexco_attention_window_bwd", "flexco_gemm",
            "flexco_kernel_timer_start", "flexco_kernel_timer_stop", "flexco_kernel_timer_sample", "flexco_probe_mfma", "flexco_probe_read",
            "flexco_latency_estimate", "flexco_sched_window", "flexco_sched_inference", "flexco_sched_advance",
-           "flexco_lm_loss_workspace_bytes", "flexco_lm_loss", "flexco_adam_step")
+           "flexco_lm_loss_workspace_bytes", "flexco_lm_loss", "flexco_adam_step", "flexco_prune_graph")
 KERNEL_IDS = {"gemm_fwd": 0, "gemm_bwd": 1, "attn_fwd": 2, "attn_merge": 3, "attn_bwd": 4, "elemwise": 5, "lora": 6,
               "generic": 7}
 
@@ -354,6 +365,19 @@ def flexco_sched_advance(entries, prompt_len, prefilled, gen_len, generated, sta
     _check(_lib.flexco_sched_advance(e.shape[1], e[0].ctypes.data, e[1].ctypes.data, e[3].ctypes.data, int(state.size),
                                      prompt_len.ctypes.data, prefilled.ctypes.data, gen_len.ctypes.data,
                                      generated.ctypes.data, state.ctypes.data))
+
+
+def flexco_prune_graph(op_kind, op_cheap, op_inputs, op_out, tensor_class, need_grad):
+    """op_inputs: one list of tensor ids per operator.  -> int32 array [n_tensors] of KEEP_* values"""
+    n_ops, n_t = len(op_kind), len(tensor_class)
+    off = np.zeros(n_ops + 1, dtype=np.int32)
+    off[1:] = np.cumsum([len(i) for i in op_inputs])
+    flat = _i32([t for i in op_inputs for t in i] or [0])
+    arrs = [_i32(op_kind), _i32(op_cheap), off, flat, _i32(op_out), _i32(tensor_class), _i32(need_grad)]
+    g = Graph(n_ops, n_t, *[a.ctypes.data for a in arrs])
+    keep = np.full(n_t, -1, dtype=np.int32)
+    _check(_lib.flexco_prune_graph(C.byref(g), keep.ctypes.data))
+    return keep
 
 
 def flexco_kernel_timer_start(kernel_id, max_launches):

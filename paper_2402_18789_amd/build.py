@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.environ.get("FLEXCO_BUILD_OBJ", os.path.join(ROOT, "_build"))
 LIB = os.environ.get("FLEXCO_BUILD_LIB", os.path.join(HERE, "libflexco.so"))
-SOURCES = ["flexco_maps.cpp", "flexco_sched.cpp", "flexco_api.hip", "kernels_generic.hip", "attn_generic.hip", "gemm_mfma.hip",
+SOURCES = ["flexco_maps.cpp", "flexco_sched.cpp", "flexco_prune.cpp", "flexco_api.hip", "kernels_generic.hip", "attn_generic.hip", "gemm_mfma.hip",
            "attn_mfma.hip", "lora_mfma.hip", "attn_bwd_mfma.hip", "probes.hip", "train_head.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
