@@ -29,14 +29,18 @@ class Case:
     """One layer, one pool, at most one finetune sequence; both sides in lock step."""
 
     def __init__(self, cfg, batch, seed=0, layer=0, kv_split_pages=0, pool_dtype=np.float64, weights=None, lora=None,
-                 keep_u=True, adapters=None):
-        """adapters: optional list of LoRA weight sets indexed by adapter id (several adapters served in one
+                 keep_u=True, adapters=None, gpu_page_shift=0):
+        """gpu_page_shift: the device side keeps every sequence in the physical pages `oracle page id + shift`
+        of a pool that many pages larger (the oracle's results do not depend on which pages hold a
+        sequence), so that a case can sit astride the 2^31-element / 4 GiB offsets of a large pool.
+        adapters: optional list of LoRA weight sets indexed by adapter id (several adapters served in one
         batch); `lora` (default: adapter 0's seeded weights) is then adapters[ft adapter], the one trained."""
         self.cfg, self.seed, self.layer_id = cfg, seed, layer
         self.W = weights if weights is not None else gen.layer_weights(cfg, seed, layer)
         self.lora = lora if lora is not None else gen.lora_weights(cfg, seed, layer)
         self.batch = batch
         self.split = kv_split_pages
+        self.shift = int(gpu_page_shift)
         # oracle state
         self.o_pool = OL.KVPool(batch.num_pages, cfg.page_size, cfg.kv_dim, dtype=pool_dtype)
         self.o_ft = {}
@@ -52,7 +56,7 @@ class Case:
                     dl = HH.DeviceLora(cfg, lo)
                     self._keep.append(dl)
                     self.adapters_d.append(dl.c)
-        self.d_pool = HH.DevicePool(cfg, batch.num_pages)
+        self.d_pool = HH.DevicePool(cfg, batch.num_pages + self.shift)
         self.d_ft = {}
         for r in batch.requests:
             if r.kind == KIND_FINETUNE:
@@ -60,6 +64,10 @@ class Case:
                 self.o_ft[r.seq_id] = OL.FtState(cfg, L)
                 self.d_ft[r.seq_id] = HH.DeviceFtState(cfg, L, keep_u=keep_u)
         self.fill_prefixes(batch)
+
+    def dpages(self, pages):
+        """device-side page ids of an oracle-side page list"""
+        return (np.asarray(pages, dtype=np.int64) + self.shift).astype(np.int32)
 
     def fill_prefixes(self, batch):
         """Seeded K/V rows for every position already cached when the batch starts."""
@@ -70,12 +78,13 @@ class Case:
             pages = batch.seq_pages[r.seq_id]
             slots = self.o_pool.slots(pages, r.start_pos)
             self.o_pool.k[slots], self.o_pool.v[slots] = k, v
-            self.d_pool.write_rows(pages, k, v)
+            self.d_pool.write_rows(self.dpages(pages), k, v)
 
     def forward(self, batch, x, oracle=True, return_all=False):
         """-> (y_gpu, y_oracle or None, device batch)"""
         cfg = self.cfg
-        db = HH.DeviceBatch(cfg, batch.requests, batch.seq_pages, batch.num_pages, self.split)
+        db = HH.DeviceBatch(cfg, batch.requests, {sid: self.dpages(p) for sid, p in batch.seq_pages.items()},
+                            batch.num_pages + self.shift, self.split)
         ws = HH.Workspace(self.dev.c, db.host_maps.T, db.host_maps.n_parts)
         dt = HH.TORCH_DTYPE[cfg.dtype]
         x_d = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to("cuda", dt)
@@ -106,7 +115,7 @@ class Case:
         dt = HH.TORCH_DTYPE[cfg.dtype]
         dY_d = torch.from_numpy(np.ascontiguousarray(dY, dtype=np.float32)).to("cuda", dt)
         dX_d = torch.empty_like(dY_d) if need_dx else None
-        pages_d = torch.from_numpy(np.asarray(pages, dtype=np.int32)).to("cuda")
+        pages_d = torch.from_numpy(self.dpages(pages)).to("cuda")
         B.flexco_lora_bwd(self.dev.c, self.dev.w, self.dev.lora, self.d_pool.c, pages_d, len(pages), st_d.c,
                           win_start, win_len, dY_d, dX_d, ws.ptr, ws.bytes)
         torch.cuda.synchronize()

@@ -219,13 +219,13 @@ def test_attention_window_bwd(cfg_name, win_start, win_len):
 # whole layer: forward iterations, then token-window backward
 # ------------------------------------------------------------------------------------------
 def run_layer_case(cfg, batch0, ft_window, prefill_chunk, bwd_windows, seed=0, split=0, need_dx=True, tol_qk=None,
-                   keep_u=True, adapters=None, ft_adapter=0):
+                   keep_u=True, adapters=None, ft_adapter=0, gpu_page_shift=0):
     """tol_qk: bound for the tensors that depend on the gradient through the softmax logits (dX, the K
     accumulator, dA/dB of q and k) when it differs from the general one (see the callers that pass it)."""
     report = []
     tol = TOL[cfg.dtype]
     tol_qk = tol if tol_qk is None else tol_qk
-    case = Case(cfg, batch0, seed=seed, kv_split_pages=split, keep_u=keep_u, adapters=adapters,
+    case = Case(cfg, batch0, seed=seed, kv_split_pages=split, keep_u=keep_u, adapters=adapters, gpu_page_shift=gpu_page_shift,
                 lora=adapters[ft_adapter] if adapters is not None else None)
     batch, it = batch0, 0
     ft_seq = [r.seq_id for r in batch0.requests if r.kind == KIND_FINETUNE][0]
@@ -237,7 +237,7 @@ def run_layer_case(cfg, batch0, ft_window, prefill_chunk, bwd_windows, seed=0, s
         y_g, y_o, db = case.forward(batch, x)
         assert_close(f"y it{it}", y_g, y_o, tol, report)
         for r, off in zip(batch.requests, np.cumsum([0] + [q.n_new for q in batch.requests])):
-            kg, vg = case.d_pool.read_rows(batch.seq_pages[r.seq_id], r.n_new, r.start_pos)
+            kg, vg = case.d_pool.read_rows(case.dpages(batch.seq_pages[r.seq_id]), r.n_new, r.start_pos)
             sl = case.o_pool.slots(batch.seq_pages[r.seq_id], r.start_pos + r.n_new)[r.start_pos:]
             assert_close(f"K append it{it}", kg, case.o_pool.k[sl], tol)
             assert_close(f"V append it{it}", vg, case.o_pool.v[sl], tol)
@@ -307,6 +307,21 @@ def test_layer_small_bf16():
     say("layer small bf16")
     b = gen.batch_scaled(7, 10, 3, 600, [(0, 130, 130), (256, 64, 400)], [(0, 100, 260)])
     run_layer_case(SMALL_BF16, b, ft_window=160, prefill_chunk=70, bwd_windows=[60, 200], seed=7)
+
+
+def test_layer_small_bf16_pool_astride_4gib():
+    """A paged pool larger than 2^31 elements (4 GiB) per K and V: the batch's pages sit on both sides of
+    that offset, so every kernel that addresses the pool (append, attention forward, its backward) needs
+    64-bit offsets."""
+    say("layer small bf16, pages astride the 4 GiB offset of the pool")
+    cfg = SMALL_BF16
+    b = gen.batch_scaled(9, 8, 3, 500, [(0, 100, 100), (128, 64, 300)], [(0, 96, 224)])
+    page_elems = cfg.n_kv_heads * cfg.page_size * cfg.head_dim
+    boundary_page = (1 << 31) // page_elems
+    shift = boundary_page - b.num_pages // 2
+    case, _ = run_layer_case(cfg, b, ft_window=128, prefill_chunk=70, bwd_windows=[100, 124], seed=9, gpu_page_shift=shift)
+    used = np.concatenate([case.dpages(p) for p in b.seq_pages.values()])
+    assert used.min() < boundary_page <= used.max()
 
 
 def test_layer_small_bf16_group5_all_targets():
