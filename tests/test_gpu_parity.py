@@ -137,7 +137,7 @@ def attention_case(cfg, batch, split, seed=3):
 
 
 @pytest.mark.parametrize("name,split", [("c1", 0), ("c1", 2), ("small_bf16", 0), ("small_bf16", 2), ("g5", 4), ("mha", 2),
-                                        ("g8", 4)])
+                                        ("g8", 4), ("long", 0)])
 def test_attention_mixed(name, split):
     say(f"attention_mixed {name} split={split}")
     if name == "c1":
@@ -148,6 +148,10 @@ def test_attention_mixed(name, split):
     elif name == "g5":
         cfg = SMALL_BF16_G5
         batch = gen.batch_scaled(5, 7, 17, 333, [(0, 40, 40)], [(64, 100, 164)])
+    elif name == "long":                     # the longest contexts of the larger configurations: 16 key splits
+        cfg = SMALL_BF16
+        batch = gen.mixed_batch(16, 8, decode_ctx=(16384, 8191, 4097, 1), prefill=[(7000, 100, 7100)],
+                                finetune=[(3840, 256, 4096)])
     elif name == "mha":
         cfg = SMALL_BF16_MHA                 # 16 tokens per tile, 64 per work item
         batch = gen.batch_scaled(6, 5, 9, 200, [(0, 150, 150), (40, 77, 117)], [(30, 100, 130)])
@@ -172,6 +176,8 @@ def test_attention_mixed(name, split):
     ("mha", 70, 90),                # kv group of 1: the second half of a dK/dV block has no head of its own
     ("g8", 17, 50),                 # kv group of 8
     ("c1", 5, 6),                   # fp32 generic path
+    ("small_bf16", 3840, 256),      # the last window of a 4096-token sequence
+    ("small_bf16", 8000, 192),      # of an 8192-token one
 ])
 def test_attention_window_bwd(cfg_name, win_start, win_len):
     say(f"attention_window_bwd {cfg_name} window [{win_start}, +{win_len})")
