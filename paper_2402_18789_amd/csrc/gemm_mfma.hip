@@ -462,16 +462,23 @@ int32_t launch_cfg(const void* A, const void* W, void* C, const void* bias, cons
   // the dispatch itself)
   hipEvent_t e0 = nullptr, e1 = nullptr;
   if (timer_id >= 0) (void)kernel_timer_pair(timer_id, &e0, &e1, first_of_call);
-  hipExtLaunchKernelGGL(kern, dim3(tiles_m * tiles_n, splits), dim3(256), 0, s, e0, e1, 0, (const bf16_t*)A,
-                        (const bf16_t*)W, (bf16_t*)C, (const bf16_t*)bias, (const bf16_t*)res, M, N, K, lda, ldw, ldc, ldr,
-                        tiles_m, tiles_n, ext, splits > 1 ? part : nullptr, K / splits, glu);
+  // (the plain launch when no pair is due: it is the form a stream capture records)
+#define FLEXCO_LAUNCH_TIMED(kern_, grid_, ...)                                                        \
+  {                                                                                                   \
+    if (e0) hipExtLaunchKernelGGL(kern_, grid_, dim3(256), 0, s, e0, e1, 0, __VA_ARGS__);             \
+    else hipLaunchKernelGGL(kern_, grid_, dim3(256), 0, s, __VA_ARGS__);                              \
+  }
+  FLEXCO_LAUNCH_TIMED(kern, dim3(tiles_m * tiles_n, splits), (const bf16_t*)A, (const bf16_t*)W, (bf16_t*)C,
+                      (const bf16_t*)bias, (const bf16_t*)res, M, N, K, lda, ldw, ldc, ldr, tiles_m, tiles_n, ext,
+                      splits > 1 ? part : nullptr, K / splits, glu)
   if (splits > 1) {
     const size_t quads = ((size_t)M * N + 3) / 4;
     e0 = e1 = nullptr;
     if (timer_id >= 0) (void)kernel_timer_pair(timer_id, &e0, &e1, false);
-    hipExtLaunchKernelGGL(gemm_splitk_reduce_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s, e0, e1, 0,
-                          part, splits, (bf16_t*)C, (const bf16_t*)bias, (const bf16_t*)res, M, N, ldc, ldr);
+    FLEXCO_LAUNCH_TIMED(gemm_splitk_reduce_kernel, dim3((unsigned)((quads + 255) / 256)), part, splits, (bf16_t*)C,
+                        (const bf16_t*)bias, (const bf16_t*)res, M, N, ldc, ldr)
   }
+#undef FLEXCO_LAUNCH_TIMED
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(FLEXCO_EHIP, "launch of gemm_bf16 failed: %s", hipGetErrorString(e));
   return FLEXCO_OK;

@@ -82,6 +82,13 @@ def lora_weights(cfg: LayerCfg, seed: int, layer: int = 0, adapter: int = 0, b_s
     return out
 
 
+def ia3_weights(cfg: LayerCfg, seed: int, layer: int = 0, adapter: int = 0, std=0.25):
+    """(IA)^3 scaling vectors {"k", "v": [kv_dim], "ff": [ffn]}, 1 + N(0, std) in the storage type (the
+    method starts them at one; a trained adapter has moved away from it, so that a dropped scale shows)."""
+    return {name: normal(cfg, rng(seed, cfg.name, layer, "ia3", adapter, name), (n,), std=std, mean=1.0)
+            for name, n in (("k", cfg.kv_dim), ("v", cfg.kv_dim), ("ff", cfg.ffn))}
+
+
 def layer_input(cfg: LayerCfg, seed: int, T: int, tag="x") -> np.ndarray:
     return normal(cfg, rng(seed, cfg.name, tag), (T, cfg.hidden))
 
