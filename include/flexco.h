@@ -191,6 +191,8 @@ typedef struct flexco_kv_pool {
  * saved_u[t] (optional, NULL = not kept): the rank-r product x_t A_t^T of LoRA target t in fp32
  * (4 r bytes per token and target): with it the backward pass does not multiply the saved inputs
  * by A_t again for the dB_t gradient.  Either every target of cfg.lora_targets has one or none.
+ * saved_k0 / saved_v0: only for the (IA)^3 entry points, the other operand of the two products whose
+ * vectors are trained (2 nkv d elements per token on top of the set above).
  * dk_accum / dv_accum: the statically allocated KV-gradient accumulator of Sec. 7. */
 typedef struct flexco_ft_state {
   int32_t seq_len;
@@ -204,6 +206,8 @@ typedef struct flexco_ft_state {
   float* dk_accum;    /* [L, nkv d] float             */
   float* dv_accum;    /* [L, nkv d] float             */
   float* saved_u[FLEXCO_N_TARGETS];   /* [L, r] float or NULL */
+  void*  saved_k0;    /* [L, nkv d] key projection output before the (IA)^3 scale; NULL unless (IA)^3 */
+  void*  saved_v0;    /* [L, nkv d] value projection output before the (IA)^3 scale; NULL unless (IA)^3 */
 } flexco_ft_state;
 
 /* Message for the last failing call on this thread ("" if none). */
@@ -305,6 +309,37 @@ int32_t flexco_lora_bwd(const flexco_layer_cfg* cfg, const flexco_base_weights* 
                         const int32_t* seq_pages, int32_t n_seq_pages,
                         const flexco_ft_state* ft, int32_t win_start, int32_t win_len,
                         const void* dY, void* dX, void* ws, size_t ws_bytes, void* stream);
+
+/* (IA)^3 as a bypass network (Sec. 4.1: Y = X (.) l = X + X (.) (l - 1)): three learned vectors per
+ * layer, on the key projection's output (before its rotation), on the value projection's output and
+ * on the SwiGLU product the down projection reads.  Device pointers; l_* in the dtype of cfg;
+ * dl_* fp32, accumulated into by flexco_ia3_bwd (may be NULL for the forward pass). */
+typedef struct flexco_ia3 {
+  const void* l_k;    /* [nkv d] */
+  const void* l_v;    /* [nkv d] */
+  const void* l_ff;   /* [F]     */
+  float* dl_k;        /* [nkv d] */
+  float* dl_v;        /* [nkv d] */
+  float* dl_ff;       /* [F]     */
+} flexco_ia3;
+
+/* flexco_layer_forward with an (IA)^3 network in place of LoRA (cfg->lora_targets must be 0): rows of
+ * requests with adapter >= 0 are scaled, rows with adapter -1 run the base model.  Rows of the finetune
+ * window store, besides the set of flexco_layer_forward, the unscaled key and value rows in
+ * ft->saved_k0 / saved_v0 (both required when ft is given).  Everything else as flexco_layer_forward. */
+int32_t flexco_layer_forward_ia3(const flexco_layer_cfg* cfg, const flexco_base_weights* w,
+                                 const flexco_ia3* ia3, const flexco_maps* maps, const void* x_in,
+                                 void* x_out, const flexco_kv_pool* pool, const flexco_ft_state* ft,
+                                 void* ws, size_t ws_bytes, void* stream);
+
+/* Token-level backward of one window through a layer with an (IA)^3 network (Alg. 2's Backward / Add /
+ * Slice / CalculateGrads steps with the products' gradients in place of LoRA's): dl_k, dl_v, dl_ff are
+ * accumulated (column sums over the window's rows, added in a fixed order), dX as in flexco_lora_bwd
+ * (NULL: not computed; the vectors are still trained).  Arguments and effects as flexco_lora_bwd. */
+int32_t flexco_ia3_bwd(const flexco_layer_cfg* cfg, const flexco_base_weights* w, const flexco_ia3* ia3,
+                       const flexco_kv_pool* pool, const int32_t* seq_pages, int32_t n_seq_pages,
+                       const flexco_ft_state* ft, int32_t win_start, int32_t win_len, const void* dY,
+                       void* dX, void* ws, size_t ws_bytes, void* stream);
 
 /* Attention backward of one window (the attention part of flexco_lora_bwd, exported for
  * unit parity).  q, out, dout: device [win_len, nq d] rows of the window (q after RoPE);

@@ -20,7 +20,7 @@ FLEXCO_DECODE, FLEXCO_PREFILL, FLEXCO_FINETUNE = 0, 1, 2
 FLEXCO_REQ_WAITING, FLEXCO_REQ_RUNNING, FLEXCO_REQ_FINISHED = 0, 1, 2
 TARGET_NAMES = ("q", "k", "v", "o", "gate", "up", "down")
 N_TARGETS = 7
-ABI_VERSION = 3
+ABI_VERSION = 4
 
 
 class FlexcoError(RuntimeError):
@@ -69,7 +69,12 @@ class KVPool(C.Structure):
 class FtState(C.Structure):
     _fields_ = [("seq_len", C.c_int32)] + [(n, C.c_void_p) for n in
                                            ("q_cache", "saved_x", "saved_x2", "saved_gate", "saved_up", "saved_attn",
-                                            "lse", "dk_accum", "dv_accum")] + [("saved_u", C.c_void_p * 7)]
+                                            "lse", "dk_accum", "dv_accum")] + [("saved_u", C.c_void_p * 7)] + \
+               [("saved_k0", C.c_void_p), ("saved_v0", C.c_void_p)]
+
+
+class Ia3(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("l_k", "l_v", "l_ff", "dl_k", "dl_v", "dl_ff")]
 
 
 class Graph(C.Structure):
@@ -111,6 +116,8 @@ def _load():
         "flexco_layer_forward": [P(LayerCfg), P(BaseWeights), P(Lora), P(Maps), vp, vp, P(KVPool), P(FtState), vp, sz, vp],
         "flexco_layer_forward_multi": [P(LayerCfg), P(BaseWeights), P(Lora), i32, P(Maps), vp, vp, P(KVPool), P(FtState), vp,
                                        sz, vp],
+        "flexco_layer_forward_ia3": [P(LayerCfg), P(BaseWeights), P(Ia3), P(Maps), vp, vp, P(KVPool), P(FtState), vp, sz, vp],
+        "flexco_ia3_bwd": [P(LayerCfg), P(BaseWeights), P(Ia3), P(KVPool), vp, i32, P(FtState), i32, i32, vp, vp, vp, sz, vp],
         "flexco_attention_mixed": [P(LayerCfg), P(Maps), vp, P(KVPool), vp, vp, vp, sz, vp],
         "flexco_lora_fwd": [vp, vp, i32, i32, i32, i32, f32, i32, P(vp), P(vp), i32, P(i32), P(i32), i32, vp, vp],
         "flexco_lora_bwd": [P(LayerCfg), P(BaseWeights), P(Lora), P(KVPool), vp, i32, P(FtState), i32, i32, vp, vp, vp, sz, vp],
@@ -143,7 +150,8 @@ EXPORTS = ("flexco_last_error", "flexco_abi_version", "flexco_maps_blob_ints", "
            "flexco_lora_fwd", "flexco_lora_bwd", "flexco_attention_window_bwd", "flexco_gemm",
            "flexco_kernel_timer_start", "flexco_kernel_timer_stop", "flexco_kernel_timer_sample", "flexco_probe_mfma", "flexco_probe_read",
            "flexco_latency_estimate", "flexco_sched_window", "flexco_sched_inference", "flexco_sched_advance",
-           "flexco_lm_loss_workspace_bytes", "flexco_lm_loss", "flexco_adam_step", "flexco_prune_graph")
+           "flexco_lm_loss_workspace_bytes", "flexco_lm_loss", "flexco_adam_step", "flexco_prune_graph",
+           "flexco_layer_forward_ia3", "flexco_ia3_bwd")
 KERNEL_IDS = {"gemm_fwd": 0, "gemm_bwd": 1, "attn_fwd": 2, "attn_merge": 3, "attn_bwd": 4, "elemwise": 5, "lora": 6,
               "generic": 7}
 
@@ -256,6 +264,16 @@ def flexco_layer_forward_multi(cfg, w, adapters, maps, x_in, x_out, pool, ft, ws
 def flexco_layer_forward(cfg, w, lora, maps, x_in, x_out, pool, ft, ws, ws_bytes, stream=None):
     _check(_lib.flexco_layer_forward(C.byref(cfg), C.byref(w), _opt(lora), C.byref(maps), _ptr(x_in), _ptr(x_out),
                                      C.byref(pool), _opt(ft), _ptr(ws), ws_bytes, _stream(stream)))
+
+
+def flexco_layer_forward_ia3(cfg, w, ia3, maps, x_in, x_out, pool, ft, ws, ws_bytes, stream=None):
+    _check(_lib.flexco_layer_forward_ia3(C.byref(cfg), C.byref(w), _opt(ia3), C.byref(maps), _ptr(x_in), _ptr(x_out),
+                                         C.byref(pool), _opt(ft), _ptr(ws), ws_bytes, _stream(stream)))
+
+
+def flexco_ia3_bwd(cfg, w, ia3, pool, seq_pages, n_seq_pages, ft, win_start, win_len, dY, dX, ws, ws_bytes, stream=None):
+    _check(_lib.flexco_ia3_bwd(C.byref(cfg), C.byref(w), _opt(ia3), C.byref(pool), _ptr(seq_pages), n_seq_pages,
+                               C.byref(ft), win_start, win_len, _ptr(dY), _ptr(dX), _ptr(ws), ws_bytes, _stream(stream)))
 
 
 def flexco_attention_mixed(cfg, maps, q, pool, out, lse, ws, ws_bytes, stream=None):

@@ -159,6 +159,7 @@ struct BwdWs {
   float *delta, *u, *t;
   float* gemm_part;        // split-K partial sums of the input-gradient GEMMs
   size_t gemm_part_elems;
+  float* colsum_part;      // per-chunk column sums of the (IA)^3 vector gradients: [ceil(n / 32)][max(F, nkv d)]
   LoraWs lw;
   size_t bytes;
 };
@@ -210,6 +211,8 @@ BwdWs carve_bwd(const flexco_layer_cfg& c, int n, void* base) {
   w.t = (float*)cv.take(sizeof(float) * n * r);
   w.gemm_part_elems = c.dtype == FLEXCO_BF16 ? (size_t)n * SPLITK_COLS : 0;
   w.gemm_part = (float*)cv.take(sizeof(float) * w.gemm_part_elems);
+  w.colsum_part = (float*)cv.take(sizeof(float) * (size_t)((n + 31) / 32) *
+                                  std::max<size_t>(c.ffn, (size_t)c.n_kv_heads * c.head_dim));
   carve_lora(c, n, true, cv, w.lw);
   w.bytes = cv.off;
   return w;
@@ -255,6 +258,15 @@ int32_t check_lora(const flexco_layer_cfg& c, const flexco_lora* l, bool need_gr
     FLEXCO_CHECK(aligned16(l->A[t]) && aligned16(l->B[t]), FLEXCO_EINVAL, "LoRA target %d: misaligned", t);
     if (need_grads) FLEXCO_CHECK(l->dA[t] && l->dB[t], FLEXCO_EINVAL, "LoRA target %d: dA or dB is NULL", t);
   }
+  return FLEXCO_OK;
+}
+
+int32_t check_ia3(const flexco_layer_cfg& c, const flexco_ia3* a, bool need_grads) {
+  FLEXCO_CHECK(a != nullptr, FLEXCO_EINVAL, "ia3 is NULL");
+  FLEXCO_CHECK(c.lora_targets == 0, FLEXCO_EUNSUPPORTED, "an (IA)^3 call takes a configuration without LoRA targets");
+  FLEXCO_CHECK(a->l_k && a->l_v && a->l_ff, FLEXCO_EINVAL, "an (IA)^3 vector is NULL");
+  FLEXCO_CHECK(aligned16(a->l_k) && aligned16(a->l_v) && aligned16(a->l_ff), FLEXCO_EINVAL, "an (IA)^3 vector is misaligned");
+  if (need_grads) FLEXCO_CHECK(a->dl_k && a->dl_v && a->dl_ff, FLEXCO_EINVAL, "an (IA)^3 gradient vector is NULL");
   return FLEXCO_OK;
 }
 
@@ -670,13 +682,19 @@ extern "C" int32_t flexco_lora_fwd(const void* x, void* y, int32_t T, int32_t in
 
 static int32_t layer_forward_impl(const flexco_layer_cfg* cfg, const flexco_base_weights* w, const Adapters& ad,
                                   const flexco_maps* maps, const void* x_in, void* x_out, const flexco_kv_pool* pool,
-                                  const flexco_ft_state* ft, void* ws, size_t ws_bytes, void* stream) {
+                                  const flexco_ft_state* ft, void* ws, size_t ws_bytes, void* stream,
+                                  const flexco_ia3* ia3 = nullptr) {
   FLEXCO_TRY(check_cfg(cfg));
   FLEXCO_TRY(check_weights(w));
   FLEXCO_TRY(check_maps(*cfg, maps));
   FLEXCO_TRY(check_pool(*cfg, pool));
   const flexco_layer_cfg& c = *cfg;
   const flexco_maps& m = *maps;
+  if (ia3) {
+    FLEXCO_TRY(check_ia3(c, ia3, false));
+    FLEXCO_CHECK(!ft || (ft->saved_k0 && ft->saved_v0 && aligned16(ft->saved_k0) && aligned16(ft->saved_v0)),
+                 FLEXCO_EINVAL, "ft state: saved_k0 / saved_v0 are required with (IA)^3");
+  }
   if (m.n_lora > 0 && c.lora_targets != 0) {
     FLEXCO_CHECK(ad.ads != nullptr && ad.n >= 1, FLEXCO_EINVAL, "the batch has adapter tokens but no adapter is given");
     FLEXCO_CHECK(ad.any_id || m.n_adapters <= ad.n, FLEXCO_EINVAL, "the batch uses adapter id %d, %d adapters are given",
@@ -712,6 +730,15 @@ static int32_t layer_forward_impl(const flexco_layer_cfg* cfg, const flexco_base
     const int tg[3] = {FLEXCO_T_Q, FLEXCO_T_K, FLEXCO_T_V}, c0[3] = {0, qd, qd + kd};
     FLEXCO_TRY(forward_projection(c, ad, m, k.h, H, w->wqkv, w->bqkv, nullptr, 0, k.qkv, qkvd, tg, c0, 3, k, ft, s));
   }
+  if (ia3 && m.n_lora > 0) {   // keys and values of the adapter's rows, scaled before the rotation and the append
+    Ia3ScaleArgs sa;
+    memset(&sa, 0, sizeof(sa));
+    sa.n_seg = 2;
+    sa.col0[0] = qd; sa.width[0] = kd; sa.l[0] = ia3->l_k; sa.save[0] = ft ? ft->saved_k0 : nullptr; sa.ld_save[0] = kd;
+    sa.col0[1] = qd + kd; sa.width[1] = kd; sa.l[1] = ia3->l_v; sa.save[1] = ft ? ft->saved_v0 : nullptr; sa.ld_save[1] = kd;
+    sa.ft_tok0 = m.ft_tok0; sa.n_ft = ft ? m.n_ft : 0; sa.ft_pos0 = m.ft_pos0;
+    EW(launch_ia3_scale_rows(k.qkv, qkvd, m.lora_tok, m.n_lora, sa, dt, s));
+  }
   EW(launch_rope_append(c, k.qkv, m.tok_pos, m.slot, *pool, T, m.ft_tok0, m.n_ft, m.ft_pos0,
                         ft ? ft->q_cache : nullptr, s));
   FLEXCO_TRY(run_attention(c, m, k.qkv, qkvd, *pool, k.attn, qd, ft ? k.lse : nullptr, k.part_ml, k.part_acc, s));
@@ -727,6 +754,12 @@ static int32_t layer_forward_impl(const flexco_layer_cfg* cfg, const flexco_base
     FLEXCO_TRY(forward_projection(c, ad, m, k.h, H, w->wgu, nullptr, nullptr, 0, k.gu, 2 * F, tg, c0, 2, k, ft, s, &glu));
   }
   if (!glu.done) EW(launch_swiglu(k.gu, k.act, T, F, dt, s));
+  if (ia3 && m.n_lora > 0) {   // the SwiGLU product of the adapter's rows
+    Ia3ScaleArgs sa;
+    memset(&sa, 0, sizeof(sa));
+    sa.n_seg = 1; sa.col0[0] = 0; sa.width[0] = F; sa.l[0] = ia3->l_ff;
+    EW(launch_ia3_scale_rows(k.act, F, m.lora_tok, m.n_lora, sa, dt, s));
+  }
   {
     const int tg[1] = {FLEXCO_T_DOWN}, c0[1] = {0};
     FLEXCO_TRY(forward_projection(c, ad, m, k.act, F, w->wd, nullptr, k.x2, H, x_out, H, tg, c0, 1, k, ft, s));
@@ -763,6 +796,16 @@ extern "C" int32_t flexco_layer_forward(const flexco_layer_cfg* cfg, const flexc
   clear_error();
   const Adapters ad{lora, lora ? 1 : 0, true};
   return layer_forward_impl(cfg, w, ad, maps, x_in, x_out, pool, ft, ws, ws_bytes, stream);
+}
+
+extern "C" int32_t flexco_layer_forward_ia3(const flexco_layer_cfg* cfg, const flexco_base_weights* w,
+                                            const flexco_ia3* ia3, const flexco_maps* maps, const void* x_in,
+                                            void* x_out, const flexco_kv_pool* pool, const flexco_ft_state* ft,
+                                            void* ws, size_t ws_bytes, void* stream) {
+  clear_error();
+  FLEXCO_CHECK(ia3 != nullptr, FLEXCO_EINVAL, "ia3 is NULL");
+  const Adapters ad{nullptr, 0, true};
+  return layer_forward_impl(cfg, w, ad, maps, x_in, x_out, pool, ft, ws, ws_bytes, stream, ia3);
 }
 
 extern "C" int32_t flexco_layer_forward_multi(const flexco_layer_cfg* cfg, const flexco_base_weights* w,
@@ -812,17 +855,22 @@ extern "C" int32_t flexco_attention_window_bwd(const flexco_layer_cfg* cfg, cons
                                    dv_accum, (float*)ws, (hipStream_t)stream);
 }
 
-extern "C" int32_t flexco_lora_bwd(const flexco_layer_cfg* cfg, const flexco_base_weights* w,
-                                   const flexco_lora* lora, const flexco_kv_pool* pool, const int32_t* seq_pages,
-                                   int32_t n_seq_pages, const flexco_ft_state* ft, int32_t win_start, int32_t win_len,
-                                   const void* dY, void* dX, void* ws, size_t ws_bytes, void* stream) {
-  clear_error();
+// One token window backward through the layer; the bypass network is LoRA (`lora`, per cfg.lora_targets) or
+// (IA)^3 (`ia3`, cfg without LoRA targets) or none.
+static int32_t layer_backward_impl(const flexco_layer_cfg* cfg, const flexco_base_weights* w,
+                                   const flexco_lora* lora, const flexco_ia3* ia3, const flexco_kv_pool* pool,
+                                   const int32_t* seq_pages, int32_t n_seq_pages, const flexco_ft_state* ft,
+                                   int32_t win_start, int32_t win_len, const void* dY, void* dX, void* ws,
+                                   size_t ws_bytes, void* stream) {
   FLEXCO_TRY(check_cfg(cfg));
   FLEXCO_TRY(check_weights(w));
   FLEXCO_TRY(check_pool(*cfg, pool));
   const flexco_layer_cfg& c = *cfg;
   FLEXCO_TRY(check_lora(c, lora, true));
+  if (ia3) FLEXCO_TRY(check_ia3(c, ia3, true));
   FLEXCO_CHECK(ft && seq_pages && dY && ws, FLEXCO_EINVAL, "NULL argument");
+  FLEXCO_CHECK(!ia3 || (ft->saved_k0 && ft->saved_v0 && aligned16(ft->saved_k0) && aligned16(ft->saved_v0)),
+               FLEXCO_EINVAL, "ft state: saved_k0 / saved_v0 are required with (IA)^3");
   FLEXCO_CHECK(ft->q_cache && ft->saved_x && ft->saved_x2 && ft->saved_gate && ft->saved_up && ft->saved_attn &&
                    ft->lse && ft->dk_accum && ft->dv_accum, FLEXCO_EINVAL, "ft state has a NULL buffer");
   FLEXCO_TRY(check_saved_u(c, ft));
@@ -882,6 +930,10 @@ extern "C" int32_t flexco_lora_bwd(const flexco_layer_cfg* cfg, const flexco_bas
 
   // ---- MLP side: down projection, SwiGLU, gate/up projections, second norm -------------
   FLEXCO_TRY(backward_projection(c, lora, n, dY, H, w->wd, k.dact, grp[0], k, outer, s));
+  if (ia3) {   // dl_ff += colsum(dact (.) act0) with the rematerialised SwiGLU product; dact <- dact (.) l_ff
+    EW(launch_swiglu_remat(gate_w, up_w, k.act, n, F, dt, s));
+    EW(launch_ia3_colgrad(k.dact, F, k.act, F, ia3->l_ff, k.colsum_part, ia3->dl_ff, n, F, dt, s));
+  }
   EW(launch_swiglu_bwd(gate_w, up_w, k.dact, k.dgu, n, F, dt, s, act_late ? k.act : nullptr));
   FLEXCO_TRY(backward_projection(c, lora, n, k.dgu, 2 * F, w->wgu, k.dh, grp[1], k, outer, s));
   EW(launch_rmsnorm_bwd(x2_w, w->g2, k.dh, dY, k.dx2, n, H, c.rms_eps, dt, s, hn2_late ? k.hn2 : nullptr));
@@ -891,12 +943,38 @@ extern "C" int32_t flexco_lora_bwd(const flexco_layer_cfg* cfg, const flexco_bas
   FLEXCO_TRY(attention_window_bwd_impl(c, *pool, seq_pages, win_start, win_len, q_w, attn_w, lse_w, k.dattn, k.dq,
                                        ft->dk_accum, ft->dv_accum, k.delta, s));
   // ---- q/k/v side: the window's accumulator rows are complete now (Sec. 7) ---------------
-  if (dX || qkv_lora) {
+  if (dX || qkv_lora || ia3) {
     EW(launch_rope_bwd_pack(c, k.dq, ft->dk_accum + w0 * kd, ft->dv_accum + w0 * kd, k.dqkv, win_start, n, s));
-    FLEXCO_TRY(backward_projection(c, lora, n, k.dqkv, qkvd, w->wqkv, dX ? k.dh : nullptr, grp[3], k, outer, s));
+    if (ia3) {   // the k and v column ranges of the packed rows: dl += colsum(d (.) unscaled rows), d <- d (.) l
+      EW(launch_ia3_colgrad(boff(k.dqkv, qd, e), qkvd, boff(ft->saved_k0, w0 * kd, e), kd, ia3->l_k, k.colsum_part,
+                            ia3->dl_k, n, kd, dt, s));
+      EW(launch_ia3_colgrad(boff(k.dqkv, qd + kd, e), qkvd, boff(ft->saved_v0, w0 * kd, e), kd, ia3->l_v, k.colsum_part,
+                            ia3->dl_v, n, kd, dt, s));
+    }
+    if (dX || qkv_lora)
+      FLEXCO_TRY(backward_projection(c, lora, n, k.dqkv, qkvd, w->wqkv, dX ? k.dh : nullptr, grp[3], k, outer, s));
   }
   // ---- every queued dA / dB product of the window in one launch ----------------------------
   if (dX) EW(launch_rmsnorm_bwd(x_w, w->g1, k.dh, k.dx2, dX, n, H, c.rms_eps, dt, s, hn_late ? k.hn : nullptr));
   LR(launch_lora_outer_batch(outer, s));
   return FLEXCO_OK;
+}
+
+extern "C" int32_t flexco_lora_bwd(const flexco_layer_cfg* cfg, const flexco_base_weights* w,
+                                   const flexco_lora* lora, const flexco_kv_pool* pool, const int32_t* seq_pages,
+                                   int32_t n_seq_pages, const flexco_ft_state* ft, int32_t win_start, int32_t win_len,
+                                   const void* dY, void* dX, void* ws, size_t ws_bytes, void* stream) {
+  clear_error();
+  return layer_backward_impl(cfg, w, lora, nullptr, pool, seq_pages, n_seq_pages, ft, win_start, win_len, dY, dX, ws,
+                             ws_bytes, stream);
+}
+
+extern "C" int32_t flexco_ia3_bwd(const flexco_layer_cfg* cfg, const flexco_base_weights* w, const flexco_ia3* ia3,
+                                  const flexco_kv_pool* pool, const int32_t* seq_pages, int32_t n_seq_pages,
+                                  const flexco_ft_state* ft, int32_t win_start, int32_t win_len, const void* dY,
+                                  void* dX, void* ws, size_t ws_bytes, void* stream) {
+  clear_error();
+  FLEXCO_CHECK(ia3 != nullptr, FLEXCO_EINVAL, "ia3 is NULL");
+  return layer_backward_impl(cfg, w, nullptr, ia3, pool, seq_pages, n_seq_pages, ft, win_start, win_len, dY, dX, ws,
+                             ws_bytes, stream);
 }

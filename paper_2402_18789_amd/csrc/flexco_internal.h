@@ -130,6 +130,20 @@ int32_t launch_swiglu(const void* gu, void* act, int T, int F, int dtype, hipStr
 int32_t launch_swiglu_bwd(const void* gate, const void* up, const void* dact, void* dgu, int n, int F, int dtype,
                           hipStream_t s, void* act = nullptr);
 int32_t launch_swiglu_remat(const void* gate, const void* up, void* act, int n, int F, int dtype, hipStream_t s);
+// (IA)^3 forward scale of up to two column ranges of the listed token rows (see ia3_scale_rows_kernel)
+struct Ia3ScaleArgs {
+  int n_seg;
+  int col0[2], width[2];
+  const void* l[2];
+  void* save[2];          // unscaled values of the finetune window's rows, or NULL
+  size_t ld_save[2];
+  int ft_tok0, n_ft, ft_pos0;
+};
+int32_t launch_ia3_scale_rows(void* buf, size_t ld, const int32_t* tok, int n_tok, const Ia3ScaleArgs& a, int dtype,
+                              hipStream_t s);
+// dl[c] += sum_r G[r, c] X[r, c];  G[r, c] *= l[c];  part: float [ceil(n / 32)][C] scratch
+int32_t launch_ia3_colgrad(void* G, size_t ldg, const void* X, size_t ldx, const void* l, float* part, float* dl, int n,
+                           int C, int dtype, hipStream_t s);
 struct CopyRowsBatch {
   const char* src[8]; size_t ld_src[8];
   char* dst[8]; size_t ld_dst[8];

@@ -232,6 +232,59 @@ __global__ __launch_bounds__(256) void rope_bwd_pack_kernel(const T* __restrict_
 }
 
 // --------------------------------------------------------------------------------------
+// (IA)^3 bypass network (Sec. 4.1: Y = X + X (.) (l - 1) = X (.) l on the adapter's rows).
+// Forward: one block per listed token; up to two column ranges of the row, each with its own vector;
+// rows of the finetune window first keep the unscaled values (the other operand of the product, which
+// the vector's gradient needs).
+// --------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void ia3_scale_rows_kernel(T* __restrict__ buf, size_t ldb,
+                                                             const int32_t* __restrict__ tok, Ia3ScaleArgs a) {
+  const int t = tok[blockIdx.x];
+  T* row = buf + (size_t)t * ldb;
+  const bool is_ft = t >= a.ft_tok0 && t < a.ft_tok0 + a.n_ft;
+  for (int sg = 0; sg < a.n_seg; ++sg) {
+    const T* l = (const T*)a.l[sg];
+    T* sv = (is_ft && a.save[sg]) ? (T*)a.save[sg] + (size_t)(a.ft_pos0 + (t - a.ft_tok0)) * a.ld_save[sg] : nullptr;
+    T* p = row + a.col0[sg];
+    for (int c = threadIdx.x; c < a.width[sg]; c += 256) {
+      const T v = p[c];
+      if (sv) sv[c] = v;
+      st(p + c, (float)v * ld(l + c));
+    }
+  }
+}
+
+// Backward of the product Y = X (.) l over a window of n rows: G holds dY.  Per chunk of 32 rows and per
+// column, part[chunk][c] = sum_r G[r, c] X[r, c] (the chunk's share of dl[c]), and G[r, c] <- G[r, c] l[c]
+// (= dX) in place.  The second kernel adds the chunks in order into dl: no atomics, a fixed order.
+template <typename T>
+__global__ __launch_bounds__(256) void ia3_colgrad_kernel(T* __restrict__ G, size_t ldg, const T* __restrict__ X,
+                                                          size_t ldx, const T* __restrict__ l,
+                                                          float* __restrict__ part, int n, int C) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= C) return;
+  const int r0 = blockIdx.y * 32, r1 = min(r0 + 32, n);
+  const float lc = ld(l + c);
+  float acc = 0.f;
+  for (int r = r0; r < r1; ++r) {
+    const float g = ld(G + (size_t)r * ldg + c);
+    acc += g * ld(X + (size_t)r * ldx + c);
+    st(G + (size_t)r * ldg + c, g * lc);
+  }
+  part[(size_t)blockIdx.y * C + c] = acc;
+}
+
+__global__ __launch_bounds__(256) void ia3_colgrad_finalize_kernel(const float* __restrict__ part, int chunks, int C,
+                                                                   float* __restrict__ dl) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= C) return;
+  float acc = 0.f;
+  for (int k = 0; k < chunks; ++k) acc += part[(size_t)k * C + c];
+  dl[c] += acc;
+}
+
+// --------------------------------------------------------------------------------------
 // SwiGLU forward / backward
 // --------------------------------------------------------------------------------------
 template <typename T, bool VEC>
@@ -545,6 +598,23 @@ int32_t launch_rope_bwd_pack(const flexco_layer_cfg& c, const void* dq, const fl
                                          dk_rows, dv_rows, (T*)dqkv, c.n_q_heads, c.n_kv_heads, c.head_dim,
                                          c.rope_theta, win_start));
   return post_launch("rope_bwd_pack");
+}
+
+int32_t launch_ia3_scale_rows(void* buf, size_t ld, const int32_t* tok, int n_tok, const Ia3ScaleArgs& a, int dtype,
+                              hipStream_t s) {
+  if (n_tok == 0 || a.n_seg == 0) return FLEXCO_OK;
+  DISPATCH_T(dtype, hipLaunchKernelGGL((ia3_scale_rows_kernel<T>), dim3(n_tok), dim3(256), 0, s, (T*)buf, ld, tok, a));
+  return post_launch("ia3_scale_rows");
+}
+
+int32_t launch_ia3_colgrad(void* G, size_t ldg, const void* X, size_t ldx, const void* l, float* part, float* dl, int n,
+                           int C, int dtype, hipStream_t s) {
+  if (n == 0 || C == 0) return FLEXCO_OK;
+  const int chunks = (n + 31) / 32;
+  DISPATCH_T(dtype, hipLaunchKernelGGL((ia3_colgrad_kernel<T>), dim3((C + 255) / 256, chunks), dim3(256), 0, s, (T*)G,
+                                       ldg, (const T*)X, ldx, (const T*)l, part, n, C));
+  hipLaunchKernelGGL(ia3_colgrad_finalize_kernel, dim3((C + 255) / 256), dim3(256), 0, s, part, chunks, C, dl);
+  return post_launch("ia3_colgrad");
 }
 
 int32_t launch_swiglu(const void* gu, void* act, int T_, int F, int dtype, hipStream_t s) {

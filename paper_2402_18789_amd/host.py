@@ -44,6 +44,21 @@ class DeviceLora:
             self.c.dA[i], self.c.dB[i] = self.dA[t].data_ptr(), self.dB[t].data_ptr()
 
 
+class DeviceIa3:
+    """One (IA)^3 adapter and its gradient buffers on the GPU.  ia3: {"k", "v": [nkv d], "ff": [F]}."""
+
+    def __init__(self, cfg, ia3, device="cuda"):
+        dt = TORCH_DTYPE[cfg.dtype]
+        self.l = {n: _dev(ia3[n], dt, device) for n in ("k", "v", "ff")}
+        self.dl = {n: torch.zeros(self.l[n].shape, dtype=torch.float32, device=device) for n in ("k", "v", "ff")}
+        self.c = B.Ia3(self.l["k"].data_ptr(), self.l["v"].data_ptr(), self.l["ff"].data_ptr(),
+                       self.dl["k"].data_ptr(), self.dl["v"].data_ptr(), self.dl["ff"].data_ptr())
+
+    def zero_grads(self):
+        for t in self.dl.values():
+            t.zero_()
+
+
 class DeviceLayer:
     """Frozen weights (+ one LoRA adapter and its gradient buffers) of one layer on the GPU.
     W: {wq, wk, wv, wo, wg, wu, wd [out, in], g1, g2, optional bq, bk, bv};
@@ -130,7 +145,7 @@ class DevicePool:
 
 
 class DeviceFtState:
-    def __init__(self, cfg, L, device="cuda", keep_u=True):
+    def __init__(self, cfg, L, device="cuda", keep_u=True, ia3=False):
         dt = TORCH_DTYPE[cfg.dtype]
         z = lambda w, d=dt: torch.zeros((L, w), dtype=d, device=device)
         self.L = L
@@ -148,6 +163,11 @@ class DeviceFtState:
             for t in cfg.lora_targets:
                 self.u[t] = z(cfg.lora_rank, torch.float32)
                 self.c.saved_u[B.TARGET_NAMES.index(t)] = self.u[t].data_ptr()
+
+        # unscaled key / value rows: the other operand of the (IA)^3 products
+        if ia3:
+            self.k0, self.v0 = z(cfg.kv_dim), z(cfg.kv_dim)
+            self.c.saved_k0, self.c.saved_v0 = self.k0.data_ptr(), self.v0.data_ptr()
 
     def zero_accum(self):
         self.dk_accum.zero_()
