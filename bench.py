@@ -51,6 +51,9 @@ def main():
                     help="co-serving as in Sec. 6.2 of the paper: the window backward runs on a second stream, "
                          "concurrently with the forward of the batch, on a finetune sequence of its own")
     ap.add_argument("--no-two-stream", action="store_true", help="skip the additional two-stream measurement")
+    ap.add_argument("--bypass", choices=("lora", "ia3"), default="lora",
+                    help="bypass network of the finetune window: LoRA r16 on q,k,v,o,down (the headline workload) or "
+                         "(IA)^3 vectors on k, v and the FFN activation (same batch, same base layer)")
     ap.add_argument("--kv-split-pages", type=int, default=0,
                     help="pages per attention work item (0 = the library's default)")
     args = ap.parse_args()
@@ -66,11 +69,16 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     cfg = CONFIGS["c2_llama8b_layer"]
+    use_ia3 = args.bypass == "ia3"
+    if use_ia3:
+        cfg = cfg.with_(lora_targets=())
     seed = args.seed
     t_setup = time.time()
     batch = gen.batch_c2(seed)
     W = gen.layer_weights(cfg, seed, 0)
-    lora = gen.lora_weights(cfg, seed, 0)
+    lora = None if use_ia3 else gen.lora_weights(cfg, seed, 0)
+    ia3_np = gen.ia3_weights(cfg, seed, 0) if use_ia3 else None
+    ia3 = HH.DeviceIa3(cfg, ia3_np) if use_ia3 else None
     layers = [HH.DeviceLayer(cfg, W, lora) for _ in range(max(1, args.weight_copies))]
     n_seq_pages = len(batch.seq_pages[[r for r in batch.requests if r.kind == 2][0].seq_id])
     pool = HH.DevicePool(cfg, batch.num_pages + n_seq_pages)   # + room for the two-stream run's own sequence
@@ -84,7 +92,7 @@ def main():
         if r.start_pos:
             k, v = gen.kv_prefix(cfg, seed, 0, r.seq_id, r.start_pos)
             pool.write_rows(batch.seq_pages[r.seq_id], k, v)
-    ft = HH.DeviceFtState(cfg, L)
+    ft = HH.DeviceFtState(cfg, L, ia3=use_ia3)
     db = HH.DeviceBatch(cfg, batch.requests, batch.seq_pages, batch.num_pages, args.kv_split_pages)
     hm = db.host_maps
     T, n_ft = hm.T, hm.n_ft
@@ -106,26 +114,38 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    def forward(ly, ftc, wsx):
+        if use_ia3:
+            B.flexco_layer_forward_ia3(ly.c, ly.w, ia3.c, db.maps, x, y, pool.c, ftc, wsx.ptr, wsx.bytes)
+        else:
+            B.flexco_layer_forward(ly.c, ly.w, ly.lora, db.maps, x, y, pool.c, ftc, wsx.ptr, wsx.bytes)
+
+    def backward(ly, pages, ftc, wsx, stream=None):
+        if use_ia3:
+            B.flexco_ia3_bwd(ly.c, ly.w, ia3.c, pool.c, pages, n_ft_pages, ftc, ft_req.start_pos, ft_req.n_new, dY, dX,
+                             wsx.ptr, wsx.bytes, stream=stream)
+        else:
+            B.flexco_lora_bwd(ly.c, ly.w, ly.lora, pool.c, pages, n_ft_pages, ftc, ft_req.start_pos, ft_req.n_new, dY, dX,
+                              wsx.ptr, wsx.bytes, stream=stream)
+
     def step_serial(i):
         ly = layers[i % len(layers)]
-        B.flexco_layer_forward(ly.c, ly.w, ly.lora, db.maps, x, y, pool.c, ft.c, ws.ptr, ws.bytes)
-        B.flexco_lora_bwd(ly.c, ly.w, ly.lora, pool.c, ft_pages, n_ft_pages, ft.c, ft_req.start_pos, ft_req.n_new,
-                          dY, dX, ws.ptr, ws.bytes)
+        forward(ly, ft.c, ws)
+        backward(ly, ft_pages, ft.c, ws)
 
     def make_overlap_step():
         # The backward window of an iteration belongs to a sequence whose forward passes ran in earlier
         # iterations (Alg. 2: all forward windows, then the backward windows).  That sequence gets pages
         # and finetune state of its own - copies of what one forward of the batch leaves behind - so the
         # two streams touch disjoint data, the frozen weights and LoRA factors (both only read) apart.
-        ly = layers[0]
-        B.flexco_layer_forward(ly.c, ly.w, ly.lora, db.maps, x, y, pool.c, ft.c, ws.ptr, ws.bytes)
+        forward(layers[0], ft.c, ws)
         torch.cuda.synchronize()
         src_pages = ft_pages.long()
         bwd_pages = torch.arange(batch.num_pages, batch.num_pages + n_ft_pages, device="cuda")
         pool.k[bwd_pages] = pool.k[src_pages]
         pool.v[bwd_pages] = pool.v[src_pages]
-        ft_b = HH.DeviceFtState(cfg, L)
-        for name in ("q_cache", "attn", "x", "x2", "gate", "up", "lse"):
+        ft_b = HH.DeviceFtState(cfg, L, ia3=use_ia3)
+        for name in ("q_cache", "attn", "x", "x2", "gate", "up", "lse") + (("k0", "v0") if use_ia3 else ()):
             getattr(ft_b, name).copy_(getattr(ft, name))
         bwd_pages = bwd_pages.to(torch.int32)
         ws_b = HH.Workspace(layers[0].c, T, hm.n_parts, n_ft, L)
@@ -134,9 +154,8 @@ def main():
 
         def step_two_streams(i):
             ly = layers[i % len(layers)]
-            B.flexco_layer_forward(ly.c, ly.w, ly.lora, db.maps, x, y, pool.c, ft.c, ws.ptr, ws.bytes)
-            B.flexco_lora_bwd(ly.c, ly.w, ly.lora, pool.c, bwd_pages, n_ft_pages, ft_b.c, ft_req.start_pos,
-                              ft_req.n_new, dY, dX, ws_b.ptr, ws_b.bytes, stream=side)
+            forward(ly, ft.c, ws)
+            backward(ly, bwd_pages, ft_b.c, ws_b, stream=side)
         step_two_streams.keep = (ft_b, ws_b, bwd_pages, side)
         return step_two_streams
 
@@ -210,7 +229,8 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "c2_llama8b_layer: 1 LLaMA-3.1-8B-shaped layer, T=1024 = 256 decode (ctx U[512,4096], "
                                "page 16) + 2x256 prefill + 256 finetune (last window of 2048); forward of all "
-                               "tokens + LoRA r16 (q,k,v,o,down) window backward",
+                               "tokens + " + ("(IA)^3 (k, v, FFN activation) window backward" if use_ia3 else
+                                              "LoRA r16 (q,k,v,o,down) window backward"),
                    "tokens": T, "finetune_tokens": n_ft, "requests": hm.n_req,
                    "cached_positions": int(sum(r.start_pos + r.n_new for r in batch.requests)),
                    "weight_copies_cycled": len(layers),
@@ -239,7 +259,7 @@ def main():
                               "what": "same steps, the window backward on a second stream concurrent with the "
                                       "forward (Sec. 6.2 of the paper), on a finetune sequence of its own"}
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, batch, sample, W, lora, seed, x_np, ft_req, L)
+        out["cpu_baseline"] = cpu_baseline(cfg, batch, sample, W, lora, seed, x_np, ft_req, L, ia3_np)
     print(json.dumps(out), flush=True)
 
 
@@ -336,10 +356,11 @@ def roofline_entry(name, avg_launch_ms, launches_per_step, work):
     return base
 
 
-def cpu_baseline(cfg, batch, sample, W, lora, seed, x_np, ft_req, L):
+def cpu_baseline(cfg, batch, sample, W, lora, seed, x_np, ft_req, L, ia3=None):
     """The oracle, as it stands, on a bounded sample of the same workload (forward of the sampled
     requests' tokens + the finetune window's backward), timed on this machine's host cores."""
     from oracle import layer as OL
+    from oracle import ia3 as OI
     from oracle.maps import build_maps
     from workload import gen
     import threadpoolctl
@@ -352,7 +373,7 @@ def cpu_baseline(cfg, batch, sample, W, lora, seed, x_np, ft_req, L):
             pool.k[sl], pool.v[sl] = k, v
     rows = gen.sample_token_rows(batch, sample)
     om = build_maps(sample, batch.seq_pages, batch.page_size, batch.num_pages)
-    st = {ft_req.seq_id: OL.FtState(cfg, L)}
+    st = {ft_req.seq_id: OI.Ia3FtState(cfg, L) if ia3 is not None else OL.FtState(cfg, L)}
     threads = sum(p.get("num_threads", 0) for p in threadpoolctl.threadpool_info() if p.get("user_api") == "blas") or os.cpu_count()
     log("cpu baseline: oracle on %d sampled tokens (%d requests), %d BLAS threads" % (len(rows), len(sample), threads))
     dY = gen.layer_input(cfg, seed, ft_req.n_new, tag="dy")
@@ -362,11 +383,17 @@ def cpu_baseline(cfg, batch, sample, W, lora, seed, x_np, ft_req, L):
     reps = 0
     while reps < 6 and (t_f + t_b) < 10.0:
         t0 = time.perf_counter()
-        OL.layer_forward_mixed(cfg, W, lora, om, x_np[rows], pool, st)
+        if ia3 is not None:
+            OI.forward_mixed(cfg, W, ia3, om, x_np[rows], pool, st)
+        else:
+            OL.layer_forward_mixed(cfg, W, lora, om, x_np[rows], pool, st)
         t_f += time.perf_counter() - t0
         t0 = time.perf_counter()
-        OL.layer_backward_window(cfg, W, lora, st[ft_req.seq_id], pool.k[sl].astype(np.float64),
-                                 pool.v[sl].astype(np.float64), ft_req.start_pos, ft_req.n_new, dY, {})
+        kk, vv = pool.k[sl].astype(np.float64), pool.v[sl].astype(np.float64)
+        if ia3 is not None:
+            OI.backward_window(cfg, W, ia3, st[ft_req.seq_id], kk, vv, ft_req.start_pos, ft_req.n_new, dY, {})
+        else:
+            OL.layer_backward_window(cfg, W, lora, st[ft_req.seq_id], kk, vv, ft_req.start_pos, ft_req.n_new, dY, {})
         t_b += time.perf_counter() - t0
         reps += 1
     log("cpu baseline: %d passes, forward %.1fs, backward %.1fs, total incl. setup %.1fs" % (reps, t_f, t_b, time.time() - t_all))

@@ -159,7 +159,7 @@ struct BwdWs {
   float *delta, *u, *t;
   float* gemm_part;        // split-K partial sums of the input-gradient GEMMs
   size_t gemm_part_elems;
-  float* colsum_part;      // per-chunk column sums of the (IA)^3 vector gradients: [ceil(n / 32)][max(F, nkv d)]
+  float* colsum_part;      // per-chunk column sums of the (IA)^3 vector gradients: [ceil(n / 8)][max(F, nkv d)]
   LoraWs lw;
   size_t bytes;
 };
@@ -211,7 +211,7 @@ BwdWs carve_bwd(const flexco_layer_cfg& c, int n, void* base) {
   w.t = (float*)cv.take(sizeof(float) * n * r);
   w.gemm_part_elems = c.dtype == FLEXCO_BF16 ? (size_t)n * SPLITK_COLS : 0;
   w.gemm_part = (float*)cv.take(sizeof(float) * w.gemm_part_elems);
-  w.colsum_part = (float*)cv.take(sizeof(float) * (size_t)((n + 31) / 32) *
+  w.colsum_part = (float*)cv.take(sizeof(float) * (size_t)((n + 7) / 8) *
                                   std::max<size_t>(c.ffn, (size_t)c.n_kv_heads * c.head_dim));
   carve_lora(c, n, true, cv, w.lw);
   w.bytes = cv.off;

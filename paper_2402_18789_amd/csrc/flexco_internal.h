@@ -141,7 +141,7 @@ struct Ia3ScaleArgs {
 };
 int32_t launch_ia3_scale_rows(void* buf, size_t ld, const int32_t* tok, int n_tok, const Ia3ScaleArgs& a, int dtype,
                               hipStream_t s);
-// dl[c] += sum_r G[r, c] X[r, c];  G[r, c] *= l[c];  part: float [ceil(n / 32)][C] scratch
+// dl[c] += sum_r G[r, c] X[r, c];  G[r, c] *= l[c];  part: float [ceil(n / 8)][C] scratch
 int32_t launch_ia3_colgrad(void* G, size_t ldg, const void* X, size_t ldx, const void* l, float* part, float* dl, int n,
                            int C, int dtype, hipStream_t s);
 struct CopyRowsBatch {

@@ -237,9 +237,10 @@ __global__ __launch_bounds__(256) void rope_bwd_pack_kernel(const T* __restrict_
 // rows of the finetune window first keep the unscaled values (the other operand of the product, which
 // the vector's gradient needs).
 // --------------------------------------------------------------------------------------
-template <typename T>
+template <typename T, bool VEC>
 __global__ __launch_bounds__(256) void ia3_scale_rows_kernel(T* __restrict__ buf, size_t ldb,
                                                              const int32_t* __restrict__ tok, Ia3ScaleArgs a) {
+  constexpr int N = VEC ? Vec<T>::N : 1;
   const int t = tok[blockIdx.x];
   T* row = buf + (size_t)t * ldb;
   const bool is_ft = t >= a.ft_tok0 && t < a.ft_tok0 + a.n_ft;
@@ -247,32 +248,55 @@ __global__ __launch_bounds__(256) void ia3_scale_rows_kernel(T* __restrict__ buf
     const T* l = (const T*)a.l[sg];
     T* sv = (is_ft && a.save[sg]) ? (T*)a.save[sg] + (size_t)(a.ft_pos0 + (t - a.ft_tok0)) * a.ld_save[sg] : nullptr;
     T* p = row + a.col0[sg];
-    for (int c = threadIdx.x; c < a.width[sg]; c += 256) {
-      const T v = p[c];
-      if (sv) sv[c] = v;
-      st(p + c, (float)v * ld(l + c));
+    for (int c = threadIdx.x * N; c < a.width[sg]; c += 256 * N) {
+      float v[N], lv[N];
+      if (VEC) {
+        Vec<T>::load(p + c, v);
+        Vec<T>::load(l + c, lv);
+        if (sv) Vec<T>::store(sv + c, v);          // (a value of type T passes through float unchanged)
+#pragma unroll
+        for (int j = 0; j < N; ++j) v[j] *= lv[j];
+        Vec<T>::store(p + c, v);
+      } else {
+        v[0] = ld(p + c);
+        if (sv) st(sv + c, v[0]);
+        st(p + c, v[0] * ld(l + c));
+      }
     }
   }
 }
 
-// Backward of the product Y = X (.) l over a window of n rows: G holds dY.  Per chunk of 32 rows and per
-// column, part[chunk][c] = sum_r G[r, c] X[r, c] (the chunk's share of dl[c]), and G[r, c] <- G[r, c] l[c]
+// Backward of the product Y = X (.) l over a window of n rows: G holds dY.  Per chunk of IA3_CHUNK rows and
+// per column, part[chunk][c] = sum_r G[r, c] X[r, c] (the chunk's share of dl[c]), and G[r, c] <- G[r, c] l[c]
 // (= dX) in place.  The second kernel adds the chunks in order into dl: no atomics, a fixed order.
-template <typename T>
+constexpr int IA3_CHUNK = 8;
+template <typename T, bool VEC>
 __global__ __launch_bounds__(256) void ia3_colgrad_kernel(T* __restrict__ G, size_t ldg, const T* __restrict__ X,
                                                           size_t ldx, const T* __restrict__ l,
                                                           float* __restrict__ part, int n, int C) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
+  constexpr int N = VEC ? Vec<T>::N : 1;
+  const int c = (blockIdx.x * 256 + threadIdx.x) * N;
   if (c >= C) return;
-  const int r0 = blockIdx.y * 32, r1 = min(r0 + 32, n);
-  const float lc = ld(l + c);
-  float acc = 0.f;
-  for (int r = r0; r < r1; ++r) {
-    const float g = ld(G + (size_t)r * ldg + c);
-    acc += g * ld(X + (size_t)r * ldx + c);
-    st(G + (size_t)r * ldg + c, g * lc);
+  const int r0 = blockIdx.y * IA3_CHUNK;
+  float lv[N], acc[N], g[IA3_CHUNK][N], x[IA3_CHUNK][N];
+  if (VEC) Vec<T>::load(l + c, lv); else lv[0] = ld(l + c);
+#pragma unroll
+  for (int j = 0; j < N; ++j) acc[j] = 0.f;
+#pragma unroll
+  for (int i = 0; i < IA3_CHUNK; ++i) {            // every load of the chunk in flight before the first use
+    const int r = min(r0 + i, n - 1);
+    if (VEC) { Vec<T>::load(G + (size_t)r * ldg + c, g[i]); Vec<T>::load(X + (size_t)r * ldx + c, x[i]); }
+    else { g[i][0] = ld(G + (size_t)r * ldg + c); x[i][0] = ld(X + (size_t)r * ldx + c); }
   }
-  part[(size_t)blockIdx.y * C + c] = acc;
+#pragma unroll
+  for (int i = 0; i < IA3_CHUNK; ++i) {
+    if (r0 + i >= n) break;
+#pragma unroll
+    for (int j = 0; j < N; ++j) { acc[j] += g[i][j] * x[i][j]; g[i][j] *= lv[j]; }
+    if (VEC) Vec<T>::store(G + (size_t)(r0 + i) * ldg + c, g[i]); else st(G + (size_t)(r0 + i) * ldg + c, g[i][0]);
+  }
+#pragma unroll
+  for (int j = 0; j < N; ++j) part[(size_t)blockIdx.y * C + c + j] = acc[j];
 }
 
 __global__ __launch_bounds__(256) void ia3_colgrad_finalize_kernel(const float* __restrict__ part, int chunks, int C,
@@ -280,7 +304,13 @@ __global__ __launch_bounds__(256) void ia3_colgrad_finalize_kernel(const float* 
   const int c = blockIdx.x * 256 + threadIdx.x;
   if (c >= C) return;
   float acc = 0.f;
-  for (int k = 0; k < chunks; ++k) acc += part[(size_t)k * C + c];
+  for (int k0 = 0; k0 < chunks; k0 += 8) {   // eight loads in flight, added in chunk order
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = k0 + i < chunks ? part[(size_t)(k0 + i) * C + c] : 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc += v[i];
+  }
   dl[c] += acc;
 }
 
@@ -603,16 +633,25 @@ int32_t launch_rope_bwd_pack(const flexco_layer_cfg& c, const void* dq, const fl
 int32_t launch_ia3_scale_rows(void* buf, size_t ld, const int32_t* tok, int n_tok, const Ia3ScaleArgs& a, int dtype,
                               hipStream_t s) {
   if (n_tok == 0 || a.n_seg == 0) return FLEXCO_OK;
-  DISPATCH_T(dtype, hipLaunchKernelGGL((ia3_scale_rows_kernel<T>), dim3(n_tok), dim3(256), 0, s, (T*)buf, ld, tok, a));
+  const int vn = dtype == FLEXCO_BF16 ? 8 : 4;
+  bool vec = ld % vn == 0 && aligned16(buf);
+  for (int sg = 0; sg < a.n_seg; ++sg)
+    vec = vec && a.col0[sg] % vn == 0 && a.width[sg] % vn == 0 && aligned16(a.l[sg]) && aligned16(a.save[sg]) &&
+          a.ld_save[sg] % vn == 0;
+  DISPATCH_TV(dtype, vec, hipLaunchKernelGGL((ia3_scale_rows_kernel<T, VEC>), dim3(n_tok), dim3(256), 0, s, (T*)buf, ld,
+                                             tok, a));
   return post_launch("ia3_scale_rows");
 }
 
 int32_t launch_ia3_colgrad(void* G, size_t ldg, const void* X, size_t ldx, const void* l, float* part, float* dl, int n,
                            int C, int dtype, hipStream_t s) {
   if (n == 0 || C == 0) return FLEXCO_OK;
-  const int chunks = (n + 31) / 32;
-  DISPATCH_T(dtype, hipLaunchKernelGGL((ia3_colgrad_kernel<T>), dim3((C + 255) / 256, chunks), dim3(256), 0, s, (T*)G,
-                                       ldg, (const T*)X, ldx, (const T*)l, part, n, C));
+  const int chunks = (n + IA3_CHUNK - 1) / IA3_CHUNK;
+  const int vn = dtype == FLEXCO_BF16 ? 8 : 4;
+  const bool vec = C % vn == 0 && ldg % vn == 0 && ldx % vn == 0 && aligned16(G) && aligned16(X) && aligned16(l);
+  const int per = 256 * (vec ? vn : 1);
+  DISPATCH_TV(dtype, vec, hipLaunchKernelGGL((ia3_colgrad_kernel<T, VEC>), dim3((C + per - 1) / per, chunks), dim3(256), 0,
+                                             s, (T*)G, ldg, (const T*)X, ldx, (const T*)l, part, n, C));
   hipLaunchKernelGGL(ia3_colgrad_finalize_kernel, dim3((C + 255) / 256), dim3(256), 0, s, part, chunks, C, dl);
   return post_launch("ia3_colgrad");
 }
