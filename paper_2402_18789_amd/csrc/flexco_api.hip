@@ -107,6 +107,7 @@ extern "C" int32_t flexco_kernel_timer_stop(int32_t kernel_id, double* total_ms,
 namespace {
 
 constexpr size_t SPLITK_COLS = 32768;   // split-K scratch of the backward GEMMs: rows x this many floats
+constexpr int FWD_SPLITK_MAX_T = 256;   // forward batches up to this many tokens get split-K scratch too
 
 struct Carver {
   char* base;
@@ -151,8 +152,10 @@ void carve_lora(const flexco_layer_cfg& c, int rows, bool backward, Carver& cv, 
 struct FwdWs {
   void *h, *qkv, *attn, *x2, *gu, *act;
   float *lse, *u, *part_ml, *part_acc;
+  float* gemm_part;        // split-K partial sums of the forward projections of a small batch (last in the carve)
+  size_t gemm_part_elems;
   LoraWs lw;
-  size_t bytes;
+  size_t bytes, bytes_without_part;
 };
 struct BwdWs {
   void *hn, *hn2, *act, *dact, *dgu, *dh, *dx2, *dattn, *dq, *dqkv;   // hn = norm1(x), hn2 = norm2(x2)
@@ -186,6 +189,11 @@ FwdWs carve_fwd(const flexco_layer_cfg& c, int T, int n_parts, void* base) {
   w.part_ml = (float*)cv.take(sizeof(float) * prow * 2);
   w.part_acc = (float*)cv.take(sizeof(float) * prow * c.head_dim);
   carve_lora(c, T, false, cv, w.lw);
+  // A batch of few tokens has fewer output tiles than the chip has CUs: its projections cut K across
+  // blocks like the backward window's do, and need the partial sums' scratch.
+  w.bytes_without_part = cv.off;
+  w.gemm_part_elems = (c.dtype == FLEXCO_BF16 && T <= FWD_SPLITK_MAX_T) ? (size_t)T * SPLITK_COLS : 0;
+  w.gemm_part = (float*)cv.take(sizeof(float) * w.gemm_part_elems);
   w.bytes = cv.off;
   return w;
 }
@@ -421,7 +429,7 @@ int32_t forward_projection(const flexco_layer_cfg& c, const Adapters& ad, const 
       if (rc != FLEXCO_EUNSUPPORTED) return rc;
       clear_error();
     }
-    int32_t rc = launch_gemm(x, W, y, bias, res, T, N, K, K, K, N, ldr, false, dt, s, &ext);
+    int32_t rc = launch_gemm(x, W, y, bias, res, T, N, K, K, K, N, ldr, false, dt, s, &ext, k.gemm_part, k.gemm_part_elems);
     if (rc != FLEXCO_EUNSUPPORTED) return rc;
     clear_error();   // e.g. a target boundary inside a 32-column fragment: run the bypass as separate kernels
   }
@@ -430,7 +438,7 @@ int32_t forward_projection(const flexco_layer_cfg& c, const Adapters& ad, const 
     if (rc != FLEXCO_EUNSUPPORTED) return rc;
     clear_error();
   }
-  FLEXCO_TRY(launch_gemm(x, W, y, bias, res, T, N, K, K, K, N, ldr, false, dt, s));
+  FLEXCO_TRY(launch_gemm(x, W, y, bias, res, T, N, K, K, K, N, ldr, false, dt, s, nullptr, k.gemm_part, k.gemm_part_elems));
   // more adapters than the folded path takes: the backward pass (which folds whenever it can) still
   // expects the finetune rows' rank-r products where the state keeps them
   if (nact > 0 && nused > FUSED_ADAPTERS && lora_mfma_ok(c, K) && ft && m.n_ft > 0 && ft->saved_u[targets[act[0]]]) {
@@ -610,7 +618,9 @@ extern "C" int32_t flexco_workspace_bytes(const flexco_layer_cfg* cfg, int32_t T
   FLEXCO_TRY(check_cfg(cfg));
   FLEXCO_CHECK(out_bytes != nullptr, FLEXCO_EINVAL, "out_bytes is NULL");
   FLEXCO_CHECK(T_max >= 0 && n_parts_max >= 0 && win_max >= 0 && kv_max >= 0, FLEXCO_EINVAL, "negative size");
-  const size_t f = carve_fwd(*cfg, T_max, n_parts_max, nullptr).bytes;
+  // (a batch of at most FWD_SPLITK_MAX_T tokens also asks for split-K scratch: cover the largest such batch)
+  const size_t f = std::max(carve_fwd(*cfg, T_max, n_parts_max, nullptr).bytes,
+                            carve_fwd(*cfg, std::min(T_max, FWD_SPLITK_MAX_T), n_parts_max, nullptr).bytes);
   const size_t b = carve_bwd(*cfg, win_max, nullptr).bytes;
   *out_bytes = f > b ? f : b;
   return FLEXCO_OK;
@@ -717,6 +727,11 @@ static int32_t layer_forward_impl(const flexco_layer_cfg* cfg, const flexco_base
                  "finetune window [%d, %d) exceeds the state's seq_len %d", m.ft_pos0, m.ft_pos0 + m.n_ft, ft->seq_len);
   }
   FwdWs k = carve_fwd(c, m.T, m.n_parts, ws);
+  if (k.bytes > ws_bytes && k.bytes_without_part <= ws_bytes) {   // no room for the split-K scratch: run unsplit
+    k.gemm_part = nullptr;
+    k.gemm_part_elems = 0;
+    k.bytes = k.bytes_without_part;
+  }
   FLEXCO_CHECK(k.bytes <= ws_bytes, FLEXCO_EWORKSPACE, "forward needs %zu workspace bytes, got %zu", k.bytes, ws_bytes);
 
   hipStream_t s = (hipStream_t)stream;

@@ -52,9 +52,29 @@ int32_t build(const flexco_batch_desc* d, int32_t page_size, int32_t num_pages, 
               int32_t kv_split_pages, Built& b, bool count_only) {
   const int group = nq / nkv;
   b.tile_tokens = std::max(1, 16 / group);
-  b.split_pages = kv_split_pages > 0 ? kv_split_pages : 64;
-  FLEXCO_CHECK(b.split_pages % 2 == 0, FLEXCO_EINVAL, "kv_split_pages must be even (got %d)", b.split_pages);
   const int n_req = d->n_req;
+  b.split_pages = kv_split_pages;
+  if (kv_split_pages <= 0) {
+    // Default: 64 pages per split.  A batch of few requests would leave most of the chip without an
+    // attention work item (one wavefront per item and kv head): take the largest of 64, 32, 16, 8 pages
+    // that gives at least 1024 wavefronts, else 8.
+    b.split_pages = 8;
+    for (int cand = 64; cand >= 16; cand /= 2) {
+      int64_t items = 0;
+      for (int r = 0; r < n_req; ++r) {
+        if (d->n_new[r] <= 0 || d->start_pos[r] < 0 || page_size <= 0) continue;   // rejected below
+        const int tiles = (d->n_new[r] + b.tile_tokens - 1) / b.tile_tokens;
+        for (int tl0 = 0; tl0 < tiles; tl0 += FLEXCO_ATTN_ITEM_TILES) {
+          const int last_tile = std::min(tl0 + FLEXCO_ATTN_ITEM_TILES, tiles) - 1;
+          const int last_tok = std::min((last_tile + 1) * b.tile_tokens, d->n_new[r]) - 1;
+          const int vis_pages = (d->start_pos[r] + last_tok) / page_size + 1;
+          items += (vis_pages + cand - 1) / cand;
+        }
+      }
+      if (items * nkv >= 1024) { b.split_pages = cand; break; }
+    }
+  }
+  FLEXCO_CHECK(b.split_pages % 2 == 0, FLEXCO_EINVAL, "kv_split_pages must be even (got %d)", b.split_pages);
   std::vector<int32_t> need(n_req);
   int64_t T64 = 0;
   for (int r = 0; r < n_req; ++r) {

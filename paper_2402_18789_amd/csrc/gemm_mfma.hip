@@ -553,6 +553,14 @@ int32_t launch_gemm_mfma(const void* A, const void* W, void* C, const void* bias
     return launch_cfg<128, 128, true>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, ext, s, timer_id, part, sp);
   }
   if (!ext_fits(ext, false, N)) return FLEXCO_EUNSUPPORTED;
+  // A batch of few tokens (decode-only iterations) has one or two row tiles and far fewer output tiles
+  // than CUs, and its time is the weight stream's: cut K across blocks so that the whole chip pulls on it.
+  if (part && M <= 256) {
+    const int tiles = ((M + 127) / 128) * ((N + 127) / 128);
+    const int sp = tiles < 192 ? pick_splits(M, N, K, tiles, part_elems, 256) : 1;
+    if (sp > 1)
+      return launch_cfg<128, 128, false>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, ext, s, timer_id, part, sp);
+  }
   // Forward form: tile shapes by estimated time.  A launch runs in rounds of one block per CU; a round
   // costs the tile's area over the rate its kernel sustains with the chip full (measured, relative:
   // 256 x 256 tiles 1.24, 256 x 192 1.09, 128 x 192 1.0, 128 x 128 0.875).  Candidates: one shape for

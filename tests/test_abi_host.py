@@ -81,6 +81,22 @@ def test_maps_bit_exact_vs_oracle(name, nq, nkv, split):
     assert cm["tile_tokens"] == max(1, 16 // (nq // nkv))
 
 
+def test_default_key_split_follows_the_batch_size():
+    """64 pages per split when that already gives the chip enough work items; fewer pages per split for
+    batches of few requests (down to 8), so that a decode-only iteration of 16 requests is not 128
+    wavefronts walking 1000 keys each.  Any split leaves the cover intact."""
+    assert c_maps(gen.batch_c2(0), 32, 8)["kv_split_pages"] == 64
+    for n_dec, want in ((16, 8), (64, 16), (100, 32), (200, 64)):
+        ctx = gen.rng(0, "split", n_dec).integers(256, 1025, size=n_dec)
+        batch = gen.mixed_batch(16, 0, decode_ctx=ctx)
+        cm = c_maps(batch, 32, 8)
+        assert cm["kv_split_pages"] == want, (n_dec, cm["kv_split_pages"])
+        assert cm["n_items"] * 8 >= 1024 or want == 8
+        om = build_maps(batch.requests, batch.seq_pages, batch.page_size, batch.num_pages)
+        assert check_attention_cover(om, work_items(cm, batch.page_size))
+    assert c_maps(gen.mixed_batch(16, 0, decode_ctx=(300,)), 32, 8, split=64)["kv_split_pages"] == 64   # an explicit value is kept
+
+
 def test_work_list_is_deterministic():
     a, b = c_maps(gen.batch_c2(0), 32, 8), c_maps(gen.batch_c2(0), 32, 8)
     for k in a:
