@@ -341,6 +341,38 @@ int32_t flexco_ia3_bwd(const flexco_layer_cfg* cfg, const flexco_base_weights* w
                        const flexco_ft_state* ft, int32_t win_start, int32_t win_len, const void* dY,
                        void* dX, void* ws, size_t ws_bytes, void* stream);
 
+/* Bottleneck adapter as a bypass network on a layer's output rows (Sec. 4.1: a bypass network reads one
+ * backbone tensor X and its output is added to one backbone tensor; here Y = X + relu(X W_down^T) W_up^T,
+ * no biases).  Device pointers; weights in the call's dtype, gradients fp32 and accumulated into. */
+typedef struct flexco_adapter {
+  int32_t bottleneck;    /* b, 1..64 */
+  const void* w_down;    /* [b, H]   */
+  const void* w_up;      /* [H, b]   */
+  float* dw_down;        /* [b, H], may be NULL for the forward pass */
+  float* dw_up;          /* [H, b]   */
+} flexco_adapter;
+
+/* Scratch bytes of the two adapter calls for batches of at most T_max tokens and windows of at most win_max rows. */
+int32_t flexco_adapter_workspace_bytes(int32_t dtype, int32_t hidden, int32_t bottleneck, int32_t T_max,
+                                       int32_t win_max, size_t* out_bytes);
+
+/* Forward of the adapter, in place on the rows of y [T, hidden] whose request carries an adapter
+ * (maps->lora_tok); other rows are untouched.  Rows of the finetune window first copy their input into
+ * saved_in [seq_len, hidden] at their positions (what graph pruning keeps for this network; NULL when the
+ * batch has no finetune request).  ws: device scratch of flexco_adapter_workspace_bytes.
+ * Call it after flexco_layer_forward on that call's x_out. */
+int32_t flexco_adapter_fwd(int32_t dtype, int32_t hidden, const flexco_adapter* ad, const flexco_maps* maps,
+                           void* y, void* saved_in, int32_t seq_len, void* ws, size_t ws_bytes, void* stream);
+
+/* Backward of the adapter over the window rows [win_start, win_start + win_len) of the finetune sequence:
+ * dY [win_len, hidden] holds the gradient of the adapter's output on entry and of its input on return
+ * (in place); dw_down, dw_up += the window's contributions.  The ReLU output is recomputed from saved_in.
+ * ws: device scratch of flexco_adapter_workspace_bytes.  Call it before flexco_lora_bwd / flexco_ia3_bwd of the
+ * same layer. */
+int32_t flexco_adapter_bwd(int32_t dtype, int32_t hidden, const flexco_adapter* ad, const void* saved_in,
+                           int32_t seq_len, int32_t win_start, int32_t win_len, void* dY, void* ws,
+                           size_t ws_bytes, void* stream);
+
 /* Attention backward of one window (the attention part of flexco_lora_bwd, exported for
  * unit parity).  q, out, dout: device [win_len, nq d] rows of the window (q after RoPE);
  * lse: device float [win_len, nq].  dq: device [win_len, nq d] (dtype of cfg), written.

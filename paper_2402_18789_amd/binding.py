@@ -73,6 +73,11 @@ class FtState(C.Structure):
                [("saved_k0", C.c_void_p), ("saved_v0", C.c_void_p)]
 
 
+class Adapter(C.Structure):
+    _fields_ = [("bottleneck", C.c_int32), ("w_down", C.c_void_p), ("w_up", C.c_void_p), ("dw_down", C.c_void_p),
+                ("dw_up", C.c_void_p)]
+
+
 class Ia3(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("l_k", "l_v", "l_ff", "dl_k", "dl_v", "dl_ff")]
 
@@ -118,6 +123,9 @@ def _load():
                                        sz, vp],
         "flexco_layer_forward_ia3": [P(LayerCfg), P(BaseWeights), P(Ia3), P(Maps), vp, vp, P(KVPool), P(FtState), vp, sz, vp],
         "flexco_ia3_bwd": [P(LayerCfg), P(BaseWeights), P(Ia3), P(KVPool), vp, i32, P(FtState), i32, i32, vp, vp, vp, sz, vp],
+        "flexco_adapter_workspace_bytes": [i32, i32, i32, i32, i32, P(sz)],
+        "flexco_adapter_fwd": [i32, i32, P(Adapter), P(Maps), vp, vp, i32, vp, sz, vp],
+        "flexco_adapter_bwd": [i32, i32, P(Adapter), vp, i32, i32, i32, vp, vp, sz, vp],
         "flexco_attention_mixed": [P(LayerCfg), P(Maps), vp, P(KVPool), vp, vp, vp, sz, vp],
         "flexco_lora_fwd": [vp, vp, i32, i32, i32, i32, f32, i32, P(vp), P(vp), i32, P(i32), P(i32), i32, vp, vp],
         "flexco_lora_bwd": [P(LayerCfg), P(BaseWeights), P(Lora), P(KVPool), vp, i32, P(FtState), i32, i32, vp, vp, vp, sz, vp],
@@ -151,7 +159,8 @@ EXPORTS = ("flexco_last_error", "flexco_abi_version", "flexco_maps_blob_ints", "
            "flexco_kernel_timer_start", "flexco_kernel_timer_stop", "flexco_kernel_timer_sample", "flexco_probe_mfma", "flexco_probe_read",
            "flexco_latency_estimate", "flexco_sched_window", "flexco_sched_inference", "flexco_sched_advance",
            "flexco_lm_loss_workspace_bytes", "flexco_lm_loss", "flexco_adam_step", "flexco_prune_graph",
-           "flexco_layer_forward_ia3", "flexco_ia3_bwd")
+           "flexco_layer_forward_ia3", "flexco_ia3_bwd", "flexco_adapter_workspace_bytes", "flexco_adapter_fwd",
+           "flexco_adapter_bwd")
 KERNEL_IDS = {"gemm_fwd": 0, "gemm_bwd": 1, "attn_fwd": 2, "attn_merge": 3, "attn_bwd": 4, "elemwise": 5, "lora": 6,
               "generic": 7}
 
@@ -274,6 +283,22 @@ def flexco_layer_forward_ia3(cfg, w, ia3, maps, x_in, x_out, pool, ft, ws, ws_by
 def flexco_ia3_bwd(cfg, w, ia3, pool, seq_pages, n_seq_pages, ft, win_start, win_len, dY, dX, ws, ws_bytes, stream=None):
     _check(_lib.flexco_ia3_bwd(C.byref(cfg), C.byref(w), _opt(ia3), C.byref(pool), _ptr(seq_pages), n_seq_pages,
                                C.byref(ft), win_start, win_len, _ptr(dY), _ptr(dX), _ptr(ws), ws_bytes, _stream(stream)))
+
+
+def flexco_adapter_workspace_bytes(dtype, hidden, bottleneck, T_max, win_max):
+    out = C.c_size_t(0)
+    _check(_lib.flexco_adapter_workspace_bytes(dtype, hidden, bottleneck, T_max, win_max, C.byref(out)))
+    return out.value
+
+
+def flexco_adapter_fwd(dtype, hidden, ad, maps, y, saved_in, seq_len, ws, ws_bytes, stream=None):
+    _check(_lib.flexco_adapter_fwd(dtype, hidden, C.byref(ad), C.byref(maps), _ptr(y), _ptr(saved_in), seq_len, _ptr(ws),
+                                   ws_bytes, _stream(stream)))
+
+
+def flexco_adapter_bwd(dtype, hidden, ad, saved_in, seq_len, win_start, win_len, dY, ws, ws_bytes, stream=None):
+    _check(_lib.flexco_adapter_bwd(dtype, hidden, C.byref(ad), _ptr(saved_in), seq_len, win_start, win_len, _ptr(dY),
+                                   _ptr(ws), ws_bytes, _stream(stream)))
 
 
 def flexco_attention_mixed(cfg, maps, q, pool, out, lse, ws, ws_bytes, stream=None):

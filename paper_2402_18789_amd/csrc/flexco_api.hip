@@ -993,3 +993,141 @@ extern "C" int32_t flexco_ia3_bwd(const flexco_layer_cfg* cfg, const flexco_base
   return layer_backward_impl(cfg, w, nullptr, ia3, pool, seq_pages, n_seq_pages, ft, win_start, win_len, dY, dX, ws,
                              ws_bytes, stream);
 }
+
+namespace {
+int32_t check_adapter(int32_t dtype, int32_t hidden, const flexco_adapter* ad, bool need_grads) {
+  FLEXCO_CHECK(dtype == FLEXCO_F32 || dtype == FLEXCO_BF16, FLEXCO_ESHAPE, "unknown dtype %d", dtype);
+  FLEXCO_CHECK(hidden > 0 && (hidden * esize(dtype)) % 16 == 0, FLEXCO_ESHAPE, "hidden rows must be multiples of 16 bytes");
+  FLEXCO_CHECK(ad != nullptr, FLEXCO_EINVAL, "adapter is NULL");
+  FLEXCO_CHECK(ad->bottleneck >= 1 && ad->bottleneck <= 64, FLEXCO_ESHAPE, "bottleneck %d outside [1, 64]", ad->bottleneck);
+  FLEXCO_CHECK(ad->w_down && ad->w_up, FLEXCO_EINVAL, "an adapter weight is NULL");
+  if (need_grads) FLEXCO_CHECK(ad->dw_down && ad->dw_up, FLEXCO_EINVAL, "an adapter gradient buffer is NULL");
+  return FLEXCO_OK;
+}
+}  // namespace
+
+// The adapter's scratch.  Matrix-core path (bf16, b = 64, hidden a multiple of 128): forward = the bf16 ReLU output
+// of every token row; backward = u, t (fp32), t in bf16 and the transposed up-projection.  Otherwise the
+// rank-r fallback kernels: one / two fp32 [rows, b] arrays.
+namespace {
+bool adapter_mfma_ok(int32_t dtype, int32_t hidden, int b) { return dtype == FLEXCO_BF16 && b == 64 && hidden % 128 == 0; }
+size_t adapter_fwd_bytes(int32_t dtype, int32_t hidden, int b, size_t T, size_t n_rows) {
+  return adapter_mfma_ok(dtype, hidden, b) ? align_up(sizeof(bf16_t) * T * b, 256) : sizeof(float) * n_rows * b;
+}
+size_t adapter_bwd_bytes(int32_t dtype, int32_t hidden, int b, size_t n) {
+  size_t need = 2 * align_up(sizeof(float) * n * b, 256);
+  if (adapter_mfma_ok(dtype, hidden, b)) need += align_up(sizeof(bf16_t) * n * b, 256) + align_up(sizeof(bf16_t) * (size_t)b * hidden, 256);
+  return need;
+}
+}  // namespace
+
+extern "C" int32_t flexco_adapter_workspace_bytes(int32_t dtype, int32_t hidden, int32_t bottleneck, int32_t T_max,
+                                                  int32_t win_max, size_t* out_bytes) {
+  clear_error();
+  FLEXCO_CHECK(out_bytes != nullptr, FLEXCO_EINVAL, "out_bytes is NULL");
+  FLEXCO_CHECK(hidden > 0 && bottleneck >= 1 && bottleneck <= 64 && T_max >= 0 && win_max >= 0, FLEXCO_EINVAL,
+               "size out of range");
+  *out_bytes = std::max(adapter_fwd_bytes(dtype, hidden, bottleneck, T_max, T_max),
+                        adapter_bwd_bytes(dtype, hidden, bottleneck, win_max));
+  return FLEXCO_OK;
+}
+
+extern "C" int32_t flexco_adapter_fwd(int32_t dtype, int32_t hidden, const flexco_adapter* ad, const flexco_maps* maps,
+                                      void* y, void* saved_in, int32_t seq_len, void* ws, size_t ws_bytes,
+                                      void* stream) {
+  clear_error();
+  FLEXCO_TRY(check_adapter(dtype, hidden, ad, false));
+  FLEXCO_CHECK(maps != nullptr && y != nullptr, FLEXCO_EINVAL, "maps or y is NULL");
+  const flexco_maps& m = *maps;
+  FLEXCO_CHECK(m.T > 0 && m.n_lora >= 0 && m.n_lora <= m.T && (m.n_lora == 0 || (m.lora_tok && m.tok_adapter)),
+               FLEXCO_EINVAL, "maps describe no adapter token list");
+  FLEXCO_CHECK(aligned16(y) && aligned16(saved_in) && aligned16(ws) && aligned16(ad->w_down) && aligned16(ad->w_up),
+               FLEXCO_EINVAL, "misaligned pointer");
+  hipStream_t s = (hipStream_t)stream;
+  const size_t e = esize(dtype);
+  const int b = ad->bottleneck;
+  if (saved_in && m.n_ft > 0) {   // the window's input rows, kept for the backward pass
+    FLEXCO_CHECK(m.ft_pos0 + m.n_ft <= seq_len, FLEXCO_ESHAPE, "finetune window [%d, %d) exceeds seq_len %d", m.ft_pos0,
+                 m.ft_pos0 + m.n_ft, seq_len);
+    EW(launch_copy_rows(boff(y, (size_t)m.ft_tok0 * hidden, e), hidden * e, boff(saved_in, (size_t)m.ft_pos0 * hidden, e),
+                        hidden * e, m.n_ft, hidden * e, s));
+  }
+  if (m.n_lora == 0) return FLEXCO_OK;
+  const size_t need = adapter_fwd_bytes(dtype, hidden, b, m.T, m.n_lora);
+  FLEXCO_CHECK(ws != nullptr && ws_bytes >= need, FLEXCO_EWORKSPACE, "adapter forward needs %zu workspace bytes, got %zu",
+               need, ws_bytes);
+  if (adapter_mfma_ok(dtype, hidden, b)) {
+    // r = relu(y W_down^T) for every token row in bf16 (zero rows where the token carries no adapter), then
+    // y += r W_up^T as a projection with K = b whose residual is y itself
+    LoraShrinkArgs sa;
+    memset(&sa, 0, sizeof(sa));
+    sa.X[0] = (const bf16_t*)y; sa.ldx[0] = hidden; sa.S[0] = (const bf16_t*)ad->w_down; sa.lds[0] = hidden; sa.K[0] = hidden;
+    sa.out_ext[0] = (bf16_t*)ws; sa.row_adapter = m.tok_adapter; sa.want[0] = -1; sa.rows = m.T; sa.r = b; sa.scale = 1.f;
+    sa.relu = 1;
+    LR(launch_lora_shrink_mfma(sa, 1, s));
+    const int32_t rc = launch_gemm(ws, ad->w_up, y, nullptr, y, m.T, hidden, b, b, b, hidden, hidden, false, dtype, s, nullptr,
+                                   nullptr, 0);
+    if (rc != FLEXCO_EUNSUPPORTED) return rc;
+    return fail(FLEXCO_EUNSUPPORTED, "adapter forward: the K = %d projection is not covered", b);
+  }
+  float* u = (float*)ws;
+  KernelTimerScope ts(FLEXCO_K_LORA, s);
+  FLEXCO_TRY(launch_lora_shrink(y, hidden, ad->w_down, u, m.n_lora, hidden, b, dtype, m.lora_tok, s));
+  FLEXCO_TRY(launch_relu_mask(u, nullptr, (size_t)m.n_lora * b, s));
+  return launch_lora_expand(u, ad->w_up, y, hidden, m.n_lora, hidden, b, 1.f, dtype, m.lora_tok, s);
+}
+
+extern "C" int32_t flexco_adapter_bwd(int32_t dtype, int32_t hidden, const flexco_adapter* ad, const void* saved_in,
+                                      int32_t seq_len, int32_t win_start, int32_t win_len, void* dY, void* ws,
+                                      size_t ws_bytes, void* stream) {
+  clear_error();
+  FLEXCO_TRY(check_adapter(dtype, hidden, ad, true));
+  FLEXCO_CHECK(saved_in && dY && ws, FLEXCO_EINVAL, "NULL argument");
+  FLEXCO_CHECK(win_start >= 0 && win_len > 0, FLEXCO_EINVAL, "window [%d, +%d) is invalid", win_start, win_len);
+  FLEXCO_CHECK(win_start + win_len <= seq_len, FLEXCO_ESHAPE, "window end %d exceeds seq_len %d", win_start + win_len, seq_len);
+  FLEXCO_CHECK(aligned16(saved_in) && aligned16(dY) && aligned16(ws) && aligned16(ad->w_down) && aligned16(ad->w_up),
+               FLEXCO_EINVAL, "misaligned pointer");
+  const int b = ad->bottleneck, n = win_len;
+  const size_t need = adapter_bwd_bytes(dtype, hidden, b, n);
+  FLEXCO_CHECK(ws_bytes >= need, FLEXCO_EWORKSPACE, "adapter backward needs %zu workspace bytes, got %zu", need, ws_bytes);
+  hipStream_t s = (hipStream_t)stream;
+  Carver cv{(char*)ws};
+  float* u = (float*)cv.take(sizeof(float) * (size_t)n * b);
+  float* t = (float*)cv.take(sizeof(float) * (size_t)n * b);
+  const void* x_w = boff(saved_in, (size_t)win_start * hidden, esize(dtype));
+  if (adapter_mfma_ok(dtype, hidden, b)) {
+    bf16_t* t_ext = (bf16_t*)cv.take(sizeof(bf16_t) * (size_t)n * b);
+    bf16_t* w_up_t = (bf16_t*)cv.take(sizeof(bf16_t) * (size_t)b * hidden);
+    // u = relu(x W_down^T) and t = dY W_up in one launch, t masked by the ReLU
+    LoraTransposeArgs ta;
+    memset(&ta, 0, sizeof(ta));
+    ta.B[0] = (const bf16_t*)ad->w_up; ta.Bt[0] = w_up_t; ta.out[0] = hidden; ta.r = b;
+    LR(launch_lora_transpose(ta, 1, s));
+    LoraShrinkArgs sa;
+    memset(&sa, 0, sizeof(sa));
+    sa.rows = n; sa.r = b; sa.scale = 1.f; sa.f32_lo = 0; sa.f32_hi = n; sa.relu = 1;
+    sa.X[0] = (const bf16_t*)x_w; sa.ldx[0] = hidden; sa.S[0] = (const bf16_t*)ad->w_down; sa.lds[0] = hidden; sa.K[0] = hidden;
+    sa.out_f32[0] = u;
+    sa.X[1] = (const bf16_t*)dY; sa.ldx[1] = hidden; sa.S[1] = w_up_t; sa.lds[1] = hidden; sa.K[1] = hidden; sa.out_f32[1] = t;
+    LR(launch_lora_shrink_mfma(sa, 2, s));
+    LR(launch_relu_bwd_mask(u, t, t_ext, (size_t)n * b, s));
+    // dW_up[o, j] += sum_m dY[m, o] u[m, j];  dW_down[j, i] += sum_m x[m, i] t[m, j]   (before dY changes)
+    LoraOuterArgs outer;
+    memset(&outer, 0, sizeof(outer));
+    outer.n = n; outer.r = b; outer.scale = 1.f; outer.count = 2;
+    outer.X[0] = (const bf16_t*)dY; outer.ldx[0] = hidden; outer.U[0] = u; outer.G[0] = ad->dw_up; outer.g_i[0] = b;
+    outer.g_j[0] = 1; outer.n_long[0] = hidden;
+    outer.X[1] = (const bf16_t*)x_w; outer.ldx[1] = hidden; outer.U[1] = t; outer.G[1] = ad->dw_down; outer.g_i[1] = 1;
+    outer.g_j[1] = hidden; outer.n_long[1] = hidden;
+    LR(launch_lora_outer_batch(outer, s));
+    // dY += t W_down: the input-gradient form with K = b, dY as its own residual
+    const int32_t rc = launch_gemm(t_ext, ad->w_down, dY, nullptr, dY, n, hidden, b, b, hidden, hidden, hidden, true, dtype, s,
+                                   nullptr, nullptr, 0);
+    if (rc != FLEXCO_EUNSUPPORTED) return rc;
+    return fail(FLEXCO_EUNSUPPORTED, "adapter backward: the K = %d projection is not covered", b);
+  }
+  KernelTimerScope ts(FLEXCO_K_LORA, s);
+  // u = relu(x W_down^T); t = (dY W_up) masked; dW_up += dY^T u; dW_down += t^T x; dY += t W_down
+  return launch_lora_bwd(x_w, hidden, dY, hidden, ad->w_down, ad->w_up, ad->dw_down, ad->dw_up, dY, hidden, u, t, n, hidden,
+                         hidden, b, 1.f, dtype, s, true);
+}

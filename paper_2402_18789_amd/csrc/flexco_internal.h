@@ -31,8 +31,11 @@ struct LoraShrinkArgs {     // out[z][row][rank] = sum_k X[z][row, k] S[z][rank,
   float* part;
   int part_slots;           // products the scratch is sized for
   int ksplit;               // set by the launcher
+  int relu;                 // bit z set: product z passes through max(., 0) before it is written (bottleneck adapters)
 };
 constexpr int LORA_SHRINK_SPLITS = 8;
+// t[i] <- 0 where u[i] <= 0 (the ReLU's backward mask, u = the ReLU's output); t_ext[i] = bf16(t[i])
+int32_t launch_relu_bwd_mask(const float* u, float* t, void* t_ext, size_t count, hipStream_t s);
 struct LoraTransposeArgs { const bf16_t* B[LORA_MATS]; bf16_t* Bt[LORA_MATS]; int out[LORA_MATS]; int r; };
 // batch of rank-r gradient products  G_e(i, j) += scale * sum_m X_e[m, i] U_e[m, j], m < n, i < n_long_e, j < r
 constexpr int LORA_OUTER_MAX = 2 * LORA_MATS;
@@ -160,7 +163,8 @@ int32_t launch_lora_expand(const float* u, const void* B, void* y, size_t ldy, i
                            int dtype, const int32_t* row_idx, hipStream_t s);
 int32_t launch_lora_bwd(const void* x, size_t ldx, const void* dy, size_t lddy, const void* A, const void* B,
                         float* dA, float* dB, void* dx, size_t lddx, float* u_ws, float* t_ws, int n, int in,
-                        int out, int r, float scale, int dtype, hipStream_t s);
+                        int out, int r, float scale, int dtype, hipStream_t s, bool relu = false);
+int32_t launch_relu_mask(float* u, float* t, size_t count, hipStream_t s);
 
 int32_t launch_attention_generic(const flexco_layer_cfg& c, const flexco_maps& m, const void* q, size_t ldq,
                                  const flexco_kv_pool& pool, float* part_ml, float* part_acc, hipStream_t s);

@@ -750,6 +750,22 @@ static int32_t lora_dispatch(int op, const void* X, size_t ldx, const void* S, s
   return lora_ops<64>(op, X, ldx, S, s_i, s_j, U, Y, ldy, G, g_i, g_j, n, n_long, r, scale, dtype, row_idx, s);
 }
 
+// u <- relu(u); where u <= 0 the matching element of t (if given) is zeroed: the ReLU's backward mask
+__global__ __launch_bounds__(256) void relu_mask_kernel(float* __restrict__ u, float* __restrict__ t, size_t count) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= count) return;
+  if (!(u[i] > 0.f)) {
+    u[i] = 0.f;
+    if (t) t[i] = 0.f;
+  }
+}
+
+int32_t launch_relu_mask(float* u, float* t, size_t count, hipStream_t s) {
+  if (count == 0) return FLEXCO_OK;
+  hipLaunchKernelGGL(relu_mask_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s, u, t, count);
+  return post_launch("relu_mask");
+}
+
 // u[n, r] = x[rows, in] A^T,  A [r, in]; rows = row_idx[0..n) or 0..n
 int32_t launch_lora_shrink(const void* x, size_t ldx, const void* A, float* u, int n, int in, int r, int dtype,
                            const int32_t* row_idx, hipStream_t s) {
@@ -764,12 +780,14 @@ int32_t launch_lora_expand(const float* u, const void* B, void* y, size_t ldy, i
 
 // Gradients of one LoRA bypass on n rows (Sec. 4.1 form y = scale (x A^T) B^T):
 //   u = x A^T; t = dy B; dB += scale dy^T u; dA += scale t^T x; dx += scale t A
+// With relu (a bottleneck adapter: y = relu(x A^T) B^T) u becomes relu(u) and t is zeroed where u <= 0.
 int32_t launch_lora_bwd(const void* x, size_t ldx, const void* dy, size_t lddy, const void* A, const void* B,
                         float* dA, float* dB, void* dx, size_t lddx, float* u_ws, float* t_ws, int n, int in,
-                        int out, int r, float scale, int dtype, hipStream_t s) {
+                        int out, int r, float scale, int dtype, hipStream_t s, bool relu) {
   int32_t rc;
   if ((rc = lora_dispatch(0, x, ldx, A, 1, (size_t)in, u_ws, nullptr, 0, nullptr, 0, 0, n, in, r, 0.f, dtype, s))) return rc;
   if ((rc = lora_dispatch(0, dy, lddy, B, (size_t)r, 1, t_ws, nullptr, 0, nullptr, 0, 0, n, out, r, 0.f, dtype, s))) return rc;
+  if (relu && (rc = launch_relu_mask(u_ws, t_ws, (size_t)n * r, s))) return rc;
   if ((rc = lora_dispatch(2, dy, lddy, nullptr, 0, 0, u_ws, nullptr, 0, dB, (size_t)r, 1, n, out, r, scale, dtype, s))) return rc;
   if ((rc = lora_dispatch(2, x, ldx, nullptr, 0, 0, t_ws, nullptr, 0, dA, 1, (size_t)in, n, in, r, scale, dtype, s))) return rc;
   if (dx)

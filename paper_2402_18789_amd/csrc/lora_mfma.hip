@@ -102,6 +102,7 @@ __global__ __launch_bounds__(1024) void lora_shrink_kernel(LoraShrinkArgs a) {
         a.part[((size_t)(z * a.ksplit + blockIdx.z) * a.rows) * a.r + o] = v;
         continue;
       }
+      if (a.relu >> z & 1) v = fmaxf(v, 0.f);
       if (a.out_f32[z] && out_ok && orow >= a.f32_lo && orow < a.f32_hi)
         a.out_f32[z][(size_t)(orow - a.f32_lo) * a.r + rank] = v;
       if (a.out_ext[z]) a.out_ext[z][o] = (bf16_t)(out_ok ? v * a.scale : 0.f);
@@ -121,9 +122,19 @@ __global__ __launch_bounds__(256) void lora_shrink_finalize_kernel(LoraShrinkArg
   float v = 0.f;
   if (out_ok)   // (a tile without any adapter row wrote no partial products)
     for (int ks = 0; ks < a.ksplit; ++ks) v += a.part[((size_t)(z * a.ksplit + ks) * a.rows) * a.r + o];
+  if (a.relu >> z & 1) v = fmaxf(v, 0.f);
   if (a.out_f32[z] && out_ok && orow >= a.f32_lo && orow < a.f32_hi)
     a.out_f32[z][(size_t)(orow - a.f32_lo) * a.r + rank] = v;
   if (a.out_ext[z]) a.out_ext[z][o] = (bf16_t)(out_ok ? v * a.scale : 0.f);
+}
+
+__global__ __launch_bounds__(256) void relu_bwd_mask_kernel(const float* __restrict__ u, float* __restrict__ t,
+                                                            bf16_t* __restrict__ t_ext, size_t count) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= count) return;
+  const float v = u[i] > 0.f ? t[i] : 0.f;
+  t[i] = v;
+  if (t_ext) t_ext[i] = (bf16_t)v;
 }
 
 // Bt[j][o] = B[o][j]
@@ -355,6 +366,12 @@ int32_t launch_lora_shrink_mfma(const LoraShrinkArgs& a_in, int n_mats, hipStrea
     hipLaunchKernelGGL(lora_shrink_finalize_kernel, dim3((unsigned)(((size_t)a.rows * a.r + 255) / 256), n_mats), dim3(256),
                        0, s, a);
   return post("lora_shrink");
+}
+
+int32_t launch_relu_bwd_mask(const float* u, float* t, void* t_ext, size_t count, hipStream_t s) {
+  if (count == 0) return FLEXCO_OK;
+  hipLaunchKernelGGL(relu_bwd_mask_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s, u, t, (bf16_t*)t_ext, count);
+  return post("relu_bwd_mask");
 }
 
 int32_t launch_lora_transpose(const LoraTransposeArgs& a, int n_mats, hipStream_t s) {

@@ -45,6 +45,8 @@ def say(msg):
 @pytest.mark.parametrize("M,N,K,trans", [(68, 768, 256, 0), (68, 256, 688, 0), (33, 100, 72, 1), (256, 512, 1024, 0),
                                          (1024, 1536, 512, 0), (300, 1408, 512, 1), (256, 4096, 1024, 1),
                                          (1, 256, 256, 0), (129, 384, 136, 0),
+                                         # a single k-stage (the bottleneck adapter's two projections)
+                                         (200, 512, 64, 0), (130, 640, 64, 1),
                                          # >= 192 tiles of 256 x 256: the large-tile kernel, ragged in M and N,
                                          # odd and even numbers of k-stages
                                          (300, 49160, 320, 0), (520, 24584, 192, 0), (256, 49152, 64, 0),
