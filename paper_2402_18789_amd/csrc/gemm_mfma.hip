@@ -533,6 +533,42 @@ static int pick_splits(int M, int N, int K, int tiles, size_t part_elems, int wa
   return best;
 }
 
+// Tile shapes of a forward-form product by estimated time.  A launch runs in rounds of one block per CU; a
+// round costs the tile's area over the rate its kernel sustains with the chip full (measured, relative:
+// 256 x 256 tiles 1.24, 256 x 192 1.09, 128 x 192 1.0, 128 x 128 0.875).  Candidates: columns [0, 256 a) in
+// 256-wide tiles and the rest in ONE of the three narrower shapes, as two launches (a partial last round of
+// wide tiles is what the narrower ones avoid); a = 0 is a single shape for the whole matrix.
+struct GemmPlan {
+  int a256;    // number of 256-wide column tiles
+  int rest;    // shape of the remaining columns: 0 = 128 x 128, 1 = 128 x 192, 2 = 256 x 192
+};
+static GemmPlan plan_forward(int M, int N) {
+  const int CU = 256;
+  auto rounds = [&](long tiles) { return (double)((tiles + CU - 1) / CU); };
+  const long tm256 = (M + 255) / 256, tm128 = (M + 127) / 128;
+  const double c256 = 256.0 * 256 / 1.24;
+  const long tm_rest[3] = {tm128, tm128, tm256};
+  const int bn_rest[3] = {128, 192, 192};
+  const double c_rest[3] = {128.0 * 128 / 0.875, 128.0 * 192 / 1.0, 256.0 * 192 / 1.09};
+  GemmPlan best{0, 0};
+  double best_t = 1e300;
+  const int n256 = (N + 255) / 256;
+  for (int a = n256; a >= 0; --a) {
+    const int rest = N - 256 * a;                   // columns left for the narrower tiles
+    if (rest < 0 && a != n256) continue;
+    const double t_a = a ? rounds(tm256 * a) * c256 : 0.0;
+    if (rest <= 0) {
+      if (t_a < best_t - 1e-9) { best_t = t_a; best = GemmPlan{a, 0}; }
+      continue;
+    }
+    for (int sh = 2; sh >= 0; --sh) {
+      const double t = t_a + rounds(tm_rest[sh] * ((rest + bn_rest[sh] - 1) / bn_rest[sh])) * c_rest[sh];
+      if (t < best_t - 1e-9) { best_t = t; best = GemmPlan{a, sh}; }
+    }
+  }
+  return best;
+}
+
 int32_t launch_gemm_mfma(const void* A, const void* W, void* C, const void* bias, const void* residual, int M, int N,
                          int K, size_t lda, size_t ldw, size_t ldc, size_t ldr, bool trans_w, const GemmExt* ext_in,
                          hipStream_t s, float* part, size_t part_elems, int timer_id) {
@@ -561,40 +597,23 @@ int32_t launch_gemm_mfma(const void* A, const void* W, void* C, const void* bias
     if (sp > 1)
       return launch_cfg<128, 128, false>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, ext, s, timer_id, part, sp);
   }
-  // Forward form: tile shapes by estimated time.  A launch runs in rounds of one block per CU; a round
-  // costs the tile's area over the rate its kernel sustains with the chip full (measured, relative:
-  // 256 x 256 tiles 1.24, 256 x 192 1.09, 128 x 192 1.0, 128 x 128 0.875).  Candidates: one shape for
-  // the whole matrix, or columns [0, 256 a) in 256-wide tiles and the rest in 192-wide ones, as two
-  // launches (a partial last round of wide tiles is what the narrower ones avoid).
-  const int CU = 256;
-  auto rounds = [&](long tiles) { return (double)((tiles + CU - 1) / CU); };
-  const long tm256 = (M + 255) / 256, tm128 = (M + 127) / 128;
-  const double c256 = 256.0 * 256 / 1.24, c256n = 256.0 * 192 / 1.09, c128n = 128.0 * 192 / 1.0, c128 = 128.0 * 128 / 0.875;
-  double best = rounds(tm128 * ((N + 127) / 128)) * c128;
-  int shape = 0, a_best = 0;                        // 0: 128 x 128, 1: 128 x 192, 2: 256-wide (a tiles) + 192-wide
-  {
-    const double t = rounds(tm128 * ((N + 191) / 192)) * c128n;
-    if (t < best) { best = t; shape = 1; }
-  }
-  const int n256 = (N + 255) / 256;
-  for (int a = n256; a >= 0; --a) {
-    const int rest = N - 256 * a;                   // columns left for 192-wide tiles
-    if (rest < 0 && a != n256) continue;
-    const long b = rest > 0 ? (rest + 191) / 192 : 0;
-    const double t = (a ? rounds(tm256 * a) * c256 : 0.0) + (b ? rounds(tm256 * b) * c256n : 0.0);
-    if (t < best - 1e-9) { best = t; shape = 2; a_best = a; }
-  }
-  if (shape == 0) return launch_cfg<128, 128, false>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, ext, s, timer_id);
-  if (shape == 1) return launch_cfg<128, 192, false>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, ext, s, timer_id);
-  const int n1 = std::min(N, 256 * a_best);
+  const GemmPlan pl = plan_forward(M, N);
+  const int n1 = std::min(N, 256 * pl.a256);
   if (n1 > 0)
     FLEXCO_TRY((launch_cfg<256, 256, false>(A, W, C, bias, residual, M, n1, K, lda, ldw, ldc, ldr, sub_ext(ext, 0, n1), s,
                                             timer_id)));
   if (n1 < N) {
     const bf16_t* W1 = (const bf16_t*)W + (size_t)n1 * ldw;
-    return launch_cfg<256, 192, false>(A, W1, (bf16_t*)C + n1, bias ? (const bf16_t*)bias + n1 : nullptr,
-                                       residual ? (const bf16_t*)residual + n1 : nullptr, M, N - n1, K, lda, ldw, ldc, ldr,
-                                       sub_ext(ext, n1, N), s, timer_id, nullptr, 1, n1 == 0);
+    bf16_t* C1 = (bf16_t*)C + n1;
+    const bf16_t* b1 = bias ? (const bf16_t*)bias + n1 : nullptr;
+    const bf16_t* r1 = residual ? (const bf16_t*)residual + n1 : nullptr;
+    const GemmExt e1 = sub_ext(ext, n1, N);
+    const bool first = n1 == 0;
+    if (pl.rest == 0)
+      return launch_cfg<128, 128, false>(A, W1, C1, b1, r1, M, N - n1, K, lda, ldw, ldc, ldr, e1, s, timer_id, nullptr, 1, first);
+    if (pl.rest == 1)
+      return launch_cfg<128, 192, false>(A, W1, C1, b1, r1, M, N - n1, K, lda, ldw, ldc, ldr, e1, s, timer_id, nullptr, 1, first);
+    return launch_cfg<256, 192, false>(A, W1, C1, b1, r1, M, N - n1, K, lda, ldw, ldc, ldr, e1, s, timer_id, nullptr, 1, first);
   }
   return FLEXCO_OK;
 }
@@ -613,38 +632,23 @@ int32_t launch_gemm_glu_mfma(const void* A, const void* W, void* act, int M, int
   GemmGlu glu;
   glu.F = F; glu.col0 = 0; glu.save_gate = (bf16_t*)save_gate; glu.save_up = (bf16_t*)save_up;
   glu.save_row0 = save_row0; glu.save_rows = save_gate ? save_rows : 0; glu.ld_save = ld_save;
-  const int N = 2 * F, CU = 256;
-  auto rounds = [&](long tiles) { return (double)((tiles + CU - 1) / CU); };
-  const long tm256 = (M + 255) / 256, tm128 = (M + 127) / 128;
-  const double c256 = 256.0 * 256 / 1.24, c256n = 256.0 * 192 / 1.09, c128n = 128.0 * 192 / 1.0, c128 = 128.0 * 128 / 0.875;
-  double best = rounds(tm128 * ((N + 127) / 128)) * c128;
-  int shape = 0, a_best = 0;
-  {
-    const double t = rounds(tm128 * ((N + 191) / 192)) * c128n;
-    if (t < best) { best = t; shape = 1; }
-  }
-  const int n256 = (N + 255) / 256;
-  for (int a = n256; a >= 0; --a) {
-    const int rest = N - 256 * a;
-    if (rest < 0 && a != n256) continue;
-    const long b = rest > 0 ? (rest + 191) / 192 : 0;
-    const double t = (a ? rounds(tm256 * a) * c256 : 0.0) + (b ? rounds(tm256 * b) * c256n : 0.0);
-    if (t < best - 1e-9) { best = t; shape = 2; a_best = a; }
-  }
-  if (shape == 0)
-    return launch_cfg<128, 128, false, true>(A, W, act, nullptr, nullptr, M, N, K, lda, ldw, ld_act, 0, ext, s, timer_id,
-                                             nullptr, 1, true, &glu);
-  if (shape == 1)
-    return launch_cfg<128, 192, false, true>(A, W, act, nullptr, nullptr, M, N, K, lda, ldw, ld_act, 0, ext, s, timer_id,
-                                             nullptr, 1, true, &glu);
-  const int n1 = std::min(N, 256 * a_best);        // interleaved columns of the 256-wide tiles = 2 x their act columns
+  const int N = 2 * F;
+  const GemmPlan pl = plan_forward(M, N);
+  const int n1 = std::min(N, 256 * pl.a256);        // interleaved columns of the 256-wide tiles = 2 x their act columns
   if (n1 > 0)
     FLEXCO_TRY((launch_cfg<256, 256, false, true>(A, W, act, nullptr, nullptr, M, n1, K, lda, ldw, ld_act, 0, ext, s,
                                                   timer_id, nullptr, 1, true, &glu)));
   if (n1 < N) {
     glu.col0 = n1 / 2;
-    return launch_cfg<256, 192, false, true>(A, W, act, nullptr, nullptr, M, N - n1, K, lda, ldw, ld_act, 0, ext, s,
-                                             timer_id, nullptr, 1, n1 == 0, &glu);
+    const bool first = n1 == 0;
+    if (pl.rest == 0)
+      return launch_cfg<128, 128, false, true>(A, W, act, nullptr, nullptr, M, N - n1, K, lda, ldw, ld_act, 0, ext, s, timer_id,
+                                               nullptr, 1, first, &glu);
+    if (pl.rest == 1)
+      return launch_cfg<128, 192, false, true>(A, W, act, nullptr, nullptr, M, N - n1, K, lda, ldw, ld_act, 0, ext, s, timer_id,
+                                               nullptr, 1, first, &glu);
+    return launch_cfg<256, 192, false, true>(A, W, act, nullptr, nullptr, M, N - n1, K, lda, ldw, ld_act, 0, ext, s, timer_id,
+                                             nullptr, 1, first, &glu);
   }
   return FLEXCO_OK;
 }
