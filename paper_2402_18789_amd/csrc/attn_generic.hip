@@ -99,12 +99,13 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(const int32_t* __restric
                                                         const float* __restrict__ part_ml,
                                                         const float* __restrict__ part_acc, T* __restrict__ out,
                                                         size_t ldo, float* __restrict__ lse, int nq, int nkv, int d,
-                                                        int cols_per_tile) {
+                                                        int cols_per_tile, int skip_single_split) {
   const int t = blockIdx.x, h = blockIdx.y;
   const int group = nq / nkv, kvh = h / group;
   const int tile = tok_tile[t];
   const int c = (t - tile_tok0[tile]) * group + h % group;
   const int nsplit = tile_nsplit[tile], part0 = tile_part0[tile];
+  if (skip_single_split && nsplit == 1) return;   // the attention kernel has written these rows itself
   float M = -INFINITY;
   for (int s = 0; s < nsplit; ++s) {
     const size_t idx = ((size_t)(part0 + s) * nkv + kvh) * cols_per_tile + c;
@@ -304,11 +305,12 @@ int32_t launch_attention_generic(const flexco_layer_cfg& c, const flexco_maps& m
 }
 
 int32_t launch_attention_merge(const flexco_layer_cfg& c, const flexco_maps& m, const float* part_ml,
-                               const float* part_acc, void* out, size_t ldo, float* lse, hipStream_t s) {
+                               const float* part_acc, void* out, size_t ldo, float* lse, hipStream_t s,
+                               bool skip_single_split) {
   const int cpt = m.tile_tokens * (c.n_q_heads / c.n_kv_heads);
   DISPATCH_T(c.dtype, hipLaunchKernelGGL((attn_merge_kernel<T>), dim3(m.T, c.n_q_heads), dim3(64), 0, s, m.tok_tile,
                                          m.tile_tok0, m.tile_nsplit, m.tile_part0, part_ml, part_acc, (T*)out, ldo,
-                                         lse, c.n_q_heads, c.n_kv_heads, c.head_dim, cpt));
+                                         lse, c.n_q_heads, c.n_kv_heads, c.head_dim, cpt, skip_single_split ? 1 : 0));
   return post_launch("attn_merge");
 }
 

@@ -35,6 +35,10 @@ struct FwdArgs {
       *item_split, *item_ntiles;
   int max_pages, nq, nkv, n_items, split_pages;
   float scale_log2;   // log2(e) / sqrt(d)
+  // a tile with a single key split needs no merge: its rows go straight to the output
+  bf16_t* out;
+  size_t ldo;
+  float* lse;         // or NULL
 };
 
 constexpr int D = 128, PS = 16;
@@ -203,6 +207,22 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(FwdArgs a, const bf1
     float lsum = l[cs];
     lsum += __shfl_xor(lsum, 16, 64);
     lsum += __shfl_xor(lsum, 32, 64);
+    if (a.tile_nsplit[tile] == 1) {   // the whole key range in one split: normalise and write the output rows
+      if (c < a.tile_ntok[tile] * group) {
+        const int t = a.tile_tok0[tile] + c / group, h = kvh * group + c % group;
+        const float inv = 1.0f / lsum;
+        bf16_t* po = a.out + (size_t)t * a.ldo + h * D + 4 * g;
+#pragma unroll
+        for (int mt = 0; mt < 8; ++mt) {
+          bf16x4 v;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) v[q] = (bf16_t)(o[cs][mt][q] * inv);
+          *reinterpret_cast<bf16x4*>(po + mt * 16) = v;
+        }
+        if (a.lse && g == 0) a.lse[(size_t)t * a.nq + h] = m[cs] * 0.6931471805599453f + __logf(lsum);
+      }
+      continue;
+    }
     if (c < a.tile_ntok[tile] * group) {
       const size_t idx = ((size_t)(a.tile_part0[tile] + split) * a.nkv + kvh) * cpt + c;
       if (g == 0) {
@@ -219,10 +239,11 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(FwdArgs a, const bf1
 }  // namespace
 
 int32_t launch_attention_mfma(const flexco_layer_cfg& c, const flexco_maps& m, const void* q, size_t ldq,
-                              const flexco_kv_pool& pool, float* part_ml, float* part_acc, hipStream_t s) {
+                              const flexco_kv_pool& pool, float* part_ml, float* part_acc, void* out, size_t ldo,
+                              float* lse, hipStream_t s) {
   const int group = c.n_q_heads / c.n_kv_heads;
   if (c.dtype != FLEXCO_BF16 || c.head_dim != D || c.page_size != PS || group > 16 || ldq % 8 != 0 ||
-      m.kv_split_pages > 64)
+      m.kv_split_pages > 64 || ldo % 4 != 0 || ((uintptr_t)out & 7))
     return FLEXCO_EUNSUPPORTED;
   FwdArgs a;
   a.tok_pos = m.tok_pos; a.block_table = m.block_table; a.tile_req = m.tile_req; a.tile_tok0 = m.tile_tok0;
@@ -231,6 +252,7 @@ int32_t launch_attention_mfma(const flexco_layer_cfg& c, const flexco_maps& m, c
   a.max_pages = m.max_pages; a.nq = c.n_q_heads; a.nkv = c.n_kv_heads; a.n_items = m.n_items;
   a.split_pages = m.kv_split_pages;
   a.scale_log2 = 1.4426950408889634f / sqrtf((float)D);
+  a.out = (bf16_t*)out; a.ldo = ldo; a.lse = lse;
   hipLaunchKernelGGL(attn_fwd_mfma_kernel, dim3((m.n_items * c.n_kv_heads + 3) / 4), dim3(256), 0, s, a,
                      (const bf16_t*)q, ldq, (const bf16_t*)pool.k_pages, (const bf16_t*)pool.v_pages, part_ml,
                      part_acc);

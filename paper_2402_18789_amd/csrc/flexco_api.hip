@@ -579,18 +579,20 @@ int32_t run_attention(const flexco_layer_cfg& c, const flexco_maps& m, const voi
                       const flexco_kv_pool& pool, void* out, size_t ldo, float* lse, float* part_ml, float* part_acc,
                       hipStream_t s) {
   int32_t rc;
+  bool direct = true;    // the matrix-core kernel writes the rows of single-split tiles itself
   {
     KernelTimerScope ts(FLEXCO_K_ATTN_FWD, s);
-    rc = launch_attention_mfma(c, m, q, ldq, pool, part_ml, part_acc, s);
+    rc = launch_attention_mfma(c, m, q, ldq, pool, part_ml, part_acc, out, ldo, lse, s);
   }
   if (rc == FLEXCO_EUNSUPPORTED) {
     clear_error();
+    direct = false;
     KernelTimerScope ts(FLEXCO_K_GENERIC, s);
     rc = launch_attention_generic(c, m, q, ldq, pool, part_ml, part_acc, s);
   }
   if (rc) return rc;
   KernelTimerScope ts(FLEXCO_K_ATTN_MERGE, s);
-  return launch_attention_merge(c, m, part_ml, part_acc, out, ldo, lse, s);
+  return launch_attention_merge(c, m, part_ml, part_acc, out, ldo, lse, s, direct);
 }
 
 }  // namespace

@@ -170,13 +170,14 @@ int32_t launch_attention_generic(const flexco_layer_cfg& c, const flexco_maps& m
                                  const flexco_kv_pool& pool, float* part_ml, float* part_acc, hipStream_t s);
 // bf16, head_dim 128, page_size 16, group <= 16; otherwise FLEXCO_EUNSUPPORTED without launching
 int32_t launch_attention_mfma(const flexco_layer_cfg& c, const flexco_maps& m, const void* q, size_t ldq,
-                              const flexco_kv_pool& pool, float* part_ml, float* part_acc, hipStream_t s);
+                              const flexco_kv_pool& pool, float* part_ml, float* part_acc, void* out, size_t ldo,
+                              float* lse, hipStream_t s);
 // bf16 window backward on the matrix cores; FLEXCO_EUNSUPPORTED (nothing launched) for other shapes
 int32_t launch_attention_bwd_mfma(const flexco_layer_cfg& c, const flexco_kv_pool& pool, const int32_t* seq_pages,
                                   int win_start, int win_len, const void* q, const float* lse, const float* delta,
                                   const void* dout, void* dq, float* dk_accum, float* dv_accum, hipStream_t s);
 int32_t launch_attention_merge(const flexco_layer_cfg& c, const flexco_maps& m, const float* part_ml,
-                               const float* part_acc, void* out, size_t ldo, float* lse, hipStream_t s);
+                               const float* part_acc, void* out, size_t ldo, float* lse, hipStream_t s, bool skip_single_split = false);
 int32_t launch_attention_delta(const flexco_layer_cfg& c, const void* out, const void* dout, float* delta, int n,
                                hipStream_t s);
 int32_t launch_attention_bwd_generic(const flexco_layer_cfg& c, const flexco_kv_pool& pool, const int32_t* seq_pages,
