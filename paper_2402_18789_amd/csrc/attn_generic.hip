@@ -99,7 +99,7 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(const int32_t* __restric
                                                         const float* __restrict__ part_ml,
                                                         const float* __restrict__ part_acc, T* __restrict__ out,
                                                         size_t ldo, float* __restrict__ lse, int nq, int nkv, int d,
-                                                        int cols_per_tile, int skip_single_split) {
+                                                        int cols_per_tile, int skip_single_split, AttnKeep keep) {
   const int t = blockIdx.x, h = blockIdx.y;
   const int group = nq / nkv, kvh = h / group;
   const int tile = tok_tile[t];
@@ -118,6 +118,7 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(const int32_t* __restric
     if (ms > -INFINITY) L += part_ml[idx * 2 + 1] * __expf(ms - M);
   }
   const float inv = 1.0f / L;
+  const bool kept = keep.lse2 && t >= keep.tok0 && t < keep.tok0 + keep.n;
   for (int dd = threadIdx.x; dd < d; dd += 64) {
     float acc = 0.f;
     for (int s = 0; s < nsplit; ++s) {
@@ -126,8 +127,12 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(const int32_t* __restric
       if (ms > -INFINITY) acc += part_acc[idx * d + dd] * __expf(ms - M);
     }
     st(out + (size_t)t * ldo + h * d + dd, acc * inv);
+    if (kept) st((T*)keep.out2 + ((size_t)(t - keep.tok0) * nq + h) * d + dd, acc * inv);
   }
-  if (lse && threadIdx.x == 0) lse[(size_t)t * nq + h] = M + __logf(L);
+  if (threadIdx.x == 0) {
+    if (lse) lse[(size_t)t * nq + h] = M + __logf(L);
+    if (kept) keep.lse2[(size_t)(t - keep.tok0) * nq + h] = M + __logf(L);
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -306,11 +311,13 @@ int32_t launch_attention_generic(const flexco_layer_cfg& c, const flexco_maps& m
 
 int32_t launch_attention_merge(const flexco_layer_cfg& c, const flexco_maps& m, const float* part_ml,
                                const float* part_acc, void* out, size_t ldo, float* lse, hipStream_t s,
-                               bool skip_single_split) {
+                               bool skip_single_split, const AttnKeep* keep_in) {
+  AttnKeep keep{nullptr, nullptr, 0, 0};
+  if (keep_in) keep = *keep_in;
   const int cpt = m.tile_tokens * (c.n_q_heads / c.n_kv_heads);
   DISPATCH_T(c.dtype, hipLaunchKernelGGL((attn_merge_kernel<T>), dim3(m.T, c.n_q_heads), dim3(64), 0, s, m.tok_tile,
                                          m.tile_tok0, m.tile_nsplit, m.tile_part0, part_ml, part_acc, (T*)out, ldo,
-                                         lse, c.n_q_heads, c.n_kv_heads, c.head_dim, cpt, skip_single_split ? 1 : 0));
+                                         lse, c.n_q_heads, c.n_kv_heads, c.head_dim, cpt, skip_single_split ? 1 : 0, keep));
   return post_launch("attn_merge");
 }
 

@@ -39,6 +39,7 @@ struct FwdArgs {
   bf16_t* out;
   size_t ldo;
   float* lse;         // or NULL
+  AttnKeep keep;      // second copy of the finetune window's rows
 };
 
 constexpr int D = 128, PS = 16;
@@ -220,6 +221,17 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(FwdArgs a, const bf1
           *reinterpret_cast<bf16x4*>(po + mt * 16) = v;
         }
         if (a.lse && g == 0) a.lse[(size_t)t * a.nq + h] = m[cs] * 0.6931471805599453f + __logf(lsum);
+        if (a.keep.lse2 && t >= a.keep.tok0 && t < a.keep.tok0 + a.keep.n) {
+          bf16_t* p2 = (bf16_t*)a.keep.out2 + ((size_t)(t - a.keep.tok0) * a.nq + h) * D + 4 * g;
+#pragma unroll
+          for (int mt = 0; mt < 8; ++mt) {
+            bf16x4 v;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) v[q] = (bf16_t)(o[cs][mt][q] * inv);
+            *reinterpret_cast<bf16x4*>(p2 + mt * 16) = v;
+          }
+          if (g == 0) a.keep.lse2[(size_t)(t - a.keep.tok0) * a.nq + h] = m[cs] * 0.6931471805599453f + __logf(lsum);
+        }
       }
       continue;
     }
@@ -240,7 +252,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(FwdArgs a, const bf1
 
 int32_t launch_attention_mfma(const flexco_layer_cfg& c, const flexco_maps& m, const void* q, size_t ldq,
                               const flexco_kv_pool& pool, float* part_ml, float* part_acc, void* out, size_t ldo,
-                              float* lse, hipStream_t s) {
+                              float* lse, hipStream_t s, const AttnKeep* keep) {
   const int group = c.n_q_heads / c.n_kv_heads;
   if (c.dtype != FLEXCO_BF16 || c.head_dim != D || c.page_size != PS || group > 16 || ldq % 8 != 0 ||
       m.kv_split_pages > 64 || ldo % 4 != 0 || ((uintptr_t)out & 7))
@@ -253,6 +265,7 @@ int32_t launch_attention_mfma(const flexco_layer_cfg& c, const flexco_maps& m, c
   a.split_pages = m.kv_split_pages;
   a.scale_log2 = 1.4426950408889634f / sqrtf((float)D);
   a.out = (bf16_t*)out; a.ldo = ldo; a.lse = lse;
+  a.keep = keep ? *keep : AttnKeep{nullptr, nullptr, 0, 0};
   hipLaunchKernelGGL(attn_fwd_mfma_kernel, dim3((m.n_items * c.n_kv_heads + 3) / 4), dim3(256), 0, s, a,
                      (const bf16_t*)q, ldq, (const bf16_t*)pool.k_pages, (const bf16_t*)pool.v_pages, part_ml,
                      part_acc);

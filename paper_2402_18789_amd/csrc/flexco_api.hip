@@ -577,12 +577,12 @@ int32_t backward_projection(const flexco_layer_cfg& c, const flexco_lora* lora, 
 
 int32_t run_attention(const flexco_layer_cfg& c, const flexco_maps& m, const void* q, size_t ldq,
                       const flexco_kv_pool& pool, void* out, size_t ldo, float* lse, float* part_ml, float* part_acc,
-                      hipStream_t s) {
+                      hipStream_t s, const AttnKeep* keep = nullptr) {
   int32_t rc;
   bool direct = true;    // the matrix-core kernel writes the rows of single-split tiles itself
   {
     KernelTimerScope ts(FLEXCO_K_ATTN_FWD, s);
-    rc = launch_attention_mfma(c, m, q, ldq, pool, part_ml, part_acc, out, ldo, lse, s);
+    rc = launch_attention_mfma(c, m, q, ldq, pool, part_ml, part_acc, out, ldo, lse, s, keep);
   }
   if (rc == FLEXCO_EUNSUPPORTED) {
     clear_error();
@@ -592,7 +592,7 @@ int32_t run_attention(const flexco_layer_cfg& c, const flexco_maps& m, const voi
   }
   if (rc) return rc;
   KernelTimerScope ts(FLEXCO_K_ATTN_MERGE, s);
-  return launch_attention_merge(c, m, part_ml, part_acc, out, ldo, lse, s, direct);
+  return launch_attention_merge(c, m, part_ml, part_acc, out, ldo, lse, s, direct, keep);
 }
 
 }  // namespace
@@ -742,7 +742,11 @@ static int32_t layer_forward_impl(const flexco_layer_cfg* cfg, const flexco_base
   const int qd = c.n_q_heads * c.head_dim, kd = c.n_kv_heads * c.head_dim, qkvd = qd + 2 * kd;
 
   // attention side
-  EW(launch_rmsnorm(x_in, w->g1, k.h, T, H, c.rms_eps, dt, s));
+  // (the finetune window's rows of x, x2, the attention output and its log-sum-exp - what graph pruning keeps,
+  // Alg. 1 - are written to the sequence's state by the kernels that read or produce them anyway)
+  const size_t p0 = m.ft_pos0;
+  EW(launch_rmsnorm(x_in, w->g1, k.h, T, H, c.rms_eps, dt, s, ft ? (void*)boff(ft->saved_x, p0 * H, e) : nullptr, m.ft_tok0,
+                    m.n_ft));
   {
     const int tg[3] = {FLEXCO_T_Q, FLEXCO_T_K, FLEXCO_T_V}, c0[3] = {0, qd, qd + kd};
     FLEXCO_TRY(forward_projection(c, ad, m, k.h, H, w->wqkv, w->bqkv, nullptr, 0, k.qkv, qkvd, tg, c0, 3, k, ft, s));
@@ -758,13 +762,16 @@ static int32_t layer_forward_impl(const flexco_layer_cfg* cfg, const flexco_base
   }
   EW(launch_rope_append(c, k.qkv, m.tok_pos, m.slot, *pool, T, m.ft_tok0, m.n_ft, m.ft_pos0,
                         ft ? ft->q_cache : nullptr, s));
-  FLEXCO_TRY(run_attention(c, m, k.qkv, qkvd, *pool, k.attn, qd, ft ? k.lse : nullptr, k.part_ml, k.part_acc, s));
+  const AttnKeep keep{ft ? (void*)boff(ft->saved_attn, p0 * qd, e) : nullptr, ft ? ft->lse + p0 * c.n_q_heads : nullptr,
+                      m.ft_tok0, ft ? m.n_ft : 0};
+  FLEXCO_TRY(run_attention(c, m, k.qkv, qkvd, *pool, k.attn, qd, nullptr, k.part_ml, k.part_acc, s, &keep));
   {
     const int tg[1] = {FLEXCO_T_O}, c0[1] = {0};
     FLEXCO_TRY(forward_projection(c, ad, m, k.attn, qd, w->wo, nullptr, x_in, H, k.x2, H, tg, c0, 1, k, ft, s));
   }
   // MLP side
-  EW(launch_rmsnorm(k.x2, w->g2, k.h, T, H, c.rms_eps, dt, s));
+  EW(launch_rmsnorm(k.x2, w->g2, k.h, T, H, c.rms_eps, dt, s, ft ? (void*)boff(ft->saved_x2, p0 * H, e) : nullptr, m.ft_tok0,
+                    m.n_ft));
   GluOut glu{k.act, (size_t)F, false};
   {
     const int tg[2] = {FLEXCO_T_GATE, FLEXCO_T_UP}, c0[2] = {0, F};
@@ -781,10 +788,10 @@ static int32_t layer_forward_impl(const flexco_layer_cfg* cfg, const flexco_base
     const int tg[1] = {FLEXCO_T_DOWN}, c0[1] = {0};
     FLEXCO_TRY(forward_projection(c, ad, m, k.act, F, w->wd, nullptr, k.x2, H, x_out, H, tg, c0, 1, k, ft, s));
   }
-  // keep what graph pruning leaves alive for the finetune rows (Alg. 1), at their positions
-  if (ft) {
+  // where the gated projection did not run (fp32), gate and up are still in the workspace: copy the window's rows
+  if (ft && !glu.done) {
     const int n = m.n_ft;
-    const size_t t0 = m.ft_tok0, p0 = m.ft_pos0;
+    const size_t t0 = m.ft_tok0;
     CopyRowsBatch cb;
     size_t wb[8];
     memset(&cb, 0, sizeof(cb));
@@ -793,14 +800,8 @@ static int32_t layer_forward_impl(const flexco_layer_cfg* cfg, const flexco_base
       cb.src[q] = (const char*)src; cb.ld_src[q] = ld_src; cb.dst[q] = (char*)dst; cb.ld_dst[q] = ld_dst;
       cb.width16[q] = (int)(width / 16); wb[q] = width;
     };
-    add(boff(x_in, t0 * H, e), H * e, boff(ft->saved_x, p0 * H, e), H * e, H * e);
-    add(boff(k.x2, t0 * H, e), H * e, boff(ft->saved_x2, p0 * H, e), H * e, H * e);
-    if (!glu.done) {   // (the gated projection has written them itself)
-      add(boff(k.gu, t0 * 2 * F, e), 2 * F * e, boff(ft->saved_gate, p0 * F, e), F * e, F * e);
-      add(boff(k.gu, t0 * 2 * F + F, e), 2 * F * e, boff(ft->saved_up, p0 * F, e), F * e, F * e);
-    }
-    add(boff(k.attn, t0 * qd, e), qd * e, boff(ft->saved_attn, p0 * qd, e), qd * e, qd * e);
-    add(k.lse + t0 * c.n_q_heads, c.n_q_heads * 4, ft->lse + p0 * c.n_q_heads, c.n_q_heads * 4, (size_t)c.n_q_heads * 4);
+    add(boff(k.gu, t0 * 2 * F, e), 2 * F * e, boff(ft->saved_gate, p0 * F, e), F * e, F * e);
+    add(boff(k.gu, t0 * 2 * F + F, e), 2 * F * e, boff(ft->saved_up, p0 * F, e), F * e, F * e);
     EW(launch_copy_rows_batch(cb, n, wb, s));
   }
   return FLEXCO_OK;

@@ -121,7 +121,8 @@ int32_t launch_lora_outer_batch(const LoraOuterArgs& a, hipStream_t s);
 int32_t launch_lora_outer_bf16(const void* X, size_t ldx, const float* U, float* G, size_t g_i, size_t g_j, int n,
                                int n_long, int r, float scale, hipStream_t s);
 
-int32_t launch_rmsnorm(const void* x, const void* g, void* h, int T, int H, float eps, int dtype, hipStream_t s);
+int32_t launch_rmsnorm(const void* x, const void* g, void* h, int T, int H, float eps, int dtype, hipStream_t s,
+                       void* save = nullptr, int save_row0 = 0, int save_rows = 0);
 int32_t launch_rmsnorm_bwd(const void* x, const void* g, const void* dh, const void* add, void* dx, int T, int H,
                            float eps, int dtype, hipStream_t s, void* hn = nullptr);
 int32_t launch_rope_append(const flexco_layer_cfg& c, void* qkv, const int32_t* tok_pos, const int32_t* slot,
@@ -169,15 +170,23 @@ int32_t launch_relu_mask(float* u, float* t, size_t count, hipStream_t s);
 int32_t launch_attention_generic(const flexco_layer_cfg& c, const flexco_maps& m, const void* q, size_t ldq,
                                  const flexco_kv_pool& pool, float* part_ml, float* part_acc, hipStream_t s);
 // bf16, head_dim 128, page_size 16, group <= 16; otherwise FLEXCO_EUNSUPPORTED without launching
+// The finetune window's rows of the attention output and of the log-sum-exp, written a second time where the
+// backward pass keeps them (row i of the window at out2 + i * nq d / lse2 + i * nq); lse2 = NULL: none.
+struct AttnKeep {
+  void* out2;
+  float* lse2;
+  int tok0, n;      // the window's token rows [tok0, tok0 + n)
+};
 int32_t launch_attention_mfma(const flexco_layer_cfg& c, const flexco_maps& m, const void* q, size_t ldq,
                               const flexco_kv_pool& pool, float* part_ml, float* part_acc, void* out, size_t ldo,
-                              float* lse, hipStream_t s);
+                              float* lse, hipStream_t s, const AttnKeep* keep = nullptr);
 // bf16 window backward on the matrix cores; FLEXCO_EUNSUPPORTED (nothing launched) for other shapes
 int32_t launch_attention_bwd_mfma(const flexco_layer_cfg& c, const flexco_kv_pool& pool, const int32_t* seq_pages,
                                   int win_start, int win_len, const void* q, const float* lse, const float* delta,
                                   const void* dout, void* dq, float* dk_accum, float* dv_accum, hipStream_t s);
 int32_t launch_attention_merge(const flexco_layer_cfg& c, const flexco_maps& m, const float* part_ml,
-                               const float* part_acc, void* out, size_t ldo, float* lse, hipStream_t s, bool skip_single_split = false);
+                               const float* part_acc, void* out, size_t ldo, float* lse, hipStream_t s, bool skip_single_split = false,
+                               const AttnKeep* keep = nullptr);
 int32_t launch_attention_delta(const flexco_layer_cfg& c, const void* out, const void* dout, float* delta, int n,
                                hipStream_t s);
 int32_t launch_attention_bwd_generic(const flexco_layer_cfg& c, const flexco_kv_pool& pool, const int32_t* seq_pages,

@@ -40,21 +40,30 @@ __device__ inline float block_sum256(float v, float* red /* >= 4 floats of LDS *
 // vector width and every pointer and row pitch is 16-byte aligned).
 template <typename T, bool VEC>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const T* __restrict__ x, const T* __restrict__ g,
-                                                      T* __restrict__ h, int H, float eps) {
+                                                      T* __restrict__ h, int H, float eps, T* __restrict__ save,
+                                                      int save_row0, int save_rows) {
   __shared__ float red[4];
   constexpr int N = Vec<T>::N;
   const size_t row = blockIdx.x;
   const T* xr = x + row * H;
+  // rows [save_row0, save_row0 + save_rows) also leave a copy of the INPUT row in `save` (the finetune
+  // window's rows of an activation graph pruning keeps, written by the kernel that reads them anyway)
+  T* sv = (save && (int)row >= save_row0 && (int)row < save_row0 + save_rows) ? save + (row - save_row0) * H : nullptr;
   float ss = 0.f;
   if (VEC) {
     for (int i = threadIdx.x * N; i < H; i += 256 * N) {
       float v[N];
       Vec<T>::load(xr + i, v);
+      if (sv) Vec<T>::store(sv + i, v);
 #pragma unroll
       for (int j = 0; j < N; ++j) ss += v[j] * v[j];
     }
   } else {
-    for (int i = threadIdx.x; i < H; i += 256) { float v = ld(xr + i); ss += v * v; }
+    for (int i = threadIdx.x; i < H; i += 256) {
+      const float v = ld(xr + i);
+      if (sv) st(sv + i, v);
+      ss += v * v;
+    }
   }
   ss = block_sum256(ss, red);
   const float rstd = 1.0f / sqrtf(ss / H + eps);
@@ -592,11 +601,12 @@ static bool vec_ok(int dtype, int width, std::initializer_list<const void*> ptrs
     else { constexpr bool VEC = false; DISPATCH_T(dtype, __VA_ARGS__); }     \
   } while (0)
 
-int32_t launch_rmsnorm(const void* x, const void* g, void* h, int T_, int H, float eps, int dtype, hipStream_t s) {
+int32_t launch_rmsnorm(const void* x, const void* g, void* h, int T_, int H, float eps, int dtype, hipStream_t s,
+                       void* save, int save_row0, int save_rows) {
   if (T_ == 0) return FLEXCO_OK;
-  const bool vec = vec_ok(dtype, H, {x, g, h});
+  const bool vec = vec_ok(dtype, H, {x, g, h, save});
   DISPATCH_TV(dtype, vec, hipLaunchKernelGGL((rmsnorm_kernel<T, VEC>), dim3(T_), dim3(256), 0, s, (const T*)x,
-                                             (const T*)g, (T*)h, H, eps));
+                                             (const T*)g, (T*)h, H, eps, (T*)save, save_row0, save ? save_rows : 0));
   return post_launch("rmsnorm");
 }
 
