@@ -41,8 +41,9 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 #define FLEXCO_LDS __attribute__((address_space(3)))
 
 struct BwdArgs {
-  const bf16_t *q, *dout;
-  const float *lse, *delta;
+  const bf16_t *q, *dout, *out;
+  const float* lse;
+  float* delta;       // [s, nq]: written by kernel A (row sums of dO (.) O), read by kernel B
   const bf16_t *kp, *vp;
   const int32_t* pages;
   bf16_t* dq;
@@ -113,7 +114,20 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_mfma_kernel(BwdArgs a) {
     }
   }
   const float lse2 = a.lse[(size_t)rcl * a.nq + h] * LOG2E;
-  const float delta = a.delta[(size_t)rcl * a.nq + h];
+  // delta_i = sum_d dO_id O_id of the wavefront's rows: the four lanes of a row hold 32 of its 128 d each
+  float delta = 0.f;
+  {
+    const bf16_t* orow = a.out + ((size_t)rcl * a.nq + h) * D + g * 8;
+#pragma unroll
+    for (int dc = 0; dc < 4; ++dc) {
+      const bf16x8 of = *reinterpret_cast<const bf16x8*>(orow + dc * 32);
+#pragma unroll
+      for (int q = 0; q < 8; ++q) delta += (float)dof[dc][q] * (float)of[q];
+    }
+    delta += __shfl_xor(delta, 16, 64);
+    delta += __shfl_xor(delta, 32, 64);
+    if (kh == 0 && g == 0 && row_ok) a.delta[(size_t)row_c * a.nq + h] = delta;   // for kernel B
+  }
 
   f32x4 dq[8];
 #pragma unroll
@@ -417,11 +431,12 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_mfma_kernel(BwdArgs a) {
 }  // namespace
 
 int32_t launch_attention_bwd_mfma(const flexco_layer_cfg& c, const flexco_kv_pool& pool, const int32_t* seq_pages,
-                                  int win_start, int win_len, const void* q, const float* lse, const float* delta,
-                                  const void* dout, void* dq, float* dk_accum, float* dv_accum, hipStream_t s) {
+                                  int win_start, int win_len, const void* q, const void* out, const float* lse,
+                                  float* delta, const void* dout, void* dq, float* dk_accum, float* dv_accum,
+                                  hipStream_t s) {
   if (c.dtype != FLEXCO_BF16 || c.head_dim != D || c.page_size != PS) return FLEXCO_EUNSUPPORTED;
   BwdArgs a;
-  a.q = (const bf16_t*)q; a.dout = (const bf16_t*)dout; a.lse = lse; a.delta = delta;
+  a.q = (const bf16_t*)q; a.dout = (const bf16_t*)dout; a.out = (const bf16_t*)out; a.lse = lse; a.delta = delta;
   a.kp = (const bf16_t*)pool.k_pages; a.vp = (const bf16_t*)pool.v_pages; a.pages = seq_pages;
   a.dq = (bf16_t*)dq; a.dk_accum = dk_accum; a.dv_accum = dv_accum;
   a.w0 = win_start; a.s = win_len; a.l = win_start + win_len; a.nq = c.n_q_heads; a.nkv = c.n_kv_heads;

@@ -844,11 +844,12 @@ static int32_t attention_window_bwd_impl(const flexco_layer_cfg& c, const flexco
                                          const void* out, const float* lse, const void* dout, void* dq,
                                          float* dk_accum, float* dv_accum, float* delta, hipStream_t s) {
   KernelTimerScope ts(FLEXCO_K_ATTN_BWD, s);
-  FLEXCO_TRY(launch_attention_delta(c, out, dout, delta, win_len, s));
-  int32_t rc = launch_attention_bwd_mfma(c, pool, seq_pages, win_start, win_len, q, lse, delta, dout, dq, dk_accum,
+  // (the matrix-core dQ kernel computes delta = rowsum(dO (.) O) of its rows itself and leaves it for the dK/dV kernel)
+  int32_t rc = launch_attention_bwd_mfma(c, pool, seq_pages, win_start, win_len, q, out, lse, delta, dout, dq, dk_accum,
                                          dv_accum, s);
   if (rc != FLEXCO_EUNSUPPORTED) return rc;
   clear_error();
+  FLEXCO_TRY(launch_attention_delta(c, out, dout, delta, win_len, s));
   return launch_attention_bwd_generic(c, pool, seq_pages, win_start, win_len, q, lse, delta, dout, dq, dk_accum,
                                       dv_accum, s);
 }

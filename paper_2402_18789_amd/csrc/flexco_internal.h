@@ -182,8 +182,9 @@ int32_t launch_attention_mfma(const flexco_layer_cfg& c, const flexco_maps& m, c
                               float* lse, hipStream_t s, const AttnKeep* keep = nullptr);
 // bf16 window backward on the matrix cores; FLEXCO_EUNSUPPORTED (nothing launched) for other shapes
 int32_t launch_attention_bwd_mfma(const flexco_layer_cfg& c, const flexco_kv_pool& pool, const int32_t* seq_pages,
-                                  int win_start, int win_len, const void* q, const float* lse, const float* delta,
-                                  const void* dout, void* dq, float* dk_accum, float* dv_accum, hipStream_t s);
+                                  int win_start, int win_len, const void* q, const void* out, const float* lse,
+                                  float* delta, const void* dout, void* dq, float* dk_accum, float* dv_accum,
+                                  hipStream_t s);
 int32_t launch_attention_merge(const flexco_layer_cfg& c, const flexco_maps& m, const float* part_ml,
                                const float* part_acc, void* out, size_t ldo, float* lse, hipStream_t s, bool skip_single_split = false,
                                const AttnKeep* keep = nullptr);
