@@ -133,6 +133,44 @@ def test_ia3_small_bf16_group5_bias():
     run_case(SMALL_BF16_G5, b, ft_window=64, prefill_chunk=40, bwd_windows=[33, 131], seed=5, tol_k=4e-2)
 
 
+def test_ia3_inference_only_batch():
+    """No finetune request (ft state = NULL): requests served with the adapter and base-model requests side by side."""
+    cfg, seed = SMALL_BF16, 11
+    say("(IA)^3 layer, inference-only batch")
+    batch = gen.with_adapters(gen.mixed_batch(16, seed, decode_ctx=(1, 16, 17, 130), prefill=[(0, 33, 70), (48, 20, 90)]), [0, -1])
+    W, ia3 = gen.layer_weights(cfg, seed, 0), gen.ia3_weights(cfg, seed, 0)
+    dev, dia = HH.DeviceLayer(cfg, W, None), HH.DeviceIa3(cfg, ia3)
+    o_pool, d_pool = OL.KVPool(batch.num_pages, cfg.page_size, cfg.kv_dim), HH.DevicePool(cfg, batch.num_pages)
+    for r in batch.requests:
+        if r.start_pos:
+            k, v = gen.kv_prefix(cfg, seed, 0, r.seq_id, r.start_pos)
+            sl = o_pool.slots(batch.seq_pages[r.seq_id], r.start_pos)
+            o_pool.k[sl], o_pool.v[sl] = k, v
+            d_pool.write_rows(batch.seq_pages[r.seq_id], k, v)
+    db = HH.DeviceBatch(cfg, batch.requests, batch.seq_pages, batch.num_pages)
+    ws = HH.Workspace(dev.c, db.host_maps.T, db.host_maps.n_parts)
+    x = gen.layer_input(cfg, seed, batch.n_tokens)
+    x_d = torch.from_numpy(x).to("cuda", torch.bfloat16)
+    y_d = torch.empty_like(x_d)
+    B.flexco_layer_forward_ia3(dev.c, dev.w, dia.c, db.maps, x_d, y_d, d_pool.c, None, ws.ptr, ws.bytes)
+    torch.cuda.synchronize()
+    om = build_maps(batch.requests, batch.seq_pages, batch.page_size, batch.num_pages)
+    y_o = OI.forward_mixed(cfg, W, ia3, om, x, o_pool, None)
+    assert_close("y", to_np(y_d), y_o, TOL["bf16"])
+    # the base-model requests' rows equal a run without any adapter, bit for bit
+    ones = HH.DeviceIa3(cfg, {k: np.ones_like(v) for k, v in ia3.items()})
+    d_pool2 = HH.DevicePool(cfg, batch.num_pages)
+    d_pool2.k.copy_(d_pool.k)
+    d_pool2.v.copy_(d_pool.v)
+    y2 = torch.empty_like(x_d)
+    B.flexco_layer_forward_ia3(dev.c, dev.w, ones.c, db.maps, x_d, y2, d_pool2.c, None, ws.ptr, ws.bytes)
+    torch.cuda.synchronize()
+    base_rows = om["tok_adapter"] < 0
+    assert base_rows.any() and (~base_rows).any()
+    assert np.array_equal(to_np(y_d)[base_rows], to_np(y2)[base_rows])
+    assert not np.array_equal(to_np(y_d)[~base_rows], to_np(y2)[~base_rows])
+
+
 def test_ia3_error_paths():
     cfg = SMALL_BF16
     W = gen.layer_weights(cfg, 0, 0)
