@@ -97,6 +97,38 @@ def test_default_key_split_follows_the_batch_size():
     assert c_maps(gen.mixed_batch(16, 0, decode_ctx=(300,)), 32, 8, split=64)["kv_split_pages"] == 64   # an explicit value is kept
 
 
+@pytest.mark.parametrize("seed", range(30))
+def test_random_batches_bit_exact_vs_oracle(seed):
+    """Seeded random request mixes (counts, contexts, chunk lengths, adapters, head grouping, key split): the integer
+    maps equal the oracle's bit for bit and the attention work list covers every (token, visible key) once."""
+    g = gen.rng(seed, "random_maps")
+    nq, nkv = [(4, 4), (8, 2), (10, 2), (8, 1), (32, 8), (40, 8), (16, 16)][seed % 7]
+    ctx = g.integers(1, 700, size=int(g.integers(0, 40)))
+    prefill = []
+    for _ in range(int(g.integers(0, 4))):
+        total = int(g.integers(2, 900))
+        start = int(g.integers(0, total - 1))
+        prefill.append((start, int(g.integers(1, total - start + 1)), total))
+    finetune = []
+    if g.integers(0, 2) or (len(ctx) == 0 and not prefill):
+        total = int(g.integers(1, 600))
+        start = int(g.integers(0, total))
+        finetune.append((start, int(g.integers(1, total - start + 1)), total))
+    batch = gen.mixed_batch(16, seed, decode_ctx=ctx, prefill=prefill, finetune=finetune)
+    batch = gen.with_adapters(batch, [int(a) for a in g.integers(-1, 4, size=5)])
+    split = int(g.choice([0, 0, 2, 6, 16, 64]))
+    om = build_maps(batch.requests, batch.seq_pages, batch.page_size, batch.num_pages)
+    cm = c_maps(batch, nq, nkv, split)
+    for k in ("T", "n_req", "n_ft", "n_seg", "max_pages"):
+        assert cm[k] == om[k], k
+    for k in COMMON:
+        assert np.array_equal(cm[k], om[k]), k
+    assert check_attention_cover(om, work_items(cm, batch.page_size))
+    assert cm["n_parts"] == cm["tile_nsplit"].sum() and cm["n_items"] == len(cm["item_tile"])
+    if split:
+        assert cm["kv_split_pages"] == split
+
+
 def test_work_list_is_deterministic():
     a, b = c_maps(gen.batch_c2(0), 32, 8), c_maps(gen.batch_c2(0), 32, 8)
     for k in a:
