@@ -530,7 +530,10 @@ int32_t lora_bwd_prepare(const flexco_layer_cfg& c, const flexco_lora* lora, int
 // buffers stay untouched until then.
 int32_t backward_projection(const flexco_layer_cfg& c, const flexco_lora* lora, int n, const void* dy, int K_dy,
                             const void* W, void* dx, const BwdGroup& g, BwdWs& k, LoraOuterArgs& outer,
-                            hipStream_t s) {
+                            hipStream_t s, int* splits_out = nullptr) {
+  // splits_out: the caller's next kernel reads dx; where the product was cut over K, the partial sums stay in
+  // k.gemm_part ([split][n][N_dx], *splits_out > 1) for that kernel to add, and dx is not written
+  if (splits_out) *splits_out = 1;
   const int dt = c.dtype, r = c.lora_rank, N_dx = g.N_dx;
   const size_t e = esize(dt);
   if (g.fused) {
@@ -560,11 +563,12 @@ int32_t backward_projection(const flexco_layer_cfg& c, const flexco_lora* lora, 
     LR(launch_lora_shrink_mfma(st, g.nact, s));
     if (dx)
       return launch_gemm(dy, W, dx, nullptr, nullptr, n, N_dx, K_dy, K_dy, N_dx, N_dx, 0, true, dt, s, &ext,
-                         k.gemm_part, k.gemm_part_elems);
+                         k.gemm_part, k.gemm_part_elems, splits_out);
     return FLEXCO_OK;
   }
+  // (the unfused LoRA kernels below add into dx: they need it complete)
   if (dx) FLEXCO_TRY(launch_gemm(dy, W, dx, nullptr, nullptr, n, N_dx, K_dy, K_dy, N_dx, N_dx, 0, true, dt, s, nullptr,
-                                 k.gemm_part, k.gemm_part_elems));
+                                 k.gemm_part, k.gemm_part_elems, g.nact == 0 ? splits_out : nullptr));
   for (int z = 0; z < g.nact; ++z) {
     const int t = g.targets[g.act[z]];
     int in, out;
@@ -600,15 +604,17 @@ int32_t run_attention(const flexco_layer_cfg& c, const flexco_maps& m, const voi
 namespace flexco {
 int32_t launch_gemm(const void* A, const void* W, void* C, const void* bias, const void* residual, int M, int N,
                     int K, size_t lda, size_t ldw, size_t ldc, size_t ldr, bool trans_w, int dtype, hipStream_t s,
-                    const GemmExt* ext, float* part, size_t part_elems) {
+                    const GemmExt* ext, float* part, size_t part_elems, int* splits_out) {
+  if (splits_out) *splits_out = 1;
   if (M == 0) return FLEXCO_OK;
   if (dtype == FLEXCO_BF16) {
     const int32_t rc = launch_gemm_mfma(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, trans_w, ext, s, part,
-                                        part_elems, trans_w ? FLEXCO_K_GEMM_BWD : FLEXCO_K_GEMM_FWD);
+                                        part_elems, trans_w ? FLEXCO_K_GEMM_BWD : FLEXCO_K_GEMM_FWD, splits_out);
     if (rc != FLEXCO_EUNSUPPORTED) return rc;
     clear_error();
   }
   if (ext && ext->n > 0) return FLEXCO_EUNSUPPORTED;   // the generic kernel has no rank-r extension
+  if (splits_out) *splits_out = 1;
   KernelTimerScope ts(FLEXCO_K_GENERIC, s);
   return launch_gemm_generic(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, trans_w, dtype, s);
 }
@@ -948,14 +954,18 @@ static int32_t layer_backward_impl(const flexco_layer_cfg* cfg, const flexco_bas
   FLEXCO_TRY(lora_bwd_prepare(c, lora, n, grp, 4, k, ft, win_start, s));
 
   // ---- MLP side: down projection, SwiGLU, gate/up projections, second norm -------------
-  FLEXCO_TRY(backward_projection(c, lora, n, dY, H, w->wd, k.dact, grp[0], k, outer, s));
+  // (where an input-gradient product was cut over K, the kernel that reads it next adds the partial sums itself)
+  int sp_dact = 1, sp_dh2 = 1, sp_dh1 = 1;
+  FLEXCO_TRY(backward_projection(c, lora, n, dY, H, w->wd, k.dact, grp[0], k, outer, s, ia3 ? nullptr : &sp_dact));
   if (ia3) {   // dl_ff += colsum(dact (.) act0) with the rematerialised SwiGLU product; dact <- dact (.) l_ff
     EW(launch_swiglu_remat(gate_w, up_w, k.act, n, F, dt, s));
     EW(launch_ia3_colgrad(k.dact, F, k.act, F, ia3->l_ff, k.colsum_part, ia3->dl_ff, n, F, dt, s));
   }
-  EW(launch_swiglu_bwd(gate_w, up_w, k.dact, k.dgu, n, F, dt, s, act_late ? k.act : nullptr));
-  FLEXCO_TRY(backward_projection(c, lora, n, k.dgu, 2 * F, w->wgu, k.dh, grp[1], k, outer, s));
-  EW(launch_rmsnorm_bwd(x2_w, w->g2, k.dh, dY, k.dx2, n, H, c.rms_eps, dt, s, hn2_late ? k.hn2 : nullptr));
+  EW(launch_swiglu_bwd(gate_w, up_w, k.dact, k.dgu, n, F, dt, s, act_late ? k.act : nullptr,
+                       sp_dact > 1 ? k.gemm_part : nullptr, sp_dact));
+  FLEXCO_TRY(backward_projection(c, lora, n, k.dgu, 2 * F, w->wgu, k.dh, grp[1], k, outer, s, &sp_dh2));
+  EW(launch_rmsnorm_bwd(x2_w, w->g2, k.dh, dY, k.dx2, n, H, c.rms_eps, dt, s, hn2_late ? k.hn2 : nullptr,
+                        sp_dh2 > 1 ? k.gemm_part : nullptr, sp_dh2));
   // ---- output projection ------------------------------------------------------------------
   FLEXCO_TRY(backward_projection(c, lora, n, k.dx2, H, w->wo, k.dattn, grp[2], k, outer, s));
   // ---- attention: dQ of the window, dK/dV of every cached row before its end (Sec. 6.1) ---
@@ -971,10 +981,12 @@ static int32_t layer_backward_impl(const flexco_layer_cfg* cfg, const flexco_bas
                             ia3->dl_v, n, kd, dt, s));
     }
     if (dX || qkv_lora)
-      FLEXCO_TRY(backward_projection(c, lora, n, k.dqkv, qkvd, w->wqkv, dX ? k.dh : nullptr, grp[3], k, outer, s));
+      FLEXCO_TRY(backward_projection(c, lora, n, k.dqkv, qkvd, w->wqkv, dX ? k.dh : nullptr, grp[3], k, outer, s,
+                                     dX ? &sp_dh1 : nullptr));
   }
   // ---- every queued dA / dB product of the window in one launch ----------------------------
-  if (dX) EW(launch_rmsnorm_bwd(x_w, w->g1, k.dh, k.dx2, dX, n, H, c.rms_eps, dt, s, hn_late ? k.hn : nullptr));
+  if (dX) EW(launch_rmsnorm_bwd(x_w, w->g1, k.dh, k.dx2, dX, n, H, c.rms_eps, dt, s, hn_late ? k.hn : nullptr,
+                                sp_dh1 > 1 ? k.gemm_part : nullptr, sp_dh1));
   LR(launch_lora_outer_batch(outer, s));
   return FLEXCO_OK;
 }

@@ -101,7 +101,7 @@ bool kernel_timer_pair(int id, hipEvent_t* start, hipEvent_t* stop, bool first_o
 // part / part_elems: optional fp32 scratch for split-K partial sums (input-gradient form)
 int32_t launch_gemm(const void* A, const void* W, void* C, const void* bias, const void* residual, int M, int N,
                     int K, size_t lda, size_t ldw, size_t ldc, size_t ldr, bool trans_w, int dtype, hipStream_t s,
-                    const GemmExt* ext = nullptr, float* part = nullptr, size_t part_elems = 0);
+                    const GemmExt* ext = nullptr, float* part = nullptr, size_t part_elems = 0, int* splits_out = nullptr);
 int32_t launch_gemm_generic(const void* A, const void* W, void* C, const void* bias, const void* residual, int M,
                             int N, int K, size_t lda, size_t ldw, size_t ldc, size_t ldr, bool trans_w, int dtype,
                             hipStream_t s);
@@ -109,7 +109,7 @@ int32_t launch_gemm_generic(const void* A, const void* W, void* C, const void* b
 int32_t launch_gemm_mfma(const void* A, const void* W, void* C, const void* bias, const void* residual, int M,
                          int N, int K, size_t lda, size_t ldw, size_t ldc, size_t ldr, bool trans_w,
                          const GemmExt* ext, hipStream_t s, float* part = nullptr, size_t part_elems = 0,
-                         int timer_id = -1);
+                         int timer_id = -1, int* splits_out = nullptr);
 // act[M, F] = silu(A Wg^T + ext) * (A Wu^T + ext), W = [Wg ; Wu]; ext entries address the 2F columns
 // [gate | up].  Returns FLEXCO_EUNSUPPORTED (without launching) for shapes it does not cover.
 int32_t launch_gemm_glu_mfma(const void* A, const void* W, void* act, int M, int F, int K, size_t lda, size_t ldw,
@@ -124,7 +124,8 @@ int32_t launch_lora_outer_bf16(const void* X, size_t ldx, const float* U, float*
 int32_t launch_rmsnorm(const void* x, const void* g, void* h, int T, int H, float eps, int dtype, hipStream_t s,
                        void* save = nullptr, int save_row0 = 0, int save_rows = 0);
 int32_t launch_rmsnorm_bwd(const void* x, const void* g, const void* dh, const void* add, void* dx, int T, int H,
-                           float eps, int dtype, hipStream_t s, void* hn = nullptr);
+                           float eps, int dtype, hipStream_t s, void* hn = nullptr,
+                           const float* dh_part = nullptr, int splits = 1);
 int32_t launch_rope_append(const flexco_layer_cfg& c, void* qkv, const int32_t* tok_pos, const int32_t* slot,
                            const flexco_kv_pool& pool, int T, int ft_tok0, int n_ft, int ft_pos0, void* q_cache,
                            hipStream_t s);
@@ -132,7 +133,8 @@ int32_t launch_rope_bwd_pack(const flexco_layer_cfg& c, const void* dq, const fl
                              void* dqkv, int win_start, int n, hipStream_t s);
 int32_t launch_swiglu(const void* gu, void* act, int T, int F, int dtype, hipStream_t s);
 int32_t launch_swiglu_bwd(const void* gate, const void* up, const void* dact, void* dgu, int n, int F, int dtype,
-                          hipStream_t s, void* act = nullptr);
+                          hipStream_t s, void* act = nullptr,
+                          const float* dact_part = nullptr, int splits = 1);
 int32_t launch_swiglu_remat(const void* gate, const void* up, void* act, int n, int F, int dtype, hipStream_t s);
 // (IA)^3 forward scale of up to two column ranges of the listed token rows (see ia3_scale_rows_kernel)
 struct Ia3ScaleArgs {

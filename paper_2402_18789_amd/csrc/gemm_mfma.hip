@@ -453,7 +453,7 @@ template <int BM, int BN, bool TRANS, bool GLU = false>
 int32_t launch_cfg(const void* A, const void* W, void* C, const void* bias, const void* res, int M, int N, int K,
                    size_t lda, size_t ldw, size_t ldc, size_t ldr, const GemmExt& ext, hipStream_t s,
                    int timer_id, float* part = nullptr, int splits = 1, bool first_of_call = true,
-                   const GemmGlu* glu_in = nullptr) {
+                   const GemmGlu* glu_in = nullptr, bool skip_reduce = false) {
   auto kern = gemm_bf16_kernel<BM, BN, TRANS, GLU>;   // all LDS is static
   GemmGlu glu;
   if (glu_in) glu = *glu_in; else memset(&glu, 0, sizeof(glu));
@@ -471,7 +471,7 @@ int32_t launch_cfg(const void* A, const void* W, void* C, const void* bias, cons
   FLEXCO_LAUNCH_TIMED(kern, dim3(tiles_m * tiles_n, splits), (const bf16_t*)A, (const bf16_t*)W, (bf16_t*)C,
                       (const bf16_t*)bias, (const bf16_t*)res, M, N, K, lda, ldw, ldc, ldr, tiles_m, tiles_n, ext,
                       splits > 1 ? part : nullptr, K / splits, glu)
-  if (splits > 1) {
+  if (splits > 1 && !skip_reduce) {
     const size_t quads = ((size_t)M * N + 3) / 4;
     e0 = e1 = nullptr;
     if (timer_id >= 0) (void)kernel_timer_pair(timer_id, &e0, &e1, false);
@@ -571,7 +571,8 @@ static GemmPlan plan_forward(int M, int N) {
 
 int32_t launch_gemm_mfma(const void* A, const void* W, void* C, const void* bias, const void* residual, int M, int N,
                          int K, size_t lda, size_t ldw, size_t ldc, size_t ldr, bool trans_w, const GemmExt* ext_in,
-                         hipStream_t s, float* part, size_t part_elems, int timer_id) {
+                         hipStream_t s, float* part, size_t part_elems, int timer_id, int* splits_out) {
+  if (splits_out) *splits_out = 1;
   // shapes the tiled kernel covers: K in whole 64-wide steps, 16-byte aligned rows
   // (and 8-byte aligned runs of 4 output columns in C, bias and residual)
   if (K % BK != 0 || lda % 8 != 0 || ldw % 8 != 0 || N % 8 != 0 || ldc % 4 != 0 || (residual && ldr % 4 != 0) ||
@@ -586,7 +587,12 @@ int32_t launch_gemm_mfma(const void* A, const void* W, void* C, const void* bias
     // (256 x 128 tiles, one block per CU, were measured slower than two co-resident 128 x 128 blocks)
     const int tiles = ((M + 127) / 128) * ((N + 127) / 128);
     const int sp = part ? pick_splits(M, N, K, tiles, part_elems, 512) : 1;
-    return launch_cfg<128, 128, true>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, ext, s, timer_id, part, sp);
+    // splits_out: the caller's next kernel adds the partial sums itself (part[split][M][N], in split order) and
+    // the reduction launch is left out; bias and residual are then not applied
+    const bool leave = splits_out && sp > 1 && !bias && !residual;
+    if (leave) *splits_out = sp;
+    return launch_cfg<128, 128, true>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, ext, s, timer_id, part, sp, true,
+                                      nullptr, leave);
   }
   if (!ext_fits(ext, false, N)) return FLEXCO_EUNSUPPORTED;
   // A batch of few tokens (decode-only iterations) has one or two row tiles and far fewer output tiles

@@ -81,12 +81,41 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const T* __restrict__ x, c
   }
 }
 
+// v[0..N) = the N consecutive elements at `idx` of a product whose split-K partial sums still lie in
+// part[split][stride]: added in split order and rounded to the storage type, exactly as the reduction
+// kernel would have written them.
+template <typename T, int N>
+__device__ inline void load_split_sum(const float* __restrict__ part, int splits, size_t stride, size_t idx, float* v) {
+#pragma unroll
+  for (int j = 0; j < N; ++j) v[j] = 0.f;
+  for (int sp = 0; sp < splits; ++sp) {
+    const float* p = part + (size_t)sp * stride + idx;
+    if (N % 4 == 0) {
+#pragma unroll
+      for (int q = 0; q < N / 4; ++q) {
+        const f32x4 t = *reinterpret_cast<const f32x4*>(p + 4 * q);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[4 * q + j] += t[j];
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < N; ++j) v[j] += p[j];
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < N; ++j) v[j] = (float)(T)v[j];
+}
+
 // dx = rstd * (g * dh) - x * rstd^3 * mean(x * g * dh)  (+ add);  hn (optional) = x rstd g, the row
 // the forward norm produced (same arithmetic, same bits), for callers that need it again
 template <typename T, bool VEC>
 __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* __restrict__ x, const T* __restrict__ g,
                                                           const T* __restrict__ dh, const T* __restrict__ add,
-                                                          T* __restrict__ dx, T* __restrict__ hn, int H, float eps) {
+                                                          T* __restrict__ dx, T* __restrict__ hn, int H, float eps,
+                                                          const float* __restrict__ dh_part, int splits, size_t stride) {
+  // dh_part: dh still lies as split-K partial sums (see load_split_sum); the row's sums are kept in LDS
+  // between the two passes (dynamic shared memory of H floats, only then)
+  extern __shared__ float dh_row[];
   __shared__ float red[4];
   constexpr int N = Vec<T>::N;
   const size_t row = blockIdx.x;
@@ -98,15 +127,24 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* __restrict__ 
       float v[N], gv[N], dv[N];
       Vec<T>::load(xr + i, v);
       Vec<T>::load(g + i, gv);
-      Vec<T>::load(dr + i, dv);
+      if (dh_part) {
+        load_split_sum<T, N>(dh_part, splits, stride, row * H + i, dv);
+#pragma unroll
+        for (int j = 0; j < N; ++j) dh_row[i + j] = dv[j];
+      } else {
+        Vec<T>::load(dr + i, dv);
+      }
 #pragma unroll
       for (int j = 0; j < N; ++j) { ss += v[j] * v[j]; sd += v[j] * gv[j] * dv[j]; }
     }
   } else {
     for (int i = threadIdx.x; i < H; i += 256) {
       float v = ld(xr + i);
+      float d1;
+      if (dh_part) { load_split_sum<T, 1>(dh_part, splits, stride, row * H + i, &d1); dh_row[i] = d1; }
+      else d1 = ld(dr + i);
       ss += v * v;
-      sd += v * ld(g + i) * ld(dr + i);
+      sd += v * ld(g + i) * d1;
     }
   }
   ss = block_sum256(ss, red);
@@ -118,7 +156,12 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* __restrict__ 
       float v[N], gv[N], dv[N], av[N];
       Vec<T>::load(xr + i, v);
       Vec<T>::load(g + i, gv);
-      Vec<T>::load(dr + i, dv);
+      if (dh_part) {           // (each thread reads back what it wrote itself)
+#pragma unroll
+        for (int j = 0; j < N; ++j) dv[j] = dh_row[i + j];
+      } else {
+        Vec<T>::load(dr + i, dv);
+      }
       if (add) Vec<T>::load(add + row * H + i, av);
       if (hn) {
         float hv[N];
@@ -136,7 +179,7 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* __restrict__ 
   } else {
     for (int i = threadIdx.x; i < H; i += 256) {
       if (hn) st(hn + row * H + i, ld(xr + i) * rstd * ld(g + i));
-      float v = rstd * ld(g + i) * ld(dr + i) - ld(xr + i) * coef;
+      float v = rstd * ld(g + i) * (dh_part ? dh_row[i] : ld(dr + i)) - ld(xr + i) * coef;
       if (add) v += ld(add + row * H + i);
       st(dx + row * H + i, v);
     }
@@ -344,14 +387,18 @@ __global__ __launch_bounds__(256) void swiglu_kernel(const T* __restrict__ gu, T
 template <typename T, bool VEC>
 __global__ __launch_bounds__(256) void swiglu_bwd_kernel(const T* __restrict__ gate, const T* __restrict__ up,
                                                          const T* __restrict__ dact, T* __restrict__ dgu,
-                                                         T* __restrict__ act, int F) {
+                                                         T* __restrict__ act, int F, const float* __restrict__ dact_part,
+                                                         int splits, size_t stride) {
   constexpr int N = VEC ? Vec<T>::N : 1;
   const size_t row = blockIdx.y;
   const int i = (blockIdx.x * 256 + threadIdx.x) * N;
   if (i >= F) return;
   float g[N], u[N], da[N];
-  if (VEC) { Vec<T>::load(gate + row * F + i, g); Vec<T>::load(up + row * F + i, u); Vec<T>::load(dact + row * F + i, da); }
-  else { g[0] = ld(gate + row * F + i); u[0] = ld(up + row * F + i); da[0] = ld(dact + row * F + i); }
+  if (VEC) { Vec<T>::load(gate + row * F + i, g); Vec<T>::load(up + row * F + i, u); }
+  else { g[0] = ld(gate + row * F + i); u[0] = ld(up + row * F + i); }
+  if (dact_part) load_split_sum<T, N>(dact_part, splits, stride, row * F + i, da);   // dact still lies as split-K partial sums
+  else if (VEC) Vec<T>::load(dact + row * F + i, da);
+  else da[0] = ld(dact + row * F + i);
   float dg[N], du[N];
 #pragma unroll
   for (int j = 0; j < N; ++j) {
@@ -611,11 +658,13 @@ int32_t launch_rmsnorm(const void* x, const void* g, void* h, int T_, int H, flo
 }
 
 int32_t launch_rmsnorm_bwd(const void* x, const void* g, const void* dh, const void* add, void* dx, int T_, int H,
-                           float eps, int dtype, hipStream_t s, void* hn) {
+                           float eps, int dtype, hipStream_t s, void* hn, const float* dh_part, int splits) {
   if (T_ == 0) return FLEXCO_OK;
-  const bool vec = vec_ok(dtype, H, {x, g, dh, add, dx, hn});
-  DISPATCH_TV(dtype, vec, hipLaunchKernelGGL((rmsnorm_bwd_kernel<T, VEC>), dim3(T_), dim3(256), 0, s, (const T*)x,
-                                             (const T*)g, (const T*)dh, (const T*)add, (T*)dx, (T*)hn, H, eps));
+  const bool vec = vec_ok(dtype, H, {x, g, dh, add, dx, hn, dh_part});
+  const size_t shm = dh_part ? sizeof(float) * (size_t)H : 0;
+  DISPATCH_TV(dtype, vec, hipLaunchKernelGGL((rmsnorm_bwd_kernel<T, VEC>), dim3(T_), dim3(256), shm, s, (const T*)x,
+                                             (const T*)g, (const T*)dh, (const T*)add, (T*)dx, (T*)hn, H, eps, dh_part,
+                                             splits, (size_t)T_ * H));
   return post_launch("rmsnorm_bwd");
 }
 
@@ -676,12 +725,13 @@ int32_t launch_swiglu(const void* gu, void* act, int T_, int F, int dtype, hipSt
 }
 
 int32_t launch_swiglu_bwd(const void* gate, const void* up, const void* dact, void* dgu, int n, int F, int dtype,
-                          hipStream_t s, void* act) {
+                          hipStream_t s, void* act, const float* dact_part, int splits) {
   if (n == 0) return FLEXCO_OK;
-  const bool vec = vec_ok(dtype, F, {gate, up, dact, dgu, act});
+  const bool vec = vec_ok(dtype, F, {gate, up, dact, dgu, act, dact_part});
   const int per = 256 * (vec ? (dtype == FLEXCO_BF16 ? 8 : 4) : 1);
   DISPATCH_TV(dtype, vec, hipLaunchKernelGGL((swiglu_bwd_kernel<T, VEC>), dim3((F + per - 1) / per, n), dim3(256), 0,
-                                             s, (const T*)gate, (const T*)up, (const T*)dact, (T*)dgu, (T*)act, F));
+                                             s, (const T*)gate, (const T*)up, (const T*)dact, (T*)dgu, (T*)act, F, dact_part,
+                                             splits, (size_t)n * F));
   return post_launch("swiglu_bwd");
 }
 
