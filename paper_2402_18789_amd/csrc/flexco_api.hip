@@ -473,6 +473,7 @@ struct BwdGroup {
   int N_dx;              // width of the projection's input = in_t of every target
   bool fused;            // bf16 matrix-core path: LoRA folded into the GEMM, gradients batched
   int act[3], nact;      // active targets (indices into targets[])
+  bool t_ready;          // fused only: a row kernel writes t_t = dy_t B_t (fp32 and the scaled bf16 copy) before the projection
 };
 
 void plan_group(const flexco_layer_cfg& c, BwdGroup& g) {
@@ -506,7 +507,8 @@ int32_t lora_bwd_prepare(const flexco_layer_cfg& c, const flexco_lora* lora, int
       const int t = g.targets[g.act[a]];
       int in, out;
       target_dims(c, t, &in, &out);
-      ta.B[nz] = (const bf16_t*)lora->B[t]; ta.Bt[nz] = k.lw.bt[t]; ta.out[nz] = out;
+      if (g.t_ready) { ta.B[nz] = nullptr; ta.Bt[nz] = nullptr; ta.out[nz] = 0; }   // (no transposed B needed)
+      else { ta.B[nz] = (const bf16_t*)lora->B[t]; ta.Bt[nz] = k.lw.bt[t]; ta.out[nz] = out; }
       if (ft->saved_u[t]) {
         k.lw.u[t] = ft->saved_u[t] + (size_t)win_start * r;
         continue;
@@ -560,7 +562,7 @@ int32_t backward_projection(const flexco_layer_cfg& c, const flexco_lora* lora, 
       outer.G[q] = lora->dA[t]; outer.g_i[q] = 1; outer.g_j[q] = in; outer.n_long[q] = in;
       outer.count = q + 1;
     }
-    LR(launch_lora_shrink_mfma(st, g.nact, s));
+    if (!g.t_ready) LR(launch_lora_shrink_mfma(st, g.nact, s));
     if (dx)
       return launch_gemm(dy, W, dx, nullptr, nullptr, n, N_dx, K_dy, K_dy, N_dx, N_dx, 0, true, dt, s, &ext,
                          k.gemm_part, k.gemm_part_elems, splits_out);
@@ -932,6 +934,29 @@ static int32_t layer_backward_impl(const flexco_layer_cfg* cfg, const flexco_bas
   grp[3].n_targets = 3; grp[3].targets[0] = FLEXCO_T_Q; grp[3].targets[1] = FLEXCO_T_K; grp[3].targets[2] = FLEXCO_T_V;
   grp[3].col0[1] = qd; grp[3].col0[2] = qd + kd; grp[3].xs[0] = grp[3].xs[1] = grp[3].xs[2] = k.hn; grp[3].N_dx = H;
   for (int gi = 0; gi < 4; ++gi) plan_group(c, grp[gi]);
+  // t_t = dy_t B_t of the down, o and q/k/v targets: by the row kernels that hold the rows of dy_t anyway (dY has a
+  // kernel of its own), where rank and type allow; gate / up keep the shrink launch (their dy comes out of a
+  // kernel that does not own whole rows)
+  const bool row_t = row_lora_ok(dt, c.lora_rank);
+  grp[0].t_ready = grp[0].fused && row_t;
+  grp[2].t_ready = grp[2].fused && row_t;
+  grp[3].t_ready = grp[3].fused && row_t;
+  auto row_lora = [&](const BwdGroup& g) {
+    RowLoraT lt = {};
+    if (!g.t_ready) return lt;
+    lt.r = c.lora_rank; lt.scale = c.lora_scale;
+    for (int i = 0; i < g.n_targets; ++i) {
+      const int t = g.targets[i];
+      if (!has_target(c, t)) continue;
+      // one target: entry 0; the q/k/v group: entry = role (0 q, 1 k, 2 v)
+      const int z = g.n_targets == 1 ? 0 : i;
+      int in, out;
+      target_dims(c, t, &in, &out);
+      lt.col0[z] = g.col0[i]; lt.col1[z] = g.col0[i] + out; lt.B[z] = lora->B[t]; lt.t[z] = k.lw.t[t]; lt.ext[z] = k.lw.ext[t];
+      ++lt.n;
+    }
+    return lt;
+  };
   LoraOuterArgs outer;
   memset(&outer, 0, sizeof(outer));
   outer.n = n; outer.r = c.lora_rank; outer.scale = c.lora_scale;
@@ -952,6 +977,7 @@ static int32_t layer_backward_impl(const flexco_layer_cfg* cfg, const flexco_bas
   if (gu_lora && !hn2_late) EW(launch_rmsnorm(x2_w, w->g2, k.hn2, n, H, c.rms_eps, dt, s));
   if (qkv_lora && !hn_late) EW(launch_rmsnorm(x_w, w->g1, k.hn, n, H, c.rms_eps, dt, s));
   FLEXCO_TRY(lora_bwd_prepare(c, lora, n, grp, 4, k, ft, win_start, s));
+  if (grp[0].t_ready) LR(launch_lora_row_t(dY, H, n, H, row_lora(grp[0]), s));
 
   // ---- MLP side: down projection, SwiGLU, gate/up projections, second norm -------------
   // (where an input-gradient product was cut over K, the kernel that reads it next adds the partial sums itself)
@@ -964,8 +990,11 @@ static int32_t layer_backward_impl(const flexco_layer_cfg* cfg, const flexco_bas
   EW(launch_swiglu_bwd(gate_w, up_w, k.dact, k.dgu, n, F, dt, s, act_late ? k.act : nullptr,
                        sp_dact > 1 ? k.gemm_part : nullptr, sp_dact));
   FLEXCO_TRY(backward_projection(c, lora, n, k.dgu, 2 * F, w->wgu, k.dh, grp[1], k, outer, s, &sp_dh2));
-  EW(launch_rmsnorm_bwd(x2_w, w->g2, k.dh, dY, k.dx2, n, H, c.rms_eps, dt, s, hn2_late ? k.hn2 : nullptr,
-                        sp_dh2 > 1 ? k.gemm_part : nullptr, sp_dh2));
+  {
+    const RowLoraT lt = row_lora(grp[2]);   // dx2 is the output projection's dy
+    EW(launch_rmsnorm_bwd(x2_w, w->g2, k.dh, dY, k.dx2, n, H, c.rms_eps, dt, s, hn2_late ? k.hn2 : nullptr,
+                          sp_dh2 > 1 ? k.gemm_part : nullptr, sp_dh2, &lt));
+  }
   // ---- output projection ------------------------------------------------------------------
   FLEXCO_TRY(backward_projection(c, lora, n, k.dx2, H, w->wo, k.dattn, grp[2], k, outer, s));
   // ---- attention: dQ of the window, dK/dV of every cached row before its end (Sec. 6.1) ---
@@ -973,7 +1002,8 @@ static int32_t layer_backward_impl(const flexco_layer_cfg* cfg, const flexco_bas
                                        ft->dk_accum, ft->dv_accum, k.delta, s));
   // ---- q/k/v side: the window's accumulator rows are complete now (Sec. 7) ---------------
   if (dX || qkv_lora || ia3) {
-    EW(launch_rope_bwd_pack(c, k.dq, ft->dk_accum + w0 * kd, ft->dv_accum + w0 * kd, k.dqkv, win_start, n, s));
+    const RowLoraT lt_qkv = ia3 ? RowLoraT{} : row_lora(grp[3]);
+    EW(launch_rope_bwd_pack(c, k.dq, ft->dk_accum + w0 * kd, ft->dv_accum + w0 * kd, k.dqkv, win_start, n, s, &lt_qkv));
     if (ia3) {   // the k and v column ranges of the packed rows: dl += colsum(d (.) unscaled rows), d <- d (.) l
       EW(launch_ia3_colgrad(boff(k.dqkv, qd, e), qkvd, boff(ft->saved_k0, w0 * kd, e), kd, ia3->l_k, k.colsum_part,
                             ia3->dl_k, n, kd, dt, s));

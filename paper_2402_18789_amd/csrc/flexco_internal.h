@@ -123,14 +123,29 @@ int32_t launch_lora_outer_bf16(const void* X, size_t ldx, const float* U, float*
 
 int32_t launch_rmsnorm(const void* x, const void* g, void* h, int T, int H, float eps, int dtype, hipStream_t s,
                        void* save = nullptr, int save_row0 = 0, int save_rows = 0);
+// The LoRA backward's rank-r products t_z = dy_z B_z (Sec. 4.1 bypass form) of up to three targets whose dy_z are
+// column ranges of ONE row that a row kernel has just produced: that kernel multiplies the row by B_z while it
+// holds it (bf16 only, r = 16 or 32), instead of a shrink launch reading the row back.
+struct RowLoraT {
+  int n;                       // targets (0: nothing to do)
+  int col0[3], col1[3];        // target z owns the row's columns [col0, col1)
+  const void* B[3];            // B_z [col1 - col0, r], row-major
+  float* t[3];                 // [rows, r] fp32, unscaled
+  void* ext[3];                // [rows, r] bf16, times scale: operand of the GEMM extension
+  int r;
+  float scale;
+};
+inline bool row_lora_ok(int dtype, int r) { return dtype == FLEXCO_BF16 && (r == 16 || r == 32); }
 int32_t launch_rmsnorm_bwd(const void* x, const void* g, const void* dh, const void* add, void* dx, int T, int H,
                            float eps, int dtype, hipStream_t s, void* hn = nullptr,
-                           const float* dh_part = nullptr, int splits = 1);
+                           const float* dh_part = nullptr, int splits = 1, const RowLoraT* lt = nullptr);
+// t = dy B for one target over n rows of width `width` (the same row product as a kernel of its own)
+int32_t launch_lora_row_t(const void* dy, size_t lddy, int n, int width, const RowLoraT& lt, hipStream_t s);
 int32_t launch_rope_append(const flexco_layer_cfg& c, void* qkv, const int32_t* tok_pos, const int32_t* slot,
                            const flexco_kv_pool& pool, int T, int ft_tok0, int n_ft, int ft_pos0, void* q_cache,
                            hipStream_t s);
 int32_t launch_rope_bwd_pack(const flexco_layer_cfg& c, const void* dq, const float* dk_rows, const float* dv_rows,
-                             void* dqkv, int win_start, int n, hipStream_t s);
+                             void* dqkv, int win_start, int n, hipStream_t s, const RowLoraT* lt = nullptr);
 int32_t launch_swiglu(const void* gu, void* act, int T, int F, int dtype, hipStream_t s);
 int32_t launch_swiglu_bwd(const void* gate, const void* up, const void* dact, void* dgu, int n, int F, int dtype,
                           hipStream_t s, void* act = nullptr,

@@ -33,6 +33,70 @@ __device__ inline float block_sum256(float v, float* red /* >= 4 floats of LDS *
   return red[0] + red[1] + red[2] + red[3];
 }
 
+// ---- rank-r products of a row with LoRA B matrices, inside the row kernel that produced the row ------------
+// acc[q] += v * B[col][q]: one 2 R-byte row of B per element
+template <int R>
+__device__ inline void lora_acc_row(float (&acc)[R], float v, const bf16_t* __restrict__ brow) {
+#pragma unroll
+  for (int q8 = 0; q8 < R / 8; ++q8) {
+    const bf16x8 b = *reinterpret_cast<const bf16x8*>(brow + 8 * q8);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) acc[8 * q8 + q] += v * (float)b[q];
+  }
+}
+// the same for N consecutive columns: every load is issued before the first multiply-add
+template <int R, int N>
+__device__ inline void lora_acc_cols(float (&acc)[R], const float (&v)[N], const bf16_t* __restrict__ brow0) {
+  bf16x8 b[N][R / 8];
+#pragma unroll
+  for (int j = 0; j < N; ++j)
+#pragma unroll
+    for (int q8 = 0; q8 < R / 8; ++q8) b[j][q8] = *reinterpret_cast<const bf16x8*>(brow0 + (size_t)j * R + 8 * q8);
+#pragma unroll
+  for (int j = 0; j < N; ++j)
+#pragma unroll
+    for (int q8 = 0; q8 < R / 8; ++q8)
+#pragma unroll
+      for (int q = 0; q < 8; ++q) acc[8 * q8 + q] += v[j] * (float)b[j][q8][q];
+}
+// sum of acc over the block's 256 threads (lanes by shuffles, the four wavefronts in order) -> t and ext of `row`
+template <int R>
+__device__ inline void lora_row_finish(float (&acc)[R], float* lds /* 4 R floats */, float* t, bf16_t* ext, size_t row,
+                                       float scale) {
+#pragma unroll
+  for (int q = 0; q < R; ++q) acc[q] = wave_sum(acc[q]);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) {
+#pragma unroll
+    for (int q = 0; q < R; ++q) lds[(threadIdx.x >> 6) * R + q] = acc[q];
+  }
+  __syncthreads();
+  if (threadIdx.x < R) {
+    const float v = lds[threadIdx.x] + lds[R + threadIdx.x] + lds[2 * R + threadIdx.x] + lds[3 * R + threadIdx.x];
+    t[row * R + threadIdx.x] = v;
+    ext[row * R + threadIdx.x] = (bf16_t)(v * scale);
+  }
+}
+
+// t = dy B of one target, one block per row (see RowLoraT)
+template <int R>
+__global__ __launch_bounds__(256) void lora_row_t_kernel(const bf16_t* __restrict__ dy, size_t lddy, int width, RowLoraT lt) {
+  __shared__ float lds[4 * R];
+  const size_t row = blockIdx.x;
+  float acc[R];
+#pragma unroll
+  for (int q = 0; q < R; ++q) acc[q] = 0.f;
+  const bf16_t* B = (const bf16_t*)lt.B[0];
+  for (int i = threadIdx.x * 8; i < width; i += 256 * 8) {
+    const bf16x8 v = *reinterpret_cast<const bf16x8*>(dy + row * lddy + i);
+    float vf[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) vf[j] = (float)v[j];
+    lora_acc_cols<R, 8>(acc, vf, B + (size_t)i * R);
+  }
+  lora_row_finish<R>(acc, lds, lt.t[0], (bf16_t*)lt.ext[0], row, lt.scale);
+}
+
 // --------------------------------------------------------------------------------------
 // RMSNorm forward / backward (one block of 256 threads per row)
 // --------------------------------------------------------------------------------------
@@ -108,11 +172,18 @@ __device__ inline void load_split_sum(const float* __restrict__ part, int splits
 
 // dx = rstd * (g * dh) - x * rstd^3 * mean(x * g * dh)  (+ add);  hn (optional) = x rstd g, the row
 // the forward norm produced (same arithmetic, same bits), for callers that need it again
-template <typename T, bool VEC>
+// R > 0 (bf16, VEC): the produced row dx is also multiplied by a LoRA B matrix (see RowLoraT; one target = the whole row)
+template <typename T, bool VEC, int R = 0>
 __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* __restrict__ x, const T* __restrict__ g,
                                                           const T* __restrict__ dh, const T* __restrict__ add,
                                                           T* __restrict__ dx, T* __restrict__ hn, int H, float eps,
-                                                          const float* __restrict__ dh_part, int splits, size_t stride) {
+                                                          const float* __restrict__ dh_part, int splits, size_t stride,
+                                                          RowLoraT lt) {
+  constexpr int RA = R > 0 ? R : 1;
+  __shared__ float lt_lds[4 * RA];
+  float lt_acc[RA];
+#pragma unroll
+  for (int q = 0; q < RA; ++q) lt_acc[q] = 0.f;
   // dh_part: dh still lies as split-K partial sums (see load_split_sum); the row's sums are kept in LDS
   // between the two passes (dynamic shared memory of H floats, only then)
   extern __shared__ float dh_row[];
@@ -175,7 +246,13 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* __restrict__ 
         if (add) v[j] += av[j];
       }
       Vec<T>::store(dx + row * H + i, v);
+      if constexpr (R > 0) {   // (the values as they were just stored)
+#pragma unroll
+        for (int j = 0; j < N; ++j) v[j] = (float)(T)v[j];
+        lora_acc_cols<R, N>(lt_acc, v, (const bf16_t*)lt.B[0] + (size_t)i * R);
+      }
     }
+    if constexpr (R > 0) lora_row_finish<R>(lt_acc, lt_lds, lt.t[0], (bf16_t*)lt.ext[0], row, lt.scale);
   } else {
     for (int i = threadIdx.x; i < H; i += 256) {
       if (hn) st(hn + row * H + i, ld(xr + i) * rstd * ld(g + i));
@@ -247,11 +324,19 @@ __global__ __launch_bounds__(256) void rope_append_kernel(T* __restrict__ qkv, c
 
 // Backward of the q/k/v rotation for a window: dqkv[n, (nq+2nkv)d] = [rope^T(dq) | rope^T(dk) | dv]
 // dq rows are in the storage type, dk/dv rows are the (float) accumulator rows of the window.
-template <typename T>
+// R > 0 (bf16): the packed row is also multiplied by the LoRA B matrices of q, k, v (see RowLoraT; entry 0 = q,
+// 1 = k, 2 = v, B = NULL where the projection carries no LoRA)
+template <typename T, int R = 0>
 __global__ __launch_bounds__(256) void rope_bwd_pack_kernel(const T* __restrict__ dq, const float* __restrict__ dk,
                                                             const float* __restrict__ dv, T* __restrict__ dqkv,
-                                                            int nq, int nkv, int d, float theta, int win_start) {
+                                                            int nq, int nkv, int d, float theta, int win_start,
+                                                            RowLoraT lt) {
   extern __shared__ float cs[];
+  constexpr int RA = R > 0 ? R : 1;
+  __shared__ float lt_lds[4 * RA];
+  float acc_q[RA], acc_k[RA], acc_v[RA];
+#pragma unroll
+  for (int q = 0; q < RA; ++q) acc_q[q] = acc_k[q] = acc_v[q] = 0.f;
   const int r = blockIdx.x;
   const int pos = win_start + r;
   const int half = d >> 1;
@@ -276,11 +361,36 @@ __global__ __launch_bounds__(256) void rope_bwd_pack_kernel(const T* __restrict_
     }
     const float c = cs[i], sn = cs[half + i];
     // transpose of the rotation: turn by the negative angle
-    st(out + head * d + i, lo * c + hi * sn);
-    st(out + head * d + half + i, hi * c - lo * sn);
+    const float rlo = lo * c + hi * sn, rhi = hi * c - lo * sn;
+    st(out + head * d + i, rlo);
+    st(out + head * d + half + i, rhi);
+    if constexpr (R > 0) {   // (the values as they were just stored)
+      const float vlo = (float)(T)rlo, vhi = (float)(T)rhi;
+      if (head < nq) {
+        if (lt.B[0]) {
+          const bf16_t* b = (const bf16_t*)lt.B[0] + (size_t)(head * d + i) * R;
+          lora_acc_row<R>(acc_q, vlo, b);
+          lora_acc_row<R>(acc_q, vhi, b + (size_t)half * R);
+        }
+      } else if (lt.B[1]) {
+        const bf16_t* b = (const bf16_t*)lt.B[1] + (size_t)((head - nq) * d + i) * R;
+        lora_acc_row<R>(acc_k, vlo, b);
+        lora_acc_row<R>(acc_k, vhi, b + (size_t)half * R);
+      }
+    }
   }
-  for (int idx = threadIdx.x; idx < nkv * d; idx += 256)
-    st(out + (nq + nkv) * d + idx, dv[(size_t)r * nkv * d + idx]);
+  for (int idx = threadIdx.x; idx < nkv * d; idx += 256) {
+    const float v = dv[(size_t)r * nkv * d + idx];
+    st(out + (nq + nkv) * d + idx, v);
+    if constexpr (R > 0) {
+      if (lt.B[2]) lora_acc_row<R>(acc_v, (float)(T)v, (const bf16_t*)lt.B[2] + (size_t)idx * R);
+    }
+  }
+  if constexpr (R > 0) {
+    if (lt.B[0]) lora_row_finish<R>(acc_q, lt_lds, lt.t[0], (bf16_t*)lt.ext[0], r, lt.scale);
+    if (lt.B[1]) lora_row_finish<R>(acc_k, lt_lds, lt.t[1], (bf16_t*)lt.ext[1], r, lt.scale);
+    if (lt.B[2]) lora_row_finish<R>(acc_v, lt_lds, lt.t[2], (bf16_t*)lt.ext[2], r, lt.scale);
+  }
 }
 
 // --------------------------------------------------------------------------------------
@@ -658,13 +768,27 @@ int32_t launch_rmsnorm(const void* x, const void* g, void* h, int T_, int H, flo
 }
 
 int32_t launch_rmsnorm_bwd(const void* x, const void* g, const void* dh, const void* add, void* dx, int T_, int H,
-                           float eps, int dtype, hipStream_t s, void* hn, const float* dh_part, int splits) {
+                           float eps, int dtype, hipStream_t s, void* hn, const float* dh_part, int splits,
+                           const RowLoraT* lt_in) {
   if (T_ == 0) return FLEXCO_OK;
   const bool vec = vec_ok(dtype, H, {x, g, dh, add, dx, hn, dh_part});
   const size_t shm = dh_part ? sizeof(float) * (size_t)H : 0;
+  RowLoraT lt = {};
+  if (lt_in && lt_in->n > 0) {
+    if (!vec || !row_lora_ok(dtype, lt_in->r) || lt_in->n != 1) return fail(FLEXCO_EUNSUPPORTED, "rmsnorm_bwd: row product not covered");
+    lt = *lt_in;
+    const size_t stride = (size_t)T_ * H;
+#define FLEXCO_NORM_BWD_LT(R_)                                                                                     \
+    hipLaunchKernelGGL((rmsnorm_bwd_kernel<bf16_t, true, R_>), dim3(T_), dim3(256), shm, s, (const bf16_t*)x,       \
+                       (const bf16_t*)g, (const bf16_t*)dh, (const bf16_t*)add, (bf16_t*)dx, (bf16_t*)hn, H, eps,   \
+                       dh_part, splits, stride, lt)
+    if (lt.r == 16) FLEXCO_NORM_BWD_LT(16); else FLEXCO_NORM_BWD_LT(32);
+#undef FLEXCO_NORM_BWD_LT
+    return post_launch("rmsnorm_bwd");
+  }
   DISPATCH_TV(dtype, vec, hipLaunchKernelGGL((rmsnorm_bwd_kernel<T, VEC>), dim3(T_), dim3(256), shm, s, (const T*)x,
                                              (const T*)g, (const T*)dh, (const T*)add, (T*)dx, (T*)hn, H, eps, dh_part,
-                                             splits, (size_t)T_ * H));
+                                             splits, (size_t)T_ * H, lt));
   return post_launch("rmsnorm_bwd");
 }
 
@@ -681,12 +805,33 @@ int32_t launch_rope_append(const flexco_layer_cfg& c, void* qkv, const int32_t* 
 }
 
 int32_t launch_rope_bwd_pack(const flexco_layer_cfg& c, const void* dq, const float* dk_rows, const float* dv_rows,
-                             void* dqkv, int win_start, int n, hipStream_t s) {
+                             void* dqkv, int win_start, int n, hipStream_t s, const RowLoraT* lt_in) {
   const size_t shm = sizeof(float) * c.head_dim;
+  RowLoraT lt = {};
+  if (lt_in && lt_in->n > 0) {
+    if (!row_lora_ok(c.dtype, lt_in->r)) return fail(FLEXCO_EUNSUPPORTED, "rope_bwd_pack: row product not covered");
+    lt = *lt_in;
+    if (lt.r == 16)
+      hipLaunchKernelGGL((rope_bwd_pack_kernel<bf16_t, 16>), dim3(n), dim3(256), shm, s, (const bf16_t*)dq, dk_rows, dv_rows,
+                         (bf16_t*)dqkv, c.n_q_heads, c.n_kv_heads, c.head_dim, c.rope_theta, win_start, lt);
+    else
+      hipLaunchKernelGGL((rope_bwd_pack_kernel<bf16_t, 32>), dim3(n), dim3(256), shm, s, (const bf16_t*)dq, dk_rows, dv_rows,
+                         (bf16_t*)dqkv, c.n_q_heads, c.n_kv_heads, c.head_dim, c.rope_theta, win_start, lt);
+    return post_launch("rope_bwd_pack");
+  }
   DISPATCH_T(c.dtype, hipLaunchKernelGGL((rope_bwd_pack_kernel<T>), dim3(n), dim3(256), shm, s, (const T*)dq,
                                          dk_rows, dv_rows, (T*)dqkv, c.n_q_heads, c.n_kv_heads, c.head_dim,
-                                         c.rope_theta, win_start));
+                                         c.rope_theta, win_start, lt));
   return post_launch("rope_bwd_pack");
+}
+
+int32_t launch_lora_row_t(const void* dy, size_t lddy, int n, int width, const RowLoraT& lt, hipStream_t s) {
+  if (n == 0) return FLEXCO_OK;
+  if (!row_lora_ok(FLEXCO_BF16, lt.r) || width % 8 != 0 || lddy % 8 != 0 || !aligned16(dy) || !aligned16(lt.B[0]))
+    return fail(FLEXCO_EUNSUPPORTED, "lora_row_t: shape not covered");
+  if (lt.r == 16) hipLaunchKernelGGL(lora_row_t_kernel<16>, dim3(n), dim3(256), 0, s, (const bf16_t*)dy, lddy, width, lt);
+  else hipLaunchKernelGGL(lora_row_t_kernel<32>, dim3(n), dim3(256), 0, s, (const bf16_t*)dy, lddy, width, lt);
+  return post_launch("lora_row_t");
 }
 
 int32_t launch_ia3_scale_rows(void* buf, size_t ld, const int32_t* tok, int n_tok, const Ia3ScaleArgs& a, int dtype,
