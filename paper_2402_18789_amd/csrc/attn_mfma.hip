@@ -71,6 +71,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(FwdArgs a, const bf1
   const int tl = tile0 + ntl - 1;
   const int last_pos = a.tok_pos[a.tile_tok0[tl] + a.tile_ntok[tl] - 1];
   const int vis_pages = last_pos / PS + 1;
+  const int first_pos = a.tok_pos[a.tile_tok0[tile0]];   // the item's first column sees the fewest keys
   const int pb = split * a.split_pages;
   const int pe = min(pb + a.split_pages, vis_pages);
 
@@ -134,6 +135,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(FwdArgs a, const bf1
           }
         }
     }
+    const bool all_visible = (pp + 2) * PS - 1 <= first_pos && pp + 1 < pe;
 #pragma unroll
     for (int cs = 0; cs < NC; ++cs) {
       if (cs >= ntl) break;                    // wavefront-uniform
@@ -144,11 +146,16 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(FwdArgs a, const bf1
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int dc = 0; dc < 4; ++dc) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[x][dc], qf[cs][dc], acc, 0, 0, 0);
-        const bool page_ok = pp + x < pe;
+        if (all_visible) {      // wavefront-uniform: both pages lie before every column's own position
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int kpos = (pp + x) * PS + 4 * g + j;
-          s[x * 4 + j] = (page_ok && kpos <= pos_c[cs]) ? acc[j] * a.scale_log2 : -INFINITY;
+          for (int j = 0; j < 4; ++j) s[x * 4 + j] = acc[j] * a.scale_log2;
+        } else {
+          const bool page_ok = pp + x < pe;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const int kpos = (pp + x) * PS + 4 * g + j;
+            s[x * 4 + j] = (page_ok && kpos <= pos_c[cs]) ? acc[j] * a.scale_log2 : -INFINITY;
+          }
         }
       }
       // ---- online softmax per column -------------------------------------------------------
@@ -172,6 +179,8 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(FwdArgs a, const bf1
 #pragma unroll
       for (int j = 0; j < 8; ++j) pf[j] = (bf16_t)p[j];
       // ---- O^T = alpha O^T + V^T P^T --------------------------------------------------------
+      // (skipping the rescaling once alpha is 1 in every lane was tried: it moves the accumulators out of
+      // the MFMA's registers and back, 45 spilled registers)
 #pragma unroll
       for (int mt = 0; mt < 8; ++mt) {
         bf16x8 vfull;
