@@ -189,6 +189,16 @@ def test_workspace_bytes_and_cfg_validation():
             B.flexco_workspace_bytes(_cfg(**bad), 8, 8, 8, 8)
 
 
+def test_workspace_covers_every_smaller_batch():
+    """A workspace sized for T_max tokens must do for any batch of fewer tokens, including the small batches whose
+    projections ask for split-K scratch (bf16, at most 256 tokens): the size never shrinks as T_max grows."""
+    from workload import CONFIGS
+    from paper_2402_18789_amd.host import c_cfg
+    c = c_cfg(CONFIGS["c2_llama8b_layer"])
+    sizes = [B.flexco_workspace_bytes(c, T, max(1, T // 4), 0, 0) for T in (1, 16, 255, 256, 257, 300, 512, 1024)]
+    assert all(a <= b for a, b in zip(sizes, sizes[1:])), sizes
+
+
 def test_entry_points_validate_before_launch():
     """NULL / misaligned arguments fail on the host: no device is needed (or present) here."""
     c = _cfg()
