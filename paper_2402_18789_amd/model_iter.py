@@ -1,0 +1,175 @@
+"""One co-serving iteration through a whole model: the mixed token batch goes forward through every
+decoder layer (each with its own frozen weights, LoRA adapter, paged KV pool and finetune state), the
+finetune window's top rows go through the generative loss head, and the window's gradient comes back
+down through every layer (Alg. 2's Forward and Backward loops over the layers for one window, with the
+inference tokens of Sec. 6.2 in the same batch); Adam over every bypass matrix is timed on its own,
+since it runs once per finetune sequence, not once per iteration.
+
+    python -m paper_2402_18789_amd.model_iter [--layers 32] [--steps 5] [--warmup 2]
+
+Default: the 8B-shaped model (32 layers, vocabulary 128 256) with a token budget of 2048 = 512 decode
+tokens (log-normal contexts, median 1024) + 1024 prefill tokens (whole prompts of 128..1024 tokens) +
+the last 512-token window of a 2048-token finetune sequence; synthetic weights and caches.  Prints one
+JSON line.  A measurement: parity of the same calls chained over layers is what the GPU tests check."""
+import argparse
+import json
+import time
+
+import numpy as np
+import torch
+
+import paper_2402_18789_amd.binding as B
+from paper_2402_18789_amd import host as HH
+from workload import gen
+from workload.configs import CONFIGS
+
+VOCAB = 128256
+
+
+def build(cfg, batch, n_layers, vocab, seed):
+    """Device state of the whole model.  Layer 0 takes the seeded host weights; the others get weights of
+    the same law from the device generator (436 MB per layer: generating them on the host would take
+    longer than the measurement)."""
+    dt = HH.TORCH_DTYPE[cfg.dtype]
+    W, lora = gen.layer_weights(cfg, seed, 0), gen.lora_weights(cfg, seed, 0)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    ft_req = [r for r in batch.requests if r.kind == 2][0]
+    L = batch.seq_capacity[ft_req.seq_id]
+    layers, pools, fts = [], [], []
+    for n in range(n_layers):
+        ly = HH.DeviceLayer(cfg, W, lora)
+        if n > 0:
+            for name in ("wqkv", "wo", "wgu", "wd"):
+                t = ly.t[name]
+                t.copy_((0.02 * torch.randn(t.shape, generator=g, device="cuda", dtype=torch.float32)).to(dt))
+            for t in cfg.lora_targets:
+                ly.A[t].copy_((0.02 * torch.randn(ly.A[t].shape, generator=g, device="cuda")).to(dt))
+                ly.Bm[t].copy_((0.01 * torch.randn(ly.Bm[t].shape, generator=g, device="cuda")).to(dt))
+        pool = HH.DevicePool(cfg, batch.num_pages)
+        pool.fill_random(seed + n)
+        layers.append(ly)
+        pools.append(pool)
+        fts.append(HH.DeviceFtState(cfg, L))
+        print("  layer %d of %d resident (%.1f GB allocated)" % (n + 1, n_layers, torch.cuda.memory_allocated() / 1e9), flush=True)
+    gain = torch.ones(cfg.hidden, device="cuda", dtype=dt)
+    w_lm = (0.02 * torch.randn((vocab, cfg.hidden), generator=g, device="cuda", dtype=torch.float32)).to(dt)
+    return layers, pools, fts, gain, w_lm, ft_req, L
+
+
+def run(n_layers=32, steps=5, warmup=2, seed=0, vocab=VOCAB, cfg_name="c3_llama8b_full", batch=None):
+    cfg = CONFIGS[cfg_name]
+    batch = batch if batch is not None else gen.batch_c3(seed)
+    dt = HH.TORCH_DTYPE[cfg.dtype]
+    layers, pools, fts, gain, w_lm, ft_req, L = build(cfg, batch, n_layers, vocab, seed)
+    db = HH.DeviceBatch(cfg, batch.requests, batch.seq_pages, batch.num_pages)
+    hm = db.host_maps
+    T, n_ft = hm.T, hm.n_ft
+    ws = HH.Workspace(layers[0].c, T, hm.n_parts, n_ft, L)
+    head = B.LmHead(cfg.hidden, vocab, HH.DTYPE_CODE[cfg.dtype], cfg.rms_eps, gain.data_ptr(), w_lm.data_ptr())
+    hb = B.flexco_lm_loss_workspace_bytes(head, n_ft)
+    hws = torch.empty(hb, dtype=torch.uint8, device="cuda")
+    loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+    g = gen.rng(seed, "model_iter", "targets")
+    targets = torch.from_numpy(g.integers(0, vocab, n_ft).astype(np.int32)).to("cuda")
+    x0 = torch.from_numpy(gen.layer_input(cfg, seed, T)).to("cuda", dt)
+    xa, xb = torch.empty_like(x0), torch.empty_like(x0)
+    da, dbuf = torch.empty((n_ft, cfg.hidden), dtype=dt, device="cuda"), torch.empty((n_ft, cfg.hidden), dtype=dt, device="cuda")
+    ft_off = int(np.cumsum([0] + [r.n_new for r in batch.requests])[batch.requests.index(ft_req)])
+    pages = torch.from_numpy(np.asarray(batch.seq_pages[ft_req.seq_id], dtype=np.int32)).to("cuda")
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+
+    def reset():
+        # the window's accumulator rows start from zero (a sequence's last window: nothing above it), and
+        # so do the gradients; the caller's business between iterations, outside the timed bracket
+        for ft in fts:
+            ft.zero_accum()
+        for ly in layers:
+            ly.zero_grads()
+        loss.zero_()
+
+    def iteration(timed):
+        if timed:
+            ev[0].record()
+        src = x0
+        for n in range(n_layers):
+            dst = xa if n % 2 == 0 else xb
+            B.flexco_layer_forward(layers[n].c, layers[n].w, layers[n].lora, db.maps, src, dst, pools[n].c, fts[n].c, ws.ptr, ws.bytes)
+            src = dst
+        if timed:
+            ev[1].record()
+        top = src[ft_off:ft_off + n_ft]
+        B.flexco_lm_loss(head, top, targets, n_ft, 1.0 / L, loss, da, hws, hb)
+        if timed:
+            ev[2].record()
+        dcur, dnext = da, dbuf
+        for n in range(n_layers - 1, -1, -1):
+            B.flexco_lora_bwd(layers[n].c, layers[n].w, layers[n].lora, pools[n].c, pages, len(pages), fts[n].c,
+                              ft_req.start_pos, ft_req.n_new, dcur, dnext if n > 0 else None, ws.ptr, ws.bytes)
+            dcur, dnext = dnext, dcur
+        if timed:
+            ev[3].record()
+        return src
+
+    for _ in range(warmup):
+        reset()
+        iteration(False)
+    torch.cuda.synchronize()
+    wall, phases = [], []
+    for _ in range(steps):
+        reset()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        out = iteration(True)
+        torch.cuda.synchronize()
+        wall.append((time.perf_counter() - t0) * 1e3)
+        phases.append([ev[i].elapsed_time(ev[i + 1]) for i in range(3)])
+    ph = np.median(np.asarray(phases), axis=0)
+    ms = float(np.median(wall))
+    finite = bool(torch.isfinite(out.float()).all().item()) and bool(torch.isfinite(loss).item())
+    grad_norm = float(sum(layers[n].dB[t].double().pow(2).sum().item() for n in range(n_layers) for t in cfg.lora_targets) ** 0.5)
+
+    # Adam over every bypass matrix (fp32 master copies of the bf16 parameters), once per sequence
+    state = []
+    for ly in layers:
+        for t in cfg.lora_targets:
+            for P, G in ((ly.A[t], ly.dA[t]), (ly.Bm[t], ly.dB[t])):
+                state.append((P, P.float().clone(), G, torch.zeros_like(G), torch.zeros_like(G)))
+    adam_ms = []
+    for k in range(3):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for P, M, G, m, v in state:
+            B.flexco_adam_step(P, M, G, m, v, P.numel(), HH.DTYPE_CODE[cfg.dtype], 1e-4, 0.9, 0.999, 1e-8, k + 1)
+        torch.cuda.synchronize()
+        adam_ms.append((time.perf_counter() - t0) * 1e3)
+    positions = int(sum(r.start_pos + r.n_new for r in batch.requests))
+    p_layer = (cfg.q_dim + 2 * cfg.kv_dim) * cfg.hidden + cfg.q_dim * cfg.hidden + 3 * cfg.hidden * cfg.ffn
+    return {
+        "what": "one co-serving iteration through the whole model: forward of the mixed batch through every layer, "
+                "loss head on the finetune window, the window's backward through every layer",
+        "config": {"workload": cfg_name, "layers": n_layers, "tokens": T, "finetune_tokens": n_ft, "requests": hm.n_req,
+                   "cached_positions": positions, "vocab": vocab},
+        "ms_per_iteration": ms, "tokens_per_s": T / ms * 1e3, "finetune_tokens_per_s": n_ft / ms * 1e3,
+        "forward_ms": float(ph[0]), "loss_head_ms": float(ph[1]), "backward_ms": float(ph[2]),
+        "ms_per_layer": (float(ph[0]) + float(ph[2])) / n_layers,
+        "adam_ms_once_per_sequence": float(np.median(adam_ms)), "adam_launches": len(state),
+        "resident_gb": {"weights": n_layers * p_layer * 2 / 1e9, "kv_pools": n_layers * batch.num_pages * cfg.page_size * 2 * cfg.kv_dim * 2 / 1e9,
+                        "allocated": torch.cuda.memory_allocated() / 1e9},
+        "loss": float(loss.item()), "lora_grad_norm_dB": grad_norm, "finite": finite,
+        "dtype": cfg.dtype, "data": "synthetic",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--layers", type=int, default=32)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--seed", type=int, default=0)
+    a = ap.parse_args()
+    print(json.dumps(run(a.layers, a.steps, a.warmup, a.seed)))
+
+
+if __name__ == "__main__":
+    main()

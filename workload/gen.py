@@ -211,6 +211,21 @@ def batch_c2(seed=0) -> Batch:
                        finetune=[(1792, 256, 2048)])
 
 
+def batch_c3(seed=0) -> Batch:
+    """8B-shaped whole-model case, token budget 2048: 512 decode tokens whose contexts follow a
+    log-normal law (median 1024, sigma 0.8, clipped to 16..8192), 1024 prefill tokens made of whole
+    prompts with lengths uniform in 128..1024 (the last one cut to the budget) and the last 512-token
+    window of a 2048-token finetune sequence."""
+    g = rng(seed, "c3", "lengths")
+    ctx = np.clip(np.round(np.exp(g.normal(np.log(1024.0), 0.8, size=512))), 16, 8192).astype(int)
+    prefill, left = [], 1024
+    while left > 0:
+        n = int(min(left, g.integers(128, 1025)))
+        prefill.append((0, n, n))
+        left -= n
+    return mixed_batch(16, seed, decode_ctx=ctx, prefill=prefill, finetune=[(1536, 512, 2048)])
+
+
 def batch_scaled(seed, n_decode, ctx_lo, ctx_hi, prefill, finetune, page_size=16) -> Batch:
     """Reduced-size batch of the same structure as batch_c2 (parity tests)."""
     ctx = rng(seed, "scaled", "decode_ctx", n_decode, ctx_lo, ctx_hi).integers(ctx_lo, ctx_hi + 1, size=n_decode)
