@@ -5,12 +5,14 @@ down through every layer (Alg. 2's Forward and Backward loops over the layers fo
 inference tokens of Sec. 6.2 in the same batch); Adam over every bypass matrix is timed on its own,
 since it runs once per finetune sequence, not once per iteration.
 
-    python -m paper_2402_18789_amd.model_iter [--layers 32] [--steps 5] [--warmup 2]
+    python -m paper_2402_18789_amd.model_iter [--config c3|c4|c5] [--layers N] [--steps 5] [--warmup 2]
 
 Default: the 8B-shaped model (32 layers, vocabulary 128 256) with a token budget of 2048 = 512 decode
 tokens (log-normal contexts, median 1024) + 1024 prefill tokens (whole prompts of 128..1024 tokens) +
 the last 512-token window of a 2048-token finetune sequence; synthetic weights and caches.  Prints one
-JSON line.  A measurement: parity of the same calls chained over layers is what the GPU tests check."""
+JSON line.  c4: the 14B shape (48 layers, LoRA on all seven projections, window 1024 of 4096, half the
+budget inference); c5: the 32B shape (64 layers, rank 32, T = 4096), whose weights, 64 KV pools and
+finetune state fill most of the GPU's memory.  A measurement: parity of the same calls chained over layers is what the GPU tests check."""
 import argparse
 import json
 import time
@@ -24,6 +26,11 @@ from workload import gen
 from workload.configs import CONFIGS
 
 VOCAB = 128256
+MODELS = {   # configuration, batch recipe, vocabulary
+    "c3": ("c3_llama8b_full", gen.batch_c3, 128256),
+    "c4": ("c4_qwen14b_full", gen.batch_c4, 152064),
+    "c5": ("c5_qwen32b_full", gen.batch_c5, 152064),
+}
 
 
 def build(cfg, batch, n_layers, vocab, seed):
@@ -57,9 +64,12 @@ def build(cfg, batch, n_layers, vocab, seed):
     return layers, pools, fts, gain, w_lm, ft_req, L
 
 
-def run(n_layers=32, steps=5, warmup=2, seed=0, vocab=VOCAB, cfg_name="c3_llama8b_full", batch=None):
+def run(n_layers=None, steps=5, warmup=2, seed=0, vocab=None, model="c3"):
+    cfg_name, make_batch, model_vocab = MODELS[model]
     cfg = CONFIGS[cfg_name]
-    batch = batch if batch is not None else gen.batch_c3(seed)
+    n_layers = n_layers or cfg.n_layers
+    vocab = vocab or model_vocab
+    batch = make_batch(seed)
     dt = HH.TORCH_DTYPE[cfg.dtype]
     layers, pools, fts, gain, w_lm, ft_req, L = build(cfg, batch, n_layers, vocab, seed)
     db = HH.DeviceBatch(cfg, batch.requests, batch.seq_pages, batch.num_pages)
@@ -163,12 +173,13 @@ def run(n_layers=32, steps=5, warmup=2, seed=0, vocab=VOCAB, cfg_name="c3_llama8
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--layers", type=int, default=32)
+    ap.add_argument("--config", choices=sorted(MODELS), default="c3")
+    ap.add_argument("--layers", type=int, default=0, help="0 = the model's own number of layers")
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--seed", type=int, default=0)
     a = ap.parse_args()
-    print(json.dumps(run(a.layers, a.steps, a.warmup, a.seed)))
+    print(json.dumps(run(a.layers, a.steps, a.warmup, a.seed, model=a.config)))
 
 
 if __name__ == "__main__":

@@ -63,6 +63,12 @@ def test_loss_head_llama_vocabulary():
     run_loss("bf16", 48, 4096, 128256, seed=2, ignore=(47,))
 
 
+def test_loss_head_qwen_vocabulary():
+    """The 14B / 32B shapes' head: hidden 5120, vocabulary 152064, a window of 40 rows."""
+    print("loss head bf16 at hidden 5120, vocabulary 152064", flush=True)
+    run_loss("bf16", 40, 5120, 152064, seed=3, ignore=(0, 39))
+
+
 def test_loss_head_all_rows_ignored_and_errors():
     cfg = C1
     H, V, n = 64, 40, 3

@@ -226,6 +226,38 @@ def batch_c3(seed=0) -> Batch:
     return mixed_batch(16, seed, decode_ctx=ctx, prefill=prefill, finetune=[(1536, 512, 2048)])
 
 
+def _lognormal_lengths(g, n, median, sigma, lo, hi):
+    return np.clip(np.round(np.exp(g.normal(np.log(float(median)), sigma, size=n))), lo, hi).astype(int)
+
+
+def _whole_prompts(g, budget, lo=128, hi=1024):
+    prefill, left = [], budget
+    while left > 0:
+        n = int(min(left, g.integers(lo, hi + 1)))
+        prefill.append((0, n, n))
+        left -= n
+    return prefill
+
+
+def batch_c4(seed=0) -> Batch:
+    """14B-shaped whole-model case, token budget 2048 at an inference share of 50 %: 512 decode tokens
+    (contexts log-normal, median 1024, sigma 0.8, clipped to 16..8192), 512 prefill tokens as whole prompts,
+    and the last 1024-token window of a 4096-token finetune sequence."""
+    g = rng(seed, "c4", "lengths")
+    ctx = _lognormal_lengths(g, 512, 1024, 0.8, 16, 8192)
+    return mixed_batch(16, seed, decode_ctx=ctx, prefill=_whole_prompts(g, 512), finetune=[(3072, 1024, 4096)])
+
+
+def batch_c5(seed=0) -> Batch:
+    """32B-shaped whole-model case, token budget 4096: 1024 decode tokens (contexts log-normal, median 320,
+    sigma 1.0, clipped to 16..16384: the law's scale is what lets 64 layers of cache, the weights and the
+    finetune state share one GPU's memory), 2048 prefill tokens as whole prompts, and the last 1024-token
+    window of a 4096-token finetune sequence."""
+    g = rng(seed, "c5", "lengths")
+    ctx = _lognormal_lengths(g, 1024, 320, 1.0, 16, 16384)
+    return mixed_batch(16, seed, decode_ctx=ctx, prefill=_whole_prompts(g, 2048), finetune=[(3072, 1024, 4096)])
+
+
 def batch_scaled(seed, n_decode, ctx_lo, ctx_hi, prefill, finetune, page_size=16) -> Batch:
     """Reduced-size batch of the same structure as batch_c2 (parity tests)."""
     ctx = rng(seed, "scaled", "decode_ctx", n_decode, ctx_lo, ctx_hi).integers(ctx_lo, ctx_hi + 1, size=n_decode)
