@@ -224,3 +224,15 @@ def test_entry_points_validate_before_launch():
     with pytest.raises(B.FlexcoError) as e:
         B.flexco_lora_fwd(16, 32, 8, 16, 16, 4, 1.0, B.FLEXCO_F32, [48], [64], [0, 8], [1], 80, stream=0)
     assert e.value.code == B.FLEXCO_EINVAL
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py --gpus N with N > 1 exits with a message and prints no result line."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr
+    assert r.stdout.strip() == ""
