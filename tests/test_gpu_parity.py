@@ -531,14 +531,30 @@ def test_layer_c2_full_size_sampled():
     the GPU runs the whole 1024-token batch; the oracle recomputes a sample of requests
     (16 decode, one prefill chunk, the finetune window) one by one from the same inputs."""
     say("layer c2 full size, sampled")
-    cfg, seed = C2, 0
+    full_size_sampled(C2, gen.batch_c2(0), 16)
+
+
+@pytest.mark.parametrize("name,make_batch,n_decode", [
+    ("c3_llama8b_full", gen.batch_c3, 16),
+    ("c4_qwen14b_full", gen.batch_c4, 8),
+    ("c5_qwen32b_full", gen.batch_c5, 8),
+])
+def test_layer_whole_model_batches_full_size_sampled(name, make_batch, n_decode):
+    """One layer of the 8B / 14B / 32B-shaped models on the whole-model configurations' full batches
+    (T = 2048 / 2048 / 4096, windows of 512 / 1024 / 1024 rows on prefixes of 1536 / 3072 / 3072), sampled
+    like the benchmark configuration's case."""
+    say("layer %s full size, sampled" % name)
+    full_size_sampled(CONFIGS[name], make_batch(0), n_decode)
+
+
+def full_size_sampled(cfg, batch, n_decode):
+    seed = 0
     tol = TOL["bf16"]
-    batch = gen.batch_c2(seed)
     W, lora = gen.layer_weights(cfg, seed, 0), gen.lora_weights(cfg, seed, 0)
     dev = HH.DeviceLayer(cfg, W, lora)
     pool = HH.DevicePool(cfg, batch.num_pages)
     pool.fill_random(seed)
-    sample = gen.sample_requests(batch, 16)
+    sample = gen.sample_requests(batch, n_decode)
     o_pool = OL.KVPool(batch.num_pages, cfg.page_size, cfg.kv_dim, dtype=np.float32)
     for r in sample:
         if r.start_pos:
