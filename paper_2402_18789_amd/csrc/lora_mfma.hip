@@ -260,20 +260,42 @@ __global__ __launch_bounds__(256) void lora_outer_mfma_kernel(LoraOuterArgs a) {
   const int t_row = 8 * g + (c >> 2);
   const int t_k = (c >> 2) & 3;
 
-  for (int mb = 0; mb < n; mb += 256) {
-    __syncthreads();   // the previous chunk's reads of ut are done
-    for (int idx = tid; idx < 256 * RT * 16; idx += 256) {
-      const int m = idx / (RT * 16), j = idx % (RT * 16);
-      ut[j * UP + m] = (bf16_t)((mb + m < n && j < r) ? U[(size_t)(mb + m) * r + j] : 0.f);
-    }
-    const int mw = mb + 64 * wave;
+  // a wavefront's two tiles of the chunk that starts at row mb0 (its own LDS buffers: nobody else reads them)
+  auto load_tiles = [&](int mb0) {
+    const int mw0 = mb0 + 64 * wave;
 #pragma unroll
     for (int st = 0; st < 2; ++st)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int row = min(mw + 32 * st + 8 * q + d_row, n - 1);   // rows past n meet zero U
+        const int row = min(mw0 + 32 * st + 8 * q + d_row, n - 1);   // rows past n meet zero U
         __builtin_amdgcn_global_load_lds(FLEXCO_GP(X + (size_t)row * ldx + d_col), FLEXCO_LP(&xt[wave][st][q * 512]), 16, 0, 0);
       }
+  };
+  load_tiles(0);
+  for (int mb = 0; mb < n; mb += 256) {
+    __syncthreads();   // the previous chunk's reads of ut are done
+    if (r == RT * 16) {
+      // full rank tiles: the chunk of U is one contiguous run of floats; 4 RT 16-byte loads per thread,
+      // all in flight before the first is converted
+      f32x4 uv[4 * RT];
+#pragma unroll
+      for (int k = 0; k < 4 * RT; ++k) {
+        const int idx4 = tid + 256 * k, m = idx4 / (4 * RT);
+        uv[k] = mb + m < n ? *reinterpret_cast<const f32x4*>(U + ((size_t)mb * r + (size_t)idx4 * 4)) : f32x4{0.f, 0.f, 0.f, 0.f};
+      }
+#pragma unroll
+      for (int k = 0; k < 4 * RT; ++k) {
+        const int idx4 = tid + 256 * k, m = idx4 / (4 * RT), j = 4 * (idx4 % (4 * RT));
+#pragma unroll
+        for (int q = 0; q < 4; ++q) ut[(j + q) * UP + m] = (bf16_t)uv[k][q];
+      }
+    } else {
+      for (int idx = tid; idx < 256 * RT * 16; idx += 256) {
+        const int m = idx / (RT * 16), j = idx % (RT * 16);
+        ut[j * UP + m] = (bf16_t)((mb + m < n && j < r) ? U[(size_t)(mb + m) * r + j] : 0.f);
+      }
+    }
+    const int mw = mb + 64 * wave;
     __syncthreads();   // ut is complete; the barrier's wait also covers this wavefront's tile loads
     if (mw < n) {
 #pragma unroll
@@ -290,6 +312,12 @@ __global__ __launch_bounds__(256) void lora_outer_mfma_kernel(LoraOuterArgs a) {
           for (int rt = 0; rt < RT; ++rt) acc[rt][cg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[rt], xf, acc[rt][cg], 0, 0, 0);
         }
       }
+    }
+    // the next chunk's tiles travel while the other wavefronts finish and U is staged: this wavefront's reads
+    // of its buffers have returned (the products above consumed them)
+    if (mb + 256 < n) {
+      asm volatile("" ::: "memory");
+      load_tiles(mb + 256);
     }
   }
   // lane (column c of group cg, g) holds ranks 16 rt + 4 g .. + 4
@@ -388,7 +416,7 @@ int32_t launch_lora_outer_batch(const LoraOuterArgs& a, hipStream_t s) {
   bool tiles_ok = a.r <= 64;     // whole 16-byte column chunks, rows and base pointers 16-byte aligned
   for (int e = 0; e < a.count; ++e) {
     mx = a.n_long[e] > mx ? a.n_long[e] : mx;
-    tiles_ok = tiles_ok && a.n_long[e] % 8 == 0 && a.n_long[e] >= 8 && a.ldx[e] % 8 == 0 && aligned16(a.X[e]);
+    tiles_ok = tiles_ok && a.n_long[e] % 8 == 0 && a.n_long[e] >= 8 && a.ldx[e] % 8 == 0 && aligned16(a.X[e]) && aligned16(a.U[e]);
   }
   const dim3 grid((mx + 63) / 64, a.count);
   if (tiles_ok) {
