@@ -317,6 +317,17 @@ def test_layer_small_bf16():
     run_layer_case(SMALL_BF16, b, ft_window=160, prefill_chunk=70, bwd_windows=[60, 200], seed=7)
 
 
+@pytest.mark.parametrize("rank", [8, 24, 48, 64])
+def test_layer_small_bf16_other_ranks(rank):
+    """LoRA ranks other than the configurations' 16 and 32, on all seven projections: 48 and 64 take the
+    matrix-core LoRA kernels with three and four rank tiles, 8 and 24 the type-generic ones.  Backward windows of
+    300 rows: the gradient launch walks more than one 256-row chunk."""
+    say("layer small bf16, LoRA rank %d" % rank)
+    cfg = SMALL_BF16_G5.with_(name="small_bf16_r%d" % rank, lora_rank=rank)
+    b = gen.batch_scaled(11, 6, 3, 300, [(0, 90, 90)], [(0, 300, 600)])
+    run_layer_case(cfg, b, ft_window=300, prefill_chunk=90, bwd_windows=[300, 300], seed=11)
+
+
 def test_layer_small_bf16_pool_astride_4gib():
     """A paged pool larger than 2^31 elements (4 GiB) per K and V: the batch's pages sit on both sides of
     that offset, so every kernel that addresses the pool (append, attention forward, its backward) needs
