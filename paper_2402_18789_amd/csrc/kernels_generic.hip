@@ -269,7 +269,9 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* __restrict__ 
 //   written to the K pages, v is written to the (position-minor) V pages, and rows of
 //   the finetune window also store the rotated q in the sequence's Q cache.
 // --------------------------------------------------------------------------------------
-template <typename T>
+// VEC: a thread rotates Vec<T>::N neighbouring pairs of one head with 16-byte accesses (head_dim / 2 a
+// multiple of the vector width, every pointer 16-byte aligned); same arithmetic, same results.
+template <typename T, bool VEC>
 __global__ __launch_bounds__(256) void rope_append_kernel(T* __restrict__ qkv, const int32_t* __restrict__ tok_pos,
                                                           const int32_t* __restrict__ slot, T* __restrict__ kp,
                                                           T* __restrict__ vp, int nq, int nkv, int d, int ps,
@@ -294,31 +296,71 @@ __global__ __launch_bounds__(256) void rope_append_kernel(T* __restrict__ qkv, c
   const int pip = sl % ps;
   const bool is_ft = (t >= ft_tok0 && t < ft_tok0 + n_ft);
   // rotate q and k heads
-  for (int idx = threadIdx.x; idx < (nq + nkv) * half; idx += 256) {
-    const int head = idx / half, i = idx % half;
-    T* hp = row + head * d;
-    const float lo = ld(hp + i), hi = ld(hp + half + i);
-    const float c = cs[i], sn = cs[half + i];
-    const float rlo = lo * c - hi * sn, rhi = hi * c + lo * sn;
-    if (head < nq) {
-      st(hp + i, rlo);
-      st(hp + half + i, rhi);
-      if (is_ft) {
-        T* qc = q_cache + (size_t)(ft_pos0 + (t - ft_tok0)) * nq * d + head * d;
-        st(qc + i, rlo);
-        st(qc + half + i, rhi);
-      }
-    } else {
-      const int kh = head - nq;
-      T* dst = kp + ((page * nkv + kh) * ps + pip) * (size_t)d;
-      st(dst + i, rlo);
-      st(dst + half + i, rhi);
-    }
-  }
   const T* vrow = row + (nq + nkv) * d;
-  for (int idx = threadIdx.x; idx < nkv * d; idx += 256) {
-    const int kh = idx / d, i = idx % d;
-    vp[((page * nkv + kh) * (size_t)d + i) * ps + pip] = vrow[idx];
+  if constexpr (VEC) {
+    constexpr int N = Vec<T>::N;
+    const int hv = half / N;
+    for (int idx = threadIdx.x; idx < (nq + nkv) * hv; idx += 256) {
+      const int head = idx / hv, i = (idx % hv) * N;
+      T* hp = row + head * d;
+      float lo[N], hi[N], rlo[N], rhi[N];
+      Vec<T>::load(hp + i, lo);
+      Vec<T>::load(hp + half + i, hi);
+#pragma unroll
+      for (int j = 0; j < N; ++j) {
+        const float c = cs[i + j], sn = cs[half + i + j];
+        rlo[j] = lo[j] * c - hi[j] * sn;
+        rhi[j] = hi[j] * c + lo[j] * sn;
+      }
+      if (head < nq) {
+        Vec<T>::store(hp + i, rlo);
+        Vec<T>::store(hp + half + i, rhi);
+        if (is_ft) {
+          T* qc = q_cache + (size_t)(ft_pos0 + (t - ft_tok0)) * nq * d + head * d;
+          Vec<T>::store(qc + i, rlo);
+          Vec<T>::store(qc + half + i, rhi);
+        }
+      } else {
+        const int kh = head - nq;
+        T* dst = kp + ((page * nkv + kh) * ps + pip) * (size_t)d;
+        Vec<T>::store(dst + i, rlo);
+        Vec<T>::store(dst + half + i, rhi);
+      }
+    }
+    // v: one 16-byte read, N element stores (a channel's positions are the contiguous index of a V page)
+    for (int idx = threadIdx.x * N; idx < nkv * d; idx += 256 * N) {
+      const int kh = idx / d, i = idx % d;
+      float v[N];
+      Vec<T>::load(vrow + idx, v);
+#pragma unroll
+      for (int j = 0; j < N; ++j) vp[((page * nkv + kh) * (size_t)d + i + j) * ps + pip] = (T)v[j];
+    }
+  } else {
+    for (int idx = threadIdx.x; idx < (nq + nkv) * half; idx += 256) {
+      const int head = idx / half, i = idx % half;
+      T* hp = row + head * d;
+      const float lo = ld(hp + i), hi = ld(hp + half + i);
+      const float c = cs[i], sn = cs[half + i];
+      const float rlo = lo * c - hi * sn, rhi = hi * c + lo * sn;
+      if (head < nq) {
+        st(hp + i, rlo);
+        st(hp + half + i, rhi);
+        if (is_ft) {
+          T* qc = q_cache + (size_t)(ft_pos0 + (t - ft_tok0)) * nq * d + head * d;
+          st(qc + i, rlo);
+          st(qc + half + i, rhi);
+        }
+      } else {
+        const int kh = head - nq;
+        T* dst = kp + ((page * nkv + kh) * ps + pip) * (size_t)d;
+        st(dst + i, rlo);
+        st(dst + half + i, rhi);
+      }
+    }
+    for (int idx = threadIdx.x; idx < nkv * d; idx += 256) {
+      const int kh = idx / d, i = idx % d;
+      vp[((page * nkv + kh) * (size_t)d + i) * ps + pip] = vrow[idx];
+    }
   }
 }
 
@@ -326,7 +368,19 @@ __global__ __launch_bounds__(256) void rope_append_kernel(T* __restrict__ qkv, c
 // dq rows are in the storage type, dk/dv rows are the (float) accumulator rows of the window.
 // R > 0 (bf16): the packed row is also multiplied by the LoRA B matrices of q, k, v (see RowLoraT; entry 0 = q,
 // 1 = k, 2 = v, B = NULL where the projection carries no LoRA)
-template <typename T, int R = 0>
+// N consecutive floats with 16-byte loads
+template <int N>
+__device__ inline void load_f32_run(const float* p, float (&v)[N]) {
+#pragma unroll
+  for (int q4 = 0; q4 < N / 4; ++q4) {
+    const f32x4 t = *reinterpret_cast<const f32x4*>(p + 4 * q4);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) v[4 * q4 + q] = t[q];
+  }
+}
+
+// VEC as in rope_append_kernel
+template <typename T, int R = 0, bool VEC = false>
 __global__ __launch_bounds__(256) void rope_bwd_pack_kernel(const T* __restrict__ dq, const float* __restrict__ dk,
                                                             const float* __restrict__ dv, T* __restrict__ dqkv,
                                                             int nq, int nkv, int d, float theta, int win_start,
@@ -349,6 +403,62 @@ __global__ __launch_bounds__(256) void rope_bwd_pack_kernel(const T* __restrict_
   }
   __syncthreads();
   T* out = dqkv + (size_t)r * (nq + 2 * nkv) * d;
+  if constexpr (VEC) {
+    constexpr int N = Vec<T>::N;
+    const int hv = half / N;
+    for (int idx = threadIdx.x; idx < (nq + nkv) * hv; idx += 256) {
+      const int head = idx / hv, i = (idx % hv) * N;
+      float lo[N], hi[N], rlo[N], rhi[N];
+      if (head < nq) {
+        const T* p = dq + (size_t)r * nq * d + head * d;
+        Vec<T>::load(p + i, lo);
+        Vec<T>::load(p + half + i, hi);
+      } else {
+        const float* p = dk + (size_t)r * nkv * d + (head - nq) * d;
+        load_f32_run<N>(p + i, lo);
+        load_f32_run<N>(p + half + i, hi);
+      }
+#pragma unroll
+      for (int j = 0; j < N; ++j) {
+        const float c = cs[i + j], sn = cs[half + i + j];
+        // transpose of the rotation: turn by the negative angle
+        rlo[j] = lo[j] * c + hi[j] * sn;
+        rhi[j] = hi[j] * c - lo[j] * sn;
+      }
+      Vec<T>::store(out + head * d + i, rlo);
+      Vec<T>::store(out + head * d + half + i, rhi);
+      if constexpr (R > 0) {   // (the values as they were just stored)
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+          rlo[j] = (float)(T)rlo[j];
+          rhi[j] = (float)(T)rhi[j];
+        }
+        if (head < nq) {
+          if (lt.B[0]) {
+            const bf16_t* b = (const bf16_t*)lt.B[0] + (size_t)(head * d + i) * R;
+            lora_acc_cols<R, N>(acc_q, rlo, b);
+            lora_acc_cols<R, N>(acc_q, rhi, b + (size_t)half * R);
+          }
+        } else if (lt.B[1]) {
+          const bf16_t* b = (const bf16_t*)lt.B[1] + (size_t)((head - nq) * d + i) * R;
+          lora_acc_cols<R, N>(acc_k, rlo, b);
+          lora_acc_cols<R, N>(acc_k, rhi, b + (size_t)half * R);
+        }
+      }
+    }
+    for (int idx = threadIdx.x * N; idx < nkv * d; idx += 256 * N) {
+      float v[N];
+      load_f32_run<N>(dv + (size_t)r * nkv * d + idx, v);
+      Vec<T>::store(out + (nq + nkv) * d + idx, v);
+      if constexpr (R > 0) {
+        if (lt.B[2]) {
+#pragma unroll
+          for (int j = 0; j < N; ++j) v[j] = (float)(T)v[j];
+          lora_acc_cols<R, N>(acc_v, v, (const bf16_t*)lt.B[2] + (size_t)idx * R);
+        }
+      }
+    }
+  } else {
   for (int idx = threadIdx.x; idx < (nq + nkv) * half; idx += 256) {
     const int head = idx / half, i = idx % half;
     float lo, hi;
@@ -385,6 +495,7 @@ __global__ __launch_bounds__(256) void rope_bwd_pack_kernel(const T* __restrict_
     if constexpr (R > 0) {
       if (lt.B[2]) lora_acc_row<R>(acc_v, (float)(T)v, (const bf16_t*)lt.B[2] + (size_t)idx * R);
     }
+  }
   }
   if constexpr (R > 0) {
     if (lt.B[0]) lora_row_finish<R>(acc_q, lt_lds, lt.t[0], (bf16_t*)lt.ext[0], r, lt.scale);
@@ -797,31 +908,34 @@ int32_t launch_rope_append(const flexco_layer_cfg& c, void* qkv, const int32_t* 
                            hipStream_t s) {
   if (T_ == 0) return FLEXCO_OK;
   const size_t shm = sizeof(float) * c.head_dim;
-  DISPATCH_T(c.dtype, hipLaunchKernelGGL((rope_append_kernel<T>), dim3(T_), dim3(256), shm, s, (T*)qkv, tok_pos,
-                                         slot, (T*)pool.k_pages, (T*)pool.v_pages, c.n_q_heads, c.n_kv_heads,
-                                         c.head_dim, c.page_size, c.rope_theta, ft_tok0, n_ft, ft_pos0,
-                                         (T*)q_cache));
+  const bool vec = c.head_dim % 2 == 0 && vec_ok(c.dtype, c.head_dim / 2, {qkv, pool.k_pages, pool.v_pages, q_cache});
+  DISPATCH_TV(c.dtype, vec, hipLaunchKernelGGL((rope_append_kernel<T, VEC>), dim3(T_), dim3(256), shm, s, (T*)qkv, tok_pos,
+                                               slot, (T*)pool.k_pages, (T*)pool.v_pages, c.n_q_heads, c.n_kv_heads,
+                                               c.head_dim, c.page_size, c.rope_theta, ft_tok0, n_ft, ft_pos0,
+                                               (T*)q_cache));
   return post_launch("rope_append");
 }
 
 int32_t launch_rope_bwd_pack(const flexco_layer_cfg& c, const void* dq, const float* dk_rows, const float* dv_rows,
                              void* dqkv, int win_start, int n, hipStream_t s, const RowLoraT* lt_in) {
   const size_t shm = sizeof(float) * c.head_dim;
+  // 16-byte accesses: also the float rows of dk / dv (their row pitch nkv d floats is a multiple of 16 bytes then)
+  const bool vec = c.head_dim % 2 == 0 && vec_ok(c.dtype, c.head_dim / 2, {dq, dk_rows, dv_rows, dqkv});
   RowLoraT lt = {};
   if (lt_in && lt_in->n > 0) {
     if (!row_lora_ok(c.dtype, lt_in->r)) return fail(FLEXCO_EUNSUPPORTED, "rope_bwd_pack: row product not covered");
     lt = *lt_in;
-    if (lt.r == 16)
-      hipLaunchKernelGGL((rope_bwd_pack_kernel<bf16_t, 16>), dim3(n), dim3(256), shm, s, (const bf16_t*)dq, dk_rows, dv_rows,
-                         (bf16_t*)dqkv, c.n_q_heads, c.n_kv_heads, c.head_dim, c.rope_theta, win_start, lt);
-    else
-      hipLaunchKernelGGL((rope_bwd_pack_kernel<bf16_t, 32>), dim3(n), dim3(256), shm, s, (const bf16_t*)dq, dk_rows, dv_rows,
-                         (bf16_t*)dqkv, c.n_q_heads, c.n_kv_heads, c.head_dim, c.rope_theta, win_start, lt);
+#define FLEXCO_ROPE_BWD_LT(R_, V_)                                                                                      \
+  hipLaunchKernelGGL((rope_bwd_pack_kernel<bf16_t, R_, V_>), dim3(n), dim3(256), shm, s, (const bf16_t*)dq, dk_rows, dv_rows, \
+                     (bf16_t*)dqkv, c.n_q_heads, c.n_kv_heads, c.head_dim, c.rope_theta, win_start, lt)
+    if (lt.r == 16) { if (vec) FLEXCO_ROPE_BWD_LT(16, true); else FLEXCO_ROPE_BWD_LT(16, false); }
+    else { if (vec) FLEXCO_ROPE_BWD_LT(32, true); else FLEXCO_ROPE_BWD_LT(32, false); }
+#undef FLEXCO_ROPE_BWD_LT
     return post_launch("rope_bwd_pack");
   }
-  DISPATCH_T(c.dtype, hipLaunchKernelGGL((rope_bwd_pack_kernel<T>), dim3(n), dim3(256), shm, s, (const T*)dq,
-                                         dk_rows, dv_rows, (T*)dqkv, c.n_q_heads, c.n_kv_heads, c.head_dim,
-                                         c.rope_theta, win_start, lt));
+  DISPATCH_TV(c.dtype, vec, hipLaunchKernelGGL((rope_bwd_pack_kernel<T, 0, VEC>), dim3(n), dim3(256), shm, s, (const T*)dq,
+                                               dk_rows, dv_rows, (T*)dqkv, c.n_q_heads, c.n_kv_heads, c.head_dim,
+                                               c.rope_theta, win_start, lt));
   return post_launch("rope_bwd_pack");
 }
 
