@@ -394,6 +394,10 @@ __global__ __launch_bounds__(256) void rope_bwd_pack_kernel(const T* __restrict_
   const int r = blockIdx.x;
   const int pos = win_start + r;
   const int half = d >> 1;
+  // a grid of two blocks per row (short windows: the row's chain of loads is the whole run time) gives the
+  // query heads to block 0 and the key heads and v to block 1
+  const int part = gridDim.y == 2 ? (int)blockIdx.y : -1;
+  const int h_lo = part == 1 ? nq : 0, h_hi = part == 0 ? nq : nq + nkv;
   for (int i = threadIdx.x; i < half; i += 256) {
     const double inv = pow((double)theta, -2.0 * (double)i / (double)d);
     double sn, c;
@@ -406,7 +410,7 @@ __global__ __launch_bounds__(256) void rope_bwd_pack_kernel(const T* __restrict_
   if constexpr (VEC) {
     constexpr int N = Vec<T>::N;
     const int hv = half / N;
-    for (int idx = threadIdx.x; idx < (nq + nkv) * hv; idx += 256) {
+    for (int idx = h_lo * hv + threadIdx.x; idx < h_hi * hv; idx += 256) {
       const int head = idx / hv, i = (idx % hv) * N;
       float lo[N], hi[N], rlo[N], rhi[N];
       if (head < nq) {
@@ -446,7 +450,7 @@ __global__ __launch_bounds__(256) void rope_bwd_pack_kernel(const T* __restrict_
         }
       }
     }
-    for (int idx = threadIdx.x * N; idx < nkv * d; idx += 256 * N) {
+    for (int idx = threadIdx.x * N; part != 0 && idx < nkv * d; idx += 256 * N) {
       float v[N];
       load_f32_run<N>(dv + (size_t)r * nkv * d + idx, v);
       Vec<T>::store(out + (nq + nkv) * d + idx, v);
@@ -459,7 +463,7 @@ __global__ __launch_bounds__(256) void rope_bwd_pack_kernel(const T* __restrict_
       }
     }
   } else {
-  for (int idx = threadIdx.x; idx < (nq + nkv) * half; idx += 256) {
+  for (int idx = h_lo * half + threadIdx.x; idx < h_hi * half; idx += 256) {
     const int head = idx / half, i = idx % half;
     float lo, hi;
     if (head < nq) {
@@ -489,7 +493,7 @@ __global__ __launch_bounds__(256) void rope_bwd_pack_kernel(const T* __restrict_
       }
     }
   }
-  for (int idx = threadIdx.x; idx < nkv * d; idx += 256) {
+  for (int idx = threadIdx.x; part != 0 && idx < nkv * d; idx += 256) {
     const float v = dv[(size_t)r * nkv * d + idx];
     st(out + (nq + nkv) * d + idx, v);
     if constexpr (R > 0) {
@@ -498,9 +502,9 @@ __global__ __launch_bounds__(256) void rope_bwd_pack_kernel(const T* __restrict_
   }
   }
   if constexpr (R > 0) {
-    if (lt.B[0]) lora_row_finish<R>(acc_q, lt_lds, lt.t[0], (bf16_t*)lt.ext[0], r, lt.scale);
-    if (lt.B[1]) lora_row_finish<R>(acc_k, lt_lds, lt.t[1], (bf16_t*)lt.ext[1], r, lt.scale);
-    if (lt.B[2]) lora_row_finish<R>(acc_v, lt_lds, lt.t[2], (bf16_t*)lt.ext[2], r, lt.scale);
+    if (lt.B[0] && part != 1) lora_row_finish<R>(acc_q, lt_lds, lt.t[0], (bf16_t*)lt.ext[0], r, lt.scale);
+    if (lt.B[1] && part != 0) lora_row_finish<R>(acc_k, lt_lds, lt.t[1], (bf16_t*)lt.ext[1], r, lt.scale);
+    if (lt.B[2] && part != 0) lora_row_finish<R>(acc_v, lt_lds, lt.t[2], (bf16_t*)lt.ext[2], r, lt.scale);
   }
 }
 
@@ -919,6 +923,8 @@ int32_t launch_rope_append(const flexco_layer_cfg& c, void* qkv, const int32_t* 
 int32_t launch_rope_bwd_pack(const flexco_layer_cfg& c, const void* dq, const float* dk_rows, const float* dv_rows,
                              void* dqkv, int win_start, int n, hipStream_t s, const RowLoraT* lt_in) {
   const size_t shm = sizeof(float) * c.head_dim;
+  if (n == 0) return FLEXCO_OK;
+  const dim3 grid(n, n <= 512 ? 2 : 1);   // few rows: two blocks per row
   // 16-byte accesses: also the float rows of dk / dv (their row pitch nkv d floats is a multiple of 16 bytes then)
   const bool vec = c.head_dim % 2 == 0 && vec_ok(c.dtype, c.head_dim / 2, {dq, dk_rows, dv_rows, dqkv});
   RowLoraT lt = {};
@@ -926,14 +932,14 @@ int32_t launch_rope_bwd_pack(const flexco_layer_cfg& c, const void* dq, const fl
     if (!row_lora_ok(c.dtype, lt_in->r)) return fail(FLEXCO_EUNSUPPORTED, "rope_bwd_pack: row product not covered");
     lt = *lt_in;
 #define FLEXCO_ROPE_BWD_LT(R_, V_)                                                                                      \
-  hipLaunchKernelGGL((rope_bwd_pack_kernel<bf16_t, R_, V_>), dim3(n), dim3(256), shm, s, (const bf16_t*)dq, dk_rows, dv_rows, \
+  hipLaunchKernelGGL((rope_bwd_pack_kernel<bf16_t, R_, V_>), grid, dim3(256), shm, s, (const bf16_t*)dq, dk_rows, dv_rows, \
                      (bf16_t*)dqkv, c.n_q_heads, c.n_kv_heads, c.head_dim, c.rope_theta, win_start, lt)
     if (lt.r == 16) { if (vec) FLEXCO_ROPE_BWD_LT(16, true); else FLEXCO_ROPE_BWD_LT(16, false); }
     else { if (vec) FLEXCO_ROPE_BWD_LT(32, true); else FLEXCO_ROPE_BWD_LT(32, false); }
 #undef FLEXCO_ROPE_BWD_LT
     return post_launch("rope_bwd_pack");
   }
-  DISPATCH_TV(c.dtype, vec, hipLaunchKernelGGL((rope_bwd_pack_kernel<T, 0, VEC>), dim3(n), dim3(256), shm, s, (const T*)dq,
+  DISPATCH_TV(c.dtype, vec, hipLaunchKernelGGL((rope_bwd_pack_kernel<T, 0, VEC>), grid, dim3(256), shm, s, (const T*)dq,
                                                dk_rows, dv_rows, (T*)dqkv, c.n_q_heads, c.n_kv_heads, c.head_dim,
                                                c.rope_theta, win_start, lt));
   return post_launch("rope_bwd_pack");
