@@ -291,6 +291,22 @@ int32_t flexco_lora_fwd(const void* x, void* y, int32_t T, int32_t in_features, 
                         const int32_t* seg_off, const int32_t* seg_adapter, int32_t n_seg,
                         float* u_ws, void* stream);
 
+/* flexco_lora_fwd for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid allocation): the same call without u_ws.  The rank-r products live in
+ * an array of FLEXCO_STATIC_SCRATCH_FLOATS floats (2 MiB) that is part of the library's image on every GPU
+ * it runs on, held until the process ends.  The call allocates and frees nothing and does not synchronise;
+ * the first call on a device looks the array's address up once (make that call outside a graph capture).
+ * Errors as flexco_lora_fwd, plus EWORKSPACE when T * rank > FLEXCO_STATIC_SCRATCH_FLOATS (nothing is
+ * launched).  All calls on one GPU share the one array: calls that overlap on a GPU (different streams,
+ * or threads) race on it; calls ordered on one stream do not.  Nothing of an earlier call's contents is
+ * read (every row is written before it is used), so the array needs no clearing. */
+#define FLEXCO_STATIC_SCRATCH_FLOATS (1 << 19)
+int32_t flexco_lora_fwd_static(const void* x, void* y, int32_t T, int32_t in_features, int32_t out_features,
+                               int32_t rank, float scale, int32_t dtype,
+                               const void* const* A_list, const void* const* B_list, int32_t n_adapters,
+                               const int32_t* seg_off, const int32_t* seg_adapter, int32_t n_seg,
+                               void* stream);
+
 /* Token-level LoRA backward of one window through one layer (Alg. 2, the Backward / Add /
  * Slice / CalculateGrads steps; Sec. 6.1; Sec. 7 KV-gradient accumulator).
  * Window = rows [win_start, win_start + win_len) of the finetune sequence; windows of a

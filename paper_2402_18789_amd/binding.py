@@ -128,6 +128,7 @@ def _load():
         "flexco_adapter_bwd": [i32, i32, P(Adapter), vp, i32, i32, i32, vp, vp, sz, vp],
         "flexco_attention_mixed": [P(LayerCfg), P(Maps), vp, P(KVPool), vp, vp, vp, sz, vp],
         "flexco_lora_fwd": [vp, vp, i32, i32, i32, i32, f32, i32, P(vp), P(vp), i32, P(i32), P(i32), i32, vp, vp],
+        "flexco_lora_fwd_static": [vp, vp, i32, i32, i32, i32, f32, i32, P(vp), P(vp), i32, P(i32), P(i32), i32, vp],
         "flexco_lora_bwd": [P(LayerCfg), P(BaseWeights), P(Lora), P(KVPool), vp, i32, P(FtState), i32, i32, vp, vp, vp, sz, vp],
         "flexco_attention_window_bwd": [P(LayerCfg), P(KVPool), vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
         "flexco_gemm": [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp],
@@ -155,7 +156,7 @@ def _load():
 _lib = _load()
 EXPORTS = ("flexco_last_error", "flexco_abi_version", "flexco_maps_blob_ints", "flexco_build_maps",
            "flexco_maps_rebase", "flexco_workspace_bytes", "flexco_layer_forward", "flexco_layer_forward_multi", "flexco_attention_mixed",
-           "flexco_lora_fwd", "flexco_lora_bwd", "flexco_attention_window_bwd", "flexco_gemm",
+           "flexco_lora_fwd", "flexco_lora_fwd_static", "flexco_lora_bwd", "flexco_attention_window_bwd", "flexco_gemm",
            "flexco_kernel_timer_start", "flexco_kernel_timer_stop", "flexco_kernel_timer_sample", "flexco_probe_mfma", "flexco_probe_read",
            "flexco_latency_estimate", "flexco_sched_window", "flexco_sched_inference", "flexco_sched_advance",
            "flexco_lm_loss_workspace_bytes", "flexco_lm_loss", "flexco_adam_step", "flexco_prune_graph",
@@ -315,6 +316,17 @@ def flexco_lora_fwd(x, y, T, in_features, out_features, rank, scale, dtype, A_li
     ip = lambda a: a.ctypes.data_as(C.POINTER(C.c_int32))
     _check(_lib.flexco_lora_fwd(_ptr(x), _ptr(y), T, in_features, out_features, rank, scale, dtype, Aarr, Barr, n,
                                 ip(so), ip(sa), len(sa), _ptr(u_ws), _stream(stream)))
+
+
+def flexco_lora_fwd_static(x, y, T, in_features, out_features, rank, scale, dtype, A_list, B_list, seg_off, seg_adapter,
+                           stream=None):
+    n = len(A_list)
+    Aarr = (C.c_void_p * n)(*[_ptr(a) for a in A_list])
+    Barr = (C.c_void_p * n)(*[_ptr(b) for b in B_list])
+    so, sa = _i32(seg_off), _i32(seg_adapter)
+    ip = lambda a: a.ctypes.data_as(C.POINTER(C.c_int32))
+    _check(_lib.flexco_lora_fwd_static(_ptr(x), _ptr(y), T, in_features, out_features, rank, scale, dtype, Aarr, Barr,
+                                       n, ip(so), ip(sa), len(sa), _stream(stream)))
 
 
 def flexco_lora_bwd(cfg, w, lora, pool, seq_pages, n_seq_pages, ft, win_start, win_len, dY, dX, ws, ws_bytes,

@@ -3,6 +3,7 @@
 // (Alg. 2) of a decoder layer.
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "flexco_internal.h"
@@ -666,11 +667,10 @@ extern "C" int32_t flexco_attention_mixed(const flexco_layer_cfg* cfg, const fle
                        (hipStream_t)stream);
 }
 
-extern "C" int32_t flexco_lora_fwd(const void* x, void* y, int32_t T, int32_t in_features, int32_t out_features,
-                                   int32_t rank, float scale, int32_t dtype, const void* const* A_list,
-                                   const void* const* B_list, int32_t n_adapters, const int32_t* seg_off,
-                                   const int32_t* seg_adapter, int32_t n_seg, float* u_ws, void* stream) {
-  clear_error();
+static int32_t lora_fwd_impl(const void* x, void* y, int32_t T, int32_t in_features, int32_t out_features,
+                             int32_t rank, float scale, int32_t dtype, const void* const* A_list,
+                             const void* const* B_list, int32_t n_adapters, const int32_t* seg_off,
+                             const int32_t* seg_adapter, int32_t n_seg, float* u_ws, void* stream) {
   FLEXCO_CHECK(x && y && A_list && B_list && seg_off && seg_adapter && u_ws, FLEXCO_EINVAL, "NULL argument");
   FLEXCO_CHECK(T > 0 && in_features > 0 && out_features > 0 && n_seg > 0 && n_adapters > 0, FLEXCO_EINVAL,
                "non-positive size");
@@ -698,6 +698,63 @@ extern "C" int32_t flexco_lora_fwd(const void* x, void* y, int32_t T, int32_t in
                           n, out_features, rank, scale, dtype, nullptr, s));
   }
   return FLEXCO_OK;
+}
+
+extern "C" int32_t flexco_lora_fwd(const void* x, void* y, int32_t T, int32_t in_features, int32_t out_features,
+                                   int32_t rank, float scale, int32_t dtype, const void* const* A_list,
+                                   const void* const* B_list, int32_t n_adapters, const int32_t* seg_off,
+                                   const int32_t* seg_adapter, int32_t n_seg, float* u_ws, void* stream) {
+  clear_error();
+  return lora_fwd_impl(x, y, T, in_features, out_features, rank, scale, dtype, A_list, B_list, n_adapters, seg_off,
+                       seg_adapter, n_seg, u_ws, stream);
+}
+
+// ---- flexco_lora_fwd_static: the same call with the rank-r scratch in the library's own image ----
+// For callers that cannot allocate device memory.  `scratch` is the device array; on the host its name is
+// only a handle for hipGetSymbolAddress, never an address: the per-device address is looked up once per
+// device and everything below uses that pointer.
+static __device__ __align__(256) float scratch[FLEXCO_STATIC_SCRATCH_FLOATS];
+
+namespace {
+constexpr int STATIC_MAX_DEVICES = 64;
+float* g_scratch_ptr[STATIC_MAX_DEVICES];   // address of `scratch` on each device, filled on first use
+std::mutex g_scratch_mutex;
+
+int32_t static_scratch(float** out) {
+  int dev = -1;
+  hipError_t rc = hipGetDevice(&dev);
+  if (rc != hipSuccess) return fail(FLEXCO_EHIP, "hipGetDevice: %s", hipGetErrorString(rc));
+  FLEXCO_CHECK(dev >= 0 && dev < STATIC_MAX_DEVICES, FLEXCO_EUNSUPPORTED, "device %d beyond the %d devices supported",
+               dev, STATIC_MAX_DEVICES);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    float* p = nullptr;
+    rc = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch));
+    if (rc != hipSuccess || !p)
+      return fail(FLEXCO_EHIP, "hipGetSymbolAddress(scratch) on device %d: %s", dev, hipGetErrorString(rc));
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return FLEXCO_OK;
+}
+}  // namespace
+
+extern "C" int32_t flexco_lora_fwd_static(const void* x, void* y, int32_t T, int32_t in_features,
+                                          int32_t out_features, int32_t rank, float scale, int32_t dtype,
+                                          const void* const* A_list, const void* const* B_list, int32_t n_adapters,
+                                          const int32_t* seg_off, const int32_t* seg_adapter, int32_t n_seg,
+                                          void* stream) {
+  clear_error();
+  FLEXCO_CHECK(T > 0 && rank > 0, FLEXCO_EINVAL, "non-positive size");
+  FLEXCO_CHECK((size_t)T * (size_t)rank <= (size_t)FLEXCO_STATIC_SCRATCH_FLOATS, FLEXCO_EWORKSPACE,
+               "T * rank = %zu exceeds the built-in scratch of %zu floats; use flexco_lora_fwd with a buffer of the caller's",
+               (size_t)T * (size_t)rank, (size_t)FLEXCO_STATIC_SCRATCH_FLOATS);
+  float* u = nullptr;
+  FLEXCO_TRY(static_scratch(&u));
+  // every row of u that the expansion reads is written by the shrink launched just before it: nothing of the
+  // previous call's contents is read, so nothing has to be cleared
+  return lora_fwd_impl(x, y, T, in_features, out_features, rank, scale, dtype, A_list, B_list, n_adapters, seg_off,
+                       seg_adapter, n_seg, u, stream);
 }
 
 static int32_t layer_forward_impl(const flexco_layer_cfg* cfg, const flexco_base_weights* w, const Adapters& ad,
