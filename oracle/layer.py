@@ -12,6 +12,16 @@ Two ways to the same numbers:
     only the activations graph pruning keeps (Algorithm 1): x, x2, gate, up, Q, K, V
     (and the attention output when the output projection carries LoRA).
 
+Storage rounding (optional, `storage=` of the METHOD's two functions): the paper says nothing
+about where a reduced-precision run rounds.  Reading: a configuration whose storage type is
+narrower than the arithmetic rounds every tensor it WRITES TO MEMORY (norm outputs, projection
+outputs, rotated q / k and the cached K / V / Q rows, attention output, x2, gate, up, their
+product, y; in the backward pass every gradient handed from one operator to the next) and
+nothing else; accumulators (LoRA gradients, KV-gradient accumulator, log-sum-exp) stay wide.
+`storage` names that rounding ("bf16", or a function array -> array; None = no rounding, the
+default and the definition); all arithmetic stays in `dtype`.  It exists to tell apart, in a parity test,
+error that comes from the storage type itself from error of the arithmetic under test.
+
 Readings of Algorithm 2 taken here: the position update l_{j+1} = l_j - s_j belongs
 inside the window loop; "Add" means accum[0:l_j) += (dK, dV); in the backward pass
 l_j is the exclusive END of window j and Slice takes the s_j rows ending there.
@@ -147,16 +157,27 @@ class FtState:
         self.dk_accum, self.dv_accum = z(cfg.kv_dim), z(cfg.kv_dim)
 
 
+def _storage_fn(storage, dtype):
+    """storage: None (no rounding), "bf16", or a function array -> array"""
+    if storage is None:
+        return lambda a: a
+    if storage == "bf16":
+        return lambda a: ops.round_bf16(np.asarray(a, dtype=dtype))
+    return lambda a: np.asarray(storage(a), dtype=dtype)
+
+
 def layer_forward_mixed(cfg, W, lora, maps, x, pool, ft_states=None, dtype=np.float64,
-                        return_all=False):
+                        return_all=False, storage=None):
     """One forward iteration of the layer over a mixed token batch, through the
     caches.  maps: oracle.maps.build_maps output.  pool: KVPool (new K/V rows are
     appended at the tokens' slots).  ft_states: {seq_id: FtState}; rows of finetune
     windows store Q and the pruned activation set there.  lora: one adapter {target: (A, B)},
     applied to the rows whose segment has adapter >= 0; or, with several adapters served in one
     batch (Sec. 6.2: the inference requests of a batch may belong to different PEFT models), a
-    list of adapters indexed by adapter id, each applied to the rows of its own requests."""
+    list of adapters indexed by adapter id, each applied to the rows of its own requests.
+    storage: rounding applied to every tensor written to memory (see the module header)."""
     W, x = _cast(W, dtype), np.asarray(x, dtype=dtype)
+    sr = _storage_fn(storage, dtype)
     T = maps["T"]
     assert x.shape[0] == T
     if isinstance(lora, list):
@@ -170,21 +191,22 @@ def layer_forward_mixed(cfg, W, lora, maps, x, pool, ft_states=None, dtype=np.fl
             if maps["seg_adapter"][s] >= 0:
                 rows[maps["seg_off"][s]:maps["seg_off"][s + 1]] = True
     pos = maps["tok_pos"]
-    h1 = ops.rmsnorm(x, W["g1"], cfg.rms_eps)
-    q0 = _proj(cfg, W, lora, "q", "wq", "bq", h1, rows)
-    k0 = _proj(cfg, W, lora, "k", "wk", "bk", h1, rows)
-    v = _proj(cfg, W, lora, "v", "wv", "bv", h1, rows)
-    q = ops.rope(q0, pos, cfg.n_q_heads, cfg.head_dim, cfg.rope_theta)
-    k = ops.rope(k0, pos, cfg.n_kv_heads, cfg.head_dim, cfg.rope_theta)
+    h1 = sr(ops.rmsnorm(x, W["g1"], cfg.rms_eps))
+    q0 = sr(_proj(cfg, W, lora, "q", "wq", "bq", h1, rows))
+    k0 = sr(_proj(cfg, W, lora, "k", "wk", "bk", h1, rows))
+    v = sr(_proj(cfg, W, lora, "v", "wv", "bv", h1, rows))
+    q = sr(ops.rope(q0, pos, cfg.n_q_heads, cfg.head_dim, cfg.rope_theta))
+    k = sr(ops.rope(k0, pos, cfg.n_kv_heads, cfg.head_dim, cfg.rope_theta))
     pool.k[maps["slot"]] = k
     pool.v[maps["slot"]] = v
     a, lse = attention_mixed(cfg, maps, q, pool)
-    x2 = x + _proj(cfg, W, lora, "o", "wo", None, a, rows)
-    h2 = ops.rmsnorm(x2, W["g2"], cfg.rms_eps)
-    gate = _proj(cfg, W, lora, "gate", "wg", None, h2, rows)
-    up = _proj(cfg, W, lora, "up", "wu", None, h2, rows)
-    act = ops.swiglu(gate, up)
-    y = x2 + _proj(cfg, W, lora, "down", "wd", None, act, rows)
+    a = sr(a)
+    x2 = sr(x + _proj(cfg, W, lora, "o", "wo", None, a, rows))
+    h2 = sr(ops.rmsnorm(x2, W["g2"], cfg.rms_eps))
+    gate = sr(_proj(cfg, W, lora, "gate", "wg", None, h2, rows))
+    up = sr(_proj(cfg, W, lora, "up", "wu", None, h2, rows))
+    act = sr(ops.swiglu(gate, up))
+    y = sr(x2 + _proj(cfg, W, lora, "down", "wd", None, act, rows))
     if ft_states is not None:
         for r in range(maps["n_req"]):
             if maps["req_kind"][r] != 2:
@@ -219,7 +241,7 @@ def attention_mixed(cfg, maps, q, pool):
 
 
 def layer_backward_window(cfg, W, lora, st, K, V, win_start, win_len, dY, grads, need_dx=True,
-                          dtype=np.float64):
+                          dtype=np.float64, storage=None):
     """Backward of one token window [win_start, win_start + win_len) of a finetune
     sequence through one layer (Alg. 2, the Backward / Add / Slice / CalculateGrads
     steps).  st: FtState filled by the forward windows.  K, V: the sequence's cached
@@ -229,23 +251,27 @@ def layer_backward_window(cfg, W, lora, st, K, V, win_start, win_len, dY, grads,
     queries and its own rows become complete.  LoRA gradients are added into grads
     {target: (dA, dB)}.  Returns dX [win_len, H] (None when need_dx is False: no
     trainable parameter below, Alg. 1's dead-output propagation).
-    Reads only x, x2, gate, up, Q, K, V (+ attn if 'o' carries LoRA) from the state."""
+    Reads only x, x2, gate, up, Q, K, V (+ attn if 'o' carries LoRA) from the state.
+    storage: rounding applied to every rematerialised activation and every gradient handed from
+    one operator to the next (see the module header); the accumulators are not rounded."""
     W, lora = _cast(W, dtype), _cast(lora, dtype)
+    sr = _storage_fn(storage, dtype)
     dY = np.asarray(dY, dtype=dtype)
     l = win_start + win_len
     w = slice(win_start, l)
     pos = np.arange(win_start, l)
     # --- MLP side (row-local); h2 and act are rematerialized --------------------
     x2 = st.x2[w]
-    h2 = ops.rmsnorm(x2, W["g2"], cfg.rms_eps)
-    act = ops.swiglu(st.gate[w], st.up[w])
-    dact = _proj_bwd(cfg, W, lora, "down", "wd", act, dY, grads)
+    h2 = sr(ops.rmsnorm(x2, W["g2"], cfg.rms_eps))
+    act = sr(ops.swiglu(st.gate[w], st.up[w]))
+    dact = sr(_proj_bwd(cfg, W, lora, "down", "wd", act, dY, grads))
     dgate, dup = ops.swiglu_bwd(st.gate[w], st.up[w], dact)
-    dh2 = _proj_bwd(cfg, W, lora, "gate", "wg", h2, dgate, grads) \
-        + _proj_bwd(cfg, W, lora, "up", "wu", h2, dup, grads)
-    dx2 = dY + ops.rmsnorm_bwd(x2, W["g2"], cfg.rms_eps, dh2)
+    dgate, dup = sr(dgate), sr(dup)
+    dh2 = sr(_proj_bwd(cfg, W, lora, "gate", "wg", h2, dgate, grads)
+             + _proj_bwd(cfg, W, lora, "up", "wu", h2, dup, grads))
+    dx2 = sr(dY + ops.rmsnorm_bwd(x2, W["g2"], cfg.rms_eps, dh2))
     attn_in = st.attn[w] if (lora and "o" in lora) else np.zeros((win_len, cfg.q_dim), dtype=dtype)
-    da = _proj_bwd(cfg, W, lora, "o", "wo", attn_in, dx2, grads)
+    da = sr(_proj_bwd(cfg, W, lora, "o", "wo", attn_in, dx2, grads))
     # --- attention: dQ for the window, dK/dV for every row before its end ------
     dq, dK, dV = ops.attention_bwd(st.q_cache[w], pos, K[:l], V[:l], cfg.n_q_heads, cfg.n_kv_heads,
                                    cfg.head_dim, da)
@@ -256,15 +282,15 @@ def layer_backward_window(cfg, W, lora, st, K, V, win_start, win_len, dY, grads,
     if not need_dx and not any(t in lora for t in ("q", "k", "v")):
         return None
     x = st.x[w]
-    h1 = ops.rmsnorm(x, W["g1"], cfg.rms_eps)
-    dq0 = ops.rope(dq, pos, cfg.n_q_heads, cfg.head_dim, cfg.rope_theta, inverse=True)
-    dk0 = ops.rope(gk, pos, cfg.n_kv_heads, cfg.head_dim, cfg.rope_theta, inverse=True)
-    dh1 = _proj_bwd(cfg, W, lora, "q", "wq", h1, dq0, grads) \
-        + _proj_bwd(cfg, W, lora, "k", "wk", h1, dk0, grads) \
-        + _proj_bwd(cfg, W, lora, "v", "wv", h1, gv, grads)
+    h1 = sr(ops.rmsnorm(x, W["g1"], cfg.rms_eps))
+    dq0 = sr(ops.rope(sr(dq), pos, cfg.n_q_heads, cfg.head_dim, cfg.rope_theta, inverse=True))
+    dk0 = sr(ops.rope(gk, pos, cfg.n_kv_heads, cfg.head_dim, cfg.rope_theta, inverse=True))
+    dh1 = sr(_proj_bwd(cfg, W, lora, "q", "wq", h1, dq0, grads)
+             + _proj_bwd(cfg, W, lora, "k", "wk", h1, dk0, grads)
+             + _proj_bwd(cfg, W, lora, "v", "wv", h1, sr(gv), grads))
     if not need_dx:
         return None
-    return dx2 + ops.rmsnorm_bwd(x, W["g1"], cfg.rms_eps, dh1)
+    return sr(dx2 + ops.rmsnorm_bwd(x, W["g1"], cfg.rms_eps, dh1))
 
 
 # ---------------------------------------------------------------------------

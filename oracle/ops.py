@@ -131,3 +131,15 @@ def lora_bwd(x, A, B, scale, dy):
     dA = scale * x.T @ t
     dx = scale * t @ A.T
     return dx, dA, dB
+
+
+# ---- storage types narrower than the arithmetic --------------------------------
+def round_bf16(a):
+    """Nearest bfloat16 value (8 significant bits, ties to even) of every element, returned in the
+    input's own floating-point type.  Written from the format's definition: a = m * 2^e with
+    0.5 <= |m| < 1, keep round_half_even(m * 2^8) / 2^8.  Values below the normal range of the format
+    (|a| < 2^-126) are outside what the layer's tensors hold and are not treated specially."""
+    a = np.asarray(a)
+    m, e = np.frexp(a)
+    return np.ldexp(np.rint(m * 256.0) / 256.0, e).astype(a.dtype)
+

@@ -12,7 +12,8 @@ tokens (log-normal contexts, median 1024) + 1024 prefill tokens (whole prompts o
 the last 512-token window of a 2048-token finetune sequence; synthetic weights and caches.  Prints one
 JSON line.  c4: the 14B shape (48 layers, LoRA on all seven projections, window 1024 of 4096, half the
 budget inference); c5: the 32B shape (64 layers, rank 32, T = 4096), whose weights, 64 KV pools and
-finetune state fill most of the GPU's memory.  A measurement: parity of the same calls chained over layers is what the GPU tests check."""
+finetune state fill most of the GPU's memory; --inference-share (c4) moves the split of the budget between
+inference tokens and the finetune window (25 / 50 / 75 / 90 %: windows of 1536 / 1024 / 512 / 205 rows).  A measurement: parity of the same calls chained over layers is what the GPU tests check."""
 import argparse
 import json
 import time
@@ -33,10 +34,12 @@ MODELS = {   # configuration, batch recipe, vocabulary
 }
 
 
-def build(cfg, batch, n_layers, vocab, seed):
+def build(cfg, batch, n_layers, vocab, seed, host_seeded_layers=(), sample=()):
     """Device state of the whole model.  Layer 0 takes the seeded host weights; the others get weights of
     the same law from the device generator (436 MB per layer: generating them on the host would take
-    longer than the measurement)."""
+    longer than the measurement).  host_seeded_layers: layers whose weights and adapter are the host
+    generator's for that layer index instead (so that a check can regenerate them), and in whose pools the
+    cached prefixes of the requests in `sample` are the host generator's rows."""
     dt = HH.TORCH_DTYPE[cfg.dtype]
     W, lora = gen.layer_weights(cfg, seed, 0), gen.lora_weights(cfg, seed, 0)
     g = torch.Generator(device="cuda")
@@ -45,8 +48,11 @@ def build(cfg, batch, n_layers, vocab, seed):
     L = batch.seq_capacity[ft_req.seq_id]
     layers, pools, fts = [], [], []
     for n in range(n_layers):
-        ly = HH.DeviceLayer(cfg, W, lora)
-        if n > 0:
+        if n > 0 and n in host_seeded_layers:
+            ly = HH.DeviceLayer(cfg, gen.layer_weights(cfg, seed, n), gen.lora_weights(cfg, seed, n))
+        else:
+            ly = HH.DeviceLayer(cfg, W, lora)
+        if n > 0 and n not in host_seeded_layers:
             for name in ("wqkv", "wo", "wgu", "wd"):
                 t = ly.t[name]
                 t.copy_((0.02 * torch.randn(t.shape, generator=g, device="cuda", dtype=torch.float32)).to(dt))
@@ -55,6 +61,11 @@ def build(cfg, batch, n_layers, vocab, seed):
                 ly.Bm[t].copy_((0.01 * torch.randn(ly.Bm[t].shape, generator=g, device="cuda")).to(dt))
         pool = HH.DevicePool(cfg, batch.num_pages)
         pool.fill_random(seed + n)
+        if n in host_seeded_layers:
+            for r in sample:
+                if r.start_pos:
+                    k, v = gen.kv_prefix(cfg, seed, n, r.seq_id, r.start_pos)
+                    pool.write_rows(batch.seq_pages[r.seq_id], k, v)
         layers.append(ly)
         pools.append(pool)
         fts.append(HH.DeviceFtState(cfg, L))
@@ -64,14 +75,20 @@ def build(cfg, batch, n_layers, vocab, seed):
     return layers, pools, fts, gain, w_lm, ft_req, L
 
 
-def run(n_layers=None, steps=5, warmup=2, seed=0, vocab=None, model="c3"):
+def run(n_layers=None, steps=5, warmup=2, seed=0, vocab=None, model="c3", inference_share=None, capture_layers=(),
+        sample=()):
+    """capture_layers: layers whose input rows, output rows, incoming gradient and outgoing gradient of the LAST
+    timed iteration are kept (copies on the device) and returned under "captured" together with the layers'
+    device objects, for a caller that checks sampled layers of the whole-model run one by one; those layers are
+    built host-seeded (see build), with the cached prefixes of `sample`'s requests."""
     cfg_name, make_batch, model_vocab = MODELS[model]
     cfg = CONFIGS[cfg_name]
     n_layers = n_layers or cfg.n_layers
     vocab = vocab or model_vocab
-    batch = make_batch(seed)
+    batch = make_batch(seed) if inference_share is None else make_batch(seed, inference_share)
     dt = HH.TORCH_DTYPE[cfg.dtype]
-    layers, pools, fts, gain, w_lm, ft_req, L = build(cfg, batch, n_layers, vocab, seed)
+    layers, pools, fts, gain, w_lm, ft_req, L = build(cfg, batch, n_layers, vocab, seed, tuple(capture_layers), sample)
+    captured = {n: {} for n in capture_layers}
     db = HH.DeviceBatch(cfg, batch.requests, batch.seq_pages, batch.num_pages)
     hm = db.host_maps
     T, n_ft = hm.T, hm.n_ft
@@ -105,6 +122,8 @@ def run(n_layers=None, steps=5, warmup=2, seed=0, vocab=None, model="c3"):
         for n in range(n_layers):
             dst = xa if n % 2 == 0 else xb
             B.flexco_layer_forward(layers[n].c, layers[n].w, layers[n].lora, db.maps, src, dst, pools[n].c, fts[n].c, ws.ptr, ws.bytes)
+            if timed and n in captured:
+                captured[n]["x_in"], captured[n]["x_out"] = src.clone(), dst.clone()
             src = dst
         if timed:
             ev[1].record()
@@ -116,6 +135,8 @@ def run(n_layers=None, steps=5, warmup=2, seed=0, vocab=None, model="c3"):
         for n in range(n_layers - 1, -1, -1):
             B.flexco_lora_bwd(layers[n].c, layers[n].w, layers[n].lora, pools[n].c, pages, len(pages), fts[n].c,
                               ft_req.start_pos, ft_req.n_new, dcur, dnext if n > 0 else None, ws.ptr, ws.bytes)
+            if timed and n in captured:
+                captured[n]["dY"], captured[n]["dX"] = dcur.clone(), (dnext.clone() if n > 0 else None)
             dcur, dnext = dnext, dcur
         if timed:
             ev[3].record()
@@ -155,7 +176,12 @@ def run(n_layers=None, steps=5, warmup=2, seed=0, vocab=None, model="c3"):
         adam_ms.append((time.perf_counter() - t0) * 1e3)
     positions = int(sum(r.start_pos + r.n_new for r in batch.requests))
     p_layer = (cfg.q_dim + 2 * cfg.kv_dim) * cfg.hidden + cfg.q_dim * cfg.hidden + 3 * cfg.hidden * cfg.ffn
+    extra = {}
+    if capture_layers:
+        extra["captured"] = {"rows": captured, "layers": layers, "fts": fts, "batch": batch, "ft_req": ft_req, "seq_len": L,
+                             "cfg": cfg}
     return {
+        **extra,
         "what": "one co-serving iteration through the whole model: forward of the mixed batch through every layer, "
                 "loss head on the finetune window, the window's backward through every layer",
         "config": {"workload": cfg_name, "layers": n_layers, "tokens": T, "finetune_tokens": n_ft, "requests": hm.n_req,
@@ -178,8 +204,12 @@ def main():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--inference-share", type=float, default=None,
+                    help="c4 only: share of the 2048-token budget that is inference tokens (0.25, 0.5, 0.75, 0.9)")
     a = ap.parse_args()
-    print(json.dumps(run(a.layers, a.steps, a.warmup, a.seed, model=a.config)))
+    if a.inference_share is not None and a.config != "c4":
+        ap.error("--inference-share belongs to --config c4")
+    print(json.dumps(run(a.layers, a.steps, a.warmup, a.seed, model=a.config, inference_share=a.inference_share)))
 
 
 if __name__ == "__main__":

@@ -23,3 +23,56 @@ def rel_err(a, b):
     a, b = np.asarray(a, dtype=np.float64), np.asarray(b, dtype=np.float64)
     den = np.max(np.abs(b))
     return float(np.max(np.abs(a - b)) / den) if den > 0 else float(np.max(np.abs(a - b)))
+
+
+def oracle_layer_case(cfg, batch0, ft_window, prefill_chunk, bwd_windows, seed=0, storage=None, dtype=np.float64):
+    """The oracle's side of a whole-layer parity case, alone: forward iterations until the finetune sequence is
+    through (seeded inputs as in the GPU parity tests), then its token-window backward with the same scaled
+    MSE gradient.  -> {name: array} of every tensor those tests compare.  `storage` / `dtype` as in
+    oracle.layer (storage rounding mode, arithmetic type)."""
+    from oracle import layer as OL
+    from oracle.maps import build_maps
+    from workload.configs import KIND_FINETUNE
+    W, lora = gen.layer_weights(cfg, seed, 0), gen.lora_weights(cfg, seed, 0)
+    pool = OL.KVPool(batch0.num_pages, cfg.page_size, cfg.kv_dim, dtype=dtype)
+    ft_seq = [r.seq_id for r in batch0.requests if r.kind == KIND_FINETUNE][0]
+    L = batch0.seq_capacity[ft_seq]
+    st = OL.FtState(cfg, L, dtype=dtype)
+    for r in batch0.requests:
+        if r.start_pos:
+            k, v = gen.kv_prefix(cfg, seed, 0, r.seq_id, r.start_pos)
+            sl = pool.slots(batch0.seq_pages[r.seq_id], r.start_pos)
+            pool.k[sl], pool.v[sl] = k, v
+    out = {}
+    batch, it = batch0, 0
+    y_ft = np.zeros((L, cfg.hidden))
+    while any(r.kind == KIND_FINETUNE for r in batch.requests):
+        x = gen.layer_input(cfg, seed, batch.n_tokens, tag=f"x{it}")
+        om = build_maps(batch.requests, batch.seq_pages, batch.page_size, batch.num_pages)
+        y = OL.layer_forward_mixed(cfg, W, lora, om, x, pool, {ft_seq: st}, dtype=dtype, storage=storage)
+        out[f"y it{it}"] = np.asarray(y, dtype=np.float64)
+        for r, off in zip(batch.requests, np.cumsum([0] + [q.n_new for q in batch.requests])):
+            if r.kind == KIND_FINETUNE:
+                y_ft[r.start_pos:r.start_pos + r.n_new] = y[off:off + r.n_new]
+        batch = gen.advance(batch, prefill_chunk=prefill_chunk, ft_window=ft_window)
+        it += 1
+    out["y_ft"] = y_ft
+    return out, (W, lora, pool, st, ft_seq, L)
+
+
+def oracle_layer_case_backward(cfg, batch0, bwd_windows, seed, state, dY, storage=None, dtype=np.float64):
+    """second half of oracle_layer_case: the backward windows for a given dY [L, H] -> {name: array}"""
+    from oracle import layer as OL
+    W, lora, pool, st, ft_seq, L = state
+    slots = pool.slots(batch0.seq_pages[ft_seq], L)
+    grads, dX, l = {}, np.zeros((L, cfg.hidden)), L
+    for s in bwd_windows:
+        dX[l - s:l] = OL.layer_backward_window(cfg, W, lora, st, pool.k[slots[:l]].astype(dtype), pool.v[slots[:l]].astype(dtype),
+                                               l - s, s, dY[l - s:l], grads, dtype=dtype, storage=storage)
+        l -= s
+    out = {"dX": dX, "dk_accum": np.asarray(st.dk_accum, dtype=np.float64), "dv_accum": np.asarray(st.dv_accum, dtype=np.float64)}
+    for name in ("q_cache", "x2", "gate", "up", "attn", "lse"):
+        out["saved " + name] = np.asarray(getattr(st, name), dtype=np.float64)
+    for t in cfg.lora_targets:
+        out[f"dA[{t}]"], out[f"dB[{t}]"] = np.asarray(grads[t][0], dtype=np.float64), np.asarray(grads[t][1], dtype=np.float64)
+    return out

@@ -25,3 +25,211 @@ def test_model_iteration_two_layers():
     assert abs(r["loss"] - math.log(4096) * 512 / 2048) < 0.2 * math.log(4096) * 512 / 2048
     assert r["lora_grad_norm_dB"] > 0
     assert r["forward_ms"] > 0 and r["backward_ms"] > 0
+
+
+# ------------------------------------------------------------------------------------------------------------
+# Three layers of the 8B shape chained, whole-model batch, against the oracle's own chain (no device value ever
+# reaches the oracle): the device runs the full T = 2048 batch through three layers with weights, pools and
+# finetune state of their own and the window's backward from a seeded top gradient back down; the oracle runs a
+# sample of the requests (decode tokens, a whole prompt, the last truncated prompt, the finetune window) through
+# the same three layers from the same seeded inputs.
+# ------------------------------------------------------------------------------------------------------------
+def _compact_pages(batch, sample):
+    """the sampled sequences' page lists renumbered 0, 1, 2, ... for a small oracle-side pool (the oracle's results
+    do not depend on which pages hold a sequence)"""
+    import numpy as np
+    out, nxt = {}, 0
+    for r in sample:
+        n = len(batch.seq_pages[r.seq_id])
+        out[r.seq_id] = np.arange(nxt, nxt + n)
+        nxt += n
+    return out, nxt
+
+
+def test_chain_of_three_layers_8b_shape_sampled():
+    import numpy as np
+    import torch
+    import paper_2402_18789_amd.binding as B
+    from paper_2402_18789_amd import host as HH
+    from oracle import layer as OL
+    from oracle.maps import build_maps
+    from workload import gen, CONFIGS
+    from gpu_common import assert_close_storage, to_np, TOL
+    say("chain of three 8B-shaped layers on the whole-model batch, sampled")
+    cfg, seed, N = CONFIGS["c3_llama8b_full"], 0, 3
+    tol = TOL["bf16"]
+    batch = gen.batch_c3(seed)
+    sample = gen.sample_requests(batch, 8)
+    ft_req = [r for r in batch.requests if r.kind == 2][0]
+    L = batch.seq_capacity[ft_req.seq_id]
+    Ws = [gen.layer_weights(cfg, seed, n) for n in range(N)]
+    los = [gen.lora_weights(cfg, seed, n) for n in range(N)]
+    devs = [HH.DeviceLayer(cfg, Ws[n], los[n]) for n in range(N)]
+    pools = [HH.DevicePool(cfg, batch.num_pages) for _ in range(N)]
+    fts = [HH.DeviceFtState(cfg, L) for _ in range(N)]
+    cpages, n_cp = _compact_pages(batch, sample)
+    o_pools = [OL.KVPool(n_cp, cfg.page_size, cfg.kv_dim, dtype=np.float32) for _ in range(N)]
+    o_fts = [OL.FtState(cfg, L) for _ in range(N)]
+    for n in range(N):
+        pools[n].fill_random(seed + n)
+        for r in sample:
+            if r.start_pos:
+                k, v = gen.kv_prefix(cfg, seed, n, r.seq_id, r.start_pos)
+                pools[n].write_rows(batch.seq_pages[r.seq_id], k, v)
+                sl = o_pools[n].slots(cpages[r.seq_id], r.start_pos)
+                o_pools[n].k[sl], o_pools[n].v[sl] = k, v
+    db = HH.DeviceBatch(cfg, batch.requests, batch.seq_pages, batch.num_pages)
+    hm = db.host_maps
+    ws = HH.Workspace(devs[0].c, hm.T, hm.n_parts, ft_req.n_new, L)
+    x_np = gen.layer_input(cfg, seed, hm.T)
+    cur = torch.from_numpy(x_np).to("cuda", torch.bfloat16)
+    say("  device: forward through %d layers, T = %d" % (N, hm.T))
+    for n in range(N):
+        out = torch.empty_like(cur)
+        B.flexco_layer_forward(devs[n].c, devs[n].w, devs[n].lora, db.maps, cur, out, pools[n].c, fts[n].c, ws.ptr, ws.bytes)
+        cur = out
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(cur.float()).all())
+    dY_np = gen.layer_input(cfg, seed, ft_req.n_new, tag="dy_top")
+    d_cur = torch.from_numpy(dY_np).to("cuda", torch.bfloat16)
+    pages_d = torch.from_numpy(np.asarray(batch.seq_pages[ft_req.seq_id], dtype=np.int32)).to("cuda")
+    for n in range(N - 1, -1, -1):
+        d_next = torch.empty_like(d_cur)
+        B.flexco_lora_bwd(devs[n].c, devs[n].w, devs[n].lora, pools[n].c, pages_d, int(pages_d.numel()), fts[n].c,
+                          ft_req.start_pos, ft_req.n_new, d_cur, d_next, ws.ptr, ws.bytes)
+        d_cur = d_next
+    torch.cuda.synchronize()
+    # ---- oracle: the sampled requests through the same chain, its own values all the way; once plain (the bar)
+    # and once with every stored tensor rounded to bf16 (what the storage type alone costs, for the rule of
+    # gpu_common.assert_close_storage) ----
+    rows = gen.sample_token_rows(batch, sample)
+    om = build_maps(sample, cpages, batch.page_size, n_cp)
+    say("  oracle: %d sampled tokens through %d layers, plain and with bf16 storage" % (len(rows), N))
+    res = {}
+    for storage in (None, "bf16"):
+        if storage is not None:                      # fresh caches and state for the second run
+            for n in range(N):
+                o_fts[n] = OL.FtState(cfg, L)
+        h = x_np[rows].astype(np.float64)
+        for n in range(N):
+            h = OL.layer_forward_mixed(cfg, Ws[n], los[n], om, h, o_pools[n], {ft_req.seq_id: o_fts[n]}, storage=storage)
+        out = {"top output (sampled rows)": h}
+        sl = o_pools[0].slots(cpages[ft_req.seq_id], L)
+        d = dY_np.astype(np.float64)
+        grads = [dict() for _ in range(N)]
+        for n in range(N - 1, -1, -1):
+            d = OL.layer_backward_window(cfg, Ws[n], los[n], o_fts[n], o_pools[n].k[sl].astype(np.float64),
+                                         o_pools[n].v[sl].astype(np.float64), ft_req.start_pos, ft_req.n_new, d, grads[n],
+                                         storage=storage)
+        out["dX below the bottom layer"] = d
+        for n in range(N):
+            out[f"layer {n} dk_accum"], out[f"layer {n} dv_accum"] = o_fts[n].dk_accum.copy(), o_fts[n].dv_accum.copy()
+            for t in cfg.lora_targets:
+                out[f"layer {n} dA[{t}]"], out[f"layer {n} dB[{t}]"] = grads[n][t]
+        res[storage] = out
+    got = {"top output (sampled rows)": to_np(cur)[rows], "dX below the bottom layer": to_np(d_cur)}
+    for n in range(N):
+        gg = devs[n].grads_numpy()
+        got[f"layer {n} dk_accum"], got[f"layer {n} dv_accum"] = to_np(fts[n].dk_accum), to_np(fts[n].dv_accum)
+        for t in cfg.lora_targets:
+            got[f"layer {n} dA[{t}]"], got[f"layer {n} dB[{t}]"] = gg[t]
+    report, excess, failures = [], [], []
+    for name in res[None]:
+        try:
+            e, _ = assert_close_storage(name, got[name], res[None][name], res["bf16"][name], tol, report)
+            if e > tol:
+                excess.append(name)
+        except AssertionError as err:
+            failures.append(str(err))
+    say("  device vs plain (bf16 storage alone vs plain): " + ", ".join(f"{r[0]}={r[1]:.1e}({r[2]:.1e})" for r in report))
+    assert not failures, failures
+    # three layers deep, bf16 storage alone costs 1e-2 .. 3e-2 on the gradients (the figures in brackets); the top
+    # output, the bottom input gradient and the bottom layer's gradients must not need the storage rule
+    assert not [n for n in excess if n.startswith(("top", "dX", "layer 0"))], excess
+
+
+# ------------------------------------------------------------------------------------------------------------
+# Sampled layers of a whole-model iteration.  All layers of the model are resident and one iteration runs
+# (forward through every layer, loss head, backward through every layer).  For the first, the middle and the last
+# layer the test takes what that layer was GIVEN in that iteration - its input rows and the gradient rows that
+# reached it, both produced by the device's layers above / below, which the oracle cannot compute at this size -
+# regenerates the layer's weights from its seed on the host, recomputes a sample of requests with the oracle and
+# holds the layer's own outputs (output rows, saved activations, input gradient, KV-gradient accumulator, LoRA
+# gradients) to it.  It is a per-layer check at depth; the chained checks whose oracle side never sees a device
+# value are the three-layer chain above and the training-step tests.
+# ------------------------------------------------------------------------------------------------------------
+def _layer_sampled_check(model, n_decode, inference_share=None):
+    import numpy as np
+    from paper_2402_18789_amd import model_iter
+    from oracle import layer as OL
+    from oracle.maps import build_maps
+    from workload import gen, CONFIGS
+    from gpu_common import assert_close, to_np, TOL
+    cfg_name, make_batch, _ = model_iter.MODELS[model]
+    cfg, seed = CONFIGS[cfg_name], 0
+    tol = TOL["bf16"]
+    batch = make_batch(seed) if inference_share is None else make_batch(seed, inference_share)
+    sample = gen.sample_requests(batch, n_decode)
+    n_layers = cfg.n_layers
+    which = (0, n_layers // 2, n_layers - 1)
+    say("whole-model iteration %s (%d layers), layers %s checked on sampled requests" % (cfg_name, n_layers, which))
+    r = model_iter.run(steps=1, warmup=1, seed=seed, model=model, inference_share=inference_share, capture_layers=which,
+                       sample=sample)
+    assert r["finite"]
+    cap = r["captured"]
+    ft_req, L = cap["ft_req"], cap["seq_len"]
+    rows = gen.sample_token_rows(batch, sample)
+    cpages, n_cp = _compact_pages(batch, sample)
+    om = build_maps(sample, cpages, batch.page_size, n_cp)
+    w = slice(ft_req.start_pos, ft_req.start_pos + ft_req.n_new)
+    for n in which:
+        c = cap["rows"][n]
+        W, lo = gen.layer_weights(cfg, seed, n), gen.lora_weights(cfg, seed, n)
+        o_pool = OL.KVPool(n_cp, cfg.page_size, cfg.kv_dim, dtype=np.float32)
+        for q in sample:
+            if q.start_pos:
+                k, v = gen.kv_prefix(cfg, seed, n, q.seq_id, q.start_pos)
+                sl = o_pool.slots(cpages[q.seq_id], q.start_pos)
+                o_pool.k[sl], o_pool.v[sl] = k, v
+        o_ft = OL.FtState(cfg, L)
+        report = []
+        y_o = OL.layer_forward_mixed(cfg, W, lo, om, to_np(c["x_in"])[rows], o_pool, {ft_req.seq_id: o_ft})
+        assert_close("y", to_np(c["x_out"])[rows], y_o, tol, report)
+        ft_d = cap["fts"][n]
+        for name in ("q_cache", "x2", "gate", "up", "attn", "lse"):
+            assert_close("saved " + name, to_np(getattr(ft_d, name))[w], getattr(o_ft, name)[w], tol, report)
+        sl = o_pool.slots(cpages[ft_req.seq_id], L)
+        grads = {}
+        dX_o = OL.layer_backward_window(cfg, W, lo, o_ft, o_pool.k[sl].astype(np.float64), o_pool.v[sl].astype(np.float64),
+                                        ft_req.start_pos, ft_req.n_new, to_np(c["dY"]), grads, need_dx=n > 0)
+        if n > 0:
+            assert_close("dX", to_np(c["dX"]), dX_o, tol, report)
+        assert_close("dk_accum", to_np(ft_d.dk_accum), o_ft.dk_accum, tol, report)
+        assert_close("dv_accum", to_np(ft_d.dv_accum), o_ft.dv_accum, tol, report)
+        gg = cap["layers"][n].grads_numpy()
+        for t in cfg.lora_targets:
+            assert_close(f"dA[{t}]", gg[t][0], grads[t][0], tol, report)
+            assert_close(f"dB[{t}]", gg[t][1], grads[t][1], tol, report)
+        say("  layer %d: " % n + ", ".join(f"{k}={e:.1e}" for k, e in report))
+    say("  iteration: %.1f ms (%d tokens, %d finetune), %.1f GB resident" % (
+        r["ms_per_iteration"], r["config"]["tokens"], r["config"]["finetune_tokens"], r["resident_gb"]["allocated"]))
+    del cap, r
+    import gc
+    import torch
+    gc.collect()
+    torch.cuda.empty_cache()
+
+
+def test_whole_model_iteration_8b_layers_sampled():
+    _layer_sampled_check("c3", 8)
+
+
+@pytest.mark.parametrize("model,share", [("c4", None), ("c4", 0.25), ("c4", 0.9), ("c5", None)])
+def test_whole_model_iteration_14b_32b_layers_sampled(model, share):
+    """The 14B-shaped (48 layers, 185 GB resident) and 32B-shaped (64 layers, 269 GB) models the same way; the
+    14B one also at the two ends of its inference-share sweep.  Minutes of set-up each: run on request,
+    FLEXCO_BIG_MODELS=1 python -m pytest tests/test_gpu_model_iter.py -m gpu -k 14b_32b -s"""
+    import os
+    if os.environ.get("FLEXCO_BIG_MODELS") != "1":
+        pytest.skip("set FLEXCO_BIG_MODELS=1 to build the 48- and 64-layer models")
+    _layer_sampled_check(model, 4, share)

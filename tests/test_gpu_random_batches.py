@@ -10,6 +10,9 @@ from test_gpu_parity import C1, SMALL_BF16, SMALL_BF16_G5, SMALL_BF16_MHA, SMALL
 
 pytestmark = pytest.mark.gpu
 
+# tensors that miss 2e-2 against the plain oracle and are held to 5e-3 against the storage-rounding oracle, per seed
+STORAGE_EXCEPTIONS = {}
+
 CFGS = [SMALL_BF16, SMALL_BF16_G5, SMALL_BF16_MHA, SMALL_BF16_G8, C1]
 
 
@@ -39,4 +42,4 @@ def test_random_mixed_batch(seed):
     say(f"random batch {seed}: {cfg.name}, {n_dec} decode, prefill {prefill}, finetune L={L} windows of {ft_window}, "
         f"backward {bwd}, split {split}, need_dx {need_dx}")
     run_layer_case(cfg, batch, ft_window=ft_window, prefill_chunk=int(g.integers(1, 80)), bwd_windows=bwd, seed=seed,
-                   split=split, need_dx=need_dx, tol_qk=4e-2 if cfg.dtype == "bf16" else None)
+                   split=split, need_dx=need_dx, storage_exceptions=STORAGE_EXCEPTIONS.get(seed, ()))

@@ -338,3 +338,127 @@ def test_lora_parameter_counts_match_paper():
     cfg = CONFIGS["c1_tiny_f32"]
     lw = gen.lora_weights(cfg, 0)
     assert lw["down"][0].shape == (cfg.ffn, cfg.lora_rank) and lw["down"][1].shape == (cfg.lora_rank, cfg.hidden)
+
+
+# ---- storage rounding mode -------------------------------------------------------------
+def test_round_bf16_is_the_format_rounding():
+    """hand values (spacing at 1.0 is 2^-7; ties go to the even significand) and the library's conversion"""
+    from oracle import ops
+    one = 1.0
+    hand = [(one, one), (one + 2.0 ** -8, one), (one + 3 * 2.0 ** -8, one + 2.0 ** -6), (one + 2.0 ** -7, one + 2.0 ** -7),
+            (one + 2.0 ** -8 + 2.0 ** -20, one + 2.0 ** -7), (-3.0 - 2.0 ** -7, -3.0), (-3.0 - 2.0 ** -6, -3.0 - 2.0 ** -6), (0.0, 0.0),
+            (2.0 - 2.0 ** -9, 2.0), (255.5, 256.0), (1e-3, 131.0 / 128.0 * 2.0 ** -10)]
+    for a, want in hand:
+        assert ops.round_bf16(np.array([a]))[0] == want, a
+    a = np.concatenate([RNG.standard_normal(20000) * s for s in (1e-6, 1e-2, 1.0, 77.0, 3e5)])
+    lib = torch.from_numpy(a.astype(np.float32)).to(torch.bfloat16).double().numpy()
+    assert np.array_equal(ops.round_bf16(a.astype(np.float32)).astype(np.float64), lib)
+    assert ops.round_bf16(a).dtype == np.float64          # the input's own type comes back
+    assert np.array_equal(ops.round_bf16(ops.round_bf16(a)), ops.round_bf16(a))     # idempotent
+
+
+def _token_level_once(cfg, W, lo, x, dY, fwd, bwd, storage):
+    """Alg. 2 for one sequence alone: forward windows, then backward windows from the end, with `storage`."""
+    n = x.shape[0]
+    pages = np.array([5, 0, 3, 1])
+    pool = L.KVPool(int(pages.max()) + 1, 4, cfg.kv_dim)
+    st = L.FtState(cfg, n)
+    y, l = np.zeros_like(x), 0
+    for s in fwd:
+        maps = build_maps([NS(kind=2, seq_id=0, start_pos=l, n_new=s, adapter=0)], {0: pages}, 4)
+        y[l:l + s] = L.layer_forward_mixed(cfg, W, lo, maps, x[l:l + s], pool, {0: st}, storage=storage)
+        l += s
+    grads, dx, l = {}, np.zeros_like(x), n
+    slots = pool.slots(pages, n)
+    for s in bwd:
+        dx[l - s:l] = L.layer_backward_window(cfg, W, lo, st, pool.k[slots[:l]], pool.v[slots[:l]], l - s, s,
+                                              dY[l - s:l], grads, storage=storage)
+        l -= s
+    return y, dx, grads, st, pool
+
+
+def test_storage_mode_none_and_identity_are_the_plain_method():
+    cfg = SMALL
+    W, lo = small_layer()
+    x, dY = seq_input(cfg, 14), RNG.standard_normal((14, cfg.hidden))
+    plain = _token_level_once(cfg, W, lo, x, dY, [5, 9], [4, 10], None)
+    ident = _token_level_once(cfg, W, lo, x, dY, [5, 9], [4, 10], lambda a: a)
+    f32 = _token_level_once(cfg, W, lo, x, dY, [5, 9], [4, 10], lambda a: np.asarray(a, dtype=np.float64))
+    for other in (ident, f32):
+        assert np.array_equal(plain[0], other[0]) and np.array_equal(plain[1], other[1])
+        for t in cfg.lora_targets:
+            assert np.array_equal(plain[2][t][0], other[2][t][0]) and np.array_equal(plain[2][t][1], other[2][t][1])
+    # and the plain method is the definition (so the switch did not disturb it)
+    dX_w, grads_w, _, _ = L.layer_backward_seq(cfg, W, lo, x, dY)
+    assert rel_err(plain[1], dX_w) < 1e-11
+    assert rel_err(plain[0], L.layer_forward_seq(cfg, W, lo, x)["y"]) < 1e-12
+
+
+def test_storage_mode_rounds_what_is_stored_and_stays_near_the_plain_method():
+    """Every tensor the state and the pool hold, and both results, are representable in the storage type;
+    accumulators are not rounded; the distance to the unrounded method is a small multiple of the
+    format's 2^-9 relative rounding (a layer output passes about ten roundings in sequence) - and not zero."""
+    from oracle import ops
+    cfg = SMALL
+    W, lo = small_layer()
+    rb = lambda a: ops.round_bf16(np.asarray(a, dtype=np.float64))
+    W = {k: rb(v) for k, v in W.items()}
+    lo = {t: (rb(A), rb(B)) for t, (A, B) in lo.items()}
+    x, dY = rb(seq_input(cfg, 14)), rb(RNG.standard_normal((14, cfg.hidden)))
+    y0, dx0, g0, st0, _ = _token_level_once(cfg, W, lo, x, dY, [5, 9], [4, 10], None)
+    y1, dx1, g1, st1, pool1 = _token_level_once(cfg, W, lo, x, dY, [5, 9], [4, 10], "bf16")
+    for name, t in (("y", y1), ("dx", dx1), ("q_cache", st1.q_cache), ("x2", st1.x2), ("gate", st1.gate), ("up", st1.up),
+                    ("attn", st1.attn), ("k", pool1.k), ("v", pool1.v)):
+        assert np.array_equal(rb(t), t), name
+    assert not np.array_equal(rb(st1.lse), st1.lse) and not np.array_equal(rb(st1.dk_accum), st1.dk_accum)
+    u = 2.0 ** -9
+    for name, a, b, k in (("y", y1, y0, 8), ("dx", dx1, dx0, 16), ("q_cache", st1.q_cache, st0.q_cache, 4),
+                          ("dk_accum", st1.dk_accum, st0.dk_accum, 16)):
+        e = rel_err(a, b)
+        assert 0.05 * u < e <= k * u, (name, e)
+    for t in cfg.lora_targets:
+        for i in (0, 1):
+            e = rel_err(g1[t][i], g0[t][i])
+            assert 0.0 < e <= 24 * u, (t, i, e)
+    # a callable does the same as the name
+    y2, dx2, _, _, _ = _token_level_once(cfg, W, lo, x, dY, [5, 9], [4, 10], rb)
+    assert np.array_equal(y2, y1) and np.array_equal(dx2, dx1)
+    # window splits no longer give bit-equal results (rounded intermediates), but stay as near
+    y3, dx3, _, _, _ = _token_level_once(cfg, W, lo, x, dY, [14], [14], "bf16")
+    assert rel_err(y3, y1) <= 8 * u and rel_err(dx3, dx1) <= 16 * u
+
+
+def test_bf16_storage_alone_misses_2e2_on_the_logit_path_of_the_short_14b_case():
+    """Evidence for the one exception of the GPU parity tests (the 14B / 32B shapes on <= 96 keys): the oracle with
+    EXACT fp64 arithmetic and bf16 storage is itself more than 2e-2 away from the unrounded oracle on the tensors
+    that depend on the gradient through the softmax logits, and well inside on all the others; and two such runs
+    that differ only in arithmetic precision (fp64 / fp32: both correct implementations of the same storage type)
+    already differ from each other by several 1e-3, which is why a device result cannot be held to the storage
+    oracle itself much tighter than to the plain one."""
+    from helpers import oracle_layer_case, oracle_layer_case_backward
+    from workload import CONFIGS
+    cfg = CONFIGS["c4_qwen14b_full"]
+    b0 = gen.batch_scaled(7, 6, 20, 300, [(0, 40, 40)], [(0, 48, 96)])
+    kw = dict(ft_window=48, prefill_chunk=40, bwd_windows=[60, 36])
+    plain, st = oracle_layer_case(cfg, b0, seed=2, **kw)
+    Ls = st[5]
+    _, dY = L.mse_loss_grad(plain["y_ft"], gen.loss_targets(cfg, 2, Ls).astype(np.float64))
+    dY = gen.storage_round(cfg, (dY * Ls * cfg.hidden).astype(np.float32)).astype(np.float64)
+    plain.update(oracle_layer_case_backward(cfg, b0, kw["bwd_windows"], 2, st, dY))
+    runs = {}
+    for label, dt in (("s64", np.float64), ("s32", np.float32)):
+        f, st = oracle_layer_case(cfg, b0, seed=2, storage="bf16", dtype=dt, **kw)
+        f.update(oracle_layer_case_backward(cfg, b0, kw["bwd_windows"], 2, st, dY, storage="bf16", dtype=dt))
+        runs[label] = f
+    logit_path = ("dX", "dk_accum", "dA[q]", "dB[q]", "dA[k]", "dB[k]")
+    for name in plain:
+        if name == "y_ft" or name == "saved x":
+            continue
+        e64 = rel_err(runs["s64"][name], plain[name])
+        e32_64 = rel_err(runs["s32"][name], runs["s64"][name])
+        if name in logit_path:
+            assert 2e-2 < e64 < 4e-2, (name, e64)
+        else:
+            assert e64 < 1e-2, (name, e64)
+        assert e32_64 < 1e-2, (name, e32_64)
+    assert max(rel_err(runs["s32"][n], runs["s64"][n]) for n in logit_path) > 2e-3

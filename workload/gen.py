@@ -239,13 +239,22 @@ def _whole_prompts(g, budget, lo=128, hi=1024):
     return prefill
 
 
-def batch_c4(seed=0) -> Batch:
-    """14B-shaped whole-model case, token budget 2048 at an inference share of 50 %: 512 decode tokens
-    (contexts log-normal, median 1024, sigma 0.8, clipped to 16..8192), 512 prefill tokens as whole prompts,
-    and the last 1024-token window of a 4096-token finetune sequence."""
-    g = rng(seed, "c4", "lengths")
-    ctx = _lognormal_lengths(g, 512, 1024, 0.8, 16, 8192)
-    return mixed_batch(16, seed, decode_ctx=ctx, prefill=_whole_prompts(g, 512), finetune=[(3072, 1024, 4096)])
+C4_SHARES = (0.25, 0.5, 0.75, 0.9)
+
+
+def batch_c4(seed=0, inference_share=0.5) -> Batch:
+    """14B-shaped whole-model case, token budget 2048 at an inference share of 25 / 50 / 75 / 90 %: the inference
+    tokens (512 / 1024 / 1536 / 1843) are half decode tokens (contexts log-normal, median 1024, sigma 0.8,
+    clipped to 16..8192) and half prefill tokens as whole prompts; the rest of the budget (1536 / 1024 / 512 /
+    205 tokens) is the last window of a 4096-token finetune sequence."""
+    budget, L = 2048, 4096
+    n_inf = int(budget * inference_share)
+    n_dec = n_inf // 2
+    n_ft = budget - n_inf
+    assert 0 < n_ft <= L and n_dec > 0
+    g = rng(seed, "c4", "lengths") if inference_share == 0.5 else rng(seed, "c4", "lengths", n_inf)
+    ctx = _lognormal_lengths(g, n_dec, 1024, 0.8, 16, 8192)
+    return mixed_batch(16, seed, decode_ctx=ctx, prefill=_whole_prompts(g, n_inf - n_dec), finetune=[(L - n_ft, n_ft, L)])
 
 
 def batch_c5(seed=0) -> Batch:
@@ -266,9 +275,12 @@ def batch_scaled(seed, n_decode, ctx_lo, ctx_hi, prefill, finetune, page_size=16
 
 def sample_requests(batch: Batch, n_decode: int):
     """A bounded sample of a batch's requests for checks the oracle runs one by one: the first
-    n_decode decode requests, the first prefill chunk and the finetune window."""
+    n_decode decode requests, the first and the last prefill request (the benchmark batch's two chunks: the one
+    without a cached prefix and the one behind 768 cached positions; in the whole-model batches a whole prompt
+    and the truncated last one) and the finetune window."""
     dec = [r for r in batch.requests if r.kind == KIND_DECODE][:n_decode]
-    pre = [r for r in batch.requests if r.kind == KIND_PREFILL][:1]
+    pre = [r for r in batch.requests if r.kind == KIND_PREFILL]
+    pre = pre[:1] + pre[-1:] if len(pre) > 1 else pre
     ftr = [r for r in batch.requests if r.kind == KIND_FINETUNE]
     return dec + pre + ftr
 
