@@ -146,6 +146,8 @@ typedef struct flexco_maps {
   int32_t blob_ints;                   /* int32 words used in the blob                    */
   int32_t n_adapters;                  /* 1 + the largest adapter id of the batch (0: none) */
   int32_t ft_adapter;                  /* adapter id of the finetune request (-1: none)   */
+  int32_t num_pages;                   /* pool size the page ids were checked against: a call that takes
+                                          these maps and a pool with fewer pages fails with FLEXCO_EPAGE */
   int32_t adapter_tok_off[FLEXCO_MAX_ADAPTERS + 1];   /* lora_tok[off[a] .. off[a+1]) = tokens of adapter a */
   const int32_t* tok_req;       /* [T]                                                    */
   const int32_t* tok_pos;       /* [T]                                                    */
@@ -312,7 +314,8 @@ int32_t flexco_lora_fwd_static(const void* x, void* y, int32_t T, int32_t in_fea
  * Window = rows [win_start, win_start + win_len) of the finetune sequence; windows of a
  * sequence must be visited from its end downwards.
  *   seq_pages : device int32 page ids of the sequence, n_seq_pages >= ceil(l / page_size),
- *               l = win_start + win_len
+ *               l = win_start + win_len; every id must lie in [0, pool->num_pages) - the array is
+ *               device memory, the call cannot check it
  *   ft        : the state the forward windows filled
  *   dY        : device [win_len, H] gradient of the layer output rows
  *   dX        : device [win_len, H] gradient of the layer input rows, or NULL when no
@@ -412,8 +415,9 @@ int32_t flexco_gemm(const void* A, const void* W, void* C, const void* bias, con
  * `kernel_id` on that launch's stream (the bf16 GEMM kernels carry the two events in their own
  * dispatch; at most max_launches launches, later ones are not timed).  flexco_kernel_timer_stop waits for the recorded events, returns the summed
  * duration in milliseconds and the number of timed launches, and releases the events.
- * Events are host-side runtime objects; no device memory is allocated.  Not thread-safe:
- * start / stop from the thread that issues the work. */
+ * Events are host-side runtime objects; no device memory is allocated.  The timer tables are
+ * guarded by a lock, so launches from several host threads do not corrupt them; a measurement is only
+ * meaningful when one thread issues the timed class (event pairs are handed out in arrival order). */
 #define FLEXCO_K_GEMM_FWD   0   /* bf16 MFMA projection, forward form              */
 #define FLEXCO_K_GEMM_BWD   1   /* bf16 MFMA projection, input-gradient form       */
 #define FLEXCO_K_ATTN_FWD   2   /* bf16 MFMA mixed paged attention (partials)      */
@@ -522,8 +526,8 @@ int32_t flexco_sched_advance(int32_t n_entries, const int32_t* req, const int32_
  * starts from.  Reading (the paper names neither head nor normalisation): next-token cross-entropy
  * through a final RMSNorm and an LM head,
  *     h = rmsnorm(x; g_final),  z = h w_lm^T,  loss_i = logsumexp(z_i) - z_i[targets_i],
- * over the rows with targets_i >= 0 (negative: the row has no next token and contributes neither
- * loss nor gradient), times `scale` (1 / tokens of the whole sequence makes the windows of a
+ * over the rows with 0 <= targets_i < vocab (any other value: the row has no next token and
+ * contributes neither loss nor gradient), times `scale` (1 / tokens of the whole sequence makes the windows of a
  * sequence add up to its mean loss). */
 typedef struct flexco_lm_head {
   int32_t hidden, vocab, dtype;   /* dtype: FLEXCO_F32 | FLEXCO_BF16 (storage of g_final, w_lm, x, dX) */

@@ -24,7 +24,8 @@ from . import ops
 
 def generative_loss(x, g, w_lm, targets, scale, eps):
     """x [n, H]: the window's rows of the last layer's output; g [H]; w_lm [V, H]; targets [n] int
-    (negative: row does not count).  Returns (loss, dx [n, H]) with loss = scale * sum_i loss_i."""
+    (a value outside [0, V): the row has no next token and does not count - the paper does not say how such rows
+    are marked).  Returns (loss, dx [n, H]) with loss = scale * sum_i loss_i."""
     targets = np.asarray(targets)
     h = ops.rmsnorm(x, g, eps)
     z = h @ w_lm.T
@@ -32,7 +33,7 @@ def generative_loss(x, g, w_lm, targets, scale, eps):
     e = np.exp(z - zmax)
     se = e.sum(axis=1, keepdims=True)
     lse = (zmax + np.log(se))[:, 0]
-    valid = targets >= 0
+    valid = (targets >= 0) & (targets < w_lm.shape[0])
     rows = np.nonzero(valid)[0]
     loss = scale * float(np.sum(lse[rows] - z[rows, targets[rows]]))
     dz = e / se                                  # softmax

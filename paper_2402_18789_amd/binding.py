@@ -12,6 +12,9 @@ import torch  # noqa: F401  loaded first: the library shares torch's HIP runtime
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("FLEXCO_LIB_PATH", os.path.join(_HERE, "libflexco.so"))
+# FLEXCO_HOST_ONLY=1: the library at FLEXCO_LIB_PATH is a build of the host sources alone (index maps, scheduler,
+# graph pruning; see build.py --host-sanitized): only the symbols it has are bound, calling a device entry point fails
+HOST_ONLY = os.environ.get("FLEXCO_HOST_ONLY") == "1"
 
 FLEXCO_OK, FLEXCO_EINVAL, FLEXCO_ESHAPE, FLEXCO_EWORKSPACE, FLEXCO_EPAGE, FLEXCO_EUNSUPPORTED, FLEXCO_EHIP = \
     0, -1, -2, -3, -4, -5, -6
@@ -20,7 +23,7 @@ FLEXCO_DECODE, FLEXCO_PREFILL, FLEXCO_FINETUNE = 0, 1, 2
 FLEXCO_REQ_WAITING, FLEXCO_REQ_RUNNING, FLEXCO_REQ_FINISHED = 0, 1, 2
 TARGET_NAMES = ("q", "k", "v", "o", "gate", "up", "down")
 N_TARGETS = 7
-ABI_VERSION = 4
+ABI_VERSION = 5
 
 
 class FlexcoError(RuntimeError):
@@ -50,7 +53,8 @@ class BatchDesc(C.Structure):
 
 
 _MAP_SCALARS = ("T", "n_req", "n_ft", "n_seg", "max_pages", "page_size", "n_tiles", "n_items", "n_parts",
-                "tile_tokens", "kv_split_pages", "ft_req", "ft_tok0", "ft_pos0", "n_lora", "max_kv_len", "blob_ints", "n_adapters", "ft_adapter")
+                "tile_tokens", "kv_split_pages", "ft_req", "ft_tok0", "ft_pos0", "n_lora", "max_kv_len", "blob_ints", "n_adapters", "ft_adapter",
+                "num_pages")
 _MAP_ARRAYS = ("tok_req", "tok_pos", "slot", "req_tok_off", "req_kv_len", "req_kind", "block_table", "ft_tok",
                "seg_off", "seg_adapter", "lora_tok", "tile_req", "tile_tok0", "tile_ntok", "tile_nsplit",
                "tile_part0", "item_tile", "item_split", "tok_tile", "tok_lora", "tok_adapter", "item_ntiles")
@@ -147,7 +151,11 @@ def _load():
         "flexco_adam_step": [vp, vp, vp, vp, vp, sz, i32, f32, f32, f32, f32, i32, vp],
     }
     for name, args in sigs.items():
-        fn = getattr(lib, name)
+        fn = getattr(lib, name, None)
+        if fn is None:
+            if HOST_ONLY:          # a build of the host sources alone has no device entry points
+                continue
+            raise ImportError("libflexco.so lacks the symbol %s" % name)
         fn.argtypes = args
         fn.restype = C.c_int32
     return lib

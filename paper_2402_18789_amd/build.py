@@ -49,5 +49,25 @@ def build(verbose=True):
     return LIB
 
 
+HOST_SOURCES = ["flexco_maps.cpp", "flexco_sched.cpp", "flexco_prune.cpp"]
+
+
+def build_host_sanitized(out_path):
+    """The host-only sources (index maps, scheduler, graph pruning) as a library of their own, compiled for the CPU
+    with AddressSanitizer and UndefinedBehaviorSanitizer (any finding aborts).  Load it with the sanitizer runtime
+    preloaded: LD_PRELOAD=$(g++ -print-file-name=libasan.so) FLEXCO_LIB_PATH=<out_path> FLEXCO_HOST_ONLY=1."""
+    cxx = os.environ.get("CXX", "g++")
+    cmd = [cxx, "-std=c++17", "-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+           "-fno-sanitize-recover=all", "-shared", "-fPIC", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC] + \
+          [os.path.join(CSRC, f) for f in HOST_SOURCES] + ["-o", out_path]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("host sanitized build failed:\n%s\n%s" % (r.stdout, r.stderr))
+    return out_path
+
+
 if __name__ == "__main__":
-    print(build())
+    if len(sys.argv) > 2 and sys.argv[1] == "--host-sanitized":
+        print(build_host_sanitized(sys.argv[2]))
+    else:
+        print(build())

@@ -27,8 +27,13 @@ struct KTimer {
   }
 };
 static KTimer g_timers[FLEXCO_N_KERNEL_IDS];
+// The timers are process-wide tables.  Launches may come from several host threads (one per stream), so every
+// access to a slot's counters goes through this lock; which launch gets which event pair is still decided in
+// arrival order, so a measurement is only meaningful when one thread issues the timed class.
+static std::mutex g_timer_mutex;
 
 KernelTimerScope::KernelTimerScope(int id_, hipStream_t s_) : id(id_), s(s_), slot(-1) {
+  std::lock_guard<std::mutex> lock(g_timer_mutex);
   KTimer& t = g_timers[id];
   if (t.begin_launch()) {
     slot = t.used++;
@@ -36,6 +41,7 @@ KernelTimerScope::KernelTimerScope(int id_, hipStream_t s_) : id(id_), s(s_), sl
   }
 }
 bool kernel_timer_pair(int id, hipEvent_t* start, hipEvent_t* stop, bool first_of_call) {
+  std::lock_guard<std::mutex> lock(g_timer_mutex);
   KTimer& t = g_timers[id];
   if (first_of_call) (void)t.begin_launch();
   if (!t.on || !t.take || 2 * (t.used + 1) > (int)t.ev.size()) return false;
@@ -45,7 +51,9 @@ bool kernel_timer_pair(int id, hipEvent_t* start, hipEvent_t* stop, bool first_o
   return true;
 }
 KernelTimerScope::~KernelTimerScope() {
-  if (slot >= 0) (void)hipEventRecord(g_timers[id].ev[2 * slot + 1], s);
+  if (slot < 0) return;
+  std::lock_guard<std::mutex> lock(g_timer_mutex);
+  if (g_timers[id].on && 2 * slot + 1 < (int)g_timers[id].ev.size()) (void)hipEventRecord(g_timers[id].ev[2 * slot + 1], s);
 }
 }  // namespace flexco
 
@@ -53,12 +61,17 @@ extern "C" int32_t flexco_kernel_timer_start(int32_t kernel_id, int32_t max_laun
   clear_error();
   FLEXCO_CHECK(kernel_id >= 0 && kernel_id < FLEXCO_N_KERNEL_IDS, FLEXCO_EINVAL, "unknown kernel id %d", kernel_id);
   FLEXCO_CHECK(max_launches > 0 && max_launches <= (1 << 20), FLEXCO_EINVAL, "max_launches out of range");
+  std::lock_guard<std::mutex> lock(g_timer_mutex);
   KTimer& t = g_timers[kernel_id];
   FLEXCO_CHECK(!t.on, FLEXCO_EINVAL, "timer %d is already running", kernel_id);
-  t.ev.resize(2 * (size_t)max_launches);
-  for (auto& e : t.ev) {
-    hipError_t rc = hipEventCreate(&e);
-    if (rc != hipSuccess) return fail(FLEXCO_EHIP, "hipEventCreate: %s", hipGetErrorString(rc));
+  t.ev.assign(2 * (size_t)max_launches, nullptr);
+  for (size_t i = 0; i < t.ev.size(); ++i) {
+    hipError_t rc = hipEventCreate(&t.ev[i]);
+    if (rc != hipSuccess) {                       // release what was created before giving up
+      for (size_t j = 0; j < i; ++j) (void)hipEventDestroy(t.ev[j]);
+      t.ev.clear();
+      return fail(FLEXCO_EHIP, "hipEventCreate: %s", hipGetErrorString(rc));
+    }
   }
   t.used = 0;
   t.launches = 0;
@@ -72,6 +85,7 @@ extern "C" int32_t flexco_kernel_timer_sample(int32_t kernel_id, int32_t stride)
   clear_error();
   FLEXCO_CHECK(kernel_id >= 0 && kernel_id < FLEXCO_N_KERNEL_IDS, FLEXCO_EINVAL, "unknown kernel id %d", kernel_id);
   FLEXCO_CHECK(stride >= 1, FLEXCO_EINVAL, "stride must be at least 1");
+  std::lock_guard<std::mutex> lock(g_timer_mutex);
   FLEXCO_CHECK(!g_timers[kernel_id].on, FLEXCO_EINVAL, "timer %d is running", kernel_id);
   g_timers[kernel_id].stride = stride;
   return FLEXCO_OK;
@@ -81,6 +95,7 @@ extern "C" int32_t flexco_kernel_timer_stop(int32_t kernel_id, double* total_ms,
   clear_error();
   FLEXCO_CHECK(kernel_id >= 0 && kernel_id < FLEXCO_N_KERNEL_IDS, FLEXCO_EINVAL, "unknown kernel id %d", kernel_id);
   FLEXCO_CHECK(total_ms && launches, FLEXCO_EINVAL, "NULL output");
+  std::lock_guard<std::mutex> lock(g_timer_mutex);
   KTimer& t = g_timers[kernel_id];
   FLEXCO_CHECK(t.on, FLEXCO_EINVAL, "timer %d is not running", kernel_id);
   double sum = 0.0;
@@ -300,6 +315,14 @@ int32_t check_maps(const flexco_layer_cfg& c, const flexco_maps* m) {
   FLEXCO_CHECK(m->tok_req && m->tok_pos && m->slot && m->block_table && m->tile_req && m->item_tile && m->tok_tile &&
                    m->tok_lora && m->tok_adapter && m->item_ntiles && m->item_split && m->tile_nsplit && m->tile_part0,
                FLEXCO_EINVAL, "maps hold a NULL array");
+  return FLEXCO_OK;
+}
+
+// the page ids inside the maps were validated against a pool of m.num_pages pages: a smaller pool would be
+// read and written past its end
+int32_t check_maps_pool(const flexco_maps& m, const flexco_kv_pool& p) {
+  FLEXCO_CHECK(m.num_pages <= p.num_pages, FLEXCO_EPAGE,
+               "maps were built for a pool of %d pages, the pool given has %d", m.num_pages, p.num_pages);
   return FLEXCO_OK;
 }
 
@@ -656,6 +679,7 @@ extern "C" int32_t flexco_attention_mixed(const flexco_layer_cfg* cfg, const fle
   FLEXCO_TRY(check_cfg(cfg));
   FLEXCO_TRY(check_maps(*cfg, maps));
   FLEXCO_TRY(check_pool(*cfg, pool));
+  FLEXCO_TRY(check_maps_pool(*maps, *pool));
   FLEXCO_CHECK(q && out && ws, FLEXCO_EINVAL, "q, out or ws is NULL");
   FLEXCO_CHECK(aligned16(q) && aligned16(out) && aligned16(ws) && aligned16(lse), FLEXCO_EINVAL, "misaligned pointer");
   const size_t prow = (size_t)maps->n_parts * cfg->n_kv_heads * cols_per_tile(*cfg);
@@ -765,6 +789,7 @@ static int32_t layer_forward_impl(const flexco_layer_cfg* cfg, const flexco_base
   FLEXCO_TRY(check_weights(w));
   FLEXCO_TRY(check_maps(*cfg, maps));
   FLEXCO_TRY(check_pool(*cfg, pool));
+  FLEXCO_TRY(check_maps_pool(*maps, *pool));
   const flexco_layer_cfg& c = *cfg;
   const flexco_maps& m = *maps;
   if (ia3) {

@@ -14,7 +14,7 @@
 #include <deque>
 #include <vector>
 
-#include "flexco_internal.h"
+#include "flexco_host.h"
 
 namespace flexco {
 namespace {

@@ -10,7 +10,7 @@
 // same order gets the same window.
 #include <cstring>
 
-#include "flexco_internal.h"
+#include "flexco_host.h"
 
 #pragma STDC FP_CONTRACT OFF
 

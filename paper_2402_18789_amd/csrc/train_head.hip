@@ -35,7 +35,8 @@ __global__ __launch_bounds__(CE_THREADS) void ce_rows_kernel(T* __restrict__ z, 
   __shared__ float red_m[CE_THREADS / 64], red_s[CE_THREADS / 64];
   __shared__ float lse_sh;
   T* zr = z + (size_t)blockIdx.x * V;
-  const int y = targets[blockIdx.x];
+  int y = targets[blockIdx.x];
+  if (y >= V) y = -1;                             // a target outside the vocabulary is treated as "no target"
   float m = -INFINITY, s = 0.f;
   for (int i = threadIdx.x * N; i < V; i += CE_THREADS * N) {
     float v[N];

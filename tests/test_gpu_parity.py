@@ -553,6 +553,16 @@ def test_error_paths_on_device():
     with pytest.raises(B.FlexcoError) as e:        # aliasing
         B.flexco_layer_forward(case.dev.c, case.dev.w, case.dev.lora, db.maps, x, x, case.d_pool.c, ft.c, ws.ptr, ws.bytes)
     assert e.value.code == B.FLEXCO_EINVAL
+    # maps whose page ids were checked against a larger pool than the one handed to the call
+    big = HH.DeviceBatch(C1, b.requests, b.seq_pages, b.num_pages + 5)
+    assert big.host_maps.num_pages == b.num_pages + 5 and db.host_maps.num_pages == b.num_pages
+    with pytest.raises(B.FlexcoError) as e:
+        B.flexco_layer_forward(case.dev.c, case.dev.w, case.dev.lora, big.maps, x, y, case.d_pool.c, ft.c, ws.ptr, ws.bytes)
+    assert e.value.code == B.FLEXCO_EPAGE
+    q = torch.zeros((68, C1.q_dim), device="cuda")
+    with pytest.raises(B.FlexcoError) as e:
+        B.flexco_attention_mixed(case.dev.c, big.maps, q, case.d_pool.c, torch.empty_like(q), None, ws.ptr, ws.bytes)
+    assert e.value.code == B.FLEXCO_EPAGE
     pages_d = torch.zeros(4, dtype=torch.int32, device="cuda")
     with pytest.raises(B.FlexcoError) as e:        # window beyond the sequence
         B.flexco_lora_bwd(case.dev.c, case.dev.w, case.dev.lora, case.d_pool.c, pages_d, 4, ft.c, 60, 10, x, y,

@@ -25,8 +25,8 @@ def run_loss(dtype, n, H, V, seed, ignore=()):
     gain = gen.storage_round(cfg, (1.0 + 0.05 * g.standard_normal(H)).astype(np.float32))
     w = gen.storage_round(cfg, (0.05 * g.standard_normal((V, H))).astype(np.float32))
     y = g.integers(0, V, n).astype(np.int32)
-    for i in ignore:
-        y[i] = -1
+    for k, i in enumerate(ignore):
+        y[i] = -1 if k % 2 == 0 else V + k        # no next token: negative, or outside the vocabulary
     scale = 1.0 / (n + 3)
     loss_o, dx_o = OT.generative_loss(x.astype(np.float64), gain.astype(np.float64), w.astype(np.float64), y, scale, 1e-5)
     dt = HH.TORCH_DTYPE[dtype]

@@ -53,6 +53,19 @@ def test_loss_is_the_textbook_cross_entropy_and_additive_over_windows():
     assert np.allclose(np.vstack([dxa, dxb]), dx, rtol=1e-12, atol=0)
 
 
+def test_rows_with_a_target_outside_the_vocabulary_do_not_count():
+    x, gain, w, y = setup(4, n=9)
+    V = w.shape[0]
+    keep = np.array([0, 2, 3, 5, 8])
+    y2 = y.copy()
+    y2[1], y2[4], y2[6], y2[7] = -1, V, V + 1000, -7
+    got, dx = T.generative_loss(x, gain, w, y2, 0.2, 1e-5)
+    want, dxk = T.generative_loss(x[keep], gain, w, y[keep], 0.2, 1e-5)      # rows are independent: drop them instead
+    assert got == pytest.approx(want, rel=1e-12)
+    assert np.allclose(dx[keep], dxk, rtol=1e-12, atol=0)
+    assert np.all(dx[[1, 4, 6, 7]] == 0.0)
+
+
 def test_loss_is_stable_for_large_logits():
     x, gain, w, y = setup(3)
     loss, dx = T.generative_loss(x, gain, 400.0 * w, y, 1.0, 1e-5)

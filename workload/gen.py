@@ -244,8 +244,8 @@ C4_SHARES = (0.25, 0.5, 0.75, 0.9)
 
 def batch_c4(seed=0, inference_share=0.5) -> Batch:
     """14B-shaped whole-model case, token budget 2048 at an inference share of 25 / 50 / 75 / 90 %: the inference
-    tokens (512 / 1024 / 1536 / 1843) are half decode tokens (contexts log-normal, median 1024, sigma 0.8,
-    clipped to 16..8192) and half prefill tokens as whole prompts; the rest of the budget (1536 / 1024 / 512 /
+    tokens (512 / 1024 / 1536 / 1843) are half decode tokens (contexts log-normal, median 1024 - 768 at 90 % -,
+    sigma 0.8, clipped to 16..8192) and half prefill tokens as whole prompts; the rest of the budget (1536 / 1024 / 512 /
     205 tokens) is the last window of a 4096-token finetune sequence."""
     budget, L = 2048, 4096
     n_inf = int(budget * inference_share)
@@ -253,7 +253,10 @@ def batch_c4(seed=0, inference_share=0.5) -> Batch:
     n_ft = budget - n_inf
     assert 0 < n_ft <= L and n_dec > 0
     g = rng(seed, "c4", "lengths") if inference_share == 0.5 else rng(seed, "c4", "lengths", n_inf)
-    ctx = _lognormal_lengths(g, n_dec, 1024, 0.8, 16, 8192)
+    # 921 decode requests at the law's median of 1024 would hold 1.3 M cached positions: 254 GB of cache over the
+    # model's 48 layers, more than one GPU has beside the weights; the 90 % point takes a median of 768
+    median = 1024 if n_dec <= 768 else 768
+    ctx = _lognormal_lengths(g, n_dec, median, 0.8, 16, 8192)
     return mixed_batch(16, seed, decode_ctx=ctx, prefill=_whole_prompts(g, n_inf - n_dec), finetune=[(L - n_ft, n_ft, L)])
 
 
