@@ -212,9 +212,17 @@ def main():
     ms_per_step = (wall_ms if args.overlap else max(wall_ms, gpu_ms)) / args.steps
     value = T / (ms_per_step * 1e-3)
 
-    work = algorithmic_work(cfg, batch, hm)
+    work = algorithmic_work(cfg, batch, hm, db.numpy())
     roofline = roofline_entry(dominant, dom_ms / max(1, dom_timed), float(dom_per_step), work)
     roofline["timed_launches"] = dom_timed
+    # the projections are as large a share of the step as the dominant kernel: their class figures beside it
+    for gk in ("gemm_fwd", "gemm_bwd"):
+        if probe.get(gk, (0, 0))[1] > 0:
+            ge = roofline_entry(gk, probe[gk][0] / probe[gk][1], probe[gk][1], work)
+            roofline["also_" + gk] = {"bound": ge["bound"], "achieved": ge["achieved"], "peak": ge["peak"], "unit": ge["unit"],
+                                      "frac": ge["frac"], "ms_per_step": round(probe[gk][0], 4)}
+            if "weight_stream_frac_of_hbm" in ge:
+                roofline["also_" + gk]["weight_stream_frac_of_hbm"] = ge["weight_stream_frac_of_hbm"]
     roofline["timing"] = "HIP events on every %d-th launch of the class inside the timed region" % stride
     classes = {}
     for name, (ms, n) in probe.items():
@@ -222,6 +230,8 @@ def main():
             e = roofline_entry(name, ms / n, n, work)
             classes[name] = {"ms_per_step": round(ms, 4), "launches_per_step": n, "achieved": e["achieved"],
                              "unit": e["unit"], "frac": e["frac"], "bound": e["bound"]}
+            if "weight_stream_frac_of_hbm" in e:
+                classes[name]["weight_stream_frac_of_hbm"] = e["weight_stream_frac_of_hbm"]
     out = {
         "metric": "co-served tokens/s per layer iteration",
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -242,6 +252,7 @@ def main():
     if per_step:
         out["ms_per_step_median"] = float(np.median(per_step))
         out["ms_per_step_min"] = float(np.min(per_step))
+    out["forward_projections"] = per_projection(B, torch, step_serial, cfg, T)
     out["measured_ceilings"] = measured_ceilings(B, torch)
     if not args.overlap and not args.no_two_stream:
         # the same K steps again with the window backward on a second stream (reported beside the
@@ -261,6 +272,36 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, batch, sample, W, lora, seed, x_np, ft_req, L, ia3_np)
     print(json.dumps(out), flush=True)
+
+
+def per_projection(B, torch, step_serial, cfg, T):
+    """The four forward projections one by one (three extra steps with an event pair on every launch of the class;
+    a projection whose tile plan is two launches is the sum of both)."""
+    kid = B.KERNEL_IDS["gemm_fwd"]
+    steps = 3
+    B.flexco_kernel_timer_sample(kid, 1)
+    B.flexco_kernel_timer_start(kid, 16 * steps)
+    for i in range(steps):
+        step_serial(i)
+    torch.cuda.synchronize()
+    each = B.flexco_kernel_timer_read(kid)
+    _, calls = B.flexco_kernel_timer_stop(kid)
+    per_step = len(each) // steps
+    H, F, qd, kd = cfg.hidden, cfg.ffn, cfg.q_dim, cfg.kv_dim
+    names = [("qkv", (qd + 2 * kd) * H), ("o", qd * H), ("gate_up", 2 * F * H), ("down", F * H)]
+    if calls != 4 * steps or per_step < 4 or len(each) != per_step * steps:
+        return {"note": "unexpected launch pattern: %d pairs for %d calls" % (len(each), calls)}
+    # the calls come in the order qkv, o, gate/up, down; extra pairs of a step belong to the widest projection
+    # (gate/up), whose plan is the one that splits into two launches at this size
+    extra = per_step - 4
+    out = {}
+    for k, (name, p) in enumerate(names):
+        lo = k if k < 2 else (2 if k == 2 else 3 + extra)
+        hi = lo + (1 + extra if k == 2 else 1)
+        ms = sum(sum(each[st * per_step + j] for j in range(lo, hi)) for st in range(steps)) / steps
+        tf = 2.0 * p * T / (ms * 1e-3) / 1e12
+        out[name] = {"ms": round(ms, 4), "launches": hi - lo, "achieved": tf, "unit": "TFLOP/s", "frac": tf / MFMA_BF16_PEAK_TFLOPS}
+    return out
 
 
 def measured_ceilings(B, torch):
@@ -284,6 +325,16 @@ def measured_ceilings(B, torch):
         torch.cuda.synchronize()
         if rep:
             best_read = max(best_read, nbytes / (ev0.elapsed_time(ev1) * 1e-3) / 1e9)
+    # the matrix cores fed from LDS as the projection kernels feed them (no global traffic, no barriers)
+    best_lds = {128: 0.0, 256: 0.0}
+    for tile in (128, 256):
+        for rep in range(3):
+            ev0.record()
+            flops = B.flexco_probe_mfma_lds(256, 4000 if tile == 128 else 1000, tile, sink)
+            ev1.record()
+            torch.cuda.synchronize()
+            if rep:
+                best_lds[tile] = max(best_lds[tile], flops / (ev0.elapsed_time(ev1) * 1e-3) / 1e12)
     # plain device-to-device copy of 1 GiB (read + write counted)
     src, dst = buf[:1 << 30], buf[1 << 30:2 << 30]
     best_copy = 0.0
@@ -295,31 +346,65 @@ def measured_ceilings(B, torch):
         if rep:
             best_copy = max(best_copy, 2.0 * (1 << 30) / (ev0.elapsed_time(ev1) * 1e-3) / 1e9)
     del src, dst, buf
-    return {"mfma_bf16_loop_tflops": best_mfma, "hbm_read_stream_gbs": best_read, "device_copy_gbs": best_copy,
+    return {"mfma_bf16_loop_tflops": best_mfma, "mfma_bf16_lds_operands_tile128_tflops": best_lds[128],
+            "mfma_bf16_lds_operands_tile256_tflops": best_lds[256], "hbm_read_stream_gbs": best_read,
+            "device_copy_gbs": best_copy,
             "what": "probe kernels of the library: 256 blocks x 4 wavefronts of back-to-back v_mfma_f32_32x32x16_bf16 on "
-                    "register operands in [-1, 1); 2048 blocks streaming 4 GiB with 16-byte loads; a 1 GiB device-to-device "
+                    "register operands in [-1, 1); the same products with operands read from LDS in the projection "
+                    "kernels' pattern for a 128 x 128 and a 256 x 256 block tile (no global traffic, no barriers); "
+                    "2048 blocks streaming 4 GiB with 16-byte loads; a 1 GiB device-to-device "
                     "copy (bytes read + bytes written)"}
 
 
-def algorithmic_work(cfg, batch, hm):
-    """Algorithmic flops / bytes per STEP of each kernel class (what the method must do)."""
-    H, F = cfg.hidden, cfg.ffn
-    qd, kd = cfg.q_dim, cfg.kv_dim
-    T, n_ft = hm.T, hm.n_ft
+def algorithmic_work(cfg, batch, hm, maps_np=None):
+    """Algorithmic flops / bytes per STEP of each kernel class: what the method must move or multiply, in the
+    storage type (2 bytes; 4 for the fp32 accumulators and log-sum-exp), each operand of each operator read or
+    written once - not what this implementation's split-K partial sums or by-products add."""
+    H, F, r = cfg.hidden, cfg.ffn, cfg.lora_rank
+    qd, kd, nq = cfg.q_dim, cfg.kv_dim, cfg.n_q_heads
+    T, n = hm.T, hm.n_ft
+    e = 2
     p_base = (qd + 2 * kd) * H + qd * H + 3 * H * F
     # attention forward: every cached position a request sees is read once, K row + V row of every kv head
-    kv_bytes = sum((r.start_pos + r.n_new) * 2 * kd * 2 for r in batch.requests)
-    ftr = [r for r in batch.requests if r.kind == 2]
+    kv_bytes = sum((q.start_pos + q.n_new) * 2 * kd * e for q in batch.requests)
+    ftr = [q for q in batch.requests if q.kind == 2]
     bwd_flops = 0.0
-    for r in ftr:
-        s, l = r.n_new, r.start_pos + r.n_new
-        vis = s * (l - s) + s * (s + 1) / 2
-        bwd_flops += 10.0 * cfg.n_q_heads * cfg.head_dim * vis
+    for q in ftr:
+        s_, l = q.n_new, q.start_pos + q.n_new
+        vis = s_ * (l - s_) + s_ * (s_ + 1) / 2
+        bwd_flops += 10.0 * nq * cfg.head_dim * vis
+    # row-wise operators (norms, rotation + cache append, SwiGLU backward, rotation backward, norm backwards)
+    fwd_rows = (2 * T * H + n * H) * e                      # norm 1: x in, h out, the window's x rows kept
+    fwd_rows += (2 * T * (qd + 2 * kd) + n * qd) * e        # rotation: q, k, v in; q, K / V pages out; Q cache rows
+    fwd_rows += (2 * T * H + n * H) * e                     # norm 2: x2 in, h2 out, the window's x2 rows kept
+    bwd_rows = (3 * n * F + 2 * n * F + n * F) * e          # SwiGLU backward: gate, up, d(act) in; d(gate), d(up), act out
+    bwd_rows += (3 * n * H + 2 * n * H) * e                 # norm 2 backward: x2, d(h2), dY in; d(x2), h2 out
+    bwd_rows += n * qd * e + 2 * n * kd * 4 + n * (qd + 2 * kd) * e     # rotation backward: dQ, the accumulators' rows in; dq, dk, dv out
+    bwd_rows += (3 * n * H + 2 * n * H) * e                 # norm 1 backward: x, d(h1), d(x2) in; dX, h1 out
+    # the bypass networks: every target reads its input rows and (backward) its output-gradient rows twice
+    # (rank-r product, then the two weight-gradient products), plus the r-wide matrices
+    dims = {"q": (H, qd), "k": (H, kd), "v": (H, kd), "o": (qd, H), "gate": (H, F), "up": (H, F), "down": (F, H)}
+    lora_b = 0.0
+    for t in cfg.lora_targets:
+        i_, o_ = dims[t]
+        lora_b += (hm.n_lora * i_ + r * i_) * e                            # forward: x rows and A
+        lora_b += (2 * n * i_ + 2 * n * o_ + 2 * r * (i_ + o_)) * e         # backward: x, dy rows (twice), A, B
+        lora_b += 2 * r * (i_ + o_) * 4                                     # dA, dB read-modify-write (fp32)
+    # split merge: the partial rows of the tiles whose key range was cut, the output rows and log-sum-exp
+    merge_b = (T * qd * e + T * nq * 4)
+    if maps_np is not None:
+        cut = maps_np["tile_nsplit"][maps_np["tile_nsplit"] > 1]
+        group = nq // cfg.n_kv_heads
+        cols = max(1, 16 // group) * group
+        merge_b += float(cut.sum()) * cfg.n_kv_heads * cols * (cfg.head_dim + 2) * 4
     return {
         "gemm_fwd": ("mfma", 2.0 * p_base * T),
-        "gemm_bwd": ("mfma", 2.0 * p_base * n_ft),
+        "gemm_bwd": ("mfma", 2.0 * p_base * n),
         "attn_fwd": ("hbm", float(kv_bytes)),
         "attn_bwd": ("mfma", bwd_flops),
+        "elemwise": ("hbm", float(fwd_rows + bwd_rows)),
+        "lora": ("hbm", float(lora_b)),
+        "attn_merge": ("hbm", float(merge_b)),
         "weights_bytes": 2.0 * p_base,
     }
 
@@ -398,8 +483,8 @@ def cpu_baseline(cfg, batch, sample, W, lora, seed, x_np, ft_req, L, ia3=None):
         reps += 1
     log("cpu baseline: %d passes, forward %.1fs, backward %.1fs, total incl. setup %.1fs" % (reps, t_f, t_b, time.time() - t_all))
     return {"value": reps * len(rows) / (t_f + t_b), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": "%d of 1024 tokens (%d decode requests, one 256-token prefill chunk, the 256-token finetune "
-                      "window): forward + that window's backward, %d passes; numpy fp64" % (len(rows), len(sample) - 2, reps),
+            "sample": "%d of 1024 tokens (%d decode requests, the two 256-token prefill chunks, the 256-token finetune "
+                      "window): forward + that window's backward, %d passes; numpy fp64" % (len(rows), len(sample) - 3, reps),
             "seconds": t_f + t_b, "host_cpus": os.cpu_count()}
 
 

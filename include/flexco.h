@@ -429,6 +429,10 @@ int32_t flexco_gemm(const void* A, const void* W, void* C, const void* bias, con
 #define FLEXCO_N_KERNEL_IDS 8
 int32_t flexco_kernel_timer_start(int32_t kernel_id, int32_t max_launches);
 int32_t flexco_kernel_timer_stop(int32_t kernel_id, double* total_ms, int64_t* launches);
+/* Before stop: waits for the event pairs recorded so far and writes their durations in milliseconds, in issue
+ * order, to ms_each[0 .. min(*n, capacity)); *n = pairs recorded (a call that issues several kernels of the
+ * class - a projection whose tile plan is two launches - records one pair per kernel). */
+int32_t flexco_kernel_timer_read(int32_t kernel_id, double* ms_each, int64_t capacity, int64_t* n);
 /* From the next start on, only every stride-th launch of the class is timed (1, the initial
  * setting: all of them); stop then returns the sum and the count of the timed launches.  A timed
  * launch holds its neighbours on the stream apart by a few microseconds, which a caller that also
@@ -562,8 +566,13 @@ int32_t flexco_adam_step(void* param, float* master, const float* grad, float* m
  *   flexco_probe_mfma: `blocks` blocks of 4 wavefronts, each `iters` x 16 back-to-back
  *     v_mfma_f32_32x32x16_bf16 on register operands with values in [-1, 1); *flops = work enqueued.
  *   flexco_probe_read: `blocks` blocks each stream their own contiguous piece of src[0, bytes) with
- *     16-byte loads; *bytes_read = bytes actually read (bytes rounded down to whole rounds). */
+ *     16-byte loads; *bytes_read = bytes actually read (bytes rounded down to whole rounds).
+ *   flexco_probe_mfma_lds: the same products with the operands fetched from LDS as the projection kernels fetch
+ *     them (tile = 128: 2 x 2 wavefronts on a 128 x 128 tile, where the LDS reads take as long as the products;
+ *     tile = 256: a 256 x 256 tile, half as long); `iters` 64-column stages per wavefront, no global memory
+ *     traffic, no barriers. */
 int32_t flexco_probe_mfma(int32_t blocks, int32_t iters, void* sink, double* flops, void* stream);
+int32_t flexco_probe_mfma_lds(int32_t blocks, int32_t iters, int32_t tile, void* sink, double* flops, void* stream);
 int32_t flexco_probe_read(const void* src, size_t bytes, int32_t blocks, void* sink, double* bytes_read,
                           void* stream);
 

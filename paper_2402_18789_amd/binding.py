@@ -140,6 +140,8 @@ def _load():
         "flexco_kernel_timer_start": [i32, i32],
         "flexco_kernel_timer_stop": [i32, P(C.c_double), P(C.c_int64)],
         "flexco_kernel_timer_sample": [i32, i32],
+        "flexco_kernel_timer_read": [i32, P(C.c_double), C.c_int64, P(C.c_int64)],
+        "flexco_probe_mfma_lds": [i32, i32, i32, vp, P(C.c_double), vp],
         "flexco_probe_mfma": [i32, i32, vp, P(C.c_double), vp],
         "flexco_probe_read": [vp, sz, i32, vp, P(C.c_double), vp],
         "flexco_latency_estimate": [P(LatencyModel), i32, i32, P(C.c_double)],
@@ -165,7 +167,7 @@ _lib = _load()
 EXPORTS = ("flexco_last_error", "flexco_abi_version", "flexco_maps_blob_ints", "flexco_build_maps",
            "flexco_maps_rebase", "flexco_workspace_bytes", "flexco_layer_forward", "flexco_layer_forward_multi", "flexco_attention_mixed",
            "flexco_lora_fwd", "flexco_lora_fwd_static", "flexco_lora_bwd", "flexco_attention_window_bwd", "flexco_gemm",
-           "flexco_kernel_timer_start", "flexco_kernel_timer_stop", "flexco_kernel_timer_sample", "flexco_probe_mfma", "flexco_probe_read",
+           "flexco_kernel_timer_start", "flexco_kernel_timer_stop", "flexco_kernel_timer_sample", "flexco_kernel_timer_read", "flexco_probe_mfma", "flexco_probe_mfma_lds", "flexco_probe_read",
            "flexco_latency_estimate", "flexco_sched_window", "flexco_sched_inference", "flexco_sched_advance",
            "flexco_lm_loss_workspace_bytes", "flexco_lm_loss", "flexco_adam_step", "flexco_prune_graph",
            "flexco_layer_forward_ia3", "flexco_ia3_bwd", "flexco_adapter_workspace_bytes", "flexco_adapter_fwd",
@@ -363,6 +365,13 @@ def flexco_probe_mfma(blocks, iters, sink, stream=None):
     return fl.value
 
 
+def flexco_probe_mfma_lds(blocks, iters, tile, sink, stream=None):
+    """-> flops enqueued"""
+    fl = C.c_double(0.0)
+    _check(_lib.flexco_probe_mfma_lds(blocks, iters, tile, _ptr(sink), C.byref(fl), _stream(stream)))
+    return fl.value
+
+
 def flexco_probe_read(src, nbytes, blocks, sink, stream=None):
     """-> bytes the kernel reads"""
     nb = C.c_double(0.0)
@@ -449,6 +458,14 @@ def flexco_kernel_timer_start(kernel_id, max_launches):
 
 def flexco_kernel_timer_sample(kernel_id, stride):
     _check(_lib.flexco_kernel_timer_sample(kernel_id, stride))
+
+
+def flexco_kernel_timer_read(kernel_id, capacity=4096):
+    """-> list of the durations (ms) of the event pairs recorded so far, in issue order"""
+    buf = (C.c_double * capacity)()
+    n = C.c_int64(0)
+    _check(_lib.flexco_kernel_timer_read(kernel_id, buf, capacity, C.byref(n)))
+    return [buf[i] for i in range(min(n.value, capacity))]
 
 
 def flexco_kernel_timer_stop(kernel_id):

@@ -91,6 +91,24 @@ extern "C" int32_t flexco_kernel_timer_sample(int32_t kernel_id, int32_t stride)
   return FLEXCO_OK;
 }
 
+extern "C" int32_t flexco_kernel_timer_read(int32_t kernel_id, double* ms_each, int64_t capacity, int64_t* n) {
+  clear_error();
+  FLEXCO_CHECK(kernel_id >= 0 && kernel_id < FLEXCO_N_KERNEL_IDS, FLEXCO_EINVAL, "unknown kernel id %d", kernel_id);
+  FLEXCO_CHECK(ms_each && n && capacity >= 0, FLEXCO_EINVAL, "NULL output or negative capacity");
+  std::lock_guard<std::mutex> lock(g_timer_mutex);
+  KTimer& t = g_timers[kernel_id];
+  FLEXCO_CHECK(t.on, FLEXCO_EINVAL, "timer %d is not running", kernel_id);
+  *n = t.used;
+  for (int i = 0; i < t.used && i < capacity; ++i) {
+    float ms = 0.f;
+    hipError_t rc = hipEventSynchronize(t.ev[2 * i + 1]);
+    if (rc == hipSuccess) rc = hipEventElapsedTime(&ms, t.ev[2 * i], t.ev[2 * i + 1]);
+    if (rc != hipSuccess) return fail(FLEXCO_EHIP, "event timing: %s", hipGetErrorString(rc));
+    ms_each[i] = ms;
+  }
+  return FLEXCO_OK;
+}
+
 extern "C" int32_t flexco_kernel_timer_stop(int32_t kernel_id, double* total_ms, int64_t* launches) {
   clear_error();
   FLEXCO_CHECK(kernel_id >= 0 && kernel_id < FLEXCO_N_KERNEL_IDS, FLEXCO_EINVAL, "unknown kernel id %d", kernel_id);

@@ -46,6 +46,59 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, float* sink)
   if (s == 12345.678f) sink[0] = s;   // keeps the loop; never true in practice
 }
 
+// The same products with their operands fetched from LDS the way the projection kernels fetch them: a block of
+// 4 wavefronts (2 x 2) owns a (64 MT) x (64 NT) tile, LDS holds one 64-column stage of both operand tiles (128-byte
+// rows, 16-byte chunks XOR-swizzled by row), and every 16-column slice costs a wavefront MT + NT ds_read_b128 for
+// MT x NT products.  No global memory traffic and no barriers inside the loop: what the matrix cores sustain when
+// LDS feeds them (MT = NT = 2: the 128 x 128 tile, LDS reads as long as the products; 4: the 256 x 256 tile, half).
+template <int MT, int NT>
+__global__ __launch_bounds__(256) void probe_mfma_lds_kernel(int iters, float* sink) {
+  constexpr int BM = 64 * MT, BN = 64 * NT;
+  __shared__ __attribute__((aligned(1024))) bf16_t tile[(BM + BN) * 64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  for (int i = tid; i < (BM + BN) * 64; i += 256) {
+    const unsigned h = (unsigned)i * 2654435761u;
+    tile[i] = (bf16_t)((float)(h >> 8 & 0xffff) / 32768.f - 1.f);
+  }
+  __syncthreads();
+  const int wm0 = (wave >> 1) * 32 * MT, wn0 = (wave & 1) * 32 * NT;
+  const int l32 = lane & 31, kg = lane >> 5;
+  f32x16 acc[MT][NT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      bf16x8 af[MT], bf[NT];
+#pragma unroll
+      for (int i = 0; i < MT; ++i) {
+        const int r = wm0 + i * 32 + l32;
+        af[i] = *reinterpret_cast<const bf16x8*>(tile + r * 64 + (((kk * 2 + kg) ^ ((r >> 1) & 7)) * 8));
+      }
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        const int r = wn0 + j * 32 + l32;
+        bf[j] = *reinterpret_cast<const bf16x8*>(tile + (BM + r) * 64 + (((kk * 2 + kg) ^ ((r >> 1) & 7)) * 8));
+      }
+#pragma unroll
+      for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[j], af[i], acc[i][j], 0, 0, 0);
+    }
+    asm volatile("" ::: "memory");      // the fragments are read again in every iteration
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j) s += acc[i][j][0];
+  if (s == 12345.678f) sink[0] = s;
+}
+
 // every block streams its own contiguous piece with 16-byte loads, 8 in flight per lane
 __global__ __launch_bounds__(256) void probe_read_kernel(const u32x4* __restrict__ src, size_t vec_per_block,
                                                          unsigned* sink) {
@@ -74,6 +127,22 @@ extern "C" int32_t flexco_probe_mfma(int32_t blocks, int32_t iters, void* sink, 
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(FLEXCO_EHIP, "launch of probe_mfma failed: %s", hipGetErrorString(e));
   *flops = (double)blocks * 4.0 * iters * 16.0 * (2.0 * 32 * 32 * 16);
+  return FLEXCO_OK;
+}
+
+extern "C" int32_t flexco_probe_mfma_lds(int32_t blocks, int32_t iters, int32_t tile, void* sink, double* flops,
+                                         void* stream) {
+  clear_error();
+  FLEXCO_CHECK(blocks > 0 && iters > 0 && sink && flops, FLEXCO_EINVAL, "probe_mfma_lds: bad argument");
+  FLEXCO_CHECK(tile == 128 || tile == 256, FLEXCO_EINVAL, "probe_mfma_lds: tile must be 128 or 256");
+  if (tile == 128)
+    hipLaunchKernelGGL((probe_mfma_lds_kernel<2, 2>), dim3(blocks), dim3(256), 0, (hipStream_t)stream, iters, (float*)sink);
+  else
+    hipLaunchKernelGGL((probe_mfma_lds_kernel<4, 4>), dim3(blocks), dim3(256), 0, (hipStream_t)stream, iters, (float*)sink);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(FLEXCO_EHIP, "launch of probe_mfma_lds failed: %s", hipGetErrorString(e));
+  const double per_slice = (tile == 128 ? 4.0 : 16.0) * (2.0 * 32 * 32 * 16);
+  *flops = (double)blocks * 4.0 * iters * 4.0 * per_slice;
   return FLEXCO_OK;
 }
 
