@@ -559,6 +559,35 @@ int32_t flexco_adam_step(void* param, float* master, const float* grad, float* m
                          int32_t dtype, float lr, float beta1, float beta2, float eps, int32_t step,
                          void* stream);
 
+/* ---- A whole model in one call (Alg. 2: its Forward and Backward loops over the layers) -------------
+ * One layer's device objects.  lora: NULL when the configuration has no LoRA targets.  ft: the finetune
+ * sequence's state in this layer (NULL only for flexco_model_forward on a batch without a finetune request). */
+typedef struct flexco_model_layer {
+  flexco_base_weights    w;
+  const flexco_lora*     lora;
+  flexco_kv_pool         pool;
+  const flexco_ft_state* ft;
+} flexco_model_layer;
+
+/* flexco_layer_forward through layers[0 .. n_layers) in order, all with the same configuration and the same
+ * batch (maps).  x_in: device [T, H], not modified; x_out: device [T, H], the last layer's output; x_tmp: device
+ * [T, H], scratch for the layers in between (may be NULL when n_layers == 1); the three must be distinct.
+ * ws as for one layer (the layers run one after the other on `stream`).  Errors: those of flexco_layer_forward;
+ * a failing layer stops the call (earlier layers' work stays enqueued). */
+int32_t flexco_model_forward(const flexco_layer_cfg* cfg, const flexco_model_layer* layers, int32_t n_layers,
+                             const flexco_maps* maps, const void* x_in, void* x_out, void* x_tmp, void* ws,
+                             size_t ws_bytes, void* stream);
+
+/* flexco_lora_bwd of one window through layers[n_layers - 1] down to layers[0].  dY: device [win_len, H], the
+ * gradient of the top layer's output rows on entry; dY and d_tmp (device [win_len, H]) are used in turn for the
+ * gradients handed down, so dY is overwritten.  need_dx0 == 0: the bottom layer computes no input gradient
+ * (nothing trainable below it).  *dx0_out (host, may be NULL) receives the buffer (dY or d_tmp) that holds the
+ * bottom layer's input gradient, or NULL.  Errors: those of flexco_lora_bwd. */
+int32_t flexco_model_backward(const flexco_layer_cfg* cfg, const flexco_model_layer* layers, int32_t n_layers,
+                              const int32_t* seq_pages, int32_t n_seq_pages, int32_t win_start, int32_t win_len,
+                              void* dY, void* d_tmp, int32_t need_dx0, void** dx0_out, void* ws, size_t ws_bytes,
+                              void* stream);
+
 /* Machine-ceiling probes for the benchmark (they compute nothing of the method): what this GPU
  * sustains for the two resources the rooflines are quoted against.  Both only enqueue one kernel
  * on `stream`; the caller times it with events.  sink: device, >= 4 bytes, never written in

@@ -96,6 +96,10 @@ TENSOR_ACTIVATION, TENSOR_FROZEN, TENSOR_TRAINABLE = 0, 1, 2
 KEEP_NONE, KEEP_STORE, KEEP_REMAT, KEEP_BITMASK = 0, 1, 2, 3
 
 
+class ModelLayer(C.Structure):
+    _fields_ = [("w", BaseWeights), ("lora", C.c_void_p), ("pool", KVPool), ("ft", C.c_void_p)]
+
+
 class LmHead(C.Structure):
     _fields_ = [("hidden", C.c_int32), ("vocab", C.c_int32), ("dtype", C.c_int32), ("rms_eps", C.c_float),
                 ("g_final", C.c_void_p), ("w_lm", C.c_void_p)]
@@ -139,6 +143,8 @@ def _load():
         "flexco_prune_graph": [P(Graph), vp],
         "flexco_kernel_timer_start": [i32, i32],
         "flexco_kernel_timer_stop": [i32, P(C.c_double), P(C.c_int64)],
+        "flexco_model_forward": [P(LayerCfg), P(ModelLayer), i32, P(Maps), vp, vp, vp, vp, sz, vp],
+        "flexco_model_backward": [P(LayerCfg), P(ModelLayer), i32, vp, i32, i32, i32, vp, vp, i32, P(vp), vp, sz, vp],
         "flexco_kernel_timer_sample": [i32, i32],
         "flexco_kernel_timer_read": [i32, P(C.c_double), C.c_int64, P(C.c_int64)],
         "flexco_probe_mfma_lds": [i32, i32, i32, vp, P(C.c_double), vp],
@@ -171,7 +177,7 @@ EXPORTS = ("flexco_last_error", "flexco_abi_version", "flexco_maps_blob_ints", "
            "flexco_latency_estimate", "flexco_sched_window", "flexco_sched_inference", "flexco_sched_advance",
            "flexco_lm_loss_workspace_bytes", "flexco_lm_loss", "flexco_adam_step", "flexco_prune_graph",
            "flexco_layer_forward_ia3", "flexco_ia3_bwd", "flexco_adapter_workspace_bytes", "flexco_adapter_fwd",
-           "flexco_adapter_bwd")
+           "flexco_adapter_bwd", "flexco_model_forward", "flexco_model_backward")
 KERNEL_IDS = {"gemm_fwd": 0, "gemm_bwd": 1, "attn_fwd": 2, "attn_merge": 3, "attn_bwd": 4, "elemwise": 5, "lora": 6,
               "generic": 7}
 
@@ -458,6 +464,41 @@ def flexco_kernel_timer_start(kernel_id, max_launches):
 
 def flexco_kernel_timer_sample(kernel_id, stride):
     _check(_lib.flexco_kernel_timer_sample(kernel_id, stride))
+
+
+def target_dims_py(cfg, t):
+    """(in_features, out_features) of LoRA target t for a workload LayerCfg (marshalling helper: buffer sizes)"""
+    qd, kd = cfg.n_q_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim
+    return {"q": (cfg.hidden, qd), "k": (cfg.hidden, kd), "v": (cfg.hidden, kd), "o": (qd, cfg.hidden),
+            "gate": (cfg.hidden, cfg.ffn), "up": (cfg.hidden, cfg.ffn), "down": (cfg.ffn, cfg.hidden)}[t]
+
+
+def make_model_layers(layers):
+    """layers: list of (BaseWeights, Lora or None, KVPool, FtState or None) -> (ctypes array, keep-alive list)"""
+    arr = (ModelLayer * len(layers))()
+    keep = []
+    for i, (w, lora, pool, ft) in enumerate(layers):
+        arr[i].w = w
+        arr[i].lora = C.cast(C.pointer(lora), C.c_void_p) if lora is not None else None
+        arr[i].pool = pool
+        arr[i].ft = C.cast(C.pointer(ft), C.c_void_p) if ft is not None else None
+        keep.append((w, lora, pool, ft))
+    return arr, keep
+
+
+def flexco_model_forward(cfg, layers_arr, n_layers, maps, x_in, x_out, x_tmp, ws, ws_bytes, stream=None):
+    _check(_lib.flexco_model_forward(C.byref(cfg), layers_arr, n_layers, C.byref(maps), _ptr(x_in), _ptr(x_out), _ptr(x_tmp),
+                                     _ptr(ws), ws_bytes, _stream(stream)))
+
+
+def flexco_model_backward(cfg, layers_arr, n_layers, seq_pages, n_seq_pages, win_start, win_len, dY, d_tmp, need_dx0, ws,
+                          ws_bytes, stream=None):
+    """-> device address of the buffer (dY or d_tmp) holding the bottom layer's input gradient, or None"""
+    out = C.c_void_p(0)
+    _check(_lib.flexco_model_backward(C.byref(cfg), layers_arr, n_layers, _ptr(seq_pages), n_seq_pages, win_start, win_len,
+                                      _ptr(dY), _ptr(d_tmp), int(bool(need_dx0)), C.byref(out), _ptr(ws), ws_bytes,
+                                      _stream(stream)))
+    return out.value
 
 
 def flexco_kernel_timer_read(kernel_id, capacity=4096):

@@ -1277,3 +1277,51 @@ extern "C" int32_t flexco_adapter_bwd(int32_t dtype, int32_t hidden, const flexc
   return launch_lora_bwd(x_w, hidden, dY, hidden, ad->w_down, ad->w_up, ad->dw_down, ad->dw_up, dY, hidden, u, t, n, hidden,
                          hidden, b, 1.f, dtype, s, true);
 }
+
+// ---- all layers of a model in one call ---------------------------------------------------------------
+// The loops of Alg. 2 over the layers (its Forward loop and its Backward loop for one window), on the host side
+// of the boundary: one call enqueues every layer's kernels, so a caller's per-layer loop - and whatever its
+// language costs per call - is gone.  Every layer is validated before the first launch of its own pass.
+extern "C" int32_t flexco_model_forward(const flexco_layer_cfg* cfg, const flexco_model_layer* layers, int32_t n_layers,
+                                        const flexco_maps* maps, const void* x_in, void* x_out, void* x_tmp, void* ws,
+                                        size_t ws_bytes, void* stream) {
+  clear_error();
+  FLEXCO_CHECK(layers != nullptr && n_layers > 0, FLEXCO_EINVAL, "no layers");
+  FLEXCO_CHECK(x_in && x_out, FLEXCO_EINVAL, "x_in or x_out is NULL");
+  FLEXCO_CHECK(n_layers == 1 || x_tmp, FLEXCO_EINVAL, "more than one layer needs the second activation buffer x_tmp");
+  FLEXCO_CHECK(x_tmp != x_out && x_tmp != x_in && x_in != x_out, FLEXCO_EINVAL, "x_in, x_out and x_tmp must be three buffers");
+  // layer i writes x_out when the number of layers after it is even, so that the last one does
+  const void* src = x_in;
+  for (int i = 0; i < n_layers; ++i) {
+    void* dst = ((n_layers - 1 - i) % 2 == 0) ? x_out : x_tmp;
+    const flexco_model_layer& l = layers[i];
+    const Adapters ad{l.lora, l.lora ? 1 : 0, true};
+    const int32_t rc = layer_forward_impl(cfg, &l.w, ad, maps, src, dst, &l.pool, l.ft, ws, ws_bytes, stream);
+    if (rc != FLEXCO_OK) return rc;
+    src = dst;
+  }
+  return FLEXCO_OK;
+}
+
+extern "C" int32_t flexco_model_backward(const flexco_layer_cfg* cfg, const flexco_model_layer* layers, int32_t n_layers,
+                                         const int32_t* seq_pages, int32_t n_seq_pages, int32_t win_start, int32_t win_len,
+                                         void* dY, void* d_tmp, int32_t need_dx0, void** dx0_out, void* ws, size_t ws_bytes,
+                                         void* stream) {
+  clear_error();
+  FLEXCO_CHECK(layers != nullptr && n_layers > 0, FLEXCO_EINVAL, "no layers");
+  FLEXCO_CHECK(dY && d_tmp && dY != d_tmp, FLEXCO_EINVAL, "dY and d_tmp must be two buffers");
+  void* cur = dY;
+  void* nxt = d_tmp;
+  for (int i = n_layers - 1; i >= 0; --i) {
+    const flexco_model_layer& l = layers[i];
+    FLEXCO_CHECK(l.ft != nullptr, FLEXCO_EINVAL, "layer %d has no finetune state", i);
+    void* dx = (i > 0 || need_dx0) ? nxt : nullptr;       // nothing trainable below the bottom layer (Alg. 1)
+    const int32_t rc = layer_backward_impl(cfg, &l.w, l.lora, nullptr, &l.pool, seq_pages, n_seq_pages, l.ft, win_start,
+                                           win_len, cur, dx, ws, ws_bytes, stream);
+    if (rc != FLEXCO_OK) return rc;
+    if (dx) { void* t = cur; cur = nxt; nxt = t; }
+  }
+  if (dx0_out) *dx0_out = need_dx0 ? cur : nullptr;
+  return FLEXCO_OK;
+}
+

@@ -25,21 +25,59 @@ def _dev(a, dtype, device):
     return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device=device, dtype=dtype).contiguous()
 
 
+class ParamArena:
+    """One flat parameter buffer and one flat gradient buffer for the bypass matrices of many layers, so that an
+    optimizer step over all of them is a single flexco_adam_step call (and zeroing the gradients a single fill).
+    Pieces are handed out 16-byte aligned (the library's alignment rule for every matrix)."""
+
+    def __init__(self, n_elems, dtype, device="cuda"):
+        self.param = torch.zeros(n_elems, dtype=dtype, device=device)
+        self.grad = torch.zeros(n_elems, dtype=torch.float32, device=device)
+        self.used = 0
+
+    @staticmethod
+    def padded(n):
+        return (n + 7) // 8 * 8            # 8 bf16 elements = 16 bytes; keeps the fp32 pieces aligned as well
+
+    def take(self, shape):
+        n = int(np.prod(shape))
+        o = self.used
+        assert o + n <= self.param.numel(), "parameter arena is full"
+        self.used = o + self.padded(n)
+        return self.param[o:o + n].view(*shape), self.grad[o:o + n].view(*shape)
+
+
+def lora_param_elems(cfg):
+    """elements (padded per matrix) one adapter of this configuration takes in a ParamArena"""
+    n = 0
+    for t in cfg.lora_targets:
+        i_, o_ = B.target_dims_py(cfg, t)
+        n += ParamArena.padded(cfg.lora_rank * i_) + ParamArena.padded(o_ * cfg.lora_rank)
+    return n
+
+
 class DeviceLora:
     """One LoRA adapter and its gradient buffers on the GPU.  lora: {target: (A [in, r], B [r, out])} in the
-    paper's orientation (stored transposed: A [r, in], B [out, r])."""
+    paper's orientation (stored transposed: A [r, in], B [out, r]).  arena: a ParamArena the matrices and their
+    gradients are carved from instead of tensors of their own."""
 
-    def __init__(self, cfg, lora, device="cuda"):
+    def __init__(self, cfg, lora, device="cuda", arena=None):
         dt = TORCH_DTYPE[cfg.dtype]
         self.c = B.Lora()
         self.A, self.Bm, self.dA, self.dB = {}, {}, {}, {}
         for t in cfg.lora_targets:
             i = B.TARGET_NAMES.index(t)
             A, Bm = lora[t]
-            self.A[t] = _dev(np.ascontiguousarray(A.T), dt, device)      # [r, in]
-            self.Bm[t] = _dev(np.ascontiguousarray(Bm.T), dt, device)    # [out, r]
-            self.dA[t] = torch.zeros(self.A[t].shape, dtype=torch.float32, device=device)
-            self.dB[t] = torch.zeros(self.Bm[t].shape, dtype=torch.float32, device=device)
+            if arena is None:
+                self.A[t] = _dev(np.ascontiguousarray(A.T), dt, device)      # [r, in]
+                self.Bm[t] = _dev(np.ascontiguousarray(Bm.T), dt, device)    # [out, r]
+                self.dA[t] = torch.zeros(self.A[t].shape, dtype=torch.float32, device=device)
+                self.dB[t] = torch.zeros(self.Bm[t].shape, dtype=torch.float32, device=device)
+            else:
+                self.A[t], self.dA[t] = arena.take(A.T.shape)
+                self.Bm[t], self.dB[t] = arena.take(Bm.T.shape)
+                self.A[t].copy_(_dev(np.ascontiguousarray(A.T), dt, device))
+                self.Bm[t].copy_(_dev(np.ascontiguousarray(Bm.T), dt, device))
             self.c.A[i], self.c.B[i] = self.A[t].data_ptr(), self.Bm[t].data_ptr()
             self.c.dA[i], self.c.dB[i] = self.dA[t].data_ptr(), self.dB[t].data_ptr()
 
@@ -64,7 +102,7 @@ class DeviceLayer:
     W: {wq, wk, wv, wo, wg, wu, wd [out, in], g1, g2, optional bq, bk, bv};
     lora: {target: (A [in, r], B [r, out])} in the paper's orientation (stored transposed)."""
 
-    def __init__(self, cfg, W, lora=None, device="cuda"):
+    def __init__(self, cfg, W, lora=None, device="cuda", arena=None):
         self.cfg = cfg
         self.c = c_cfg(cfg)
         dt = TORCH_DTYPE[cfg.dtype]
@@ -84,7 +122,7 @@ class DeviceLayer:
         self.lora = None
         self.A, self.Bm, self.dA, self.dB = {}, {}, {}, {}
         if lora and cfg.lora_targets:
-            dl = DeviceLora(cfg, lora, device)
+            dl = DeviceLora(cfg, lora, device, arena)
             self.lora, self.A, self.Bm, self.dA, self.dB = dl.c, dl.A, dl.Bm, dl.dA, dl.dB
 
     def zero_grads(self):

@@ -47,11 +47,13 @@ def build(cfg, batch, n_layers, vocab, seed, host_seeded_layers=(), sample=()):
     ft_req = [r for r in batch.requests if r.kind == 2][0]
     L = batch.seq_capacity[ft_req.seq_id]
     layers, pools, fts = [], [], []
+    # every bypass matrix of the model and its gradient in two flat buffers: one Adam launch, one gradient fill
+    arena = HH.ParamArena(n_layers * HH.lora_param_elems(cfg), dt) if cfg.lora_targets else None
     for n in range(n_layers):
         if n > 0 and n in host_seeded_layers:
-            ly = HH.DeviceLayer(cfg, gen.layer_weights(cfg, seed, n), gen.lora_weights(cfg, seed, n))
+            ly = HH.DeviceLayer(cfg, gen.layer_weights(cfg, seed, n), gen.lora_weights(cfg, seed, n), arena=arena)
         else:
-            ly = HH.DeviceLayer(cfg, W, lora)
+            ly = HH.DeviceLayer(cfg, W, lora, arena=arena)
         if n > 0 and n not in host_seeded_layers:
             for name in ("wqkv", "wo", "wgu", "wd"):
                 t = ly.t[name]
@@ -72,7 +74,7 @@ def build(cfg, batch, n_layers, vocab, seed, host_seeded_layers=(), sample=()):
         print("  layer %d of %d resident (%.1f GB allocated)" % (n + 1, n_layers, torch.cuda.memory_allocated() / 1e9), flush=True)
     gain = torch.ones(cfg.hidden, device="cuda", dtype=dt)
     w_lm = (0.02 * torch.randn((vocab, cfg.hidden), generator=g, device="cuda", dtype=torch.float32)).to(dt)
-    return layers, pools, fts, gain, w_lm, ft_req, L
+    return layers, pools, fts, gain, w_lm, ft_req, L, arena
 
 
 def run(n_layers=None, steps=5, warmup=2, seed=0, vocab=None, model="c3", inference_share=None, capture_layers=(),
@@ -87,7 +89,7 @@ def run(n_layers=None, steps=5, warmup=2, seed=0, vocab=None, model="c3", infere
     vocab = vocab or model_vocab
     batch = make_batch(seed) if inference_share is None else make_batch(seed, inference_share)
     dt = HH.TORCH_DTYPE[cfg.dtype]
-    layers, pools, fts, gain, w_lm, ft_req, L = build(cfg, batch, n_layers, vocab, seed, tuple(capture_layers), sample)
+    layers, pools, fts, gain, w_lm, ft_req, L, arena = build(cfg, batch, n_layers, vocab, seed, tuple(capture_layers), sample)
     captured = {n: {} for n in capture_layers}
     db = HH.DeviceBatch(cfg, batch.requests, batch.seq_pages, batch.num_pages)
     hm = db.host_maps
@@ -106,38 +108,53 @@ def run(n_layers=None, steps=5, warmup=2, seed=0, vocab=None, model="c3", infere
     pages = torch.from_numpy(np.asarray(batch.seq_pages[ft_req.seq_id], dtype=np.int32)).to("cuda")
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
 
+    # the library's own loop over the layers (one call per pass); with capture_layers the per-layer calls, so that
+    # a layer's input and output can be copied in between
+    model_arr, model_keep = B.make_model_layers([(layers[n].w, layers[n].lora, pools[n].c, fts[n].c) for n in range(n_layers)])
+
     def reset():
         # the window's accumulator rows start from zero (a sequence's last window: nothing above it), and
         # so do the gradients; the caller's business between iterations, outside the timed bracket
         for ft in fts:
             ft.zero_accum()
-        for ly in layers:
-            ly.zero_grads()
+        if arena is not None:
+            arena.grad.zero_()
+        else:
+            for ly in layers:
+                ly.zero_grads()
         loss.zero_()
 
     def iteration(timed):
         if timed:
             ev[0].record()
-        src = x0
-        for n in range(n_layers):
-            dst = xa if n % 2 == 0 else xb
-            B.flexco_layer_forward(layers[n].c, layers[n].w, layers[n].lora, db.maps, src, dst, pools[n].c, fts[n].c, ws.ptr, ws.bytes)
-            if timed and n in captured:
-                captured[n]["x_in"], captured[n]["x_out"] = src.clone(), dst.clone()
-            src = dst
+        if captured:
+            src = x0
+            for n in range(n_layers):
+                dst = xa if n % 2 == 0 else xb
+                B.flexco_layer_forward(layers[n].c, layers[n].w, layers[n].lora, db.maps, src, dst, pools[n].c, fts[n].c, ws.ptr, ws.bytes)
+                if timed and n in captured:
+                    captured[n]["x_in"], captured[n]["x_out"] = src.clone(), dst.clone()
+                src = dst
+        else:
+            B.flexco_model_forward(layers[0].c, model_arr, n_layers, db.maps, x0, xa, xb, ws.ptr, ws.bytes)
+            src = xa
         if timed:
             ev[1].record()
         top = src[ft_off:ft_off + n_ft]
         B.flexco_lm_loss(head, top, targets, n_ft, 1.0 / L, loss, da, hws, hb)
         if timed:
             ev[2].record()
-        dcur, dnext = da, dbuf
-        for n in range(n_layers - 1, -1, -1):
-            B.flexco_lora_bwd(layers[n].c, layers[n].w, layers[n].lora, pools[n].c, pages, len(pages), fts[n].c,
-                              ft_req.start_pos, ft_req.n_new, dcur, dnext if n > 0 else None, ws.ptr, ws.bytes)
-            if timed and n in captured:
-                captured[n]["dY"], captured[n]["dX"] = dcur.clone(), (dnext.clone() if n > 0 else None)
-            dcur, dnext = dnext, dcur
+        if captured:
+            dcur, dnext = da, dbuf
+            for n in range(n_layers - 1, -1, -1):
+                B.flexco_lora_bwd(layers[n].c, layers[n].w, layers[n].lora, pools[n].c, pages, len(pages), fts[n].c,
+                                  ft_req.start_pos, ft_req.n_new, dcur, dnext if n > 0 else None, ws.ptr, ws.bytes)
+                if timed and n in captured:
+                    captured[n]["dY"], captured[n]["dX"] = dcur.clone(), (dnext.clone() if n > 0 else None)
+                dcur, dnext = dnext, dcur
+        else:
+            B.flexco_model_backward(layers[0].c, model_arr, n_layers, pages, len(pages), ft_req.start_pos, ft_req.n_new, da,
+                                    dbuf, False, ws.ptr, ws.bytes)
         if timed:
             ev[3].record()
         return src
@@ -160,20 +177,20 @@ def run(n_layers=None, steps=5, warmup=2, seed=0, vocab=None, model="c3", infere
     finite = bool(torch.isfinite(out.float()).all().item()) and bool(torch.isfinite(loss).item())
     grad_norm = float(sum(layers[n].dB[t].double().pow(2).sum().item() for n in range(n_layers) for t in cfg.lora_targets) ** 0.5)
 
-    # Adam over every bypass matrix (fp32 master copies of the bf16 parameters), once per sequence
-    state = []
-    for ly in layers:
-        for t in cfg.lora_targets:
-            for P, G in ((ly.A[t], ly.dA[t]), (ly.Bm[t], ly.dB[t])):
-                state.append((P, P.float().clone(), G, torch.zeros_like(G), torch.zeros_like(G)))
-    adam_ms = []
-    for k in range(3):
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for P, M, G, m, v in state:
-            B.flexco_adam_step(P, M, G, m, v, P.numel(), HH.DTYPE_CODE[cfg.dtype], 1e-4, 0.9, 0.999, 1e-8, k + 1)
-        torch.cuda.synchronize()
-        adam_ms.append((time.perf_counter() - t0) * 1e3)
+    # Adam over every bypass matrix of the model (fp32 master copy of the bf16 parameters), once per sequence:
+    # one call over the flat parameter buffer
+    adam_ms, adam_launches = [], 0
+    if arena is not None:
+        n_par = arena.used
+        master = arena.param[:n_par].float()
+        m1, m2 = torch.zeros(n_par, dtype=torch.float32, device="cuda"), torch.zeros(n_par, dtype=torch.float32, device="cuda")
+        for k in range(3):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            B.flexco_adam_step(arena.param, master, arena.grad, m1, m2, n_par, HH.DTYPE_CODE[cfg.dtype], 1e-4, 0.9, 0.999, 1e-8, k + 1)
+            torch.cuda.synchronize()
+            adam_ms.append((time.perf_counter() - t0) * 1e3)
+        adam_launches = 1
     positions = int(sum(r.start_pos + r.n_new for r in batch.requests))
     p_layer = (cfg.q_dim + 2 * cfg.kv_dim) * cfg.hidden + cfg.q_dim * cfg.hidden + 3 * cfg.hidden * cfg.ffn
     extra = {}
@@ -189,7 +206,8 @@ def run(n_layers=None, steps=5, warmup=2, seed=0, vocab=None, model="c3", infere
         "ms_per_iteration": ms, "tokens_per_s": T / ms * 1e3, "finetune_tokens_per_s": n_ft / ms * 1e3,
         "forward_ms": float(ph[0]), "loss_head_ms": float(ph[1]), "backward_ms": float(ph[2]),
         "ms_per_layer": (float(ph[0]) + float(ph[2])) / n_layers,
-        "adam_ms_once_per_sequence": float(np.median(adam_ms)), "adam_launches": len(state),
+        "adam_ms_once_per_sequence": float(np.median(adam_ms)) if adam_ms else 0.0, "adam_launches": adam_launches,
+        "layer_loop": "per-layer calls (capture)" if captured else "flexco_model_forward / flexco_model_backward",
         "resident_gb": {"weights": n_layers * p_layer * 2 / 1e9, "kv_pools": n_layers * batch.num_pages * cfg.page_size * 2 * cfg.kv_dim * 2 / 1e9,
                         "allocated": torch.cuda.memory_allocated() / 1e9},
         "loss": float(loss.item()), "lora_grad_norm_dB": grad_norm, "finite": finite,

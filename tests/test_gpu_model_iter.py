@@ -233,3 +233,120 @@ def test_whole_model_iteration_14b_32b_layers_sampled(model, share):
     if os.environ.get("FLEXCO_BIG_MODELS") != "1":
         pytest.skip("set FLEXCO_BIG_MODELS=1 to build the 48- and 64-layer models")
     _layer_sampled_check(model, 4, share)
+
+
+def test_library_layer_loop_equals_per_layer_calls():
+    """flexco_model_forward / flexco_model_backward (the loops over the layers inside the library, odd and even
+    numbers of layers, with and without an input gradient below the bottom layer) leave bit for bit what the
+    same layers called one by one leave."""
+    import numpy as np
+    import torch
+    import paper_2402_18789_amd.binding as B
+    from paper_2402_18789_amd import host as HH
+    from workload import gen, CONFIGS
+    cfg = CONFIGS["c2_llama8b_layer"].with_(name="small_bf16", hidden=512, n_q_heads=8, n_kv_heads=2, head_dim=128, ffn=1408)
+    seed = 5
+    batch = gen.batch_scaled(seed, 9, 20, 500, [(0, 100, 100), (128, 64, 300)], [(64, 96, 160)])
+    ft_req = [r for r in batch.requests if r.kind == 2][0]
+    L = batch.seq_capacity[ft_req.seq_id]
+    db = HH.DeviceBatch(cfg, batch.requests, batch.seq_pages, batch.num_pages)
+    hm = db.host_maps
+    x = torch.from_numpy(gen.layer_input(cfg, seed, hm.T)).to("cuda", torch.bfloat16)
+    dY0 = torch.from_numpy(gen.layer_input(cfg, seed, ft_req.n_new, tag="dy")).to("cuda", torch.bfloat16)
+    pages = torch.from_numpy(np.asarray(batch.seq_pages[ft_req.seq_id], dtype=np.int32)).to("cuda")
+    for N, need_dx0 in ((1, True), (2, False), (3, True)):
+        say("library layer loop, %d layers, bottom input gradient %s" % (N, need_dx0))
+        arena = HH.ParamArena(N * HH.lora_param_elems(cfg), torch.bfloat16)
+
+        def fresh():
+            ls = [HH.DeviceLayer(cfg, gen.layer_weights(cfg, seed, n), gen.lora_weights(cfg, seed, n)) for n in range(N)]
+            ps = [HH.DevicePool(cfg, batch.num_pages) for _ in range(N)]
+            for n, p in enumerate(ps):
+                p.fill_random(seed + n)
+            fs = [HH.DeviceFtState(cfg, L) for _ in range(N)]
+            return ls, ps, fs
+        ws = HH.Workspace(HH.c_cfg(cfg), hm.T, hm.n_parts, ft_req.n_new, L)
+        # one by one
+        ls, ps, fs = fresh()
+        cur = x
+        for n in range(N):
+            out = torch.empty_like(x)
+            B.flexco_layer_forward(ls[n].c, ls[n].w, ls[n].lora, db.maps, cur, out, ps[n].c, fs[n].c, ws.ptr, ws.bytes)
+            cur = out
+        y_ref = cur.clone()
+        d = dY0.clone()
+        for n in range(N - 1, -1, -1):
+            dx = torch.empty_like(d) if (n > 0 or need_dx0) else None
+            B.flexco_lora_bwd(ls[n].c, ls[n].w, ls[n].lora, ps[n].c, pages, len(pages), fs[n].c, ft_req.start_pos, ft_req.n_new,
+                              d, dx, ws.ptr, ws.bytes)
+            d = dx if dx is not None else d
+        torch.cuda.synchronize()
+        dx_ref = d.clone() if need_dx0 else None
+        # the library's loops
+        ls2, ps2, fs2 = fresh()
+        arr, keep = B.make_model_layers([(ls2[n].w, ls2[n].lora, ps2[n].c, fs2[n].c) for n in range(N)])
+        y2, tmp = torch.empty_like(x), torch.empty_like(x)
+        B.flexco_model_forward(ls2[0].c, arr, N, db.maps, x, y2, tmp if N > 1 else None, ws.ptr, ws.bytes)
+        dY, dtmp = dY0.clone(), torch.empty_like(dY0)
+        where = B.flexco_model_backward(ls2[0].c, arr, N, pages, len(pages), ft_req.start_pos, ft_req.n_new, dY, dtmp, need_dx0,
+                                        ws.ptr, ws.bytes)
+        torch.cuda.synchronize()
+        assert torch.equal(y2, y_ref)
+        if need_dx0:
+            assert where in (dY.data_ptr(), dtmp.data_ptr())
+            assert torch.equal(dY if where == dY.data_ptr() else dtmp, dx_ref)
+        else:
+            assert where is None
+        for n in range(N):
+            for t in cfg.lora_targets:
+                assert torch.equal(ls2[n].dA[t], ls[n].dA[t]) and torch.equal(ls2[n].dB[t], ls[n].dB[t]), (n, t)
+            assert torch.equal(fs2[n].dk_accum, fs[n].dk_accum) and torch.equal(fs2[n].q_cache, fs[n].q_cache)
+            assert torch.equal(ps2[n].k, ps[n].k) and torch.equal(ps2[n].v, ps[n].v)
+        del arena
+    # error paths: no layers; one buffer given twice
+    with pytest.raises(B.FlexcoError):
+        B.flexco_model_forward(ls2[0].c, arr, 0, db.maps, x, y2, tmp, ws.ptr, ws.bytes)
+    with pytest.raises(B.FlexcoError):
+        B.flexco_model_forward(ls2[0].c, arr, N, db.maps, x, y2, y2, ws.ptr, ws.bytes)
+    with pytest.raises(B.FlexcoError):
+        B.flexco_model_backward(ls2[0].c, arr, N, pages, len(pages), ft_req.start_pos, ft_req.n_new, dY, dY, True, ws.ptr, ws.bytes)
+
+
+def test_adam_over_one_flat_parameter_buffer_equals_per_matrix_steps():
+    """The bypass matrices of several layers carved from one flat buffer and updated by ONE flexco_adam_step call
+    end up bit for bit where per-matrix calls put them."""
+    import torch
+    import paper_2402_18789_amd.binding as B
+    from paper_2402_18789_amd import host as HH
+    from workload import gen, CONFIGS
+    cfg = CONFIGS["c2_llama8b_layer"].with_(name="small_bf16", hidden=512, n_q_heads=8, n_kv_heads=2, head_dim=128, ffn=1408,
+                                           lora_rank=24)      # 24-row matrices: pieces that need their padding
+    N = 3
+    arena = HH.ParamArena(N * HH.lora_param_elems(cfg), torch.bfloat16)
+    flat = [HH.DeviceLora(cfg, gen.lora_weights(cfg, 2, n), arena=arena) for n in range(N)]
+    sep = [HH.DeviceLora(cfg, gen.lora_weights(cfg, 2, n)) for n in range(N)]
+    assert arena.used == arena.param.numel()
+    g = torch.Generator(device="cuda")
+    g.manual_seed(1)
+    for a, b in zip(flat, sep):
+        for t in cfg.lora_targets:
+            assert a.A[t].data_ptr() % 16 == 0 and a.dB[t].data_ptr() % 16 == 0
+            for ga, gb in ((a.dA[t], b.dA[t]), (a.dB[t], b.dB[t])):
+                gb.copy_(torch.randn(gb.shape, generator=g, device="cuda"))
+                ga.copy_(gb)
+    n = arena.used
+    master = arena.param.float()
+    m, v = torch.zeros(n, device="cuda"), torch.zeros(n, device="cuda")
+    state = []
+    for b in sep:
+        for t in cfg.lora_targets:
+            for P, G in ((b.A[t], b.dA[t]), (b.Bm[t], b.dB[t])):
+                state.append((P, P.float().clone(), G, torch.zeros_like(G), torch.zeros_like(G)))
+    for step in (1, 2):
+        B.flexco_adam_step(arena.param, master, arena.grad, m, v, n, 1, 1e-3, 0.9, 0.999, 1e-8, step)
+        for P, M, G, m1, v1 in state:
+            B.flexco_adam_step(P, M, G, m1, v1, P.numel(), 1, 1e-3, 0.9, 0.999, 1e-8, step)
+    torch.cuda.synchronize()
+    for a, b in zip(flat, sep):
+        for t in cfg.lora_targets:
+            assert torch.equal(a.A[t], b.A[t]) and torch.equal(a.Bm[t], b.Bm[t]), t
