@@ -392,6 +392,18 @@ int32_t flexco_adapter_bwd(int32_t dtype, int32_t hidden, const flexco_adapter* 
                            int32_t seq_len, int32_t win_start, int32_t win_len, void* dY, void* ws,
                            size_t ws_bytes, void* stream);
 
+/* ReLU that keeps a sign bitmask instead of its output (Sec. 5.2: the backward of a ReLU reads only the sign of its
+ * output, so a ReLU whose output no other backward operator reads - FLEXCO_KEEP_BITMASK of flexco_prune_graph -
+ * stores 1 bit per element).  x, y, dy, dx: device [n, width] dense, dtype; y may alias x and dx may alias dy.
+ * mask: device [n, ceil(width / 32)] 32-bit words, bit j of word w of a row = element 32 w + j of the row is
+ * > 0 (decided on the stored value of x); the unused high bits of a row's last word are written as zero.
+ *   fwd: y = max(x, 0), mask written.     bwd: dx = dy where the bit is set, 0 elsewhere.
+ * n <= 65535 rows per call.  Errors: EINVAL, ESHAPE, EHIP. */
+int32_t flexco_relu_bitmask_fwd(const void* x, void* y, uint32_t* mask, int32_t n, int32_t width, int32_t dtype,
+                                void* stream);
+int32_t flexco_relu_bitmask_bwd(const void* dy, const uint32_t* mask, void* dx, int32_t n, int32_t width,
+                                int32_t dtype, void* stream);
+
 /* Attention backward of one window (the attention part of flexco_lora_bwd, exported for
  * unit parity).  q, out, dout: device [win_len, nq d] rows of the window (q after RoPE);
  * lse: device float [win_len, nq].  dq: device [win_len, nq d] (dtype of cfg), written.

@@ -143,3 +143,28 @@ def round_bf16(a):
     m, e = np.frexp(a)
     return np.ldexp(np.rint(m * 256.0) / 256.0, e).astype(a.dtype)
 
+
+
+# ---- ReLU with a sign bitmask (Sec. 5.2) -------------------------------------------------
+def relu_bitmask_fwd(x):
+    """y = max(x, 0) and the only thing its backward needs: one bit per element, "x > 0".  The bits of a row are
+    packed into 32-bit words, bit j of word w = element 32 w + j (a convention; the paper fixes the idea - a
+    bitmask in place of the tensor - not a layout); unused high bits of a row's last word are zero.
+    Returns (y, mask [n, ceil(width / 32)] uint32)."""
+    x = np.asarray(x)
+    n, width = x.shape
+    words = (width + 31) // 32
+    pos = np.zeros((n, words * 32), dtype=np.uint64)
+    pos[:, :width] = x > 0
+    weights = (np.uint64(1) << np.arange(32, dtype=np.uint64))
+    mask = (pos.reshape(n, words, 32) * weights).sum(axis=2).astype(np.uint32)
+    return np.maximum(x, 0), mask
+
+
+def relu_bitmask_bwd(dy, mask):
+    """dx = dy where the element's bit is set, 0 elsewhere."""
+    dy = np.asarray(dy)
+    n, width = dy.shape
+    bits = (mask[:, :, None] >> np.arange(32, dtype=np.uint32)) & np.uint32(1)
+    keep = bits.reshape(n, -1)[:, :width].astype(bool)
+    return np.where(keep, dy, 0)

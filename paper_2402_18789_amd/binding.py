@@ -145,6 +145,8 @@ def _load():
         "flexco_kernel_timer_stop": [i32, P(C.c_double), P(C.c_int64)],
         "flexco_model_forward": [P(LayerCfg), P(ModelLayer), i32, P(Maps), vp, vp, vp, vp, sz, vp],
         "flexco_model_backward": [P(LayerCfg), P(ModelLayer), i32, vp, i32, i32, i32, vp, vp, i32, P(vp), vp, sz, vp],
+        "flexco_relu_bitmask_fwd": [vp, vp, vp, i32, i32, i32, vp],
+        "flexco_relu_bitmask_bwd": [vp, vp, vp, i32, i32, i32, vp],
         "flexco_kernel_timer_sample": [i32, i32],
         "flexco_kernel_timer_read": [i32, P(C.c_double), C.c_int64, P(C.c_int64)],
         "flexco_probe_mfma_lds": [i32, i32, i32, vp, P(C.c_double), vp],
@@ -177,7 +179,8 @@ EXPORTS = ("flexco_last_error", "flexco_abi_version", "flexco_maps_blob_ints", "
            "flexco_latency_estimate", "flexco_sched_window", "flexco_sched_inference", "flexco_sched_advance",
            "flexco_lm_loss_workspace_bytes", "flexco_lm_loss", "flexco_adam_step", "flexco_prune_graph",
            "flexco_layer_forward_ia3", "flexco_ia3_bwd", "flexco_adapter_workspace_bytes", "flexco_adapter_fwd",
-           "flexco_adapter_bwd", "flexco_model_forward", "flexco_model_backward")
+           "flexco_adapter_bwd", "flexco_model_forward", "flexco_model_backward",
+           "flexco_relu_bitmask_fwd", "flexco_relu_bitmask_bwd")
 KERNEL_IDS = {"gemm_fwd": 0, "gemm_bwd": 1, "attn_fwd": 2, "attn_merge": 3, "attn_bwd": 4, "elemwise": 5, "lora": 6,
               "generic": 7}
 
@@ -464,6 +467,14 @@ def flexco_kernel_timer_start(kernel_id, max_launches):
 
 def flexco_kernel_timer_sample(kernel_id, stride):
     _check(_lib.flexco_kernel_timer_sample(kernel_id, stride))
+
+
+def flexco_relu_bitmask_fwd(x, y, mask, n, width, dtype, stream=None):
+    _check(_lib.flexco_relu_bitmask_fwd(_ptr(x), _ptr(y), _ptr(mask), n, width, dtype, _stream(stream)))
+
+
+def flexco_relu_bitmask_bwd(dy, mask, dx, n, width, dtype, stream=None):
+    _check(_lib.flexco_relu_bitmask_bwd(_ptr(dy), _ptr(mask), _ptr(dx), n, width, dtype, _stream(stream)))
 
 
 def target_dims_py(cfg, t):

@@ -213,3 +213,37 @@ def test_lora_bwd_fd():
     fd_check(f, x, dx)
     fd_check(f, A, dA)
     fd_check(f, B, dB)
+
+
+# ---- ReLU sign bitmask (Sec. 5.2) ------------------------------------------------------------
+def test_relu_bitmask_hand_case_and_size():
+    from oracle import ops
+    x = np.zeros((2, 40))
+    x[0, [0, 3, 31, 32, 39]] = [1.0, 0.5, 2.0, 7.0, 1e-30]
+    x[0, [1, 2]] = [-1.0, -0.0]
+    x[1, :] = -1.0
+    x[1, 33] = 3.0
+    y, m = ops.relu_bitmask_fwd(x)
+    assert m.dtype == np.uint32 and m.shape == (2, 2)                 # 1 bit per element, rows padded to whole words
+    assert m[0, 0] == (1 << 0) | (1 << 3) | (1 << 31) and m[0, 1] == (1 << 0) | (1 << 7)
+    assert m[1, 0] == 0 and m[1, 1] == (1 << 1)
+    assert np.array_equal(y, np.maximum(x, 0))
+
+
+def test_relu_bitmask_backward_is_the_relu_jacobian():
+    """dx from the bitmask alone equals the gradient of sum(relu(x) * dy) by the definition (and by library autograd)"""
+    from oracle import ops
+    import torch
+    g = np.random.default_rng(5)
+    for width in (1, 31, 32, 33, 70, 128):
+        x, dy = g.standard_normal((7, width)), g.standard_normal((7, width))
+        x[g.random((7, width)) < 0.1] = 0.0                             # exact zeros: the gradient there is 0
+        _, m = ops.relu_bitmask_fwd(x)
+        dx = ops.relu_bitmask_bwd(dy, m)
+        assert np.array_equal(dx, dy * (x > 0))
+        xt = torch.tensor(x, requires_grad=True)
+        (torch.relu(xt) * torch.tensor(dy)).sum().backward()
+        assert np.array_equal(dx, xt.grad.numpy())
+        # the unused bits of the last word are zero
+        if width % 32:
+            assert np.all(m[:, -1] >> np.uint32(width % 32) == 0)
