@@ -253,6 +253,8 @@ def main():
         out["ms_per_step_median"] = float(np.median(per_step))
         out["ms_per_step_min"] = float(np.min(per_step))
     out["forward_projections"] = per_projection(B, torch, step_serial, cfg, T)
+    # bf16 launches that missed the matrix-core kernels and ran type-generic ones (all zero at this configuration)
+    out["bf16_generic_fallbacks"] = {k: v for k, v in B.flexco_bf16_fallbacks().items() if k in ("gemm_fwd", "gemm_bwd", "attn_fwd", "attn_bwd")}
     out["measured_ceilings"] = measured_ceilings(B, torch)
     if not args.overlap and not args.no_two_stream:
         # the same K steps again with the window backward on a second stream (reported beside the

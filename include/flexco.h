@@ -451,6 +451,13 @@ int32_t flexco_kernel_timer_read(int32_t kernel_id, double* ms_each, int64_t cap
  * measures end-to-end time may not want on every launch. */
 int32_t flexco_kernel_timer_sample(int32_t kernel_id, int32_t stride);
 
+/* The matrix-core kernels cover the shapes of the configurations this library was built for (attention: bf16,
+ * head_dim 128, page size 16, at most 16 query heads per kv head; projections: K a multiple of 64, 16-byte aligned
+ * rows); a bf16 call outside them runs on the type-generic kernels instead, correct but far slower.  counts
+ * [FLEXCO_N_KERNEL_IDS] (host) receives, per kernel class (FLEXCO_K_GEMM_FWD, _GEMM_BWD, _ATTN_FWD, _ATTN_BWD; the
+ * other entries stay 0), how many bf16 launches of this process took that route; reset != 0 clears the counters. */
+int32_t flexco_bf16_fallbacks(int64_t* counts, int32_t reset);
+
 /* ---- Static graph pruning (Alg. 1, Sec. 5.2), host only -------------------------------------
  * The forward graph of a PEFT model as integer arrays: operator o has kind op_kind[o], one output
  * tensor op_out[o] and the input tensors op_in[op_in_off[o] .. op_in_off[o + 1]) in the order of

@@ -147,6 +147,7 @@ def _load():
         "flexco_model_backward": [P(LayerCfg), P(ModelLayer), i32, vp, i32, i32, i32, vp, vp, i32, P(vp), vp, sz, vp],
         "flexco_relu_bitmask_fwd": [vp, vp, vp, i32, i32, i32, vp],
         "flexco_relu_bitmask_bwd": [vp, vp, vp, i32, i32, i32, vp],
+        "flexco_bf16_fallbacks": [P(C.c_int64), i32],
         "flexco_kernel_timer_sample": [i32, i32],
         "flexco_kernel_timer_read": [i32, P(C.c_double), C.c_int64, P(C.c_int64)],
         "flexco_probe_mfma_lds": [i32, i32, i32, vp, P(C.c_double), vp],
@@ -180,7 +181,7 @@ EXPORTS = ("flexco_last_error", "flexco_abi_version", "flexco_maps_blob_ints", "
            "flexco_lm_loss_workspace_bytes", "flexco_lm_loss", "flexco_adam_step", "flexco_prune_graph",
            "flexco_layer_forward_ia3", "flexco_ia3_bwd", "flexco_adapter_workspace_bytes", "flexco_adapter_fwd",
            "flexco_adapter_bwd", "flexco_model_forward", "flexco_model_backward",
-           "flexco_relu_bitmask_fwd", "flexco_relu_bitmask_bwd")
+           "flexco_relu_bitmask_fwd", "flexco_relu_bitmask_bwd", "flexco_bf16_fallbacks")
 KERNEL_IDS = {"gemm_fwd": 0, "gemm_bwd": 1, "attn_fwd": 2, "attn_merge": 3, "attn_bwd": 4, "elemwise": 5, "lora": 6,
               "generic": 7}
 
@@ -475,6 +476,13 @@ def flexco_relu_bitmask_fwd(x, y, mask, n, width, dtype, stream=None):
 
 def flexco_relu_bitmask_bwd(dy, mask, dx, n, width, dtype, stream=None):
     _check(_lib.flexco_relu_bitmask_bwd(_ptr(dy), _ptr(mask), _ptr(dx), n, width, dtype, _stream(stream)))
+
+
+def flexco_bf16_fallbacks(reset=False):
+    """-> {kernel class: bf16 launches that ran on the type-generic kernels}"""
+    buf = (C.c_int64 * len(KERNEL_IDS))()
+    _check(_lib.flexco_bf16_fallbacks(buf, int(bool(reset))))
+    return {name: int(buf[i]) for name, i in KERNEL_IDS.items()}
 
 
 def target_dims_py(cfg, t):

@@ -3,6 +3,7 @@
 // (Alg. 2) of a decoder layer.
 #include <cmath>
 #include <cstring>
+#include <atomic>
 #include <mutex>
 #include <vector>
 
@@ -132,6 +133,21 @@ extern "C" int32_t flexco_kernel_timer_stop(int32_t kernel_id, double* total_ms,
   t.used = 0;
   t.on = false;
   return rc_out;
+}
+
+// bf16 calls that took a type-generic kernel because the matrix-core kernel of their class does not cover the
+// shape (head_dim other than 128, page size other than 16, odd leading dimensions ...), per kernel class
+static std::atomic<int64_t> g_bf16_fallbacks[FLEXCO_N_KERNEL_IDS];
+static inline void note_fallback(int dtype, int kernel_id) {
+  if (dtype == FLEXCO_BF16) g_bf16_fallbacks[kernel_id].fetch_add(1, std::memory_order_relaxed);
+}
+
+extern "C" int32_t flexco_bf16_fallbacks(int64_t* counts, int32_t reset) {
+  clear_error();
+  FLEXCO_CHECK(counts != nullptr, FLEXCO_EINVAL, "counts is NULL");
+  for (int i = 0; i < FLEXCO_N_KERNEL_IDS; ++i)
+    counts[i] = reset ? g_bf16_fallbacks[i].exchange(0) : g_bf16_fallbacks[i].load();
+  return FLEXCO_OK;
 }
 
 // launches bracketed by the event timer of their kernel class (stream variable `s` in scope)
@@ -635,6 +651,7 @@ int32_t run_attention(const flexco_layer_cfg& c, const flexco_maps& m, const voi
   if (rc == FLEXCO_EUNSUPPORTED) {
     clear_error();
     direct = false;
+    note_fallback(c.dtype, FLEXCO_K_ATTN_FWD);
     KernelTimerScope ts(FLEXCO_K_GENERIC, s);
     rc = launch_attention_generic(c, m, q, ldq, pool, part_ml, part_acc, s);
   }
@@ -658,6 +675,7 @@ int32_t launch_gemm(const void* A, const void* W, void* C, const void* bias, con
     clear_error();
   }
   if (ext && ext->n > 0) return FLEXCO_EUNSUPPORTED;   // the generic kernel has no rank-r extension
+  note_fallback(dtype, trans_w ? FLEXCO_K_GEMM_BWD : FLEXCO_K_GEMM_FWD);
   if (splits_out) *splits_out = 1;
   KernelTimerScope ts(FLEXCO_K_GENERIC, s);
   return launch_gemm_generic(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, trans_w, dtype, s);
@@ -957,6 +975,7 @@ static int32_t attention_window_bwd_impl(const flexco_layer_cfg& c, const flexco
                                          dv_accum, s);
   if (rc != FLEXCO_EUNSUPPORTED) return rc;
   clear_error();
+  note_fallback(c.dtype, FLEXCO_K_ATTN_BWD);
   FLEXCO_TRY(launch_attention_delta(c, out, dout, delta, win_len, s));
   return launch_attention_bwd_generic(c, pool, seq_pages, win_start, win_len, q, lse, delta, dout, dq, dk_accum,
                                       dv_accum, s);

@@ -345,6 +345,23 @@ def test_layer_small_bf16_other_ranks(rank):
     run_layer_case(cfg, b, ft_window=300, prefill_chunk=90, bwd_windows=[300, 300], seed=11)
 
 
+def test_layer_bf16_head_dim_64_runs_on_the_generic_attention_kernels_and_says_so():
+    """bf16 with head_dim 64: outside the matrix-core attention kernels' shapes; the layer still meets the bf16 bar
+    (type-generic attention kernels, matrix-core projections) and the library counts the fallback."""
+    say("layer bf16 head_dim 64 (generic attention kernels)")
+    cfg = C2.with_(name="small_bf16_d64", hidden=512, n_q_heads=8, n_kv_heads=4, head_dim=64, ffn=1408)
+    b = gen.batch_scaled(12, 7, 3, 300, [(0, 70, 70), (64, 40, 200)], [(0, 60, 150)])
+    B.flexco_bf16_fallbacks(reset=True)
+    run_layer_case(cfg, b, ft_window=90, prefill_chunk=50, bwd_windows=[50, 100], seed=12)
+    n = B.flexco_bf16_fallbacks(reset=True)
+    say("  fallbacks: %s" % n)
+    assert n["attn_fwd"] > 0 and n["attn_bwd"] > 0 and n["gemm_fwd"] == 0 and n["gemm_bwd"] == 0
+    run_layer_case(SMALL_BF16, gen.batch_scaled(7, 10, 3, 600, [(0, 130, 130)], [(0, 100, 100)]), ft_window=100, prefill_chunk=70,
+                   bwd_windows=[100], seed=7)
+    n = B.flexco_bf16_fallbacks()
+    assert all(v == 0 for v in n.values()), n          # head_dim 128: everything on the matrix-core kernels
+
+
 def test_layer_small_bf16_pool_astride_4gib():
     """A paged pool larger than 2^31 elements (4 GiB) per K and V: the batch's pages sit on both sides of
     that offset, so every kernel that addresses the pool (append, attention forward, its backward) needs
