@@ -91,14 +91,21 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_mfma_kernel(BwdArgs a) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform: LDS bases of the loads stay scalar
   const int c = lane & 15, g = lane >> 4;
   const int rt = wave & 1, kh = wave >> 1;
-  const int h = blockIdx.y, group = a.nq / a.nkv, kvh = h / group;
-  const int i0 = blockIdx.x * 32 + rt * 16;
+  // Work-group ids go round the 8 XCDs; the kv head is the id's fastest digit, so that (with 8 kv heads) every
+  // block that reads a kv head's K / V pages runs on the same XCD and finds them in that XCD's L2 (the cached
+  // rows of one kv head of a 4096-token sequence are 2 MB; all kv heads together would not fit one L2)
+  const int group = a.nq / a.nkv;
+  const int lid = blockIdx.y * gridDim.x + blockIdx.x;
+  const int kvh = lid % a.nkv;
+  const int h = kvh * group + (lid / a.nkv) % group;
+  const int bx = lid / a.nq;                                     // row block
+  const int i0 = bx * 32 + rt * 16;
   const int row_c = i0 + c;
   const bool row_ok = row_c < a.s;
   const int rcl = row_ok ? row_c : a.s - 1;
   const int pos_c = row_ok ? a.w0 + row_c : -1;
   const int wave_last_pos = a.w0 + min(i0 + 15, a.s - 1);      // may be < first key if the tile is empty
-  const int blk_last_row = min(blockIdx.x * 32 + 31, a.s - 1);
+  const int blk_last_row = min(bx * 32 + 31, a.s - 1);
   const int np = (a.w0 + blk_last_row) / PS + 1;                 // pages visible to the block
   const int nit = (np + SP - 1) / SP;
   const int last_page = (a.l - 1) / PS, last_key = (a.l - 1) % PS;
@@ -279,8 +286,13 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_mfma_kernel(BwdArgs a) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform: LDS bases of the loads stay scalar
   const int pw = wave & 3, hg = wave >> 2;
   const int c = lane & 15, g = lane >> 4;
-  const int kvh = blockIdx.y, group = a.nq / a.nkv;
-  const int pg = blockIdx.x * 4 + pw;
+  // (kv head = fastest digit of the work-group id: see kernel A; here it is the group's Q / dO rows that the
+  // blocks of one kv head share)
+  const int group = a.nq / a.nkv;
+  const int lid = blockIdx.y * gridDim.x + blockIdx.x;
+  const int kvh = lid % a.nkv;
+  const int bx = lid / a.nkv;                                    // block of 64 keys
+  const int pg = bx * 4 + pw;
   const int key0 = pg * PS;
   const bool page_ok = key0 < a.l;
   const size_t page = (size_t)a.pages[page_ok ? pg : (a.l - 1) / PS];
@@ -304,7 +316,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_mfma_kernel(BwdArgs a) {
 #pragma unroll
   for (int mt = 0; mt < 8; ++mt) { dk[mt] = f32x4{0.f, 0.f, 0.f, 0.f}; dv[mt] = f32x4{0.f, 0.f, 0.f, 0.f}; }
 
-  const int blk_key0 = blockIdx.x * 64;
+  const int blk_key0 = bx * 64;
   const int first_row = max(0, blk_key0 - a.w0) & ~31;       // first window row that sees the block's keys
   const int nrb = (a.s - first_row + 31) / 32;               // row blocks per head
   const int nit = ((group + 1) / 2) * nrb;                   // steps: heads 2 (it / nrb) + hg
