@@ -327,16 +327,21 @@ def measured_ceilings(B, torch):
         torch.cuda.synchronize()
         if rep:
             best_read = max(best_read, nbytes / (ev0.elapsed_time(ev1) * 1e-3) / 1e9)
-    # the matrix cores fed from LDS as the projection kernels feed them (no global traffic, no barriers)
-    best_lds = {128: 0.0, 256: 0.0}
+    # the matrix cores fed from LDS as the projection kernels feed them: without and with the stage's tile loads
+    # (from a cache-resident 512 KB) and barrier
+    best_lds = {}
     for tile in (128, 256):
-        for rep in range(3):
-            ev0.record()
-            flops = B.flexco_probe_mfma_lds(256, 4000 if tile == 128 else 1000, tile, sink)
-            ev1.record()
-            torch.cuda.synchronize()
-            if rep:
-                best_lds[tile] = max(best_lds[tile], flops / (ev0.elapsed_time(ev1) * 1e-3) / 1e12)
+        for loads in (False, True):
+            best = 0.0
+            for rep in range(3):
+                ev0.record()
+                flops = B.flexco_probe_mfma_lds(256, 4000 if tile == 128 else 1000, tile, sink, buf if loads else None,
+                                                1 << 20 if loads else 0)
+                ev1.record()
+                torch.cuda.synchronize()
+                if rep:
+                    best = max(best, flops / (ev0.elapsed_time(ev1) * 1e-3) / 1e12)
+            best_lds[(tile, loads)] = best
     # plain device-to-device copy of 1 GiB (read + write counted)
     src, dst = buf[:1 << 30], buf[1 << 30:2 << 30]
     best_copy = 0.0
@@ -348,12 +353,17 @@ def measured_ceilings(B, torch):
         if rep:
             best_copy = max(best_copy, 2.0 * (1 << 30) / (ev0.elapsed_time(ev1) * 1e-3) / 1e9)
     del src, dst, buf
-    return {"mfma_bf16_loop_tflops": best_mfma, "mfma_bf16_lds_operands_tile128_tflops": best_lds[128],
-            "mfma_bf16_lds_operands_tile256_tflops": best_lds[256], "hbm_read_stream_gbs": best_read,
+    return {"mfma_bf16_loop_tflops": best_mfma,
+            "mfma_bf16_lds_operands_tile128_tflops": best_lds[(128, False)],
+            "mfma_bf16_lds_operands_tile256_tflops": best_lds[(256, False)],
+            "k_loop_without_memory_wait_tile128_tflops": best_lds[(128, True)],
+            "k_loop_without_memory_wait_tile256_tflops": best_lds[(256, True)], "hbm_read_stream_gbs": best_read,
             "device_copy_gbs": best_copy,
             "what": "probe kernels of the library: 256 blocks x 4 wavefronts of back-to-back v_mfma_f32_32x32x16_bf16 on "
                     "register operands in [-1, 1); the same products with operands read from LDS in the projection "
-                    "kernels' pattern for a 128 x 128 and a 256 x 256 block tile (no global traffic, no barriers); "
+                    "kernels' pattern for a 128 x 128 and a 256 x 256 block tile, one slice ahead (no global traffic, no "
+                    "barriers), and with a stage of tile loads into LDS from cache-resident memory plus a barrier per "
+                    "stage (the kernels' k-loop minus its wait for memory); "
                     "2048 blocks streaming 4 GiB with 16-byte loads; a 1 GiB device-to-device "
                     "copy (bytes read + bytes written)"}
 

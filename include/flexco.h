@@ -616,11 +616,15 @@ int32_t flexco_model_backward(const flexco_layer_cfg* cfg, const flexco_model_la
  *   flexco_probe_read: `blocks` blocks each stream their own contiguous piece of src[0, bytes) with
  *     16-byte loads; *bytes_read = bytes actually read (bytes rounded down to whole rounds).
  *   flexco_probe_mfma_lds: the same products with the operands fetched from LDS as the projection kernels fetch
- *     them (tile = 128: 2 x 2 wavefronts on a 128 x 128 tile, where the LDS reads take as long as the products;
- *     tile = 256: a 256 x 256 tile, half as long); `iters` 64-column stages per wavefront, no global memory
- *     traffic, no barriers. */
+ *     them, one 16-column slice ahead of the products (tile = 128: 2 x 2 wavefronts on a 128 x 128 tile, where the
+ *     LDS reads take as long as the products; tile = 256: a 256 x 256 tile, half as long); `iters` 64-column
+ *     stages per wavefront.  src == NULL: no global memory traffic and no barriers.  src != NULL (device, 16-byte
+ *     aligned, at least 8 x 2 x tile x 64 x 2 bytes of finite bf16 values): every stage also loads a stage of tile
+ *     bytes from src straight into LDS and ends with a barrier - the projection kernels' k-loop without its wait
+ *     for memory. */
 int32_t flexco_probe_mfma(int32_t blocks, int32_t iters, void* sink, double* flops, void* stream);
-int32_t flexco_probe_mfma_lds(int32_t blocks, int32_t iters, int32_t tile, void* sink, double* flops, void* stream);
+int32_t flexco_probe_mfma_lds(int32_t blocks, int32_t iters, int32_t tile, const void* src, size_t src_bytes,
+                              void* sink, double* flops, void* stream);
 int32_t flexco_probe_read(const void* src, size_t bytes, int32_t blocks, void* sink, double* bytes_read,
                           void* stream);
 

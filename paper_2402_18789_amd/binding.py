@@ -150,7 +150,7 @@ def _load():
         "flexco_bf16_fallbacks": [P(C.c_int64), i32],
         "flexco_kernel_timer_sample": [i32, i32],
         "flexco_kernel_timer_read": [i32, P(C.c_double), C.c_int64, P(C.c_int64)],
-        "flexco_probe_mfma_lds": [i32, i32, i32, vp, P(C.c_double), vp],
+        "flexco_probe_mfma_lds": [i32, i32, i32, vp, sz, vp, P(C.c_double), vp],
         "flexco_probe_mfma": [i32, i32, vp, P(C.c_double), vp],
         "flexco_probe_read": [vp, sz, i32, vp, P(C.c_double), vp],
         "flexco_latency_estimate": [P(LatencyModel), i32, i32, P(C.c_double)],
@@ -375,10 +375,10 @@ def flexco_probe_mfma(blocks, iters, sink, stream=None):
     return fl.value
 
 
-def flexco_probe_mfma_lds(blocks, iters, tile, sink, stream=None):
+def flexco_probe_mfma_lds(blocks, iters, tile, sink, src=None, src_bytes=0, stream=None):
     """-> flops enqueued"""
     fl = C.c_double(0.0)
-    _check(_lib.flexco_probe_mfma_lds(blocks, iters, tile, _ptr(sink), C.byref(fl), _stream(stream)))
+    _check(_lib.flexco_probe_mfma_lds(blocks, iters, tile, _ptr(src), src_bytes, _ptr(sink), C.byref(fl), _stream(stream)))
     return fl.value
 
 

@@ -48,15 +48,22 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, float* sink)
 
 // The same products with their operands fetched from LDS the way the projection kernels fetch them: a block of
 // 4 wavefronts (2 x 2) owns a (64 MT) x (64 NT) tile, LDS holds one 64-column stage of both operand tiles (128-byte
-// rows, 16-byte chunks XOR-swizzled by row), and every 16-column slice costs a wavefront MT + NT ds_read_b128 for
-// MT x NT products.  No global memory traffic and no barriers inside the loop: what the matrix cores sustain when
-// LDS feeds them (MT = NT = 2: the 128 x 128 tile, LDS reads as long as the products; 4: the 256 x 256 tile, half).
-template <int MT, int NT>
-__global__ __launch_bounds__(256) void probe_mfma_lds_kernel(int iters, float* sink) {
-  constexpr int BM = 64 * MT, BN = 64 * NT;
-  __shared__ __attribute__((aligned(1024))) bf16_t tile[(BM + BN) * 64];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  for (int i = tid; i < (BM + BN) * 64; i += 256) {
+// rows, 16-byte chunks XOR-swizzled by row), every 16-column slice costs a wavefront MT + NT ds_read_b128 for
+// MT x NT products, and the fragments of a slice are fetched while the slice before it is multiplied.
+// LOADS: per stage the block also brings a whole stage of tile bytes from global memory straight into a second
+// LDS buffer (global_load_lds, 1 KB per wavefront instruction, from a few hundred KB that stay in cache) and ends
+// the stage with a barrier - everything the projection kernels' k-loop does except wait for memory.
+// What the matrix cores sustain when LDS feeds them (MT = NT = 2: the 128 x 128 tile, 4: the 256 x 256 tile).
+#define FLEXCO_GP(p) ((const __attribute__((address_space(1))) void*)(p))
+#define FLEXCO_LP(p) ((__attribute__((address_space(3))) void*)(p))
+template <int MT, int NT, bool LOADS>
+__global__ __launch_bounds__(256) void probe_mfma_lds_kernel(const bf16_t* __restrict__ src, int iters, float* sink) {
+  constexpr int BM = 64 * MT, BN = 64 * NT, ST = (BM + BN) * 64;
+  __shared__ __attribute__((aligned(1024))) bf16_t tile[ST];
+  __shared__ __attribute__((aligned(1024))) bf16_t land[LOADS ? ST : 8];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  for (int i = tid; i < ST; i += 256) {
     const unsigned h = (unsigned)i * 2654435761u;
     tile[i] = (bf16_t)((float)(h >> 8 & 0xffff) / 32768.f - 1.f);
   }
@@ -70,32 +77,58 @@ __global__ __launch_bounds__(256) void probe_mfma_lds_kernel(int iters, float* s
     for (int j = 0; j < NT; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  constexpr int NLD = (BM + BN) / 32;                       // 1 KB load instructions per wavefront and stage
+  const bf16_t* g = src + (size_t)(blockIdx.x & 7) * ST + lane * 8;
+  bf16x8 a0[MT], b0[NT], a1[MT], b1[NT];
+#define FLEXCO_P_FRAGS(kk_, af_, bf_)                                                                        \
+  {                                                                                                          \
+    _Pragma("unroll") for (int i = 0; i < MT; ++i) {                                                         \
+      const int r = wm0 + i * 32 + l32;                                                                      \
+      af_[i] = *reinterpret_cast<const bf16x8*>(tile + r * 64 + ((((kk_) * 2 + kg) ^ ((r >> 1) & 7)) * 8));  \
+    }                                                                                                        \
+    _Pragma("unroll") for (int j = 0; j < NT; ++j) {                                                         \
+      const int r = wn0 + j * 32 + l32;                                                                      \
+      bf_[j] = *reinterpret_cast<const bf16x8*>(tile + (BM + r) * 64 + ((((kk_) * 2 + kg) ^ ((r >> 1) & 7)) * 8)); \
+    }                                                                                                        \
+  }
+#define FLEXCO_P_MFMAS(af_, bf_)                                                                             \
+  {                                                                                                          \
+    _Pragma("unroll") for (int i = 0; i < MT; ++i)                                                           \
+      _Pragma("unroll") for (int j = 0; j < NT; ++j)                                                         \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf_[j], af_[i], acc[i][j], 0, 0, 0);             \
+    _Pragma("unroll") for (int q = 0; q < MT * NT; ++q) {   /* reads of the next slice ahead of each product */ \
+      __builtin_amdgcn_sched_group_barrier(0x100, (MT + NT + MT * NT - 1) / (MT * NT), 0);                   \
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                     \
+    }                                                                                                        \
+    __builtin_amdgcn_sched_barrier(0);                                                                       \
+  }
+  FLEXCO_P_FRAGS(0, a0, b0)
   for (int it = 0; it < iters; ++it) {
+    if (LOADS) {
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      bf16x8 af[MT], bf[NT];
-#pragma unroll
-      for (int i = 0; i < MT; ++i) {
-        const int r = wm0 + i * 32 + l32;
-        af[i] = *reinterpret_cast<const bf16x8*>(tile + r * 64 + (((kk * 2 + kg) ^ ((r >> 1) & 7)) * 8));
-      }
-#pragma unroll
-      for (int j = 0; j < NT; ++j) {
-        const int r = wn0 + j * 32 + l32;
-        bf[j] = *reinterpret_cast<const bf16x8*>(tile + (BM + r) * 64 + (((kk * 2 + kg) ^ ((r >> 1) & 7)) * 8));
-      }
-#pragma unroll
-      for (int i = 0; i < MT; ++i)
-#pragma unroll
-        for (int j = 0; j < NT; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[j], af[i], acc[i][j], 0, 0, 0);
+      for (int p = 0; p < NLD; ++p)
+        __builtin_amdgcn_global_load_lds(FLEXCO_GP(g + (p * 4 + wave) * 512), FLEXCO_LP(land + (p * 4 + wave) * 512), 16, 0, 0);
+    }
+    FLEXCO_P_FRAGS(1, a1, b1) FLEXCO_P_MFMAS(a0, b0)
+    FLEXCO_P_FRAGS(2, a0, b0) FLEXCO_P_MFMAS(a1, b1)
+    FLEXCO_P_FRAGS(3, a1, b1) FLEXCO_P_MFMAS(a0, b0)
+    FLEXCO_P_FRAGS(0, a0, b0) FLEXCO_P_MFMAS(a1, b1)
+    if (LOADS) {
+      __builtin_amdgcn_s_waitcnt(0x0F70 | (NLD & 15) | ((NLD >> 4) << 14));   // the stage before this one has landed
+      asm volatile("" ::: "memory");
+      __builtin_amdgcn_s_barrier();
     }
     asm volatile("" ::: "memory");      // the fragments are read again in every iteration
   }
+  if (LOADS) __builtin_amdgcn_s_waitcnt(0x0F70);   // nothing may land in LDS after the block ends
+#undef FLEXCO_P_FRAGS
+#undef FLEXCO_P_MFMAS
   float s = 0.f;
 #pragma unroll
   for (int i = 0; i < MT; ++i)
 #pragma unroll
     for (int j = 0; j < NT; ++j) s += acc[i][j][0];
+  if (LOADS) s += (float)land[tid];
   if (s == 12345.678f) sink[0] = s;
 }
 
@@ -130,15 +163,20 @@ extern "C" int32_t flexco_probe_mfma(int32_t blocks, int32_t iters, void* sink, 
   return FLEXCO_OK;
 }
 
-extern "C" int32_t flexco_probe_mfma_lds(int32_t blocks, int32_t iters, int32_t tile, void* sink, double* flops,
-                                         void* stream) {
+extern "C" int32_t flexco_probe_mfma_lds(int32_t blocks, int32_t iters, int32_t tile, const void* src, size_t src_bytes,
+                                         void* sink, double* flops, void* stream) {
   clear_error();
   FLEXCO_CHECK(blocks > 0 && iters > 0 && sink && flops, FLEXCO_EINVAL, "probe_mfma_lds: bad argument");
   FLEXCO_CHECK(tile == 128 || tile == 256, FLEXCO_EINVAL, "probe_mfma_lds: tile must be 128 or 256");
-  if (tile == 128)
-    hipLaunchKernelGGL((probe_mfma_lds_kernel<2, 2>), dim3(blocks), dim3(256), 0, (hipStream_t)stream, iters, (float*)sink);
-  else
-    hipLaunchKernelGGL((probe_mfma_lds_kernel<4, 4>), dim3(blocks), dim3(256), 0, (hipStream_t)stream, iters, (float*)sink);
+  const size_t need = (size_t)8 * 2 * tile * 64 * sizeof(bf16_t);       // 8 regions of one stage of both tiles
+  FLEXCO_CHECK(!src || (aligned16(src) && src_bytes >= need), FLEXCO_EINVAL,
+               "probe_mfma_lds: src must be 16-byte aligned and hold %zu bytes", need);
+  hipStream_t s = (hipStream_t)stream;
+  const bf16_t* p = (const bf16_t*)src;
+  if (tile == 128 && src) hipLaunchKernelGGL((probe_mfma_lds_kernel<2, 2, true>), dim3(blocks), dim3(256), 0, s, p, iters, (float*)sink);
+  else if (tile == 128) hipLaunchKernelGGL((probe_mfma_lds_kernel<2, 2, false>), dim3(blocks), dim3(256), 0, s, p, iters, (float*)sink);
+  else if (src) hipLaunchKernelGGL((probe_mfma_lds_kernel<4, 4, true>), dim3(blocks), dim3(256), 0, s, p, iters, (float*)sink);
+  else hipLaunchKernelGGL((probe_mfma_lds_kernel<4, 4, false>), dim3(blocks), dim3(256), 0, s, p, iters, (float*)sink);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(FLEXCO_EHIP, "launch of probe_mfma_lds failed: %s", hipGetErrorString(e));
   const double per_slice = (tile == 128 ? 4.0 : 16.0) * (2.0 * 32 * 32 * 16);
