@@ -335,89 +335,123 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
   }
 
   // ---- epilogue: register 4 q + e of acc[i][j] is row lane % 32, column 8 q + 4 (lane / 32) + e of
-  // the 32 x 32 block ------------------------------------------------------------------------------
+  // the 32 x 32 block.  Stored as they lie, an instruction would touch 32 rows with 16 (bf16) or 32 (fp32)
+  // bytes each; measured, such stores run at about 1 TB/s where whole 128-byte lines reach 3.5.  So every
+  // wavefront turns its rows through a piece of the (now free) ring that only it touches: accumulators in,
+  // 16 bytes per lane along a row out, 128 contiguous bytes or more per row and instruction. ------------
+  __syncthreads();   // every wavefront is done with the ring, and (after its own wait above) its loads have landed
   if (GLU) {
     // registers 4 qq + e (gate) and 8 + 4 qq + e (up) of acc[i][j] belong to act column 8 qq + 4 (lane / 32) + e
     // of the fragment's 16
+    constexpr int AW = WN / 2;                       // act columns of a wavefront's tile
+    constexpr int PITCH = AW + 8;                    // staged row in elements (16 bytes of padding)
+    constexpr int LPR = AW / 8;                      // lanes that cover a row, 16 bytes each
+    constexpr int LPRP = LPR <= 4 ? 4 : 8;           // ... rounded up to a power of two (the others idle)
+    constexpr int RPI = 64 / LPRP;                   // rows per instruction
+    static_assert(4 * 32 * PITCH <= ST_ELEMS, "the staged act rows of four wavefronts fit a stage");
+    bf16_t* stg = ring0 + wave * 32 * PITCH;
     const int ac_end = min(glu.col0 + N / 2, glu.F);
+    const int ac_w = glu.col0 + tn * (BN / 2) + (wn0 >> 1);      // first act column of this wavefront
+    const int rl = lane / LPRP, cl = (lane % LPRP) * 8;
+    const bool lane_on = (lane % LPRP) < LPR && ac_w + cl < ac_end;   // F % 8 == 0: a run of 8 is in or out as a whole
 #pragma unroll
     for (int i = 0; i < MT; ++i) {
-      const int row = m0 + wm0 + i * 32 + l32;
-      const bool save = glu.save_gate && row >= glu.save_row0 && row < glu.save_row0 + glu.save_rows;
+      const int rb = m0 + wm0 + i * 32;
+      const bool band_saves = glu.save_gate && rb + 32 > glu.save_row0 && rb < glu.save_row0 + glu.save_rows;   // uniform
 #pragma unroll
-      for (int j = 0; j < NT; ++j) {
+      for (int what = 0; what < 3; ++what) {         // 0: act, 1: gate, 2: up (the last two for finetune rows only)
+        if (what > 0 && !band_saves) break;
 #pragma unroll
-        for (int qq = 0; qq < 2; ++qq) {
-          const int ac = glu.col0 + tn * (BN / 2) + ((wn0 + j * 32) >> 1) + 8 * qq + 4 * kg;
-          if (row >= M || ac >= ac_end) continue;
-          bf16x4 o, gs, us;
+        for (int j = 0; j < NT; ++j)
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            // gate and up pass through the storage type first (they are what the backward pass reads back)
-            gs[e] = (bf16_t)acc[i][j][4 * qq + e];
-            us[e] = (bf16_t)acc[i][j][8 + 4 * qq + e];
-            const float gv = (float)gs[e], uv = (float)us[e];
-            o[e] = (bf16_t)(gv / (1.0f + __expf(-gv)) * uv);
+          for (int qq = 0; qq < 2; ++qq) {
+            bf16x4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              // gate and up pass through the storage type first (they are what the backward pass reads back)
+              const bf16_t gs = (bf16_t)acc[i][j][4 * qq + e], us = (bf16_t)acc[i][j][8 + 4 * qq + e];
+              const float gv = (float)gs, uv = (float)us;
+              o[e] = what == 0 ? (bf16_t)(gv / (1.0f + __expf(-gv)) * uv) : (what == 1 ? gs : us);
+            }
+            *reinterpret_cast<bf16x4*>(stg + l32 * PITCH + j * 16 + 8 * qq + 4 * kg) = o;
           }
-          *reinterpret_cast<bf16x4*>(C + (size_t)row * ldc + ac) = o;
-          if (save) {
-            const size_t so = (size_t)(row - glu.save_row0) * glu.ld_save + ac;
-            *reinterpret_cast<bf16x4*>(glu.save_gate + so) = gs;
-            *reinterpret_cast<bf16x4*>(glu.save_up + so) = us;
-          }
+        bf16_t* dst = what == 0 ? C : (what == 1 ? glu.save_gate : glu.save_up);
+        const size_t ldd = what == 0 ? ldc : glu.ld_save;
+#pragma unroll
+        for (int p = 0; p < 32 / RPI; ++p) {
+          const int r = p * RPI + rl, row = rb + r;
+          const int drow = what == 0 ? row : row - glu.save_row0;
+          const bool ok = lane_on && row < M && (what == 0 || (drow >= 0 && drow < glu.save_rows));
+          if (ok) *reinterpret_cast<bf16x8*>(dst + (size_t)drow * ldd + ac_w + cl) = *reinterpret_cast<const bf16x8*>(stg + r * PITCH + cl);
         }
         if (MT * NT > 4) __builtin_amdgcn_sched_barrier(0);
       }
     }
     return;
   }
-  if (part) {
-    float* P = part + (size_t)blockIdx.y * M * N;
-#pragma unroll
-    for (int i = 0; i < MT; ++i) {
-      const int row = m0 + wm0 + i * 32 + l32;
-#pragma unroll
-      for (int j = 0; j < NT; ++j)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int col = n0 + wn0 + j * 32 + 8 * q + 4 * kg;
-          if (row >= M || col >= N) continue;     // N % 8 == 0: a run of 4 is inside or outside as a whole
-          f32x4 v;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * q + e];
-          *reinterpret_cast<f32x4*>(P + (size_t)row * N + col) = v;
-        }
-    }
-    return;
-  }
+  // fp32 staging (what is added to the accumulators - bias, residual - is added in fp32 before the one rounding):
+  // 32 rows x 64 columns at a time (two fragments; one if the wavefront's tile has an odd one left), rows 272 bytes apart
+  constexpr int PITCH32 = 64 + 4;
+  static_assert(2 * 32 * PITCH32 * 4 <= ST_ELEMS * 2, "the staged rows of two wavefronts fit a stage");
+  float* stg = reinterpret_cast<float*>(wave < 2 ? ring0 : ring1) + (wave & 1) * 32 * PITCH32;
+  float* P = part ? part + (size_t)blockIdx.y * M * N : nullptr;
 #pragma unroll
   for (int i = 0; i < MT; ++i) {
-    const int row = m0 + wm0 + i * 32 + l32;
+    const int rb = m0 + wm0 + i * 32;
 #pragma unroll
-    for (int j = 0; j < NT; ++j) {
+    for (int j0 = 0; j0 < NT; j0 += 2) {
+      const int nj = (j0 + 1 < NT) ? 2 : 1;          // fragments in this group (compile-time after unrolling)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int col = n0 + wn0 + j * 32 + 8 * q + 4 * kg;
-        if (row >= M || col >= N) continue;
-        float v[4];
+      for (int jj = 0; jj < 2; ++jj) {
+        if (jj >= nj) break;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * q + e];
-        if (bias) {
-          const bf16x4 b4 = *reinterpret_cast<const bf16x4*>(bias + col);
+        for (int q = 0; q < 4; ++q) {
+          f32x4 v;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] += (float)b4[e];
+          for (int e = 0; e < 4; ++e) v[e] = acc[i][j0 + jj][4 * q + e];
+          *reinterpret_cast<f32x4*>(stg + l32 * PITCH32 + jj * 32 + 8 * q + 4 * kg) = v;
         }
-        if (res) {
-          const bf16x4 r4 = *reinterpret_cast<const bf16x4*>(res + (size_t)row * ldr + col);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] += (float)r4[e];
-        }
-        bf16x4 o;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = (bf16_t)v[e];
-        *reinterpret_cast<bf16x4*>(C + (size_t)row * ldc + col) = o;
       }
-      // (keeps the scheduler from gathering the loads of the whole tile up front, which costs more
+      const int cb = n0 + wn0 + j0 * 32;             // first column of the group
+      if (part) {
+        // 16 lanes x 4 columns per row, 4 rows per instruction
+        const int rl = lane >> 4, cl = (lane & 15) * 4;
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+          const int r = p * 4 + rl, row = rb + r, col = cb + cl;
+          if (cl < nj * 32 && row < M && col < N)    // N % 8 == 0: a run of 4 is inside or outside as a whole
+            *reinterpret_cast<f32x4*>(P + (size_t)row * N + col) = *reinterpret_cast<const f32x4*>(stg + r * PITCH32 + cl);
+        }
+      } else {
+        // 8 lanes x 8 columns per row, 8 rows per instruction
+        const int rl = lane >> 3, cl = (lane & 7) * 8;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          const int r = p * 8 + rl, row = rb + r, col = cb + cl;
+          if (cl < nj * 32 && row < M && col < N) {  // N % 8 == 0: a run of 8 is inside or outside as a whole
+            const f32x4 lo = *reinterpret_cast<const f32x4*>(stg + r * PITCH32 + cl);
+            const f32x4 hi = *reinterpret_cast<const f32x4*>(stg + r * PITCH32 + cl + 4);
+            float v[8];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { v[e] = lo[e]; v[4 + e] = hi[e]; }
+            if (bias) {
+              const bf16x8 b8 = *reinterpret_cast<const bf16x8*>(bias + col);
+#pragma unroll
+              for (int e = 0; e < 8; ++e) v[e] += (float)b8[e];
+            }
+            if (res) {
+              const bf16x8 r8 = *reinterpret_cast<const bf16x8*>(res + (size_t)row * ldr + col);
+#pragma unroll
+              for (int e = 0; e < 8; ++e) v[e] += (float)r8[e];
+            }
+            bf16x8 o;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = (bf16_t)v[e];
+            *reinterpret_cast<bf16x8*>(C + (size_t)row * ldc + col) = o;
+          }
+        }
+      }
+      // (keeps the scheduler from gathering the stores of the whole tile up front, which costs more
       // registers than the large tile has left)
       if (MT * NT > 4) __builtin_amdgcn_sched_barrier(0);
     }
