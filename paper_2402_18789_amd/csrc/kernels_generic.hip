@@ -5,7 +5,10 @@
 // the bf16 configurations that are bound by HBM traffic or are tiny (norms, RoPE, SwiGLU,
 // rank-r LoRA products).  The dense bf16 contractions live in gemm_mfma.hip /
 // attn_mfma.hip.
+#include <cmath>
 #include <initializer_list>
+#include <mutex>
+#include <vector>
 #include "flexco_internal.h"
 #include "device_types.h"
 
@@ -263,6 +266,21 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* __restrict__ 
   }
 }
 
+// Rotation angles.  Pair i of a head turns by pos * theta^(-2 i / d).  The host hands over the frequencies in
+// revolutions, theta^(-2 i / d) / (2 pi), as doubles (a kernel argument: pow and a double-precision sincos per
+// (token, i) on the device were a third of these kernels' run time).  The device takes the fractional part of
+// pos * rev in double precision (exact to 1e-10 of a turn at any position) and the sine and cosine of that
+// fraction of a turn in single precision (angle in [0, 2 pi): about 5e-7 absolute).
+constexpr int ROPE_MAX_HALF = 128;   // head_dim <= 256
+struct RopeFreq {
+  double rev[ROPE_MAX_HALF];
+};
+__device__ inline void rope_cos_sin(const RopeFreq& f, int i, int pos, float* c, float* sn) {
+  const double r = (double)pos * f.rev[i];
+  const float turn = (float)(r - floor(r));
+  sincosf(turn * 6.283185307179586f, sn, c);
+}
+
 // --------------------------------------------------------------------------------------
 // RoPE + cache append (Alg. 2: Forward then Append of Q, K, V).  One block per token.
 //   qkv row = [q heads | k heads | v heads]; q is rotated in place, k is rotated and
@@ -275,19 +293,13 @@ template <typename T, bool VEC>
 __global__ __launch_bounds__(256) void rope_append_kernel(T* __restrict__ qkv, const int32_t* __restrict__ tok_pos,
                                                           const int32_t* __restrict__ slot, T* __restrict__ kp,
                                                           T* __restrict__ vp, int nq, int nkv, int d, int ps,
-                                                          float theta, int ft_tok0, int n_ft, int ft_pos0,
+                                                          RopeFreq freq, int ft_tok0, int n_ft, int ft_pos0,
                                                           T* __restrict__ q_cache) {
   extern __shared__ float cs[];   // cos[d/2], sin[d/2]
   const int t = blockIdx.x;
   const int pos = tok_pos[t];
   const int half = d >> 1;
-  for (int i = threadIdx.x; i < half; i += 256) {
-    const double inv = pow((double)theta, -2.0 * (double)i / (double)d);
-    double sn, c;
-    sincos((double)pos * inv, &sn, &c);
-    cs[i] = (float)c;
-    cs[half + i] = (float)sn;
-  }
+  for (int i = threadIdx.x; i < half; i += 256) rope_cos_sin(freq, i, pos, &cs[i], &cs[half + i]);
   __syncthreads();
   const int qkv_dim = (nq + 2 * nkv) * d;
   T* row = qkv + (size_t)t * qkv_dim;
@@ -383,7 +395,7 @@ __device__ inline void load_f32_run(const float* p, float (&v)[N]) {
 template <typename T, int R = 0, bool VEC = false>
 __global__ __launch_bounds__(256) void rope_bwd_pack_kernel(const T* __restrict__ dq, const float* __restrict__ dk,
                                                             const float* __restrict__ dv, T* __restrict__ dqkv,
-                                                            int nq, int nkv, int d, float theta, int win_start,
+                                                            int nq, int nkv, int d, RopeFreq freq, int win_start,
                                                             RowLoraT lt) {
   extern __shared__ float cs[];
   constexpr int RA = R > 0 ? R : 1;
@@ -398,13 +410,7 @@ __global__ __launch_bounds__(256) void rope_bwd_pack_kernel(const T* __restrict_
   // query heads to block 0 and the key heads and v to block 1
   const int part = gridDim.y == 2 ? (int)blockIdx.y : -1;
   const int h_lo = part == 1 ? nq : 0, h_hi = part == 0 ? nq : nq + nkv;
-  for (int i = threadIdx.x; i < half; i += 256) {
-    const double inv = pow((double)theta, -2.0 * (double)i / (double)d);
-    double sn, c;
-    sincos((double)pos * inv, &sn, &c);
-    cs[i] = (float)c;
-    cs[half + i] = (float)sn;
-  }
+  for (int i = threadIdx.x; i < half; i += 256) rope_cos_sin(freq, i, pos, &cs[i], &cs[half + i]);
   __syncthreads();
   T* out = dqkv + (size_t)r * (nq + 2 * nkv) * d;
   if constexpr (VEC) {
@@ -907,15 +913,37 @@ int32_t launch_rmsnorm_bwd(const void* x, const void* g, const void* dh, const v
   return post_launch("rmsnorm_bwd");
 }
 
+// The frequencies of a (theta, head_dim) pair, computed once (a model has one pair; a lock guards the few cached ones).
+static int32_t rope_freq(const flexco_layer_cfg& c, RopeFreq* out) {
+  const int half = c.head_dim / 2;
+  if (half > ROPE_MAX_HALF) return fail(FLEXCO_EUNSUPPORTED, "rotary embedding: head_dim %d above %d", c.head_dim, 2 * ROPE_MAX_HALF);
+  struct Entry { float theta; int d; RopeFreq f; };
+  static std::mutex mu;
+  static std::vector<Entry> cache;
+  std::lock_guard<std::mutex> lock(mu);
+  for (const Entry& e : cache)
+    if (e.theta == c.rope_theta && e.d == c.head_dim) { *out = e.f; return FLEXCO_OK; }
+  Entry e;
+  e.theta = c.rope_theta; e.d = c.head_dim;
+  for (int i = 0; i < ROPE_MAX_HALF; ++i)
+    e.f.rev[i] = i < half ? std::pow((double)c.rope_theta, -2.0 * (double)i / (double)c.head_dim) / 6.283185307179586476925 : 0.0;
+  if (cache.size() >= 16) cache.clear();
+  cache.push_back(e);
+  *out = e.f;
+  return FLEXCO_OK;
+}
+
 int32_t launch_rope_append(const flexco_layer_cfg& c, void* qkv, const int32_t* tok_pos, const int32_t* slot,
                            const flexco_kv_pool& pool, int T_, int ft_tok0, int n_ft, int ft_pos0, void* q_cache,
                            hipStream_t s) {
   if (T_ == 0) return FLEXCO_OK;
   const size_t shm = sizeof(float) * c.head_dim;
+  RopeFreq freq;
+  FLEXCO_TRY(rope_freq(c, &freq));
   const bool vec = c.head_dim % 2 == 0 && vec_ok(c.dtype, c.head_dim / 2, {qkv, pool.k_pages, pool.v_pages, q_cache});
   DISPATCH_TV(c.dtype, vec, hipLaunchKernelGGL((rope_append_kernel<T, VEC>), dim3(T_), dim3(256), shm, s, (T*)qkv, tok_pos,
                                                slot, (T*)pool.k_pages, (T*)pool.v_pages, c.n_q_heads, c.n_kv_heads,
-                                               c.head_dim, c.page_size, c.rope_theta, ft_tok0, n_ft, ft_pos0,
+                                               c.head_dim, c.page_size, freq, ft_tok0, n_ft, ft_pos0,
                                                (T*)q_cache));
   return post_launch("rope_append");
 }
@@ -924,6 +952,8 @@ int32_t launch_rope_bwd_pack(const flexco_layer_cfg& c, const void* dq, const fl
                              void* dqkv, int win_start, int n, hipStream_t s, const RowLoraT* lt_in) {
   const size_t shm = sizeof(float) * c.head_dim;
   if (n == 0) return FLEXCO_OK;
+  RopeFreq freq;
+  FLEXCO_TRY(rope_freq(c, &freq));
   const dim3 grid(n, n <= 512 ? 2 : 1);   // few rows: two blocks per row
   // 16-byte accesses: also the float rows of dk / dv (their row pitch nkv d floats is a multiple of 16 bytes then)
   const bool vec = c.head_dim % 2 == 0 && vec_ok(c.dtype, c.head_dim / 2, {dq, dk_rows, dv_rows, dqkv});
@@ -933,7 +963,7 @@ int32_t launch_rope_bwd_pack(const flexco_layer_cfg& c, const void* dq, const fl
     lt = *lt_in;
 #define FLEXCO_ROPE_BWD_LT(R_, V_)                                                                                      \
   hipLaunchKernelGGL((rope_bwd_pack_kernel<bf16_t, R_, V_>), grid, dim3(256), shm, s, (const bf16_t*)dq, dk_rows, dv_rows, \
-                     (bf16_t*)dqkv, c.n_q_heads, c.n_kv_heads, c.head_dim, c.rope_theta, win_start, lt)
+                     (bf16_t*)dqkv, c.n_q_heads, c.n_kv_heads, c.head_dim, freq, win_start, lt)
     if (lt.r == 16) { if (vec) FLEXCO_ROPE_BWD_LT(16, true); else FLEXCO_ROPE_BWD_LT(16, false); }
     else { if (vec) FLEXCO_ROPE_BWD_LT(32, true); else FLEXCO_ROPE_BWD_LT(32, false); }
 #undef FLEXCO_ROPE_BWD_LT
@@ -941,7 +971,7 @@ int32_t launch_rope_bwd_pack(const flexco_layer_cfg& c, const void* dq, const fl
   }
   DISPATCH_TV(c.dtype, vec, hipLaunchKernelGGL((rope_bwd_pack_kernel<T, 0, VEC>), grid, dim3(256), shm, s, (const T*)dq,
                                                dk_rows, dv_rows, (T*)dqkv, c.n_q_heads, c.n_kv_heads, c.head_dim,
-                                               c.rope_theta, win_start, lt));
+                                               freq, win_start, lt));
   return post_launch("rope_bwd_pack");
 }
 
