@@ -87,8 +87,8 @@ __device__ inline bf16x8 tr_pair(const bf16_t* a, const bf16_t* b) {
 // in a fixed order at the end.  (The grid has one block per CU or fewer and a step is a chain of
 // dependent LDS reads and MFMAs: eight wavefronts halve the number of steps.)
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(512) void attn_bwd_dq_mfma_kernel(BwdArgs a) {
-  constexpr int SP = 8;                                          // pages a step stages, one per wavefront
+template <int SP>                                                // pages a step stages, one per wavefront
+__global__ __launch_bounds__(64 * SP) void attn_bwd_dq_mfma_kernel(BwdArgs a) {
   __shared__ __attribute__((aligned(1024))) bf16_t kb0[SP * TILE16];
   __shared__ __attribute__((aligned(1024))) bf16_t kb1[SP * TILE16];
   __shared__ __attribute__((aligned(1024))) bf16_t vb0[SP * VPAGE];
@@ -244,7 +244,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_mfma_kernel(BwdArgs a) {
   // ---- add the four key quarters (kh = 0, 1, 2, 3 in this order), scale, store -------------------
   float* red = reinterpret_cast<float*>(kb0);                    // [2 rt][32][64 lanes] floats = 16 KB
 #pragma unroll 1
-  for (int src = 1; src < 4; ++src) {
+  for (int src = 1; src < SP / 2; ++src) {
     __syncthreads();
     if (kh == src) {
 #pragma unroll
@@ -460,7 +460,10 @@ int32_t launch_attention_bwd_mfma(const flexco_layer_cfg& c, const flexco_kv_poo
   a.w0 = win_start; a.s = win_len; a.l = win_start + win_len; a.nq = c.n_q_heads; a.nkv = c.n_kv_heads;
   a.scale = 1.0f / sqrtf((float)D);
   a.scale_log2 = a.scale * LOG2E;
-  hipLaunchKernelGGL(attn_bwd_dq_mfma_kernel, dim3((a.s + 31) / 32, a.nq), dim3(512), 0, s, a);
+#ifndef FLEXCO_DQ_SP
+#define FLEXCO_DQ_SP 8
+#endif
+  hipLaunchKernelGGL(attn_bwd_dq_mfma_kernel<FLEXCO_DQ_SP>, dim3((a.s + 31) / 32, a.nq), dim3(64 * FLEXCO_DQ_SP), 0, s, a);
   hipLaunchKernelGGL(attn_bwd_dkv_mfma_kernel, dim3((a.l + 63) / 64, a.nkv), dim3(512), 0, s, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(FLEXCO_EHIP, "launch of attn_bwd_mfma failed: %s", hipGetErrorString(e));

@@ -52,7 +52,10 @@ def say(msg):
                                          (300, 49160, 320, 0), (520, 24584, 192, 0), (256, 49152, 64, 0),
                                          # 192-wide tiles (one round of 128 x 192), ragged in N; 256-wide and
                                          # 192-wide tiles side by side in one product
-                                         (1024, 6152, 128, 0), (1024, 28672, 64, 0), (1000, 28680, 128, 0)])
+                                         (1024, 6152, 128, 0), (1024, 28672, 64, 0), (1000, 28680, 128, 0),
+                                         # more 128 x 128 tiles than CUs (450): the two-stage blocks that share a CU, ragged in
+                                         # M and N, odd number of k-stages
+                                         (1100, 6344, 320, 0)])
 def test_gemm(dtype, M, N, K, trans):
     say(f"gemm {dtype} M={M} N={N} K={K} trans={trans}")
     cfg = C1.with_(dtype=dtype)
