@@ -183,10 +183,12 @@ def test_attention_mixed(name, split):
     ("c1", 5, 6),                   # fp32 generic path
     ("small_bf16", 3840, 256),      # the last window of a 4096-token sequence
     ("small_bf16", 8000, 192),      # of an 8192-token one
+    ("c2", 203, 530),               # 17 row blocks x 32 heads: the grid of two blocks per CU (dQ kernel with four pages per
+                                    # step), 46 pages (not a multiple of 4), ragged start and end
 ])
 def test_attention_window_bwd(cfg_name, win_start, win_len):
     say(f"attention_window_bwd {cfg_name} window [{win_start}, +{win_len})")
-    cfg = {"small_bf16": SMALL_BF16, "g5": SMALL_BF16_G5, "mha": SMALL_BF16_MHA, "g8": SMALL_BF16_G8, "c1": C1}[cfg_name]
+    cfg = {"small_bf16": SMALL_BF16, "g5": SMALL_BF16_G5, "mha": SMALL_BF16_MHA, "g8": SMALL_BF16_G8, "c1": C1, "c2": C2}[cfg_name]
     l = win_start + win_len
     ps = cfg.page_size
     n_pages = (l + ps - 1) // ps
