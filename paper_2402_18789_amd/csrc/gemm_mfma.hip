@@ -254,6 +254,77 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
   constexpr int WAIT_NEXT_STAGE = NST == 4 ? FLEXCO_VMCNT(NLD) : FLEXCO_VMCNT(0);
   // the buffer freed at stage s's barrier held stage s - 1 (four stages) or stage s itself (two)
   constexpr int AHEAD = NST == 4 ? 3 : 2;
+  // ---- operands of the rank-r extension's first step and the residual / bias of the epilogue, fetched ahead of the
+  // main loop (128-row tiles: the registers are there; their round trips - one or two per block, all blocks
+  // ending together - otherwise lie open at the end of the launch) --------------------------------------------
+  // forward form: an entry covers a column range whose ends are multiples of 32, so each 32-column
+  // fragment of the tile belongs to at most one entry; fragments outside this entry multiply zeros
+#define FLEXCO_EXT_SKIPS(e_) (!TRANS && !GLU && (n0 + BN <= ext.col0[e_] || n0 >= ext.col1[e_]))
+#define FLEXCO_EXT_LOAD(e_, k2_, af_, bfr_)                                                           \
+  {                                                                                                   \
+    const bf16_t* A2_ = ext.A2[e_];                                                                   \
+    const bf16_t* W2_ = ext.W2[e_];                                                                   \
+    _Pragma("unroll") for (int i = 0; i < MT; ++i) {                                                  \
+      const int r_ = min(m0 + wm0 + i * 32 + l32, M - 1);                                             \
+      af_[i] = *reinterpret_cast<const bf16x8*>(A2_ + (size_t)r_ * ext.r + (k2_) + kg * 8);           \
+    }                                                                                                 \
+    _Pragma("unroll") for (int j = 0; j < NT; ++j) {                                                  \
+      if (GLU) {                                                                                      \
+        /* this lane's W-tile row is a gate or an up row: column of the [gate | up] range the entries address */ \
+        const int ac_ = glu.col0 + tn * (BN / 2) + ((wn0 + j * 32) >> 1) + (l32 & 15);                \
+        const int lc_ = (l32 >> 4) * glu.F + ac_;                                                     \
+        if (ac_ < glu.F && lc_ >= ext.col0[e_] && lc_ < ext.col1[e_]) {                               \
+          bfr_[j] = *reinterpret_cast<const bf16x8*>(W2_ + (size_t)(lc_ - ext.col0[e_]) * ext.ldw2[e_] + (k2_) + kg * 8); \
+        } else {                                                                                      \
+          _Pragma("unroll") for (int q = 0; q < 8; ++q) bfr_[j][q] = (bf16_t)0.f;                     \
+        }                                                                                             \
+      } else if (!TRANS) {                                                                            \
+        const int cj_ = n0 + wn0 + j * 32;                                                            \
+        if (cj_ >= ext.col0[e_] && cj_ < ext.col1[e_]) {                                              \
+          const int c_ = min(cj_ + l32, ext.col1[e_] - 1) - ext.col0[e_];                             \
+          bfr_[j] = *reinterpret_cast<const bf16x8*>(W2_ + (size_t)c_ * ext.ldw2[e_] + (k2_) + kg * 8); \
+        } else {                                                                                      \
+          _Pragma("unroll") for (int q = 0; q < 8; ++q) bfr_[j][q] = (bf16_t)0.f;                     \
+        }                                                                                             \
+      } else {                                                                                        \
+        const int c_ = min(n0 + wn0 + j * 32 + l32, N - 1);                                           \
+        _Pragma("unroll") for (int q = 0; q < 8; ++q) bfr_[j][q] = W2_[(size_t)((k2_) + kg * 8 + q) * ext.ldw2[e_] + c_]; \
+      }                                                                                               \
+    }                                                                                                 \
+  }
+  constexpr bool PF = MT * NT <= 4;
+  int e_first = -1;
+  bf16x8 paf[PF ? MT : 1], pbf[PF ? NT : 1];
+  if constexpr (PF) {
+    if (blockIdx.y == 0) {
+      for (int e = 0; e < ext.n; ++e)
+        if (!FLEXCO_EXT_SKIPS(e)) { e_first = e; break; }
+      if (e_first >= 0) FLEXCO_EXT_LOAD(e_first, 0, paf, pbf)
+    }
+  }
+  // residual and bias in the layout the epilogue stores in: 8 lanes x 8 columns per row, 8 rows per instruction,
+  // 32 rows x 64 columns per group of two fragments
+  constexpr int NG = (NT + 1) / 2;
+  constexpr bool PF_RES = !GLU && MT * NT <= 6;
+  bf16x8 rpre[PF_RES ? MT : 1][PF_RES ? NG : 1][4];
+  bf16x8 bpre[PF_RES ? NG : 1];
+  if constexpr (PF_RES) if (!part) {
+#pragma unroll
+    for (int j0 = 0; j0 < NT; j0 += 2) {
+      const int col = n0 + wn0 + j0 * 32 + (lane & 7) * 8;
+      const bool col_ok = (lane & 7) * 8 < ((j0 + 1 < NT) ? 64 : 32) && col < N;
+      if (bias && col_ok) bpre[j0 / 2] = *reinterpret_cast<const bf16x8*>(bias + col);
+      if (res) {
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+          for (int p = 0; p < 4; ++p) {
+            const int row = m0 + wm0 + i * 32 + p * 8 + (lane >> 3);
+            if (col_ok && row < M) rpre[i][j0 / 2][p] = *reinterpret_cast<const bf16x8*>(res + (size_t)row * ldr + col);
+          }
+      }
+    }
+  }
   bf16x8 af0[MT], bf0[NT], af1[MT], bf1[NT];
   if constexpr (NST == 4) {
     FLEXCO_DMA(ring0, 0)
@@ -289,46 +360,22 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
   // block) or C += sum_e A2_e W2_e (input-gradient form; every entry).  This is the LoRA bypass
   // network (Sec. 4.1) folded into the base projection as extra k-steps of 16, operands read
   // straight from global memory (they are [rows, r] / [r, cols] matrices of a few KB per tile).
+  // The first step's operands were fetched before the main loop where the tile leaves registers for them.
   for (int e = 0; e < (blockIdx.y == 0 ? ext.n : 0); ++e) {
-    // forward form: an entry covers a column range whose ends are multiples of 32, so each 32-column
-    // fragment of the tile belongs to at most one entry; fragments outside this entry multiply zeros
-    if (!TRANS && !GLU && (n0 + BN <= ext.col0[e] || n0 >= ext.col1[e])) continue;
-    const bf16_t* A2 = ext.A2[e];
-    const bf16_t* W2 = ext.W2[e];
+    if (FLEXCO_EXT_SKIPS(e)) continue;
     for (int k2 = 0; k2 < ext.r; k2 += 16) {
       bf16x8 af[MT], bfr[NT];
+      bool have = false;
+      if constexpr (PF) {
+        if (e == e_first && k2 == 0) {
 #pragma unroll
-      for (int i = 0; i < MT; ++i) {
-        const int r = min(m0 + wm0 + i * 32 + l32, M - 1);
-        af[i] = *reinterpret_cast<const bf16x8*>(A2 + (size_t)r * ext.r + k2 + kg * 8);
-      }
+          for (int i = 0; i < MT; ++i) af[i] = paf[i];
 #pragma unroll
-      for (int j = 0; j < NT; ++j) {
-        if (GLU) {
-          // this lane's W-tile row is a gate or an up row: column of the [gate | up] range the entries address
-          const int ac = glu.col0 + tn * (BN / 2) + ((wn0 + j * 32) >> 1) + (l32 & 15);
-          const int lc = (l32 >> 4) * glu.F + ac;
-          if (ac < glu.F && lc >= ext.col0[e] && lc < ext.col1[e]) {
-            bfr[j] = *reinterpret_cast<const bf16x8*>(W2 + (size_t)(lc - ext.col0[e]) * ext.ldw2[e] + k2 + kg * 8);
-          } else {
-#pragma unroll
-            for (int q = 0; q < 8; ++q) bfr[j][q] = (bf16_t)0.f;
-          }
-        } else if (!TRANS) {
-          const int cj = n0 + wn0 + j * 32;
-          if (cj >= ext.col0[e] && cj < ext.col1[e]) {
-            const int c = min(cj + l32, ext.col1[e] - 1) - ext.col0[e];
-            bfr[j] = *reinterpret_cast<const bf16x8*>(W2 + (size_t)c * ext.ldw2[e] + k2 + kg * 8);
-          } else {
-#pragma unroll
-            for (int q = 0; q < 8; ++q) bfr[j][q] = (bf16_t)0.f;
-          }
-        } else {
-          const int c = min(n0 + wn0 + j * 32 + l32, N - 1);
-#pragma unroll
-          for (int q = 0; q < 8; ++q) bfr[j][q] = W2[(size_t)(k2 + kg * 8 + q) * ext.ldw2[e] + c];
+          for (int j = 0; j < NT; ++j) bfr[j] = pbf[j];
+          have = true;
         }
       }
+      if (!have) FLEXCO_EXT_LOAD(e, k2, af, bfr)
 #pragma unroll
       for (int i = 0; i < MT; ++i)
 #pragma unroll
@@ -336,7 +383,6 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
     }
   }
-
   // ---- epilogue: register 4 q + e of acc[i][j] is row lane % 32, column 8 q + 4 (lane / 32) + e of
   // the 32 x 32 block.  Stored as they lie, an instruction would touch 32 rows with 16 (bf16) or 32 (fp32)
   // bytes each; measured, such stores run at about 1 TB/s where whole 128-byte lines reach 3.5.  So every
@@ -440,12 +486,14 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
 #pragma unroll
             for (int e = 0; e < 4; ++e) { v[e] = lo[e]; v[4 + e] = hi[e]; }
             if (bias) {
-              const bf16x8 b8 = *reinterpret_cast<const bf16x8*>(bias + col);
+              bf16x8 b8;
+              if constexpr (PF_RES) b8 = bpre[j0 / 2]; else b8 = *reinterpret_cast<const bf16x8*>(bias + col);
 #pragma unroll
               for (int e = 0; e < 8; ++e) v[e] += (float)b8[e];
             }
             if (res) {
-              const bf16x8 r8 = *reinterpret_cast<const bf16x8*>(res + (size_t)row * ldr + col);
+              bf16x8 r8;
+              if constexpr (PF_RES) r8 = rpre[i][j0 / 2][p]; else r8 = *reinterpret_cast<const bf16x8*>(res + (size_t)row * ldr + col);
 #pragma unroll
               for (int e = 0; e < 8; ++e) v[e] += (float)r8[e];
             }
