@@ -185,6 +185,7 @@ def test_attention_mixed(name, split):
     ("small_bf16", 8000, 192),      # of an 8192-token one
     ("c2", 203, 530),               # 17 row blocks x 32 heads: the grid of two blocks per CU (dQ kernel with four pages per
                                     # step), 46 pages (not a multiple of 4), ragged start and end
+    ("c2", 2100, 77),               # 35 key blocks x 8 kv heads: more dK/dV blocks than CUs (four-wavefront blocks)
 ])
 def test_attention_window_bwd(cfg_name, win_start, win_len):
     say(f"attention_window_bwd {cfg_name} window [{win_start}, +{win_len})")
