@@ -102,15 +102,17 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(FwdArgs a, const bf1
   bf16x8 kf[2][4];     // [page of the pair][d chunk]
   bf16x4 vf[2][8];     // [page of the pair][d tile]
 
-  // page ids of the whole split, one per lane (split_pages <= 64): no dependent table load per step
+  // page ids of the whole split, two per lane (split_pages <= 128): no dependent table load per step
+  // (four per lane, for splits of 256 pages, cost nine spilled registers and 20 us)
   const int npg = pe - pb;
   const int my_page = a.block_table[(size_t)r * a.max_pages + (lane < npg ? pb + lane : pb)];
+  const int my_page_hi = a.block_table[(size_t)r * a.max_pages + (64 + lane < npg ? pb + 64 + lane : pb)];
 
   auto load_pair = [&](int rel, bf16x8 (&kk)[2][4], bf16x4 (&vv)[2][8]) {
 #pragma unroll
     for (int x = 0; x < 2; ++x) {
       const int pidx = (rel + x < npg) ? rel + x : rel;
-      const size_t page = (size_t)__builtin_amdgcn_readlane(my_page, pidx);
+      const size_t page = (size_t)__builtin_amdgcn_readlane(pidx < 64 ? my_page : my_page_hi, pidx & 63);   // pidx is wavefront-uniform
       const bf16_t* kpage = kp + ((page * a.nkv + kvh) * PS + c) * (size_t)D + g * 8;
 #pragma unroll
       for (int dc = 0; dc < 4; ++dc) kk[x][dc] = *reinterpret_cast<const bf16x8*>(kpage + dc * 32);
@@ -264,7 +266,7 @@ int32_t launch_attention_mfma(const flexco_layer_cfg& c, const flexco_maps& m, c
                               float* lse, hipStream_t s, const AttnKeep* keep) {
   const int group = c.n_q_heads / c.n_kv_heads;
   if (c.dtype != FLEXCO_BF16 || c.head_dim != D || c.page_size != PS || group > 16 || ldq % 8 != 0 ||
-      m.kv_split_pages > 64 || ldo % 4 != 0 || ((uintptr_t)out & 7))
+      m.kv_split_pages > 128 || ldo % 4 != 0 || ((uintptr_t)out & 7))
     return FLEXCO_EUNSUPPORTED;
   FwdArgs a;
   a.tok_pos = m.tok_pos; a.block_table = m.block_table; a.tile_req = m.tile_req; a.tile_tok0 = m.tile_tok0;
