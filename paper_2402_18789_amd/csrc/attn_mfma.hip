@@ -44,6 +44,7 @@ struct FwdArgs {
 
 constexpr int D = 128, PS = 16;
 constexpr int NC = FLEXCO_ATTN_ITEM_TILES;   // column tiles one work item may carry
+constexpr int MAXSP = 256;                   // pages of a key split at most
 
 // A work item carries 1 .. NC neighbouring column tiles of one request (a decode token: one).  The
 // wavefront loads every K/V page of the item's key range once and multiplies it against each tile in
@@ -55,6 +56,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(FwdArgs a, const bf1
                                                             const bf16_t* __restrict__ vp,
                                                             float* __restrict__ part_ml,
                                                             float* __restrict__ part_acc) {
+  __shared__ int page_tab[4][MAXSP];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   // consecutive wavefronts take the kv heads of one item: the K (and V) blocks they read are the
   // consecutive 4 KB pieces of the same pages, fetched at about the same time
@@ -102,17 +104,21 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(FwdArgs a, const bf1
   bf16x8 kf[2][4];     // [page of the pair][d chunk]
   bf16x4 vf[2][8];     // [page of the pair][d tile]
 
-  // page ids of the whole split, two per lane (split_pages <= 128): no dependent table load per step
-  // (four per lane, for splits of 256 pages, cost nine spilled registers and 20 us)
+  // page ids of the whole split in a table of the wavefront's own in LDS (split_pages <= MAXSP; the kernel has no
+  // other use for LDS): no dependent load from global memory per step, no registers held for them.  Written and
+  // read by this wavefront only, whose LDS operations execute in order: no barrier.
   const int npg = pe - pb;
-  const int my_page = a.block_table[(size_t)r * a.max_pages + (lane < npg ? pb + lane : pb)];
-  const int my_page_hi = a.block_table[(size_t)r * a.max_pages + (64 + lane < npg ? pb + 64 + lane : pb)];
+  int* ptab = page_tab[wave];
+#pragma unroll
+  for (int q4 = 0; q4 < MAXSP / 64; ++q4)
+    if (q4 == 0 || 64 * q4 < npg)   // wavefront-uniform
+      ptab[64 * q4 + lane] = a.block_table[(size_t)r * a.max_pages + (64 * q4 + lane < npg ? pb + 64 * q4 + lane : pb)];
 
   auto load_pair = [&](int rel, bf16x8 (&kk)[2][4], bf16x4 (&vv)[2][8]) {
 #pragma unroll
     for (int x = 0; x < 2; ++x) {
       const int pidx = (rel + x < npg) ? rel + x : rel;
-      const size_t page = (size_t)__builtin_amdgcn_readlane(pidx < 64 ? my_page : my_page_hi, pidx & 63);   // pidx is wavefront-uniform
+      const size_t page = (size_t)__builtin_amdgcn_readfirstlane(ptab[pidx]);   // pidx is wavefront-uniform
       const bf16_t* kpage = kp + ((page * a.nkv + kvh) * PS + c) * (size_t)D + g * 8;
 #pragma unroll
       for (int dc = 0; dc < 4; ++dc) kk[x][dc] = *reinterpret_cast<const bf16x8*>(kpage + dc * 32);
@@ -266,7 +272,7 @@ int32_t launch_attention_mfma(const flexco_layer_cfg& c, const flexco_maps& m, c
                               float* lse, hipStream_t s, const AttnKeep* keep) {
   const int group = c.n_q_heads / c.n_kv_heads;
   if (c.dtype != FLEXCO_BF16 || c.head_dim != D || c.page_size != PS || group > 16 || ldq % 8 != 0 ||
-      m.kv_split_pages > 128 || ldo % 4 != 0 || ((uintptr_t)out & 7))
+      m.kv_split_pages > MAXSP || ldo % 4 != 0 || ((uintptr_t)out & 7))
     return FLEXCO_EUNSUPPORTED;
   FwdArgs a;
   a.tok_pos = m.tok_pos; a.block_table = m.block_table; a.tile_req = m.tile_req; a.tile_tok0 = m.tile_tok0;

@@ -656,6 +656,7 @@ int32_t run_attention(const flexco_layer_cfg& c, const flexco_maps& m, const voi
     rc = launch_attention_generic(c, m, q, ldq, pool, part_ml, part_acc, s);
   }
   if (rc) return rc;
+  if (direct && m.n_parts == m.n_tiles) return FLEXCO_OK;   // every tile had a single key split: nothing left to merge
   KernelTimerScope ts(FLEXCO_K_ATTN_MERGE, s);
   return launch_attention_merge(c, m, part_ml, part_acc, out, ldo, lse, s, direct, keep);
 }

@@ -55,12 +55,18 @@ int32_t build(const flexco_batch_desc* d, int32_t page_size, int32_t num_pages, 
   const int n_req = d->n_req;
   b.split_pages = kv_split_pages;
   if (kv_split_pages <= 0) {
-    // Default: 128 pages per split (the most the attention kernel's page-id registers hold; measured against 64
-    // on the benchmark batch: the attention kernel 3 % and the merge kernel a third faster).  A batch of few
+    // Default: 128 pages per split (measured against 64 on the benchmark batch: the attention kernel 3 % and the
+    // merge kernel a third faster) - or 256, the most the attention kernel's page-id table holds, when no request
+    // sees more pages than that: then no tile is split and the merge launch falls away (measured: 1.2 % of the
+    // benchmark step; where longer contexts keep the merge, 256 was 0.3 % slower than 128).  A batch of few
     // requests would leave most of the chip without an attention work item (one wavefront per item and kv
-    // head): take the largest of 128, 64, 32, 16, 8 pages that gives at least 1024 wavefronts, else 8.
+    // head): take the largest of these, 64, 32, 16, 8 pages that gives at least 1024 wavefronts, else 8.
+    int64_t max_vis = 0;
+    for (int r = 0; r < n_req; ++r)
+      if (d->n_new[r] > 0 && d->start_pos[r] >= 0 && page_size > 0)
+        max_vis = std::max<int64_t>(max_vis, ((int64_t)d->start_pos[r] + d->n_new[r] - 1) / page_size + 1);
     b.split_pages = 8;
-    for (int cand = 128; cand >= 16; cand /= 2) {
+    for (int cand = max_vis <= 256 ? 256 : 128; cand >= 16; cand /= 2) {
       int64_t items = 0;
       for (int r = 0; r < n_req; ++r) {
         if (d->n_new[r] <= 0 || d->start_pos[r] < 0 || page_size <= 0) continue;   // rejected below
