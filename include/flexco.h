@@ -148,6 +148,8 @@ typedef struct flexco_maps {
   int32_t ft_adapter;                  /* adapter id of the finetune request (-1: none)   */
   int32_t num_pages;                   /* pool size the page ids were checked against: a call that takes
                                           these maps and a pool with fewer pages fails with FLEXCO_EPAGE */
+  int32_t n_single;                    /* work items that are one tile of one token: the decode stream (and a
+                                          chunk's last token where it falls into an item of its own)          */
   int32_t adapter_tok_off[FLEXCO_MAX_ADAPTERS + 1];   /* lora_tok[off[a] .. off[a+1]) = tokens of adapter a */
   const int32_t* tok_req;       /* [T]                                                    */
   const int32_t* tok_pos;       /* [T]                                                    */
@@ -457,6 +459,15 @@ int32_t flexco_kernel_timer_sample(int32_t kernel_id, int32_t stride);
  * [FLEXCO_N_KERNEL_IDS] (host) receives, per kernel class (FLEXCO_K_GEMM_FWD, _GEMM_BWD, _ATTN_FWD, _ATTN_BWD; the
  * other entries stay 0), how many bf16 launches of this process took that route; reset != 0 clears the counters. */
 int32_t flexco_bf16_fallbacks(int64_t* counts, int32_t reset);
+
+/* Which kernel takes the chunk items of the attention work list - prefill chunks and finetune windows, whose tokens
+ * follow the causal pattern of prefill (Sec. 6.2) - in flexco_layer_forward*, flexco_model_forward and
+ * flexco_attention_mixed: 0 = the kernel that also streams the decode tokens (one wavefront per work item), 1 = a
+ * kernel of their own (four wavefronts per work item, K / V pages staged in LDS; the decode tokens stay where they
+ * are), -1 = chosen by batch (the default: the kernel of their own when the work list has no single-token item, i.e.
+ * nothing to stream beside them).  Both kernels do the same arithmetic per column tile.  Process-wide; returns
+ * FLEXCO_EINVAL for other values. */
+int32_t flexco_attention_chunk_path(int32_t mode);
 
 /* ---- Static graph pruning (Alg. 1, Sec. 5.2), host only -------------------------------------
  * The forward graph of a PEFT model as integer arrays: operator o has kind op_kind[o], one output

@@ -23,7 +23,7 @@ FLEXCO_DECODE, FLEXCO_PREFILL, FLEXCO_FINETUNE = 0, 1, 2
 FLEXCO_REQ_WAITING, FLEXCO_REQ_RUNNING, FLEXCO_REQ_FINISHED = 0, 1, 2
 TARGET_NAMES = ("q", "k", "v", "o", "gate", "up", "down")
 N_TARGETS = 7
-ABI_VERSION = 5
+ABI_VERSION = 6
 
 
 class FlexcoError(RuntimeError):
@@ -54,7 +54,7 @@ class BatchDesc(C.Structure):
 
 _MAP_SCALARS = ("T", "n_req", "n_ft", "n_seg", "max_pages", "page_size", "n_tiles", "n_items", "n_parts",
                 "tile_tokens", "kv_split_pages", "ft_req", "ft_tok0", "ft_pos0", "n_lora", "max_kv_len", "blob_ints", "n_adapters", "ft_adapter",
-                "num_pages")
+                "num_pages", "n_single")
 _MAP_ARRAYS = ("tok_req", "tok_pos", "slot", "req_tok_off", "req_kv_len", "req_kind", "block_table", "ft_tok",
                "seg_off", "seg_adapter", "lora_tok", "tile_req", "tile_tok0", "tile_ntok", "tile_nsplit",
                "tile_part0", "item_tile", "item_split", "tok_tile", "tok_lora", "tok_adapter", "item_ntiles")
@@ -148,6 +148,7 @@ def _load():
         "flexco_relu_bitmask_fwd": [vp, vp, vp, i32, i32, i32, vp],
         "flexco_relu_bitmask_bwd": [vp, vp, vp, i32, i32, i32, vp],
         "flexco_bf16_fallbacks": [P(C.c_int64), i32],
+        "flexco_attention_chunk_path": [i32],
         "flexco_kernel_timer_sample": [i32, i32],
         "flexco_kernel_timer_read": [i32, P(C.c_double), C.c_int64, P(C.c_int64)],
         "flexco_probe_mfma_lds": [i32, i32, i32, vp, sz, vp, P(C.c_double), vp],
@@ -181,7 +182,7 @@ EXPORTS = ("flexco_last_error", "flexco_abi_version", "flexco_maps_blob_ints", "
            "flexco_lm_loss_workspace_bytes", "flexco_lm_loss", "flexco_adam_step", "flexco_prune_graph",
            "flexco_layer_forward_ia3", "flexco_ia3_bwd", "flexco_adapter_workspace_bytes", "flexco_adapter_fwd",
            "flexco_adapter_bwd", "flexco_model_forward", "flexco_model_backward",
-           "flexco_relu_bitmask_fwd", "flexco_relu_bitmask_bwd", "flexco_bf16_fallbacks")
+           "flexco_relu_bitmask_fwd", "flexco_relu_bitmask_bwd", "flexco_bf16_fallbacks", "flexco_attention_chunk_path")
 KERNEL_IDS = {"gemm_fwd": 0, "gemm_bwd": 1, "attn_fwd": 2, "attn_merge": 3, "attn_bwd": 4, "elemwise": 5, "lora": 6,
               "generic": 7}
 
@@ -483,6 +484,10 @@ def flexco_bf16_fallbacks(reset=False):
     buf = (C.c_int64 * len(KERNEL_IDS))()
     _check(_lib.flexco_bf16_fallbacks(buf, int(bool(reset))))
     return {name: int(buf[i]) for name, i in KERNEL_IDS.items()}
+
+
+def flexco_attention_chunk_path(mode):
+    _check(_lib.flexco_attention_chunk_path(int(mode)))
 
 
 def target_dims_py(cfg, t):

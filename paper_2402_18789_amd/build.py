@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.environ.get("FLEXCO_BUILD_OBJ", os.path.join(ROOT, "_build"))
 LIB = os.environ.get("FLEXCO_BUILD_LIB", os.path.join(HERE, "libflexco.so"))
 SOURCES = ["flexco_maps.cpp", "flexco_sched.cpp", "flexco_prune.cpp", "flexco_api.hip", "kernels_generic.hip", "attn_generic.hip", "gemm_mfma.hip",
-           "attn_mfma.hip", "lora_mfma.hip", "attn_bwd_mfma.hip", "probes.hip", "train_head.hip", "relu_bitmask.hip"]
+           "attn_mfma.hip", "attn_chunk_mfma.hip", "lora_mfma.hip", "attn_bwd_mfma.hip", "probes.hip", "train_head.hip", "relu_bitmask.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC, "-Wno-unused-command-line-argument",

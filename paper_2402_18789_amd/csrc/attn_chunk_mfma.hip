@@ -1,0 +1,290 @@
+// Mixed paged attention, the chunk items on their own: prefill chunks and finetune windows whose rows are many
+// (Sec. 6.2: finetuning tokens follow the causal pattern of prefill).
+//
+// The one-launch kernel of attn_mfma.hip gives a work item - up to four column tiles of one request x one key
+// split - to ONE wavefront, which fetches K / V pages from global memory into registers and multiplies them
+// against its tiles one after the other.  That suits the decode stream (one tile per item, the time is HBM's).
+// For long windows the time is the wavefront's own chain of products and exponentials per tile, four tiles deep,
+// with one wavefront per SIMD to run it.  Here the same item goes to a BLOCK of four wavefronts, one tile each:
+// the K / V pages of a step are staged once per block in LDS (straight from global memory, a ring of four stages
+// of two pages) and every wavefront reads its operands from there; 64 KB of LDS and under 256 registers put two
+// blocks on a CU.  Same arithmetic per tile, same partial rows and direct outputs as the one-launch kernel, so
+// the merge kernel and everything after see no difference.
+//
+// bf16, head_dim 128, page_size 16, at most 16 query heads per kv head.
+#include "flexco_internal.h"
+#include "device_types.h"
+
+namespace flexco {
+
+namespace {
+
+constexpr int D = 128, PS = 16;
+constexpr int PAGE_EL = PS * D;          // elements of one K page-head block (16 keys x 128) = of one V block (128 x 16)
+constexpr int STAGE_EL = 4 * PAGE_EL;    // K page 0 | K page 1 | V page 0 | V page 1
+constexpr int MAXSP = 256;               // pages of a key split at most
+#define FLEXCO_GP(p) ((const __attribute__((address_space(1))) void*)(p))
+#define FLEXCO_LP(p) ((__attribute__((address_space(3))) void*)(p))
+
+struct ChunkArgs {
+  const int32_t *tok_pos, *block_table, *tile_req, *tile_tok0, *tile_ntok, *tile_nsplit, *tile_part0, *item_tile,
+      *item_split, *item_ntiles;
+  int max_pages, nq, nkv, n_items, split_pages;
+  float scale_log2;   // log2(e) / sqrt(d)
+  bf16_t* out;
+  size_t ldo;
+  float* lse;         // or NULL
+  AttnKeep keep;
+};
+
+// K rows in LDS ([16 keys][128] bf16, 256-byte rows): chunk cc of row r is stored at chunk cc ^ rsw(r), so that the
+// ds_read_b128 of lane (key = lane % 16, g = lane / 16) - served 16 lanes a cycle in quads {0-3, 12-15, 20-23, 24-27},
+// {4-7, 8-11, 16-19, 28-31} (+32) - touches 16 different chunks per cycle.
+__device__ inline int rsw(int r) { return (((r + ((r >> 3) << 2)) & 7) << 1) | ((r >> 3) & 1); }
+
+__global__ __launch_bounds__(256, 2) void attn_fwd_chunk_kernel(ChunkArgs a, const bf16_t* __restrict__ q, size_t ldq,
+                                                                const bf16_t* __restrict__ kp,
+                                                                const bf16_t* __restrict__ vp,
+                                                                float* __restrict__ part_ml,
+                                                                float* __restrict__ part_acc) {
+  __shared__ __attribute__((aligned(1024))) bf16_t ring0[STAGE_EL];
+  __shared__ __attribute__((aligned(1024))) bf16_t ring1[STAGE_EL];
+  __shared__ __attribute__((aligned(1024))) bf16_t ring2[STAGE_EL];
+  __shared__ __attribute__((aligned(1024))) bf16_t ring3[STAGE_EL];
+  __shared__ int page_tab[MAXSP];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int item = blockIdx.x / a.nkv, kvh = blockIdx.x % a.nkv;
+  const int tile0 = a.item_tile[item], split = a.item_split[item];
+  const int ntl = a.item_ntiles[item];
+  if (ntl == 1 && a.tile_ntok[tile0] == 1) return;   // a decode token: the one-launch kernel's (whole block, before any barrier)
+  const int r = a.tile_req[tile0];
+  const int group = a.nq / a.nkv;
+  const int c = lane & 15, g = lane >> 4;
+  // the item's keys: up to the last position of its last tile
+  const int tl = tile0 + ntl - 1;
+  const int last_pos = a.tok_pos[a.tile_tok0[tl] + a.tile_ntok[tl] - 1];
+  const int vis_pages = last_pos / PS + 1;
+  const int first_pos = a.tok_pos[a.tile_tok0[tile0]];   // the item's first column sees the fewest keys
+  const int pb = split * a.split_pages;
+  const int pe = min(pb + a.split_pages, vis_pages);
+  const int npg = pe - pb;                               // >= 1: an item exists for splits inside the visible range only
+  page_tab[tid] = a.block_table[(size_t)r * a.max_pages + (tid < npg ? pb + tid : pb)];   // MAXSP = block size
+  __syncthreads();
+
+  // this wavefront's tile (wavefronts past the item's last tile only help with the loads and the barriers)
+  const bool have = wave < ntl;
+  const int tile = tile0 + (have ? wave : 0);
+  bf16x8 qf[4];
+  int pos_c = -1;
+  f32x4 o[8];
+  float m = -INFINITY, l = 0.f;
+#pragma unroll
+  for (int mt = 0; mt < 8; ++mt) o[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  {
+    const int t0 = a.tile_tok0[tile], ntok = a.tile_ntok[tile];
+    const bool col_ok = have && c < ntok * group;
+    const int t_c = col_ok ? t0 + c / group : t0;
+    const int h_c = kvh * group + (col_ok ? c % group : 0);
+    pos_c = col_ok ? a.tok_pos[t_c] : -1;
+    const bf16_t* qr = q + (size_t)t_c * ldq + h_c * D + g * 8;
+#pragma unroll
+    for (int dc = 0; dc < 4; ++dc) qf[dc] = *reinterpret_cast<const bf16x8*>(qr + dc * 32);
+  }
+
+  // ---- tile loads: a stage = the two pages 2 st, 2 st + 1 of the split; wavefront w brings in, of each page, K rows
+  // 4 w .. 4 w + 3 (lane -> row 4 w + lane / 16, physical chunk lane % 16) and the V chunks 64 w .. 64 w + 63 of the
+  // page's 256 (a V page is [128 d][16 keys]: 32-byte rows, two chunks; physical chunk P holds logical chunk
+  // P ^ (bit 4 of P), which swaps the halves of rows d = 8 .. 15 (mod 16) so that the 8-byte reads of 32 lanes - 16
+  // rows, the same half of each - cover all banks).  Past the last stage the loads repeat it into a free buffer:
+  // the count of loads in flight stays what the waits assume.
+  const int nst = (npg + 1) / 2;
+  const int k_row = 4 * wave + (lane >> 4);
+  const int k_src = k_row * D + (((lane & 15) ^ rsw(k_row)) * 8);
+  const int v_p = 64 * wave + lane;
+  const int v_src = (v_p ^ ((v_p >> 4) & 1)) * 8;
+#define FLEXCO_CH_ISSUE(ring_, st_)                                                                   \
+  {                                                                                                   \
+    const int s2_ = 2 * min((st_), nst - 1);                                                          \
+    _Pragma("unroll") for (int x = 0; x < 2; ++x) {                                                   \
+      const size_t page_ = (size_t)__builtin_amdgcn_readfirstlane(page_tab[min(s2_ + x, npg - 1)]);   \
+      const bf16_t* kb_ = kp + (page_ * a.nkv + kvh) * (size_t)PAGE_EL;                               \
+      const bf16_t* vb_ = vp + (page_ * a.nkv + kvh) * (size_t)PAGE_EL;                               \
+      __builtin_amdgcn_global_load_lds(FLEXCO_GP(kb_ + k_src), FLEXCO_LP(ring_ + x * PAGE_EL + wave * 512), 16, 0, 0); \
+      __builtin_amdgcn_global_load_lds(FLEXCO_GP(vb_ + v_src), FLEXCO_LP(ring_ + (2 + x) * PAGE_EL + wave * 512), 16, 0, 0); \
+    }                                                                                                 \
+  }
+  // wait until this wavefront's loads of the stage about to be multiplied have landed (two later stages, 4 loads
+  // each, may stay in flight), then a barrier without memory fences
+#define FLEXCO_CH_WAIT_BARRIER                   \
+  {                                              \
+    __builtin_amdgcn_s_waitcnt(0x0F70 | 8);      \
+    asm volatile("" ::: "memory");               \
+    __builtin_amdgcn_s_barrier();                \
+    asm volatile("" ::: "memory");               \
+  }
+
+  // ---- operand fetches of one stage: K rows as A operand of S^T = K Q^T, lane (key c, g): d = 32 dc + 8 g .. + 8;
+  // V as A operand of O^T += V^T P^T, lane (d = 16 mt + c, g): keys 4 g .. 4 g + 3 of each page
+  const int kr_off = c * D;
+  const int kr_sw = rsw(c);
+  const int vr_off = ((2 * c + (g >> 1)) ^ ((c >> 3) & 1)) * 8 + (g & 1) * 4;   // + 256 elements (32 chunks) per d tile mt
+
+  // one step = 32 keys (two pages) against the 16 columns of this wavefront's tile
+#define FLEXCO_CH_COMPUTE(ring_, st_)                                                                 \
+  if (have) {                                                                                         \
+    const int pp = pb + 2 * (st_);                                                                    \
+    bf16x8 kf[2][4];                                                                                  \
+    bf16x4 vf[2][8];                                                                                  \
+    _Pragma("unroll") for (int x = 0; x < 2; ++x) {                                                   \
+      _Pragma("unroll") for (int dc = 0; dc < 4; ++dc)                                                \
+        kf[x][dc] = *reinterpret_cast<const bf16x8*>(ring_ + x * PAGE_EL + kr_off + (((dc * 4 + g) ^ kr_sw) * 8)); \
+      _Pragma("unroll") for (int mt = 0; mt < 8; ++mt)                                                \
+        vf[x][mt] = *reinterpret_cast<const bf16x4*>(ring_ + (2 + x) * PAGE_EL + mt * 256 + vr_off);  \
+    }                                                                                                 \
+    /* V bits of slots past the item's last position may be unwritten memory */                       \
+    if ((pp + 2) * PS > last_pos + 1) {                                                               \
+      _Pragma("unroll") for (int x = 0; x < 2; ++x)                                                   \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                               \
+          const bool ok = (pp + x < pe) && ((pp + x) * PS + 4 * g + j <= last_pos);                   \
+          if (!ok) {                                                                                  \
+            _Pragma("unroll") for (int mt = 0; mt < 8; ++mt) vf[x][mt][j] = (bf16_t)0.f;              \
+          }                                                                                           \
+        }                                                                                             \
+    }                                                                                                 \
+    const bool all_visible = (pp + 2) * PS - 1 <= first_pos && pp + 1 < pe;                           \
+    float s[8];                                                                                       \
+    _Pragma("unroll") for (int x = 0; x < 2; ++x) {                                                   \
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};                                                               \
+      _Pragma("unroll") for (int dc = 0; dc < 4; ++dc)                                                \
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[x][dc], qf[dc], acc, 0, 0, 0);               \
+      if (all_visible) {                                                                              \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j) s[x * 4 + j] = acc[j] * a.scale_log2;           \
+      } else {                                                                                        \
+        const bool page_ok = pp + x < pe;                                                             \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                               \
+          const int kpos = (pp + x) * PS + 4 * g + j;                                                 \
+          s[x * 4 + j] = (page_ok && kpos <= pos_c) ? acc[j] * a.scale_log2 : -INFINITY;              \
+        }                                                                                             \
+      }                                                                                               \
+    }                                                                                                 \
+    float mx = s[0];                                                                                  \
+    _Pragma("unroll") for (int j = 1; j < 8; ++j) mx = fmaxf(mx, s[j]);                               \
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));                                                           \
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));                                                           \
+    const float m_new = fmaxf(m, mx);                                                                 \
+    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;                                           \
+    const float alpha = __builtin_amdgcn_exp2f(m - m_use);                                            \
+    float p[8], psum = 0.f;                                                                           \
+    _Pragma("unroll") for (int j = 0; j < 8; ++j) {                                                   \
+      p[j] = __builtin_amdgcn_exp2f(s[j] - m_use);                                                    \
+      psum += p[j];                                                                                   \
+    }                                                                                                 \
+    l = l * alpha + psum;                                                                             \
+    m = m_new;                                                                                        \
+    bf16x8 pf;                                                                                        \
+    _Pragma("unroll") for (int j = 0; j < 8; ++j) pf[j] = (bf16_t)p[j];                               \
+    _Pragma("unroll") for (int mt = 0; mt < 8; ++mt) {                                                \
+      bf16x8 vfull;                                                                                   \
+      _Pragma("unroll") for (int j = 0; j < 4; ++j) { vfull[j] = vf[0][mt][j]; vfull[4 + j] = vf[1][mt][j]; } \
+      f32x4 acc = o[mt];                                                                              \
+      _Pragma("unroll") for (int j = 0; j < 4; ++j) acc[j] *= alpha;                                  \
+      o[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vfull, pf, acc, 0, 0, 0);                       \
+    }                                                                                                 \
+  }
+  // step st: my loads of stage st have landed -> barrier -> everyone's have, and everyone is done with the buffer of
+  // stage st - 1 -> start the loads of stage st + 3 into it -> multiply stage st
+#define FLEXCO_CH_STEP(cur_, free_, st_)                                                              \
+  {                                                                                                   \
+    FLEXCO_CH_WAIT_BARRIER                                                                            \
+    FLEXCO_CH_ISSUE(free_, (st_) + 3)                                                                 \
+    FLEXCO_CH_COMPUTE(cur_, st_)                                                                      \
+  }
+  FLEXCO_CH_ISSUE(ring0, 0)
+  FLEXCO_CH_ISSUE(ring1, 1)
+  FLEXCO_CH_ISSUE(ring2, 2)
+  int st = 0;
+  for (; st + 3 < nst; st += 4) {
+    FLEXCO_CH_STEP(ring0, ring3, st)
+    FLEXCO_CH_STEP(ring1, ring0, st + 1)
+    FLEXCO_CH_STEP(ring2, ring1, st + 2)
+    FLEXCO_CH_STEP(ring3, ring2, st + 3)
+  }
+  if (st < nst) FLEXCO_CH_STEP(ring0, ring3, st)
+  if (st + 1 < nst) FLEXCO_CH_STEP(ring1, ring0, st + 1)
+  if (st + 2 < nst) FLEXCO_CH_STEP(ring2, ring1, st + 2)
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // nothing may land in LDS after the block ends
+
+  // ---- write the tile's partial, or - the whole key range in one split - its output rows ---------------------
+  if (!have) return;
+  if (split >= a.tile_nsplit[tile]) return;   // the tile's own keys end before this split
+  const int cpt = (16 / group > 1 ? 16 / group : 1) * group;
+  float lsum = l;
+  lsum += __shfl_xor(lsum, 16, 64);
+  lsum += __shfl_xor(lsum, 32, 64);
+  if (c >= a.tile_ntok[tile] * group) return;
+  if (a.tile_nsplit[tile] == 1) {
+    const int t = a.tile_tok0[tile] + c / group, h = kvh * group + c % group;
+    const float inv = 1.0f / lsum;
+    bf16_t* po = a.out + (size_t)t * a.ldo + h * D + 4 * g;
+#pragma unroll
+    for (int mt = 0; mt < 8; ++mt) {
+      bf16x4 v;
+#pragma unroll
+      for (int qq = 0; qq < 4; ++qq) v[qq] = (bf16_t)(o[mt][qq] * inv);
+      *reinterpret_cast<bf16x4*>(po + mt * 16) = v;
+    }
+    if (a.lse && g == 0) a.lse[(size_t)t * a.nq + h] = m * 0.6931471805599453f + __logf(lsum);
+    if (a.keep.lse2 && t >= a.keep.tok0 && t < a.keep.tok0 + a.keep.n) {
+      bf16_t* p2 = (bf16_t*)a.keep.out2 + ((size_t)(t - a.keep.tok0) * a.nq + h) * D + 4 * g;
+#pragma unroll
+      for (int mt = 0; mt < 8; ++mt) {
+        bf16x4 v;
+#pragma unroll
+        for (int qq = 0; qq < 4; ++qq) v[qq] = (bf16_t)(o[mt][qq] * inv);
+        *reinterpret_cast<bf16x4*>(p2 + mt * 16) = v;
+      }
+      if (g == 0) a.keep.lse2[(size_t)(t - a.keep.tok0) * a.nq + h] = m * 0.6931471805599453f + __logf(lsum);
+    }
+    return;
+  }
+  const size_t idx = ((size_t)(a.tile_part0[tile] + split) * a.nkv + kvh) * cpt + c;
+  if (g == 0) {
+    part_ml[idx * 2] = m * 0.6931471805599453f;     // back to the natural-log domain
+    part_ml[idx * 2 + 1] = lsum;
+  }
+  float* pa = part_acc + idx * D + 4 * g;
+#pragma unroll
+  for (int mt = 0; mt < 8; ++mt) *reinterpret_cast<f32x4*>(pa + mt * 16) = o[mt];
+}
+
+}  // namespace
+
+// The chunk items of the work list (everything but single decode tokens) on the four-wavefront kernel; the caller
+// has the one-launch kernel skip them.  Same support test as launch_attention_mfma.
+int32_t launch_attention_chunk_mfma(const flexco_layer_cfg& c, const flexco_maps& m, const void* q, size_t ldq,
+                                    const flexco_kv_pool& pool, float* part_ml, float* part_acc, void* out, size_t ldo,
+                                    float* lse, hipStream_t s, const AttnKeep* keep) {
+  const int group = c.n_q_heads / c.n_kv_heads;
+  if (c.dtype != FLEXCO_BF16 || c.head_dim != D || c.page_size != PS || group > 16 || ldq % 8 != 0 ||
+      m.kv_split_pages > MAXSP || ldo % 4 != 0 || ((uintptr_t)out & 7))
+    return FLEXCO_EUNSUPPORTED;
+  if (m.n_items == 0) return FLEXCO_OK;
+  ChunkArgs a;
+  a.tok_pos = m.tok_pos; a.block_table = m.block_table; a.tile_req = m.tile_req; a.tile_tok0 = m.tile_tok0;
+  a.tile_ntok = m.tile_ntok; a.tile_nsplit = m.tile_nsplit; a.tile_part0 = m.tile_part0; a.item_tile = m.item_tile;
+  a.item_split = m.item_split; a.item_ntiles = m.item_ntiles;
+  a.max_pages = m.max_pages; a.nq = c.n_q_heads; a.nkv = c.n_kv_heads; a.n_items = m.n_items;
+  a.split_pages = m.kv_split_pages;
+  a.scale_log2 = 1.4426950408889634f / sqrtf((float)D);
+  a.out = (bf16_t*)out; a.ldo = ldo; a.lse = lse;
+  a.keep = keep ? *keep : AttnKeep{nullptr, nullptr, 0, 0};
+  hipLaunchKernelGGL(attn_fwd_chunk_kernel, dim3((unsigned)m.n_items * c.n_kv_heads), dim3(256), 0, s, a,
+                     (const bf16_t*)q, ldq, (const bf16_t*)pool.k_pages, (const bf16_t*)pool.v_pages, part_ml,
+                     part_acc);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(FLEXCO_EHIP, "launch of attn_fwd_chunk failed: %s", hipGetErrorString(e));
+  return FLEXCO_OK;
+}
+
+}  // namespace flexco

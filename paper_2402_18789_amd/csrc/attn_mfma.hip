@@ -43,7 +43,7 @@ struct FwdArgs {
 };
 
 constexpr int D = 128, PS = 16;
-constexpr int NC = FLEXCO_ATTN_ITEM_TILES;   // column tiles one work item may carry
+constexpr int NC_MAX = FLEXCO_ATTN_ITEM_TILES;   // column tiles one work item may carry
 constexpr int MAXSP = 256;                   // pages of a key split at most
 
 // A work item carries 1 .. NC neighbouring column tiles of one request (a decode token: one).  The
@@ -51,6 +51,9 @@ constexpr int MAXSP = 256;                   // pages of a key split at most
 // turn: a chunk of 16 / group * NC tokens re-reads its prefix from the caches NC times less often
 // than tile by tile.  Each tile keeps its own running maximum, sum and accumulator and its own partial
 // row, so the merge kernel sees tiles as before.
+// NC = NC_MAX: every item of the work list; NC = 1: the single decode tokens only (the other items go to the
+// four-wavefront kernel of attn_chunk_mfma.hip), at half the registers, so that both kernels' blocks fit a CU together
+template <int NC>
 __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(FwdArgs a, const bf16_t* __restrict__ q, size_t ldq,
                                                             const bf16_t* __restrict__ kp,
                                                             const bf16_t* __restrict__ vp,
@@ -66,6 +69,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(FwdArgs a, const bf1
   const int kvh = unit % a.nkv;
   const int tile0 = a.item_tile[item], split = a.item_split[item];
   const int ntl = __builtin_amdgcn_readfirstlane(a.item_ntiles[item]);
+  if (NC == 1 && !(ntl == 1 && a.tile_ntok[tile0] == 1)) return;
   const int r = a.tile_req[tile0];
   const int group = a.nq / a.nkv;
   const int c = lane & 15, g = lane >> 4;
@@ -269,11 +273,12 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(FwdArgs a, const bf1
 
 int32_t launch_attention_mfma(const flexco_layer_cfg& c, const flexco_maps& m, const void* q, size_t ldq,
                               const flexco_kv_pool& pool, float* part_ml, float* part_acc, void* out, size_t ldo,
-                              float* lse, hipStream_t s, const AttnKeep* keep) {
+                              float* lse, hipStream_t s, const AttnKeep* keep, bool skip_chunk, bool nothing_to_do) {
   const int group = c.n_q_heads / c.n_kv_heads;
   if (c.dtype != FLEXCO_BF16 || c.head_dim != D || c.page_size != PS || group > 16 || ldq % 8 != 0 ||
       m.kv_split_pages > MAXSP || ldo % 4 != 0 || ((uintptr_t)out & 7))
     return FLEXCO_EUNSUPPORTED;
+  if (nothing_to_do) return FLEXCO_OK;
   FwdArgs a;
   a.tok_pos = m.tok_pos; a.block_table = m.block_table; a.tile_req = m.tile_req; a.tile_tok0 = m.tile_tok0;
   a.tile_ntok = m.tile_ntok; a.tile_nsplit = m.tile_nsplit; a.tile_part0 = m.tile_part0; a.item_tile = m.item_tile;
@@ -283,9 +288,12 @@ int32_t launch_attention_mfma(const flexco_layer_cfg& c, const flexco_maps& m, c
   a.scale_log2 = 1.4426950408889634f / sqrtf((float)D);
   a.out = (bf16_t*)out; a.ldo = ldo; a.lse = lse;
   a.keep = keep ? *keep : AttnKeep{nullptr, nullptr, 0, 0};
-  hipLaunchKernelGGL(attn_fwd_mfma_kernel, dim3((m.n_items * c.n_kv_heads + 3) / 4), dim3(256), 0, s, a,
-                     (const bf16_t*)q, ldq, (const bf16_t*)pool.k_pages, (const bf16_t*)pool.v_pages, part_ml,
-                     part_acc);
+  if (skip_chunk)
+    hipLaunchKernelGGL(attn_fwd_mfma_kernel<1>, dim3((m.n_items * c.n_kv_heads + 3) / 4), dim3(256), 0, s, a,
+                       (const bf16_t*)q, ldq, (const bf16_t*)pool.k_pages, (const bf16_t*)pool.v_pages, part_ml, part_acc);
+  else
+    hipLaunchKernelGGL(attn_fwd_mfma_kernel<NC_MAX>, dim3((m.n_items * c.n_kv_heads + 3) / 4), dim3(256), 0, s, a,
+                       (const bf16_t*)q, ldq, (const bf16_t*)pool.k_pages, (const bf16_t*)pool.v_pages, part_ml, part_acc);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(FLEXCO_EHIP, "launch of attn_fwd_mfma failed: %s", hipGetErrorString(e));
   return FLEXCO_OK;

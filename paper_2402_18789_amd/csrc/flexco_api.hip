@@ -135,11 +135,24 @@ extern "C" int32_t flexco_kernel_timer_stop(int32_t kernel_id, double* total_ms,
   return rc_out;
 }
 
+// Which kernel takes the chunk items (prefill chunks, finetune windows) of the attention work list: -1 = by batch
+// (the four-wavefront kernel when the work list has no single-token item: beside a decode stream the one-launch
+// kernel hides the chunk items in the stream's waits, which two launches one after the other cannot),
+// 0 = the one-launch kernel, 1 = the four-wavefront kernel.
+static std::atomic<int> g_chunk_path{-1};
+
 // bf16 calls that took a type-generic kernel because the matrix-core kernel of their class does not cover the
 // shape (head_dim other than 128, page size other than 16, odd leading dimensions ...), per kernel class
 static std::atomic<int64_t> g_bf16_fallbacks[FLEXCO_N_KERNEL_IDS];
 static inline void note_fallback(int dtype, int kernel_id) {
   if (dtype == FLEXCO_BF16) g_bf16_fallbacks[kernel_id].fetch_add(1, std::memory_order_relaxed);
+}
+
+extern "C" int32_t flexco_attention_chunk_path(int32_t mode) {
+  clear_error();
+  FLEXCO_CHECK(mode >= -1 && mode <= 1, FLEXCO_EINVAL, "mode %d: -1 (by batch), 0 or 1", mode);
+  g_chunk_path.store(mode);
+  return FLEXCO_OK;
 }
 
 extern "C" int32_t flexco_bf16_fallbacks(int64_t* counts, int32_t reset) {
@@ -646,7 +659,11 @@ int32_t run_attention(const flexco_layer_cfg& c, const flexco_maps& m, const voi
   bool direct = true;    // the matrix-core kernel writes the rows of single-split tiles itself
   {
     KernelTimerScope ts(FLEXCO_K_ATTN_FWD, s);
-    rc = launch_attention_mfma(c, m, q, ldq, pool, part_ml, part_acc, out, ldo, lse, s, keep);
+    const int mode = g_chunk_path.load();
+    const bool chunk = mode > 0 || (mode < 0 && m.n_single == 0);
+    // (with no single-token item the one-launch kernel has nothing left to do; its support test still decides)
+    rc = launch_attention_mfma(c, m, q, ldq, pool, part_ml, part_acc, out, ldo, lse, s, keep, chunk, chunk && m.n_single == 0);
+    if (rc == FLEXCO_OK && chunk) rc = launch_attention_chunk_mfma(c, m, q, ldq, pool, part_ml, part_acc, out, ldo, lse, s, keep);
   }
   if (rc == FLEXCO_EUNSUPPORTED) {
     clear_error();

@@ -272,7 +272,7 @@ using namespace flexco;
 
 extern "C" const char* flexco_last_error(void) { return g_err; }
 
-extern "C" int32_t flexco_abi_version(void) { return 5; }
+extern "C" int32_t flexco_abi_version(void) { return 6; }
 
 extern "C" int32_t flexco_maps_blob_ints(const flexco_batch_desc* desc, int32_t page_size, int32_t n_q_heads,
                                          int32_t n_kv_heads, int32_t kv_split_pages, size_t* out_ints) {
@@ -312,6 +312,9 @@ extern "C" int32_t flexco_build_maps(const flexco_batch_desc* desc, int32_t page
   m.n_adapters = b.n_adapters;
   m.ft_adapter = b.ft_req >= 0 ? desc->adapter[b.ft_req] : -1;
   m.num_pages = num_pages;
+  m.n_single = 0;
+  for (size_t i = 0; i < b.item_tile.size(); ++i)
+    m.n_single += (b.item_ntiles[i] == 1 && b.tile_ntok[b.item_tile[i]] == 1) ? 1 : 0;
   memcpy(m.adapter_tok_off, b.adapter_tok_off, sizeof(m.adapter_tok_off));
   m.tok_req = w.put(b.tok_req); m.tok_pos = w.put(b.tok_pos); m.slot = w.put(b.slot);
   m.req_tok_off = w.put(b.req_tok_off); m.req_kv_len = w.put(b.req_kv_len); m.req_kind = w.put(b.req_kind);

@@ -104,6 +104,27 @@ def test_default_key_split_follows_the_batch_size():
     assert c_maps(gen.mixed_batch(16, 0, decode_ctx=(300,)), 32, 8, split=64)["kv_split_pages"] == 64   # an explicit value is kept
 
 
+def count_single(cm):
+    """Work items of one tile that holds one token, counted from the work list itself."""
+    return sum(1 for it in range(cm["n_items"])
+               if cm["item_ntiles"][it] == 1 and cm["tile_ntok"][cm["item_tile"][it]] == 1)
+
+
+def test_n_single_counts_the_one_token_work_items():
+    """n_single is what decides which attention kernel takes the chunk items: zero exactly when no work item is a
+    lone token.  A decode request gives one such item per key split; a chunk whose length leaves one token in its
+    last tile gives them too; a chunk of whole tiles gives none."""
+    c2 = c_maps(gen.batch_c2(0), 32, 8)
+    assert c2["n_single"] == count_single(c2) >= 256                   # 256 decode requests
+    tile = c2["tile_tokens"]                                           # 4 tokens per tile at 32 / 8 heads
+    whole = c_maps(gen.mixed_batch(16, 0, prefill=[(0, 25 * tile, 25 * tile)], finetune=[(64, 7 * tile, 64 + 7 * tile)]), 32, 8)
+    assert whole["n_single"] == 0 == count_single(whole)
+    ragged = c_maps(gen.mixed_batch(16, 0, prefill=[(0, 25 * tile + 1, 25 * tile + 1)]), 32, 8, split=2)
+    assert ragged["n_single"] == count_single(ragged)
+    one = c_maps(gen.mixed_batch(16, 0, decode_ctx=(300,)), 32, 8, split=4)
+    assert one["n_single"] == count_single(one) == -(-301 // (4 * 16))  # one item per key split of its 301 visible keys
+
+
 @pytest.mark.parametrize("seed", range(30))
 def test_random_batches_bit_exact_vs_oracle(seed):
     """Seeded random request mixes (counts, contexts, chunk lengths, adapters, head grouping, key split): the integer
@@ -128,6 +149,7 @@ def test_random_batches_bit_exact_vs_oracle(seed):
     cm = c_maps(batch, nq, nkv, split)
     for k in ("T", "n_req", "n_ft", "n_seg", "max_pages"):
         assert cm[k] == om[k], k
+    assert cm["n_single"] == count_single(cm)
     for k in COMMON:
         assert np.array_equal(cm[k], om[k]), k
     assert check_attention_cover(om, work_items(cm, batch.page_size))

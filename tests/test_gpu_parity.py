@@ -141,10 +141,21 @@ def attention_case(cfg, batch, split, seed=3):
     return to_np(out_d), a_o, to_np(lse_d), lse_o
 
 
+# chunk_path: which kernel takes the prefill chunks and finetune windows (flexco_attention_chunk_path): 0 = the one that
+# streams the decode tokens, 1 = the four-wavefront kernel with K / V staged in LDS
+@pytest.mark.parametrize("chunk_path", [0, 1])
 @pytest.mark.parametrize("name,split", [("c1", 0), ("c1", 2), ("small_bf16", 0), ("small_bf16", 2), ("g5", 4), ("mha", 2),
-                                        ("g8", 4), ("long", 0)])
-def test_attention_mixed(name, split):
-    say(f"attention_mixed {name} split={split}")
+                                        ("g8", 4), ("long", 0), ("small_bf16", 6), ("long", 250), ("windows", 0), ("windows", 32)])
+def test_attention_mixed(name, split, chunk_path):
+    say(f"attention_mixed {name} split={split} chunk_path={chunk_path}")
+    B.flexco_attention_chunk_path(chunk_path)
+    try:
+        _attention_mixed(name, split)
+    finally:
+        B.flexco_attention_chunk_path(-1)
+
+
+def _attention_mixed(name, split):
     if name == "c1":
         cfg, batch = C1, gen.batch_c1(0)
     elif name == "small_bf16":
@@ -157,6 +168,9 @@ def test_attention_mixed(name, split):
         cfg = SMALL_BF16
         batch = gen.mixed_batch(16, 8, decode_ctx=(16384, 8191, 4097, 1), prefill=[(7000, 100, 7100)],
                                 finetune=[(3840, 256, 4096)])
+    elif name == "windows":                  # no decode token at all (by default the four-wavefront kernel's case): a prompt
+        cfg = SMALL_BF16_G5                  # from position 0 and a window on a long prefix, 113 pages (an odd number of stages)
+        batch = gen.mixed_batch(16, 0, decode_ctx=(), prefill=[(0, 300, 300)], finetune=[(1500, 300, 1800)])
     elif name == "mha":
         cfg = SMALL_BF16_MHA                 # 16 tokens per tile, 64 per work item
         batch = gen.batch_scaled(6, 5, 9, 200, [(0, 150, 150), (40, 77, 117)], [(30, 100, 130)])
