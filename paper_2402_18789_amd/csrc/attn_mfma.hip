@@ -52,7 +52,7 @@ constexpr int MAXSP = 256;                   // pages of a key split at most
 // than tile by tile.  Each tile keeps its own running maximum, sum and accumulator and its own partial
 // row, so the merge kernel sees tiles as before.
 // NC = NC_MAX: every item of the work list; NC = 1: the single decode tokens only (the other items go to the
-// four-wavefront kernel of attn_chunk_mfma.hip), at half the registers, so that both kernels' blocks fit a CU together
+// four-wavefront kernel of attn_chunk_mfma.hip)
 template <int NC>
 __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(FwdArgs a, const bf16_t* __restrict__ q, size_t ldq,
                                                             const bf16_t* __restrict__ kp,
