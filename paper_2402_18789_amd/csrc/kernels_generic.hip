@@ -17,14 +17,32 @@ namespace flexco {
 // --------------------------------------------------------------------------------------
 // reductions
 // --------------------------------------------------------------------------------------
+// Every lane gets the result.  Within a row of 16 lanes the partner's value comes through the data-parallel
+// primitives, as an operand modifier of the addition itself (lane ^ 1, lane ^ 2, then the other quad of eight lanes
+// and the other half of the row by mirrored reads - the quads, then the halves, are uniform by then); only the two
+// exchanges between rows go through the LDS crossbar (a rank-16 row product ends with sixteen of these sums per
+// wavefront: 4.1 of the norm backward's 17.6 us were the 96 crossbar exchanges of the all-crossbar form).
+template <int CTRL>
+__device__ inline float dpp_read(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, false));
+}
+constexpr int DPP_XOR1 = 0xB1, DPP_XOR2 = 0x4E, DPP_HALF_MIRROR = 0x141, DPP_MIRROR = 0x140;
 __device__ inline float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  v += dpp_read<DPP_XOR1>(v);
+  v += dpp_read<DPP_XOR2>(v);
+  v += dpp_read<DPP_HALF_MIRROR>(v);
+  v += dpp_read<DPP_MIRROR>(v);
+  v += __shfl_xor(v, 16, 64);
+  v += __shfl_xor(v, 32, 64);
   return v;
 }
 __device__ inline float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  v = fmaxf(v, dpp_read<DPP_XOR1>(v));
+  v = fmaxf(v, dpp_read<DPP_XOR2>(v));
+  v = fmaxf(v, dpp_read<DPP_HALF_MIRROR>(v));
+  v = fmaxf(v, dpp_read<DPP_MIRROR>(v));
+  v = fmaxf(v, __shfl_xor(v, 16, 64));
+  v = fmaxf(v, __shfl_xor(v, 32, 64));
   return v;
 }
 // sum over a block of 256 threads; every thread gets the result
@@ -62,9 +80,26 @@ __device__ inline void lora_acc_cols(float (&acc)[R], const float (&v)[N], const
 #pragma unroll
       for (int q = 0; q < 8; ++q) acc[8 * q8 + q] += v[j] * (float)b[j][q8][q];
 }
-// sum of acc over the block's 256 threads (lanes by shuffles, the four wavefronts in order) -> t and ext of `row`
-template <int R>
-__device__ inline void lora_row_finish(float (&acc)[R], float* lds /* 4 R floats */, float* t, bf16_t* ext, size_t row,
+// the two halves of lora_acc_cols apart, for kernels that request the rows of B before they have the values
+template <int R, int N>
+__device__ inline void lora_load_cols(bf16x8 (&b)[N][R / 8], const bf16_t* __restrict__ brow0) {
+#pragma unroll
+  for (int j = 0; j < N; ++j)
+#pragma unroll
+    for (int q8 = 0; q8 < R / 8; ++q8) b[j][q8] = *reinterpret_cast<const bf16x8*>(brow0 + (size_t)j * R + 8 * q8);
+}
+template <int R, int N>
+__device__ inline void lora_fma_cols(float (&acc)[R], const float (&v)[N], const bf16x8 (&b)[N][R / 8]) {
+#pragma unroll
+  for (int j = 0; j < N; ++j)
+#pragma unroll
+    for (int q8 = 0; q8 < R / 8; ++q8)
+#pragma unroll
+      for (int q = 0; q < 8; ++q) acc[8 * q8 + q] += v[j] * (float)b[j][q8][q];
+}
+// sum of acc over the block's 256 threads (the lanes of a wavefront, then the four wavefronts in order) -> t and ext of `row`
+template <int R, int NW = 4>
+__device__ inline void lora_row_finish(float (&acc)[R], float* lds /* NW R floats */, float* t, bf16_t* ext, size_t row,
                                        float scale) {
 #pragma unroll
   for (int q = 0; q < R; ++q) acc[q] = wave_sum(acc[q]);
@@ -75,29 +110,31 @@ __device__ inline void lora_row_finish(float (&acc)[R], float* lds /* 4 R floats
   }
   __syncthreads();
   if (threadIdx.x < R) {
-    const float v = lds[threadIdx.x] + lds[R + threadIdx.x] + lds[2 * R + threadIdx.x] + lds[3 * R + threadIdx.x];
+    float v = lds[threadIdx.x];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) v += lds[w * R + threadIdx.x];
     t[row * R + threadIdx.x] = v;
     ext[row * R + threadIdx.x] = (bf16_t)(v * scale);
   }
 }
 
-// t = dy B of one target, one block per row (see RowLoraT)
-template <int R>
-__global__ __launch_bounds__(256) void lora_row_t_kernel(const bf16_t* __restrict__ dy, size_t lddy, int width, RowLoraT lt) {
-  __shared__ float lds[4 * R];
+// t = dy B of one target, one block of NW wavefronts per row (see RowLoraT)
+template <int R, int NW>
+__global__ __launch_bounds__(64 * NW) void lora_row_t_kernel(const bf16_t* __restrict__ dy, size_t lddy, int width, RowLoraT lt) {
+  __shared__ float lds[NW * R];
   const size_t row = blockIdx.x;
   float acc[R];
 #pragma unroll
   for (int q = 0; q < R; ++q) acc[q] = 0.f;
   const bf16_t* B = (const bf16_t*)lt.B[0];
-  for (int i = threadIdx.x * 8; i < width; i += 256 * 8) {
+  for (int i = threadIdx.x * 8; i < width; i += 64 * NW * 8) {
     const bf16x8 v = *reinterpret_cast<const bf16x8*>(dy + row * lddy + i);
     float vf[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) vf[j] = (float)v[j];
     lora_acc_cols<R, 8>(acc, vf, B + (size_t)i * R);
   }
-  lora_row_finish<R>(acc, lds, lt.t[0], (bf16_t*)lt.ext[0], row, lt.scale);
+  lora_row_finish<R, NW>(acc, lds, lt.t[0], (bf16_t*)lt.ext[0], row, lt.scale);
 }
 
 // --------------------------------------------------------------------------------------
@@ -266,6 +303,114 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* __restrict__ 
   }
 }
 
+// The same backward for bf16 rows of up to 8192 elements, sixteen wavefronts per row: a thread owns four elements of
+// each 4096-element stretch and keeps them in registers between the two passes, and every load of a row (x, g, the
+// residual gradient, all split-K partial sums) is in flight at once.  A window of a few hundred rows gives the
+// one-block-per-row kernel above one block of four wavefronts per CU, which waits out the latency of each of its
+// loads in turn; here the chip holds four times as many wavefronts and each waits once.
+// The sums over the row are taken in another order than above: hn may differ from the forward norm's row in the last
+// bit of an element.
+template <int R, int IT>
+__global__ __launch_bounds__(1024) void rmsnorm_bwd_wide_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ g,
+                                                                const bf16_t* __restrict__ dh,
+                                                                const bf16_t* __restrict__ add, bf16_t* __restrict__ dx,
+                                                                bf16_t* __restrict__ hn, int H, float eps,
+                                                                const float* __restrict__ dh_part, int splits,
+                                                                size_t stride, RowLoraT lt) {
+  constexpr int RA = R > 0 ? R : 1;
+  __shared__ float red[2][16];
+  __shared__ float lt_lds[16 * RA];
+  const size_t row = blockIdx.x;
+  const int wave = threadIdx.x >> 6;
+  float v[IT][4], gv[IT][4], dv[IT][4], av[IT][4];
+  auto ld4 = [](const bf16_t* p, float (&o)[4]) {
+    const bf16x4 t = *reinterpret_cast<const bf16x4*>(p);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) o[j] = (float)t[j];
+  };
+  auto st4 = [](bf16_t* p, const float (&o)[4]) {
+    bf16x4 t;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) t[j] = (bf16_t)o[j];
+    *reinterpret_cast<bf16x4*>(p) = t;
+  };
+  float ss = 0.f, sd = 0.f;
+  bf16x8 bfrag[IT][4][R > 0 ? R / 8 : 1];   // the rows of B this thread's elements meet, fetched with the row
+#pragma unroll
+  for (int it = 0; it < IT; ++it) {
+    const int i = (it * 1024 + (int)threadIdx.x) * 4;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[it][j] = gv[it][j] = dv[it][j] = av[it][j] = 0.f;
+    if (i < H) {
+      if constexpr (R > 0) lora_load_cols<R, 4>(bfrag[it], (const bf16_t*)lt.B[0] + (size_t)i * R);
+      ld4(x + row * H + i, v[it]);
+      ld4(g + i, gv[it]);
+      if (add) ld4(add + row * H + i, av[it]);
+      if (dh_part) {   // split-K partial sums, added in split order and rounded to the storage type (see load_split_sum)
+        const float* p = dh_part + row * H + i;
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        int sp = 0;
+        for (; sp + 4 <= splits; sp += 4) {
+          const f32x4 t0 = *reinterpret_cast<const f32x4*>(p + (size_t)sp * stride);
+          const f32x4 t1 = *reinterpret_cast<const f32x4*>(p + (size_t)(sp + 1) * stride);
+          const f32x4 t2 = *reinterpret_cast<const f32x4*>(p + (size_t)(sp + 2) * stride);
+          const f32x4 t3 = *reinterpret_cast<const f32x4*>(p + (size_t)(sp + 3) * stride);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) acc[j] = (((acc[j] + t0[j]) + t1[j]) + t2[j]) + t3[j];
+        }
+        for (; sp < splits; ++sp) {
+          const f32x4 t0 = *reinterpret_cast<const f32x4*>(p + (size_t)sp * stride);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) acc[j] += t0[j];
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) dv[it][j] = (float)(bf16_t)acc[j];
+      } else {
+        ld4(dh + row * H + i, dv[it]);
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) { ss += v[it][j] * v[it][j]; sd += v[it][j] * gv[it][j] * dv[it][j]; }
+    }
+  }
+  ss = wave_sum(ss);
+  sd = wave_sum(sd);
+  if ((threadIdx.x & 63) == 0) { red[0][wave] = ss; red[1][wave] = sd; }
+  __syncthreads();
+  ss = sd = 0.f;
+#pragma unroll
+  for (int w = 0; w < 16; ++w) { ss += red[0][w]; sd += red[1][w]; }
+  const float rstd = 1.0f / sqrtf(ss / H + eps);
+  const float coef = rstd * rstd * rstd * sd / H;
+  float lt_acc[RA];
+#pragma unroll
+  for (int q = 0; q < RA; ++q) lt_acc[q] = 0.f;
+#pragma unroll
+  for (int it = 0; it < IT; ++it) {
+    const int i = (it * 1024 + (int)threadIdx.x) * 4;
+    if (i < H) {
+      if (hn) {
+        float hv[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) hv[j] = v[it][j] * rstd * gv[it][j];
+        st4(hn + row * H + i, hv);
+      }
+      float o[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        o[j] = rstd * gv[it][j] * dv[it][j] - v[it][j] * coef;
+        if (add) o[j] += av[it][j];
+      }
+      st4(dx + row * H + i, o);
+      if constexpr (R > 0) {   // (the values as they were just stored)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) o[j] = (float)(bf16_t)o[j];
+        lora_fma_cols<R, 4>(lt_acc, o, bfrag[it]);
+      }
+    }
+  }
+  if constexpr (R > 0) lora_row_finish<R, 16>(lt_acc, lt_lds, lt.t[0], (bf16_t*)lt.ext[0], row, lt.scale);
+}
+
 // Rotation angles.  Pair i of a head turns by pos * theta^(-2 i / d).  The host hands over the frequencies in
 // revolutions, theta^(-2 i / d) / (2 pi), as doubles (a kernel argument: pow and a double-precision sincos per
 // (token, i) on the device were a third of these kernels' run time).  The device takes the fractional part of
@@ -300,6 +445,32 @@ __global__ __launch_bounds__(256) void rope_append_kernel(T* __restrict__ qkv, c
   const int pos = tok_pos[t];
   const int half = d >> 1;
   for (int i = threadIdx.x; i < half; i += 256) rope_cos_sin(freq, i, pos, &cs[i], &cs[half + i]);
+  // the run of tokens this token's v row is written with (below): its first token and its length.  One lane per
+  // neighbouring token looks at that token's slot and its predecessor's, all at once (a chain of dependent loads
+  // along the run would cost more than the kernel's whole run time)
+  constexpr int RUN = 16;
+  __shared__ int run_info[2];
+  if constexpr (VEC) {
+    if (threadIdx.x < 64) {
+      const int k = threadIdx.x, tt = t - (RUN - 1) + k;     // lanes 0 .. 31: tokens t - 15 .. t + 16
+      bool first = false;                                     // tt begins a run (or lies past the batch)
+      if (k < 2 * RUN) {
+        if (tt >= (int)gridDim.x) first = true;
+        else if (tt >= 0) {
+          const int s1 = slot[tt];
+          first = tt == 0 || slot[tt - 1] + 1 != s1 || (s1 % ps) % RUN == 0;
+        }
+      }
+      const unsigned long long m = __ballot(first);
+      if (k == 0) {
+        const int k0 = 31 - __clz((unsigned)(m & 0xFFFFu));              // the last beginning at or before t
+        const unsigned after = (unsigned)((m >> RUN) & 0xFFFFu);
+        const int k1 = after ? RUN + __ffs(after) - 1 : 2 * RUN;         // the first beginning after t
+        run_info[0] = t - (RUN - 1) + k0;
+        run_info[1] = k1 - k0;
+      }
+    }
+  }
   __syncthreads();
   const int qkv_dim = (nq + 2 * nkv) * d;
   T* row = qkv + (size_t)t * qkv_dim;
@@ -339,13 +510,42 @@ __global__ __launch_bounds__(256) void rope_append_kernel(T* __restrict__ qkv, c
         Vec<T>::store(dst + half + i, rhi);
       }
     }
-    // v: one 16-byte read, N element stores (a channel's positions are the contiguous index of a V page)
-    for (int idx = threadIdx.x * N; idx < nkv * d; idx += 256 * N) {
-      const int kh = idx / d, i = idx % d;
-      float v[N];
-      Vec<T>::load(vrow + idx, v);
+    // v: a channel's positions are the contiguous index of a V page, so one token's row is nkv d scattered elements
+    // (these stores were half of the kernel's time).  Tokens whose slots follow each other inside a page (a chunk's
+    // rows) form a run; a run begins at a page's first position, at a multiple of 16 positions, and where the slot
+    // is not the one after the previous token's.  The blocks of a run's tokens share its v rows out by channels:
+    // each reads its channels of every row of the run (no block ever writes them) and stores, per channel, the
+    // run's positions side by side - 16-byte pieces for a run of 16, a contiguous stretch of the page per block.
+    const int t0 = run_info[0], len = run_info[1];
+    const int j = t - t0;
+    const int pip0 = pip - j;
+    const int nv = nkv * d / N;                       // 16-byte pieces of a v row
+    const int v_lo = (int)((long)nv * j / len), v_hi = (int)((long)nv * (j + 1) / len);
+    const bool whole = len == RUN && ps % N == 0;
+    const T* vrow0 = qkv + (size_t)t0 * qkv_dim + (nq + nkv) * d;
+    for (int vi = v_lo + threadIdx.x; vi < v_hi; vi += 256) {
+      const int idx = vi * N, kh = idx / d, i = idx % d;
+      T* dst = vp + ((page * nkv + kh) * (size_t)d + i) * ps + pip0;
+      if (whole) {        // (all sixteen loads in flight before the first store)
+        float rows[RUN][N];
 #pragma unroll
-      for (int j = 0; j < N; ++j) vp[((page * nkv + kh) * (size_t)d + i + j) * ps + pip] = (T)v[j];
+        for (int jj = 0; jj < RUN; ++jj) Vec<T>::load(vrow0 + (size_t)jj * qkv_dim + idx, rows[jj]);
+#pragma unroll
+        for (int c = 0; c < N; ++c) {
+          float col[RUN];
+#pragma unroll
+          for (int jj = 0; jj < RUN; ++jj) col[jj] = rows[jj][c];
+#pragma unroll
+          for (int piece = 0; piece < RUN / N; ++piece) Vec<T>::store(dst + (size_t)c * ps + piece * N, &col[piece * N]);
+        }
+      } else {
+        for (int jj = 0; jj < len; ++jj) {
+          float v[N];
+          Vec<T>::load(vrow0 + (size_t)jj * qkv_dim + idx, v);
+#pragma unroll
+          for (int c = 0; c < N; ++c) dst[(size_t)c * ps + jj] = (T)v[c];
+        }
+      }
     }
   } else {
     for (int idx = threadIdx.x; idx < (nq + nkv) * half; idx += 256) {
@@ -895,6 +1095,23 @@ int32_t launch_rmsnorm_bwd(const void* x, const void* g, const void* dh, const v
   const bool vec = vec_ok(dtype, H, {x, g, dh, add, dx, hn, dh_part});
   const size_t shm = dh_part ? sizeof(float) * (size_t)H : 0;
   RowLoraT lt = {};
+  // bf16 rows of up to 8192 elements: sixteen wavefronts per row
+  if (dtype == FLEXCO_BF16 && vec && H <= 8192 && (!lt_in || lt_in->n == 0 || (lt_in->n == 1 && row_lora_ok(dtype, lt_in->r)))) {
+    if (lt_in && lt_in->n > 0) lt = *lt_in;
+    const int R = lt_in && lt_in->n > 0 ? lt.r : 0;
+    const size_t stride = (size_t)T_ * H;
+#define FLEXCO_NORM_BWD_WIDE(R_, IT_)                                                                              \
+    hipLaunchKernelGGL((rmsnorm_bwd_wide_kernel<R_, IT_>), dim3(T_), dim3(1024), 0, s, (const bf16_t*)x,            \
+                       (const bf16_t*)g, (const bf16_t*)dh, (const bf16_t*)add, (bf16_t*)dx, (bf16_t*)hn, H, eps,   \
+                       dh_part, splits, stride, lt)
+    if (H <= 4096) {
+      if (R == 0) FLEXCO_NORM_BWD_WIDE(0, 1); else if (R == 16) FLEXCO_NORM_BWD_WIDE(16, 1); else FLEXCO_NORM_BWD_WIDE(32, 1);
+    } else {
+      if (R == 0) FLEXCO_NORM_BWD_WIDE(0, 2); else if (R == 16) FLEXCO_NORM_BWD_WIDE(16, 2); else FLEXCO_NORM_BWD_WIDE(32, 2);
+    }
+#undef FLEXCO_NORM_BWD_WIDE
+    return post_launch("rmsnorm_bwd");
+  }
   if (lt_in && lt_in->n > 0) {
     if (!vec || !row_lora_ok(dtype, lt_in->r) || lt_in->n != 1) return fail(FLEXCO_EUNSUPPORTED, "rmsnorm_bwd: row product not covered");
     lt = *lt_in;
@@ -979,8 +1196,9 @@ int32_t launch_lora_row_t(const void* dy, size_t lddy, int n, int width, const R
   if (n == 0) return FLEXCO_OK;
   if (!row_lora_ok(FLEXCO_BF16, lt.r) || width % 8 != 0 || lddy % 8 != 0 || !aligned16(dy) || !aligned16(lt.B[0]))
     return fail(FLEXCO_EUNSUPPORTED, "lora_row_t: shape not covered");
-  if (lt.r == 16) hipLaunchKernelGGL(lora_row_t_kernel<16>, dim3(n), dim3(256), 0, s, (const bf16_t*)dy, lddy, width, lt);
-  else hipLaunchKernelGGL(lora_row_t_kernel<32>, dim3(n), dim3(256), 0, s, (const bf16_t*)dy, lddy, width, lt);
+  // (sixteen wavefronts per row were measured slower here: the sixteen sums per wavefront at the end grow with them)
+  if (lt.r == 16) hipLaunchKernelGGL((lora_row_t_kernel<16, 4>), dim3(n), dim3(256), 0, s, (const bf16_t*)dy, lddy, width, lt);
+  else hipLaunchKernelGGL((lora_row_t_kernel<32, 4>), dim3(n), dim3(256), 0, s, (const bf16_t*)dy, lddy, width, lt);
   return post_launch("lora_row_t");
 }
 
