@@ -137,8 +137,8 @@ __global__ __launch_bounds__(64 * SP) void attn_bwd_dq_mfma_kernel(BwdArgs a) {
 #pragma unroll
       for (int q = 0; q < 8; ++q) delta += (float)dof[dc][q] * (float)of[q];
     }
-    delta += __shfl_xor(delta, 16, 64);
-    delta += __shfl_xor(delta, 32, 64);
+    delta = sum_xor16(delta);
+    delta = sum_xor32(delta);
     if (kh == 0 && g == 0 && row_ok) a.delta[(size_t)row_c * a.nq + h] = delta;   // for kernel B
   }
 

@@ -170,8 +170,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_chunk_kernel(ChunkArgs a, con
     }                                                                                                 \
     float mx = s[0];                                                                                  \
     _Pragma("unroll") for (int j = 1; j < 8; ++j) mx = fmaxf(mx, s[j]);                               \
-    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));                                                           \
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));                                                           \
+    mx = max_xor16(mx);                                                                               \
+    mx = max_xor32(mx);                                                                               \
     const float m_new = fmaxf(m, mx);                                                                 \
     const float m_use = (m_new == -INFINITY) ? 0.f : m_new;                                           \
     const float alpha = __builtin_amdgcn_exp2f(m - m_use);                                            \
@@ -220,8 +220,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_chunk_kernel(ChunkArgs a, con
   if (split >= a.tile_nsplit[tile]) return;   // the tile's own keys end before this split
   const int cpt = (16 / group > 1 ? 16 / group : 1) * group;
   float lsum = l;
-  lsum += __shfl_xor(lsum, 16, 64);
-  lsum += __shfl_xor(lsum, 32, 64);
+  lsum = sum_xor16(lsum);
+  lsum = sum_xor32(lsum);
   if (c >= a.tile_ntok[tile] * group) return;
   if (a.tile_nsplit[tile] == 1) {
     const int t = a.tile_tok0[tile] + c / group, h = kvh * group + c % group;

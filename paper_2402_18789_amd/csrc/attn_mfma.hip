@@ -18,7 +18,7 @@
 //       ([d][16 positions] per page), so lane (d, g) fetches the matching 4 + 4 positions
 //       with two 8-byte loads.
 // Online softmax runs per column in the exp2 domain; the running maximum is reduced over the
-// four lanes that share a column with two cross-lane shuffles.  Each work item writes an
+// four lanes that share a column with two row swaps (no LDS).  Each work item writes an
 // un-normalised partial (m, l, acc[128]) per column; a merge kernel combines the splits.
 //
 // Key positions beyond a column's own position are masked in the scores; positions beyond
@@ -174,8 +174,8 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(FwdArgs a, const bf1
       float mx = s[0];
 #pragma unroll
       for (int j = 1; j < 8; ++j) mx = fmaxf(mx, s[j]);
-      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      mx = max_xor16(mx);
+      mx = max_xor32(mx);
       const float m_new = fmaxf(m[cs], mx);
       const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
       const float alpha = __builtin_amdgcn_exp2f(m[cs] - m_use);
@@ -227,8 +227,8 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(FwdArgs a, const bf1
     const int tile = tile0 + cs;
     if (split >= a.tile_nsplit[tile]) continue;   // the tile's own keys end before this split
     float lsum = l[cs];
-    lsum += __shfl_xor(lsum, 16, 64);
-    lsum += __shfl_xor(lsum, 32, 64);
+    lsum = sum_xor16(lsum);
+    lsum = sum_xor32(lsum);
     if (a.tile_nsplit[tile] == 1) {   // the whole key range in one split: normalise and write the output rows
       if (c < a.tile_ntok[tile] * group) {
         const int t = a.tile_tok0[tile] + c / group, h = kvh * group + c % group;

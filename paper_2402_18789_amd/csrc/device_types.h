@@ -16,6 +16,22 @@ __device__ inline float ld(const bf16_t* p) { return (float)*p; }
 __device__ inline void st(float* p, float v) { *p = v; }
 __device__ inline void st(bf16_t* p, float v) { *p = (bf16_t)v; }   // round to nearest even
 
+// Exchanges between the four rows of 16 lanes of a wavefront without the LDS crossbar: gfx950's row swaps.
+// v_permlane16_swap a, b swaps the odd rows of a with the even rows of b; v_permlane32_swap the upper half of a
+// with the lower half of b.  With a = b = v on entry, a then holds the value of the even row of each pair of rows
+// (of the lower half) in both rows (halves) and b that of the odd row (upper half): a op b is v op (the value of
+// lane ^ 16, lane ^ 32) in every lane, the same bits in both partners.  (One wait state around the swap for the
+// vector ALU's read-after-write rules, which the compiler does not track through the asm.)
+__device__ inline void row_pair_swap(float& a, float& b) {
+  asm("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+}
+__device__ inline void half_swap(float& a, float& b) {
+  asm("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+}
+__device__ inline float sum_xor16(float v) { float a = v, b = v; row_pair_swap(a, b); return a + b; }
+__device__ inline float sum_xor32(float v) { float a = v, b = v; half_swap(a, b); return a + b; }
+__device__ inline float max_xor16(float v) { float a = v, b = v; row_pair_swap(a, b); return fmaxf(a, b); }
+__device__ inline float max_xor32(float v) { float a = v, b = v; half_swap(a, b); return fmaxf(a, b); }
 
 // 16-byte row accesses of the element-wise kernels: N consecutive elements as floats
 template <typename T> struct Vec;

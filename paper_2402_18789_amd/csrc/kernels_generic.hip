@@ -21,7 +21,9 @@ namespace flexco {
 // primitives, as an operand modifier of the addition itself (lane ^ 1, lane ^ 2, then the other quad of eight lanes
 // and the other half of the row by mirrored reads - the quads, then the halves, are uniform by then); only the two
 // exchanges between rows go through the LDS crossbar (a rank-16 row product ends with sixteen of these sums per
-// wavefront: 4.1 of the norm backward's 17.6 us were the 96 crossbar exchanges of the all-crossbar form).
+// wavefront: 4.1 of the norm backward's 17.6 us were the 96 crossbar exchanges of the all-crossbar form; row swaps
+// for the last two steps as well, as the attention kernels use them in their softmax chain, were 3 - 5 % slower
+// here, where sixteen independent sums overlap their crossbar round trips).
 template <int CTRL>
 __device__ inline float dpp_read(float v) {
   return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, false));
