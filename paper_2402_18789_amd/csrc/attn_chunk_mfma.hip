@@ -23,6 +23,7 @@ constexpr int D = 128, PS = 16;
 constexpr int PAGE_EL = PS * D;          // elements of one K page-head block (16 keys x 128) = of one V block (128 x 16)
 constexpr int STAGE_EL = 4 * PAGE_EL;    // K page 0 | K page 1 | V page 0 | V page 1
 constexpr int MAXSP = 256;               // pages of a key split at most
+constexpr float LAZY = 8.f;              // how far (log2) a column's maximum may run ahead of its reference point
 #define FLEXCO_GP(p) ((const __attribute__((address_space(1))) void*)(p))
 #define FLEXCO_LP(p) ((__attribute__((address_space(3))) void*)(p))
 
@@ -41,6 +42,15 @@ struct ChunkArgs {
 // ds_read_b128 of lane (key = lane % 16, g = lane / 16) - served 16 lanes a cycle in quads {0-3, 12-15, 20-23, 24-27},
 // {4-7, 8-11, 16-19, 28-31} (+32) - touches 16 different chunks per cycle.
 __device__ inline int rsw(int r) { return (((r + ((r >> 3) << 2)) & 7) << 1) | ((r >> 3) & 1); }
+
+// One 8-byte LDS read that stays one: left to itself the compiler pairs the reads of two d tiles, 512 bytes apart,
+// into a ds_read2st64_b64, whose two halves meet in the same banks (counted: 39 % of this kernel's LDS cycles were
+// bank conflicts, all from these reads).  A volatile access is not merged and is still tracked by the compiler's waits.
+__device__ inline bf16x4 lds_read_8(const bf16_t* p) {
+  typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+  const u32x2 v = *(const volatile __attribute__((address_space(3))) u32x2*)FLEXCO_LP(p);
+  return __builtin_bit_cast(bf16x4, v);
+}
 
 __global__ __launch_bounds__(256, 2) void attn_fwd_chunk_kernel(ChunkArgs a, const bf16_t* __restrict__ q, size_t ldq,
                                                                 const bf16_t* __restrict__ kp,
@@ -114,14 +124,14 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_chunk_kernel(ChunkArgs a, con
       __builtin_amdgcn_global_load_lds(FLEXCO_GP(vb_ + v_src), FLEXCO_LP(ring_ + (2 + x) * PAGE_EL + wave * 512), 16, 0, 0); \
     }                                                                                                 \
   }
-  // wait until this wavefront's loads of the stage about to be multiplied have landed (two later stages, 4 loads
-  // each, may stay in flight), then a barrier without memory fences
-#define FLEXCO_CH_WAIT_BARRIER                   \
-  {                                              \
-    __builtin_amdgcn_s_waitcnt(0x0F70 | 8);      \
-    asm volatile("" ::: "memory");               \
-    __builtin_amdgcn_s_barrier();                \
-    asm volatile("" ::: "memory");               \
+  // wait until this wavefront's loads of all stages but the last LATEST_ issued have landed (4 loads each), then a
+  // barrier without memory fences
+#define FLEXCO_CH_WAIT_BARRIER(LATEST_)                     \
+  {                                                         \
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (4 * (LATEST_)));   \
+    asm volatile("" ::: "memory");                          \
+    __builtin_amdgcn_s_barrier();                           \
+    asm volatile("" ::: "memory");                          \
   }
 
   // ---- operand fetches of one stage: K rows as A operand of S^T = K Q^T, lane (key c, g): d = 32 dc + 8 g .. + 8;
@@ -130,42 +140,94 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_chunk_kernel(ChunkArgs a, con
   const int kr_sw = rsw(c);
   const int vr_off = ((2 * c + (g >> 1)) ^ ((c >> 3) & 1)) * 8 + (g & 1) * 4;   // + 256 elements (32 chunks) per d tile mt
 
-  // one step = 32 keys (two pages) against the 16 columns of this wavefront's tile
-#define FLEXCO_CH_COMPUTE(ring_, st_)                                                                 \
-  if (have) {                                                                                         \
-    const int pp = pb + 2 * (st_);                                                                    \
+  // A step = 32 keys (two pages) against the 16 columns of this wavefront's tile, in two halves that run one stage
+  // apart: the score products of stage st + 1 are issued before the softmax of stage st, so that the matrix cores
+  // work through them while the vector ALU does the maxima, exponentials and conversions.
+  // first half: raw scores (before scale and mask) of the stage in ring_, into sc_[page]
+#define FLEXCO_CH_SCORES(ring_, sc_)                                                                  \
+  {                                                                                                   \
     bf16x8 kf[2][4];                                                                                  \
-    bf16x4 vf[2][8];                                                                                  \
-    _Pragma("unroll") for (int x = 0; x < 2; ++x) {                                                   \
+    _Pragma("unroll") for (int x = 0; x < 2; ++x)                                                     \
       _Pragma("unroll") for (int dc = 0; dc < 4; ++dc)                                                \
         kf[x][dc] = *reinterpret_cast<const bf16x8*>(ring_ + x * PAGE_EL + kr_off + (((dc * 4 + g) ^ kr_sw) * 8)); \
-      _Pragma("unroll") for (int mt = 0; mt < 8; ++mt)                                                \
-        vf[x][mt] = *reinterpret_cast<const bf16x4*>(ring_ + (2 + x) * PAGE_EL + mt * 256 + vr_off);  \
+    _Pragma("unroll") for (int x = 0; x < 2; ++x) {                                                   \
+      sc_[x] = f32x4{0.f, 0.f, 0.f, 0.f};                                                             \
+      _Pragma("unroll") for (int dc = 0; dc < 4; ++dc)                                                \
+        sc_[x] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[x][dc], qf[dc], sc_[x], 0, 0, 0);         \
     }                                                                                                 \
+  }
+  // second half: softmax of the scores sc_ of stage st_ and O^T += V^T P^T with the stage's V
+  // V operands per d tile: keys 4 g .. 4 g + 3 of page 0 | of page 1, as the product takes them
+#define FLEXCO_CH_LOAD_V(ring_, vf_)                                                                  \
+    _Pragma("unroll") for (int mt = 0; mt < 8; ++mt)                                                  \
+      vf_[mt] = __builtin_shufflevector(lds_read_8(ring_ + 2 * PAGE_EL + mt * 256 + vr_off),          \
+                                        lds_read_8(ring_ + 3 * PAGE_EL + mt * 256 + vr_off), 0, 1, 2, 3, 4, 5, 6, 7);
+#define FLEXCO_CH_PV(vf_, pf_, alpha_)                                                                \
+    _Pragma("unroll") for (int mt = 0; mt < 8; ++mt) {                                                \
+      f32x4 acc = o[mt];                                                                              \
+      _Pragma("unroll") for (int j = 0; j < 4; ++j) acc[j] *= alpha_;                                 \
+      o[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf_[mt], pf_, acc, 0, 0, 0);                    \
+    }
+  // ... of a stage that lies wholly before every column's own position (most stages of a long window): no masks, no
+  // clearing of unwritten V slots, no branch - one basic block per step, which the compiler may order as it likes and
+  // which keeps the accumulators where they are (every branch in a step cost a copy of all 32 of them at its end)
+#define FLEXCO_CH_SOFTMAX_PV_VISIBLE(ring_, sc_)                                                      \
+  {                                                                                                   \
+    bf16x8 vf[8];                                                                                     \
+    FLEXCO_CH_LOAD_V(ring_, vf)                                                                       \
+    float s[8];                                                                                       \
+    _Pragma("unroll") for (int x = 0; x < 2; ++x)                                                     \
+      _Pragma("unroll") for (int j = 0; j < 4; ++j) s[x * 4 + j] = sc_[x][j] * a.scale_log2;          \
+    float mx = s[0];                                                                                  \
+    _Pragma("unroll") for (int j = 1; j < 8; ++j) mx = fmaxf(mx, s[j]);                               \
+    mx = max_xor16(mx);                                                                               \
+    mx = max_xor32(mx);                                                                               \
+    /* The reference point m of a column's exponentials need not be its running maximum: any m gives the same */ \
+    /* row after the final division by l.  It follows the maximum only when that has moved up by more than    */ \
+    /* LAZY (exponentials then stay below 2^LAZY: no overflow, same relative rounding in bf16), so that the    */ \
+    /* accumulators are rescaled in few steps - in place, inside a branch the wavefront takes as one - instead */ \
+    /* of in every step (32 of a step's 80 vector instructions).                                              */ \
+    if (__builtin_amdgcn_ballot_w64(mx > m + LAZY) != 0) {                                            \
+      const float m_upd = mx > m + LAZY ? mx : m;                                                     \
+      const float alpha = __builtin_amdgcn_exp2f(m - m_upd);                                          \
+      l *= alpha;                                                                                     \
+      m = m_upd;                                                                                      \
+      _Pragma("unroll") for (int mt = 0; mt < 8; ++mt)                                                \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j) o[mt][j] *= alpha;                              \
+    }                                                                                                 \
+    float p[8], psum = 0.f;                                                                           \
+    _Pragma("unroll") for (int j = 0; j < 8; ++j) {                                                   \
+      p[j] = __builtin_amdgcn_exp2f(s[j] - m);                                                        \
+      psum += p[j];                                                                                   \
+    }                                                                                                 \
+    l += psum;                                                                                        \
+    bf16x8 pf;                                                                                        \
+    _Pragma("unroll") for (int j = 0; j < 8; ++j) pf[j] = (bf16_t)p[j];                               \
+    _Pragma("unroll") for (int mt = 0; mt < 8; ++mt)                                                  \
+      o[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[mt], pf, o[mt], 0, 0, 0);                    \
+  }
+  // ... of any stage
+#define FLEXCO_CH_SOFTMAX_PV(ring_, st_, sc_)                                                         \
+  {                                                                                                   \
+    const int pp = pb + 2 * (st_);                                                                    \
+    bf16x8 vf[8];                                                                                     \
+    FLEXCO_CH_LOAD_V(ring_, vf)                                                                       \
     /* V bits of slots past the item's last position may be unwritten memory */                       \
     if ((pp + 2) * PS > last_pos + 1) {                                                               \
       _Pragma("unroll") for (int x = 0; x < 2; ++x)                                                   \
         _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                               \
           const bool ok = (pp + x < pe) && ((pp + x) * PS + 4 * g + j <= last_pos);                   \
           if (!ok) {                                                                                  \
-            _Pragma("unroll") for (int mt = 0; mt < 8; ++mt) vf[x][mt][j] = (bf16_t)0.f;              \
+            _Pragma("unroll") for (int mt = 0; mt < 8; ++mt) vf[mt][4 * x + j] = (bf16_t)0.f;         \
           }                                                                                           \
         }                                                                                             \
     }                                                                                                 \
-    const bool all_visible = (pp + 2) * PS - 1 <= first_pos && pp + 1 < pe;                           \
     float s[8];                                                                                       \
     _Pragma("unroll") for (int x = 0; x < 2; ++x) {                                                   \
-      f32x4 acc = {0.f, 0.f, 0.f, 0.f};                                                               \
-      _Pragma("unroll") for (int dc = 0; dc < 4; ++dc)                                                \
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[x][dc], qf[dc], acc, 0, 0, 0);               \
-      if (all_visible) {                                                                              \
-        _Pragma("unroll") for (int j = 0; j < 4; ++j) s[x * 4 + j] = acc[j] * a.scale_log2;           \
-      } else {                                                                                        \
-        const bool page_ok = pp + x < pe;                                                             \
-        _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                               \
-          const int kpos = (pp + x) * PS + 4 * g + j;                                                 \
-          s[x * 4 + j] = (page_ok && kpos <= pos_c) ? acc[j] * a.scale_log2 : -INFINITY;              \
-        }                                                                                             \
+      const bool page_ok = pp + x < pe;                                                               \
+      _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                 \
+        const int kpos = (pp + x) * PS + 4 * g + j;                                                   \
+        s[x * 4 + j] = (page_ok && kpos <= pos_c) ? sc_[x][j] * a.scale_log2 : -INFINITY;             \
       }                                                                                               \
     }                                                                                                 \
     float mx = s[0];                                                                                  \
@@ -184,35 +246,69 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_chunk_kernel(ChunkArgs a, con
     m = m_new;                                                                                        \
     bf16x8 pf;                                                                                        \
     _Pragma("unroll") for (int j = 0; j < 8; ++j) pf[j] = (bf16_t)p[j];                               \
-    _Pragma("unroll") for (int mt = 0; mt < 8; ++mt) {                                                \
-      bf16x8 vfull;                                                                                   \
-      _Pragma("unroll") for (int j = 0; j < 4; ++j) { vfull[j] = vf[0][mt][j]; vfull[4 + j] = vf[1][mt][j]; } \
-      f32x4 acc = o[mt];                                                                              \
-      _Pragma("unroll") for (int j = 0; j < 4; ++j) acc[j] *= alpha;                                  \
-      o[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vfull, pf, acc, 0, 0, 0);                       \
-    }                                                                                                 \
+    FLEXCO_CH_PV(vf, pf, alpha)                                                                       \
   }
-  // step st: my loads of stage st have landed -> barrier -> everyone's have, and everyone is done with the buffer of
-  // stage st - 1 -> start the loads of stage st + 3 into it -> multiply stage st
-#define FLEXCO_CH_STEP(cur_, free_, st_)                                                              \
+  // step st (cur_ holds stage st, next_ stage st + 1, free_ held stage st - 1): my loads of stage st + 1 have landed
+  // (those of stage st + 2 may be in flight) -> barrier -> everyone's have, and everyone is done with stage st - 1 ->
+  // start the loads of stage st + 3 into its buffer -> scores of stage st + 1 -> softmax and V products of stage st.
+  // Every form of a step has this one barrier, so the wavefronts of a block may each be in a loop of their own.
+#define FLEXCO_CH_STEP_VISIBLE(cur_, next_, free_, st_, sc_cur_, sc_next_)                            \
   {                                                                                                   \
-    FLEXCO_CH_WAIT_BARRIER                                                                            \
+    FLEXCO_CH_WAIT_BARRIER(1)                                                                         \
     FLEXCO_CH_ISSUE(free_, (st_) + 3)                                                                 \
-    FLEXCO_CH_COMPUTE(cur_, st_)                                                                      \
+    FLEXCO_CH_SCORES(next_, sc_next_)                                                                 \
+    FLEXCO_CH_SOFTMAX_PV_VISIBLE(cur_, sc_cur_)                                                       \
+  }
+#define FLEXCO_CH_STEP(cur_, next_, free_, st_, sc_cur_, sc_next_)                                    \
+  {                                                                                                   \
+    FLEXCO_CH_WAIT_BARRIER(1)                                                                         \
+    FLEXCO_CH_ISSUE(free_, (st_) + 3)                                                                 \
+    if ((st_) + 1 < nst) FLEXCO_CH_SCORES(next_, sc_next_)                                            \
+    FLEXCO_CH_SOFTMAX_PV(cur_, st_, sc_cur_)                                                          \
+  }
+#define FLEXCO_CH_STEP_IDLE(free_, st_)                                                               \
+  {                                                                                                   \
+    FLEXCO_CH_WAIT_BARRIER(1)                                                                         \
+    FLEXCO_CH_ISSUE(free_, (st_) + 3)                                                                 \
   }
   FLEXCO_CH_ISSUE(ring0, 0)
   FLEXCO_CH_ISSUE(ring1, 1)
   FLEXCO_CH_ISSUE(ring2, 2)
+  FLEXCO_CH_WAIT_BARRIER(2)        // stage 0 is there
   int st = 0;
-  for (; st + 3 < nst; st += 4) {
-    FLEXCO_CH_STEP(ring0, ring3, st)
-    FLEXCO_CH_STEP(ring1, ring0, st + 1)
-    FLEXCO_CH_STEP(ring2, ring1, st + 2)
-    FLEXCO_CH_STEP(ring3, ring2, st + 3)
+  if (have) {
+    f32x4 sc_a[2], sc_b[2];
+    FLEXCO_CH_SCORES(ring0, sc_a)
+    // leading stages wholly before the item's first position and inside the split, in fours (the ring's period),
+    // and never the last stage (the visible form computes the next stage's scores without asking)
+    const int n_vis = max(min((first_pos + 1) / PS - pb, npg), 0) / 2;
+    const int n_vis4 = min(n_vis, nst - 1) & ~3;
+    for (; st < n_vis4; st += 4) {
+      FLEXCO_CH_STEP_VISIBLE(ring0, ring1, ring3, st, sc_a, sc_b)
+      FLEXCO_CH_STEP_VISIBLE(ring1, ring2, ring0, st + 1, sc_b, sc_a)
+      FLEXCO_CH_STEP_VISIBLE(ring2, ring3, ring1, st + 2, sc_a, sc_b)
+      FLEXCO_CH_STEP_VISIBLE(ring3, ring0, ring2, st + 3, sc_b, sc_a)
+    }
+    for (; st + 3 < nst; st += 4) {
+      FLEXCO_CH_STEP(ring0, ring1, ring3, st, sc_a, sc_b)
+      FLEXCO_CH_STEP(ring1, ring2, ring0, st + 1, sc_b, sc_a)
+      FLEXCO_CH_STEP(ring2, ring3, ring1, st + 2, sc_a, sc_b)
+      FLEXCO_CH_STEP(ring3, ring0, ring2, st + 3, sc_b, sc_a)
+    }
+    if (st < nst) FLEXCO_CH_STEP(ring0, ring1, ring3, st, sc_a, sc_b)
+    if (st + 1 < nst) FLEXCO_CH_STEP(ring1, ring2, ring0, st + 1, sc_b, sc_a)
+    if (st + 2 < nst) FLEXCO_CH_STEP(ring2, ring3, ring1, st + 2, sc_a, sc_b)
+  } else {
+    for (; st + 3 < nst; st += 4) {
+      FLEXCO_CH_STEP_IDLE(ring3, st)
+      FLEXCO_CH_STEP_IDLE(ring0, st + 1)
+      FLEXCO_CH_STEP_IDLE(ring1, st + 2)
+      FLEXCO_CH_STEP_IDLE(ring2, st + 3)
+    }
+    if (st < nst) FLEXCO_CH_STEP_IDLE(ring3, st)
+    if (st + 1 < nst) FLEXCO_CH_STEP_IDLE(ring0, st + 1)
+    if (st + 2 < nst) FLEXCO_CH_STEP_IDLE(ring1, st + 2)
   }
-  if (st < nst) FLEXCO_CH_STEP(ring0, ring3, st)
-  if (st + 1 < nst) FLEXCO_CH_STEP(ring1, ring0, st + 1)
-  if (st + 2 < nst) FLEXCO_CH_STEP(ring2, ring1, st + 2)
   __builtin_amdgcn_s_waitcnt(0x0F70);   // nothing may land in LDS after the block ends
 
   // ---- write the tile's partial, or - the whole key range in one split - its output rows ---------------------
