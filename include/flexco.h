@@ -150,6 +150,9 @@ typedef struct flexco_maps {
                                           these maps and a pool with fewer pages fails with FLEXCO_EPAGE */
   int32_t n_single;                    /* work items that are one tile of one token: the decode stream (and a
                                           chunk's last token where it falls into an item of its own)          */
+  int32_t stream_pages;                /* K / V pages those items read (what the decode stream costs)         */
+  int32_t chunk_tile_pages;            /* sum over the other items of pages x column tiles (what the chunks'
+                                          products cost); both capped at INT32_MAX                            */
   int32_t adapter_tok_off[FLEXCO_MAX_ADAPTERS + 1];   /* lora_tok[off[a] .. off[a+1]) = tokens of adapter a */
   const int32_t* tok_req;       /* [T]                                                    */
   const int32_t* tok_pos;       /* [T]                                                    */
@@ -464,9 +467,14 @@ int32_t flexco_bf16_fallbacks(int64_t* counts, int32_t reset);
  * follow the causal pattern of prefill (Sec. 6.2) - in flexco_layer_forward*, flexco_model_forward and
  * flexco_attention_mixed: 0 = the kernel that also streams the decode tokens (one wavefront per work item), 1 = a
  * kernel of their own (four wavefronts per work item, K / V pages staged in LDS; the decode tokens stay where they
- * are), -1 = chosen by batch (the default: the kernel of their own when the work list has no single-token item, i.e.
- * nothing to stream beside them).  Both kernels do the same arithmetic per column tile.  Process-wide; returns
- * FLEXCO_EINVAL for other values. */
+ * are) launched after the decode tokens' kernel, 2 = that kernel launched beside the decode tokens' kernel, on a side
+ * stream of the library's own (default priority; created on the device's first such call, which therefore must not
+ * fall inside a stream capture) that leaves the caller's stream before the attention and rejoins it after: to the
+ * caller's stream the call behaves as before, also under capture; -1 = chosen by batch, the default: the kernel of
+ * their own alone when the work list has no single-token item, beside the decode stream when the chunks' products
+ * outweigh it (flexco_maps.chunk_tile_pages >= stream_pages), else the one kernel for everything (a light chunk load
+ * hides in the decode stream's waits).  Both kernels do the same arithmetic per column tile: results do not depend
+ * on the mode.  Process-wide; returns FLEXCO_EINVAL for other values. */
 int32_t flexco_attention_chunk_path(int32_t mode);
 
 /* ---- Static graph pruning (Alg. 1, Sec. 5.2), host only -------------------------------------

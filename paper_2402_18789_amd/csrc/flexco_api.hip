@@ -136,9 +136,10 @@ extern "C" int32_t flexco_kernel_timer_stop(int32_t kernel_id, double* total_ms,
 }
 
 // Which kernel takes the chunk items (prefill chunks, finetune windows) of the attention work list: -1 = by batch
-// (the four-wavefront kernel when the work list has no single-token item: beside a decode stream the one-launch
-// kernel hides the chunk items in the stream's waits, which two launches one after the other cannot),
-// 0 = the one-launch kernel, 1 = the four-wavefront kernel.
+// (the four-wavefront kernel alone when the work list has no single-token item, beside the decode tokens' kernel on a
+// side stream when the chunks' products outweigh the decode stream, else the one-launch kernel: a light chunk load
+// hides in the stream's waits there), 0 = the one-launch kernel, 1 = the four-wavefront kernel after the decode
+// tokens' kernel, 2 = beside it.
 static std::atomic<int> g_chunk_path{-1};
 
 // bf16 calls that took a type-generic kernel because the matrix-core kernel of their class does not cover the
@@ -148,9 +149,35 @@ static inline void note_fallback(int dtype, int kernel_id) {
   if (dtype == FLEXCO_BF16) g_bf16_fallbacks[kernel_id].fetch_add(1, std::memory_order_relaxed);
 }
 
+// Side stream of a device (default priority) and the two events that fork it from and join it to the caller's
+// stream, made on first use and kept; the lock is held while a fork / join pair is enqueued, so that two host
+// threads do not interleave their records and waits on the shared events.
+namespace {
+struct SideStream {
+  hipStream_t stream = nullptr;
+  hipEvent_t fork = nullptr, join = nullptr;
+};
+std::mutex g_side_mu;
+SideStream g_side[64];
+int32_t side_stream(SideStream** out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= 64) return fail(FLEXCO_EHIP, "side stream: no current device");
+  SideStream& ss = g_side[dev];
+  if (!ss.stream) {
+    if ((e = hipStreamCreateWithFlags(&ss.stream, hipStreamNonBlocking)) != hipSuccess ||
+        (e = hipEventCreateWithFlags(&ss.fork, hipEventDisableTiming)) != hipSuccess ||
+        (e = hipEventCreateWithFlags(&ss.join, hipEventDisableTiming)) != hipSuccess)
+      return fail(FLEXCO_EHIP, "side stream: %s", hipGetErrorString(e));
+  }
+  *out = &ss;
+  return FLEXCO_OK;
+}
+}  // namespace
+
 extern "C" int32_t flexco_attention_chunk_path(int32_t mode) {
   clear_error();
-  FLEXCO_CHECK(mode >= -1 && mode <= 1, FLEXCO_EINVAL, "mode %d: -1 (by batch), 0 or 1", mode);
+  FLEXCO_CHECK(mode >= -1 && mode <= 2, FLEXCO_EINVAL, "mode %d: -1 (by batch), 0, 1 or 2", mode);
   g_chunk_path.store(mode);
   return FLEXCO_OK;
 }
@@ -660,10 +687,32 @@ int32_t run_attention(const flexco_layer_cfg& c, const flexco_maps& m, const voi
   {
     KernelTimerScope ts(FLEXCO_K_ATTN_FWD, s);
     const int mode = g_chunk_path.load();
-    const bool chunk = mode > 0 || (mode < 0 && m.n_single == 0);
-    // (with no single-token item the one-launch kernel has nothing left to do; its support test still decides)
-    rc = launch_attention_mfma(c, m, q, ldq, pool, part_ml, part_acc, out, ldo, lse, s, keep, chunk, chunk && m.n_single == 0);
-    if (rc == FLEXCO_OK && chunk) rc = launch_attention_chunk_mfma(c, m, q, ldq, pool, part_ml, part_acc, out, ldo, lse, s, keep);
+    const bool mixed = m.n_single > 0 && m.n_single < m.n_items;
+    const bool beside = mixed && (mode == 2 || (mode < 0 && m.chunk_tile_pages >= m.stream_pages));
+    const bool chunk = mode > 0 || (mode < 0 && m.n_single == 0) || beside;
+    if (!beside) {
+      // (with no single-token item the one-launch kernel has nothing left to do; its support test still decides)
+      rc = launch_attention_mfma(c, m, q, ldq, pool, part_ml, part_acc, out, ldo, lse, s, keep, chunk, chunk && m.n_single == 0);
+      if (rc == FLEXCO_OK && chunk) rc = launch_attention_chunk_mfma(c, m, q, ldq, pool, part_ml, part_acc, out, ldo, lse, s, keep);
+    } else {
+      // the decode tokens' kernel on the caller's stream and the chunk items' kernel on the side stream, which
+      // leaves the caller's stream before the first and rejoins it after the second: the two run beside each other
+      // (one lives on HBM, the other on the matrix cores and the vector ALU) and write different rows
+      std::lock_guard<std::mutex> lock(g_side_mu);
+      SideStream* ss = nullptr;
+      FLEXCO_TRY(side_stream(&ss));
+      hipError_t e;
+      if ((e = hipEventRecord(ss->fork, s)) != hipSuccess || (e = hipStreamWaitEvent(ss->stream, ss->fork, 0)) != hipSuccess)
+        return fail(FLEXCO_EHIP, "attention: fork of the side stream failed: %s", hipGetErrorString(e));
+      rc = launch_attention_mfma(c, m, q, ldq, pool, part_ml, part_acc, out, ldo, lse, s, keep, true, false);
+      // (after the fork the side stream must rejoin whatever happens, a stream capture would not end otherwise)
+      const int32_t rc2 = rc == FLEXCO_OK
+                              ? launch_attention_chunk_mfma(c, m, q, ldq, pool, part_ml, part_acc, out, ldo, lse, ss->stream, keep)
+                              : FLEXCO_OK;
+      if ((e = hipEventRecord(ss->join, ss->stream)) != hipSuccess || (e = hipStreamWaitEvent(s, ss->join, 0)) != hipSuccess)
+        return fail(FLEXCO_EHIP, "attention: join of the side stream failed: %s", hipGetErrorString(e));
+      if (rc == FLEXCO_OK) rc = rc2;
+    }
   }
   if (rc == FLEXCO_EUNSUPPORTED) {
     clear_error();

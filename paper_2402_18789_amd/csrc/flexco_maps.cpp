@@ -272,7 +272,7 @@ using namespace flexco;
 
 extern "C" const char* flexco_last_error(void) { return g_err; }
 
-extern "C" int32_t flexco_abi_version(void) { return 6; }
+extern "C" int32_t flexco_abi_version(void) { return 7; }
 
 extern "C" int32_t flexco_maps_blob_ints(const flexco_batch_desc* desc, int32_t page_size, int32_t n_q_heads,
                                          int32_t n_kv_heads, int32_t kv_split_pages, size_t* out_ints) {
@@ -313,8 +313,21 @@ extern "C" int32_t flexco_build_maps(const flexco_batch_desc* desc, int32_t page
   m.ft_adapter = b.ft_req >= 0 ? desc->adapter[b.ft_req] : -1;
   m.num_pages = num_pages;
   m.n_single = 0;
-  for (size_t i = 0; i < b.item_tile.size(); ++i)
-    m.n_single += (b.item_ntiles[i] == 1 && b.tile_ntok[b.item_tile[i]] == 1) ? 1 : 0;
+  int64_t stream_pages = 0, chunk_tile_pages = 0;
+  for (size_t i = 0; i < b.item_tile.size(); ++i) {
+    const int last = b.item_tile[i] + b.item_ntiles[i] - 1;       // the item's last tile sees its whole key range
+    const int vis_pages = b.tok_pos[b.tile_tok0[last] + b.tile_ntok[last] - 1] / page_size + 1;
+    const int pb = b.item_split[i] * b.split_pages;
+    const int pages = std::min(pb + b.split_pages, vis_pages) - pb;
+    if (b.item_ntiles[i] == 1 && b.tile_ntok[b.item_tile[i]] == 1) {
+      ++m.n_single;
+      stream_pages += pages;
+    } else {
+      chunk_tile_pages += (int64_t)pages * b.item_ntiles[i];
+    }
+  }
+  m.stream_pages = (int32_t)std::min<int64_t>(stream_pages, INT32_MAX);
+  m.chunk_tile_pages = (int32_t)std::min<int64_t>(chunk_tile_pages, INT32_MAX);
   memcpy(m.adapter_tok_off, b.adapter_tok_off, sizeof(m.adapter_tok_off));
   m.tok_req = w.put(b.tok_req); m.tok_pos = w.put(b.tok_pos); m.slot = w.put(b.slot);
   m.req_tok_off = w.put(b.req_tok_off); m.req_kv_len = w.put(b.req_kv_len); m.req_kind = w.put(b.req_kind);

@@ -110,6 +110,35 @@ def count_single(cm):
                if cm["item_ntiles"][it] == 1 and cm["tile_ntok"][cm["item_tile"][it]] == 1)
 
 
+def work_sums(cm, page_size):
+    """(pages read by the one-token items, sum over the other items of pages x tiles), from the work list itself."""
+    stream = chunk = 0
+    for it in range(cm["n_items"]):
+        t0, ntl, sp = cm["item_tile"][it], cm["item_ntiles"][it], cm["item_split"][it]
+        last = t0 + ntl - 1
+        vis = cm["tok_pos"][cm["tile_tok0"][last] + cm["tile_ntok"][last] - 1] // page_size + 1
+        pages = min((sp + 1) * cm["kv_split_pages"], vis) - sp * cm["kv_split_pages"]
+        if ntl == 1 and cm["tile_ntok"][t0] == 1:
+            stream += pages
+        else:
+            chunk += pages * ntl
+    return stream, chunk
+
+
+def test_work_sums_that_pick_the_attention_kernels():
+    """stream_pages / chunk_tile_pages weigh the decode stream against the chunks' products (the default choice of
+    flexco_attention_chunk_path): equal to the sums over the work list; the benchmark batch is stream-heavy, the
+    14B-shaped batch with a 1024-row window on a 3072-row prefix chunk-heavy."""
+    c2 = c_maps(gen.batch_c2(0), 32, 8)
+    assert (c2["stream_pages"], c2["chunk_tile_pages"]) == work_sums(c2, 16)
+    assert c2["chunk_tile_pages"] < c2["stream_pages"]
+    c4 = c_maps(gen.batch_c4(0), 40, 8)
+    assert (c4["stream_pages"], c4["chunk_tile_pages"]) == work_sums(c4, 16)
+    assert c4["chunk_tile_pages"] > c4["stream_pages"]
+    none = c_maps(gen.mixed_batch(16, 0, prefill=[(0, 100, 100)]), 32, 8)
+    assert none["stream_pages"] == work_sums(none, 16)[0] and none["chunk_tile_pages"] == work_sums(none, 16)[1] > 0
+
+
 def test_n_single_counts_the_one_token_work_items():
     """n_single is what decides which attention kernel takes the chunk items: zero exactly when no work item is a
     lone token.  A decode request gives one such item per key split; a chunk whose length leaves one token in its
@@ -150,6 +179,7 @@ def test_random_batches_bit_exact_vs_oracle(seed):
     for k in ("T", "n_req", "n_ft", "n_seg", "max_pages"):
         assert cm[k] == om[k], k
     assert cm["n_single"] == count_single(cm)
+    assert (cm["stream_pages"], cm["chunk_tile_pages"]) == work_sums(cm, batch.page_size)
     for k in COMMON:
         assert np.array_equal(cm[k], om[k]), k
     assert check_attention_cover(om, work_items(cm, batch.page_size))

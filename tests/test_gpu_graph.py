@@ -21,9 +21,20 @@ def say(msg):
     print(msg, flush=True)
 
 
-def test_layer_forward_and_window_backward_replay_from_a_graph():
+@pytest.mark.parametrize("chunk_path", [-1, 2])
+def test_layer_forward_and_window_backward_replay_from_a_graph(chunk_path):
+    """chunk_path 2: the attention's chunk items run on the library's side stream, which leaves the captured stream and
+    rejoins it inside the call (flexco_attention_chunk_path); the eager run before the capture has created it."""
+    B.flexco_attention_chunk_path(chunk_path)
+    try:
+        _replay_from_a_graph(chunk_path)
+    finally:
+        B.flexco_attention_chunk_path(-1)
+
+
+def _replay_from_a_graph(chunk_path):
     cfg, seed = SMALL_BF16, 5
-    say("graph capture: mixed batch forward + window backward")
+    say(f"graph capture: mixed batch forward + window backward, chunk_path={chunk_path}")
     batch = gen.batch_scaled(seed, 9, 3, 400, [(0, 70, 70), (128, 64, 300)], [(96, 64, 160)])
     W, lora = gen.layer_weights(cfg, seed, 0), gen.lora_weights(cfg, seed, 0)
     dev = HH.DeviceLayer(cfg, W, lora)

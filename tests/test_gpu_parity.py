@@ -143,7 +143,7 @@ def attention_case(cfg, batch, split, seed=3):
 
 # chunk_path: which kernel takes the prefill chunks and finetune windows (flexco_attention_chunk_path): 0 = the one that
 # streams the decode tokens, 1 = the four-wavefront kernel with K / V staged in LDS
-@pytest.mark.parametrize("chunk_path", [0, 1])
+@pytest.mark.parametrize("chunk_path", [0, 1, 2])
 @pytest.mark.parametrize("name,split", [("c1", 0), ("c1", 2), ("small_bf16", 0), ("small_bf16", 2), ("g5", 4), ("mha", 2),
                                         ("g8", 4), ("long", 0), ("small_bf16", 6), ("long", 250), ("windows", 0), ("windows", 32)])
 def test_attention_mixed(name, split, chunk_path):
