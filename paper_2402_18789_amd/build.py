@@ -18,9 +18,16 @@ FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Xclang", "-tar
          "-Wno-unknown-warning-option"] + os.environ.get("FLEXCO_BUILD_FLAGS", "").split()
 
 
+# Per-source flags.  Kernels whose accumulators fit the 256 architectural registers of a wavefront take their matrix
+# products in the form that reads and writes plain vector registers: left to its default the compiler parked the
+# attention backward's accumulators in accumulation registers and moved them in and out around every product
+# (112 moves per step of the dQ kernel beside its 24 products).
+SOURCE_FLAGS = {"attn_bwd_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+
+
 def _compile(src):
     obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
-    cmd = [HIPCC, "-x", "hip"] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [HIPCC, "-x", "hip"] + FLAGS + SOURCE_FLAGS.get(src, []) + ["-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("hipcc failed for %s:\n%s\n%s" % (src, r.stdout, r.stderr))

@@ -186,8 +186,10 @@ __global__ __launch_bounds__(64 * SP) void attn_bwd_dq_mfma_kernel(BwdArgs a) {
   // logical chunk 2 d + (s % 4) / 2, physical = logical ^ (8 if bit 3 of d, i.e. g odd)
   const int v_base = (((2 * (8 * g + s4) + (sc >> 1)) ^ ((g & 1) << 3)) * 8) + (sc & 1) * 4;
 
-#define FLEXCO_DQ_COMPUTE(kb_, vb_, it_)                                                              \
-  if ((SP * (it_) + 2 * kh) * PS <= wave_last_pos) { /* else: nothing visible to these rows (uniform) */ \
+  // MASKED_ = false: the step's keys lie before every row's own position (the leading steps of a window on a long
+  // prefix): no comparisons, no per-element branches
+#define FLEXCO_DQ_COMPUTE(kb_, vb_, it_, MASKED_)                                                     \
+  if (!(MASKED_) || (SP * (it_) + 2 * kh) * PS <= wave_last_pos) { /* else: nothing visible to these rows (uniform) */ \
     float ds[8];                                                                                      \
     _Pragma("unroll") for (int xx = 0; xx < 2; ++xx) {                                                \
       const bf16_t* kt_ = kb_ + (2 * kh + xx) * TILE16;                                               \
@@ -202,9 +204,11 @@ __global__ __launch_bounds__(64 * SP) void attn_bwd_dq_mfma_kernel(BwdArgs a) {
       }                                                                                               \
       _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                 \
         const int kpos = (SP * (it_) + 2 * kh + xx) * PS + 4 * g + j;                                 \
-        const bool ok = kpos <= pos_c;                                                                \
-        const float p = __builtin_amdgcn_exp2f(sacc[j] * a.scale_log2 - lse2);                        \
-        ds[xx * 4 + j] = ok ? p * (pacc[j] - delta) : 0.f;                                            \
+        const bool ok = !(MASKED_) || kpos <= pos_c;                                                  \
+        /* (the mask goes into the exponent: 2^-inf = 0 without a branch around the exponential) */   \
+        const float e_ = sacc[j] * a.scale_log2 - lse2;                                               \
+        const float p = __builtin_amdgcn_exp2f(ok ? e_ : -INFINITY);                                  \
+        ds[xx * 4 + j] = p * (pacc[j] - delta);                                                       \
       }                                                                                               \
     }                                                                                                 \
     bf16x8 dsf;                                                                                       \
@@ -219,14 +223,14 @@ __global__ __launch_bounds__(64 * SP) void attn_bwd_dq_mfma_kernel(BwdArgs a) {
 
   // step it: my loads of step it have landed -> barrier -> everyone's have, and everyone is done
   // with the other buffer set -> start the loads of step it + 1 into it -> multiply step it
-#define FLEXCO_DQ_STEP(kb_, vb_, kn_, vn_, it_)                                                       \
+#define FLEXCO_DQ_STEP(kb_, vb_, kn_, vn_, it_, MASKED_)                                              \
   {                                                                                                   \
     FLEXCO_WAIT_ALL_BARRIER                                                                           \
     if ((it_) + 1 < nit) {                                                                            \
       FLEXCO_ISSUE(kn_, vn_, (it_) + 1, page_nxt)                                                     \
       page_nxt = a.pages[min(SP * ((it_) + 2) + wave, last_page)];                                    \
     }                                                                                                 \
-    FLEXCO_DQ_COMPUTE(kb_, vb_, it_)                                                                  \
+    FLEXCO_DQ_COMPUTE(kb_, vb_, it_, MASKED_)                                                         \
   }
 
   {
@@ -234,12 +238,21 @@ __global__ __launch_bounds__(64 * SP) void attn_bwd_dq_mfma_kernel(BwdArgs a) {
     FLEXCO_ISSUE(kb0, vb0, 0, page0)
     page_nxt = a.pages[min(SP + wave, last_page)];
   }
+  // leading steps whose two pages of this wavefront (2 kh, 2 kh + 1 of the step's SP) end at or before the position
+  // of the wavefront's first row, in pairs (the two buffer sets); every form of a step has the one barrier, so the
+  // wavefronts of a block may be in different loops
+  const int vis_pages = (a.w0 + i0 + 1) / PS - 2 * kh - 2;           // step it is wholly visible iff SP it <= this
+  const int n_vis = i0 < a.s && vis_pages >= 0 ? min(vis_pages / SP + 1, nit) & ~1 : 0;
   int it = 0;
-  for (; it + 1 < nit; it += 2) {
-    FLEXCO_DQ_STEP(kb0, vb0, kb1, vb1, it)
-    FLEXCO_DQ_STEP(kb1, vb1, kb0, vb0, it + 1)
+  for (; it < n_vis; it += 2) {
+    FLEXCO_DQ_STEP(kb0, vb0, kb1, vb1, it, false)
+    FLEXCO_DQ_STEP(kb1, vb1, kb0, vb0, it + 1, false)
   }
-  if (it < nit) FLEXCO_DQ_STEP(kb0, vb0, kb1, vb1, it)
+  for (; it + 1 < nit; it += 2) {
+    FLEXCO_DQ_STEP(kb0, vb0, kb1, vb1, it, true)
+    FLEXCO_DQ_STEP(kb1, vb1, kb0, vb0, it + 1, true)
+  }
+  if (it < nit) FLEXCO_DQ_STEP(kb0, vb0, kb1, vb1, it, true)
 
   // ---- add the four key quarters (kh = 0, 1, 2, 3 in this order), scale, store -------------------
   float* red = reinterpret_cast<float*>(kb0);                    // [2 rt][32][64 lanes] floats = 16 KB
@@ -357,6 +370,8 @@ __global__ __launch_bounds__(256 * NH, NH == 1 ? 2 : 1) void attn_bwd_dkv_mfma_k
   const int tr_base = tr_row * D + (sc & 1) * 4;
   const int tr_sw = rsw(tr_row), tr_hi = sc >> 1;
 
+  // (an unmasked form of the step for row blocks wholly after the page, chosen per step, cost more in register copies
+  // where the two forms join than the masks do: 200 moves per step; the dQ kernel's steps split into two loops instead)
 #define FLEXCO_DKV_COMPUTE(qb_, ob_, ld_, it_)                                                        \
   {                                                                                                   \
     const int r0 = first_row + 32 * ((it_) % nrb);                                                    \
@@ -379,9 +394,11 @@ __global__ __launch_bounds__(256 * NH, NH == 1 ? 2 : 1) void attn_bwd_dkv_mfma_k
           const int rl = x * 16 + 4 * g + j;            /* lane (key c, g) holds rows 4g..4g+3 of tile x */ \
           const int row = r0 + rl;                                                                    \
           const bool ok = key_ok && row < a.s && kpos <= a.w0 + row;                                  \
-          const float pv = __builtin_amdgcn_exp2f(sacc[j] * a.scale_log2 - lt_[rl] * LOG2E);          \
-          p[x * 4 + j] = ok ? pv : 0.f;                                                               \
-          ds[x * 4 + j] = ok ? pv * (pacc[j] - lt_[32 + rl]) : 0.f;                                   \
+          /* (the mask goes into the exponent: 2^-inf = 0 without a branch around the exponential) */ \
+          const float e_ = sacc[j] * a.scale_log2 - lt_[rl] * LOG2E;   /* (read before the choice: no branch) */ \
+          const float pv = __builtin_amdgcn_exp2f(ok ? e_ : -INFINITY);                               \
+          p[x * 4 + j] = pv;                                                                          \
+          ds[x * 4 + j] = pv * (pacc[j] - lt_[32 + rl]);                                              \
         }                                                                                             \
       }                                                                                               \
       bf16x8 pf, dsf;                                                                                 \
