@@ -376,7 +376,10 @@ __global__ __launch_bounds__(256 * NH, NH == 1 ? 2 : 1) void attn_bwd_dkv_mfma_k
   {                                                                                                   \
     const int r0 = first_row + 32 * ((it_) % nrb);                                                    \
     const bool head_ok = NH * ((it_) / nrb) + hg < group;                                             \
-    if (head_ok && page_ok && key0 <= a.w0 + min(r0 + 31, a.s - 1)) { /* else nothing to add (uniform) */ \
+    /* (a step with nothing to add - a head past the group, a page past the sequence, rows before the page - is not */ \
+    /* skipped: its elements are all masked and add zeros; a branch around the products cost a copy of all 64      */ \
+    /* accumulator registers every second step)                                                                   */ \
+    {                                                                                                 \
       const bf16_t* qt_ = qb_[hg];                                                                    \
       const bf16_t* ot_ = ob_[hg];                                                                    \
       const float* lt_ = ld_[hg];                                                                     \
@@ -393,7 +396,7 @@ __global__ __launch_bounds__(256 * NH, NH == 1 ? 2 : 1) void attn_bwd_dkv_mfma_k
         _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                               \
           const int rl = x * 16 + 4 * g + j;            /* lane (key c, g) holds rows 4g..4g+3 of tile x */ \
           const int row = r0 + rl;                                                                    \
-          const bool ok = key_ok && row < a.s && kpos <= a.w0 + row;                                  \
+          const bool ok = head_ok && key_ok && row < a.s && kpos <= a.w0 + row;                       \
           /* (the mask goes into the exponent: 2^-inf = 0 without a branch around the exponential) */ \
           const float e_ = sacc[j] * a.scale_log2 - lt_[rl] * LOG2E;   /* (read before the choice: no branch) */ \
           const float pv = __builtin_amdgcn_exp2f(ok ? e_ : -INFINITY);                               \
