@@ -191,8 +191,9 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(FwdArgs a, const bf1
 #pragma unroll
       for (int j = 0; j < 8; ++j) pf[j] = (bf16_t)p[j];
       // ---- O^T = alpha O^T + V^T P^T --------------------------------------------------------
-      // (skipping the rescaling once alpha is 1 in every lane was tried: it moves the accumulators out of
-      // the MFMA's registers and back, 45 spilled registers)
+      // (skipping the rescaling while no maximum moves - by a branch with the products inside, or, as the chunk
+      // kernel does, by an in-place multiplication in a branch of its own - was tried twice here: with four tiles'
+      // accumulators the compiler spills 37 - 45 registers and the decode stream slows down by 10 %)
 #pragma unroll
       for (int mt = 0; mt < 8; ++mt) {
         bf16x8 vfull;
