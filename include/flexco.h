@@ -473,8 +473,9 @@ int32_t flexco_bf16_fallbacks(int64_t* counts, int32_t reset);
  * caller's stream the call behaves as before, also under capture; -1 = chosen by batch, the default: the kernel of
  * their own alone when the work list has no single-token item, beside the decode stream when the chunks' products
  * outweigh it (flexco_maps.chunk_tile_pages >= stream_pages), else the one kernel for everything (a light chunk load
- * hides in the decode stream's waits).  Both kernels do the same arithmetic per column tile: results do not depend
- * on the mode.  Process-wide; returns FLEXCO_EINVAL for other values. */
+ * hides in the decode stream's waits).  Both kernels take the same products per column tile; their results agree to
+ * rounding (the kernels scale their running sums at different steps).  Process-wide; returns FLEXCO_EINVAL for other
+ * values. */
 int32_t flexco_attention_chunk_path(int32_t mode);
 
 /* ---- Static graph pruning (Alg. 1, Sec. 5.2), host only -------------------------------------

@@ -8,8 +8,9 @@
 // with one wavefront per SIMD to run it.  Here the same item goes to a BLOCK of four wavefronts, one tile each:
 // the K / V pages of a step are staged once per block in LDS (straight from global memory, a ring of four stages
 // of two pages) and every wavefront reads its operands from there; 64 KB of LDS and under 256 registers put two
-// blocks on a CU.  Same arithmetic per tile, same partial rows and direct outputs as the one-launch kernel, so
-// the merge kernel and everything after see no difference.
+// blocks on a CU.  The same products per tile and the same form of partial rows and direct outputs as the one-launch
+// kernel, so the merge kernel and everything after see no difference; the reference point of a column's
+// exponentials may lag its running maximum here (LAZY below), which moves results by rounding only.
 //
 // bf16, head_dim 128, page_size 16, at most 16 query heads per kv head.
 #include "flexco_internal.h"
