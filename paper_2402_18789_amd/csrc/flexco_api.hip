@@ -198,6 +198,7 @@ namespace {
 
 constexpr size_t SPLITK_COLS = 32768;   // split-K scratch of the backward GEMMs: rows x this many floats
 constexpr int FWD_SPLITK_MAX_T = 256;   // forward batches up to this many tokens get split-K scratch too
+constexpr int ROW_T_MAX_ROWS = 512;     // windows up to this many rows take t = dy B inside the row kernels
 
 struct Carver {
   char* base;
@@ -1123,7 +1124,10 @@ static int32_t layer_backward_impl(const flexco_layer_cfg* cfg, const flexco_bas
   // t_t = dy_t B_t of the down, o and q/k/v targets: by the row kernels that hold the rows of dy_t anyway (dY has a
   // kernel of its own), where rank and type allow; gate / up keep the shrink launch (their dy comes out of a
   // kernel that does not own whole rows)
-  const bool row_t = row_lora_ok(dt, c.lora_rank);
+  // (windows of up to ROW_T_MAX_ROWS rows: a row kernel's product costs its row a fixed few microseconds, a shrink
+  // launch costs about 12 us whatever the window; measured per layer at the 14B shape's 1024-row window: 287 us of
+  // small backward kernels with the row products, 238 with three shrink launches; even at 512 rows)
+  const bool row_t = row_lora_ok(dt, c.lora_rank) && n <= ROW_T_MAX_ROWS;
   grp[0].t_ready = grp[0].fused && row_t;
   grp[2].t_ready = grp[2].fused && row_t;
   grp[3].t_ready = grp[3].fused && row_t;
