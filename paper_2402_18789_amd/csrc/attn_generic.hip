@@ -135,6 +135,64 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(const int32_t* __restric
   }
 }
 
+__device__ inline void store4(float* p, const float (&v)[4]) { *reinterpret_cast<f32x4*>(p) = f32x4{v[0], v[1], v[2], v[3]}; }
+__device__ inline void store4(bf16_t* p, const float (&v)[4]) {
+  bf16x4 t;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) t[j] = (bf16_t)v[j];
+  *reinterpret_cast<bf16x4*>(p) = t;
+}
+
+// The same for head_dim 128 with 16-byte accesses: 32 lanes per (token, query head), eight of them per block (the
+// one-wavefront form above is a grid of T x nq blocks of which most leave at once - tiles with a single split - and
+// the others read four bytes per lane).
+template <typename T>
+__global__ __launch_bounds__(256) void attn_merge128_kernel(const int32_t* __restrict__ tok_tile,
+                                                            const int32_t* __restrict__ tile_tok0,
+                                                            const int32_t* __restrict__ tile_nsplit,
+                                                            const int32_t* __restrict__ tile_part0,
+                                                            const float* __restrict__ part_ml,
+                                                            const float* __restrict__ part_acc, T* __restrict__ out,
+                                                            size_t ldo, float* __restrict__ lse, int nq, int nkv,
+                                                            int cols_per_tile, int skip_single_split, AttnKeep keep) {
+  constexpr int d = 128;
+  const int t = blockIdx.x, h = blockIdx.y * 8 + (threadIdx.x >> 5), ln = threadIdx.x & 31;
+  if (h >= nq) return;
+  const int group = nq / nkv, kvh = h / group;
+  const int tile = tok_tile[t];
+  const int nsplit = tile_nsplit[tile];
+  if (skip_single_split && nsplit == 1) return;   // the attention kernel has written these rows itself
+  const int c = (t - tile_tok0[tile]) * group + h % group;
+  const size_t idx0 = ((size_t)tile_part0[tile] * nkv + kvh) * cols_per_tile + c;
+  const size_t step = (size_t)nkv * cols_per_tile;         // from one split's row to the next
+  float M = -INFINITY;
+  for (int s = 0; s < nsplit; ++s) M = fmaxf(M, part_ml[(idx0 + s * step) * 2]);
+  float L = 0.f;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int s = 0; s < nsplit; ++s) {
+    const size_t idx = idx0 + s * step;
+    const float ms = part_ml[idx * 2];
+    if (ms > -INFINITY) {
+      const float w = __expf(ms - M);
+      L += part_ml[idx * 2 + 1] * w;
+      const f32x4 a = *reinterpret_cast<const f32x4*>(part_acc + idx * d + 4 * ln);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[j] += a[j] * w;
+    }
+  }
+  const float inv = 1.0f / L;
+  float v[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) v[j] = acc[j] * inv;
+  const bool kept = keep.lse2 && t >= keep.tok0 && t < keep.tok0 + keep.n;
+  store4(out + (size_t)t * ldo + h * d + 4 * ln, v);
+  if (kept) store4((T*)keep.out2 + ((size_t)(t - keep.tok0) * nq + h) * d + 4 * ln, v);
+  if (ln == 0) {
+    if (lse) lse[(size_t)t * nq + h] = M + __logf(L);
+    if (kept) keep.lse2[(size_t)(t - keep.tok0) * nq + h] = M + __logf(L);
+  }
+}
+
 // ------------------------------------------------------------------------------------------
 // window backward (Sec. 6.1): queries = window rows at positions win_start + i, keys/values
 // = cached rows [0, l).  P is recomputed from Q, K and the stored log-sum-exp.
@@ -315,6 +373,13 @@ int32_t launch_attention_merge(const flexco_layer_cfg& c, const flexco_maps& m, 
   AttnKeep keep{nullptr, nullptr, 0, 0};
   if (keep_in) keep = *keep_in;
   const int cpt = m.tile_tokens * (c.n_q_heads / c.n_kv_heads);
+  if (c.head_dim == 128 && ((uintptr_t)part_acc & 15) == 0 && ldo % 4 == 0 && ((uintptr_t)out & 15) == 0 &&
+      ((uintptr_t)keep.out2 & 15) == 0) {
+    DISPATCH_T(c.dtype, hipLaunchKernelGGL((attn_merge128_kernel<T>), dim3(m.T, (c.n_q_heads + 7) / 8), dim3(256), 0, s,
+                                           m.tok_tile, m.tile_tok0, m.tile_nsplit, m.tile_part0, part_ml, part_acc, (T*)out,
+                                           ldo, lse, c.n_q_heads, c.n_kv_heads, cpt, skip_single_split ? 1 : 0, keep));
+    return post_launch("attn_merge");
+  }
   DISPATCH_T(c.dtype, hipLaunchKernelGGL((attn_merge_kernel<T>), dim3(m.T, c.n_q_heads), dim3(64), 0, s, m.tok_tile,
                                          m.tile_tok0, m.tile_nsplit, m.tile_part0, part_ml, part_acc, (T*)out, ldo,
                                          lse, c.n_q_heads, c.n_kv_heads, c.head_dim, cpt, skip_single_split ? 1 : 0, keep));
