@@ -53,7 +53,12 @@ __device__ inline bf16x4 lds_read_8(const bf16_t* p) {
   return __builtin_bit_cast(bf16x4, v);
 }
 
-__global__ __launch_bounds__(256, 2) void attn_fwd_chunk_kernel(ChunkArgs a, const bf16_t* __restrict__ q, size_t ldq,
+// RING = stages of the K / V ring.  4: 65 KB of LDS, two blocks per CU, two stages of loads in flight - the form that
+// runs beside the decode tokens' kernel.  3: 49 KB and at most 168 registers, three blocks per CU, one stage in flight -
+// 7 - 10 % faster when the kernel has the chip to itself (three wavefronts per SIMD fill each other's waits), no
+// better beside the decode stream, which it crowds out of the CUs.
+template <int RING>
+__global__ __launch_bounds__(256, RING == 3 ? 3 : 2) void attn_fwd_chunk_kernel(ChunkArgs a, const bf16_t* __restrict__ q, size_t ldq,
                                                                 const bf16_t* __restrict__ kp,
                                                                 const bf16_t* __restrict__ vp,
                                                                 float* __restrict__ part_ml,
@@ -61,7 +66,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_chunk_kernel(ChunkArgs a, con
   __shared__ __attribute__((aligned(1024))) bf16_t ring0[STAGE_EL];
   __shared__ __attribute__((aligned(1024))) bf16_t ring1[STAGE_EL];
   __shared__ __attribute__((aligned(1024))) bf16_t ring2[STAGE_EL];
-  __shared__ __attribute__((aligned(1024))) bf16_t ring3[STAGE_EL];
+  __shared__ __attribute__((aligned(1024))) bf16_t ring3[RING == 4 ? STAGE_EL : 8];
   __shared__ int page_tab[MAXSP];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -255,60 +260,97 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_chunk_kernel(ChunkArgs a, con
   // Every form of a step has this one barrier, so the wavefronts of a block may each be in a loop of their own.
 #define FLEXCO_CH_STEP_VISIBLE(cur_, next_, free_, st_, sc_cur_, sc_next_)                            \
   {                                                                                                   \
-    FLEXCO_CH_WAIT_BARRIER(1)                                                                         \
-    FLEXCO_CH_ISSUE(free_, (st_) + 3)                                                                 \
+    FLEXCO_CH_WAIT_BARRIER(RING - 3)                                                                  \
+    FLEXCO_CH_ISSUE(free_, (st_) + RING - 1)                                                          \
     FLEXCO_CH_SCORES(next_, sc_next_)                                                                 \
     FLEXCO_CH_SOFTMAX_PV_VISIBLE(cur_, sc_cur_)                                                       \
   }
 #define FLEXCO_CH_STEP(cur_, next_, free_, st_, sc_cur_, sc_next_)                                    \
   {                                                                                                   \
-    FLEXCO_CH_WAIT_BARRIER(1)                                                                         \
-    FLEXCO_CH_ISSUE(free_, (st_) + 3)                                                                 \
+    FLEXCO_CH_WAIT_BARRIER(RING - 3)                                                                  \
+    FLEXCO_CH_ISSUE(free_, (st_) + RING - 1)                                                          \
     if ((st_) + 1 < nst) FLEXCO_CH_SCORES(next_, sc_next_)                                            \
     FLEXCO_CH_SOFTMAX_PV(cur_, st_, sc_cur_)                                                          \
   }
 #define FLEXCO_CH_STEP_IDLE(free_, st_)                                                               \
   {                                                                                                   \
-    FLEXCO_CH_WAIT_BARRIER(1)                                                                         \
-    FLEXCO_CH_ISSUE(free_, (st_) + 3)                                                                 \
+    FLEXCO_CH_WAIT_BARRIER(RING - 3)                                                                  \
+    FLEXCO_CH_ISSUE(free_, (st_) + RING - 1)                                                          \
   }
-  FLEXCO_CH_ISSUE(ring0, 0)
-  FLEXCO_CH_ISSUE(ring1, 1)
-  FLEXCO_CH_ISSUE(ring2, 2)
-  FLEXCO_CH_WAIT_BARRIER(2)        // stage 0 is there
-  int st = 0;
-  if (have) {
-    f32x4 sc_a[2], sc_b[2];
-    FLEXCO_CH_SCORES(ring0, sc_a)
-    // leading stages wholly before the item's first position and inside the split, in fours (the ring's period),
-    // and never the last stage (the visible form computes the next stage's scores without asking)
-    const int n_vis = max(min((first_pos + 1) / PS - pb, npg), 0) / 2;
-    const int n_vis4 = min(n_vis, nst - 1) & ~3;
-    for (; st < n_vis4; st += 4) {
-      FLEXCO_CH_STEP_VISIBLE(ring0, ring1, ring3, st, sc_a, sc_b)
-      FLEXCO_CH_STEP_VISIBLE(ring1, ring2, ring0, st + 1, sc_b, sc_a)
-      FLEXCO_CH_STEP_VISIBLE(ring2, ring3, ring1, st + 2, sc_a, sc_b)
-      FLEXCO_CH_STEP_VISIBLE(ring3, ring0, ring2, st + 3, sc_b, sc_a)
+  // three buffers: step st reads V of stage st in ring[st % 3] and K of stage st + 1 in ring[(st + 1) % 3] and refills
+  // ring[(st + 2) % 3]; with the two score buffers in turn the pattern repeats every six steps
+#define FLEXCO_CH_SIX(STEP_, st_)                                     \
+      STEP_(ring0, ring1, ring2, (st_), sc_a, sc_b)                   \
+      STEP_(ring1, ring2, ring0, (st_) + 1, sc_b, sc_a)               \
+      STEP_(ring2, ring0, ring1, (st_) + 2, sc_a, sc_b)               \
+      STEP_(ring0, ring1, ring2, (st_) + 3, sc_b, sc_a)               \
+      STEP_(ring1, ring2, ring0, (st_) + 4, sc_a, sc_b)               \
+      STEP_(ring2, ring0, ring1, (st_) + 5, sc_b, sc_a)
+  if constexpr (RING == 4) {
+    FLEXCO_CH_ISSUE(ring0, 0)
+    FLEXCO_CH_ISSUE(ring1, 1)
+    FLEXCO_CH_ISSUE(ring2, 2)
+    FLEXCO_CH_WAIT_BARRIER(2)        // stage 0 is there
+    int st = 0;
+    if (have) {
+      f32x4 sc_a[2], sc_b[2];
+      FLEXCO_CH_SCORES(ring0, sc_a)
+      // leading stages wholly before the item's first position and inside the split, in fours (the ring's period),
+      // and never the last stage (the visible form computes the next stage's scores without asking)
+      const int n_vis = max(min((first_pos + 1) / PS - pb, npg), 0) / 2;
+      const int n_vis4 = min(n_vis, nst - 1) & ~3;
+      for (; st < n_vis4; st += 4) {
+        FLEXCO_CH_STEP_VISIBLE(ring0, ring1, ring3, st, sc_a, sc_b)
+        FLEXCO_CH_STEP_VISIBLE(ring1, ring2, ring0, st + 1, sc_b, sc_a)
+        FLEXCO_CH_STEP_VISIBLE(ring2, ring3, ring1, st + 2, sc_a, sc_b)
+        FLEXCO_CH_STEP_VISIBLE(ring3, ring0, ring2, st + 3, sc_b, sc_a)
+      }
+      for (; st + 3 < nst; st += 4) {
+        FLEXCO_CH_STEP(ring0, ring1, ring3, st, sc_a, sc_b)
+        FLEXCO_CH_STEP(ring1, ring2, ring0, st + 1, sc_b, sc_a)
+        FLEXCO_CH_STEP(ring2, ring3, ring1, st + 2, sc_a, sc_b)
+        FLEXCO_CH_STEP(ring3, ring0, ring2, st + 3, sc_b, sc_a)
+      }
+      if (st < nst) FLEXCO_CH_STEP(ring0, ring1, ring3, st, sc_a, sc_b)
+      if (st + 1 < nst) FLEXCO_CH_STEP(ring1, ring2, ring0, st + 1, sc_b, sc_a)
+      if (st + 2 < nst) FLEXCO_CH_STEP(ring2, ring3, ring1, st + 2, sc_a, sc_b)
+    } else {
+      for (; st + 3 < nst; st += 4) {
+        FLEXCO_CH_STEP_IDLE(ring3, st)
+        FLEXCO_CH_STEP_IDLE(ring0, st + 1)
+        FLEXCO_CH_STEP_IDLE(ring1, st + 2)
+        FLEXCO_CH_STEP_IDLE(ring2, st + 3)
+      }
+      if (st < nst) FLEXCO_CH_STEP_IDLE(ring3, st)
+      if (st + 1 < nst) FLEXCO_CH_STEP_IDLE(ring0, st + 1)
+      if (st + 2 < nst) FLEXCO_CH_STEP_IDLE(ring1, st + 2)
     }
-    for (; st + 3 < nst; st += 4) {
-      FLEXCO_CH_STEP(ring0, ring1, ring3, st, sc_a, sc_b)
-      FLEXCO_CH_STEP(ring1, ring2, ring0, st + 1, sc_b, sc_a)
-      FLEXCO_CH_STEP(ring2, ring3, ring1, st + 2, sc_a, sc_b)
-      FLEXCO_CH_STEP(ring3, ring0, ring2, st + 3, sc_b, sc_a)
-    }
-    if (st < nst) FLEXCO_CH_STEP(ring0, ring1, ring3, st, sc_a, sc_b)
-    if (st + 1 < nst) FLEXCO_CH_STEP(ring1, ring2, ring0, st + 1, sc_b, sc_a)
-    if (st + 2 < nst) FLEXCO_CH_STEP(ring2, ring3, ring1, st + 2, sc_a, sc_b)
   } else {
-    for (; st + 3 < nst; st += 4) {
-      FLEXCO_CH_STEP_IDLE(ring3, st)
-      FLEXCO_CH_STEP_IDLE(ring0, st + 1)
-      FLEXCO_CH_STEP_IDLE(ring1, st + 2)
-      FLEXCO_CH_STEP_IDLE(ring2, st + 3)
+    FLEXCO_CH_ISSUE(ring0, 0)
+    FLEXCO_CH_ISSUE(ring1, 1)
+    FLEXCO_CH_WAIT_BARRIER(1)        // stage 0 is there
+    int st = 0;
+    if (have) {
+      f32x4 sc_a[2], sc_b[2];
+      FLEXCO_CH_SCORES(ring0, sc_a)
+      const int n_vis = max(min((first_pos + 1) / PS - pb, npg), 0) / 2;
+      const int n_vis6 = (min(n_vis, nst - 1) / 6) * 6;
+      for (; st < n_vis6; st += 6) { FLEXCO_CH_SIX(FLEXCO_CH_STEP_VISIBLE, st) }
+      for (; st + 5 < nst; st += 6) { FLEXCO_CH_SIX(FLEXCO_CH_STEP, st) }
+      if (st < nst) FLEXCO_CH_STEP(ring0, ring1, ring2, st, sc_a, sc_b)
+      if (st + 1 < nst) FLEXCO_CH_STEP(ring1, ring2, ring0, st + 1, sc_b, sc_a)
+      if (st + 2 < nst) FLEXCO_CH_STEP(ring2, ring0, ring1, st + 2, sc_a, sc_b)
+      if (st + 3 < nst) FLEXCO_CH_STEP(ring0, ring1, ring2, st + 3, sc_b, sc_a)
+      if (st + 4 < nst) FLEXCO_CH_STEP(ring1, ring2, ring0, st + 4, sc_a, sc_b)
+    } else {
+      for (; st + 2 < nst; st += 3) {
+        FLEXCO_CH_STEP_IDLE(ring2, st)
+        FLEXCO_CH_STEP_IDLE(ring0, st + 1)
+        FLEXCO_CH_STEP_IDLE(ring1, st + 2)
+      }
+      if (st < nst) FLEXCO_CH_STEP_IDLE(ring2, st)
+      if (st + 1 < nst) FLEXCO_CH_STEP_IDLE(ring0, st + 1)
     }
-    if (st < nst) FLEXCO_CH_STEP_IDLE(ring3, st)
-    if (st + 1 < nst) FLEXCO_CH_STEP_IDLE(ring0, st + 1)
-    if (st + 2 < nst) FLEXCO_CH_STEP_IDLE(ring1, st + 2)
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);   // nothing may land in LDS after the block ends
 
@@ -358,10 +400,11 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_chunk_kernel(ChunkArgs a, con
 }  // namespace
 
 // The chunk items of the work list (everything but single decode tokens) on the four-wavefront kernel; the caller
-// has the one-launch kernel skip them.  Same support test as launch_attention_mfma.
+// has the one-launch kernel skip them.  Same support test as launch_attention_mfma.  alone: no other kernel of the
+// call runs beside this one (the work list has no decode token).
 int32_t launch_attention_chunk_mfma(const flexco_layer_cfg& c, const flexco_maps& m, const void* q, size_t ldq,
                                     const flexco_kv_pool& pool, float* part_ml, float* part_acc, void* out, size_t ldo,
-                                    float* lse, hipStream_t s, const AttnKeep* keep) {
+                                    float* lse, hipStream_t s, const AttnKeep* keep, bool alone) {
   const int group = c.n_q_heads / c.n_kv_heads;
   if (c.dtype != FLEXCO_BF16 || c.head_dim != D || c.page_size != PS || group > 16 || ldq % 8 != 0 ||
       m.kv_split_pages > MAXSP || ldo % 4 != 0 || ((uintptr_t)out & 7))
@@ -376,9 +419,14 @@ int32_t launch_attention_chunk_mfma(const flexco_layer_cfg& c, const flexco_maps
   a.scale_log2 = 1.4426950408889634f / sqrtf((float)D);
   a.out = (bf16_t*)out; a.ldo = ldo; a.lse = lse;
   a.keep = keep ? *keep : AttnKeep{nullptr, nullptr, 0, 0};
-  hipLaunchKernelGGL(attn_fwd_chunk_kernel, dim3((unsigned)m.n_items * c.n_kv_heads), dim3(256), 0, s, a,
-                     (const bf16_t*)q, ldq, (const bf16_t*)pool.k_pages, (const bf16_t*)pool.v_pages, part_ml,
-                     part_acc);
+  if (alone)
+    hipLaunchKernelGGL(attn_fwd_chunk_kernel<3>, dim3((unsigned)m.n_items * c.n_kv_heads), dim3(256), 0, s, a,
+                       (const bf16_t*)q, ldq, (const bf16_t*)pool.k_pages, (const bf16_t*)pool.v_pages, part_ml,
+                       part_acc);
+  else
+    hipLaunchKernelGGL(attn_fwd_chunk_kernel<4>, dim3((unsigned)m.n_items * c.n_kv_heads), dim3(256), 0, s, a,
+                       (const bf16_t*)q, ldq, (const bf16_t*)pool.k_pages, (const bf16_t*)pool.v_pages, part_ml,
+                       part_acc);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(FLEXCO_EHIP, "launch of attn_fwd_chunk failed: %s", hipGetErrorString(e));
   return FLEXCO_OK;

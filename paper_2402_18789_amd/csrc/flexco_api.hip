@@ -694,7 +694,8 @@ int32_t run_attention(const flexco_layer_cfg& c, const flexco_maps& m, const voi
     if (!beside) {
       // (with no single-token item the one-launch kernel has nothing left to do; its support test still decides)
       rc = launch_attention_mfma(c, m, q, ldq, pool, part_ml, part_acc, out, ldo, lse, s, keep, chunk, chunk && m.n_single == 0);
-      if (rc == FLEXCO_OK && chunk) rc = launch_attention_chunk_mfma(c, m, q, ldq, pool, part_ml, part_acc, out, ldo, lse, s, keep);
+      if (rc == FLEXCO_OK && chunk)
+        rc = launch_attention_chunk_mfma(c, m, q, ldq, pool, part_ml, part_acc, out, ldo, lse, s, keep, m.n_single == 0);
     } else {
       // the decode tokens' kernel on the caller's stream and the chunk items' kernel on the side stream, which
       // leaves the caller's stream before the first and rejoins it after the second: the two run beside each other

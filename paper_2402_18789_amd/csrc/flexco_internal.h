@@ -190,7 +190,7 @@ int32_t launch_attention_mfma(const flexco_layer_cfg& c, const flexco_maps& m, c
 // the chunk items (everything but single decode tokens) of the same work list, four wavefronts per item, K / V staged in LDS
 int32_t launch_attention_chunk_mfma(const flexco_layer_cfg& c, const flexco_maps& m, const void* q, size_t ldq,
                                     const flexco_kv_pool& pool, float* part_ml, float* part_acc, void* out, size_t ldo,
-                                    float* lse, hipStream_t s, const AttnKeep* keep = nullptr);
+                                    float* lse, hipStream_t s, const AttnKeep* keep = nullptr, bool alone = false);
 // bf16 window backward on the matrix cores; FLEXCO_EUNSUPPORTED (nothing launched) for other shapes
 int32_t launch_attention_bwd_mfma(const flexco_layer_cfg& c, const flexco_kv_pool& pool, const int32_t* seq_pages,
                                   int win_start, int win_len, const void* q, const void* out, const float* lse,
