@@ -636,6 +636,16 @@ def test_layer_c4_inference_share_sweep_full_size_sampled(share):
     full_size_sampled(CONFIGS["c4_qwen14b_full"], gen.batch_c4(0, share), 6)
 
 
+def test_layer_c4_decode_free_iteration_full_size():
+    """An iteration without inference decode tokens at the 14B shape (a whole 512-token prompt and the 1024-row
+    finetune window on its 3072-row prefix): the attention's chunk items then run on the four-wavefront kernel alone, in
+    its three-stage form; every request goes through the oracle."""
+    say("layer c4, decode-free iteration, full size")
+    cfg = CONFIGS["c4_qwen14b_full"]
+    batch = gen.mixed_batch(cfg.page_size, 0, decode_ctx=(), prefill=[(0, 512, 512)], finetune=[(3072, 1024, 4096)])
+    full_size_sampled(cfg, batch, 0)
+
+
 def full_size_sampled(cfg, batch, n_decode):
     seed = 0
     tol = TOL["bf16"]
