@@ -105,24 +105,26 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
   constexpr int SL = BK / 16;                                       // MFMA k-slices per stage
   constexpr int PA = BM / 32, PB = BN / 32;                         // 1 KB load instructions per wavefront and stage
   constexpr int ST_ELEMS = (BM + BN) * BK;
-  static_assert(!TRANS || BN == 128, "the input-gradient form's W tile swizzle assumes 256-byte rows");
+  static_assert(!TRANS || BN == 128 || BN == 256, "the input-gradient form's W tile swizzle assumes 256- or 512-byte rows");
   __shared__ __attribute__((aligned(1024))) bf16_t ring0[ST_ELEMS];
   __shared__ __attribute__((aligned(1024))) bf16_t ring1[ST_ELEMS];
   __shared__ __attribute__((aligned(1024))) bf16_t ring2[NST == 4 ? ST_ELEMS : 8];
   __shared__ __attribute__((aligned(1024))) bf16_t ring3[NST == 4 ? ST_ELEMS : 8];
   // [rows][64] tiles (128-byte rows): chunk c of row r is stored at chunk c ^ ((r >> 1) & 7) (the
   // variant measured fastest for the ds_read_b128 operand fetches: 85 % of the LDS peak).
-  // [64][128] W tile of the input-gradient form (256-byte rows, read by transposing LDS reads of
+  // [64][BN] W tile of the input-gradient form (256- or 512-byte rows, read by transposing LDS reads of
   // 4 consecutive rows x 64 bytes per pass): chunk c of row r is stored at chunk c ^ (4 (r & 3)),
-  // which puts the four rows of a pass on the four 64-byte quarters of the banks.
+  // which puts the four rows of a pass on the four 64-byte quarters of the banks (the exchange stays
+  // inside a 256-byte half of a 512-byte row).
 #define FLEXCO_KEY(r_) (((r_) >> 1) & 7)
   // Load instruction p of wavefront w fills 1 KB = rows 8 (4 p + w) .. + 8 of a [rows][64] tile (rows
-  // 4 (4 p + w) .. + 4 of the [64][128] tile); lane l lands at base + 16 l, so it fetches from global
-  // memory the logical chunk that belongs at its physical chunk.  The keys do not depend on p.
+  // TR (4 p + w) .. + TR of the [64][BN] tile, TR = 512 / BN); lane l lands at base + 16 l, so it fetches from
+  // global memory the logical chunk that belongs at its physical chunk.  The keys do not depend on p.
   const int d_row = lane >> 3;
   const int d_c = (lane & 7) ^ FLEXCO_KEY(wave * 8 + d_row);
-  const int t_row = lane >> 4;
-  const int t_c = (lane & 15) ^ (t_row << 2);
+  constexpr int TCH = BN / 8, TR = 64 / TCH;      // 16-byte chunks of a W-tile row, rows per load instruction
+  const int t_row = lane / TCH;
+  const int t_c = (lane % TCH) ^ (((wave * TR + t_row) & 3) << 2);
   const bf16_t* ga[PA];
   const bf16_t* gw[PB];
 #pragma unroll
@@ -142,7 +144,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
     } else {
       int col = n0 + t_c * 8;
       if (col >= N) col = 0;   // masked at the store
-      gw[p] = W + (size_t)(kbeg + (p * 4 + wave) * 4 + t_row) * ldw + col;
+      gw[p] = W + (size_t)(kbeg + (p * 4 + wave) * TR + t_row) * ldw + col;
     }
   }
   const int ns = k_chunk / BK;                   // stages of this block
@@ -620,6 +622,9 @@ static int pick_splits(int M, int N, int K, int tiles, size_t part_elems, int wa
   return best;
 }
 
+// Rates of the input-gradient form's two tile shapes with the chip full, PFLOP/s (measured at M = 1024).
+constexpr double TRANS_RATE_128 = 0.8, TRANS_RATE_256 = 1.0;
+
 // Tile shapes of a forward-form product by estimated time.  A launch runs in rounds of one block per CU; a
 // round costs the tile's area over the rate its kernel sustains with the chip full (measured, relative:
 // 256 x 256 tiles 1.24, 256 x 192 1.09, 128 x 192 1.0, 128 x 128 0.875).  Candidates: columns [0, 256 a) in
@@ -674,11 +679,33 @@ int32_t launch_gemm_mfma(const void* A, const void* W, void* C, const void* bias
     // (256 x 128 tiles, one block per CU, were measured slower than two co-resident 128 x 128 blocks)
     const int tiles = ((M + 127) / 128) * ((N + 127) / 128);
     const int sp = part ? pick_splits(M, N, K, tiles, part_elems, 512) : 1;
+    // A window of 512 rows or more has the rows for 256 x 256 tiles, one block per CU, which sustain more per CU
+    // than two 128 x 128 blocks; few of them cover the output, so the choice goes by estimated time: the k-range of
+    // a block x the area a CU holds at a time over the rate of the shape, x the rounds of the grid - whole rounds
+    // for the large tile (one block per CU, all of one length), the plain ratio of blocks to slots for the small one
+    // (a slot is refilled as it frees) - plus the partial sums' way out and back in.
+    int sp256 = 0;
+    if (M >= 512) {
+      auto est_us = [&](double rounds, int splits, double area, double pflops) {
+        return rounds * (K / splits) * area * 2.0 * 256 / (pflops * 1e9) + (splits > 1 ? (double)splits * M * N * 8.0 / 6e6 : 0.0);
+      };
+      double best = est_us(std::max(1.0, (double)tiles * sp / 512), sp, 2.0 * 128 * 128, TRANS_RATE_128);
+      const long tiles256 = (long)((M + 255) / 256) * ((N + 255) / 256);
+      for (int c = 1; c <= 16; ++c) {
+        if (K % (c * BK) != 0 || (c > 1 && (K / c < 8 * BK || !part || (size_t)c * M * N > part_elems))) continue;
+        const double t = est_us((double)((tiles256 * c + 255) / 256), c, 256.0 * 256, TRANS_RATE_256);
+        if (t < best - 1e-9) { best = t; sp256 = c; }
+      }
+    }
+    const int spu = sp256 ? sp256 : sp;
     // splits_out: the caller's next kernel adds the partial sums itself (part[split][M][N], in split order) and
     // the reduction launch is left out; bias and residual are then not applied
-    const bool leave = splits_out && sp > 1 && !bias && !residual;
-    if (leave) *splits_out = sp;
-    return launch_cfg<128, 128, true>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, ext, s, timer_id, part, sp, true,
+    const bool leave = splits_out && spu > 1 && !bias && !residual;
+    if (leave) *splits_out = spu;
+    if (sp256)
+      return launch_cfg<256, 256, true>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, ext, s, timer_id, part, spu, true,
+                                        nullptr, leave);
+    return launch_cfg<128, 128, true>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, ext, s, timer_id, part, spu, true,
                                       nullptr, leave);
   }
   if (!ext_fits(ext, false, N)) return FLEXCO_EUNSUPPORTED;

@@ -55,7 +55,11 @@ def say(msg):
                                          (1024, 6152, 128, 0), (1024, 28672, 64, 0), (1000, 28680, 128, 0),
                                          # more 128 x 128 tiles than CUs (450): the two-stage blocks that share a CU, ragged in
                                          # M and N, odd number of k-stages
-                                         (1100, 6344, 320, 0)])
+                                         (1100, 6344, 320, 0),
+                                         # input-gradient form on 256 x 256 tiles (a window of 512 rows or more whose
+                                         # large tiles fill most of the CUs in one round), ragged in M and N, odd and
+                                         # even numbers of k-stages
+                                         (1000, 13832, 320, 1), (700, 18184, 128, 1)])
 def test_gemm(dtype, M, N, K, trans):
     say(f"gemm {dtype} M={M} N={N} K={K} trans={trans}")
     cfg = C1.with_(dtype=dtype)
