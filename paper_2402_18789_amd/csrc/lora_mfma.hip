@@ -22,8 +22,8 @@ namespace flexco {
 
 namespace {
 
-// One block per 16 rows and matrix; K is cut across the block's wavefronts (blockDim.x / 64, a
-// power of two <= 16), whose partial sums are added in wavefront order through LDS.
+// One block per 16 rows and matrix; K is cut across the block's wavefronts (blockDim.x / 64, at most 16),
+// whose partial sums are added in wavefront order through LDS.
 template <int RT>   // rank tiles of 16
 __global__ __launch_bounds__(1024) void lora_shrink_kernel(LoraShrinkArgs a) {
   __shared__ float red[16][RT][64][4];
@@ -370,8 +370,8 @@ int32_t launch_lora_shrink_mfma(const LoraShrinkArgs& a_in, int n_mats, hipStrea
   if (a.rows == 0 || n_mats == 0) return FLEXCO_OK;
   for (int z = 0; z < n_mats; ++z)
     if (a.K[z] % 128 != 0) return fail(FLEXCO_ESHAPE, "LoRA shrink: K = %d is not a multiple of 128", a.K[z]);
-  // K is cut into whole groups of 4 MFMA steps (128 columns), first over the wavefronts of a block (a
-  // power of two <= 16), and - long contractions with scratch at hand - over several blocks per row tile,
+  // K is cut into whole groups of 4 MFMA steps (128 columns), first over the wavefronts of a block (at
+  // most 16), and - long contractions with scratch at hand - over several blocks per row tile,
   // so that more than rows / 16 CUs pull the operands in
   int kmin = a.K[0], kmax = a.K[0];
   for (int z = 1; z < n_mats; ++z) { kmin = a.K[z] < kmin ? a.K[z] : kmin; kmax = a.K[z] > kmax ? a.K[z] : kmax; }
@@ -379,9 +379,15 @@ int32_t launch_lora_shrink_mfma(const LoraShrinkArgs& a_in, int n_mats, hipStrea
   if (a.part && n_mats <= a.part_slots && kmin == kmax && kmax >= 8192)
     for (int sp = LORA_SHRINK_SPLITS; sp > 1; --sp)
       if (kmax % (128 * sp) == 0 && kmax / sp >= 1024) { a.ksplit = sp; break; }
-  int nw = a.ksplit > 1 ? 8 : 16;
-  for (int z = 0; z < n_mats; ++z)
-    while (nw > 1 && a.K[z] % (128 * nw * a.ksplit) != 0) nw >>= 1;
+  // wavefronts of a block: a count (not only powers of two) that cuts every K into whole groups, taken for the fewest
+  // load rounds of the longest contraction (a round is up to 256 columns per wavefront), the smallest such count
+  int nw = 1, best_rounds = (kmax / a.ksplit + 255) / 256;
+  for (int c = 2; c <= 16; ++c) {
+    bool fits = true;
+    for (int z = 0; z < n_mats; ++z) fits = fits && a.K[z] % (128 * c * a.ksplit) == 0;
+    const int rounds = (kmax / (c * a.ksplit) + 255) / 256;
+    if (fits && rounds < best_rounds) { nw = c; best_rounds = rounds; }
+  }
   const dim3 grid((a.rows + 15) / 16, n_mats, a.ksplit), block(64 * nw);
   const int rt = (a.r + 15) / 16;
   switch (rt) {
