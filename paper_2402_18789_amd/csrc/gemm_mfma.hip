@@ -622,8 +622,9 @@ static int pick_splits(int M, int N, int K, int tiles, size_t part_elems, int wa
   return best;
 }
 
-// Rates of the input-gradient form's two tile shapes with the chip full, PFLOP/s (measured at M = 1024).
-constexpr double TRANS_RATE_128 = 0.8, TRANS_RATE_256 = 1.0;
+// Rates of the input-gradient form's two tile shapes with every block slot taken, PFLOP/s (fitted to twelve products of
+// 512 to 1536 rows at the 8B, 14B and 32B shapes; with them the estimate picks the faster shape in each).
+constexpr double TRANS_RATE_128 = 0.94, TRANS_RATE_256 = 1.05;
 
 // Tile shapes of a forward-form product by estimated time.  A launch runs in rounds of one block per CU; a
 // round costs the tile's area over the rate its kernel sustains with the chip full (measured, relative:
@@ -680,20 +681,20 @@ int32_t launch_gemm_mfma(const void* A, const void* W, void* C, const void* bias
     const int tiles = ((M + 127) / 128) * ((N + 127) / 128);
     const int sp = part ? pick_splits(M, N, K, tiles, part_elems, 512) : 1;
     // A window of 512 rows or more has the rows for 256 x 256 tiles, one block per CU, which sustain more per CU
-    // than two 128 x 128 blocks; few of them cover the output, so the choice goes by estimated time: the k-range of
-    // a block x the area a CU holds at a time over the rate of the shape, x the rounds of the grid - whole rounds
-    // for the large tile (one block per CU, all of one length), the plain ratio of blocks to slots for the small one
-    // (a slot is refilled as it frees) - plus the partial sums' way out and back in.
+    // than two 128 x 128 blocks; few of them cover the output, so the choice goes by estimated time: whole rounds of
+    // the grid over the block slots x the k-range of a block x the area a CU holds at a time over the rate of the
+    // shape, plus the partial sums' way out and back in (1 us per million of them).
     int sp256 = 0;
     if (M >= 512) {
-      auto est_us = [&](double rounds, int splits, double area, double pflops) {
-        return rounds * (K / splits) * area * 2.0 * 256 / (pflops * 1e9) + (splits > 1 ? (double)splits * M * N * 8.0 / 6e6 : 0.0);
+      auto est_us = [&](long blocks, int slots, int splits, double area, double pflops) {
+        const double rounds = (double)((blocks * splits + slots - 1) / slots);
+        return rounds * (K / splits) * area * 2.0 * 256 / (pflops * 1e9) + (splits > 1 ? (double)splits * M * N * 1e-6 : 0.0);
       };
-      double best = est_us(std::max(1.0, (double)tiles * sp / 512), sp, 2.0 * 128 * 128, TRANS_RATE_128);
+      double best = 0.97 * est_us(tiles, 512, sp, 2.0 * 128 * 128, TRANS_RATE_128);   // (the large tile has to win clearly)
       const long tiles256 = (long)((M + 255) / 256) * ((N + 255) / 256);
       for (int c = 1; c <= 16; ++c) {
         if (K % (c * BK) != 0 || (c > 1 && (K / c < 8 * BK || !part || (size_t)c * M * N > part_elems))) continue;
-        const double t = est_us((double)((tiles256 * c + 255) / 256), c, 256.0 * 256, TRANS_RATE_256);
+        const double t = est_us(tiles256, 256, c, 256.0 * 256, TRANS_RATE_256);
         if (t < best - 1e-9) { best = t; sp256 = c; }
       }
     }
