@@ -427,6 +427,16 @@ int32_t flexco_attention_window_bwd(const flexco_layer_cfg* cfg, const flexco_kv
 int32_t flexco_gemm(const void* A, const void* W, void* C, const void* bias, const void* residual,
                     int32_t M, int32_t N, int32_t K, int32_t trans_w, int32_t dtype, void* stream);
 
+/* How the bf16 matrix-core path would tile a product of these sizes (host arithmetic only: no GPU is touched, nothing
+ * is launched) - the plan flexco_gemm, the frozen base projections over all tokens of the batch (Sec. 6.2; the gated
+ * gate/up projection with N = 2 ffn) and the window backward's input-gradient products (Alg. 2; trans_w = 1) follow.
+ * part_elems: floats of split-K scratch the caller has (0 = none: flexco_gemm; the layer calls bring rows x 32768 for
+ * the window backward and for forward batches of at most 256 tokens).  out (host, 11 ints): out[0] = launches (1 or 2,
+ * side by side in the output columns), then per launch: tile rows, tile columns, output columns covered, blocks K is
+ * cut over, stages of the LDS ring; unused entries 0.  Errors: EINVAL (NULL, non-positive sizes), ESHAPE (K not a
+ * multiple of 64 or N not a multiple of 8: such products run on the type-generic kernels). */
+int32_t flexco_gemm_plan(int32_t M, int32_t N, int32_t K, int32_t trans_w, int64_t part_elems, int32_t* out);
+
 /* Per-kernel timing with HIP events, for roofline measurement.  While a timer is running the
  * library records one event before and one after every launch of the kernel class
  * `kernel_id` on that launch's stream (the bf16 GEMM kernels carry the two events in their own

@@ -23,7 +23,7 @@ FLEXCO_DECODE, FLEXCO_PREFILL, FLEXCO_FINETUNE = 0, 1, 2
 FLEXCO_REQ_WAITING, FLEXCO_REQ_RUNNING, FLEXCO_REQ_FINISHED = 0, 1, 2
 TARGET_NAMES = ("q", "k", "v", "o", "gate", "up", "down")
 N_TARGETS = 7
-ABI_VERSION = 7
+ABI_VERSION = 8
 
 
 class FlexcoError(RuntimeError):
@@ -140,6 +140,7 @@ def _load():
         "flexco_lora_bwd": [P(LayerCfg), P(BaseWeights), P(Lora), P(KVPool), vp, i32, P(FtState), i32, i32, vp, vp, vp, sz, vp],
         "flexco_attention_window_bwd": [P(LayerCfg), P(KVPool), vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
         "flexco_gemm": [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp],
+        "flexco_gemm_plan": [i32, i32, i32, i32, C.c_int64, P(i32)],
         "flexco_prune_graph": [P(Graph), vp],
         "flexco_kernel_timer_start": [i32, i32],
         "flexco_kernel_timer_stop": [i32, P(C.c_double), P(C.c_int64)],
@@ -176,7 +177,7 @@ def _load():
 _lib = _load()
 EXPORTS = ("flexco_last_error", "flexco_abi_version", "flexco_maps_blob_ints", "flexco_build_maps",
            "flexco_maps_rebase", "flexco_workspace_bytes", "flexco_layer_forward", "flexco_layer_forward_multi", "flexco_attention_mixed",
-           "flexco_lora_fwd", "flexco_lora_fwd_static", "flexco_lora_bwd", "flexco_attention_window_bwd", "flexco_gemm",
+           "flexco_lora_fwd", "flexco_lora_fwd_static", "flexco_lora_bwd", "flexco_attention_window_bwd", "flexco_gemm", "flexco_gemm_plan",
            "flexco_kernel_timer_start", "flexco_kernel_timer_stop", "flexco_kernel_timer_sample", "flexco_kernel_timer_read", "flexco_probe_mfma", "flexco_probe_mfma_lds", "flexco_probe_read",
            "flexco_latency_estimate", "flexco_sched_window", "flexco_sched_inference", "flexco_sched_advance",
            "flexco_lm_loss_workspace_bytes", "flexco_lm_loss", "flexco_adam_step", "flexco_prune_graph",
@@ -367,6 +368,13 @@ def flexco_attention_window_bwd(cfg, pool, seq_pages, n_seq_pages, win_start, wi
 def flexco_gemm(A, W, Cout, bias, residual, M, N, K, trans_w, dtype, stream=None):
     _check(_lib.flexco_gemm(_ptr(A), _ptr(W), _ptr(Cout), _ptr(bias), _ptr(residual), M, N, K, int(trans_w), dtype,
                             _stream(stream)))
+
+
+def flexco_gemm_plan(M, N, K, trans_w, part_elems=0):
+    """-> list of (tile rows, tile columns, output columns, K splits, ring stages), one per launch"""
+    out = (C.c_int32 * 11)()
+    _check(_lib.flexco_gemm_plan(M, N, K, int(trans_w), int(part_elems), out))
+    return [tuple(out[1 + 5 * i:6 + 5 * i]) for i in range(out[0])]
 
 
 def flexco_probe_mfma(blocks, iters, sink, stream=None):

@@ -777,6 +777,21 @@ extern "C" int32_t flexco_gemm(const void* A, const void* W, void* C, const void
                      (hipStream_t)stream);
 }
 
+extern "C" int32_t flexco_gemm_plan(int32_t M, int32_t N, int32_t K, int32_t trans_w, int64_t part_elems, int32_t* out) {
+  clear_error();
+  FLEXCO_CHECK(out != nullptr, FLEXCO_EINVAL, "out is NULL");
+  FLEXCO_CHECK(M > 0 && N > 0 && K > 0 && part_elems >= 0, FLEXCO_EINVAL, "M, N, K must be positive, part_elems not negative");
+  FLEXCO_CHECK(K % 64 == 0 && N % 8 == 0, FLEXCO_ESHAPE, "the matrix-core path takes K in multiples of 64 and N in multiples of 8");
+  const GemmLaunchPlan pl = plan_gemm_mfma(M, N, K, trans_w != 0, (size_t)part_elems);
+  for (int i = 0; i < 11; ++i) out[i] = 0;
+  out[0] = pl.n;
+  for (int i = 0; i < pl.n; ++i) {
+    int32_t* o = out + 1 + 5 * i;
+    o[0] = pl.step[i].bm; o[1] = pl.step[i].bn; o[2] = pl.step[i].cols; o[3] = pl.step[i].splits; o[4] = pl.step[i].stages;
+  }
+  return FLEXCO_OK;
+}
+
 extern "C" int32_t flexco_attention_mixed(const flexco_layer_cfg* cfg, const flexco_maps* maps, const void* q,
                                           const flexco_kv_pool* pool, void* out, float* lse, void* ws,
                                           size_t ws_bytes, void* stream) {

@@ -94,6 +94,12 @@ int32_t launch_gemm(const void* A, const void* W, void* C, const void* bias, con
 int32_t launch_gemm_generic(const void* A, const void* W, void* C, const void* bias, const void* residual, int M,
                             int N, int K, size_t lda, size_t ldw, size_t ldc, size_t ldr, bool trans_w, int dtype,
                             hipStream_t s);
+// How the bf16 MFMA path tiles a product: one or two launches side by side in the output columns, each one tile
+// shape (bm x bn), `cols` output columns, K cut over `splits` blocks, a ring of `stages` stages.  part_elems: floats of
+// split-K scratch at hand (0 = none).  The gated form is the forward plan over its 2F interleaved columns.
+struct GemmLaunchStep { int bm, bn, cols, splits, stages; };
+struct GemmLaunchPlan { int n; GemmLaunchStep step[2]; };
+GemmLaunchPlan plan_gemm_mfma(int M, int N, int K, bool trans_w, size_t part_elems);
 // bf16 MFMA path; returns FLEXCO_EUNSUPPORTED (without launching) for shapes it does not cover
 int32_t launch_gemm_mfma(const void* A, const void* W, void* C, const void* bias, const void* residual, int M,
                          int N, int K, size_t lda, size_t ldw, size_t ldc, size_t ldr, bool trans_w,

@@ -272,7 +272,7 @@ using namespace flexco;
 
 extern "C" const char* flexco_last_error(void) { return g_err; }
 
-extern "C" int32_t flexco_abi_version(void) { return 7; }
+extern "C" int32_t flexco_abi_version(void) { return 8; }
 
 extern "C" int32_t flexco_maps_blob_ints(const flexco_batch_desc* desc, int32_t page_size, int32_t n_q_heads,
                                          int32_t n_kv_heads, int32_t kv_split_pages, size_t* out_ints) {

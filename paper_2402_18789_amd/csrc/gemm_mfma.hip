@@ -662,24 +662,20 @@ static GemmPlan plan_forward(int M, int N) {
   return best;
 }
 
-int32_t launch_gemm_mfma(const void* A, const void* W, void* C, const void* bias, const void* residual, int M, int N,
-                         int K, size_t lda, size_t ldw, size_t ldc, size_t ldr, bool trans_w, const GemmExt* ext_in,
-                         hipStream_t s, float* part, size_t part_elems, int timer_id, int* splits_out) {
-  if (splits_out) *splits_out = 1;
-  // shapes the tiled kernel covers: K in whole 64-wide steps, 16-byte aligned rows
-  // (and 8-byte aligned runs of 4 output columns in C, bias and residual)
-  if (K % BK != 0 || lda % 8 != 0 || ldw % 8 != 0 || N % 8 != 0 || ldc % 4 != 0 || (residual && ldr % 4 != 0) ||
-      ((uintptr_t)C & 7) || ((uintptr_t)bias & 7) || ((uintptr_t)residual & 7))
-    return FLEXCO_EUNSUPPORTED;
-  GemmExt ext;
-  if (ext_in) ext = *ext_in; else ext.n = 0;
+// What launch_gemm_mfma does for a shape: one or two launches, each a tile shape over a range of output columns,
+// possibly with K cut across blocks.  A pure function of the arguments (host arithmetic only).
+GemmLaunchPlan plan_gemm_mfma(int M, int N, int K, bool trans_w, size_t part_elems) {
+  GemmLaunchPlan pl;
+  pl.n = 0;
+  auto add = [&](int bm, int bn, int cols, int splits, int stages) {
+    pl.step[pl.n++] = GemmLaunchStep{bm, bn, cols, splits, stages};
+  };
   if (trans_w) {
-    if (!ext_fits(ext, true, N)) return FLEXCO_EUNSUPPORTED;
     // few row tiles (a finetune window) and a long contraction: cut K across blocks so that the
     // weight stream is spread over the whole chip; partial sums are reduced in split order
     // (256 x 128 tiles, one block per CU, were measured slower than two co-resident 128 x 128 blocks)
     const int tiles = ((M + 127) / 128) * ((N + 127) / 128);
-    const int sp = part ? pick_splits(M, N, K, tiles, part_elems, 512) : 1;
+    const int sp = part_elems ? pick_splits(M, N, K, tiles, part_elems, 512) : 1;
     // A window of 512 rows or more has the rows for 256 x 256 tiles, one block per CU, which sustain more per CU
     // than two 128 x 128 blocks; few of them cover the output, so the choice goes by estimated time: whole rounds of
     // the grid over the block slots x the k-range of a block x the area a CU holds at a time over the rate of the
@@ -693,53 +689,89 @@ int32_t launch_gemm_mfma(const void* A, const void* W, void* C, const void* bias
       double best = 0.97 * est_us(tiles, 512, sp, 2.0 * 128 * 128, TRANS_RATE_128);   // (the large tile has to win clearly)
       const long tiles256 = (long)((M + 255) / 256) * ((N + 255) / 256);
       for (int c = 1; c <= 16; ++c) {
-        if (K % (c * BK) != 0 || (c > 1 && (K / c < 8 * BK || !part || (size_t)c * M * N > part_elems))) continue;
+        if (K % (c * BK) != 0 || (c > 1 && (K / c < 8 * BK || (size_t)c * M * N > part_elems))) continue;
         const double t = est_us(tiles256, 256, c, 256.0 * 256, TRANS_RATE_256);
         if (t < best - 1e-9) { best = t; sp256 = c; }
       }
     }
-    const int spu = sp256 ? sp256 : sp;
-    // splits_out: the caller's next kernel adds the partial sums itself (part[split][M][N], in split order) and
-    // the reduction launch is left out; bias and residual are then not applied
-    const bool leave = splits_out && spu > 1 && !bias && !residual;
-    if (leave) *splits_out = spu;
-    if (sp256)
-      return launch_cfg<256, 256, true>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, ext, s, timer_id, part, spu, true,
-                                        nullptr, leave);
-    return launch_cfg<128, 128, true>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, ext, s, timer_id, part, spu, true,
-                                      nullptr, leave);
+    if (sp256) add(256, 256, N, sp256, 2);
+    else add(128, 128, N, sp, 2);
+    return pl;
   }
-  if (!ext_fits(ext, false, N)) return FLEXCO_EUNSUPPORTED;
   // A batch of few tokens (decode-only iterations) has one or two row tiles and far fewer output tiles
   // than CUs, and its time is the weight stream's: cut K across blocks so that the whole chip pulls on it.
-  if (part && M <= 256) {
+  if (part_elems && M <= 256) {
     const int tiles = ((M + 127) / 128) * ((N + 127) / 128);
     const int sp = tiles < 192 ? pick_splits(M, N, K, tiles, part_elems, 256) : 1;
-    if (sp > 1)
-      return launch_cfg<128, 128, false>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, ext, s, timer_id, part, sp);
+    if (sp > 1) {
+      add(128, 128, N, sp, 4);
+      return pl;
+    }
   }
-  const GemmPlan pl = plan_forward(M, N);
-  const int n1 = std::min(N, 256 * pl.a256);
-  if (n1 > 0)
-    FLEXCO_TRY((launch_cfg<256, 256, false>(A, W, C, bias, residual, M, n1, K, lda, ldw, ldc, ldr, sub_ext(ext, 0, n1), s,
-                                            timer_id)));
+  const GemmPlan fp = plan_forward(M, N);
+  const int n1 = std::min(N, 256 * fp.a256);
+  if (n1 > 0) add(256, 256, n1, 1, 2);
   if (n1 < N) {
-    const bf16_t* W1 = (const bf16_t*)W + (size_t)n1 * ldw;
-    bf16_t* C1 = (bf16_t*)C + n1;
-    const bf16_t* b1 = bias ? (const bf16_t*)bias + n1 : nullptr;
-    const bf16_t* r1 = residual ? (const bf16_t*)residual + n1 : nullptr;
-    const GemmExt e1 = sub_ext(ext, n1, N);
-    const bool first = n1 == 0;
     // more 128 x 128 tiles than CUs: two-stage blocks, two per CU (the planner takes 128 x 192 tiles for single
     // rounds only)
     const long t128 = (long)((M + 127) / 128) * ((N - n1 + 127) / 128);
-    if (pl.rest == 0 && t128 > 256)
-      return launch_cfg<128, 128, false, false, 2>(A, W1, C1, b1, r1, M, N - n1, K, lda, ldw, ldc, ldr, e1, s, timer_id, nullptr, 1, first);
-    if (pl.rest == 0)
-      return launch_cfg<128, 128, false>(A, W1, C1, b1, r1, M, N - n1, K, lda, ldw, ldc, ldr, e1, s, timer_id, nullptr, 1, first);
-    if (pl.rest == 1)
-      return launch_cfg<128, 192, false>(A, W1, C1, b1, r1, M, N - n1, K, lda, ldw, ldc, ldr, e1, s, timer_id, nullptr, 1, first);
-    return launch_cfg<256, 192, false>(A, W1, C1, b1, r1, M, N - n1, K, lda, ldw, ldc, ldr, e1, s, timer_id, nullptr, 1, first);
+    if (fp.rest == 0) add(128, 128, N - n1, 1, t128 > 256 ? 2 : 4);
+    else if (fp.rest == 1) add(128, 192, N - n1, 1, 4);
+    else add(256, 192, N - n1, 1, 2);
+  }
+  return pl;
+}
+
+int32_t launch_gemm_mfma(const void* A, const void* W, void* C, const void* bias, const void* residual, int M, int N,
+                         int K, size_t lda, size_t ldw, size_t ldc, size_t ldr, bool trans_w, const GemmExt* ext_in,
+                         hipStream_t s, float* part, size_t part_elems, int timer_id, int* splits_out) {
+  if (splits_out) *splits_out = 1;
+  // shapes the tiled kernel covers: K in whole 64-wide steps, 16-byte aligned rows
+  // (and 8-byte aligned runs of 4 output columns in C, bias and residual)
+  if (K % BK != 0 || lda % 8 != 0 || ldw % 8 != 0 || N % 8 != 0 || ldc % 4 != 0 || (residual && ldr % 4 != 0) ||
+      ((uintptr_t)C & 7) || ((uintptr_t)bias & 7) || ((uintptr_t)residual & 7))
+    return FLEXCO_EUNSUPPORTED;
+  GemmExt ext;
+  if (ext_in) ext = *ext_in; else ext.n = 0;
+  if (!ext_fits(ext, trans_w, N)) return FLEXCO_EUNSUPPORTED;
+  const GemmLaunchPlan pl = plan_gemm_mfma(M, N, K, trans_w, part ? part_elems : 0);
+  if (trans_w) {
+    const GemmLaunchStep& st = pl.step[0];
+    // splits_out: the caller's next kernel adds the partial sums itself (part[split][M][N], in split order) and
+    // the reduction launch is left out; bias and residual are then not applied
+    const bool leave = splits_out && st.splits > 1 && !bias && !residual;
+    if (leave) *splits_out = st.splits;
+    if (st.bm == 256)
+      return launch_cfg<256, 256, true>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, ext, s, timer_id, part, st.splits,
+                                        true, nullptr, leave);
+    return launch_cfg<128, 128, true>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, ext, s, timer_id, part, st.splits, true,
+                                      nullptr, leave);
+  }
+  if (pl.step[0].splits > 1)
+    return launch_cfg<128, 128, false>(A, W, C, bias, residual, M, N, K, lda, ldw, ldc, ldr, ext, s, timer_id, part,
+                                       pl.step[0].splits);
+  int c0 = 0;
+  for (int i = 0; i < pl.n; ++i) {
+    const GemmLaunchStep& st = pl.step[i];
+    const bf16_t* W1 = (const bf16_t*)W + (size_t)c0 * ldw;
+    bf16_t* C1 = (bf16_t*)C + c0;
+    const bf16_t* b1 = bias ? (const bf16_t*)bias + c0 : nullptr;
+    const bf16_t* r1 = residual ? (const bf16_t*)residual + c0 : nullptr;
+    const GemmExt e1 = sub_ext(ext, c0, c0 + st.cols);
+    const bool first = i == 0;
+    int32_t rc;
+    if (st.bm == 256 && st.bn == 256)
+      rc = launch_cfg<256, 256, false>(A, W1, C1, b1, r1, M, st.cols, K, lda, ldw, ldc, ldr, e1, s, timer_id, nullptr, 1, first);
+    else if (st.bm == 256)
+      rc = launch_cfg<256, 192, false>(A, W1, C1, b1, r1, M, st.cols, K, lda, ldw, ldc, ldr, e1, s, timer_id, nullptr, 1, first);
+    else if (st.bn == 192)
+      rc = launch_cfg<128, 192, false>(A, W1, C1, b1, r1, M, st.cols, K, lda, ldw, ldc, ldr, e1, s, timer_id, nullptr, 1, first);
+    else if (st.stages == 2)
+      rc = launch_cfg<128, 128, false, false, 2>(A, W1, C1, b1, r1, M, st.cols, K, lda, ldw, ldc, ldr, e1, s, timer_id, nullptr, 1, first);
+    else
+      rc = launch_cfg<128, 128, false>(A, W1, C1, b1, r1, M, st.cols, K, lda, ldw, ldc, ldr, e1, s, timer_id, nullptr, 1, first);
+    if (rc) return rc;
+    c0 += st.cols;
   }
   return FLEXCO_OK;
 }
@@ -759,26 +791,30 @@ int32_t launch_gemm_glu_mfma(const void* A, const void* W, void* act, int M, int
   glu.F = F; glu.col0 = 0; glu.save_gate = (bf16_t*)save_gate; glu.save_up = (bf16_t*)save_up;
   glu.save_row0 = save_row0; glu.save_rows = save_gate ? save_rows : 0; glu.ld_save = ld_save;
   const int N = 2 * F;
-  const GemmPlan pl = plan_forward(M, N);
-  const int n1 = std::min(N, 256 * pl.a256);        // interleaved columns of the 256-wide tiles = 2 x their act columns
-  if (n1 > 0)
-    FLEXCO_TRY((launch_cfg<256, 256, false, true>(A, W, act, nullptr, nullptr, M, n1, K, lda, ldw, ld_act, 0, ext, s,
-                                                  timer_id, nullptr, 1, true, &glu)));
-  if (n1 < N) {
-    glu.col0 = n1 / 2;
-    const bool first = n1 == 0;
-    const long t128 = (long)((M + 127) / 128) * ((N - n1 + 127) / 128);
-    if (pl.rest == 0 && t128 > 256)
-      return launch_cfg<128, 128, false, true, 2>(A, W, act, nullptr, nullptr, M, N - n1, K, lda, ldw, ld_act, 0, ext, s, timer_id,
-                                                  nullptr, 1, first, &glu);
-    if (pl.rest == 0)
-      return launch_cfg<128, 128, false, true>(A, W, act, nullptr, nullptr, M, N - n1, K, lda, ldw, ld_act, 0, ext, s, timer_id,
-                                               nullptr, 1, first, &glu);
-    if (pl.rest == 1)
-      return launch_cfg<128, 192, false, true>(A, W, act, nullptr, nullptr, M, N - n1, K, lda, ldw, ld_act, 0, ext, s, timer_id,
-                                               nullptr, 1, first, &glu);
-    return launch_cfg<256, 192, false, true>(A, W, act, nullptr, nullptr, M, N - n1, K, lda, ldw, ld_act, 0, ext, s, timer_id,
+  const GemmLaunchPlan pl = plan_gemm_mfma(M, N, K, false, 0);
+  int c0 = 0;                                       // interleaved columns done = 2 x the act columns done
+  for (int i = 0; i < pl.n; ++i) {
+    const GemmLaunchStep& st = pl.step[i];
+    glu.col0 = c0 / 2;
+    const bool first = i == 0;
+    int32_t rc;
+    if (st.bm == 256 && st.bn == 256)
+      rc = launch_cfg<256, 256, false, true>(A, W, act, nullptr, nullptr, M, st.cols, K, lda, ldw, ld_act, 0, ext, s, timer_id,
                                              nullptr, 1, first, &glu);
+    else if (st.bm == 256)
+      rc = launch_cfg<256, 192, false, true>(A, W, act, nullptr, nullptr, M, st.cols, K, lda, ldw, ld_act, 0, ext, s, timer_id,
+                                             nullptr, 1, first, &glu);
+    else if (st.bn == 192)
+      rc = launch_cfg<128, 192, false, true>(A, W, act, nullptr, nullptr, M, st.cols, K, lda, ldw, ld_act, 0, ext, s, timer_id,
+                                             nullptr, 1, first, &glu);
+    else if (st.stages == 2)
+      rc = launch_cfg<128, 128, false, true, 2>(A, W, act, nullptr, nullptr, M, st.cols, K, lda, ldw, ld_act, 0, ext, s, timer_id,
+                                                nullptr, 1, first, &glu);
+    else
+      rc = launch_cfg<128, 128, false, true>(A, W, act, nullptr, nullptr, M, st.cols, K, lda, ldw, ld_act, 0, ext, s, timer_id,
+                                             nullptr, 1, first, &glu);
+    if (rc) return rc;
+    c0 += st.cols;
   }
   return FLEXCO_OK;
 }
