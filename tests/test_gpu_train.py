@@ -69,6 +69,15 @@ def test_loss_head_qwen_vocabulary():
     run_loss("bf16", 40, 5120, 152064, seed=3, ignore=(0, 39))
 
 
+def test_loss_head_window_of_600_rows_takes_the_large_input_gradient_tile():
+    """dH = dZ W of 600 rows at hidden 1024, vocabulary 32768: 256 x 256 tiles with K cut over 16 blocks (the plan says so),
+    the last row tile ragged, the partial sums added by the reduction kernel."""
+    n, H, V = 600, 1024, 32768
+    assert B.flexco_gemm_plan(n, H, V, 1, 16 * n * H) == [(256, 256, H, 16, 2)]
+    print(f"loss head bf16 n={n} H={H} V={V}", flush=True)
+    run_loss("bf16", n, H, V, seed=4, ignore=(0, 599))
+
+
 def test_loss_head_all_rows_ignored_and_errors():
     cfg = C1
     H, V, n = 64, 40, 3
