@@ -57,16 +57,29 @@ int32_t build(const flexco_batch_desc* d, int32_t page_size, int32_t num_pages, 
   if (kv_split_pages <= 0) {
     // Default: 128 pages per split (measured against 64 on the benchmark batch: the attention kernel 3 % and the
     // merge kernel a third faster) - or 256, the most the attention kernel's page-id table holds, when no request
-    // sees more pages than that: then no tile is split and the merge launch falls away (measured: 1.2 % of the
-    // benchmark step; where longer contexts keep the merge, 256 was 0.3 % slower than 128).  A batch of few
+    // sees more pages than that (then no tile is split and the merge launch falls away: 1.2 % of the benchmark
+    // step) or when the one-token requests' pages outweigh the other requests' pages x column tiles, i.e. the
+    // decode stream carries the attention (measured on such batches with contexts of up to 8192 keys: 1.6 - 4.7 %
+    // of the attention against 128; where the chunks carry it 128 stays ahead by 2 - 7 %).  A batch of few
     // requests would leave most of the chip without an attention work item (one wavefront per item and kv
     // head): take the largest of these, 64, 32, 16, 8 pages that gives at least 1024 wavefronts, else 8.
-    int64_t max_vis = 0;
-    for (int r = 0; r < n_req; ++r)
-      if (d->n_new[r] > 0 && d->start_pos[r] >= 0 && page_size > 0)
-        max_vis = std::max<int64_t>(max_vis, ((int64_t)d->start_pos[r] + d->n_new[r] - 1) / page_size + 1);
+    int64_t max_vis = 0, stream = 0, chunks = 0;
+    for (int r = 0; r < n_req; ++r) {
+      if (d->n_new[r] <= 0 || d->start_pos[r] < 0 || page_size <= 0) continue;   // rejected below
+      max_vis = std::max<int64_t>(max_vis, ((int64_t)d->start_pos[r] + d->n_new[r] - 1) / page_size + 1);
+      if (d->n_new[r] == 1) {
+        stream += d->start_pos[r] / page_size + 1;
+        continue;
+      }
+      const int tiles = (d->n_new[r] + b.tile_tokens - 1) / b.tile_tokens;
+      for (int tl0 = 0; tl0 < tiles; tl0 += FLEXCO_ATTN_ITEM_TILES) {
+        const int last_tile = std::min(tl0 + FLEXCO_ATTN_ITEM_TILES, tiles) - 1;
+        const int last_tok = std::min((last_tile + 1) * b.tile_tokens, d->n_new[r]) - 1;
+        chunks += (int64_t)((d->start_pos[r] + last_tok) / page_size + 1) * (last_tile - tl0 + 1);
+      }
+    }
     b.split_pages = 8;
-    for (int cand = max_vis <= 256 ? 256 : 128; cand >= 16; cand /= 2) {
+    for (int cand = (max_vis <= 256 || stream > chunks) ? 256 : 128; cand >= 16; cand /= 2) {
       int64_t items = 0;
       for (int r = 0; r < n_req; ++r) {
         if (d->n_new[r] <= 0 || d->start_pos[r] < 0 || page_size <= 0) continue;   // rejected below

@@ -87,12 +87,17 @@ def test_maps_bit_exact_vs_oracle(name, nq, nkv, split):
 
 
 def test_default_key_split_follows_the_batch_size():
-    """128 pages per split (256 when no request sees more pages than that) when that already gives the chip enough
-    work items; fewer pages per split for
+    """128 pages per split (256 when no request sees more pages than that, or when the decode stream's pages outweigh the
+    other requests' pages x column tiles) when that already gives the chip enough work items; fewer pages per split for
     batches of few requests (down to 8), so that a decode-only iteration of 16 requests is not 128
     wavefronts walking 1000 keys each.  Any split leaves the cover intact."""
     assert c_maps(gen.batch_c2(0), 32, 8)["kv_split_pages"] == 256     # contexts of at most 4096 keys = 256 pages
-    assert c_maps(gen.batch_c3(0), 32, 8)["kv_split_pages"] == 128     # contexts of up to 8192 keys
+    c3 = c_maps(gen.batch_c3(0), 32, 8)                                # contexts of up to 8192 keys, a decode-heavy batch
+    assert c3["kv_split_pages"] == 256 and c3["stream_pages"] > c3["chunk_tile_pages"]
+    c4 = c_maps(gen.batch_c4(0), 40, 8)                                # contexts of up to 8192 keys, a 1024-row window on 3072
+    assert c4["kv_split_pages"] == 128 and c4["stream_pages"] < c4["chunk_tile_pages"]
+    for share, want in ((0.25, 128), (0.75, 256), (0.9, 256)):
+        assert c_maps(gen.batch_c4(0, share), 40, 8)["kv_split_pages"] == want
     for n_dec, want in ((16, 8), (64, 16), (100, 32), (200, 256)):
         ctx = gen.rng(0, "split", n_dec).integers(256, 1025, size=n_dec)
         batch = gen.mixed_batch(16, 0, decode_ctx=ctx)
