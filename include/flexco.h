@@ -230,7 +230,7 @@ int32_t flexco_maps_blob_ints(const flexco_batch_desc* desc, int32_t page_size,
 
 /* Builds the index maps of a mixed batch on the host (Sec. 6.2: the scheduler's output is
  * this call's input).  desc, blob: host.  blob_ints: capacity of blob in int32 words.
- * num_pages: size of the pool the page ids refer to.  kv_split_pages: 0 = default (128 - 256 when no request sees more pages than that, so that nothing needs merging -, or down to 8 for batches too small to fill the chip); at most 256 on the matrix-core path.
+ * num_pages: size of the pool the page ids refer to.  kv_split_pages: 0 = default (128 - 256 when no request sees more pages than that, so that nothing needs merging, or when the one-token requests' pages outweigh the other requests' pages x column tiles -, or down to 8 for batches too small to fill the chip); at most 256 on the matrix-core path.
  * Errors: EINVAL (null, non-positive sizes, unknown kind), EPAGE (page id outside
  * [0, num_pages), kv_len beyond the request's pages, two tokens on one slot),
  * EUNSUPPORTED (more than one finetune request), EWORKSPACE (blob too small). */
